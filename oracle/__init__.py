@@ -1,0 +1,219 @@
+"""ctypes wrapper around the plain-C CPU oracle (``bgl_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: tests, the smoke check and the benchmark's
+``cpu_baseline`` leg may import this package; the product package never does.
+It shares nothing with the HIP library.  Citations of the paper sit on the C
+functions; this file only marshals numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "bgl_oracle.c")
+_LIB = os.path.join(_HERE, "libbgl_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, no OpenMP, no vectorising flags)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-o", _LIB, _SRC])
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_LIB)
+        u64, i64, i32, vp = C.c_uint64, C.c_int64, C.c_int32, C.c_void_p
+        L.bglo_mix64.restype = u64
+        L.bglo_mix64.argtypes = [u64]
+        L.bglo_draw.restype = u64
+        L.bglo_draw.argtypes = [u64, i32, i32, i32]
+        L.bglo_mulhi64.restype = u64
+        L.bglo_mulhi64.argtypes = [u64, u64]
+        L.bglo_floyd_from_t.restype = None
+        L.bglo_floyd_from_t.argtypes = [i64, i32, vp, vp]
+        L.bglo_sample_positions.restype = i32
+        L.bglo_sample_positions.argtypes = [u64, i32, i32, i64, i32, vp]
+        L.bglo_sample_khop.restype = C.c_int
+        L.bglo_sample_khop.argtypes = [vp, C.c_int, vp, i64, vp, i32, vp, i32, u64,
+                                       vp, i64, vp, vp, vp, vp, vp, vp]
+        L.bglo_cache_create.restype = vp
+        L.bglo_cache_create.argtypes = [i64, i32, vp, i64]
+        L.bglo_cache_destroy.restype = None
+        L.bglo_cache_destroy.argtypes = [vp]
+        L.bglo_cache_lookup_gather.restype = i64
+        L.bglo_cache_lookup_gather.argtypes = [vp, vp, i64, vp, vp, vp]
+        L.bglo_cache_insert_fifo.restype = None
+        L.bglo_cache_insert_fifo.argtypes = [vp, vp, vp, i64, vp]
+        L.bglo_cache_tail.restype = u64
+        L.bglo_cache_tail.argtypes = [vp]
+        for name in ("bglo_cache_slot_to_node", "bglo_cache_node_to_slot", "bglo_cache_buffer"):
+            getattr(L, name).restype = vp
+            getattr(L, name).argtypes = [vp]
+        L.bglo_cache_stats.restype = None
+        L.bglo_cache_stats.argtypes = [vp, vp, vp]
+        _lib = L
+    return _lib
+
+
+def _ptr(a: np.ndarray) -> int:
+    return a.ctypes.data
+
+
+def mix64(z: int) -> int:
+    return int(lib().bglo_mix64(z & (2**64 - 1)))
+
+
+def draw(rng_seed: int, hop: int, node: int, slot: int) -> int:
+    return int(lib().bglo_draw(rng_seed & (2**64 - 1), hop, node, slot))
+
+
+def mulhi64(x: int, m: int) -> int:
+    return int(lib().bglo_mulhi64(x, m))
+
+
+def floyd_from_t(d: int, k: int, t) -> np.ndarray:
+    t = np.ascontiguousarray(t, dtype=np.int64)
+    pos = np.zeros(k, dtype=np.int64)
+    lib().bglo_floyd_from_t(d, k, _ptr(t), _ptr(pos))
+    return pos
+
+
+def sample_positions(rng_seed: int, hop: int, node: int, d: int, fanout: int) -> np.ndarray:
+    pos = np.zeros(max(fanout, min(d, fanout), 1), dtype=np.int64)
+    c = lib().bglo_sample_positions(rng_seed & (2**64 - 1), hop, node, d, fanout, _ptr(pos))
+    return pos[:c].copy()
+
+
+def frontier_bounds(num_seeds: int, fanouts, num_nodes: int):
+    """Upper bounds |frontier_h| <= min(N, B * prod(1+f)) and per-hop edge bounds."""
+    nf = [min(num_seeds, num_nodes)]
+    ne = []
+    for f in fanouts:
+        ne.append(nf[-1] * f)
+        nf.append(min(num_nodes, nf[-1] * (1 + f)))
+    return nf, ne
+
+
+class Subgraph:
+    """Result of :func:`sample_khop` (numpy arrays trimmed to their real sizes)."""
+
+    def __init__(self):
+        self.input_nodes = None
+        self.n_frontier = None
+        self.row_ptr = []
+        self.col_local = []
+        self.col_global = []
+        self.nnz = []
+
+
+def sample_khop(row_ptr: np.ndarray, col: np.ndarray, seeds, fanouts, rng_seed: int) -> Subgraph:
+    row_ptr = np.ascontiguousarray(row_ptr)
+    assert row_ptr.dtype in (np.int32, np.int64)
+    bits = 64 if row_ptr.dtype == np.int64 else 32
+    col = np.ascontiguousarray(col, dtype=np.int32)
+    seeds = np.ascontiguousarray(seeds, dtype=np.int32)
+    fan = np.ascontiguousarray(fanouts, dtype=np.int32)
+    K = len(fan)
+    N = len(row_ptr) - 1
+    nf, ne = frontier_bounds(len(seeds), [int(f) for f in fan], N)
+    input_nodes = np.empty(max(nf[-1], 1), dtype=np.int32)
+    n_frontier = np.zeros(K + 1, dtype=np.int32)
+    rps = [np.zeros(nf[h] + 1, dtype=np.int32) for h in range(K)]
+    cls = [np.empty(max(ne[h], 1), dtype=np.int32) for h in range(K)]
+    cgs = [np.empty(max(ne[h], 1), dtype=np.int32) for h in range(K)]
+    PtrArr = C.c_void_p * K
+    cap_edges = np.array(ne, dtype=np.int64)
+    nnz = np.zeros(K, dtype=np.int64)
+    rc = lib().bglo_sample_khop(
+        _ptr(row_ptr), bits, _ptr(col), N, _ptr(seeds), len(seeds), _ptr(fan), K,
+        rng_seed & (2**64 - 1), _ptr(input_nodes), nf[-1], _ptr(n_frontier),
+        C.cast(PtrArr(*[_ptr(a) for a in rps]), C.c_void_p),
+        C.cast(PtrArr(*[_ptr(a) for a in cls]), C.c_void_p),
+        C.cast(PtrArr(*[_ptr(a) for a in cgs]), C.c_void_p),
+        _ptr(cap_edges), _ptr(nnz))
+    if rc != 0:
+        raise ValueError(f"bglo_sample_khop failed with status {rc}")
+    sg = Subgraph()
+    sg.n_frontier = n_frontier
+    sg.input_nodes = input_nodes[: n_frontier[K]].copy()
+    for h in range(K):
+        e = int(nnz[h])
+        sg.row_ptr.append(rps[h][: n_frontier[h] + 1].copy())
+        sg.col_local.append(cls[h][:e].copy())
+        sg.col_global.append(cgs[h][:e].copy())
+        sg.nnz.append(e)
+    return sg
+
+
+class Cache:
+    """FIFO feature cache over a host feature table given as a 2-D byte view."""
+
+    def __init__(self, capacity_rows: int, features: np.ndarray):
+        feats = features if features.flags.c_contiguous else np.ascontiguousarray(features)
+        self._features = feats  # keep alive
+        self.num_nodes = feats.shape[0]
+        self.row_bytes = feats.strides[0]
+        self.capacity = capacity_rows
+        self._h = lib().bglo_cache_create(capacity_rows, self.row_bytes, _ptr(feats), self.num_nodes)
+        if not self._h:
+            raise ValueError("bglo_cache_create failed")
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            lib().bglo_cache_destroy(self._h)
+            self._h = None
+
+    def lookup_gather(self, ids):
+        ids = np.ascontiguousarray(ids, dtype=np.int32)
+        n = len(ids)
+        out = np.empty((n, self.row_bytes), dtype=np.uint8)
+        out_slot = np.empty(n, dtype=np.int32)
+        miss_pos = np.empty(max(n, 1), dtype=np.int32)
+        n_hit = lib().bglo_cache_lookup_gather(self._h, _ptr(ids), n, _ptr(out), _ptr(out_slot), _ptr(miss_pos))
+        if n_hit < 0:
+            raise ValueError("node id out of range")
+        return out, out_slot, miss_pos[: n - n_hit].copy(), int(n_hit)
+
+    def insert_fifo(self, ids, miss_pos, out_rows):
+        ids = np.ascontiguousarray(ids, dtype=np.int32)
+        miss_pos = np.ascontiguousarray(miss_pos, dtype=np.int32)
+        out_rows = np.ascontiguousarray(out_rows)
+        lib().bglo_cache_insert_fifo(self._h, _ptr(ids), _ptr(miss_pos), len(miss_pos), _ptr(out_rows))
+
+    @property
+    def tail(self) -> int:
+        return int(lib().bglo_cache_tail(self._h))
+
+    def _view(self, fn, dtype, shape):
+        p = getattr(lib(), fn)(self._h)
+        n = int(np.prod(shape))
+        buf = (C.c_uint8 * (n * np.dtype(dtype).itemsize)).from_address(p)
+        return np.frombuffer(buf, dtype=dtype).reshape(shape).copy()
+
+    @property
+    def slot_to_node(self) -> np.ndarray:
+        return self._view("bglo_cache_slot_to_node", np.int32, (self.capacity,))
+
+    @property
+    def node_to_slot(self) -> np.ndarray:
+        return self._view("bglo_cache_node_to_slot", np.int32, (self.num_nodes,))
+
+    @property
+    def buffer(self) -> np.ndarray:
+        return self._view("bglo_cache_buffer", np.uint8, (self.capacity, self.row_bytes))
+
+    def stats(self):
+        a, b = C.c_uint64(0), C.c_uint64(0)
+        lib().bglo_cache_stats(self._h, C.addressof(a), C.addressof(b))
+        return a.value, b.value
