@@ -1,0 +1,233 @@
+/*
+ * bgl.h - C ABI of the MI355X minibatch-preparation library.
+ *
+ * The library implements, as HIP kernels for gfx950, the data path that the
+ * BGL paper (arXiv 2112.08541) is about: for every training iteration, sample a
+ * k-hop subgraph around a batch of training nodes (Sec. 2.1 stage 1, Sec. 5.1
+ * "Mini-batch Sampling Algorithms") and retrieve the features of its nodes
+ * through a GPU-resident FIFO feature cache (Sec. 3.2 and the "Feature Cache
+ * Engine" paragraphs of Sec. 4).
+ *
+ * Conventions
+ *  - Every call returns a status: BGL_OK or a negative BGL_E* code.  Nothing
+ *    throws or aborts; bgl_last_error() returns a thread-local message for the
+ *    last failing call on this thread.
+ *  - "host" pointers are dereferenced by the CPU inside the call; "device"
+ *    pointers are only handed to kernels.  The library never takes ownership of
+ *    caller memory.  Handles are opaque, created by *_load_* / *_create and
+ *    released by *_destroy.
+ *  - Streams are hipStream_t values passed as void* (NULL = the default
+ *    stream).  Calls that take a stream only enqueue work; results are valid
+ *    once the stream has been synchronised.  Calls on one handle must be
+ *    serialised by the caller (the paper serialises all operations on one GPU
+ *    cache through one queue, Sec. 3.2.3).
+ *  - All ids are int32 node ids in [0, num_nodes).
+ */
+#ifndef BGL_H
+#define BGL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BGL_OK 0
+#define BGL_EINVAL (-1)       /* bad argument */
+#define BGL_ENOMEM (-2)       /* host or device allocation failed */
+#define BGL_EHIP (-3)         /* a HIP runtime call failed */
+#define BGL_ECAPACITY (-4)    /* a caller-provided buffer is too small */
+#define BGL_EUNSUPPORTED (-5) /* valid request outside the implemented range */
+
+#define BGL_MAX_HOPS 8
+#define BGL_MAX_FANOUT 64
+
+/* Where bgl_graph_load_csr keeps the CSR arrays. */
+#define BGL_DEVICE 0      /* copy both arrays into HBM */
+#define BGL_HOST_PINNED 1 /* caller's arrays are page-locked; kernels read them in place */
+
+typedef struct bgl_graph bgl_graph_t;
+typedef struct bgl_cache bgl_cache_t;
+
+const char *bgl_last_error(void);
+
+/* ------------------------------------------------------------------ graph */
+
+/*
+ * Register a graph in CSR form (the graph structure the samplers of Sec. 3.1
+ * work on).  Row v holds the neighbors that sampling may pick for v.
+ *   row_ptr      host, num_nodes+1 offsets, int32 (row_ptr_bits = 32) or int64 (64)
+ *   col_idx      host, num_edges int32 node ids
+ *   placement    BGL_DEVICE: arrays are copied to HBM, the caller may free its
+ *                copies on return.  BGL_HOST_PINNED: arrays must be page-locked
+ *                (hipHostMalloc or equivalent) and stay alive and unchanged
+ *                until bgl_graph_destroy.
+ * Validated on the host: row_ptr[0] == 0, non-decreasing, row_ptr[N] ==
+ * num_edges, every degree < 2^31, every column id in [0, num_nodes).
+ * Errors: BGL_EINVAL (null pointers, bad sizes, failed validation, memory not
+ * page-locked), BGL_ENOMEM, BGL_EHIP.
+ */
+int bgl_graph_load_csr(const void *row_ptr, int row_ptr_bits, const int32_t *col_idx,
+                       int64_t num_nodes, int64_t num_edges, int placement,
+                       bgl_graph_t **out);
+int bgl_graph_destroy(bgl_graph_t *g);
+
+/* --------------------------------------------------------------- sampling */
+
+/*
+ * Result of bgl_sample_khop.  All pointers are device pointers into the
+ * workspace given to that call and stay valid until the workspace is reused.
+ * Hop h connects destination nodes input_nodes[0 .. n_frontier[h]) to source
+ * nodes input_nodes[0 .. n_frontier[h+1]) in CSR form with local ids:
+ * row_ptr[h] has n_frontier[h]+1 entries, col_local[h] has nnz[h] entries.
+ * Sizes live in `counts` (device) in this layout:
+ *   counts[0 .. num_hops]                          n_frontier[h]
+ *   counts[BGL_MAX_HOPS+1 .. BGL_MAX_HOPS+num_hops] nnz[h]
+ *   counts[BGL_COUNTS_LEN-1]                       status (0 = ok, else a BGL_E* code)
+ * n_input = n_frontier[num_hops].
+ */
+#define BGL_COUNTS_LEN (2 * BGL_MAX_HOPS + 2)
+typedef struct {
+    int32_t num_hops;
+    int32_t *input_nodes;              /* frontier_K: global ids, unique, seeds first */
+    int32_t *row_ptr[BGL_MAX_HOPS];
+    int32_t *col_local[BGL_MAX_HOPS];
+    int64_t cap_nodes[BGL_MAX_HOPS + 1]; /* upper bounds on n_frontier[h] */
+    int64_t cap_edges[BGL_MAX_HOPS];     /* upper bounds on nnz[h] */
+    const int32_t *counts;               /* device, BGL_COUNTS_LEN ints */
+} bgl_subgraph_t;
+
+/* Bytes of device workspace bgl_sample_khop needs for these arguments. */
+int bgl_sample_workspace_bytes(int32_t num_seeds, const int32_t *fanouts, int32_t num_hops,
+                               int64_t num_nodes, size_t *bytes);
+
+/*
+ * k-hop fanout neighbor sampling with per-hop deduplication (Sec. 3.1:
+ * iterative next-hop sampling from the training nodes; Sec. 5.1: one fanout per
+ * hop, e.g. {15,10,5}).
+ *
+ * frontier_0 = seeds with repeats removed (first occurrence kept).  For hop h
+ * every node v of frontier_h draws c = min(fanouts[h], degree(v)) distinct
+ * edge positions of its CSR row, uniformly (all of them, in row order, when
+ * degree <= fanout; otherwise Floyd's subset algorithm on a counter-based
+ * generator keyed on (rng_seed, h, v, slot)).  frontier_{h+1} is frontier_h
+ * followed by the not-yet-seen sampled neighbors in (frontier index, slot)
+ * order, so local ids are stable across hops.
+ *
+ *   seeds            device, num_seeds ids (any order, repeats allowed)
+ *   fanouts          host, num_hops values in [1, BGL_MAX_FANOUT]; fanouts[0] applies at the seeds
+ *   rng_seed         per-call seed; the same seed reproduces the same sample
+ *   workspace        device, 256-byte aligned, >= bgl_sample_workspace_bytes(...)
+ *   out              host struct filled before return (pointers into workspace)
+ *   counts_host      optional page-locked host array of BGL_COUNTS_LEN ints that
+ *                    receives a copy of out->counts on `stream`
+ * Asynchronous on `stream`.  A seed id outside [0, num_nodes) is dropped and
+ * sets status BGL_EINVAL in counts.
+ * Errors: BGL_EINVAL (null/misaligned pointers, num_seeds < 1, num_hops outside
+ * [1, BGL_MAX_HOPS], fanout < 1), BGL_EUNSUPPORTED (fanout > BGL_MAX_FANOUT),
+ * BGL_ECAPACITY (workspace too small), BGL_EHIP.
+ */
+int bgl_sample_khop(const bgl_graph_t *g, const int32_t *seeds, int32_t num_seeds,
+                    const int32_t *fanouts, int32_t num_hops, uint64_t rng_seed,
+                    void *workspace, size_t workspace_bytes, bgl_subgraph_t *out,
+                    int32_t *counts_host, void *stream);
+
+/* ------------------------------------------------------------------ cache */
+
+/*
+ * Create a FIFO feature cache in HBM (Sec. 3.2.3: one cache map and one cache
+ * buffer per GPU).  The cache buffer holds capacity_rows rows of row_bytes
+ * bytes; the map from node id to buffer slot is an open-addressing hash table.
+ * Rows are opaque bytes (fp32, bf16, ...).
+ *   host_features  the backing store for misses: num_nodes rows of row_bytes
+ *                  bytes, 16-byte aligned, in page-locked host memory (read in
+ *                  place by kernels over the host link) or in device memory.
+ *                  Must stay alive and unchanged until bgl_cache_destroy
+ *                  (features do not change during training, Sec. 4).
+ * Errors: BGL_EINVAL (capacity_rows < 1, row_bytes < 16 or not a multiple of
+ * 16, null/misaligned/pageable features, num_nodes < 1), BGL_ENOMEM, BGL_EHIP.
+ */
+int bgl_cache_create(int64_t capacity_rows, int32_t row_bytes, const void *host_features,
+                     int64_t num_nodes, bgl_cache_t **out);
+int bgl_cache_destroy(bgl_cache_t *c);
+
+/*
+ * Cache workflow steps 4-6 of Sec. 3.2.3: look the ids up in the cache map,
+ * gather the rows of the hits from the cache buffer, fetch the rows of the
+ * misses from the backing store.  The lookup sees the cache as it was when the
+ * call's work starts on main_stream; nothing in the cache changes (FIFO: a hit
+ * does not renew a row).
+ *   ids             device, n ids, no repeats (the input_nodes of bgl_sample_khop)
+ *   out_rows        device, n * row_bytes bytes, 16-byte aligned; row i = features of ids[i]
+ *   out_slot        device, n ints: buffer slot of ids[i], or -1 for a miss
+ *   miss_pos        device, room for n ints: the positions i of the misses, ascending
+ *   n_hit_host      optional page-locked host int64 that receives the number of hits
+ *   main_stream     probe, hit gather and miss list run here
+ *   side_stream     the miss fetch runs here, concurrently with the hit gather
+ *                   (NULL: a stream owned by the cache).  Before returning, the
+ *                   call makes main_stream wait for it, so in main_stream order
+ *                   all outputs are complete.
+ * An id outside [0, num_nodes) is reported as a miss whose row is left
+ * untouched, and sets the cache's status (bgl_cache_stats) to BGL_EINVAL.
+ * Errors: BGL_EINVAL (null/misaligned pointers, n < 0 or n >= 2^31), BGL_ENOMEM, BGL_EHIP.
+ */
+int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64_t n, void *out_rows,
+                            int32_t *out_slot, int32_t *miss_pos, int64_t *n_hit_host,
+                            void *main_stream, void *side_stream);
+
+/*
+ * Cache update of Sec. 3.2.3 (last step) with the FIFO rule of Sec. 4: the
+ * buffer is a circular queue with a running `tail`; miss number r of this call
+ * (in miss_pos order) takes slot (tail + r) mod capacity, the node that held
+ * that slot is removed from the map, the new node is entered and its row
+ * copied from out_rows; then tail += n_miss.  The first insertion ever goes to
+ * slot 0.  With n_miss > capacity the result equals inserting one by one (only
+ * the last `capacity` misses stay).
+ *   ids, miss_pos, out_rows   device; as produced by bgl_cache_lookup_gather
+ *   n_miss          number of entries of miss_pos to insert, or -1 to use the
+ *                   miss count the last bgl_cache_lookup_gather left on the
+ *                   device (no host round trip)
+ * Must be enqueued after the lookup_gather that produced its inputs (same
+ * stream, or ordered by the caller).
+ * Errors: BGL_EINVAL, BGL_EHIP.
+ */
+int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const int32_t *miss_pos,
+                          int64_t n_miss, const void *out_rows, void *stream);
+
+/*
+ * Copy the logical cache state to the host (synchronises the device):
+ * slot_to_node[capacity] (-1 = empty slot), tail (insertions so far) and,
+ * if buffer is non-NULL, capacity * row_bytes bytes of cached rows.
+ */
+int bgl_cache_export_state(bgl_cache_t *c, int32_t *slot_to_node, uint64_t *tail, void *buffer);
+
+/*
+ * Counters since creation (synchronises the device): ids looked up, hits, rows
+ * inserted, rows evicted, and the sticky status word (BGL_OK, or BGL_EINVAL if
+ * an out-of-range id was ever seen, BGL_ECAPACITY if the map overflowed).
+ * Any output pointer may be NULL.
+ */
+int bgl_cache_stats(bgl_cache_t *c, uint64_t *lookups, uint64_t *hits, uint64_t *inserts,
+                    uint64_t *evictions, int32_t *status);
+
+/*
+ * Per-kernel timing for measurements.  When enabled, the cache brackets each of
+ * its kernels with HIP events on the stream the kernel runs on; bgl_cache_profile
+ * synchronises the device and returns the summed milliseconds and the number
+ * of launches of one stage since profiling was (re-)enabled.
+ */
+#define BGL_STAGE_PROBE 0       /* map lookup */
+#define BGL_STAGE_MISS_LIST 1   /* ordered list of miss positions + counters */
+#define BGL_STAGE_GATHER_HIT 2  /* cache buffer -> out_rows */
+#define BGL_STAGE_FETCH_MISS 3  /* backing store -> out_rows */
+#define BGL_STAGE_INSERT_MAP 4  /* evict + enter ids in the map */
+#define BGL_STAGE_INSERT_ROWS 5 /* out_rows -> cache buffer */
+#define BGL_NUM_STAGES 6
+int bgl_cache_set_profiling(bgl_cache_t *c, int enable);
+int bgl_cache_profile(bgl_cache_t *c, int stage, double *total_ms, int64_t *launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BGL_H */

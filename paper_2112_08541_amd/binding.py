@@ -1,0 +1,289 @@
+"""Thin ctypes binding over libbgl.so (the C ABI declared in include/bgl.h).
+
+Argument marshalling only: every step of sampling and of the cache workflow runs
+in the library's HIP kernels.  PyTorch supplies device memory, page-locked host
+memory and streams.  There is no fallback: importing this module without a built
+library, or calling it without a GPU, raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbgl.so")
+
+BGL_OK, BGL_EINVAL, BGL_ENOMEM, BGL_EHIP, BGL_ECAPACITY, BGL_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+BGL_MAX_HOPS = 8
+BGL_MAX_FANOUT = 64
+BGL_COUNTS_LEN = 2 * BGL_MAX_HOPS + 2
+BGL_DEVICE, BGL_HOST_PINNED = 0, 1
+(STAGE_PROBE, STAGE_MISS_LIST, STAGE_GATHER_HIT, STAGE_FETCH_MISS,
+ STAGE_INSERT_MAP, STAGE_INSERT_ROWS) = range(6)
+STAGE_NAMES = ["probe", "miss_list", "gather_hit", "fetch_miss", "insert_map", "insert_rows"]
+
+EXPORTS = [
+    "bgl_last_error", "bgl_graph_load_csr", "bgl_graph_destroy", "bgl_sample_workspace_bytes",
+    "bgl_sample_khop", "bgl_cache_create", "bgl_cache_destroy", "bgl_cache_lookup_gather",
+    "bgl_cache_insert_fifo", "bgl_cache_export_state", "bgl_cache_stats",
+    "bgl_cache_set_profiling", "bgl_cache_profile",
+]
+
+
+class BglError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"bgl status {code}: {msg}")
+        self.code = code
+
+
+class SubgraphStruct(C.Structure):
+    _fields_ = [
+        ("num_hops", C.c_int32),
+        ("input_nodes", C.c_void_p),
+        ("row_ptr", C.c_void_p * BGL_MAX_HOPS),
+        ("col_local", C.c_void_p * BGL_MAX_HOPS),
+        ("cap_nodes", C.c_int64 * (BGL_MAX_HOPS + 1)),
+        ("cap_edges", C.c_int64 * BGL_MAX_HOPS),
+        ("counts", C.c_void_p),
+    ]
+
+
+def load_library(path: str = LIB_PATH) -> C.CDLL:
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -m paper_2112_08541_amd.buildlib`")
+    L = C.CDLL(path)
+    i64, i32, u64, vp, ci = C.c_int64, C.c_int32, C.c_uint64, C.c_void_p, C.c_int
+    L.bgl_last_error.restype = C.c_char_p
+    L.bgl_last_error.argtypes = []
+    L.bgl_graph_load_csr.argtypes = [vp, ci, vp, i64, i64, ci, C.POINTER(vp)]
+    L.bgl_graph_destroy.argtypes = [vp]
+    L.bgl_sample_workspace_bytes.argtypes = [i32, vp, i32, i64, C.POINTER(C.c_size_t)]
+    L.bgl_sample_khop.argtypes = [vp, vp, i32, vp, i32, u64, vp, C.c_size_t,
+                                  C.POINTER(SubgraphStruct), vp, vp]
+    L.bgl_cache_create.argtypes = [i64, i32, vp, i64, C.POINTER(vp)]
+    L.bgl_cache_destroy.argtypes = [vp]
+    L.bgl_cache_lookup_gather.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, vp]
+    L.bgl_cache_insert_fifo.argtypes = [vp, vp, vp, i64, vp, vp]
+    L.bgl_cache_export_state.argtypes = [vp, vp, C.POINTER(u64), vp]
+    L.bgl_cache_stats.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(u64),
+                                  C.POINTER(u64), C.POINTER(i32)]
+    L.bgl_cache_set_profiling.argtypes = [vp, ci]
+    L.bgl_cache_profile.argtypes = [vp, ci, C.POINTER(C.c_double), C.POINTER(i64)]
+    for name in EXPORTS:
+        if name != "bgl_last_error":
+            getattr(L, name).restype = ci
+    return L
+
+
+_lib: Optional[C.CDLL] = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = load_library()
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != BGL_OK:
+        raise BglError(rc, lib().bgl_last_error().decode())
+
+
+def _require_gpu() -> None:
+    if not torch.cuda.is_available():
+        raise RuntimeError("paper_2112_08541_amd needs a GPU: there is no CPU path")
+
+
+def _stream_handle(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def _dev_ptr(t: Optional[torch.Tensor], dtype=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"expected dtype {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _host_ptr(x) -> int:
+    if isinstance(x, torch.Tensor):
+        if x.is_cuda or not x.is_contiguous():
+            raise ValueError("expected a contiguous host tensor")
+        return x.data_ptr()
+    if not x.flags.c_contiguous:
+        raise ValueError("expected a C-contiguous array")
+    return x.ctypes.data
+
+
+class Graph:
+    """bgl_graph_load_csr / bgl_graph_destroy."""
+
+    def __init__(self, row_ptr, col_idx, placement: int = BGL_DEVICE):
+        _require_gpu()
+        rp_dtype = row_ptr.dtype
+        bits = 64 if rp_dtype in (np.int64, torch.int64) else 32
+        if bits == 32 and rp_dtype not in (np.int32, torch.int32):
+            raise ValueError("row_ptr must be int32 or int64")
+        self.num_nodes = int(row_ptr.shape[0]) - 1
+        self.num_edges = int(col_idx.shape[0])
+        self.placement = placement
+        self._keep = (row_ptr, col_idx) if placement == BGL_HOST_PINNED else None
+        h = C.c_void_p()
+        _check(lib().bgl_graph_load_csr(_host_ptr(row_ptr), bits, _host_ptr(col_idx), self.num_nodes,
+                                        self.num_edges, placement, C.byref(h)))
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().bgl_graph_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+
+class SampledBatch:
+    """Device-side result of one bgl_sample_khop call (views into the sampler's workspace)."""
+
+    def __init__(self, sampler: "Sampler", st: SubgraphStruct):
+        self._s = sampler
+        self.struct = st
+        self.num_hops = st.num_hops
+
+    def counts(self) -> np.ndarray:
+        """Host copy of the counts block; the stream must have been synchronised."""
+        return self._s.counts_host.numpy().copy()
+
+    def sizes(self):
+        c = self.counts()
+        K = self.num_hops
+        status = int(c[BGL_COUNTS_LEN - 1])
+        if status != 0:
+            raise BglError(status, "sampling reported an error on the device (seed id out of range?)")
+        return c[: K + 1].astype(np.int64), c[BGL_MAX_HOPS + 1: BGL_MAX_HOPS + 1 + K].astype(np.int64)
+
+    def _view(self, ptr: int, n: int) -> torch.Tensor:
+        off = ptr - self._s.workspace.data_ptr()
+        return self._s.workspace[off: off + 4 * n].view(torch.int32)
+
+    def input_nodes(self, n: Optional[int] = None) -> torch.Tensor:
+        """int32 device view of frontier_K (first n entries; default: the upper bound)."""
+        K = self.num_hops
+        return self._view(self.struct.input_nodes, int(self.struct.cap_nodes[K]) if n is None else n)
+
+    def row_ptr(self, h: int, n_dst: int) -> torch.Tensor:
+        return self._view(self.struct.row_ptr[h], n_dst + 1)
+
+    def col_local(self, h: int, nnz: int) -> torch.Tensor:
+        return self._view(self.struct.col_local[h], nnz)
+
+
+class Sampler:
+    """Owns the device workspace for bgl_sample_khop at a fixed (num_seeds, fanouts)."""
+
+    def __init__(self, graph: Graph, num_seeds: int, fanouts: Sequence[int]):
+        _require_gpu()
+        self.graph = graph
+        self.num_seeds = int(num_seeds)
+        self.fanouts = np.ascontiguousarray(fanouts, dtype=np.int32)
+        nbytes = C.c_size_t(0)
+        _check(lib().bgl_sample_workspace_bytes(self.num_seeds, self.fanouts.ctypes.data,
+                                                len(self.fanouts), graph.num_nodes, C.byref(nbytes)))
+        self.workspace_bytes = int(nbytes.value)
+        self.workspace = torch.empty(self.workspace_bytes + 256, dtype=torch.uint8, device="cuda")
+        pad = (-self.workspace.data_ptr()) % 256
+        self.workspace = self.workspace[pad: pad + self.workspace_bytes]
+        self.counts_host = torch.zeros(BGL_COUNTS_LEN, dtype=torch.int32).pin_memory()
+
+    def sample(self, seeds: torch.Tensor, rng_seed: int, stream=None) -> SampledBatch:
+        if seeds.numel() != self.num_seeds:
+            raise ValueError("seed count differs from the one the workspace was sized for")
+        st = SubgraphStruct()
+        _check(lib().bgl_sample_khop(self.graph._h, _dev_ptr(seeds, torch.int32), self.num_seeds,
+                                     self.fanouts.ctypes.data, len(self.fanouts),
+                                     int(rng_seed) & (2**64 - 1), self.workspace.data_ptr(),
+                                     self.workspace_bytes, C.byref(st), self.counts_host.data_ptr(),
+                                     _stream_handle(stream)))
+        return SampledBatch(self, st)
+
+
+class Cache:
+    """bgl_cache_* calls on one cache handle."""
+
+    def __init__(self, capacity_rows: int, features, num_nodes: Optional[int] = None,
+                 row_bytes: Optional[int] = None):
+        _require_gpu()
+        if isinstance(features, torch.Tensor):
+            nn = features.shape[0]
+            rb = features.stride(0) * features.element_size()
+            ptr = features.data_ptr()
+        else:
+            nn = features.shape[0]
+            rb = features.strides[0]
+            ptr = features.ctypes.data
+        self.num_nodes = int(num_nodes if num_nodes is not None else nn)
+        self.row_bytes = int(row_bytes if row_bytes is not None else rb)
+        self.capacity = int(capacity_rows)
+        self._features = features
+        h = C.c_void_p()
+        _check(lib().bgl_cache_create(self.capacity, self.row_bytes, ptr, self.num_nodes, C.byref(h)))
+        self._h = h
+        self.n_hit_host = torch.zeros(1, dtype=torch.int64).pin_memory()
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().bgl_cache_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def lookup_gather(self, ids: torch.Tensor, n: int, out_rows: torch.Tensor, out_slot: torch.Tensor,
+                      miss_pos: torch.Tensor, main_stream=None, side_stream=None) -> None:
+        if n > 0 and (ids.numel() < n or out_slot.numel() < n or miss_pos.numel() < n or
+                      out_rows.numel() * out_rows.element_size() < n * self.row_bytes):
+            raise ValueError("an argument is smaller than n")
+        _check(lib().bgl_cache_lookup_gather(
+            self._h, _dev_ptr(ids, torch.int32), n, _dev_ptr(out_rows), _dev_ptr(out_slot, torch.int32),
+            _dev_ptr(miss_pos, torch.int32), self.n_hit_host.data_ptr(), _stream_handle(main_stream),
+            None if side_stream is None else int(side_stream.cuda_stream)))
+
+    def insert_fifo(self, ids: torch.Tensor, miss_pos: torch.Tensor, n_miss: int,
+                    out_rows: torch.Tensor, stream=None) -> None:
+        _check(lib().bgl_cache_insert_fifo(self._h, _dev_ptr(ids, torch.int32),
+                                           _dev_ptr(miss_pos, torch.int32), n_miss, _dev_ptr(out_rows),
+                                           _stream_handle(stream)))
+
+    def export_state(self, with_buffer: bool = True):
+        s2n = np.empty(self.capacity, dtype=np.int32)
+        tail = C.c_uint64(0)
+        buf = np.empty((self.capacity, self.row_bytes), dtype=np.uint8) if with_buffer else None
+        _check(lib().bgl_cache_export_state(self._h, s2n.ctypes.data, C.byref(tail),
+                                            buf.ctypes.data if with_buffer else None))
+        return s2n, int(tail.value), buf
+
+    def stats(self):
+        vals = [C.c_uint64(0) for _ in range(4)]
+        status = C.c_int32(0)
+        _check(lib().bgl_cache_stats(self._h, *[C.byref(v) for v in vals], C.byref(status)))
+        return dict(lookups=vals[0].value, hits=vals[1].value, inserts=vals[2].value,
+                    evictions=vals[3].value, status=status.value)
+
+    def set_profiling(self, enable: bool) -> None:
+        _check(lib().bgl_cache_set_profiling(self._h, 1 if enable else 0))
+
+    def profile(self):
+        out = {}
+        for s, name in enumerate(STAGE_NAMES):
+            ms, n = C.c_double(0), C.c_int64(0)
+            _check(lib().bgl_cache_profile(self._h, s, C.byref(ms), C.byref(n)))
+            out[name] = (ms.value, n.value)
+        return out

@@ -1,0 +1,675 @@
+// GPU-resident FIFO feature cache (BGL paper, Sec. 3.2: dynamic FIFO policy,
+// cache map + cache buffer per GPU, lookup / gather / fetch / update workflow;
+// Sec. 4 "Feature Cache Engine": circular buffer addressed through a running
+// tail, the occupant of the next position is evicted from the map and its row
+// overwritten, cache work on a dedicated stream).
+//
+// Cache map: open addressing over 128-byte buckets.  A bucket is 16 64-bit
+// words = exactly one cache line: words 0..14 hold (node id << 32 | slot) or
+// EMPTY, word 15 is a sticky overflow mark that is set when an insertion had to
+// walk past the full bucket.  A group of 16 lanes reads a bucket with one
+// coalesced request and finds the id with a wavefront ballot; a lookup ends at
+// the first bucket without the overflow mark.  Because the mark is only needed
+// for full buckets (rare at load <= 1/2), evictions simply blank their word:
+// no tombstones, no rebuilds.  slot_to_entry[slot] remembers the word that maps
+// a slot's occupant, so an eviction needs no search.
+#include <algorithm>
+#include <mutex>
+#include <vector>
+
+#include "bgl_internal.h"
+
+namespace {
+
+using namespace bgl;
+
+constexpr uint64_t EMPTY64 = ~0ull;
+constexpr int BUCKET = 16;       // 64-bit words per bucket (15 entries + overflow mark)
+constexpr int KEYS_PER_TILE = 256;  // ids per workgroup in probe / miss-list kernels
+constexpr int PROF_RING = 4096;
+
+struct CacheDev {          // device-resident scalars
+    unsigned long long tail;
+    unsigned long long lookups, hits, inserts;
+    long long n_miss_last;  // miss count of the most recent lookup
+    long long n_hit_last;   // hit count of the most recent lookup
+    int status;
+};
+
+}  // namespace
+
+struct bgl_cache {
+    int64_t capacity;
+    int32_t row_bytes;
+    int64_t num_nodes;
+    const char *features;   // device-visible backing store
+    int device;
+    char *buffer;           // capacity * row_bytes
+    uint64_t *table;        // num_buckets * BUCKET words
+    uint32_t num_buckets;   // power of two
+    int32_t *slot_to_node;  // capacity
+    uint32_t *slot_to_entry;
+    CacheDev *dev;
+    int32_t *mbs;           // per-tile miss counts, then their exclusive prefix
+    int64_t mbs_cap;
+    int64_t last_n;         // n of the most recent lookup
+    hipStream_t own_side;
+    hipEvent_t ev_probe, ev_miss;
+    // profiling
+    bool profiling;
+    std::vector<hipEvent_t> prof_ev;  // pairs
+    struct Rec { int stage; int ev; };
+    std::vector<Rec> prof_rec;
+    double prof_ms[BGL_NUM_STAGES];
+    int64_t prof_n[BGL_NUM_STAGES];
+};
+
+namespace {
+
+// ------------------------------------------------------------------ kernels
+__global__ void k_fill_u64(uint64_t *p, int64_t n, uint64_t v, int mark_stride)
+{
+    // every mark_stride-th word (the overflow marks) starts at 0
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = ((i % mark_stride) == mark_stride - 1) ? 0ull : v;
+}
+
+__global__ void k_fill_i32(int32_t *p, int64_t n, int32_t v)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = v;
+}
+
+// 16 lanes per id: one bucket (one cache line) per request, ballot for the match.
+__global__ __launch_bounds__(256) void k_probe(const int32_t *__restrict__ ids, int64_t n,
+                                               int64_t num_nodes,
+                                               const uint64_t *__restrict__ table,
+                                               uint32_t bucket_mask, int32_t *out_slot,
+                                               int32_t *mbs, CacheDev *dev)
+{
+    __shared__ int sh_miss;
+    if (threadIdx.x == 0) sh_miss = 0;
+    __syncthreads();
+    const int l = threadIdx.x & (BUCKET - 1);
+    const int grp = threadIdx.x / BUCKET;                 // 16 groups per workgroup
+    const int gshift = (threadIdx.x & (kWave - 1)) & ~(BUCKET - 1);
+    const int64_t tile0 = (int64_t)blockIdx.x * KEYS_PER_TILE;
+    int my_miss = 0;
+    for (int it = 0; it < KEYS_PER_TILE / 16; ++it) {
+        const int64_t i = tile0 + it * 16 + grp;
+        if (i >= n) break;  // uniform inside the group
+        const int32_t key = ids[i];
+        int slot = -1;
+        if (key < 0 || (int64_t)key >= num_nodes) {
+            if (l == 0) dev->status = BGL_EINVAL;
+        } else {
+            uint32_t b = hash32((uint32_t)key) & bucket_mask;
+            for (uint32_t tries = 0; tries <= bucket_mask; ++tries) {
+                const uint64_t e = table[(size_t)b * BUCKET + l];
+                const bool m = l < BUCKET - 1 && (uint32_t)(e >> 32) == (uint32_t)key;
+                const uint32_t mm = (uint32_t)(__ballot(m) >> gshift) & 0xffffu;
+                if (mm) {
+                    slot = (int)(uint32_t)__shfl(e, __ffs(mm) - 1, BUCKET);
+                    break;
+                }
+                const uint64_t mark = __shfl(e, BUCKET - 1, BUCKET);
+                if (mark == 0) break;  // nothing was ever pushed past this bucket
+                b = (b + 1) & bucket_mask;
+            }
+        }
+        if (l == 0) {
+            out_slot[i] = slot;
+            my_miss += slot < 0;
+        }
+    }
+    if (l == 0 && my_miss) atomicAdd(&sh_miss, my_miss);
+    __syncthreads();
+    if (threadIdx.x == 0) mbs[blockIdx.x] = sh_miss;
+}
+
+// One workgroup: exclusive prefix of the per-tile miss counts (in place) and
+// the call's counters.
+__global__ __launch_bounds__(1024) void k_scan_miss(int32_t *mbs, int64_t n, CacheDev *dev)
+{
+    __shared__ int sh_scan[1024 / kWave];
+    const int nb = (int)((n + KEYS_PER_TILE - 1) / KEYS_PER_TILE);
+    int carry = 0;
+    for (int base = 0; base < nb; base += 1024) {
+        const int idx = base + threadIdx.x;
+        const int v = idx < nb ? mbs[idx] : 0;
+        int tot;
+        const int ex = block_excl_scan<1024>(v, sh_scan, tot);
+        if (idx < nb) mbs[idx] = carry + ex;
+        carry += tot;
+    }
+    if (threadIdx.x == 0) {
+        dev->n_miss_last = carry;
+        dev->n_hit_last = n - carry;
+        dev->lookups += (unsigned long long)n;
+        dev->hits += (unsigned long long)(n - carry);
+    }
+}
+
+// Ordered list of miss positions.
+__global__ __launch_bounds__(KEYS_PER_TILE) void k_miss_list(const int32_t *__restrict__ out_slot,
+                                                             int64_t n,
+                                                             const int32_t *__restrict__ mpre,
+                                                             int32_t *miss_pos)
+{
+    __shared__ int sh_scan[KEYS_PER_TILE / kWave];
+    const int64_t i = (int64_t)blockIdx.x * KEYS_PER_TILE + threadIdx.x;
+    const int flag = (i < n && out_slot[i] < 0) ? 1 : 0;
+    int tot;
+    const int ex = block_excl_scan<KEYS_PER_TILE>(flag, sh_scan, tot);
+    if (flag) miss_pos[mpre[blockIdx.x] + ex] = (int32_t)i;
+}
+
+// Row copies move 16-byte chunks; a row has Q = row_bytes / 16 of them.  Chunk
+// index -> (row, chunk in row) with a compile-time Q where the width is a
+// common one, so the division is a multiply.
+template <int Q>
+struct RowSplit {
+    __device__ __forceinline__ static void split(int64_t idx, int q, int64_t &row, int &c)
+    {
+        if (Q > 0) { row = idx / Q; c = (int)(idx - row * Q); }
+        else { row = idx / q; c = (int)(idx - row * q); }
+    }
+};
+
+constexpr int COPY_THREADS = 256;
+constexpr int COPY_UNROLL = 4;
+
+// out[i] = buffer[out_slot[i]] for the hits.  Consecutive lanes take consecutive
+// 16-byte chunks of the output, so stores are fully coalesced and the loads of
+// one row are contiguous; four independent chunks per lane keep loads in flight.
+template <int Q>
+__global__ __launch_bounds__(COPY_THREADS) void k_gather_hits(
+    const int32_t *__restrict__ out_slot, int64_t n, int q, const uint4 *__restrict__ buffer,
+    uint4 *__restrict__ out)
+{
+    const int64_t total = n * (Q > 0 ? Q : q);
+    const int64_t base = (int64_t)blockIdx.x * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
+    uint4 v[COPY_UNROLL];
+    bool ok[COPY_UNROLL];
+#pragma unroll
+    for (int k = 0; k < COPY_UNROLL; ++k) {
+        const int64_t idx = base + k * COPY_THREADS;
+        ok[k] = false;
+        if (idx < total) {
+            int64_t row; int c;
+            RowSplit<Q>::split(idx, q, row, c);
+            const int slot = out_slot[row];
+            if (slot >= 0) {
+                ok[k] = true;
+                v[k] = buffer[(int64_t)slot * (Q > 0 ? Q : q) + c];
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < COPY_UNROLL; ++k)
+        if (ok[k]) out[base + k * COPY_THREADS] = v[k];
+}
+
+// out[i] = features[ids[i]] for the misses; the loads cross the host link when
+// the backing store is page-locked host memory.
+template <int Q>
+__global__ __launch_bounds__(COPY_THREADS) void k_fetch_miss(
+    const int32_t *__restrict__ out_slot, const int32_t *__restrict__ ids, int64_t n, int q,
+    int64_t num_nodes, const uint4 *__restrict__ features, uint4 *__restrict__ out)
+{
+    const int64_t total = n * (Q > 0 ? Q : q);
+    const int64_t base = (int64_t)blockIdx.x * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
+    uint4 v[COPY_UNROLL];
+    bool ok[COPY_UNROLL];
+#pragma unroll
+    for (int k = 0; k < COPY_UNROLL; ++k) {
+        const int64_t idx = base + k * COPY_THREADS;
+        ok[k] = false;
+        if (idx < total) {
+            int64_t row; int c;
+            RowSplit<Q>::split(idx, q, row, c);
+            if (out_slot[row] < 0) {
+                const int32_t id = ids[row];
+                if (id >= 0 && (int64_t)id < num_nodes) {
+                    ok[k] = true;
+                    v[k] = features[(int64_t)id * (Q > 0 ? Q : q) + c];
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < COPY_UNROLL; ++k)
+        if (ok[k]) out[base + k * COPY_THREADS] = v[k];
+}
+
+__device__ __forceinline__ void insert_range(const CacheDev *dev, int64_t n_miss_arg,
+                                             int64_t capacity, int64_t &n_miss, int64_t &start)
+{
+    n_miss = n_miss_arg >= 0 ? n_miss_arg : dev->n_miss_last;
+    start = n_miss > capacity ? n_miss - capacity : 0;  // earlier ranks would be overwritten
+}
+
+// Map update: 16 lanes per inserted row.  Evict the slot's occupant (blank its
+// word), then claim a free word in the new id's bucket chain with a CAS.
+__global__ __launch_bounds__(256) void k_insert_map(const int32_t *__restrict__ ids,
+                                                    const int32_t *__restrict__ miss_pos,
+                                                    int64_t n_miss_arg, int64_t capacity,
+                                                    int64_t num_nodes, uint64_t *table,
+                                                    uint32_t bucket_mask, int32_t *slot_to_node,
+                                                    uint32_t *slot_to_entry, CacheDev *dev)
+{
+    int64_t n_miss, start;
+    insert_range(dev, n_miss_arg, capacity, n_miss, start);
+    const int l = threadIdx.x & (BUCKET - 1);
+    const int gshift = (threadIdx.x & (kWave - 1)) & ~(BUCKET - 1);
+    const int64_t r = start + ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / BUCKET;
+    if (r >= n_miss) return;  // uniform inside the group
+    const int64_t slot = (int64_t)((dev->tail + (unsigned long long)r) % (unsigned long long)capacity);
+    const int32_t key = ids[miss_pos[r]];
+    const int32_t old = slot_to_node[slot];
+    if (old >= 0 && l == 0)
+        __hip_atomic_store(&table[slot_to_entry[slot]], EMPTY64, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    if (key < 0 || (int64_t)key >= num_nodes) {
+        // reported by the lookup already: the slot's row will be overwritten, so
+        // leave the slot unmapped rather than mapped to the wrong bytes
+        if (l == 0) {
+            slot_to_node[slot] = -1;
+            dev->status = BGL_EINVAL;
+        }
+        return;
+    }
+    const uint64_t mine = ((uint64_t)(uint32_t)key << 32) | (uint32_t)slot;
+    uint32_t b = hash32((uint32_t)key) & bucket_mask;
+    uint32_t entry = 0;
+    bool done = false;
+    // every failed CAS means another group filled a word: at most 15 retries per
+    // bucket, and a table at load <= 1/2 always has a bucket with a free word
+    for (uint32_t tries = 0; tries < 16u * (bucket_mask + 1u) && !done; ++tries) {
+        const uint64_t e = __hip_atomic_load(&table[(size_t)b * BUCKET + l], __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
+        const bool free_word = l < BUCKET - 1 && e == EMPTY64;
+        const uint32_t fm = (uint32_t)(__ballot(free_word) >> gshift) & 0xffffu;
+        if (fm) {
+            const int t = __ffs(fm) - 1;
+            int won = 0;
+            if (l == t) {
+                unsigned long long prev = atomicCAS(
+                    (unsigned long long *)&table[(size_t)b * BUCKET + t], EMPTY64, mine);
+                won = prev == EMPTY64;
+            }
+            won = __shfl(won, t, BUCKET);
+            if (won) {
+                entry = b * BUCKET + (uint32_t)t;
+                done = true;
+            }
+        } else {
+            if (l == BUCKET - 1 && e == 0)
+                __hip_atomic_store(&table[(size_t)b * BUCKET + l], 1ull, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            b = (b + 1) & bucket_mask;
+        }
+    }
+    if (l == 0) {
+        if (done) {
+            slot_to_node[slot] = key;
+            slot_to_entry[slot] = entry;
+        } else {
+            dev->status = BGL_ECAPACITY;
+        }
+    }
+}
+
+// buffer[(tail + r) % capacity] = out[miss_pos[r]]: the destination is a
+// contiguous (wrapping) run of slots, so the stores stream.
+template <int Q>
+__global__ __launch_bounds__(COPY_THREADS) void k_insert_rows(
+    const int32_t *__restrict__ miss_pos, int64_t n_miss_arg, int64_t capacity, int q,
+    const uint4 *__restrict__ out, uint4 *__restrict__ buffer, const CacheDev *dev)
+{
+    int64_t n_miss, start;
+    insert_range(dev, n_miss_arg, capacity, n_miss, start);
+    const int qq = Q > 0 ? Q : q;
+    const int64_t total = (n_miss - start) * qq;
+    const int64_t base = (int64_t)blockIdx.x * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
+    if ((int64_t)blockIdx.x * (COPY_THREADS * COPY_UNROLL) >= total) return;
+    const unsigned long long tail = dev->tail;
+    uint4 v[COPY_UNROLL];
+    int64_t dst[COPY_UNROLL];
+#pragma unroll
+    for (int k = 0; k < COPY_UNROLL; ++k) {
+        const int64_t idx = base + k * COPY_THREADS;
+        dst[k] = -1;
+        if (idx < total) {
+            int64_t rr; int c;
+            RowSplit<Q>::split(idx, q, rr, c);
+            const int64_t r = start + rr;
+            const int64_t slot = (int64_t)((tail + (unsigned long long)r) % (unsigned long long)capacity);
+            v[k] = out[(int64_t)miss_pos[r] * qq + c];
+            dst[k] = slot * qq + c;
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < COPY_UNROLL; ++k)
+        if (dst[k] >= 0) buffer[dst[k]] = v[k];
+}
+
+__global__ void k_advance_tail(CacheDev *dev, int64_t n_miss_arg)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        const long long n = n_miss_arg >= 0 ? n_miss_arg : dev->n_miss_last;
+        dev->tail += (unsigned long long)n;
+        dev->inserts += (unsigned long long)n;
+    }
+}
+
+// ------------------------------------------------------------------ host helpers
+struct Prof {
+    bgl_cache *c;
+    hipStream_t st;
+    int ev = -1;
+    Prof(bgl_cache *c_, int stage, hipStream_t st_) : c(c_), st(st_)
+    {
+        if (!c->profiling || c->prof_rec.size() >= PROF_RING) return;
+        ev = (int)c->prof_rec.size() * 2;
+        c->prof_rec.push_back({stage, ev});
+        (void)hipEventRecord(c->prof_ev[ev], st);
+    }
+    ~Prof()
+    {
+        if (ev >= 0) (void)hipEventRecord(c->prof_ev[ev + 1], st);
+    }
+};
+
+void drain_profile(bgl_cache *c)
+{
+    for (auto &r : c->prof_rec) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, c->prof_ev[r.ev], c->prof_ev[r.ev + 1]) == hipSuccess) {
+            c->prof_ms[r.stage] += ms;
+            c->prof_n[r.stage] += 1;
+        }
+    }
+    c->prof_rec.clear();
+}
+
+template <typename F>
+void dispatch_q(int q, F &&f)
+{
+    switch (q) {
+    case 25: f(std::integral_constant<int, 25>{}); break;  // 100 x fp32
+    case 32: f(std::integral_constant<int, 32>{}); break;  // 128 x fp32
+    case 64: f(std::integral_constant<int, 64>{}); break;  // 512 x bf16
+    default: f(std::integral_constant<int, 0>{}); break;
+    }
+}
+
+int copy_blocks(int64_t rows, int q)
+{
+    return (int)bgl::ceil_div(rows * q, (int64_t)COPY_THREADS * COPY_UNROLL);
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ C ABI
+extern "C" int bgl_cache_create(int64_t capacity_rows, int32_t row_bytes,
+                                const void *host_features, int64_t num_nodes, bgl_cache_t **out)
+{
+    if (!out) BGL_FAIL(BGL_EINVAL, "out is null");
+    *out = nullptr;
+    if (capacity_rows < 1 || capacity_rows > INT32_MAX)
+        BGL_FAIL(BGL_EINVAL, "capacity_rows must be in [1, 2^31) (got %lld)", (long long)capacity_rows);
+    if (row_bytes < 16 || row_bytes % 16 != 0)
+        BGL_FAIL(BGL_EINVAL, "row_bytes must be a positive multiple of 16 (got %d)", row_bytes);
+    if (num_nodes < 1 || num_nodes > INT32_MAX) BGL_FAIL(BGL_EINVAL, "num_nodes out of range");
+    if (!host_features || !bgl::aligned(host_features, 16))
+        BGL_FAIL(BGL_EINVAL, "host_features is null or not 16-byte aligned");
+
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, host_features) != hipSuccess) {
+        (void)hipGetLastError();
+        BGL_FAIL(BGL_EINVAL, "host_features is neither page-locked host memory nor device memory");
+    }
+    const char *feat_dev = nullptr;
+    if (attr.type == hipMemoryTypeHost || attr.type == hipMemoryTypeDevice ||
+        attr.type == hipMemoryTypeManaged) {
+        feat_dev = static_cast<const char *>(attr.devicePointer);
+    }
+    if (!feat_dev)
+        BGL_FAIL(BGL_EINVAL, "host_features is neither page-locked host memory nor device memory");
+
+    bgl_cache *c = new (std::nothrow) bgl_cache();
+    if (!c) BGL_FAIL(BGL_ENOMEM, "out of host memory");
+    c->capacity = capacity_rows;
+    c->row_bytes = row_bytes;
+    c->num_nodes = num_nodes;
+    c->features = feat_dev;
+    c->profiling = false;
+    for (int s = 0; s < BGL_NUM_STAGES; ++s) { c->prof_ms[s] = 0; c->prof_n[s] = 0; }
+    c->mbs = nullptr;
+    c->mbs_cap = 0;
+    c->last_n = 0;
+    // load <= 1/2 of the 15 usable words per bucket
+    uint64_t nbk = 1;
+    while (nbk * 15 < (uint64_t)capacity_rows * 2) nbk <<= 1;
+    c->num_buckets = (uint32_t)nbk;
+
+    auto fail = [&](int code) { bgl_cache_destroy(c); return code; };
+    hipError_t e;
+    if (hipGetDevice(&c->device) != hipSuccess) { bgl::set_error("hipGetDevice failed"); return fail(BGL_EHIP); }
+#define TRY_ALLOC(ptr, bytes)                                                              \
+    if ((e = hipMalloc((void **)&(ptr), (bytes))) != hipSuccess) {                         \
+        bgl::set_error("hipMalloc of %zu bytes failed: %s", (size_t)(bytes), hipGetErrorString(e)); \
+        return fail(e == hipErrorOutOfMemory ? BGL_ENOMEM : BGL_EHIP);                     \
+    }
+    TRY_ALLOC(c->buffer, (size_t)capacity_rows * row_bytes);
+    TRY_ALLOC(c->table, (size_t)nbk * BUCKET * sizeof(uint64_t));
+    TRY_ALLOC(c->slot_to_node, (size_t)capacity_rows * sizeof(int32_t));
+    TRY_ALLOC(c->slot_to_entry, (size_t)capacity_rows * sizeof(uint32_t));
+    TRY_ALLOC(c->dev, sizeof(CacheDev));
+#undef TRY_ALLOC
+    if (hipStreamCreateWithFlags(&c->own_side, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_probe, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_miss, hipEventDisableTiming) != hipSuccess) {
+        bgl::set_error("stream/event creation failed");
+        return fail(BGL_EHIP);
+    }
+    hipLaunchKernelGGL(k_fill_u64, dim3(2048), dim3(256), 0, 0, c->table, (int64_t)nbk * BUCKET,
+                       EMPTY64, BUCKET);
+    hipLaunchKernelGGL(k_fill_i32, dim3(1024), dim3(256), 0, 0, c->slot_to_node, capacity_rows, -1);
+    if (hipMemset(c->dev, 0, sizeof(CacheDev)) != hipSuccess ||
+        hipMemset(c->buffer, 0, (size_t)capacity_rows * row_bytes) != hipSuccess ||
+        hipDeviceSynchronize() != hipSuccess) {
+        bgl::set_error("cache initialisation failed: %s", hipGetErrorString(hipGetLastError()));
+        return fail(BGL_EHIP);
+    }
+    *out = c;
+    return BGL_OK;
+}
+
+extern "C" int bgl_cache_destroy(bgl_cache_t *c)
+{
+    if (!c) return BGL_OK;
+    (void)hipDeviceSynchronize();
+    for (auto ev : c->prof_ev) (void)hipEventDestroy(ev);
+    if (c->ev_probe) (void)hipEventDestroy(c->ev_probe);
+    if (c->ev_miss) (void)hipEventDestroy(c->ev_miss);
+    if (c->own_side) (void)hipStreamDestroy(c->own_side);
+    (void)hipFree(c->buffer);
+    (void)hipFree(c->table);
+    (void)hipFree(c->slot_to_node);
+    (void)hipFree(c->slot_to_entry);
+    (void)hipFree(c->dev);
+    (void)hipFree(c->mbs);
+    delete c;
+    return BGL_OK;
+}
+
+extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64_t n,
+                                       void *out_rows, int32_t *out_slot, int32_t *miss_pos,
+                                       int64_t *n_hit_host, void *main_stream, void *side_stream)
+{
+    if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
+    if (n < 0 || n > INT32_MAX) BGL_FAIL(BGL_EINVAL, "n must be in [0, 2^31) (got %lld)", (long long)n);
+    if (n > 0 && (!ids || !out_rows || !out_slot || !miss_pos))
+        BGL_FAIL(BGL_EINVAL, "ids, out_rows, out_slot and miss_pos must not be null");
+    if (!bgl::aligned(out_rows, 16)) BGL_FAIL(BGL_EINVAL, "out_rows is not 16-byte aligned");
+    hipStream_t ms = static_cast<hipStream_t>(main_stream);
+    hipStream_t ss = side_stream ? static_cast<hipStream_t>(side_stream) : c->own_side;
+    const int64_t tiles = bgl::ceil_div(n, KEYS_PER_TILE);
+    if (tiles + 1 > c->mbs_cap) {
+        BGL_HIP(hipStreamSynchronize(ms));
+        (void)hipFree(c->mbs);
+        c->mbs = nullptr;
+        c->mbs_cap = 0;
+        const int64_t cap = std::max<int64_t>(2 * tiles + 1, 1024);
+        BGL_HIP(hipMalloc((void **)&c->mbs, sizeof(int32_t) * (size_t)cap));
+        c->mbs_cap = cap;
+    }
+    c->last_n = n;
+    const int q = c->row_bytes / 16;
+    if (n > 0) {
+        {
+            Prof p(c, BGL_STAGE_PROBE, ms);
+            hipLaunchKernelGGL(k_probe, dim3((unsigned)tiles), dim3(256), 0, ms, ids, n, c->num_nodes,
+                               c->table, c->num_buckets - 1, out_slot, c->mbs, c->dev);
+        }
+        const bool two_streams = ss != ms;
+        if (two_streams) {
+            BGL_HIP(hipEventRecord(c->ev_probe, ms));
+            BGL_HIP(hipStreamWaitEvent(ss, c->ev_probe, 0));
+        }
+        {
+            Prof p(c, BGL_STAGE_FETCH_MISS, ss);
+            dispatch_q(q, [&](auto Q) {
+                hipLaunchKernelGGL((k_fetch_miss<decltype(Q)::value>), dim3(copy_blocks(n, q)),
+                                   dim3(COPY_THREADS), 0, ss, out_slot, ids, n, q, c->num_nodes,
+                                   reinterpret_cast<const uint4 *>(c->features),
+                                   reinterpret_cast<uint4 *>(out_rows));
+            });
+        }
+        if (two_streams) BGL_HIP(hipEventRecord(c->ev_miss, ss));
+        {
+            Prof p(c, BGL_STAGE_MISS_LIST, ms);
+            hipLaunchKernelGGL(k_scan_miss, dim3(1), dim3(1024), 0, ms, c->mbs, n, c->dev);
+            hipLaunchKernelGGL(k_miss_list, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), 0, ms, out_slot,
+                               n, c->mbs, miss_pos);
+        }
+        if (n_hit_host)
+            BGL_HIP(hipMemcpyAsync(n_hit_host, &c->dev->n_hit_last, sizeof(int64_t),
+                                   hipMemcpyDeviceToHost, ms));
+        {
+            Prof p(c, BGL_STAGE_GATHER_HIT, ms);
+            dispatch_q(q, [&](auto Q) {
+                hipLaunchKernelGGL((k_gather_hits<decltype(Q)::value>), dim3(copy_blocks(n, q)),
+                                   dim3(COPY_THREADS), 0, ms, out_slot, n, q,
+                                   reinterpret_cast<const uint4 *>(c->buffer),
+                                   reinterpret_cast<uint4 *>(out_rows));
+            });
+        }
+        if (two_streams) BGL_HIP(hipStreamWaitEvent(ms, c->ev_miss, 0));
+    } else {
+        hipLaunchKernelGGL(k_scan_miss, dim3(1), dim3(1024), 0, ms, c->mbs, (int64_t)0, c->dev);
+        if (n_hit_host)
+            BGL_HIP(hipMemcpyAsync(n_hit_host, &c->dev->n_hit_last, sizeof(int64_t),
+                                   hipMemcpyDeviceToHost, ms));
+    }
+    BGL_HIP(hipGetLastError());
+    return BGL_OK;
+}
+
+extern "C" int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const int32_t *miss_pos,
+                                     int64_t n_miss, const void *out_rows, void *stream)
+{
+    if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
+    if (n_miss < -1 || n_miss > INT32_MAX) BGL_FAIL(BGL_EINVAL, "n_miss out of range");
+    const int64_t bound = n_miss >= 0 ? n_miss : c->last_n;  // launch size
+    if (bound > 0 && (!ids || !miss_pos || !out_rows))
+        BGL_FAIL(BGL_EINVAL, "ids, miss_pos and out_rows must not be null");
+    if (!bgl::aligned(out_rows, 16)) BGL_FAIL(BGL_EINVAL, "out_rows is not 16-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int q = c->row_bytes / 16;
+    const int64_t eff = std::min<int64_t>(bound, c->capacity);
+    if (eff > 0) {
+        {
+            Prof p(c, BGL_STAGE_INSERT_MAP, st);
+            hipLaunchKernelGGL(k_insert_map, dim3((unsigned)bgl::ceil_div(eff * BUCKET, 256)), dim3(256),
+                               0, st, ids, miss_pos, n_miss, c->capacity, c->num_nodes, c->table,
+                               c->num_buckets - 1, c->slot_to_node, c->slot_to_entry, c->dev);
+        }
+        {
+            Prof p(c, BGL_STAGE_INSERT_ROWS, st);
+            dispatch_q(q, [&](auto Q) {
+                hipLaunchKernelGGL((k_insert_rows<decltype(Q)::value>), dim3(copy_blocks(eff, q)),
+                                   dim3(COPY_THREADS), 0, st, miss_pos, n_miss, c->capacity, q,
+                                   reinterpret_cast<const uint4 *>(out_rows),
+                                   reinterpret_cast<uint4 *>(c->buffer), c->dev);
+            });
+        }
+    }
+    hipLaunchKernelGGL(k_advance_tail, dim3(1), dim3(64), 0, st, c->dev, n_miss);
+    BGL_HIP(hipGetLastError());
+    return BGL_OK;
+}
+
+extern "C" int bgl_cache_export_state(bgl_cache_t *c, int32_t *slot_to_node, uint64_t *tail,
+                                      void *buffer)
+{
+    if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
+    BGL_HIP(hipDeviceSynchronize());
+    if (slot_to_node)
+        BGL_HIP(hipMemcpy(slot_to_node, c->slot_to_node, sizeof(int32_t) * (size_t)c->capacity,
+                          hipMemcpyDeviceToHost));
+    if (tail) {
+        CacheDev h;
+        BGL_HIP(hipMemcpy(&h, c->dev, sizeof(h), hipMemcpyDeviceToHost));
+        *tail = h.tail;
+    }
+    if (buffer)
+        BGL_HIP(hipMemcpy(buffer, c->buffer, (size_t)c->capacity * c->row_bytes, hipMemcpyDeviceToHost));
+    return BGL_OK;
+}
+
+extern "C" int bgl_cache_stats(bgl_cache_t *c, uint64_t *lookups, uint64_t *hits, uint64_t *inserts,
+                               uint64_t *evictions, int32_t *status)
+{
+    if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
+    BGL_HIP(hipDeviceSynchronize());
+    CacheDev h;
+    BGL_HIP(hipMemcpy(&h, c->dev, sizeof(h), hipMemcpyDeviceToHost));
+    if (lookups) *lookups = h.lookups;
+    if (hits) *hits = h.hits;
+    if (inserts) *inserts = h.inserts;
+    // every insertion beyond the first `capacity` ones overwrote an occupied slot
+    if (evictions) *evictions = h.tail > (uint64_t)c->capacity ? h.tail - (uint64_t)c->capacity : 0;
+    if (status) *status = h.status;
+    return BGL_OK;
+}
+
+extern "C" int bgl_cache_set_profiling(bgl_cache_t *c, int enable)
+{
+    if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
+    BGL_HIP(hipDeviceSynchronize());
+    if (enable && c->prof_ev.empty()) {
+        c->prof_ev.resize(2 * PROF_RING, nullptr);
+        for (auto &ev : c->prof_ev) BGL_HIP(hipEventCreate(&ev));
+    }
+    c->prof_rec.clear();
+    c->prof_rec.reserve(PROF_RING);
+    for (int s = 0; s < BGL_NUM_STAGES; ++s) { c->prof_ms[s] = 0; c->prof_n[s] = 0; }
+    c->profiling = enable != 0;
+    return BGL_OK;
+}
+
+extern "C" int bgl_cache_profile(bgl_cache_t *c, int stage, double *total_ms, int64_t *launches)
+{
+    if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
+    if (stage < 0 || stage >= BGL_NUM_STAGES) BGL_FAIL(BGL_EINVAL, "unknown stage %d", stage);
+    BGL_HIP(hipDeviceSynchronize());
+    drain_profile(c);
+    if (total_ms) *total_ms = c->prof_ms[stage];
+    if (launches) *launches = c->prof_n[stage];
+    return BGL_OK;
+}

@@ -1,0 +1,255 @@
+"""Seeded synthetic workloads shaped like the paper's datasets (Table 2 of the
+paper: node/edge counts and feature widths of Ogbn-products and Ogbn-papers;
+batch size and fanouts of its Sec. 5.1).  None of those datasets is used: the
+graphs here are generated power-law graphs with the same shapes.
+
+This module only produces *inputs* (graphs, feature tables, seed lists, one
+64-bit RNG seed per batch).  It contains nothing of the sampling or caching
+method, so both the HIP library's tests and the CPU oracle's tests can be fed
+from it.  It imports neither of them.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import dataclasses
+import os
+import subprocess
+from typing import List, Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "csrc", "gen_inputs.c")
+_LIB = os.path.join(_HERE, "libbgl_gen.so")
+
+
+def build(force: bool = False) -> str:
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared",
+                               "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def _gen() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB):
+            build()
+        L = C.CDLL(_LIB)
+        i64, i32, u64, vp, dbl = C.c_int64, C.c_int32, C.c_uint64, C.c_void_p, C.c_double
+        L.bglgen_degrees.restype = i64
+        L.bglgen_degrees.argtypes = [i64, dbl, i64, i64, u64, vp]
+        L.bglgen_row_ptr.restype = i64
+        L.bglgen_row_ptr.argtypes = [i64, vp, vp, C.c_int]
+        L.bglgen_permutation.restype = None
+        L.bglgen_permutation.argtypes = [i64, u64, vp, vp]
+        L.bglgen_edges.restype = C.c_int
+        L.bglgen_edges.argtypes = [i64, vp, C.c_int, vp, u64, i64, dbl, dbl, vp, vp]
+        L.bglgen_features.restype = C.c_int
+        L.bglgen_features.argtypes = [i64, i32, i32, u64, vp]
+        L.bglgen_bfs_order.restype = i64
+        L.bglgen_bfs_order.argtypes = [i64, vp, C.c_int, vp, vp, i64, vp]
+        _lib = L
+    return _lib
+
+
+@dataclasses.dataclass(frozen=True)
+class Config:
+    """One benchmark/parity configuration (the five of the project's baseline file)."""
+    name: str
+    num_nodes: int
+    mean_degree: float
+    dmax: int
+    feat_dim: int
+    feat_dtype: str            # "f32" | "bf16"
+    batch: int
+    fanouts: tuple
+    cache_rows: int
+    num_batches: int
+    order: str                 # "random_all" | "random_train" | "po"
+    train_size: int
+    row_ptr_bits: int = 32
+    graph_placement: str = "device"   # "device" | "host_pinned"
+    seed: int = 20211208
+    comm_size: int = 4096
+    p_local: float = 0.75
+    beta: float = 0.75
+    po_sequences: int = 5
+    dmin: int = 1
+
+    @property
+    def elem_bytes(self) -> int:
+        return 4 if self.feat_dtype == "f32" else 2
+
+    @property
+    def row_bytes(self) -> int:
+        return self.feat_dim * self.elem_bytes
+
+
+CONFIGS = {
+    "tiny": Config("tiny", 10_000, 10.0, 1_000, 100, "f32", 512, (10, 5), 2_000, 20,
+                   "random_all", 0, seed=20211208, dmin=2),
+    "mid": Config("mid", 2_450_000, 50.2, 20_000, 100, "f32", 1024, (15, 10, 5), 490_000, 200,
+                  "random_train", 204_800, seed=20211209, dmin=8),
+    "bfs": Config("bfs", 2_450_000, 50.2, 20_000, 100, "f32", 1024, (15, 10, 5), 245_000, 200,
+                  "po", 204_800, seed=20211209, dmin=8),
+    "large": Config("large", 111_000_000, 14.4, 50_000, 128, "f32", 1024, (15, 10, 5), 25_000_000, 200,
+                    "random_train", 1_200_000, row_ptr_bits=64, graph_placement="host_pinned",
+                    seed=20211211, dmin=3),
+    "wide": Config("wide", 30_000_000, 20.0, 20_000, 512, "bf16", 4096, (25, 10), 4_500_000, 100,
+                   "random_train", 409_600, seed=20211212, dmin=4),
+}
+
+
+def scaled(cfg: Config, num_nodes: int, num_batches: Optional[int] = None) -> Config:
+    """Same shape at a smaller node count: cache fraction, training fraction and
+    degree distribution are kept; used where the full size does not fit."""
+    f = num_nodes / cfg.num_nodes
+    return dataclasses.replace(
+        cfg, name=f"{cfg.name}@{num_nodes}", num_nodes=num_nodes,
+        dmax=max(4 * cfg.dmin, int(cfg.mean_degree * 4), min(cfg.dmax, num_nodes // 4)),
+        cache_rows=max(16, int(round(cfg.cache_rows * f))),
+        train_size=(max(cfg.batch * (num_batches or cfg.num_batches),
+                        int(round(cfg.train_size * f))) if cfg.train_size else 0),
+        num_batches=num_batches or cfg.num_batches)
+
+
+def _alloc(shape, dtype, pinned: bool):
+    """numpy array, optionally backed by page-locked memory (needs a GPU runtime)."""
+    if pinned:
+        import torch
+        if torch.cuda.is_available():
+            tdt = {np.dtype(np.int32): torch.int32, np.dtype(np.int64): torch.int64,
+                   np.dtype(np.float32): torch.float32, np.dtype(np.uint16): torch.uint16,
+                   np.dtype(np.uint8): torch.uint8}[np.dtype(dtype)]
+            t = torch.empty(shape, dtype=tdt, pin_memory=True)
+            a = t.numpy()
+            return a, t
+    return np.empty(shape, dtype=dtype), None
+
+
+@dataclasses.dataclass
+class Workload:
+    cfg: Config
+    row_ptr: np.ndarray          # int32 or int64 [N+1]
+    col: np.ndarray              # int32 [E]
+    features: np.ndarray         # float32 [N, dim] or uint16 (bf16 bits) [N, dim]
+    seed_batches: np.ndarray     # int32 [num_batches, batch]
+    rng_seeds: np.ndarray        # uint64 [num_batches], one per sampling call
+    keepalive: list = dataclasses.field(default_factory=list)
+
+    @property
+    def num_edges(self) -> int:
+        return int(self.row_ptr[-1])
+
+    def feature_bytes(self) -> np.ndarray:
+        return self.features.view(np.uint8).reshape(self.features.shape[0], -1)
+
+
+def make_graph(cfg: Config, pinned: bool = False):
+    g = _gen()
+    N = cfg.num_nodes
+    deg = np.empty(N, dtype=np.int32)
+    E = g.bglgen_degrees(N, float(cfg.mean_degree), int(cfg.dmin), int(cfg.dmax), cfg.seed, deg.ctypes.data)
+    if E < 0:
+        raise ValueError("bad degree parameters")
+    if cfg.row_ptr_bits == 32 and E >= 2**31:
+        raise ValueError("edge count needs 64-bit row offsets")
+    keep = []
+    rp, t = _alloc(N + 1, np.int64 if cfg.row_ptr_bits == 64 else np.int32, pinned)
+    keep.append(t)
+    g.bglgen_row_ptr(N, deg.ctypes.data, rp.ctypes.data, cfg.row_ptr_bits)
+    del deg
+    col, t = _alloc(max(E, 1), np.int32, pinned)
+    keep.append(t)
+    perm = np.empty(N, dtype=np.int32)
+    inv = np.empty(N, dtype=np.int32)
+    g.bglgen_permutation(N, cfg.seed + 1, perm.ctypes.data, inv.ctypes.data)
+    rc = g.bglgen_edges(N, rp.ctypes.data, cfg.row_ptr_bits, col.ctypes.data, cfg.seed + 2,
+                        cfg.comm_size, cfg.p_local, cfg.beta, perm.ctypes.data, inv.ctypes.data)
+    if rc != 0:
+        raise ValueError("edge generation failed")
+    return rp, col[:E], keep
+
+
+def make_features(cfg: Config, pinned: bool = False):
+    dt = np.float32 if cfg.feat_dtype == "f32" else np.uint16
+    feats, t = _alloc((cfg.num_nodes, cfg.feat_dim), dt, pinned)
+    rc = _gen().bglgen_features(cfg.num_nodes, cfg.feat_dim, cfg.elem_bytes, cfg.seed + 3, feats.ctypes.data)
+    if rc != 0:
+        raise ValueError("feature generation failed")
+    return feats, [t]
+
+
+def bfs_order(row_ptr: np.ndarray, col: np.ndarray, is_train: np.ndarray, root: int) -> np.ndarray:
+    N = len(row_ptr) - 1
+    bits = 64 if row_ptr.dtype == np.int64 else 32
+    is_train = np.ascontiguousarray(is_train, dtype=np.uint8)
+    out = np.empty(int(is_train.sum()), dtype=np.int32)
+    n = _gen().bglgen_bfs_order(N, row_ptr.ctypes.data, bits, col.ctypes.data,
+                                is_train.ctypes.data, int(root), out.ctypes.data)
+    if n != len(out):
+        raise RuntimeError("BFS order did not visit every training node")
+    return out
+
+
+def proximity_order(row_ptr, col, train_nodes: np.ndarray, n_sequences: int,
+                    batch: int, num_batches: int, rng: np.random.Generator) -> np.ndarray:
+    """Seed order of the paper's Sec. 3.2.2: several breadth-first sequences over
+    the training nodes from random roots, each rotated by a random offset; batches
+    take nodes from the sequences in turn, skipping nodes already used."""
+    N = len(row_ptr) - 1
+    is_train = np.zeros(N, dtype=np.uint8)
+    is_train[train_nodes] = 1
+    seqs = []
+    for _ in range(n_sequences):
+        root = int(rng.integers(0, N))
+        s = bfs_order(row_ptr, col, is_train, root)
+        seqs.append(np.roll(s, int(rng.integers(0, len(s)))))
+    used = np.zeros(N, dtype=bool)
+    cursors = [0] * n_sequences
+    order = np.empty(batch * num_batches, dtype=np.int32)
+    k, turn = 0, 0
+    total = len(train_nodes)
+    while k < len(order):
+        if k >= total:
+            raise ValueError("not enough training nodes for the requested batches")
+        s = seqs[turn % n_sequences]
+        c = cursors[turn % n_sequences]
+        while used[s[c]]:
+            c += 1
+        order[k] = s[c]
+        used[s[c]] = True
+        cursors[turn % n_sequences] = c + 1
+        k += 1
+        turn += 1
+    return order.reshape(num_batches, batch)
+
+
+def make_seed_batches(cfg: Config, row_ptr=None, col=None) -> np.ndarray:
+    rng = np.random.default_rng(cfg.seed + 4)
+    N, B, nb = cfg.num_nodes, cfg.batch, cfg.num_batches
+    if cfg.order == "random_all":
+        return np.stack([rng.choice(N, size=B, replace=False) for _ in range(nb)]).astype(np.int32)
+    train = rng.choice(N, size=cfg.train_size, replace=False).astype(np.int32)
+    if cfg.order == "random_train":
+        if B * nb > len(train):
+            raise ValueError("training set smaller than one epoch of batches")
+        return rng.permutation(train)[: B * nb].reshape(nb, B).astype(np.int32)
+    if cfg.order == "po":
+        return proximity_order(row_ptr, col, train, cfg.po_sequences, B, nb, rng)
+    raise ValueError(cfg.order)
+
+
+def make_workload(cfg: Config, pinned: bool = False) -> Workload:
+    """Generate everything one configuration needs.  `pinned` places the feature
+    table (and, for host-resident graphs, the CSR) in page-locked memory."""
+    rp, col, keep = make_graph(cfg, pinned and cfg.graph_placement == "host_pinned")
+    feats, keep2 = make_features(cfg, pinned)
+    seeds = make_seed_batches(cfg, rp, col)
+    rng = np.random.default_rng(cfg.seed + 5)
+    rng_seeds = rng.integers(0, 2**64, size=cfg.num_batches, dtype=np.uint64)
+    return Workload(cfg, rp, col, feats, seeds, rng_seeds, keep + keep2)

@@ -1,0 +1,313 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU
+oracle, bit for bit (sampled ids, CSR blocks, lookup results, feature bytes,
+cache state).  Integer and byte work only, so the bar is exact equality."""
+import dataclasses
+import os
+
+import numpy as np
+import pytest
+
+from helpers import GpuPipeline, OraclePipeline, assert_batch_equal, assert_state_equal
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch_mod():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return torch
+
+
+@pytest.fixture(scope="module")
+def B(torch_mod):
+    from paper_2112_08541_amd import binding
+    binding.lib()  # must load: there is no fallback
+    return binding
+
+
+def _inputs():
+    from paper_2112_08541_amd import inputs
+    return inputs
+
+
+# ------------------------------------------------------------------ sampling
+def csr_from_adj(adj, dtype=np.int32):
+    rp = np.zeros(len(adj) + 1, dtype=dtype)
+    col = []
+    for i, row in enumerate(adj):
+        col.extend(row)
+        rp[i + 1] = len(col)
+    return rp, np.array(col if col else [0], dtype=np.int32)[: len(col)]
+
+
+def gpu_sample(B, torch, rp, col, seeds, fanouts, rng_seed, placement=None):
+    g = B.Graph(rp, col, B.BGL_DEVICE if placement is None else placement)
+    s = B.Sampler(g, len(seeds), fanouts)
+    sb = s.sample(torch.tensor(seeds, dtype=torch.int32, device="cuda"), rng_seed)
+    torch.cuda.synchronize()
+    nf, nnz = sb.sizes()
+    K = len(fanouts)
+    res = dict(n_frontier=nf, nnz=nnz, input_nodes=sb.input_nodes(int(nf[K])).cpu().numpy(),
+               row_ptr=[sb.row_ptr(h, int(nf[h])).cpu().numpy() for h in range(K)],
+               col_local=[sb.col_local(h, int(nnz[h])).cpu().numpy() for h in range(K)])
+    return res
+
+
+def assert_sample_equal(res, sg):
+    assert res["n_frontier"].tolist() == sg.n_frontier.tolist()
+    assert res["nnz"].tolist() == list(sg.nnz)
+    assert np.array_equal(res["input_nodes"], sg.input_nodes)
+    for h in range(len(sg.nnz)):
+        assert np.array_equal(res["row_ptr"][h], sg.row_ptr[h])
+        assert np.array_equal(res["col_local"][h], sg.col_local[h])
+
+
+TINY_GRAPHS = {
+    "path": [[1], [0, 2], [1, 3], [2, 4], [3]],
+    "star": [[1, 2, 3, 4, 5, 6, 7], [0], [0], [0], [0], [0], [0], [0]],
+    "clique6": [[j for j in range(6) if j != i] for i in range(6)],
+    "two_components": [[1, 2], [0, 2], [0, 1], [4], [3, 5], [4]],
+    "isolated": [[1], [0], [], [0, 1]],
+    "multi_edges": [[1, 1, 1, 2], [0, 0], [2, 2, 0, 0, 1]],
+}
+
+
+@pytest.mark.parametrize("name", sorted(TINY_GRAPHS))
+@pytest.mark.parametrize("dtype", [np.int32, np.int64])
+def test_sample_tiny_graphs(B, torch_mod, name, dtype):
+    import oracle
+    rp, col = csr_from_adj(TINY_GRAPHS[name], dtype)
+    N = len(rp) - 1
+    for fanouts in ([2], [1, 1], [2, 2, 2], [3, 1], [10, 10], [64]):
+        for seed in range(3):
+            seeds = [seed % N, (seed * 3 + 1) % N, seed % N]
+            res = gpu_sample(B, torch_mod, rp, col, seeds, fanouts, 1000 + seed)
+            assert_sample_equal(res, oracle.sample_khop(rp, col, seeds, fanouts, 1000 + seed))
+
+
+@pytest.mark.parametrize("fanouts", [(1,), (3,), (4,), (5, 5), (8, 3), (15, 10, 5), (16,), (17,), (25, 10),
+                                     (33, 2), (64, 1), (2, 2, 2, 2, 2, 2, 2, 2)])
+def test_sample_random_graph_all_group_widths(B, torch_mod, fanouts):
+    """Dense-ish random graph so that Floyd's algorithm (degree > fanout) runs for
+    every lane-group width, several tiles and a ragged tail."""
+    import oracle
+    rng = np.random.default_rng(sum(fanouts))
+    N = 3000
+    deg = rng.integers(0, 120, N)
+    deg[rng.integers(0, N, 50)] = 0
+    rp = np.zeros(N + 1, dtype=np.int32)
+    rp[1:] = np.cumsum(deg)
+    col = rng.integers(0, N, rp[-1]).astype(np.int32)
+    seeds = rng.integers(0, N, 777).astype(np.int32)  # with repeats
+    for s in (1, 2**63 + 12345):
+        res = gpu_sample(B, torch_mod, rp, col, seeds.tolist(), list(fanouts), s)
+        assert_sample_equal(res, oracle.sample_khop(rp, col, seeds, list(fanouts), s))
+
+
+def test_sample_high_degree_hub_and_host_pinned_graph(B, torch_mod):
+    import oracle
+    rng = np.random.default_rng(11)
+    N = 5000
+    deg = rng.integers(1, 8, N)
+    deg[7] = 70000  # hub with degree far above 2^16
+    rp = np.zeros(N + 1, dtype=np.int64)
+    rp[1:] = np.cumsum(deg)
+    col = rng.integers(0, N, rp[-1]).astype(np.int32)
+    col[rp[100]: rp[101]] = 7  # make the hub reachable
+    rp_t = torch_mod.from_numpy(rp).pin_memory()
+    col_t = torch_mod.from_numpy(col).pin_memory()
+    seeds = [100, 7, 3, 4000]
+    for fan in ([15, 10], [64, 64]):
+        res = gpu_sample(B, torch_mod, rp_t, col_t, seeds, fan, 99, B.BGL_HOST_PINNED)
+        assert_sample_equal(res, oracle.sample_khop(rp, col, seeds, fan, 99))
+
+
+def test_sample_is_deterministic_and_seed_sensitive(B, torch_mod):
+    w = _inputs().make_workload(_inputs().CONFIGS["tiny"])
+    a = gpu_sample(B, torch_mod, w.row_ptr, w.col, w.seed_batches[0].tolist(), [10, 5], 5)
+    b = gpu_sample(B, torch_mod, w.row_ptr, w.col, w.seed_batches[0].tolist(), [10, 5], 5)
+    c = gpu_sample(B, torch_mod, w.row_ptr, w.col, w.seed_batches[0].tolist(), [10, 5], 6)
+    assert np.array_equal(a["input_nodes"], b["input_nodes"])
+    assert all(np.array_equal(x, y) for x, y in zip(a["col_local"], b["col_local"]))
+    assert not np.array_equal(a["input_nodes"], c["input_nodes"])
+
+
+def test_sample_reports_out_of_range_seed(B, torch_mod):
+    rp, col = csr_from_adj(TINY_GRAPHS["path"])
+    g = B.Graph(rp, col)
+    s = B.Sampler(g, 3, [2])
+    sb = s.sample(torch_mod.tensor([0, 9, 1], dtype=torch_mod.int32, device="cuda"), 1)
+    torch_mod.cuda.synchronize()
+    with pytest.raises(B.BglError) as e:
+        sb.sizes()
+    assert e.value.code == B.BGL_EINVAL
+
+
+# --------------------------------------------------------------------- cache
+def run_cache_stream(B, torch, feats, cap, batches, device_n_miss=False, side=True):
+    """Feed id batches through GPU cache and oracle cache; compare after every call."""
+    import oracle
+    N, rb = feats.shape[0], feats.shape[1] * feats.itemsize
+    feat_t = torch.from_numpy(feats.view(np.uint8).reshape(N, rb)).pin_memory()
+    gc = B.Cache(cap, feat_t, num_nodes=N, row_bytes=rb)
+    oc = oracle.Cache(cap, feats)
+    side_stream = torch.cuda.Stream() if side else None
+    for bi, ids in enumerate(batches):
+        n = len(ids)
+        ids_t = torch.tensor(ids, dtype=torch.int32, device="cuda") if n else torch.empty(1, dtype=torch.int32, device="cuda")
+        out = torch.full((max(n, 1), rb), 0xCD, dtype=torch.uint8, device="cuda")
+        out_slot = torch.full((max(n, 1),), -7, dtype=torch.int32, device="cuda")
+        miss_pos = torch.full((max(n, 1),), -7, dtype=torch.int32, device="cuda")
+        gc.lookup_gather(ids_t, n, out, out_slot, miss_pos, side_stream=side_stream)
+        o_out, o_slot, o_miss, o_hit = oc.lookup_gather(ids)
+        if device_n_miss:
+            gc.insert_fifo(ids_t, miss_pos, -1, out)
+            torch.cuda.synchronize()
+            n_hit = int(gc.n_hit_host[0])
+        else:
+            torch.cuda.synchronize()
+            n_hit = int(gc.n_hit_host[0])
+            gc.insert_fifo(ids_t, miss_pos, n - n_hit, out)
+        oc.insert_fifo(ids, o_miss, o_out)
+        assert n_hit == o_hit, f"batch {bi}"
+        assert np.array_equal(out_slot[:n].cpu().numpy(), o_slot), f"batch {bi}"
+        assert np.array_equal(miss_pos[: n - n_hit].cpu().numpy(), o_miss), f"batch {bi}"
+        assert np.array_equal(out[:n].cpu().numpy(), o_out), f"batch {bi}"
+        assert_state_equal(gc, oc, f"batch {bi}")
+    return gc, oc
+
+
+def test_cache_hand_worked_example(B, torch_mod, golden_dir):
+    lines = [l.strip() for l in open(os.path.join(golden_dir, "fifo_worked_example.txt"))
+             if l.strip() and not l.startswith("#")]
+    cap = int(lines[0].split()[1])
+    batches, expect = [], []
+    for l in lines[1:]:
+        if l.startswith("batch"):
+            parts = [p.split() for p in l[len("batch"):].split("|")]
+            batches.append([int(x) for x in parts[0]])
+            expect.append(([int(x) for x in parts[2]], int(parts[3][0])))
+    feats = np.random.default_rng(0).standard_normal((16, 4)).astype(np.float32)
+    gc, _ = run_cache_stream(B, torch_mod, feats, cap, batches)
+    s2n, tail, _ = gc.export_state(False)
+    assert s2n.tolist() == expect[-1][0] and tail == expect[-1][1]
+    assert gc.stats()["hits"] == 2 and gc.stats()["lookups"] == 13
+
+
+@pytest.mark.parametrize("dim,dtype", [(4, np.float32), (100, np.float32), (128, np.float32),
+                                       (512, np.uint16), (12, np.float32), (264, np.uint16)])
+@pytest.mark.parametrize("device_n_miss", [False, True])
+def test_cache_random_streams(B, torch_mod, dim, dtype, device_n_miss):
+    rng = np.random.default_rng(dim)
+    N, cap = 20000, 3000
+    if dtype == np.float32:
+        feats = rng.standard_normal((N, dim)).astype(np.float32)
+    else:
+        feats = rng.integers(0, 2**16, (N, dim), dtype=np.uint16)
+    batches = []
+    for b in range(12):
+        size = int(rng.integers(1, 2500)) if b != 5 else 7000  # batch 5: more misses than slots
+        hot = rng.zipf(1.2, size) % N
+        batches.append(list(dict.fromkeys(hot.tolist())))
+    batches.insert(3, [])          # empty lookup
+    batches.insert(8, batches[7])  # immediate repeat: all hits unless evicted
+    run_cache_stream(B, torch_mod, feats, cap, batches, device_n_miss=device_n_miss)
+
+
+def test_cache_single_stream_and_tiny_capacity(B, torch_mod):
+    rng = np.random.default_rng(3)
+    feats = rng.standard_normal((500, 8)).astype(np.float32)
+    batches = [rng.permutation(500)[: int(rng.integers(1, 200))].tolist() for _ in range(15)]
+    run_cache_stream(B, torch_mod, feats, 1, batches, side=False)
+    run_cache_stream(B, torch_mod, feats, 17, batches, side=False)
+    run_cache_stream(B, torch_mod, feats, 500, batches)
+
+
+def test_cache_long_churn_keeps_map_exact(B, torch_mod):
+    """Many times the capacity flows through a small cache: every eviction blanks a
+    map word and every insertion reuses one; lookups must stay exact."""
+    rng = np.random.default_rng(5)
+    N, cap = 50000, 1500
+    feats = rng.standard_normal((N, 4)).astype(np.float32)
+    batches = [rng.permutation(N)[:1400].tolist() for _ in range(60)]
+    gc, oc = run_cache_stream(B, torch_mod, feats, cap, batches, device_n_miss=True)
+    # full map check: look up every node id
+    ids = torch_mod.arange(N, dtype=torch_mod.int32, device="cuda")
+    out = torch_mod.empty((N, 16), dtype=torch_mod.uint8, device="cuda")
+    out_slot = torch_mod.empty(N, dtype=torch_mod.int32, device="cuda")
+    miss_pos = torch_mod.empty(N, dtype=torch_mod.int32, device="cuda")
+    gc.lookup_gather(ids, N, out, out_slot, miss_pos)
+    torch_mod.cuda.synchronize()
+    assert np.array_equal(out_slot.cpu().numpy(), oc.node_to_slot)
+    assert np.array_equal(out.cpu().numpy(), feats.view(np.uint8).reshape(N, 16))
+
+
+def test_cache_flags_out_of_range_id(B, torch_mod):
+    feats = np.zeros((10, 4), dtype=np.float32)
+    feat_t = torch_mod.from_numpy(feats.view(np.uint8).reshape(10, 16)).pin_memory()
+    gc = B.Cache(4, feat_t, num_nodes=10, row_bytes=16)
+    ids = torch_mod.tensor([1, 10, 2], dtype=torch_mod.int32, device="cuda")
+    out = torch_mod.full((3, 16), 0x55, dtype=torch_mod.uint8, device="cuda")
+    out_slot = torch_mod.empty(3, dtype=torch_mod.int32, device="cuda")
+    miss_pos = torch_mod.empty(3, dtype=torch_mod.int32, device="cuda")
+    gc.lookup_gather(ids, 3, out, out_slot, miss_pos)
+    gc.insert_fifo(ids, miss_pos, -1, out)
+    assert gc.stats()["status"] == B.BGL_EINVAL
+    assert out[1].cpu().tolist() == [0x55] * 16  # untouched row
+
+
+# ------------------------------------------------------------ whole pipeline
+def run_config(cfg, n_batches, device_n_miss=False, check_every=1):
+    inputs = _inputs()
+    w = inputs.make_workload(cfg, pinned=True)
+    gp = GpuPipeline(w, device_n_miss=device_n_miss)
+    op = OraclePipeline(w)
+    hits = total = 0
+    for b in range(n_batches):
+        full = (b % check_every == 0) or b == n_batches - 1
+        g = gp.run_batch(w.seed_batches[b], w.rng_seeds[b], fetch=full)
+        o = op.run_batch(w.seed_batches[b], w.rng_seeds[b])
+        if full:
+            assert_batch_equal(g, o, f"{cfg.name} batch {b}")
+        else:
+            assert g["n"] == o["n"] and g["n_hit"] == o["n_hit"], f"{cfg.name} batch {b}"
+        hits += o["n_hit"]
+        total += o["n"]
+    assert_state_equal(gp.cache, op.cache, cfg.name)
+    return hits / max(total, 1)
+
+
+def test_pipeline_tiny_config_all_batches():
+    cfg = _inputs().CONFIGS["tiny"]
+    run_config(cfg, cfg.num_batches)
+    run_config(cfg, cfg.num_batches, device_n_miss=True)
+
+
+def test_pipeline_mid_config_full_size():
+    cfg = _inputs().CONFIGS["mid"]
+    run_config(cfg, 12, device_n_miss=True, check_every=4)
+
+
+def test_pipeline_bfs_order_config_full_size_and_locality():
+    inputs = _inputs()
+    po = run_config(inputs.CONFIGS["bfs"], 10, check_every=5)
+    rnd = run_config(dataclasses.replace(inputs.CONFIGS["bfs"], order="random_train", name="bfs-random"),
+                     10, check_every=5)
+    # proximity-aware order must beat random order at equal cache size (paper Sec. 3.2.2)
+    assert po > rnd
+
+
+def test_pipeline_large_shape_scaled():
+    """Large config's shape (int64 offsets, CSR read in place from page-locked host
+    memory, 512-byte rows) at 1/50 of the node count."""
+    inputs = _inputs()
+    cfg = inputs.scaled(inputs.CONFIGS["large"], 2_220_000, num_batches=6)
+    run_config(cfg, 6, check_every=2)
+
+
+def test_pipeline_wide_shape_scaled():
+    """Wide config's shape (bf16 x 512 rows, 4096 seeds, fanout 25/10) at 1/10 of the nodes."""
+    inputs = _inputs()
+    cfg = inputs.scaled(inputs.CONFIGS["wide"], 3_000_000, num_batches=4)
+    run_config(cfg, 4, check_every=2)
