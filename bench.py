@@ -1,0 +1,229 @@
+#!/usr/bin/env python3
+"""Benchmark of the minibatch-preparation hot path on one MI355X.
+
+One "step" = one minibatch through the whole path: k-hop neighbor sampling,
+cache lookup, gather of the hits from HBM, fetch of the misses from page-locked
+host memory, FIFO insertion.  Workload: the "mid" configuration (2.45 M nodes,
+~122 M edges, fp32 x 100 features, 1,024 seeds, fanout 15/10/5, cache of 20 % of
+the nodes, one epoch of 200 random-order batches starting from an empty cache),
+a synthetic stand-in with the shape of Ogbn-products.
+
+Prints ONE JSON line; see the design doc for how each field is measured.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+HOST_LINK_NOMINAL_GBS = 64.0   # PCIe Gen5 x16, one direction, nominal
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="mid", help="workload preset (default: mid)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stage-timers", action="store_true",
+                    help="leave the per-kernel HIP events out of the timed region")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run three plain 1 GiB device-to-device copies (the known-size "
+                         "kernel that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--cpu-batches", type=int, default=100,
+                    help="batches of the same workload the oracle is timed on")
+    return ap.parse_args()
+
+
+def measure_h2d_peak(torch, nbytes=256 << 20):
+    """Pinned-memory host-to-device copy rate on this machine (GB/s), the practical
+    ceiling of the host link that the miss fetch is compared with."""
+    src = torch.empty(nbytes, dtype=torch.uint8).pin_memory()
+    dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    dst.copy_(src, non_blocking=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(4):
+        dst.copy_(src, non_blocking=True)
+    torch.cuda.synchronize()
+    return 4 * nbytes / (time.perf_counter() - t0) / 1e9
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        return 2
+    import numpy as np
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    if args.calibrate_copy:
+        a = torch.full((1 << 30,), 7, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": 1 << 30, "copies": 3}))
+        return 0
+    from paper_2112_08541_amd import binding as B
+    from paper_2112_08541_amd import inputs
+
+    cfg = inputs.CONFIGS[args.config]
+    torch.cuda.set_device(0)
+    w = inputs.make_workload(cfg, pinned=True)
+    feat_t = next(t for t in w.keepalive if t is not None and t.data_ptr() == w.features.ctypes.data)
+    placement = B.BGL_HOST_PINNED if cfg.graph_placement == "host_pinned" else B.BGL_DEVICE
+    graph = B.Graph(w.row_ptr, w.col, placement)
+    sampler = B.Sampler(graph, cfg.batch, cfg.fanouts)
+    cap = int(min(cfg.num_nodes, cfg.batch * np.prod([1 + f for f in cfg.fanouts])))
+    out_rows = torch.empty((cap, cfg.row_bytes), dtype=torch.uint8, device="cuda")
+    out_slot = torch.empty(cap, dtype=torch.int32, device="cuda")
+    miss_pos = torch.empty(cap, dtype=torch.int32, device="cuda")
+    seeds_dev = torch.from_numpy(w.seed_batches).cuda()      # inputs resident in HBM
+    side = torch.cuda.Stream()
+    main_stream = torch.cuda.current_stream()
+    nb = cfg.num_batches
+    K = len(cfg.fanouts)
+
+    # Two sampling workspaces: batch i+1 is sampled while batch i's misses cross the host link.
+    samplers = [sampler, B.Sampler(graph, cfg.batch, cfg.fanouts)]
+
+    def run_epoch(cache, steps, record):
+        """`steps` minibatches, software-pipelined two deep.  Per batch i:
+        lookup_gather(i) [main: probe, lists, hit gather; side: miss fetch] ->
+        sample(i+1) on main, overlapping the fetch -> insert_fifo(i) (waits for the
+        fetch) -> the host waits only for sample(i+1)'s sizes.  Cache state advances
+        strictly batch by batch."""
+        n_list, hit_list = [], []
+        sb = samplers[0].sample(seeds_dev[0], int(w.rng_seeds[0]))
+        main_stream.synchronize()
+        n = int(samplers[0].counts_host[K])
+        ev = torch.cuda.Event()
+        for i in range(steps):
+            ids = sb.input_nodes(cap)
+            cache.lookup_gather(ids, n, out_rows, out_slot, miss_pos, side_stream=side)
+            nxt = i + 1
+            if nxt < steps:
+                b = nxt % nb
+                smp = samplers[nxt % 2]
+                sb_next = smp.sample(seeds_dev[b], int(w.rng_seeds[b]) ^ (nxt // nb))
+                ev.record(main_stream)
+            cache.insert_fifo(ids, miss_pos, -1, out_rows)
+            n_list.append(n)
+            if nxt < steps:
+                ev.synchronize()                     # sizes of batch i+1 (and n_hit of batch i) are on the host
+                hit_list.append(int(cache.n_hit_host[0]))
+                n = int(smp.counts_host[K])
+                sb = sb_next
+        torch.cuda.synchronize()
+        hit_list.append(int(cache.n_hit_host[0]))
+        return n_list, hit_list
+
+    # warm-up on a scratch cache of the same size, so the timed epoch starts from an empty cache
+    if args.warmup > 0:
+        scratch = B.Cache(cfg.cache_rows, feat_t, num_nodes=cfg.num_nodes, row_bytes=cfg.row_bytes)
+        run_epoch(scratch, args.warmup, False)
+        scratch.close()
+
+    cache = B.Cache(cfg.cache_rows, feat_t, num_nodes=cfg.num_nodes, row_bytes=cfg.row_bytes)
+    if not args.no_stage_timers:
+        cache.set_profiling(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    n_list, hit_list = run_epoch(cache, args.steps, True)
+    t1 = time.perf_counter()
+    elapsed = t1 - t0
+
+    n_arr, h_arr = np.array(n_list, dtype=np.int64), np.array(hit_list, dtype=np.int64)
+    tot_n, tot_hit = int(n_arr.sum()), int(h_arr.sum())
+    tot_miss = tot_n - tot_hit
+    st = cache.stats()
+    assert st["status"] == 0 and st["lookups"] == tot_n and st["hits"] == tot_hit
+    # steady state: batches issued after the cache has filled once
+    filled = np.cumsum(n_arr - h_arr) >= cfg.cache_rows
+    steady = slice(int(np.argmax(filled)) + 1, None) if filled.any() else slice(0, 0)
+    steady_ratio = (float(h_arr[steady].sum()) / float(n_arr[steady].sum())) if n_arr[steady].sum() else None
+
+    rb = cfg.row_bytes
+    result = {
+        "metric": "minibatches/sec + gathered feature GB/s (% HBM peak) + cache hit ratio",
+        "value": args.steps / elapsed,
+        "unit": "minibatches/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": 1e3 * elapsed / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{cfg.name}: N={cfg.num_nodes} E={w.num_edges} power-law graph, "
+                        f"{cfg.feat_dtype} x {cfg.feat_dim} features, batch {cfg.batch}, "
+                        f"fanout {list(cfg.fanouts)}, FIFO cache {cfg.cache_rows} rows, "
+                        f"{cfg.order} seed order, epoch from an empty cache",
+            "row_bytes": rb,
+            "mean_input_nodes": tot_n / args.steps,
+            "hit_ratio_cumulative": tot_hit / max(tot_n, 1),
+            "hit_ratio_steady_state": steady_ratio,
+            "gathered_feature_GBps": rb * tot_n / elapsed / 1e9,
+        },
+    }
+    if not args.no_stage_timers:
+        prof = cache.profile()
+        g_ms, g_n = prof["gather_hit"]
+        f_ms, f_n = prof["fetch_miss"]
+        achieved = 2.0 * rb * tot_hit / (g_ms * 1e-3) / 1e9 if g_ms > 0 else 0.0
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", "gather_hit_mid_traffic.json")
+        if os.path.exists(tpath):
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        result["roofline"] = {
+            "kernel": "k_gather_hits", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+            "bytes_per_launch": 2.0 * rb * tot_hit / max(g_n, 1),
+            "avg_launch_us": 1e3 * g_ms / max(g_n, 1), "launches": g_n,
+        }
+        link = tot_miss * rb / (f_ms * 1e-3) / 1e9 if f_ms > 0 else 0.0
+        h2d = measure_h2d_peak(torch)
+        result["host_link"] = {
+            "kernel": "k_fetch_miss", "achieved": link, "unit": "GB/s",
+            "nominal_peak": HOST_LINK_NOMINAL_GBS, "measured_h2d_copy_peak": h2d,
+            "frac_of_nominal": link / HOST_LINK_NOMINAL_GBS, "frac_of_measured": link / h2d,
+            "avg_launch_us": 1e3 * f_ms / max(f_n, 1),
+        }
+        result["stage_ms_per_step"] = {k: v[0] / max(v[1], 1) for k, v in prof.items()}
+
+    if not args.no_cpu_baseline:
+        import oracle
+        oc = oracle.Cache(cfg.cache_rows, w.features)
+        nbat = min(args.cpu_batches, nb)
+        c0 = time.perf_counter()
+        for b in range(nbat):
+            sg = oracle.sample_khop(w.row_ptr, w.col, w.seed_batches[b], cfg.fanouts, int(w.rng_seeds[b]))
+            out, o_slot, o_miss, o_hit = oc.lookup_gather(sg.input_nodes)
+            oc.insert_fifo(sg.input_nodes, o_miss, out)
+        c1 = time.perf_counter()
+        result["cpu_baseline"] = {
+            "value": nbat / (c1 - c0), "unit": "minibatches/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {nbat} of the {nb} batches of the same workload, same inputs, "
+                      "from an empty cache (includes the Python/numpy marshalling around the C oracle)",
+            "host_cores_available": os.cpu_count(),
+        }
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -163,11 +163,17 @@ int bgl_cache_destroy(bgl_cache_t *c);
  *   out_slot        device, n ints: buffer slot of ids[i], or -1 for a miss
  *   miss_pos        device, room for n ints: the positions i of the misses, ascending
  *   n_hit_host      optional page-locked host int64 that receives the number of hits
- *   main_stream     probe, hit gather and miss list run here
- *   side_stream     the miss fetch runs here, concurrently with the hit gather
- *                   (NULL: a stream owned by the cache).  Before returning, the
- *                   call makes main_stream wait for it, so in main_stream order
- *                   all outputs are complete.
+ *   main_stream     probe, miss list and hit gather run here; in main_stream
+ *                   order out_slot, miss_pos, the hit count and the rows of the
+ *                   hits are complete when the call's work is done
+ *   side_stream     the miss fetch runs here (NULL: a stream owned by the
+ *                   cache), after the hit gather, so that work enqueued on
+ *                   main_stream afterwards (the next batch's sampling) overlaps
+ *                   the host-link transfer.  The rows of the misses are complete
+ *                   for a stream once it has passed bgl_cache_wait_rows or the
+ *                   following bgl_cache_insert_fifo.  If side_stream equals
+ *                   main_stream everything is in main_stream order.
+ * ids, out_rows and miss_pos must stay untouched until the miss fetch is done.
  * An id outside [0, num_nodes) is reported as a miss whose row is left
  * untouched, and sets the cache's status (bgl_cache_stats) to BGL_EINVAL.
  * Errors: BGL_EINVAL (null/misaligned pointers, n < 0 or n >= 2^31), BGL_ENOMEM, BGL_EHIP.
@@ -189,11 +195,19 @@ int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64_t n, void 
  *                   miss count the last bgl_cache_lookup_gather left on the
  *                   device (no host round trip)
  * Must be enqueued after the lookup_gather that produced its inputs (same
- * stream, or ordered by the caller).
+ * stream, or ordered by the caller); it waits for that call's miss fetch itself.
  * Errors: BGL_EINVAL, BGL_EHIP.
  */
 int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const int32_t *miss_pos,
                           int64_t n_miss, const void *out_rows, void *stream);
+
+/*
+ * Make `stream` wait (on the device, not the host) until the miss rows of the
+ * most recent bgl_cache_lookup_gather are in out_rows.  A no-op when that call
+ * ran on a single stream.  Consumers of out_rows other than
+ * bgl_cache_insert_fifo (the model's first layer) call this first.
+ */
+int bgl_cache_wait_rows(bgl_cache_t *c, void *stream);
 
 /*
  * Copy the logical cache state to the host (synchronises the device):

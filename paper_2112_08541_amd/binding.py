@@ -29,7 +29,7 @@ STAGE_NAMES = ["probe", "miss_list", "gather_hit", "fetch_miss", "insert_map", "
 EXPORTS = [
     "bgl_last_error", "bgl_graph_load_csr", "bgl_graph_destroy", "bgl_sample_workspace_bytes",
     "bgl_sample_khop", "bgl_cache_create", "bgl_cache_destroy", "bgl_cache_lookup_gather",
-    "bgl_cache_insert_fifo", "bgl_cache_export_state", "bgl_cache_stats",
+    "bgl_cache_insert_fifo", "bgl_cache_wait_rows", "bgl_cache_export_state", "bgl_cache_stats",
     "bgl_cache_set_profiling", "bgl_cache_profile",
 ]
 
@@ -68,6 +68,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     L.bgl_cache_destroy.argtypes = [vp]
     L.bgl_cache_lookup_gather.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, vp]
     L.bgl_cache_insert_fifo.argtypes = [vp, vp, vp, i64, vp, vp]
+    L.bgl_cache_wait_rows.argtypes = [vp, vp]
     L.bgl_cache_export_state.argtypes = [vp, vp, C.POINTER(u64), vp]
     L.bgl_cache_stats.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(u64),
                                   C.POINTER(u64), C.POINTER(i32)]
@@ -144,7 +145,7 @@ class Graph:
         self._h = h
 
     def close(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and lib is not None:
             lib().bgl_graph_destroy(self._h)
             self._h = None
 
@@ -240,7 +241,7 @@ class Cache:
         self.n_hit_host = torch.zeros(1, dtype=torch.int64).pin_memory()
 
     def close(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and lib is not None:
             lib().bgl_cache_destroy(self._h)
             self._h = None
 
@@ -261,6 +262,9 @@ class Cache:
         _check(lib().bgl_cache_insert_fifo(self._h, _dev_ptr(ids, torch.int32),
                                            _dev_ptr(miss_pos, torch.int32), n_miss, _dev_ptr(out_rows),
                                            _stream_handle(stream)))
+
+    def wait_rows(self, stream=None) -> None:
+        _check(lib().bgl_cache_wait_rows(self._h, _stream_handle(stream)))
 
     def export_state(self, with_buffer: bool = True):
         s2n = np.empty(self.capacity, dtype=np.int32)

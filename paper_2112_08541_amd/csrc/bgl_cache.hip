@@ -52,9 +52,12 @@ struct bgl_cache {
     CacheDev *dev;
     int32_t *mbs;           // per-tile miss counts, then their exclusive prefix
     int64_t mbs_cap;
+    int32_t *hit_pos;       // positions of the hits of the most recent lookup
+    int64_t hit_cap;
     int64_t last_n;         // n of the most recent lookup
     hipStream_t own_side;
-    hipEvent_t ev_probe, ev_miss;
+    hipEvent_t ev_listed, ev_miss;
+    bool fetch_pending;     // ev_miss marks a miss fetch nobody has waited for yet
     // profiling
     bool profiling;
     std::vector<hipEvent_t> prof_ev;  // pairs
@@ -152,18 +155,21 @@ __global__ __launch_bounds__(1024) void k_scan_miss(int32_t *mbs, int64_t n, Cac
     }
 }
 
-// Ordered list of miss positions.
-__global__ __launch_bounds__(KEYS_PER_TILE) void k_miss_list(const int32_t *__restrict__ out_slot,
-                                                             int64_t n,
-                                                             const int32_t *__restrict__ mpre,
-                                                             int32_t *miss_pos)
+// Ordered lists of the miss positions and of the hit positions.  A hit's rank
+// is its position minus the number of misses before it.
+__global__ __launch_bounds__(KEYS_PER_TILE) void k_split_list(const int32_t *__restrict__ out_slot,
+                                                              int64_t n,
+                                                              const int32_t *__restrict__ mpre,
+                                                              int32_t *miss_pos, int32_t *hit_pos)
 {
     __shared__ int sh_scan[KEYS_PER_TILE / kWave];
     const int64_t i = (int64_t)blockIdx.x * KEYS_PER_TILE + threadIdx.x;
     const int flag = (i < n && out_slot[i] < 0) ? 1 : 0;
     int tot;
     const int ex = block_excl_scan<KEYS_PER_TILE>(flag, sh_scan, tot);
-    if (flag) miss_pos[mpre[blockIdx.x] + ex] = (int32_t)i;
+    const int mrank = mpre[blockIdx.x] + ex;
+    if (flag) miss_pos[mrank] = (int32_t)i;
+    else if (i < n) hit_pos[i - mrank] = (int32_t)i;
 }
 
 // Row copies move 16-byte chunks; a row has Q = row_bytes / 16 of them.  Chunk
@@ -180,68 +186,81 @@ struct RowSplit {
 
 constexpr int COPY_THREADS = 256;
 constexpr int COPY_UNROLL = 4;
+// Workgroups of the miss fetch.  48 x 256 lanes x 4 chunks = 768 KiB of loads in
+// flight saturate the host link; much more than that queues host reads in front
+// of the concurrent hit gather's HBM reads and slows it by an order of magnitude.
+constexpr int FETCH_BLOCKS = 48;
 
-// out[i] = buffer[out_slot[i]] for the hits.  Consecutive lanes take consecutive
-// 16-byte chunks of the output, so stores are fully coalesced and the loads of
-// one row are contiguous; four independent chunks per lane keep loads in flight.
+// out[i] = buffer[out_slot[i]] for every hit i (taken from the hit list, so the
+// work is proportional to the hits).  Consecutive lanes take consecutive
+// 16-byte chunks of a row, so the loads and stores of one row are contiguous;
+// four independent chunks per lane keep loads in flight.  The grid is sized for
+// n rows; workgroups beyond the hit count leave at once.
 template <int Q>
 __global__ __launch_bounds__(COPY_THREADS) void k_gather_hits(
-    const int32_t *__restrict__ out_slot, int64_t n, int q, const uint4 *__restrict__ buffer,
-    uint4 *__restrict__ out)
+    const int32_t *__restrict__ hit_pos, const int32_t *__restrict__ out_slot, int q,
+    const uint4 *__restrict__ buffer, uint4 *__restrict__ out, const CacheDev *dev)
 {
-    const int64_t total = n * (Q > 0 ? Q : q);
+    const int qq = Q > 0 ? Q : q;
+    const int64_t total = (int64_t)dev->n_hit_last * qq;
     const int64_t base = (int64_t)blockIdx.x * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
+    if (base - threadIdx.x >= total) return;
     uint4 v[COPY_UNROLL];
-    bool ok[COPY_UNROLL];
+    int64_t dst[COPY_UNROLL];
 #pragma unroll
     for (int k = 0; k < COPY_UNROLL; ++k) {
         const int64_t idx = base + k * COPY_THREADS;
-        ok[k] = false;
+        dst[k] = -1;
         if (idx < total) {
-            int64_t row; int c;
-            RowSplit<Q>::split(idx, q, row, c);
-            const int slot = out_slot[row];
-            if (slot >= 0) {
-                ok[k] = true;
-                v[k] = buffer[(int64_t)slot * (Q > 0 ? Q : q) + c];
-            }
+            int64_t r; int c;
+            RowSplit<Q>::split(idx, q, r, c);
+            const int32_t row = hit_pos[r];
+            v[k] = buffer[(int64_t)out_slot[row] * qq + c];
+            dst[k] = (int64_t)row * qq + c;
         }
     }
 #pragma unroll
     for (int k = 0; k < COPY_UNROLL; ++k)
-        if (ok[k]) out[base + k * COPY_THREADS] = v[k];
+        if (dst[k] >= 0) out[dst[k]] = v[k];
 }
 
-// out[i] = features[ids[i]] for the misses; the loads cross the host link when
-// the backing store is page-locked host memory.
+// out[miss_pos[r]] = features[ids[miss_pos[r]]] for every miss r; the loads cross
+// the host link when the backing store is page-locked host memory.  The link
+// needs little data in flight compared with HBM, and waves blocked on it would
+// otherwise hold the wave slots the concurrent hit gather needs, so this kernel
+// runs as a small fixed grid that strides over the miss list.
 template <int Q>
 __global__ __launch_bounds__(COPY_THREADS) void k_fetch_miss(
-    const int32_t *__restrict__ out_slot, const int32_t *__restrict__ ids, int64_t n, int q,
-    int64_t num_nodes, const uint4 *__restrict__ features, uint4 *__restrict__ out)
+    const int32_t *__restrict__ miss_pos, const int32_t *__restrict__ ids, int q,
+    int64_t num_nodes, const uint4 *__restrict__ features, uint4 *__restrict__ out,
+    const CacheDev *dev)
 {
-    const int64_t total = n * (Q > 0 ? Q : q);
-    const int64_t base = (int64_t)blockIdx.x * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
-    uint4 v[COPY_UNROLL];
-    bool ok[COPY_UNROLL];
+    const int qq = Q > 0 ? Q : q;
+    const int64_t total = (int64_t)dev->n_miss_last * qq;
+    const int64_t step = (int64_t)gridDim.x * (COPY_THREADS * COPY_UNROLL);
+    for (int64_t base = (int64_t)blockIdx.x * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
+         base - threadIdx.x < total; base += step) {
+        uint4 v[COPY_UNROLL];
+        int64_t dst[COPY_UNROLL];
 #pragma unroll
-    for (int k = 0; k < COPY_UNROLL; ++k) {
-        const int64_t idx = base + k * COPY_THREADS;
-        ok[k] = false;
-        if (idx < total) {
-            int64_t row; int c;
-            RowSplit<Q>::split(idx, q, row, c);
-            if (out_slot[row] < 0) {
+        for (int k = 0; k < COPY_UNROLL; ++k) {
+            const int64_t idx = base + k * COPY_THREADS;
+            dst[k] = -1;
+            if (idx < total) {
+                int64_t r; int c;
+                RowSplit<Q>::split(idx, q, r, c);
+                const int32_t row = miss_pos[r];
                 const int32_t id = ids[row];
                 if (id >= 0 && (int64_t)id < num_nodes) {
-                    ok[k] = true;
-                    v[k] = features[(int64_t)id * (Q > 0 ? Q : q) + c];
+                    v[k] = features[(int64_t)id * qq + c];
+                    dst[k] = (int64_t)row * qq + c;
                 }
             }
         }
-    }
 #pragma unroll
-    for (int k = 0; k < COPY_UNROLL; ++k)
-        if (ok[k]) out[base + k * COPY_THREADS] = v[k];
+        for (int k = 0; k < COPY_UNROLL; ++k)
+            if (dst[k] >= 0) out[dst[k]] = v[k];
+    }
 }
 
 __device__ __forceinline__ void insert_range(const CacheDev *dev, int64_t n_miss_arg,
@@ -447,9 +466,12 @@ extern "C" int bgl_cache_create(int64_t capacity_rows, int32_t row_bytes,
     c->num_nodes = num_nodes;
     c->features = feat_dev;
     c->profiling = false;
+    c->fetch_pending = false;
     for (int s = 0; s < BGL_NUM_STAGES; ++s) { c->prof_ms[s] = 0; c->prof_n[s] = 0; }
     c->mbs = nullptr;
     c->mbs_cap = 0;
+    c->hit_pos = nullptr;
+    c->hit_cap = 0;
     c->last_n = 0;
     // load <= 1/2 of the 15 usable words per bucket
     uint64_t nbk = 1;
@@ -471,7 +493,7 @@ extern "C" int bgl_cache_create(int64_t capacity_rows, int32_t row_bytes,
     TRY_ALLOC(c->dev, sizeof(CacheDev));
 #undef TRY_ALLOC
     if (hipStreamCreateWithFlags(&c->own_side, hipStreamNonBlocking) != hipSuccess ||
-        hipEventCreateWithFlags(&c->ev_probe, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_listed, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&c->ev_miss, hipEventDisableTiming) != hipSuccess) {
         bgl::set_error("stream/event creation failed");
         return fail(BGL_EHIP);
@@ -494,7 +516,7 @@ extern "C" int bgl_cache_destroy(bgl_cache_t *c)
     if (!c) return BGL_OK;
     (void)hipDeviceSynchronize();
     for (auto ev : c->prof_ev) (void)hipEventDestroy(ev);
-    if (c->ev_probe) (void)hipEventDestroy(c->ev_probe);
+    if (c->ev_listed) (void)hipEventDestroy(c->ev_listed);
     if (c->ev_miss) (void)hipEventDestroy(c->ev_miss);
     if (c->own_side) (void)hipStreamDestroy(c->own_side);
     (void)hipFree(c->buffer);
@@ -503,6 +525,7 @@ extern "C" int bgl_cache_destroy(bgl_cache_t *c)
     (void)hipFree(c->slot_to_entry);
     (void)hipFree(c->dev);
     (void)hipFree(c->mbs);
+    (void)hipFree(c->hit_pos);
     delete c;
     return BGL_OK;
 }
@@ -528,34 +551,34 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
         BGL_HIP(hipMalloc((void **)&c->mbs, sizeof(int32_t) * (size_t)cap));
         c->mbs_cap = cap;
     }
+    if (n > c->hit_cap) {
+        BGL_HIP(hipStreamSynchronize(ms));
+        (void)hipFree(c->hit_pos);
+        c->hit_pos = nullptr;
+        c->hit_cap = 0;
+        const int64_t cap = std::max<int64_t>(n + n / 2, 4096);
+        BGL_HIP(hipMalloc((void **)&c->hit_pos, sizeof(int32_t) * (size_t)cap));
+        c->hit_cap = cap;
+    }
     c->last_n = n;
     const int q = c->row_bytes / 16;
+    const bool two_streams = ss != ms;
+    if (c->fetch_pending) {
+        // the previous call's fetch still reads that call's lists
+        BGL_HIP(hipStreamWaitEvent(ms, c->ev_miss, 0));
+        c->fetch_pending = false;
+    }
     if (n > 0) {
         {
             Prof p(c, BGL_STAGE_PROBE, ms);
             hipLaunchKernelGGL(k_probe, dim3((unsigned)tiles), dim3(256), 0, ms, ids, n, c->num_nodes,
                                c->table, c->num_buckets - 1, out_slot, c->mbs, c->dev);
         }
-        const bool two_streams = ss != ms;
-        if (two_streams) {
-            BGL_HIP(hipEventRecord(c->ev_probe, ms));
-            BGL_HIP(hipStreamWaitEvent(ss, c->ev_probe, 0));
-        }
-        {
-            Prof p(c, BGL_STAGE_FETCH_MISS, ss);
-            dispatch_q(q, [&](auto Q) {
-                hipLaunchKernelGGL((k_fetch_miss<decltype(Q)::value>), dim3(copy_blocks(n, q)),
-                                   dim3(COPY_THREADS), 0, ss, out_slot, ids, n, q, c->num_nodes,
-                                   reinterpret_cast<const uint4 *>(c->features),
-                                   reinterpret_cast<uint4 *>(out_rows));
-            });
-        }
-        if (two_streams) BGL_HIP(hipEventRecord(c->ev_miss, ss));
         {
             Prof p(c, BGL_STAGE_MISS_LIST, ms);
             hipLaunchKernelGGL(k_scan_miss, dim3(1), dim3(1024), 0, ms, c->mbs, n, c->dev);
-            hipLaunchKernelGGL(k_miss_list, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), 0, ms, out_slot,
-                               n, c->mbs, miss_pos);
+            hipLaunchKernelGGL(k_split_list, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), 0, ms, out_slot,
+                               n, c->mbs, miss_pos, c->hit_pos);
         }
         if (n_hit_host)
             BGL_HIP(hipMemcpyAsync(n_hit_host, &c->dev->n_hit_last, sizeof(int64_t),
@@ -564,12 +587,33 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
             Prof p(c, BGL_STAGE_GATHER_HIT, ms);
             dispatch_q(q, [&](auto Q) {
                 hipLaunchKernelGGL((k_gather_hits<decltype(Q)::value>), dim3(copy_blocks(n, q)),
-                                   dim3(COPY_THREADS), 0, ms, out_slot, n, q,
+                                   dim3(COPY_THREADS), 0, ms, c->hit_pos, out_slot, q,
                                    reinterpret_cast<const uint4 *>(c->buffer),
-                                   reinterpret_cast<uint4 *>(out_rows));
+                                   reinterpret_cast<uint4 *>(out_rows), c->dev);
             });
         }
-        if (two_streams) BGL_HIP(hipStreamWaitEvent(ms, c->ev_miss, 0));
+        // The miss fetch starts once the hit gather is done: host-link reads
+        // queued in the memory pipeline would otherwise stall the gather's HBM
+        // reads, and the fetch (milliseconds) loses nothing by starting a few
+        // tens of microseconds later.
+        if (two_streams) {
+            BGL_HIP(hipEventRecord(c->ev_listed, ms));
+            BGL_HIP(hipStreamWaitEvent(ss, c->ev_listed, 0));
+        }
+        {
+            Prof p(c, BGL_STAGE_FETCH_MISS, ss);
+            const int blocks = (int)std::min<int64_t>(copy_blocks(n, q), FETCH_BLOCKS);
+            dispatch_q(q, [&](auto Q) {
+                hipLaunchKernelGGL((k_fetch_miss<decltype(Q)::value>), dim3(blocks),
+                                   dim3(COPY_THREADS), 0, ss, miss_pos, ids, q, c->num_nodes,
+                                   reinterpret_cast<const uint4 *>(c->features),
+                                   reinterpret_cast<uint4 *>(out_rows), c->dev);
+            });
+        }
+        if (two_streams) {
+            BGL_HIP(hipEventRecord(c->ev_miss, ss));
+            c->fetch_pending = true;
+        }
     } else {
         hipLaunchKernelGGL(k_scan_miss, dim3(1), dim3(1024), 0, ms, c->mbs, (int64_t)0, c->dev);
         if (n_hit_host)
@@ -592,6 +636,7 @@ extern "C" int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const i
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int q = c->row_bytes / 16;
     const int64_t eff = std::min<int64_t>(bound, c->capacity);
+    if (c->fetch_pending) BGL_HIP(hipStreamWaitEvent(st, c->ev_miss, 0));  // rows of the misses
     if (eff > 0) {
         {
             Prof p(c, BGL_STAGE_INSERT_MAP, st);
@@ -611,6 +656,13 @@ extern "C" int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const i
     }
     hipLaunchKernelGGL(k_advance_tail, dim3(1), dim3(64), 0, st, c->dev, n_miss);
     BGL_HIP(hipGetLastError());
+    return BGL_OK;
+}
+
+extern "C" int bgl_cache_wait_rows(bgl_cache_t *c, void *stream)
+{
+    if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
+    if (c->fetch_pending) BGL_HIP(hipStreamWaitEvent(static_cast<hipStream_t>(stream), c->ev_miss, 0));
     return BGL_OK;
 }
 
