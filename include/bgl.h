@@ -238,6 +238,9 @@ int bgl_cache_stats(bgl_cache_t *c, uint64_t *lookups, uint64_t *hits, uint64_t 
 #define BGL_STAGE_INSERT_MAP 4  /* evict + enter ids in the map */
 #define BGL_STAGE_INSERT_ROWS 5 /* out_rows -> cache buffer */
 #define BGL_NUM_STAGES 6
+/* pseudo stage: what an event pair reads around a kernel that does nothing
+ * (measured when profiling is enabled); total_ms is that single figure */
+#define BGL_STAGE_EVENT_OVERHEAD 100
 int bgl_cache_set_profiling(bgl_cache_t *c, int enable);
 int bgl_cache_profile(bgl_cache_t *c, int stage, double *total_ms, int64_t *launches);
 

@@ -290,4 +290,7 @@ class Cache:
             ms, n = C.c_double(0), C.c_int64(0)
             _check(lib().bgl_cache_profile(self._h, s, C.byref(ms), C.byref(n)))
             out[name] = (ms.value, n.value)
+        ms, n = C.c_double(0), C.c_int64(0)
+        _check(lib().bgl_cache_profile(self._h, 100, C.byref(ms), C.byref(n)))
+        out["event_overhead"] = (ms.value, 1)
         return out

@@ -52,7 +52,7 @@ struct bgl_cache {
     CacheDev *dev;
     int32_t *mbs;           // per-tile miss counts, then their exclusive prefix
     int64_t mbs_cap;
-    int32_t *hit_pos;       // positions of the hits of the most recent lookup
+    int32_t *hit_pos;       // hits of the most recent lookup: hit_cap positions, then hit_cap slots
     int64_t hit_cap;
     int64_t last_n;         // n of the most recent lookup
     hipStream_t own_side;
@@ -63,6 +63,7 @@ struct bgl_cache {
     std::vector<hipEvent_t> prof_ev;  // pairs
     struct Rec { int stage; int ev; };
     std::vector<Rec> prof_rec;
+    double prof_overhead_ms;  // event pair around an (almost) empty kernel
     double prof_ms[BGL_NUM_STAGES];
     int64_t prof_n[BGL_NUM_STAGES];
 };
@@ -155,21 +156,27 @@ __global__ __launch_bounds__(1024) void k_scan_miss(int32_t *mbs, int64_t n, Cac
     }
 }
 
-// Ordered lists of the miss positions and of the hit positions.  A hit's rank
-// is its position minus the number of misses before it.
+// Ordered lists of the miss positions and of the hits (position and slot side by
+// side, so the gather needs no dependent lookup).  A hit's rank is its position
+// minus the number of misses before it.
 __global__ __launch_bounds__(KEYS_PER_TILE) void k_split_list(const int32_t *__restrict__ out_slot,
                                                               int64_t n,
                                                               const int32_t *__restrict__ mpre,
-                                                              int32_t *miss_pos, int32_t *hit_pos)
+                                                              int32_t *miss_pos, int32_t *hit_pos,
+                                                              int32_t *hit_slot)
 {
     __shared__ int sh_scan[KEYS_PER_TILE / kWave];
     const int64_t i = (int64_t)blockIdx.x * KEYS_PER_TILE + threadIdx.x;
-    const int flag = (i < n && out_slot[i] < 0) ? 1 : 0;
+    const int slot = i < n ? out_slot[i] : 0;
+    const int flag = (i < n && slot < 0) ? 1 : 0;
     int tot;
     const int ex = block_excl_scan<KEYS_PER_TILE>(flag, sh_scan, tot);
     const int mrank = mpre[blockIdx.x] + ex;
     if (flag) miss_pos[mrank] = (int32_t)i;
-    else if (i < n) hit_pos[i - mrank] = (int32_t)i;
+    else if (i < n) {
+        hit_pos[i - mrank] = (int32_t)i;
+        hit_slot[i - mrank] = slot;
+    }
 }
 
 // Row copies move 16-byte chunks; a row has Q = row_bytes / 16 of them.  Chunk
@@ -186,10 +193,10 @@ struct RowSplit {
 
 constexpr int COPY_THREADS = 256;
 constexpr int COPY_UNROLL = 4;
-// Workgroups of the miss fetch.  48 x 256 lanes x 4 chunks = 768 KiB of loads in
+// Workgroups of the miss fetch.  64 x 256 lanes x 4 chunks = 1 MiB of loads in
 // flight saturate the host link; much more than that queues host reads in front
 // of the concurrent hit gather's HBM reads and slows it by an order of magnitude.
-constexpr int FETCH_BLOCKS = 48;
+constexpr int FETCH_BLOCKS = 64;
 
 // out[i] = buffer[out_slot[i]] for every hit i (taken from the hit list, so the
 // work is proportional to the hits).  Consecutive lanes take consecutive
@@ -198,7 +205,7 @@ constexpr int FETCH_BLOCKS = 48;
 // n rows; workgroups beyond the hit count leave at once.
 template <int Q>
 __global__ __launch_bounds__(COPY_THREADS) void k_gather_hits(
-    const int32_t *__restrict__ hit_pos, const int32_t *__restrict__ out_slot, int q,
+    const int32_t *__restrict__ hit_pos, const int32_t *__restrict__ hit_slot, int q,
     const uint4 *__restrict__ buffer, uint4 *__restrict__ out, const CacheDev *dev)
 {
     const int qq = Q > 0 ? Q : q;
@@ -214,9 +221,8 @@ __global__ __launch_bounds__(COPY_THREADS) void k_gather_hits(
         if (idx < total) {
             int64_t r; int c;
             RowSplit<Q>::split(idx, q, r, c);
-            const int32_t row = hit_pos[r];
-            v[k] = buffer[(int64_t)out_slot[row] * qq + c];
-            dst[k] = (int64_t)row * qq + c;
+            v[k] = buffer[(int64_t)hit_slot[r] * qq + c];
+            dst[k] = (int64_t)hit_pos[r] * qq + c;
         }
     }
 #pragma unroll
@@ -557,7 +563,7 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
         c->hit_pos = nullptr;
         c->hit_cap = 0;
         const int64_t cap = std::max<int64_t>(n + n / 2, 4096);
-        BGL_HIP(hipMalloc((void **)&c->hit_pos, sizeof(int32_t) * (size_t)cap));
+        BGL_HIP(hipMalloc((void **)&c->hit_pos, 2 * sizeof(int32_t) * (size_t)cap));  // positions, then slots
         c->hit_cap = cap;
     }
     c->last_n = n;
@@ -578,7 +584,7 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
             Prof p(c, BGL_STAGE_MISS_LIST, ms);
             hipLaunchKernelGGL(k_scan_miss, dim3(1), dim3(1024), 0, ms, c->mbs, n, c->dev);
             hipLaunchKernelGGL(k_split_list, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), 0, ms, out_slot,
-                               n, c->mbs, miss_pos, c->hit_pos);
+                               n, c->mbs, miss_pos, c->hit_pos, c->hit_pos + c->hit_cap);
         }
         if (n_hit_host)
             BGL_HIP(hipMemcpyAsync(n_hit_host, &c->dev->n_hit_last, sizeof(int64_t),
@@ -587,7 +593,7 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
             Prof p(c, BGL_STAGE_GATHER_HIT, ms);
             dispatch_q(q, [&](auto Q) {
                 hipLaunchKernelGGL((k_gather_hits<decltype(Q)::value>), dim3(copy_blocks(n, q)),
-                                   dim3(COPY_THREADS), 0, ms, c->hit_pos, out_slot, q,
+                                   dim3(COPY_THREADS), 0, ms, c->hit_pos, c->hit_pos + c->hit_cap, q,
                                    reinterpret_cast<const uint4 *>(c->buffer),
                                    reinterpret_cast<uint4 *>(out_rows), c->dev);
             });
@@ -712,12 +718,33 @@ extern "C" int bgl_cache_set_profiling(bgl_cache_t *c, int enable)
     c->prof_rec.reserve(PROF_RING);
     for (int s = 0; s < BGL_NUM_STAGES; ++s) { c->prof_ms[s] = 0; c->prof_n[s] = 0; }
     c->profiling = enable != 0;
+    if (enable) {
+        // What an event pair reads for a kernel that does nothing (tail += 0):
+        // the launch gap that every bracketed stage time includes.
+        double sum = 0;
+        const int reps = 16;
+        for (int r = 0; r < reps + 2; ++r) {
+            BGL_HIP(hipEventRecord(c->prof_ev[0], 0));
+            hipLaunchKernelGGL(k_advance_tail, dim3(1), dim3(64), 0, 0, c->dev, (int64_t)0);
+            BGL_HIP(hipEventRecord(c->prof_ev[1], 0));
+            BGL_HIP(hipEventSynchronize(c->prof_ev[1]));
+            float ms = 0.f;
+            BGL_HIP(hipEventElapsedTime(&ms, c->prof_ev[0], c->prof_ev[1]));
+            if (r >= 2) sum += ms;
+        }
+        c->prof_overhead_ms = sum / reps;
+    }
     return BGL_OK;
 }
 
 extern "C" int bgl_cache_profile(bgl_cache_t *c, int stage, double *total_ms, int64_t *launches)
 {
     if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
+    if (stage == BGL_STAGE_EVENT_OVERHEAD) {
+        if (total_ms) *total_ms = c->prof_overhead_ms;
+        if (launches) *launches = 1;
+        return BGL_OK;
+    }
     if (stage < 0 || stage >= BGL_NUM_STAGES) BGL_FAIL(BGL_EINVAL, "unknown stage %d", stage);
     BGL_HIP(hipDeviceSynchronize());
     drain_profile(c);
