@@ -81,7 +81,7 @@ def main():
     cfg = inputs.CONFIGS[args.config]
     torch.cuda.set_device(0)
     w = inputs.make_workload(cfg, pinned=True)
-    feat_t = next(t for t in w.keepalive if t is not None and t.data_ptr() == w.features.ctypes.data)
+    feat_t = w.features.ctypes.data      # address of the page-locked feature table
     placement = B.BGL_HOST_PINNED if cfg.graph_placement == "host_pinned" else B.BGL_DEVICE
     graph = B.Graph(w.row_ptr, w.col, placement)
     sampler = B.Sampler(graph, cfg.batch, cfg.fanouts)

@@ -223,7 +223,11 @@ class Cache:
     def __init__(self, capacity_rows: int, features, num_nodes: Optional[int] = None,
                  row_bytes: Optional[int] = None):
         _require_gpu()
-        if isinstance(features, torch.Tensor):
+        if isinstance(features, int):  # raw address of page-locked or device memory
+            if num_nodes is None or row_bytes is None:
+                raise ValueError("num_nodes and row_bytes are required with a raw address")
+            nn, rb, ptr = num_nodes, row_bytes, features
+        elif isinstance(features, torch.Tensor):
             nn = features.shape[0]
             rb = features.stride(0) * features.element_size()
             ptr = features.data_ptr()

@@ -117,17 +117,46 @@ def scaled(cfg: Config, num_nodes: int, num_batches: Optional[int] = None) -> Co
         num_batches=num_batches or cfg.num_batches)
 
 
+class PinnedBuffer:
+    """Page-locked host memory of exactly the requested size (hipHostMalloc through
+    ctypes; a framework allocator may round large requests up to a power of two,
+    which the 50+ GB feature table cannot afford)."""
+
+    _hip = None
+
+    def __init__(self, nbytes: int):
+        if PinnedBuffer._hip is None:
+            PinnedBuffer._hip = C.CDLL("libamdhip64.so")
+            PinnedBuffer._hip.hipHostMalloc.argtypes = [C.POINTER(C.c_void_p), C.c_size_t, C.c_uint]
+            PinnedBuffer._hip.hipHostFree.argtypes = [C.c_void_p]
+        p = C.c_void_p()
+        rc = PinnedBuffer._hip.hipHostMalloc(C.byref(p), max(int(nbytes), 1), 0)
+        if rc != 0 or not p.value:
+            raise MemoryError(f"hipHostMalloc of {nbytes} bytes failed with status {rc}")
+        self.ptr, self.nbytes = p.value, int(nbytes)
+
+    def data_ptr(self) -> int:
+        return self.ptr
+
+    def array(self, shape, dtype) -> np.ndarray:
+        buf = (C.c_uint8 * max(self.nbytes, 1)).from_address(self.ptr)
+        return np.frombuffer(buf, dtype=dtype, count=int(np.prod(shape))).reshape(shape)
+
+    def __del__(self):
+        if getattr(self, "ptr", None) and PinnedBuffer._hip is not None:
+            PinnedBuffer._hip.hipHostFree(self.ptr)
+            self.ptr = None
+
+
 def _alloc(shape, dtype, pinned: bool):
-    """numpy array, optionally backed by page-locked memory (needs a GPU runtime)."""
+    """numpy array, optionally backed by page-locked memory (needs a GPU runtime).
+    Returns (array, owner); keep `owner` alive as long as the array is in use."""
     if pinned:
         import torch
         if torch.cuda.is_available():
-            tdt = {np.dtype(np.int32): torch.int32, np.dtype(np.int64): torch.int64,
-                   np.dtype(np.float32): torch.float32, np.dtype(np.uint16): torch.uint16,
-                   np.dtype(np.uint8): torch.uint8}[np.dtype(dtype)]
-            t = torch.empty(shape, dtype=tdt, pin_memory=True)
-            a = t.numpy()
-            return a, t
+            n = int(np.prod(shape)) * np.dtype(dtype).itemsize
+            buf = PinnedBuffer(n)
+            return buf.array(shape, dtype), buf
     return np.empty(shape, dtype=dtype), None
 
 

@@ -25,7 +25,7 @@ class GpuPipeline:
                 self.feat_t = t
         if self.feat_t is None:  # not generated into pinned memory: make a pinned copy
             self.feat_t = torch.from_numpy(feats.view(np.uint8).reshape(feats.shape[0], -1)).pin_memory()
-        self.cache = B.Cache(cache_rows or cfg.cache_rows, self.feat_t,
+        self.cache = B.Cache(cache_rows or cfg.cache_rows, self.feat_t.data_ptr(),
                              num_nodes=cfg.num_nodes, row_bytes=cfg.row_bytes)
         K = len(cfg.fanouts)
         self.cap = int(min(cfg.num_nodes, cfg.batch * np.prod([1 + f for f in cfg.fanouts])))

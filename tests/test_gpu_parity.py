@@ -311,3 +311,28 @@ def test_pipeline_wide_shape_scaled():
     inputs = _inputs()
     cfg = inputs.scaled(inputs.CONFIGS["wide"], 3_000_000, num_batches=4)
     run_config(cfg, 4, check_every=2)
+
+
+# ------------------------------------------------ full-size large / wide
+SKIP_FULL = os.environ.get("BGL_SKIP_FULL_SIZE", "") not in ("", "0")
+
+
+def run_full(cfg, n_batches, check_every):
+    try:
+        return run_config(cfg, n_batches, device_n_miss=True, check_every=check_every)
+    except MemoryError as e:  # the box cannot page-lock this much host memory
+        pytest.skip(f"not enough page-locked host memory for {cfg.name}: {e}")
+
+
+@pytest.mark.skipif(SKIP_FULL, reason="BGL_SKIP_FULL_SIZE is set")
+def test_pipeline_wide_config_full_size():
+    """30 M nodes, ~600 M edges, bf16 x 512 rows, 4,096 seeds, fanout 25/10, 4.5 M-row cache
+    (~33 GB of page-locked host memory, ~20 s)."""
+    run_full(_inputs().CONFIGS["wide"], 4, 2)
+
+
+@pytest.mark.skipif(SKIP_FULL, reason="BGL_SKIP_FULL_SIZE is set")
+def test_pipeline_large_config_full_size():
+    """111 M nodes, ~1.6 B edges (int64 offsets, CSR read in place from page-locked host
+    memory), fp32 x 128 rows, 25 M-row cache (~64 GB of page-locked host memory, ~30 s)."""
+    run_full(_inputs().CONFIGS["large"], 3, 1)
