@@ -235,9 +235,8 @@ int bgl_cache_stats(bgl_cache_t *c, uint64_t *lookups, uint64_t *hits, uint64_t 
 #define BGL_STAGE_MISS_LIST 1   /* ordered list of miss positions + counters */
 #define BGL_STAGE_GATHER_HIT 2  /* cache buffer -> out_rows */
 #define BGL_STAGE_FETCH_MISS 3  /* backing store -> out_rows */
-#define BGL_STAGE_INSERT_MAP 4  /* evict + enter ids in the map */
-#define BGL_STAGE_INSERT_ROWS 5 /* out_rows -> cache buffer */
-#define BGL_NUM_STAGES 6
+#define BGL_STAGE_INSERT 4      /* evict + enter ids in the map, out_rows -> cache buffer */
+#define BGL_NUM_STAGES 5
 /* pseudo stage: what an event pair reads around a kernel that does nothing
  * (measured when profiling is enabled); total_ms is that single figure */
 #define BGL_STAGE_EVENT_OVERHEAD 100

@@ -7,9 +7,13 @@
 // Cache map: open addressing over 128-byte buckets.  A bucket is 16 64-bit
 // words = exactly one cache line: words 0..14 hold (node id << 32 | slot) or
 // EMPTY, word 15 is a sticky overflow mark that is set when an insertion had to
-// walk past the full bucket.  A group of 16 lanes reads a bucket with one
-// coalesced request and finds the id with a wavefront ballot; a lookup ends at
-// the first bucket without the overflow mark.  Because the mark is only needed
+// walk past the full bucket.  A lookup reads its id's bucket (one line) and ends
+// at the first bucket without the overflow mark (one id per lane: a wavefront
+// keeps 64 independent line reads in flight; a 16-lanes-per-id lookup that found
+// the id with a ballot was measured at half the speed, the lookup being latency
+// bound).  An insertion is done by a group of 16 lanes that reads the bucket with
+// one coalesced request, picks a free word with a wavefront ballot and claims it
+// with a CAS.  Because the mark is only needed
 // for full buckets (rare at load <= 1/2), evictions simply blank their word:
 // no tombstones, no rebuilds.  slot_to_entry[slot] remembers the word that maps
 // a slot's occupant, so an eviction needs no search.
@@ -86,55 +90,60 @@ __global__ void k_fill_i32(int32_t *p, int64_t n, int32_t v)
     for (; i < n; i += stride) p[i] = v;
 }
 
-// 16 lanes per id: one bucket (one cache line) per request, ballot for the match.
-__global__ __launch_bounds__(256) void k_probe(const int32_t *__restrict__ ids, int64_t n,
-                                               int64_t num_nodes,
-                                               const uint64_t *__restrict__ table,
-                                               uint32_t bucket_mask, int32_t *out_slot,
-                                               int32_t *mbs, CacheDev *dev)
+// Map lookup, one id per lane.  A lane reads its id's whole bucket (one 128-byte
+// line, eight 16-byte loads issued together) and compares the 15 entries in
+// registers; the chain continues only past a bucket that carries the overflow
+// mark.  A wavefront thus keeps 64 independent line reads in flight, which is
+// what a latency-bound random lookup needs.  The misses of a wavefront are
+// counted with one ballot.
+__global__ __launch_bounds__(KEYS_PER_TILE) void k_probe(const int32_t *__restrict__ ids, int64_t n,
+                                                         int64_t num_nodes,
+                                                         const uint64_t *__restrict__ table,
+                                                         uint32_t bucket_mask, int32_t *out_slot,
+                                                         int32_t *mbs, CacheDev *dev)
 {
-    __shared__ int sh_miss;
-    if (threadIdx.x == 0) sh_miss = 0;
-    __syncthreads();
-    const int l = threadIdx.x & (BUCKET - 1);
-    const int grp = threadIdx.x / BUCKET;                 // 16 groups per workgroup
-    const int gshift = (threadIdx.x & (kWave - 1)) & ~(BUCKET - 1);
-    const int64_t tile0 = (int64_t)blockIdx.x * KEYS_PER_TILE;
-    int my_miss = 0;
-    for (int it = 0; it < KEYS_PER_TILE / 16; ++it) {
-        const int64_t i = tile0 + it * 16 + grp;
-        if (i >= n) break;  // uniform inside the group
-        const int32_t key = ids[i];
-        int slot = -1;
-        if (key < 0 || (int64_t)key >= num_nodes) {
-            if (l == 0) dev->status = BGL_EINVAL;
+    __shared__ int sh_miss[KEYS_PER_TILE / kWave];
+    const int64_t i = (int64_t)blockIdx.x * KEYS_PER_TILE + threadIdx.x;
+    int slot = -1;
+    if (i < n) {
+        const int32_t id = ids[i];
+        if (id < 0 || (int64_t)id >= num_nodes) {
+            dev->status = BGL_EINVAL;
         } else {
-            uint32_t b = hash32((uint32_t)key) & bucket_mask;
+            const uint32_t key = (uint32_t)id;
+            uint32_t b = hash32(key) & bucket_mask;
             for (uint32_t tries = 0; tries <= bucket_mask; ++tries) {
-                const uint64_t e = table[(size_t)b * BUCKET + l];
-                const bool m = l < BUCKET - 1 && (uint32_t)(e >> 32) == (uint32_t)key;
-                const uint32_t mm = (uint32_t)(__ballot(m) >> gshift) & 0xffffu;
-                if (mm) {
-                    slot = (int)(uint32_t)__shfl(e, __ffs(mm) - 1, BUCKET);
-                    break;
+                const ulonglong2 *bp = reinterpret_cast<const ulonglong2 *>(table + (size_t)b * BUCKET);
+                ulonglong2 w[BUCKET / 2];
+#pragma unroll
+                for (int k = 0; k < BUCKET / 2; ++k) w[k] = bp[k];
+                bool found = false;
+#pragma unroll
+                for (int k = 0; k < BUCKET / 2; ++k) {
+                    if ((uint32_t)(w[k].x >> 32) == key) { slot = (int)(uint32_t)w[k].x; found = true; }
+                    if (k < BUCKET / 2 - 1 && (uint32_t)(w[k].y >> 32) == key) {
+                        slot = (int)(uint32_t)w[k].y;
+                        found = true;
+                    }
                 }
-                const uint64_t mark = __shfl(e, BUCKET - 1, BUCKET);
-                if (mark == 0) break;  // nothing was ever pushed past this bucket
+                if (found || w[BUCKET / 2 - 1].y == 0) break;  // mark clear: nothing was pushed past this bucket
                 b = (b + 1) & bucket_mask;
             }
         }
-        if (l == 0) {
-            out_slot[i] = slot;
-            my_miss += slot < 0;
-        }
+        out_slot[i] = slot;
     }
-    if (l == 0 && my_miss) atomicAdd(&sh_miss, my_miss);
+    const uint64_t missed = __ballot(i < n && slot < 0);
+    if ((threadIdx.x & (kWave - 1)) == 0) sh_miss[threadIdx.x / kWave] = __popcll(missed);
     __syncthreads();
-    if (threadIdx.x == 0) mbs[blockIdx.x] = sh_miss;
+    if (threadIdx.x == 0) {
+        int t = 0;
+#pragma unroll
+        for (int k = 0; k < KEYS_PER_TILE / kWave; ++k) t += sh_miss[k];
+        mbs[blockIdx.x] = t;
+    }
 }
 
-// One workgroup: exclusive prefix of the per-tile miss counts (in place) and
-// the call's counters.
+// Counters of an empty lookup (n = 0); with n > 0 k_split_list publishes them.
 __global__ __launch_bounds__(1024) void k_scan_miss(int32_t *mbs, int64_t n, CacheDev *dev)
 {
     __shared__ int sh_scan[1024 / kWave];
@@ -158,24 +167,38 @@ __global__ __launch_bounds__(1024) void k_scan_miss(int32_t *mbs, int64_t n, Cac
 
 // Ordered lists of the miss positions and of the hits (position and slot side by
 // side, so the gather needs no dependent lookup).  A hit's rank is its position
-// minus the number of misses before it.
+// minus the number of misses before it.  Every workgroup sums the miss counts of
+// the tiles before it (a few thousand ints at most); the last one also
+// publishes the call's counters.
 __global__ __launch_bounds__(KEYS_PER_TILE) void k_split_list(const int32_t *__restrict__ out_slot,
                                                               int64_t n,
-                                                              const int32_t *__restrict__ mpre,
+                                                              const int32_t *__restrict__ mbs,
                                                               int32_t *miss_pos, int32_t *hit_pos,
-                                                              int32_t *hit_slot)
+                                                              int32_t *hit_slot, CacheDev *dev)
 {
     __shared__ int sh_scan[KEYS_PER_TILE / kWave];
+    __shared__ int sh_base;
+    int part = 0;
+    for (int t = threadIdx.x; t < (int)blockIdx.x; t += KEYS_PER_TILE) part += mbs[t];
+    int tot;
+    (void)block_excl_scan<KEYS_PER_TILE>(part, sh_scan, tot);
+    if (threadIdx.x == 0) sh_base = tot;
     const int64_t i = (int64_t)blockIdx.x * KEYS_PER_TILE + threadIdx.x;
     const int slot = i < n ? out_slot[i] : 0;
     const int flag = (i < n && slot < 0) ? 1 : 0;
-    int tot;
-    const int ex = block_excl_scan<KEYS_PER_TILE>(flag, sh_scan, tot);
-    const int mrank = mpre[blockIdx.x] + ex;
+    const int ex = block_excl_scan<KEYS_PER_TILE>(flag, sh_scan, tot);  // its barriers publish sh_base
+    const int mrank = sh_base + ex;
     if (flag) miss_pos[mrank] = (int32_t)i;
     else if (i < n) {
         hit_pos[i - mrank] = (int32_t)i;
         hit_slot[i - mrank] = slot;
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+        const long long n_miss = sh_base + tot;
+        dev->n_miss_last = n_miss;
+        dev->n_hit_last = n - n_miss;
+        dev->lookups += (unsigned long long)n;
+        dev->hits += (unsigned long long)(n - n_miss);
     }
 }
 
@@ -269,29 +292,23 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_miss(
     }
 }
 
-__device__ __forceinline__ void insert_range(const CacheDev *dev, int64_t n_miss_arg,
-                                             int64_t capacity, int64_t &n_miss, int64_t &start)
-{
-    n_miss = n_miss_arg >= 0 ? n_miss_arg : dev->n_miss_last;
-    start = n_miss > capacity ? n_miss - capacity : 0;  // earlier ranks would be overwritten
-}
-
 // Map update: 16 lanes per inserted row.  Evict the slot's occupant (blank its
-// word), then claim a free word in the new id's bucket chain with a CAS.
-__global__ __launch_bounds__(256) void k_insert_map(const int32_t *__restrict__ ids,
-                                                    const int32_t *__restrict__ miss_pos,
-                                                    int64_t n_miss_arg, int64_t capacity,
-                                                    int64_t num_nodes, uint64_t *table,
-                                                    uint32_t bucket_mask, int32_t *slot_to_node,
-                                                    uint32_t *slot_to_entry, CacheDev *dev)
+// word, found through slot_to_entry), then read the new id's bucket with one
+// coalesced request, pick a free word with a wavefront ballot and claim it with
+// a CAS.  Bucket words are read with device-scope atomic loads so that the retry
+// after a lost CAS sees the winner's word.  (One row per lane was measured too:
+// no faster, the update is bound by its random lines, not by lane count.)
+__device__ __forceinline__ void insert_map_part(
+    int64_t block, const int32_t *__restrict__ ids, const int32_t *__restrict__ miss_pos,
+    int64_t n_miss, int64_t start, unsigned long long tail, int64_t capacity, int64_t num_nodes,
+    uint64_t *table, uint32_t bucket_mask, int32_t *slot_to_node, uint32_t *slot_to_entry,
+    CacheDev *dev)
 {
-    int64_t n_miss, start;
-    insert_range(dev, n_miss_arg, capacity, n_miss, start);
     const int l = threadIdx.x & (BUCKET - 1);
     const int gshift = (threadIdx.x & (kWave - 1)) & ~(BUCKET - 1);
-    const int64_t r = start + ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / BUCKET;
+    const int64_t r = start + (block * COPY_THREADS + threadIdx.x) / BUCKET;
     if (r >= n_miss) return;  // uniform inside the group
-    const int64_t slot = (int64_t)((dev->tail + (unsigned long long)r) % (unsigned long long)capacity);
+    const int64_t slot = (int64_t)((tail + (unsigned long long)r) % (unsigned long long)capacity);
     const int32_t key = ids[miss_pos[r]];
     const int32_t old = slot_to_node[slot];
     if (old >= 0 && l == 0)
@@ -310,7 +327,7 @@ __global__ __launch_bounds__(256) void k_insert_map(const int32_t *__restrict__ 
     uint32_t b = hash32((uint32_t)key) & bucket_mask;
     uint32_t entry = 0;
     bool done = false;
-    // every failed CAS means another group filled a word: at most 15 retries per
+    // every lost CAS means another group filled a word: at most 15 retries per
     // bucket, and a table at load <= 1/2 always has a bucket with a free word
     for (uint32_t tries = 0; tries < 16u * (bucket_mask + 1u) && !done; ++tries) {
         const uint64_t e = __hip_atomic_load(&table[(size_t)b * BUCKET + l], __ATOMIC_RELAXED,
@@ -350,17 +367,15 @@ __global__ __launch_bounds__(256) void k_insert_map(const int32_t *__restrict__ 
 // buffer[(tail + r) % capacity] = out[miss_pos[r]]: the destination is a
 // contiguous (wrapping) run of slots, so the stores stream.
 template <int Q>
-__global__ __launch_bounds__(COPY_THREADS) void k_insert_rows(
-    const int32_t *__restrict__ miss_pos, int64_t n_miss_arg, int64_t capacity, int q,
-    const uint4 *__restrict__ out, uint4 *__restrict__ buffer, const CacheDev *dev)
+__device__ __forceinline__ void insert_rows_part(
+    int64_t block, const int32_t *__restrict__ miss_pos, int64_t n_miss, int64_t start,
+    unsigned long long tail, int64_t capacity, int q, const uint4 *__restrict__ out,
+    uint4 *__restrict__ buffer)
 {
-    int64_t n_miss, start;
-    insert_range(dev, n_miss_arg, capacity, n_miss, start);
     const int qq = Q > 0 ? Q : q;
     const int64_t total = (n_miss - start) * qq;
-    const int64_t base = (int64_t)blockIdx.x * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
-    if ((int64_t)blockIdx.x * (COPY_THREADS * COPY_UNROLL) >= total) return;
-    const unsigned long long tail = dev->tail;
+    const int64_t base = block * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
+    if (base - threadIdx.x >= total) return;
     uint4 v[COPY_UNROLL];
     int64_t dst[COPY_UNROLL];
 #pragma unroll
@@ -379,6 +394,40 @@ __global__ __launch_bounds__(COPY_THREADS) void k_insert_rows(
 #pragma unroll
     for (int k = 0; k < COPY_UNROLL; ++k)
         if (dst[k] >= 0) buffer[dst[k]] = v[k];
+}
+
+// One launch does the whole FIFO update: the first map_blocks workgroups update
+// the map (random accesses, latency bound), the others copy the rows (streaming,
+// bandwidth bound), so the two overlap.  tail is advanced by k_advance_tail
+// afterwards (every workgroup here reads it).
+template <int Q>
+__global__ __launch_bounds__(COPY_THREADS) void k_insert(
+    const int32_t *__restrict__ ids, const int32_t *__restrict__ miss_pos, int64_t n_miss_arg,
+    int64_t capacity, int64_t num_nodes, uint64_t *table, uint32_t bucket_mask,
+    int32_t *slot_to_node, uint32_t *slot_to_entry, int q, const uint4 *__restrict__ out,
+    uint4 *__restrict__ buffer, CacheDev *dev, int map_blocks)
+{
+    const int64_t n_miss = n_miss_arg >= 0 ? n_miss_arg : dev->n_miss_last;
+    const int64_t start = n_miss > capacity ? n_miss - capacity : 0;  // earlier ranks would be overwritten
+    const unsigned long long tail = dev->tail;
+    // alternate the two roles so that both kinds of workgroup are resident together
+    const int row_blocks = (int)gridDim.x - map_blocks;
+    const int paired = map_blocks < row_blocks ? map_blocks : row_blocks;
+    const int b = (int)blockIdx.x;
+    bool map_role;
+    int idx;
+    if (b < 2 * paired) {
+        map_role = (b & 1) == 0;
+        idx = b >> 1;
+    } else {
+        map_role = map_blocks > row_blocks;
+        idx = b - paired;
+    }
+    if (map_role)
+        insert_map_part(idx, ids, miss_pos, n_miss, start, tail, capacity, num_nodes, table,
+                        bucket_mask, slot_to_node, slot_to_entry, dev);
+    else
+        insert_rows_part<Q>(idx, miss_pos, n_miss, start, tail, capacity, q, out, buffer);
 }
 
 __global__ void k_advance_tail(CacheDev *dev, int64_t n_miss_arg)
@@ -577,14 +626,13 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
     if (n > 0) {
         {
             Prof p(c, BGL_STAGE_PROBE, ms);
-            hipLaunchKernelGGL(k_probe, dim3((unsigned)tiles), dim3(256), 0, ms, ids, n, c->num_nodes,
+            hipLaunchKernelGGL(k_probe, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), 0, ms, ids, n, c->num_nodes,
                                c->table, c->num_buckets - 1, out_slot, c->mbs, c->dev);
         }
         {
             Prof p(c, BGL_STAGE_MISS_LIST, ms);
-            hipLaunchKernelGGL(k_scan_miss, dim3(1), dim3(1024), 0, ms, c->mbs, n, c->dev);
             hipLaunchKernelGGL(k_split_list, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), 0, ms, out_slot,
-                               n, c->mbs, miss_pos, c->hit_pos, c->hit_pos + c->hit_cap);
+                               n, c->mbs, miss_pos, c->hit_pos, c->hit_pos + c->hit_cap, c->dev);
         }
         if (n_hit_host)
             BGL_HIP(hipMemcpyAsync(n_hit_host, &c->dev->n_hit_last, sizeof(int64_t),
@@ -644,21 +692,16 @@ extern "C" int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const i
     const int64_t eff = std::min<int64_t>(bound, c->capacity);
     if (c->fetch_pending) BGL_HIP(hipStreamWaitEvent(st, c->ev_miss, 0));  // rows of the misses
     if (eff > 0) {
-        {
-            Prof p(c, BGL_STAGE_INSERT_MAP, st);
-            hipLaunchKernelGGL(k_insert_map, dim3((unsigned)bgl::ceil_div(eff * BUCKET, 256)), dim3(256),
-                               0, st, ids, miss_pos, n_miss, c->capacity, c->num_nodes, c->table,
-                               c->num_buckets - 1, c->slot_to_node, c->slot_to_entry, c->dev);
-        }
-        {
-            Prof p(c, BGL_STAGE_INSERT_ROWS, st);
-            dispatch_q(q, [&](auto Q) {
-                hipLaunchKernelGGL((k_insert_rows<decltype(Q)::value>), dim3(copy_blocks(eff, q)),
-                                   dim3(COPY_THREADS), 0, st, miss_pos, n_miss, c->capacity, q,
-                                   reinterpret_cast<const uint4 *>(out_rows),
-                                   reinterpret_cast<uint4 *>(c->buffer), c->dev);
-            });
-        }
+        Prof p(c, BGL_STAGE_INSERT, st);
+        const int map_blocks = (int)bgl::ceil_div(eff * BUCKET, COPY_THREADS);
+        const int row_blocks = copy_blocks(eff, q);
+        dispatch_q(q, [&](auto Q) {
+            hipLaunchKernelGGL((k_insert<decltype(Q)::value>), dim3(map_blocks + row_blocks),
+                               dim3(COPY_THREADS), 0, st, ids, miss_pos, n_miss, c->capacity,
+                               c->num_nodes, c->table, c->num_buckets - 1, c->slot_to_node,
+                               c->slot_to_entry, q, reinterpret_cast<const uint4 *>(out_rows),
+                               reinterpret_cast<uint4 *>(c->buffer), c->dev, map_blocks);
+        });
     }
     hipLaunchKernelGGL(k_advance_tail, dim3(1), dim3(64), 0, st, c->dev, n_miss);
     BGL_HIP(hipGetLastError());

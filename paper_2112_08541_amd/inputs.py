@@ -143,8 +143,9 @@ class PinnedBuffer:
         return np.frombuffer(buf, dtype=dtype, count=int(np.prod(shape))).reshape(shape)
 
     def __del__(self):
-        if getattr(self, "ptr", None) and PinnedBuffer._hip is not None:
-            PinnedBuffer._hip.hipHostFree(self.ptr)
+        hip = getattr(type(self), "_hip", None) if type is not None else None
+        if getattr(self, "ptr", None) and hip is not None:
+            hip.hipHostFree(self.ptr)
             self.ptr = None
 
 
