@@ -226,10 +226,12 @@ int bgl_cache_stats(bgl_cache_t *c, uint64_t *lookups, uint64_t *hits, uint64_t 
                     uint64_t *evictions, int32_t *status);
 
 /*
- * Per-kernel timing for measurements.  When enabled, the cache brackets each of
- * its kernels with HIP events on the stream the kernel runs on; bgl_cache_profile
- * synchronises the device and returns the summed milliseconds and the number
- * of launches of one stage since profiling was (re-)enabled.
+ * Per-kernel timing for measurements.  `stage_mask` has bit (1 << stage) set for
+ * every stage whose kernels the cache shall bracket with HIP events on the
+ * stream they run on (0 = off, BGL_ALL_STAGES = all); every event pair costs a
+ * few microseconds of launch gap on that stream.  bgl_cache_profile synchronises
+ * the device and returns the summed milliseconds and the number of launches of
+ * one stage since profiling was (re-)enabled.
  */
 #define BGL_STAGE_PROBE 0       /* map lookup */
 #define BGL_STAGE_MISS_LIST 1   /* ordered list of miss positions + counters */
@@ -240,7 +242,8 @@ int bgl_cache_stats(bgl_cache_t *c, uint64_t *lookups, uint64_t *hits, uint64_t 
 /* pseudo stage: what an event pair reads around a kernel that does nothing
  * (measured when profiling is enabled); total_ms is that single figure */
 #define BGL_STAGE_EVENT_OVERHEAD 100
-int bgl_cache_set_profiling(bgl_cache_t *c, int enable);
+#define BGL_ALL_STAGES ((1 << BGL_NUM_STAGES) - 1)
+int bgl_cache_set_profiling(bgl_cache_t *c, int stage_mask);
 int bgl_cache_profile(bgl_cache_t *c, int stage, double *total_ms, int64_t *launches);
 
 #ifdef __cplusplus

@@ -284,8 +284,15 @@ class Cache:
         return dict(lookups=vals[0].value, hits=vals[1].value, inserts=vals[2].value,
                     evictions=vals[3].value, status=status.value)
 
-    def set_profiling(self, enable: bool) -> None:
-        _check(lib().bgl_cache_set_profiling(self._h, 1 if enable else 0))
+    def set_profiling(self, stages=True) -> None:
+        """stages: False/True (none/all) or an iterable of stage names to bracket with events."""
+        if stages is True:
+            mask = (1 << len(STAGE_NAMES)) - 1
+        elif not stages:
+            mask = 0
+        else:
+            mask = sum(1 << STAGE_NAMES.index(s) for s in stages)
+        _check(lib().bgl_cache_set_profiling(self._h, mask))
 
     def profile(self):
         out = {}

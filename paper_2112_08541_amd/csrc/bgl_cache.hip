@@ -33,8 +33,11 @@ constexpr int KEYS_PER_TILE = 256;  // ids per workgroup in probe / miss-list ke
 constexpr int PROF_RING = 4096;
 
 struct CacheDev {          // device-resident scalars
-    unsigned long long tail;
-    unsigned long long lookups, hits, inserts;
+    // tail is kept twice: FIFO update number k reads tail[k & 1] in every
+    // workgroup while one lane writes tail[(k + 1) & 1], so no launch is needed
+    // just to advance it.  The host counts the updates (bgl_cache::insert_calls).
+    unsigned long long tail[2];
+    unsigned long long lookups, hits;
     long long n_miss_last;  // miss count of the most recent lookup
     long long n_hit_last;   // hit count of the most recent lookup
     int status;
@@ -59,11 +62,12 @@ struct bgl_cache {
     int32_t *hit_pos;       // hits of the most recent lookup: hit_cap positions, then hit_cap slots
     int64_t hit_cap;
     int64_t last_n;         // n of the most recent lookup
+    uint64_t insert_calls;  // FIFO updates enqueued so far (selects the live copy of tail)
     hipStream_t own_side;
     hipEvent_t ev_listed, ev_miss;
     bool fetch_pending;     // ev_miss marks a miss fetch nobody has waited for yet
     // profiling
-    bool profiling;
+    unsigned profiling;     // bit s set: stage s is bracketed with events
     std::vector<hipEvent_t> prof_ev;  // pairs
     struct Rec { int stage; int ev; };
     std::vector<Rec> prof_rec;
@@ -144,7 +148,8 @@ __global__ __launch_bounds__(KEYS_PER_TILE) void k_probe(const int32_t *__restri
 }
 
 // Counters of an empty lookup (n = 0); with n > 0 k_split_list publishes them.
-__global__ __launch_bounds__(1024) void k_scan_miss(int32_t *mbs, int64_t n, CacheDev *dev)
+__global__ __launch_bounds__(1024) void k_scan_miss(int32_t *mbs, int64_t n, CacheDev *dev,
+                                                    int64_t *n_hit_host)
 {
     __shared__ int sh_scan[1024 / kWave];
     const int nb = (int)((n + KEYS_PER_TILE - 1) / KEYS_PER_TILE);
@@ -162,6 +167,7 @@ __global__ __launch_bounds__(1024) void k_scan_miss(int32_t *mbs, int64_t n, Cac
         dev->n_hit_last = n - carry;
         dev->lookups += (unsigned long long)n;
         dev->hits += (unsigned long long)(n - carry);
+        if (n_hit_host) *n_hit_host = n - carry;
     }
 }
 
@@ -174,7 +180,8 @@ __global__ __launch_bounds__(KEYS_PER_TILE) void k_split_list(const int32_t *__r
                                                               int64_t n,
                                                               const int32_t *__restrict__ mbs,
                                                               int32_t *miss_pos, int32_t *hit_pos,
-                                                              int32_t *hit_slot, CacheDev *dev)
+                                                              int32_t *hit_slot, CacheDev *dev,
+                                                              int64_t *n_hit_host)
 {
     __shared__ int sh_scan[KEYS_PER_TILE / kWave];
     __shared__ int sh_base;
@@ -199,6 +206,8 @@ __global__ __launch_bounds__(KEYS_PER_TILE) void k_split_list(const int32_t *__r
         dev->n_hit_last = n - n_miss;
         dev->lookups += (unsigned long long)n;
         dev->hits += (unsigned long long)(n - n_miss);
+        // page-locked host memory: visible to the host once the kernel has completed
+        if (n_hit_host) *n_hit_host = n - n_miss;
     }
 }
 
@@ -398,18 +407,19 @@ __device__ __forceinline__ void insert_rows_part(
 
 // One launch does the whole FIFO update: the first map_blocks workgroups update
 // the map (random accesses, latency bound), the others copy the rows (streaming,
-// bandwidth bound), so the two overlap.  tail is advanced by k_advance_tail
-// afterwards (every workgroup here reads it).
+// bandwidth bound), so the two overlap.  Every workgroup reads tail[par]; one lane
+// stores the advanced value in tail[par ^ 1] for the next update.
 template <int Q>
 __global__ __launch_bounds__(COPY_THREADS) void k_insert(
     const int32_t *__restrict__ ids, const int32_t *__restrict__ miss_pos, int64_t n_miss_arg,
     int64_t capacity, int64_t num_nodes, uint64_t *table, uint32_t bucket_mask,
     int32_t *slot_to_node, uint32_t *slot_to_entry, int q, const uint4 *__restrict__ out,
-    uint4 *__restrict__ buffer, CacheDev *dev, int map_blocks)
+    uint4 *__restrict__ buffer, CacheDev *dev, int map_blocks, int par)
 {
     const int64_t n_miss = n_miss_arg >= 0 ? n_miss_arg : dev->n_miss_last;
     const int64_t start = n_miss > capacity ? n_miss - capacity : 0;  // earlier ranks would be overwritten
-    const unsigned long long tail = dev->tail;
+    const unsigned long long tail = dev->tail[par];
+    if (blockIdx.x == 0 && threadIdx.x == 0) dev->tail[par ^ 1] = tail + (unsigned long long)n_miss;
     // alternate the two roles so that both kinds of workgroup are resident together
     const int row_blocks = (int)gridDim.x - map_blocks;
     const int paired = map_blocks < row_blocks ? map_blocks : row_blocks;
@@ -430,14 +440,16 @@ __global__ __launch_bounds__(COPY_THREADS) void k_insert(
         insert_rows_part<Q>(idx, miss_pos, n_miss, start, tail, capacity, q, out, buffer);
 }
 
-__global__ void k_advance_tail(CacheDev *dev, int64_t n_miss_arg)
+// FIFO update when the launch above is skipped (nothing can be inserted).
+__global__ void k_advance_tail(CacheDev *dev, int64_t n_miss_arg, int par)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
         const long long n = n_miss_arg >= 0 ? n_miss_arg : dev->n_miss_last;
-        dev->tail += (unsigned long long)n;
-        dev->inserts += (unsigned long long)n;
+        dev->tail[par ^ 1] = dev->tail[par] + (unsigned long long)n;
     }
 }
+
+__global__ void k_noop() {}
 
 // ------------------------------------------------------------------ host helpers
 struct Prof {
@@ -446,7 +458,7 @@ struct Prof {
     int ev = -1;
     Prof(bgl_cache *c_, int stage, hipStream_t st_) : c(c_), st(st_)
     {
-        if (!c->profiling || c->prof_rec.size() >= PROF_RING) return;
+        if (!(c->profiling & (1u << stage)) || c->prof_rec.size() >= PROF_RING) return;
         ev = (int)c->prof_rec.size() * 2;
         c->prof_rec.push_back({stage, ev});
         (void)hipEventRecord(c->prof_ev[ev], st);
@@ -520,7 +532,7 @@ extern "C" int bgl_cache_create(int64_t capacity_rows, int32_t row_bytes,
     c->row_bytes = row_bytes;
     c->num_nodes = num_nodes;
     c->features = feat_dev;
-    c->profiling = false;
+    c->profiling = 0;
     c->fetch_pending = false;
     for (int s = 0; s < BGL_NUM_STAGES; ++s) { c->prof_ms[s] = 0; c->prof_n[s] = 0; }
     c->mbs = nullptr;
@@ -528,6 +540,7 @@ extern "C" int bgl_cache_create(int64_t capacity_rows, int32_t row_bytes,
     c->hit_pos = nullptr;
     c->hit_cap = 0;
     c->last_n = 0;
+    c->insert_calls = 0;
     // load <= 1/2 of the 15 usable words per bucket
     uint64_t nbk = 1;
     while (nbk * 15 < (uint64_t)capacity_rows * 2) nbk <<= 1;
@@ -616,6 +629,17 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
         c->hit_cap = cap;
     }
     c->last_n = n;
+    // the hit count goes straight into the caller's page-locked word (no copy launch)
+    int64_t *n_hit_dev = nullptr;
+    if (n_hit_host) {
+        hipPointerAttribute_t attr;
+        if (hipPointerGetAttributes(&attr, n_hit_host) != hipSuccess || attr.type != hipMemoryTypeHost ||
+            !attr.devicePointer) {
+            (void)hipGetLastError();
+            BGL_FAIL(BGL_EINVAL, "n_hit_host must be page-locked host memory");
+        }
+        n_hit_dev = static_cast<int64_t *>(attr.devicePointer);
+    }
     const int q = c->row_bytes / 16;
     const bool two_streams = ss != ms;
     if (c->fetch_pending) {
@@ -632,11 +656,9 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
         {
             Prof p(c, BGL_STAGE_MISS_LIST, ms);
             hipLaunchKernelGGL(k_split_list, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), 0, ms, out_slot,
-                               n, c->mbs, miss_pos, c->hit_pos, c->hit_pos + c->hit_cap, c->dev);
+                               n, c->mbs, miss_pos, c->hit_pos, c->hit_pos + c->hit_cap, c->dev,
+                               n_hit_dev);
         }
-        if (n_hit_host)
-            BGL_HIP(hipMemcpyAsync(n_hit_host, &c->dev->n_hit_last, sizeof(int64_t),
-                                   hipMemcpyDeviceToHost, ms));
         {
             Prof p(c, BGL_STAGE_GATHER_HIT, ms);
             dispatch_q(q, [&](auto Q) {
@@ -669,10 +691,8 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
             c->fetch_pending = true;
         }
     } else {
-        hipLaunchKernelGGL(k_scan_miss, dim3(1), dim3(1024), 0, ms, c->mbs, (int64_t)0, c->dev);
-        if (n_hit_host)
-            BGL_HIP(hipMemcpyAsync(n_hit_host, &c->dev->n_hit_last, sizeof(int64_t),
-                                   hipMemcpyDeviceToHost, ms));
+        hipLaunchKernelGGL(k_scan_miss, dim3(1), dim3(1024), 0, ms, c->mbs, (int64_t)0, c->dev,
+                           n_hit_dev);
     }
     BGL_HIP(hipGetLastError());
     return BGL_OK;
@@ -691,6 +711,7 @@ extern "C" int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const i
     const int q = c->row_bytes / 16;
     const int64_t eff = std::min<int64_t>(bound, c->capacity);
     if (c->fetch_pending) BGL_HIP(hipStreamWaitEvent(st, c->ev_miss, 0));  // rows of the misses
+    const int par = (int)(c->insert_calls & 1);
     if (eff > 0) {
         Prof p(c, BGL_STAGE_INSERT, st);
         const int map_blocks = (int)bgl::ceil_div(eff * BUCKET, COPY_THREADS);
@@ -700,10 +721,12 @@ extern "C" int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const i
                                dim3(COPY_THREADS), 0, st, ids, miss_pos, n_miss, c->capacity,
                                c->num_nodes, c->table, c->num_buckets - 1, c->slot_to_node,
                                c->slot_to_entry, q, reinterpret_cast<const uint4 *>(out_rows),
-                               reinterpret_cast<uint4 *>(c->buffer), c->dev, map_blocks);
+                               reinterpret_cast<uint4 *>(c->buffer), c->dev, map_blocks, par);
         });
+    } else {
+        hipLaunchKernelGGL(k_advance_tail, dim3(1), dim3(64), 0, st, c->dev, n_miss, par);
     }
-    hipLaunchKernelGGL(k_advance_tail, dim3(1), dim3(64), 0, st, c->dev, n_miss);
+    c->insert_calls += 1;
     BGL_HIP(hipGetLastError());
     return BGL_OK;
 }
@@ -726,7 +749,7 @@ extern "C" int bgl_cache_export_state(bgl_cache_t *c, int32_t *slot_to_node, uin
     if (tail) {
         CacheDev h;
         BGL_HIP(hipMemcpy(&h, c->dev, sizeof(h), hipMemcpyDeviceToHost));
-        *tail = h.tail;
+        *tail = h.tail[c->insert_calls & 1];
     }
     if (buffer)
         BGL_HIP(hipMemcpy(buffer, c->buffer, (size_t)c->capacity * c->row_bytes, hipMemcpyDeviceToHost));
@@ -742,9 +765,10 @@ extern "C" int bgl_cache_stats(bgl_cache_t *c, uint64_t *lookups, uint64_t *hits
     BGL_HIP(hipMemcpy(&h, c->dev, sizeof(h), hipMemcpyDeviceToHost));
     if (lookups) *lookups = h.lookups;
     if (hits) *hits = h.hits;
-    if (inserts) *inserts = h.inserts;
+    const uint64_t tail = h.tail[c->insert_calls & 1];
+    if (inserts) *inserts = tail;  // every insertion advances tail by one
     // every insertion beyond the first `capacity` ones overwrote an occupied slot
-    if (evictions) *evictions = h.tail > (uint64_t)c->capacity ? h.tail - (uint64_t)c->capacity : 0;
+    if (evictions) *evictions = tail > (uint64_t)c->capacity ? tail - (uint64_t)c->capacity : 0;
     if (status) *status = h.status;
     return BGL_OK;
 }
@@ -760,15 +784,15 @@ extern "C" int bgl_cache_set_profiling(bgl_cache_t *c, int enable)
     c->prof_rec.clear();
     c->prof_rec.reserve(PROF_RING);
     for (int s = 0; s < BGL_NUM_STAGES; ++s) { c->prof_ms[s] = 0; c->prof_n[s] = 0; }
-    c->profiling = enable != 0;
+    c->profiling = (unsigned)enable;
     if (enable) {
-        // What an event pair reads for a kernel that does nothing (tail += 0):
+        // What an event pair reads for a kernel that does nothing:
         // the launch gap that every bracketed stage time includes.
         double sum = 0;
         const int reps = 16;
         for (int r = 0; r < reps + 2; ++r) {
             BGL_HIP(hipEventRecord(c->prof_ev[0], 0));
-            hipLaunchKernelGGL(k_advance_tail, dim3(1), dim3(64), 0, 0, c->dev, (int64_t)0);
+            hipLaunchKernelGGL(k_noop, dim3(1), dim3(64), 0, 0);
             BGL_HIP(hipEventRecord(c->prof_ev[1], 0));
             BGL_HIP(hipEventSynchronize(c->prof_ev[1]));
             float ms = 0.f;
