@@ -79,6 +79,7 @@ def main():
         return 0
     from paper_2112_08541_amd import binding as B
     from paper_2112_08541_amd import inputs
+    from paper_2112_08541_amd.pipeline import MinibatchPipeline
 
     cfg = inputs.CONFIGS[args.config]
     torch.cuda.set_device(0)
@@ -86,63 +87,26 @@ def main():
     feat_t = w.features.ctypes.data      # address of the page-locked feature table
     placement = B.BGL_HOST_PINNED if cfg.graph_placement == "host_pinned" else B.BGL_DEVICE
     graph = B.Graph(w.row_ptr, w.col, placement)
-    sampler = B.Sampler(graph, cfg.batch, cfg.fanouts)
-    cap = int(min(cfg.num_nodes, cfg.batch * np.prod([1 + f for f in cfg.fanouts])))
-    out_rows = torch.empty((cap, cfg.row_bytes), dtype=torch.uint8, device="cuda")
-    out_slot = torch.empty(cap, dtype=torch.int32, device="cuda")
-    miss_pos = torch.empty(cap, dtype=torch.int32, device="cuda")
     seeds_dev = torch.from_numpy(w.seed_batches).cuda()      # inputs resident in HBM
-    side = torch.cuda.Stream()
-    main_stream = torch.cuda.current_stream()
     nb = cfg.num_batches
-    K = len(cfg.fanouts)
 
-    # Two sampling workspaces: batch i+1 is sampled while batch i's misses cross the host link.
-    samplers = [sampler, B.Sampler(graph, cfg.batch, cfg.fanouts)]
-
-    def run_epoch(cache, steps, record):
-        """`steps` minibatches, software-pipelined two deep.  Per batch i:
-        lookup_gather(i) [main: probe, lists, hit gather; side: miss fetch] ->
-        sample(i+1) on main, overlapping the fetch -> insert_fifo(i) (waits for the
-        fetch) -> the host waits only for sample(i+1)'s sizes.  Cache state advances
-        strictly batch by batch."""
-        n_list, hit_list = [], []
-        sb = samplers[0].sample(seeds_dev[0], int(w.rng_seeds[0]))
-        main_stream.synchronize()
-        n = int(samplers[0].counts_host[K])
-        ev = torch.cuda.Event()
-        for i in range(steps):
-            ids = sb.input_nodes(cap)
-            cache.lookup_gather(ids, n, out_rows, out_slot, miss_pos, side_stream=side)
-            nxt = i + 1
-            if nxt < steps:
-                b = nxt % nb
-                smp = samplers[nxt % 2]
-                sb_next = smp.sample(seeds_dev[b], int(w.rng_seeds[b]) ^ (nxt // nb))
-                ev.record(main_stream)
-            cache.insert_fifo(ids, miss_pos, -1, out_rows)
-            n_list.append(n)
-            if nxt < steps:
-                ev.synchronize()                     # sizes of batch i+1 (and n_hit of batch i) are on the host
-                hit_list.append(int(cache.n_hit_host[0]))
-                n = int(smp.counts_host[K])
-                sb = sb_next
-        torch.cuda.synchronize()
-        hit_list.append(int(cache.n_hit_host[0]))
-        return n_list, hit_list
+    def new_cache():
+        return B.Cache(cfg.cache_rows, feat_t, num_nodes=cfg.num_nodes, row_bytes=cfg.row_bytes)
 
     # warm-up on a scratch cache of the same size, so the timed epoch starts from an empty cache
+    scratch = new_cache()
+    pipe = MinibatchPipeline(graph, scratch, cfg.batch, cfg.fanouts, cfg.row_bytes)
     if args.warmup > 0:
-        scratch = B.Cache(cfg.cache_rows, feat_t, num_nodes=cfg.num_nodes, row_bytes=cfg.row_bytes)
-        run_epoch(scratch, args.warmup, False)
-        scratch.close()
+        pipe.run(seeds_dev, w.rng_seeds, args.warmup)
+    scratch.close()
 
-    cache = B.Cache(cfg.cache_rows, feat_t, num_nodes=cfg.num_nodes, row_bytes=cfg.row_bytes)
+    cache = new_cache()
+    pipe.set_cache(cache)
     if not args.no_stage_timers:
         cache.set_profiling(True if args.all_stage_timers else ("gather_hit", "fetch_miss"))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    n_list, hit_list = run_epoch(cache, args.steps, True)
+    n_list, hit_list = pipe.run(seeds_dev, w.rng_seeds, args.steps)   # ends with a device synchronise
     t1 = time.perf_counter()
     elapsed = t1 - t0
 

@@ -9,7 +9,7 @@ without the HIP library being loaded.
 """
 import importlib
 
-__all__ = ["binding", "inputs", "buildlib"]
+__all__ = ["binding", "inputs", "buildlib", "pipeline"]
 
 
 def __getattr__(name):

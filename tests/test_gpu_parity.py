@@ -289,6 +289,41 @@ def test_pipeline_mid_config_full_size():
     run_config(cfg, 12, device_n_miss=True, check_every=4)
 
 
+def test_overlapped_pipeline_as_benchmarked_matches_oracle(torch_mod, B):
+    """The launch configuration bench.py times (two sampling workspaces, next batch sampled
+    while the misses are fetched on the side stream, device-side miss count) on the
+    full-size mid workload: every batch's outputs and the final cache state."""
+    from paper_2112_08541_amd.pipeline import MinibatchPipeline
+    inputs = _inputs()
+    cfg = inputs.CONFIGS["mid"]
+    w = inputs.make_workload(cfg, pinned=True)
+    graph = B.Graph(w.row_ptr, w.col)
+    cache = B.Cache(cfg.cache_rows, w.features.ctypes.data, num_nodes=cfg.num_nodes, row_bytes=cfg.row_bytes)
+    pipe = MinibatchPipeline(graph, cache, cfg.batch, cfg.fanouts, cfg.row_bytes)
+    seeds_dev = torch_mod.from_numpy(w.seed_batches).cuda()
+    got = {}
+
+    def grab(i, sb, n, p):
+        torch_mod.cuda.current_stream().synchronize()
+        nf, nnz = sb.sizes()
+        n_hit = int(p.cache.n_hit_host[0])
+        got[i] = dict(n_frontier=nf, nnz=nnz, n=n, n_hit=n_hit,
+                      input_nodes=sb.input_nodes(n).cpu().numpy(),
+                      row_ptr=[sb.row_ptr(h, int(nf[h])).cpu().numpy() for h in range(len(nnz))],
+                      col_local=[sb.col_local(h, int(nnz[h])).cpu().numpy() for h in range(len(nnz))],
+                      out_slot=p.out_slot[:n].cpu().numpy(), miss_pos=p.miss_pos[: n - n_hit].cpu().numpy(),
+                      out_rows=p.out_rows[:n].cpu().numpy())
+
+    steps = 8
+    n_list, hit_list = pipe.run(seeds_dev, w.rng_seeds, steps, on_batch=grab)
+    op = OraclePipeline(w)
+    for b in range(steps):
+        o = op.run_batch(w.seed_batches[b], w.rng_seeds[b])
+        assert_batch_equal(got[b], o, f"overlapped batch {b}")
+        assert n_list[b] == o["n"] and hit_list[b] == o["n_hit"]
+    assert_state_equal(cache, op.cache, "overlapped")
+
+
 def test_pipeline_bfs_order_config_full_size_and_locality():
     inputs = _inputs()
     po = run_config(inputs.CONFIGS["bfs"], 10, check_every=5)
