@@ -195,7 +195,8 @@ int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64_t n, void 
  *                   miss count the last bgl_cache_lookup_gather left on the
  *                   device (no host round trip)
  * Must be enqueued after the lookup_gather that produced its inputs (same
- * stream, or ordered by the caller); it waits for that call's miss fetch itself.
+ * stream, or ordered by the caller).  The map update is enqueued first and does
+ * not wait for that call's miss fetch; the row copy waits for it on the device.
  * Errors: BGL_EINVAL, BGL_EHIP.
  */
 int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const int32_t *miss_pos,
@@ -237,8 +238,9 @@ int bgl_cache_stats(bgl_cache_t *c, uint64_t *lookups, uint64_t *hits, uint64_t 
 #define BGL_STAGE_MISS_LIST 1   /* ordered list of miss positions + counters */
 #define BGL_STAGE_GATHER_HIT 2  /* cache buffer -> out_rows */
 #define BGL_STAGE_FETCH_MISS 3  /* backing store -> out_rows */
-#define BGL_STAGE_INSERT 4      /* evict + enter ids in the map, out_rows -> cache buffer */
-#define BGL_NUM_STAGES 5
+#define BGL_STAGE_INSERT_MAP 4  /* evict + enter ids in the map */
+#define BGL_STAGE_INSERT_ROWS 5 /* out_rows -> cache buffer */
+#define BGL_NUM_STAGES 6
 /* pseudo stage: what an event pair reads around a kernel that does nothing
  * (measured when profiling is enabled); total_ms is that single figure */
 #define BGL_STAGE_EVENT_OVERHEAD 100

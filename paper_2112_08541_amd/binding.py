@@ -22,8 +22,9 @@ BGL_MAX_HOPS = 8
 BGL_MAX_FANOUT = 64
 BGL_COUNTS_LEN = 2 * BGL_MAX_HOPS + 2
 BGL_DEVICE, BGL_HOST_PINNED = 0, 1
-STAGE_PROBE, STAGE_MISS_LIST, STAGE_GATHER_HIT, STAGE_FETCH_MISS, STAGE_INSERT = range(5)
-STAGE_NAMES = ["probe", "miss_list", "gather_hit", "fetch_miss", "insert"]
+(STAGE_PROBE, STAGE_MISS_LIST, STAGE_GATHER_HIT, STAGE_FETCH_MISS,
+ STAGE_INSERT_MAP, STAGE_INSERT_ROWS) = range(6)
+STAGE_NAMES = ["probe", "miss_list", "gather_hit", "fetch_miss", "insert_map", "insert_rows"]
 
 EXPORTS = [
     "bgl_last_error", "bgl_graph_load_csr", "bgl_graph_destroy", "bgl_sample_workspace_bytes",

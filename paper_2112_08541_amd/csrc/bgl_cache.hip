@@ -405,42 +405,34 @@ __device__ __forceinline__ void insert_rows_part(
         if (dst[k] >= 0) buffer[dst[k]] = v[k];
 }
 
-// One launch does the whole FIFO update: the first map_blocks workgroups update
-// the map (random accesses, latency bound), the others copy the rows (streaming,
-// bandwidth bound), so the two overlap.  Every workgroup reads tail[par]; one lane
-// stores the advanced value in tail[par ^ 1] for the next update.
-template <int Q>
-__global__ __launch_bounds__(COPY_THREADS) void k_insert(
+// The FIFO update is two launches because only the row copy needs the fetched
+// rows: the map update is enqueued ahead of the wait for the miss fetch and runs
+// while the host link is still busy.  Both read tail[par]; the row copy stores the
+// advanced value in tail[par ^ 1] for the next update.
+__global__ __launch_bounds__(COPY_THREADS) void k_insert_map(
     const int32_t *__restrict__ ids, const int32_t *__restrict__ miss_pos, int64_t n_miss_arg,
     int64_t capacity, int64_t num_nodes, uint64_t *table, uint32_t bucket_mask,
-    int32_t *slot_to_node, uint32_t *slot_to_entry, int q, const uint4 *__restrict__ out,
-    uint4 *__restrict__ buffer, CacheDev *dev, int map_blocks, int par)
+    int32_t *slot_to_node, uint32_t *slot_to_entry, CacheDev *dev, int par)
 {
     const int64_t n_miss = n_miss_arg >= 0 ? n_miss_arg : dev->n_miss_last;
     const int64_t start = n_miss > capacity ? n_miss - capacity : 0;  // earlier ranks would be overwritten
-    const unsigned long long tail = dev->tail[par];
-    if (blockIdx.x == 0 && threadIdx.x == 0) dev->tail[par ^ 1] = tail + (unsigned long long)n_miss;
-    // alternate the two roles so that both kinds of workgroup are resident together
-    const int row_blocks = (int)gridDim.x - map_blocks;
-    const int paired = map_blocks < row_blocks ? map_blocks : row_blocks;
-    const int b = (int)blockIdx.x;
-    bool map_role;
-    int idx;
-    if (b < 2 * paired) {
-        map_role = (b & 1) == 0;
-        idx = b >> 1;
-    } else {
-        map_role = map_blocks > row_blocks;
-        idx = b - paired;
-    }
-    if (map_role)
-        insert_map_part(idx, ids, miss_pos, n_miss, start, tail, capacity, num_nodes, table,
-                        bucket_mask, slot_to_node, slot_to_entry, dev);
-    else
-        insert_rows_part<Q>(idx, miss_pos, n_miss, start, tail, capacity, q, out, buffer);
+    insert_map_part(blockIdx.x, ids, miss_pos, n_miss, start, dev->tail[par], capacity, num_nodes,
+                    table, bucket_mask, slot_to_node, slot_to_entry, dev);
 }
 
-// FIFO update when the launch above is skipped (nothing can be inserted).
+template <int Q>
+__global__ __launch_bounds__(COPY_THREADS) void k_insert_rows(
+    const int32_t *__restrict__ miss_pos, int64_t n_miss_arg, int64_t capacity, int q,
+    const uint4 *__restrict__ out, uint4 *__restrict__ buffer, CacheDev *dev, int par)
+{
+    const int64_t n_miss = n_miss_arg >= 0 ? n_miss_arg : dev->n_miss_last;
+    const int64_t start = n_miss > capacity ? n_miss - capacity : 0;
+    const unsigned long long tail = dev->tail[par];
+    if (blockIdx.x == 0 && threadIdx.x == 0) dev->tail[par ^ 1] = tail + (unsigned long long)n_miss;
+    insert_rows_part<Q>(blockIdx.x, miss_pos, n_miss, start, tail, capacity, q, out, buffer);
+}
+
+// FIFO update when the launches above are skipped (nothing can be inserted).
 __global__ void k_advance_tail(CacheDev *dev, int64_t n_miss_arg, int par)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
@@ -710,20 +702,27 @@ extern "C" int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const i
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int q = c->row_bytes / 16;
     const int64_t eff = std::min<int64_t>(bound, c->capacity);
-    if (c->fetch_pending) BGL_HIP(hipStreamWaitEvent(st, c->ev_miss, 0));  // rows of the misses
     const int par = (int)(c->insert_calls & 1);
     if (eff > 0) {
-        Prof p(c, BGL_STAGE_INSERT, st);
-        const int map_blocks = (int)bgl::ceil_div(eff * BUCKET, COPY_THREADS);
-        const int row_blocks = copy_blocks(eff, q);
-        dispatch_q(q, [&](auto Q) {
-            hipLaunchKernelGGL((k_insert<decltype(Q)::value>), dim3(map_blocks + row_blocks),
+        {
+            Prof p(c, BGL_STAGE_INSERT_MAP, st);
+            hipLaunchKernelGGL(k_insert_map, dim3((unsigned)bgl::ceil_div(eff * BUCKET, COPY_THREADS)),
                                dim3(COPY_THREADS), 0, st, ids, miss_pos, n_miss, c->capacity,
                                c->num_nodes, c->table, c->num_buckets - 1, c->slot_to_node,
-                               c->slot_to_entry, q, reinterpret_cast<const uint4 *>(out_rows),
-                               reinterpret_cast<uint4 *>(c->buffer), c->dev, map_blocks, par);
-        });
+                               c->slot_to_entry, c->dev, par);
+        }
+        if (c->fetch_pending) BGL_HIP(hipStreamWaitEvent(st, c->ev_miss, 0));  // rows of the misses
+        {
+            Prof p(c, BGL_STAGE_INSERT_ROWS, st);
+            dispatch_q(q, [&](auto Q) {
+                hipLaunchKernelGGL((k_insert_rows<decltype(Q)::value>), dim3(copy_blocks(eff, q)),
+                                   dim3(COPY_THREADS), 0, st, miss_pos, n_miss, c->capacity, q,
+                                   reinterpret_cast<const uint4 *>(out_rows),
+                                   reinterpret_cast<uint4 *>(c->buffer), c->dev, par);
+            });
+        }
     } else {
+        if (c->fetch_pending) BGL_HIP(hipStreamWaitEvent(st, c->ev_miss, 0));
         hipLaunchKernelGGL(k_advance_tail, dim3(1), dim3(64), 0, st, c->dev, n_miss, par);
     }
     c->insert_calls += 1;
