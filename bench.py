@@ -181,6 +181,28 @@ def main():
         }
         result["stage_ms_per_step"] = {k: v[0] / v[1] for k, v in prof.items() if v[1] > 0}  # event pairs, uncorrected
 
+        # The same kernel on a launch that is mostly hits (outside the timed region, not
+        # part of `value`): the epoch's last batch is looked up again right after its
+        # insertion; only the rows its own insertions evicted miss.
+        if pipe.last_n:
+            cache.set_profiling(("gather_hit",))
+            reps, hits2 = 5, 0
+            for _ in range(reps):
+                cache.lookup_gather(pipe.last_ids, pipe.last_n, pipe.out_rows, pipe.out_slot, pipe.miss_pos,
+                                    side_stream=pipe.side)
+                torch.cuda.synchronize()
+                hits2 += int(cache.n_hit_host[0])
+            p2 = cache.profile()
+            k_ms = max(p2["gather_hit"][0] - p2["event_overhead"][0] * reps, 1e-9)
+            a2 = 2.0 * rb * hits2 / (k_ms * 1e-3) / 1e9
+            result["roofline_repeat_lookup"] = {
+                "kernel": "k_gather_hits", "bound": "hbm", "achieved": a2, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": a2 / HBM_PEAK_GBS, "bytes_per_launch": 2.0 * rb * hits2 / reps,
+                "avg_launch_us": 1e3 * k_ms / reps, "launches": reps,
+                "hit_ratio": hits2 / (reps * pipe.last_n),
+                "note": "last batch of the epoch looked up again after its insertion; not part of value",
+            }
+
     if not args.no_cpu_baseline:
         import oracle
         oc = oracle.Cache(cfg.cache_rows, w.features)

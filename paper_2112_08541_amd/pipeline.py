@@ -34,6 +34,7 @@ class MinibatchPipeline:
         self.miss_pos = torch.empty(self.cap, dtype=torch.int32, device="cuda")
         self.side = torch.cuda.Stream()
         self.main = torch.cuda.current_stream()
+        self.last_ids, self.last_n = None, 0    # input nodes of the most recent batch
 
     def set_cache(self, cache: B.Cache) -> None:
         self.cache = cache
@@ -68,6 +69,7 @@ class MinibatchPipeline:
                 ev.record(main)
             cache.insert_fifo(ids, self.miss_pos, -1, self.out_rows, stream=main)
             n_list.append(n)
+            self.last_ids, self.last_n = ids, n
             if on_batch is not None:
                 on_batch(i, sb, n, self)
             if nxt < steps:
