@@ -62,6 +62,12 @@ def lib() -> C.CDLL:
             getattr(L, name).argtypes = [vp]
         L.bglo_cache_stats.restype = None
         L.bglo_cache_stats.argtypes = [vp, vp, vp]
+        L.bglo_bfs_sequence.restype = i64
+        L.bglo_bfs_sequence.argtypes = [vp, C.c_int, vp, i64, vp, i64, vp]
+        L.bglo_po_merge.restype = C.c_int
+        L.bglo_po_merge.argtypes = [vp, i64, i32, vp, i64, i64, vp]
+        L.bglo_shuffling_error.restype = C.c_int
+        L.bglo_shuffling_error.argtypes = [vp, i64, i32, vp, i32, vp, vp]
         _lib = L
     return _lib
 
@@ -217,3 +223,42 @@ class Cache:
         a, b = C.c_uint64(0), C.c_uint64(0)
         lib().bglo_cache_stats(self._h, C.addressof(a), C.addressof(b))
         return a.value, b.value
+
+
+def bfs_sequence(row_ptr: np.ndarray, col: np.ndarray, train_nodes, root: int) -> np.ndarray:
+    """Training nodes in canonical BFS order from `root` (levels, ids inside a level,
+    restart at the smallest unvisited id)."""
+    row_ptr = np.ascontiguousarray(row_ptr)
+    bits = 64 if row_ptr.dtype == np.int64 else 32
+    col = np.ascontiguousarray(col, dtype=np.int32)
+    N = len(row_ptr) - 1
+    is_train = np.zeros(N, dtype=np.uint8)
+    is_train[np.asarray(train_nodes, dtype=np.int64)] = 1
+    seq = np.empty(int(is_train.sum()), dtype=np.int32)
+    n = lib().bglo_bfs_sequence(_ptr(row_ptr), bits, _ptr(col), N, _ptr(is_train), int(root), _ptr(seq))
+    if n != len(seq):
+        raise ValueError("bglo_bfs_sequence failed")
+    return seq
+
+
+def proximity_order(row_ptr, col, train_nodes, roots, shifts, num_out: int) -> np.ndarray:
+    train_nodes = np.asarray(train_nodes, dtype=np.int32)
+    seqs = np.concatenate([bfs_sequence(row_ptr, col, train_nodes, r) for r in roots]).astype(np.int32)
+    shifts = np.ascontiguousarray(shifts, dtype=np.int64)
+    order = np.empty(num_out, dtype=np.int32)
+    rc = lib().bglo_po_merge(_ptr(seqs), len(train_nodes), len(roots), _ptr(shifts), len(row_ptr) - 1,
+                             num_out, _ptr(order))
+    if rc != 0:
+        raise ValueError(f"bglo_po_merge failed with status {rc}")
+    return order
+
+
+def shuffling_error(order, batch: int, labels, num_classes: int):
+    order = np.ascontiguousarray(order, dtype=np.int32)
+    labels = np.ascontiguousarray(labels, dtype=np.int32)
+    a, b = C.c_double(0), C.c_double(0)
+    rc = lib().bglo_shuffling_error(_ptr(order), len(order), batch, _ptr(labels), num_classes,
+                                    C.addressof(a), C.addressof(b))
+    if rc != 0:
+        raise ValueError("bglo_shuffling_error failed")
+    return a.value, b.value

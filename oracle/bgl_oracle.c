@@ -298,3 +298,120 @@ void bglo_cache_stats(const bglo_cache *c, uint64_t *lookups, uint64_t *hits)
     *lookups = c->lookups;
     *hits = c->hits;
 }
+
+/* ------------------------------------------------------------------------- */
+/* Proximity-aware ordering (Sec. 3.2.2): training-node sequences in BFS order
+ * from several roots, each sequence rotated by a random offset, batches filled
+ * from the sequences in turn.  The random roots and offsets are inputs.
+ *
+ * Canonical BFS order (the paper only says "BFS order"): nodes are visited level
+ * by level; inside a level in increasing node id; when a traversal is exhausted
+ * it restarts at the smallest node id not visited yet (small components end up
+ * at the end of the sequence, as Sec. 3.2.2 observes).  Only training nodes are
+ * recorded. */
+static int cmp_i32(const void *a, const void *b)
+{
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/* Returns the number of training nodes recorded in seq, or -1 on bad arguments. */
+int64_t bglo_bfs_sequence(const void *row_ptr, int row_ptr_bits, const int32_t *col,
+                          int64_t num_nodes, const uint8_t *is_train, int64_t root,
+                          int32_t *seq)
+{
+    if (num_nodes <= 0 || root < 0 || root >= num_nodes) return -1;
+    uint8_t *seen = (uint8_t *)calloc((size_t)num_nodes, 1);
+    int32_t *cur = (int32_t *)malloc(sizeof(int32_t) * (size_t)num_nodes);
+    int32_t *nxt = (int32_t *)malloc(sizeof(int32_t) * (size_t)num_nodes);
+    if (!seen || !cur || !nxt) { free(seen); free(cur); free(nxt); return -1; }
+    int64_t n_out = 0, n_seen = 0, scan = 0;
+    int64_t start = root;
+    while (n_seen < num_nodes) {
+        int64_t n_cur = 1;
+        cur[0] = (int32_t)start;
+        seen[start] = 1;
+        while (n_cur > 0) {
+            n_seen += n_cur;
+            for (int64_t i = 0; i < n_cur; ++i)          /* the level, in id order */
+                if (is_train[cur[i]]) seq[n_out++] = cur[i];
+            int64_t n_nxt = 0;
+            for (int64_t i = 0; i < n_cur; ++i) {
+                int64_t lo = rp_at(row_ptr, row_ptr_bits, cur[i]);
+                int64_t hi = rp_at(row_ptr, row_ptr_bits, (int64_t)cur[i] + 1);
+                for (int64_t e = lo; e < hi; ++e) {
+                    int32_t u = col[e];
+                    if (!seen[u]) { seen[u] = 1; nxt[n_nxt++] = u; }
+                }
+            }
+            qsort(nxt, (size_t)n_nxt, sizeof(int32_t), cmp_i32);
+            int32_t *t = cur; cur = nxt; nxt = t;
+            n_cur = n_nxt;
+        }
+        while (scan < num_nodes && seen[scan]) ++scan;   /* smallest unvisited id */
+        if (scan >= num_nodes) break;
+        start = scan;
+    }
+    free(seen); free(cur); free(nxt);
+    return n_out;
+}
+
+/* Merge: sequence j is read from offset shifts[j] (cyclically); turn t takes the
+ * next node of sequence t mod S that no earlier turn has taken.  seqs holds the S
+ * sequences back to back (each num_train long).  Writes num_out <= num_train ids. */
+int bglo_po_merge(const int32_t *seqs, int64_t num_train, int32_t num_seq, const int64_t *shifts,
+                  int64_t num_nodes, int64_t num_out, int32_t *order)
+{
+    if (num_seq < 1 || num_out > num_train) return -1;
+    uint8_t *used = (uint8_t *)calloc((size_t)num_nodes, 1);
+    int64_t *cursor = (int64_t *)calloc((size_t)num_seq, sizeof(int64_t));
+    if (!used || !cursor) { free(used); free(cursor); return -2; }
+    int64_t turn = 0;
+    for (int64_t k = 0; k < num_out; ++k, ++turn) {
+        int32_t j = (int32_t)(turn % num_seq);
+        const int32_t *s = seqs + (size_t)j * (size_t)num_train;
+        int32_t v;
+        for (;;) {
+            v = s[(shifts[j] + cursor[j]) % num_train];
+            cursor[j] += 1;
+            if (!used[v]) break;
+        }
+        used[v] = 1;
+        order[k] = v;
+    }
+    free(used); free(cursor);
+    return 0;
+}
+
+/* Shuffling error (Sec. 3.2.2, after Meng et al.): total variation distance
+ * between the label distribution of a batch and that of all ordered nodes;
+ * reading: reported as the mean and the maximum over the batches (the paper
+ * "estimates the probability of each label as the frequency per mini-batch"
+ * without saying how batches are combined). */
+int bglo_shuffling_error(const int32_t *order, int64_t n, int32_t batch, const int32_t *labels,
+                         int32_t num_classes, double *mean_tv, double *max_tv)
+{
+    if (n <= 0 || batch <= 0 || num_classes <= 0) return -1;
+    /* integer counts first, so that equal frequencies compare equal */
+    int64_t *g = (int64_t *)calloc((size_t)num_classes, sizeof(int64_t));
+    int64_t *b = (int64_t *)calloc((size_t)num_classes, sizeof(int64_t));
+    for (int64_t i = 0; i < n; ++i) g[labels[order[i]]] += 1;
+    int64_t nb = 0;
+    double sum = 0.0, mx = 0.0;
+    for (int64_t s = 0; s < n; s += batch, ++nb) {
+        int64_t e = s + batch < n ? s + batch : n;
+        for (int32_t c = 0; c < num_classes; ++c) b[c] = 0;
+        for (int64_t i = s; i < e; ++i) b[labels[order[i]]] += 1;
+        double tv = 0.0;
+        for (int32_t c = 0; c < num_classes; ++c) {
+            double pb = (double)b[c] / (double)(e - s), pg = (double)g[c] / (double)n;
+            tv += 0.5 * (pb > pg ? pb - pg : pg - pb);
+        }
+        sum += tv;
+        if (tv > mx) mx = tv;
+    }
+    *mean_tv = sum / (double)nb;
+    *max_tv = mx;
+    free(g); free(b);
+    return 0;
+}
