@@ -203,6 +203,29 @@ def main():
                 "note": "last batch of the epoch looked up again after its insertion; not part of value",
             }
 
+    if cfg.order == "po":
+        # Proximity-aware ordering as the library computes it (once per epoch, outside the
+        # timed region): 5 BFS sequences over the training set on the GPU, merged on the host.
+        rng = np.random.default_rng(cfg.seed + 6)
+        train = np.unique(w.seed_batches.reshape(-1)).astype(np.int32)
+        roots = rng.integers(0, cfg.num_nodes, cfg.po_sequences)
+        shifts = rng.integers(0, len(train), cfg.po_sequences)
+        B.order_proximity(graph, train, roots, shifts, len(train))          # warm-up
+        o0 = time.perf_counter()
+        order = B.order_proximity(graph, train, roots, shifts, len(train))
+        o1 = time.perf_counter()
+        result["ordering"] = {
+            "call": "bgl_order_proximity", "sequences": cfg.po_sequences, "train_nodes": int(len(train)),
+            "seconds": o1 - o0,
+            "edges_traversed_per_s": cfg.po_sequences * w.num_edges / (o1 - o0),
+        }
+        if not args.no_cpu_baseline:
+            import oracle
+            c0 = time.perf_counter()
+            want = oracle.proximity_order(w.row_ptr, w.col, train, roots, shifts, len(train))
+            result["ordering"]["oracle_seconds"] = time.perf_counter() - c0
+            assert np.array_equal(order, want)
+
     if not args.no_cpu_baseline:
         import oracle
         oc = oracle.Cache(cfg.cache_rows, w.features)

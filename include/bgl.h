@@ -248,6 +248,52 @@ int bgl_cache_stats(bgl_cache_t *c, uint64_t *lookups, uint64_t *hits, uint64_t 
 int bgl_cache_set_profiling(bgl_cache_t *c, int stage_mask);
 int bgl_cache_profile(bgl_cache_t *c, int stage, double *total_ms, int64_t *launches);
 
+/* --------------------------------------------------------------- ordering */
+
+/*
+ * One BFS sequence of the training nodes (Sec. 3.2.2: training-node sequences
+ * generated in BFS order).  The traversal runs on the GPU over the registered
+ * graph.  Canonical order: level by level from `root`, ids ascending inside a
+ * level; when a traversal is exhausted it restarts at the smallest node id not
+ * visited yet, so small components end up at the end of the sequence.  Only the
+ * training nodes are recorded.
+ *   train_nodes   host, num_train distinct node ids
+ *   seq           host, receives num_train ids
+ * Synchronous (returns when seq is filled).
+ * Errors: BGL_EINVAL (null pointers, root or a training id outside
+ * [0, num_nodes), repeated training id, num_train outside [1, num_nodes]),
+ * BGL_ENOMEM, BGL_EHIP.
+ */
+int bgl_order_bfs_sequence(const bgl_graph_t *g, const int32_t *train_nodes, int64_t num_train,
+                           int64_t root, int32_t *seq, void *stream);
+
+/*
+ * Proximity-aware order of the training nodes (Sec. 3.2.2): num_sequences BFS
+ * sequences from the given roots; sequence j is read cyclically starting at
+ * offset shifts[j] (the paper's random shift); the output takes nodes from the
+ * sequences in turn (turn t: the next node of sequence t mod num_sequences that
+ * no earlier turn has taken), so consecutive batches draw from every sequence.
+ * The random roots and shifts are the caller's draws.
+ *   roots, shifts host, num_sequences values; 0 <= shifts[j] < num_train
+ *   order         host, receives the first num_out <= num_train nodes of the order
+ * Synchronous.  Errors as above.
+ */
+int bgl_order_proximity(const bgl_graph_t *g, const int32_t *train_nodes, int64_t num_train,
+                        int32_t num_sequences, const int64_t *roots, const int64_t *shifts,
+                        int64_t num_out, int32_t *order, void *stream);
+
+/*
+ * Shuffling error of an order (Sec. 3.2.2, the quantity compared with
+ * sqrt(b*M)/n to choose the number of sequences): total variation distance
+ * between the label distribution of a batch and the label distribution of all
+ * n ordered nodes, as the mean and the maximum over the batches of `batch`
+ * consecutive nodes.  Host only.
+ *   labels        host, num_nodes labels in [0, num_classes)
+ * Errors: BGL_EINVAL.
+ */
+int bgl_order_shuffling_error(const int32_t *order, int64_t n, int32_t batch, const int32_t *labels,
+                              int64_t num_nodes, int32_t num_classes, double *mean_tv, double *max_tv);
+
 #ifdef __cplusplus
 }
 #endif

@@ -31,6 +31,7 @@ EXPORTS = [
     "bgl_sample_khop", "bgl_cache_create", "bgl_cache_destroy", "bgl_cache_lookup_gather",
     "bgl_cache_insert_fifo", "bgl_cache_wait_rows", "bgl_cache_export_state", "bgl_cache_stats",
     "bgl_cache_set_profiling", "bgl_cache_profile",
+    "bgl_order_bfs_sequence", "bgl_order_proximity", "bgl_order_shuffling_error",
 ]
 
 
@@ -74,6 +75,10 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
                                   C.POINTER(u64), C.POINTER(i32)]
     L.bgl_cache_set_profiling.argtypes = [vp, ci]
     L.bgl_cache_profile.argtypes = [vp, ci, C.POINTER(C.c_double), C.POINTER(i64)]
+    L.bgl_order_bfs_sequence.argtypes = [vp, vp, i64, i64, vp, vp]
+    L.bgl_order_proximity.argtypes = [vp, vp, i64, i32, vp, vp, i64, vp, vp]
+    L.bgl_order_shuffling_error.argtypes = [vp, i64, i32, vp, i64, i32, C.POINTER(C.c_double),
+                                            C.POINTER(C.c_double)]
     for name in EXPORTS:
         if name != "bgl_last_error":
             getattr(L, name).restype = ci
@@ -305,3 +310,36 @@ class Cache:
         _check(lib().bgl_cache_profile(self._h, 100, C.byref(ms), C.byref(n)))
         out["event_overhead"] = (ms.value, 1)
         return out
+
+
+def order_bfs_sequence(graph: Graph, train_nodes, root: int, stream=None) -> np.ndarray:
+    """bgl_order_bfs_sequence: the training nodes in canonical BFS order from `root`."""
+    train = np.ascontiguousarray(train_nodes, dtype=np.int32)
+    seq = np.empty(len(train), dtype=np.int32)
+    _check(lib().bgl_order_bfs_sequence(graph._h, train.ctypes.data, len(train), int(root),
+                                        seq.ctypes.data, _stream_handle(stream)))
+    return seq
+
+
+def order_proximity(graph: Graph, train_nodes, roots, shifts, num_out: int, stream=None) -> np.ndarray:
+    """bgl_order_proximity: the first num_out nodes of the proximity-aware order."""
+    train = np.ascontiguousarray(train_nodes, dtype=np.int32)
+    roots = np.ascontiguousarray(roots, dtype=np.int64)
+    shifts = np.ascontiguousarray(shifts, dtype=np.int64)
+    if len(roots) != len(shifts):
+        raise ValueError("one shift per root")
+    order = np.empty(max(num_out, 1), dtype=np.int32)
+    _check(lib().bgl_order_proximity(graph._h, train.ctypes.data, len(train), len(roots),
+                                     roots.ctypes.data, shifts.ctypes.data, int(num_out),
+                                     order.ctypes.data, _stream_handle(stream)))
+    return order[:num_out]
+
+
+def order_shuffling_error(order, batch: int, labels, num_classes: int):
+    """bgl_order_shuffling_error: (mean, max) total variation distance over the batches."""
+    order = np.ascontiguousarray(order, dtype=np.int32)
+    labels = np.ascontiguousarray(labels, dtype=np.int32)
+    a, b = C.c_double(0), C.c_double(0)
+    _check(lib().bgl_order_shuffling_error(order.ctypes.data, len(order), int(batch), labels.ctypes.data,
+                                           len(labels), int(num_classes), C.byref(a), C.byref(b)))
+    return a.value, b.value

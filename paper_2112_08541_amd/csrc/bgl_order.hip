@@ -1,0 +1,375 @@
+// Proximity-aware ordering of the training nodes (BGL paper, Sec. 3.2.2):
+// several BFS sequences over the training nodes from given roots, each read from
+// a given offset, merged into batches in turn.  The traversals run on the GPU;
+// the merge (a strictly sequential scan over a few hundred thousand ids) and the
+// shuffling-error statistic run on the host.
+//
+// Canonical BFS order: level by level, ids ascending inside a level, restart at
+// the smallest id not visited yet.  A level-synchronous bitmap BFS gives exactly
+// that: the next level is a bitmap, and compacting a bitmap yields ids in
+// ascending order for free.  Per level: expand (16 lanes walk one frontier
+// node's row, test-and-set the visited bitmap), then count / scan / write to turn
+// the next-level bitmap into the sorted frontier list and to append its training
+// nodes to the sequence.  Restarts: nodes all of whose out-neighbors are visited
+// ("closed") would each be a one-node traversal; all closed nodes below the
+// smallest open node are taken in one step, which is the same order.
+#include <algorithm>
+#include <climits>
+#include <vector>
+
+#include "bgl_internal.h"
+
+namespace {
+
+using namespace bgl;
+
+constexpr int BT = 256;
+
+struct OrderDev {
+    int fsize;      // size of the frontier the last compaction wrote
+    int seq_len;    // training nodes recorded so far
+    int open_min;   // smallest unvisited node that has an unvisited out-neighbor
+    int status;
+};
+
+__device__ __forceinline__ bool test_bit(const uint32_t *bm, uint32_t v) { return (bm[v >> 5] >> (v & 31)) & 1u; }
+
+__global__ void k_fill_u32(uint32_t *p, int64_t n, uint32_t v)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = v;
+}
+
+__global__ void k_set_bits(const int32_t *ids, int64_t n, int64_t num_nodes, uint32_t *bm, OrderDev *dev)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int32_t v = ids[i];
+    if (v < 0 || (int64_t)v >= num_nodes) { dev->status = BGL_EINVAL; return; }
+    const uint32_t old = atomicOr(&bm[(uint32_t)v >> 5], 1u << (v & 31));
+    if (old & (1u << (v & 31))) dev->status = BGL_EINVAL;  // listed twice
+}
+
+// A fresh traversal: bits at and above num_nodes count as visited.
+__global__ void k_reset(uint32_t *visited, uint32_t *next, int64_t words, int64_t num_nodes, OrderDev *dev)
+{
+    const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (w == 0) { dev->fsize = 0; dev->seq_len = 0; dev->open_min = INT_MAX; }
+    if (w >= words) return;
+    uint32_t v = 0;
+    const int64_t base = w * 32;
+    if (base + 32 > num_nodes) v = num_nodes > base ? ~0u << (uint32_t)(num_nodes - base) : ~0u;
+    visited[w] = v;
+    next[w] = 0;
+}
+
+// Start (or restart) a traversal at one node; node < 0 means "at dev->open_min".
+__global__ void k_start_at(int32_t node, uint32_t *visited, const uint32_t *train, int32_t *frontier,
+                           int32_t *seq, OrderDev *dev)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const int32_t v = node >= 0 ? node : dev->open_min;
+    visited[(uint32_t)v >> 5] |= 1u << (v & 31);
+    frontier[0] = v;
+    dev->fsize = 1;
+    if (test_bit(train, (uint32_t)v)) seq[dev->seq_len++] = v;
+    dev->open_min = INT_MAX;
+}
+
+// 16 lanes per frontier node walk its row; a neighbor seen for the first time goes into `next`.
+template <typename RP>
+__global__ __launch_bounds__(BT) void k_expand(const RP *__restrict__ row_ptr, const int32_t *__restrict__ col,
+                                               const int32_t *__restrict__ frontier, int fsize,
+                                               uint32_t *visited, uint32_t *next)
+{
+    const int64_t g = ((int64_t)blockIdx.x * BT + threadIdx.x) >> 4;
+    const int l = threadIdx.x & 15;
+    if (g >= fsize) return;
+    const int32_t v = frontier[g];
+    const int64_t lo = (int64_t)row_ptr[v], hi = (int64_t)row_ptr[v + 1];
+    for (int64_t e = lo + l; e < hi; e += 16) {
+        const uint32_t u = (uint32_t)col[e];
+        const uint32_t bit = 1u << (u & 31);
+        if (!(visited[u >> 5] & bit)) {
+            const uint32_t old = atomicOr(&visited[u >> 5], bit);
+            if (!(old & bit)) atomicOr(&next[u >> 5], bit);
+        }
+    }
+}
+
+// Bitmap -> ascending id list, three steps.  One bitmap word per lane.
+__global__ __launch_bounds__(BT) void k_bm_count(const uint32_t *__restrict__ next, const uint32_t *__restrict__ train,
+                                                 int64_t words, int32_t *bs_all, int32_t *bs_tr)
+{
+    __shared__ int sh[BT / kWave];
+    const int64_t w = (int64_t)blockIdx.x * BT + threadIdx.x;
+    const uint32_t m = w < words ? next[w] : 0u;
+    const uint32_t t = w < words ? (m & train[w]) : 0u;
+    int ta, tt;
+    (void)block_excl_scan<BT>(__popc(m), sh, ta);
+    (void)block_excl_scan<BT>(__popc(t), sh, tt);
+    if (threadIdx.x == 0) { bs_all[blockIdx.x] = ta; bs_tr[blockIdx.x] = tt; }
+}
+
+__global__ __launch_bounds__(1024) void k_bm_scan(int32_t *bs_all, int32_t *bs_tr, int nb, OrderDev *dev,
+                                                  int32_t *seq_base)
+{
+    __shared__ int sh[1024 / kWave];
+    int ca = 0, ct = 0;
+    for (int base = 0; base < nb; base += 1024) {
+        const int i = base + threadIdx.x;
+        const int a = i < nb ? bs_all[i] : 0, t = i < nb ? bs_tr[i] : 0;
+        int ta, tt;
+        const int ea = block_excl_scan<1024>(a, sh, ta);
+        const int et = block_excl_scan<1024>(t, sh, tt);
+        if (i < nb) { bs_all[i] = ca + ea; bs_tr[i] = ct + et; }
+        ca += ta;
+        ct += tt;
+    }
+    if (threadIdx.x == 0) {
+        dev->fsize = ca;
+        *seq_base = dev->seq_len;
+        dev->seq_len += ct;
+    }
+}
+
+__global__ __launch_bounds__(BT) void k_bm_write(uint32_t *next, const uint32_t *__restrict__ train, int64_t words,
+                                                 const int32_t *__restrict__ pre_all, const int32_t *__restrict__ pre_tr,
+                                                 const int32_t *__restrict__ seq_base, int32_t *frontier, int32_t *seq)
+{
+    __shared__ int sh[BT / kWave];
+    const int64_t w = (int64_t)blockIdx.x * BT + threadIdx.x;
+    uint32_t m = w < words ? next[w] : 0u;
+    uint32_t t = w < words ? (m & train[w]) : 0u;
+    int ta, tt;
+    int oa = pre_all[blockIdx.x] + block_excl_scan<BT>(__popc(m), sh, ta);
+    int ot = *seq_base + pre_tr[blockIdx.x] + block_excl_scan<BT>(__popc(t), sh, tt);
+    if (m) next[w] = 0;
+    const int32_t base = (int32_t)(w * 32);
+    while (m) { frontier[oa++] = base + (__ffs(m) - 1); m &= m - 1; }
+    while (t) { seq[ot++] = base + (__ffs(t) - 1); t &= t - 1; }
+}
+
+// Smallest unvisited node with an unvisited out-neighbor other than itself.
+template <typename RP>
+__global__ __launch_bounds__(BT) void k_open_min(const RP *__restrict__ row_ptr, const int32_t *__restrict__ col,
+                                                 const uint32_t *__restrict__ visited, int64_t num_nodes, OrderDev *dev)
+{
+    const int64_t v = (int64_t)blockIdx.x * BT + threadIdx.x;
+    if (v >= num_nodes || test_bit(visited, (uint32_t)v)) return;
+    if (v >= dev->open_min) return;  // cannot improve the minimum
+    const int64_t lo = (int64_t)row_ptr[v], hi = (int64_t)row_ptr[v + 1];
+    for (int64_t e = lo; e < hi; ++e) {
+        const uint32_t u = (uint32_t)col[e];
+        if ((int64_t)u != v && !test_bit(visited, u)) { atomicMin(&dev->open_min, (int)v); return; }
+    }
+}
+
+// Every unvisited node below dev->open_min is closed: visit them all, in id order.
+__global__ __launch_bounds__(BT) void k_take_closed(uint32_t *visited, uint32_t *next, int64_t words, const OrderDev *dev)
+{
+    const int64_t w = (int64_t)blockIdx.x * BT + threadIdx.x;
+    if (w >= words) return;
+    const int64_t limit = dev->open_min;  // INT_MAX: take everything
+    const int64_t base = w * 32;
+    if (base >= limit) return;
+    uint32_t free_bits = ~visited[w];
+    if (limit < base + 32) free_bits &= (1u << (uint32_t)(limit - base)) - 1u;
+    if (free_bits) { visited[w] |= free_bits; next[w] = free_bits; }
+}
+
+struct OrderWork {
+    uint32_t *visited = nullptr, *next = nullptr, *train = nullptr;
+    int32_t *frontier = nullptr, *seq = nullptr, *train_ids = nullptr, *bs_all = nullptr, *bs_tr = nullptr, *seq_base = nullptr;
+    OrderDev *dev = nullptr;
+    OrderDev *host = nullptr;  // page-locked mirror
+    ~OrderWork()
+    {
+        (void)hipFree(visited); (void)hipFree(next); (void)hipFree(train); (void)hipFree(frontier);
+        (void)hipFree(seq); (void)hipFree(train_ids); (void)hipFree(bs_all); (void)hipFree(bs_tr);
+        (void)hipFree(seq_base); (void)hipFree(dev);
+        if (host) (void)hipHostFree(host);
+    }
+};
+
+int read_dev(OrderWork &w, hipStream_t st)
+{
+    BGL_HIP(hipMemcpyAsync(w.host, w.dev, sizeof(OrderDev), hipMemcpyDeviceToHost, st));
+    BGL_HIP(hipStreamSynchronize(st));
+    return BGL_OK;
+}
+
+int prepare(const bgl_graph *g, const int32_t *train_nodes, int64_t num_train, OrderWork &w, hipStream_t st)
+{
+    const int64_t N = g->num_nodes, words = ceil_div(N, 32);
+    const int nb = (int)ceil_div(words, BT);
+    BGL_HIP(hipMalloc((void **)&w.visited, words * 4));
+    BGL_HIP(hipMalloc((void **)&w.next, words * 4));
+    BGL_HIP(hipMalloc((void **)&w.train, words * 4));
+    BGL_HIP(hipMalloc((void **)&w.frontier, N * 4));
+    BGL_HIP(hipMalloc((void **)&w.seq, std::max<int64_t>(num_train, 1) * 4));
+    BGL_HIP(hipMalloc((void **)&w.train_ids, std::max<int64_t>(num_train, 1) * 4));
+    BGL_HIP(hipMalloc((void **)&w.bs_all, (nb + 1) * 4));
+    BGL_HIP(hipMalloc((void **)&w.bs_tr, (nb + 1) * 4));
+    BGL_HIP(hipMalloc((void **)&w.seq_base, 4));
+    BGL_HIP(hipMalloc((void **)&w.dev, sizeof(OrderDev)));
+    BGL_HIP(hipHostMalloc((void **)&w.host, sizeof(OrderDev), hipHostMallocDefault));
+    BGL_HIP(hipMemsetAsync(w.dev, 0, sizeof(OrderDev), st));
+    BGL_HIP(hipMemcpyAsync(w.train_ids, train_nodes, num_train * 4, hipMemcpyHostToDevice, st));
+    hipLaunchKernelGGL(k_fill_u32, dim3(std::min<int64_t>(ceil_div(words, BT), 4096)), dim3(BT), 0, st, w.train, words, 0u);
+    if (num_train > 0)
+        hipLaunchKernelGGL(k_set_bits, dim3((unsigned)ceil_div(num_train, BT)), dim3(BT), 0, st, w.train_ids,
+                           num_train, N, w.train, w.dev);
+    int rc = read_dev(w, st);
+    if (rc != BGL_OK) return rc;
+    if (w.host->status != 0) BGL_FAIL(BGL_EINVAL, "train_nodes holds an id outside [0, num_nodes) or a repeated id");
+    return BGL_OK;
+}
+
+// One traversal; leaves the sequence (num_train ids) in w.seq.
+template <typename RP>
+int bfs_sequence(const bgl_graph *g, int64_t root, int64_t num_train, OrderWork &w, hipStream_t st)
+{
+    const int64_t N = g->num_nodes, words = ceil_div(N, 32);
+    const int nb = (int)ceil_div(words, BT);
+    const RP *rp = static_cast<const RP *>(g->row_ptr);
+    hipLaunchKernelGGL(k_reset, dim3(nb), dim3(BT), 0, st, w.visited, w.next, words, N, w.dev);
+    hipLaunchKernelGGL(k_start_at, dim3(1), dim3(64), 0, st, (int32_t)root, w.visited, w.train, w.frontier, w.seq, w.dev);
+    int64_t visited_count = 1;
+    int fsize = 1;
+    auto compact = [&]() {
+        hipLaunchKernelGGL(k_bm_count, dim3(nb), dim3(BT), 0, st, w.next, w.train, words, w.bs_all, w.bs_tr);
+        hipLaunchKernelGGL(k_bm_scan, dim3(1), dim3(1024), 0, st, w.bs_all, w.bs_tr, nb, w.dev, w.seq_base);
+        hipLaunchKernelGGL(k_bm_write, dim3(nb), dim3(BT), 0, st, w.next, w.train, words, w.bs_all, w.bs_tr,
+                           w.seq_base, w.frontier, w.seq);
+    };
+    for (;;) {
+        while (fsize > 0) {
+            hipLaunchKernelGGL((k_expand<RP>), dim3((unsigned)ceil_div((int64_t)fsize * 16, BT)), dim3(BT), 0, st, rp,
+                               g->col, w.frontier, fsize, w.visited, w.next);
+            compact();
+            int rc = read_dev(w, st);
+            if (rc != BGL_OK) return rc;
+            fsize = w.host->fsize;
+            visited_count += fsize;
+        }
+        if (visited_count >= N) break;
+        hipLaunchKernelGGL((k_open_min<RP>), dim3((unsigned)ceil_div(N, BT)), dim3(BT), 0, st, rp, g->col, w.visited, N, w.dev);
+        hipLaunchKernelGGL(k_take_closed, dim3(nb), dim3(BT), 0, st, w.visited, w.next, words, w.dev);
+        compact();
+        int rc = read_dev(w, st);
+        if (rc != BGL_OK) return rc;
+        visited_count += w.host->fsize;
+        if (w.host->open_min == INT_MAX) break;  // everything that was left was closed
+        hipLaunchKernelGGL(k_start_at, dim3(1), dim3(64), 0, st, (int32_t)-1, w.visited, w.train, w.frontier, w.seq, w.dev);
+        fsize = 1;
+        visited_count += 1;
+    }
+    BGL_HIP(hipGetLastError());
+    int rc = read_dev(w, st);
+    if (rc != BGL_OK) return rc;
+    if (visited_count != N || w.host->seq_len != num_train)
+        BGL_FAIL(BGL_EHIP, "traversal ended with %lld of %lld nodes and %d of %lld training nodes",
+                 (long long)visited_count, (long long)N, w.host->seq_len, (long long)num_train);
+    return BGL_OK;
+}
+
+int check_order_args(const bgl_graph_t *g, const int32_t *train_nodes, int64_t num_train)
+{
+    if (!g) BGL_FAIL(BGL_EINVAL, "graph handle is null");
+    if (num_train < 1 || num_train > g->num_nodes) BGL_FAIL(BGL_EINVAL, "num_train must be in [1, num_nodes]");
+    if (!train_nodes) BGL_FAIL(BGL_EINVAL, "train_nodes is null");
+    return BGL_OK;
+}
+
+}  // namespace
+
+extern "C" int bgl_order_bfs_sequence(const bgl_graph_t *g, const int32_t *train_nodes, int64_t num_train,
+                                      int64_t root, int32_t *seq, void *stream)
+{
+    int rc = check_order_args(g, train_nodes, num_train);
+    if (rc != BGL_OK) return rc;
+    if (root < 0 || root >= g->num_nodes) BGL_FAIL(BGL_EINVAL, "root is outside [0, num_nodes)");
+    if (!seq) BGL_FAIL(BGL_EINVAL, "seq is null");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    OrderWork w;
+    if ((rc = prepare(g, train_nodes, num_train, w, st)) != BGL_OK) return rc;
+    rc = g->bits == 64 ? bfs_sequence<int64_t>(g, root, num_train, w, st) : bfs_sequence<int32_t>(g, root, num_train, w, st);
+    if (rc != BGL_OK) return rc;
+    BGL_HIP(hipMemcpyAsync(seq, w.seq, num_train * 4, hipMemcpyDeviceToHost, st));
+    BGL_HIP(hipStreamSynchronize(st));
+    return BGL_OK;
+}
+
+extern "C" int bgl_order_proximity(const bgl_graph_t *g, const int32_t *train_nodes, int64_t num_train,
+                                   int32_t num_sequences, const int64_t *roots, const int64_t *shifts,
+                                   int64_t num_out, int32_t *order, void *stream)
+{
+    int rc = check_order_args(g, train_nodes, num_train);
+    if (rc != BGL_OK) return rc;
+    if (num_sequences < 1 || !roots || !shifts) BGL_FAIL(BGL_EINVAL, "need at least one sequence with a root and a shift");
+    if (num_out < 0 || num_out > num_train) BGL_FAIL(BGL_EINVAL, "num_out must be in [0, num_train]");
+    if (num_out > 0 && !order) BGL_FAIL(BGL_EINVAL, "order is null");
+    for (int j = 0; j < num_sequences; ++j) {
+        if (roots[j] < 0 || roots[j] >= g->num_nodes) BGL_FAIL(BGL_EINVAL, "roots[%d] is outside [0, num_nodes)", j);
+        if (shifts[j] < 0 || shifts[j] >= num_train) BGL_FAIL(BGL_EINVAL, "shifts[%d] is outside [0, num_train)", j);
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    OrderWork w;
+    if ((rc = prepare(g, train_nodes, num_train, w, st)) != BGL_OK) return rc;
+    std::vector<std::vector<int32_t>> seqs((size_t)num_sequences);
+    for (int j = 0; j < num_sequences; ++j) {
+        rc = g->bits == 64 ? bfs_sequence<int64_t>(g, roots[j], num_train, w, st)
+                           : bfs_sequence<int32_t>(g, roots[j], num_train, w, st);
+        if (rc != BGL_OK) return rc;
+        seqs[(size_t)j].resize((size_t)num_train);
+        BGL_HIP(hipMemcpyAsync(seqs[(size_t)j].data(), w.seq, num_train * 4, hipMemcpyDeviceToHost, st));
+        BGL_HIP(hipStreamSynchronize(st));
+    }
+    // merge: turn t takes the next node of sequence t mod S that no earlier turn has taken
+    std::vector<uint8_t> used((size_t)g->num_nodes, 0);
+    std::vector<int64_t> cursor((size_t)num_sequences, 0);
+    for (int64_t k = 0, turn = 0; k < num_out; ++k, ++turn) {
+        const size_t j = (size_t)(turn % num_sequences);
+        int32_t v;
+        do {
+            v = seqs[j][(size_t)((shifts[j] + cursor[j]) % num_train)];
+            cursor[j] += 1;
+        } while (used[(size_t)v]);
+        used[(size_t)v] = 1;
+        order[k] = v;
+    }
+    return BGL_OK;
+}
+
+extern "C" int bgl_order_shuffling_error(const int32_t *order, int64_t n, int32_t batch, const int32_t *labels,
+                                         int64_t num_nodes, int32_t num_classes, double *mean_tv, double *max_tv)
+{
+    if (!order || !labels || !mean_tv || !max_tv) BGL_FAIL(BGL_EINVAL, "null argument");
+    if (n < 1 || batch < 1 || num_classes < 1 || num_nodes < 1) BGL_FAIL(BGL_EINVAL, "sizes must be positive");
+    std::vector<int64_t> global((size_t)num_classes, 0), local((size_t)num_classes);
+    for (int64_t i = 0; i < n; ++i) {
+        if (order[i] < 0 || order[i] >= num_nodes) BGL_FAIL(BGL_EINVAL, "order[%lld] is not a node id", (long long)i);
+        const int32_t c = labels[order[i]];
+        if (c < 0 || c >= num_classes) BGL_FAIL(BGL_EINVAL, "label of node %d is outside [0, num_classes)", order[i]);
+        global[(size_t)c] += 1;
+    }
+    double sum = 0.0, mx = 0.0;
+    int64_t batches = 0;
+    for (int64_t s = 0; s < n; s += batch, ++batches) {
+        const int64_t e = std::min<int64_t>(s + batch, n);
+        std::fill(local.begin(), local.end(), 0);
+        for (int64_t i = s; i < e; ++i) local[(size_t)labels[order[i]]] += 1;
+        double tv = 0.0;
+        for (int32_t c = 0; c < num_classes; ++c) {
+            const double pb = (double)local[(size_t)c] / (double)(e - s), pg = (double)global[(size_t)c] / (double)n;
+            tv += 0.5 * (pb > pg ? pb - pg : pg - pb);
+        }
+        sum += tv;
+        mx = std::max(mx, tv);
+    }
+    *mean_tv = sum / (double)batches;
+    *max_tv = mx;
+    return BGL_OK;
+}
