@@ -283,6 +283,26 @@ int bgl_order_proximity(const bgl_graph_t *g, const int32_t *train_nodes, int64_
                         int64_t num_out, int32_t *order, void *stream);
 
 /*
+ * Number of BFS sequences (Sec. 3.2.2: "gradually increases the number of
+ * sequences from one until the shuffling error is smaller than the requirement").
+ * Computes max_sequences BFS sequences once, then for s = 1, 2, ... merges the
+ * first s of them and measures the mean shuffling error of the merged order over
+ * batches of `batch`; stops at the first s whose error is <= threshold (the
+ * caller's bound, e.g. sqrt(b*M)/n), or at max_sequences.
+ *   chosen               host, receives s
+ *   mean_tv_per_count    optional host array of max_sequences doubles: the error
+ *                        for every count that was tried (entries after `chosen`
+ *                        are left untouched)
+ *   order                host, num_train ids: the merged order for `chosen`
+ * Synchronous.  Errors as bgl_order_proximity and bgl_order_shuffling_error.
+ */
+int bgl_order_choose_sequences(const bgl_graph_t *g, const int32_t *train_nodes, int64_t num_train,
+                               int32_t max_sequences, const int64_t *roots, const int64_t *shifts,
+                               int32_t batch, const int32_t *labels, int32_t num_classes,
+                               double threshold, int32_t *chosen, double *mean_tv_per_count,
+                               int32_t *order, void *stream);
+
+/*
  * Shuffling error of an order (Sec. 3.2.2, the quantity compared with
  * sqrt(b*M)/n to choose the number of sequences): total variation distance
  * between the label distribution of a batch and the label distribution of all

@@ -31,7 +31,8 @@ EXPORTS = [
     "bgl_sample_khop", "bgl_cache_create", "bgl_cache_destroy", "bgl_cache_lookup_gather",
     "bgl_cache_insert_fifo", "bgl_cache_wait_rows", "bgl_cache_export_state", "bgl_cache_stats",
     "bgl_cache_set_profiling", "bgl_cache_profile",
-    "bgl_order_bfs_sequence", "bgl_order_proximity", "bgl_order_shuffling_error",
+    "bgl_order_bfs_sequence", "bgl_order_proximity", "bgl_order_choose_sequences",
+    "bgl_order_shuffling_error",
 ]
 
 
@@ -77,6 +78,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     L.bgl_cache_profile.argtypes = [vp, ci, C.POINTER(C.c_double), C.POINTER(i64)]
     L.bgl_order_bfs_sequence.argtypes = [vp, vp, i64, i64, vp, vp]
     L.bgl_order_proximity.argtypes = [vp, vp, i64, i32, vp, vp, i64, vp, vp]
+    L.bgl_order_choose_sequences.argtypes = [vp, vp, i64, i32, vp, vp, i32, vp, i32, C.c_double,
+                                             C.POINTER(i32), vp, vp, vp]
     L.bgl_order_shuffling_error.argtypes = [vp, i64, i32, vp, i64, i32, C.POINTER(C.c_double),
                                             C.POINTER(C.c_double)]
     for name in EXPORTS:
@@ -343,3 +346,23 @@ def order_shuffling_error(order, batch: int, labels, num_classes: int):
     _check(lib().bgl_order_shuffling_error(order.ctypes.data, len(order), int(batch), labels.ctypes.data,
                                            len(labels), int(num_classes), C.byref(a), C.byref(b)))
     return a.value, b.value
+
+
+def order_choose_sequences(graph: Graph, train_nodes, roots, shifts, batch: int, labels,
+                           num_classes: int, threshold: float, stream=None):
+    """bgl_order_choose_sequences: (chosen count, errors per tried count, merged order)."""
+    train = np.ascontiguousarray(train_nodes, dtype=np.int32)
+    roots = np.ascontiguousarray(roots, dtype=np.int64)
+    shifts = np.ascontiguousarray(shifts, dtype=np.int64)
+    labels = np.ascontiguousarray(labels, dtype=np.int32)
+    if len(labels) != graph.num_nodes:
+        raise ValueError("one label per node")
+    chosen = C.c_int32(0)
+    errs = np.full(len(roots), np.nan)
+    order = np.empty(len(train), dtype=np.int32)
+    _check(lib().bgl_order_choose_sequences(graph._h, train.ctypes.data, len(train), len(roots),
+                                            roots.ctypes.data, shifts.ctypes.data, int(batch),
+                                            labels.ctypes.data, int(num_classes), float(threshold),
+                                            C.byref(chosen), errs.ctypes.data, order.ctypes.data,
+                                            _stream_handle(stream)))
+    return chosen.value, errs[: chosen.value].copy(), order

@@ -302,23 +302,28 @@ extern "C" int bgl_order_bfs_sequence(const bgl_graph_t *g, const int32_t *train
     return BGL_OK;
 }
 
-extern "C" int bgl_order_proximity(const bgl_graph_t *g, const int32_t *train_nodes, int64_t num_train,
-                                   int32_t num_sequences, const int64_t *roots, const int64_t *shifts,
-                                   int64_t num_out, int32_t *order, void *stream)
+namespace {
+
+int check_proximity_args(const bgl_graph_t *g, const int32_t *train_nodes, int64_t num_train,
+                         int32_t num_sequences, const int64_t *roots, const int64_t *shifts)
 {
     int rc = check_order_args(g, train_nodes, num_train);
     if (rc != BGL_OK) return rc;
     if (num_sequences < 1 || !roots || !shifts) BGL_FAIL(BGL_EINVAL, "need at least one sequence with a root and a shift");
-    if (num_out < 0 || num_out > num_train) BGL_FAIL(BGL_EINVAL, "num_out must be in [0, num_train]");
-    if (num_out > 0 && !order) BGL_FAIL(BGL_EINVAL, "order is null");
     for (int j = 0; j < num_sequences; ++j) {
         if (roots[j] < 0 || roots[j] >= g->num_nodes) BGL_FAIL(BGL_EINVAL, "roots[%d] is outside [0, num_nodes)", j);
         if (shifts[j] < 0 || shifts[j] >= num_train) BGL_FAIL(BGL_EINVAL, "shifts[%d] is outside [0, num_train)", j);
     }
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    return BGL_OK;
+}
+
+int compute_sequences(const bgl_graph_t *g, const int32_t *train_nodes, int64_t num_train, int32_t num_sequences,
+                      const int64_t *roots, hipStream_t st, std::vector<std::vector<int32_t>> &seqs)
+{
     OrderWork w;
-    if ((rc = prepare(g, train_nodes, num_train, w, st)) != BGL_OK) return rc;
-    std::vector<std::vector<int32_t>> seqs((size_t)num_sequences);
+    int rc = prepare(g, train_nodes, num_train, w, st);
+    if (rc != BGL_OK) return rc;
+    seqs.assign((size_t)num_sequences, std::vector<int32_t>());
     for (int j = 0; j < num_sequences; ++j) {
         rc = g->bits == 64 ? bfs_sequence<int64_t>(g, roots[j], num_train, w, st)
                            : bfs_sequence<int32_t>(g, roots[j], num_train, w, st);
@@ -327,8 +332,14 @@ extern "C" int bgl_order_proximity(const bgl_graph_t *g, const int32_t *train_no
         BGL_HIP(hipMemcpyAsync(seqs[(size_t)j].data(), w.seq, num_train * 4, hipMemcpyDeviceToHost, st));
         BGL_HIP(hipStreamSynchronize(st));
     }
-    // merge: turn t takes the next node of sequence t mod S that no earlier turn has taken
-    std::vector<uint8_t> used((size_t)g->num_nodes, 0);
+    return BGL_OK;
+}
+
+// turn t takes the next node of sequence t mod S that no earlier turn has taken
+void merge_sequences(const std::vector<std::vector<int32_t>> &seqs, int32_t num_sequences, const int64_t *shifts,
+                     int64_t num_train, int64_t num_nodes, int64_t num_out, int32_t *order)
+{
+    std::vector<uint8_t> used((size_t)num_nodes, 0);
     std::vector<int64_t> cursor((size_t)num_sequences, 0);
     for (int64_t k = 0, turn = 0; k < num_out; ++k, ++turn) {
         const size_t j = (size_t)(turn % num_sequences);
@@ -339,6 +350,46 @@ extern "C" int bgl_order_proximity(const bgl_graph_t *g, const int32_t *train_no
         } while (used[(size_t)v]);
         used[(size_t)v] = 1;
         order[k] = v;
+    }
+}
+
+}  // namespace
+
+extern "C" int bgl_order_proximity(const bgl_graph_t *g, const int32_t *train_nodes, int64_t num_train,
+                                   int32_t num_sequences, const int64_t *roots, const int64_t *shifts,
+                                   int64_t num_out, int32_t *order, void *stream)
+{
+    int rc = check_proximity_args(g, train_nodes, num_train, num_sequences, roots, shifts);
+    if (rc != BGL_OK) return rc;
+    if (num_out < 0 || num_out > num_train) BGL_FAIL(BGL_EINVAL, "num_out must be in [0, num_train]");
+    if (num_out > 0 && !order) BGL_FAIL(BGL_EINVAL, "order is null");
+    std::vector<std::vector<int32_t>> seqs;
+    rc = compute_sequences(g, train_nodes, num_train, num_sequences, roots, static_cast<hipStream_t>(stream), seqs);
+    if (rc != BGL_OK) return rc;
+    merge_sequences(seqs, num_sequences, shifts, num_train, g->num_nodes, num_out, order);
+    return BGL_OK;
+}
+
+extern "C" int bgl_order_choose_sequences(const bgl_graph_t *g, const int32_t *train_nodes, int64_t num_train,
+                                          int32_t max_sequences, const int64_t *roots, const int64_t *shifts,
+                                          int32_t batch, const int32_t *labels, int32_t num_classes,
+                                          double threshold, int32_t *chosen, double *mean_tv_per_count,
+                                          int32_t *order, void *stream)
+{
+    int rc = check_proximity_args(g, train_nodes, num_train, max_sequences, roots, shifts);
+    if (rc != BGL_OK) return rc;
+    if (!labels || !chosen || !order) BGL_FAIL(BGL_EINVAL, "labels, chosen and order must not be null");
+    std::vector<std::vector<int32_t>> seqs;
+    rc = compute_sequences(g, train_nodes, num_train, max_sequences, roots, static_cast<hipStream_t>(stream), seqs);
+    if (rc != BGL_OK) return rc;
+    for (int32_t s = 1; s <= max_sequences; ++s) {
+        merge_sequences(seqs, s, shifts, num_train, g->num_nodes, num_train, order);
+        double mean_tv = 0.0, max_tv = 0.0;
+        rc = bgl_order_shuffling_error(order, num_train, batch, labels, g->num_nodes, num_classes, &mean_tv, &max_tv);
+        if (rc != BGL_OK) return rc;
+        if (mean_tv_per_count) mean_tv_per_count[s - 1] = mean_tv;
+        *chosen = s;
+        if (mean_tv <= threshold) break;   // `order` holds the order for this count
     }
     return BGL_OK;
 }

@@ -122,3 +122,27 @@ def test_host_pinned_graph_and_errors(B):
         B.order_bfs_sequence(g, [1, 2], 3000)         # bad root
     with pytest.raises(B.BglError):
         B.order_proximity(g, [1, 2, 3], [0], [3], 3)  # shift out of range
+
+
+def test_choose_sequences_matches_a_loop_over_the_oracle(B):
+    import oracle
+    rng = np.random.default_rng(12)
+    N = 20000
+    rp, col = random_graph(rng, N, 6)
+    # labels follow the generation order of ids, so BFS from one root gives skewed batches
+    labels = (np.arange(N) * 5 // N).astype(np.int32)
+    train = rng.choice(N, 4000, replace=False).astype(np.int32)
+    roots = rng.integers(0, N, 6)
+    shifts = rng.integers(0, len(train), 6)
+    g = B.Graph(rp, col)
+    want_errs = []
+    for s in range(1, 7):
+        o = oracle.proximity_order(rp, col, train, roots[:s], shifts[:s], len(train))
+        want_errs.append(oracle.shuffling_error(o, 100, labels, 5)[0])
+    for threshold in (0.0, sorted(want_errs)[2], 1.0):
+        chosen, errs, order = B.order_choose_sequences(g, train, roots, shifts, 100, labels, 5, threshold)
+        expect = next((s for s in range(1, 7) if want_errs[s - 1] <= threshold), 6)
+        assert chosen == expect
+        assert np.allclose(errs, want_errs[:chosen], rtol=0, atol=1e-12)
+        want = oracle.proximity_order(rp, col, train, roots[:chosen], shifts[:chosen], len(train))
+        assert np.array_equal(order, want)
