@@ -304,16 +304,10 @@ void bglo_cache_stats(const bglo_cache *c, uint64_t *lookups, uint64_t *hits)
  * from several roots, each sequence rotated by a random offset, batches filled
  * from the sequences in turn.  The random roots and offsets are inputs.
  *
- * Canonical BFS order (the paper only says "BFS order"): nodes are visited level
- * by level; inside a level in increasing node id; when a traversal is exhausted
- * it restarts at the smallest node id not visited yet (small components end up
- * at the end of the sequence, as Sec. 3.2.2 observes).  Only training nodes are
- * recorded. */
-static int cmp_i32(const void *a, const void *b)
-{
-    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
-    return (x > y) - (x < y);
-}
+ * BFS order: the textbook first-in-first-out queue traversal, the neighbors of a
+ * node taken in CSR row order; when a traversal is exhausted it restarts at the
+ * smallest node id not visited yet (small components end up at the end of the
+ * sequence, as Sec. 3.2.2 observes).  Only training nodes are recorded. */
 
 /* Returns the number of training nodes recorded in seq, or -1 on bad arguments. */
 int64_t bglo_bfs_sequence(const void *row_ptr, int row_ptr_bits, const int32_t *col,
@@ -322,37 +316,28 @@ int64_t bglo_bfs_sequence(const void *row_ptr, int row_ptr_bits, const int32_t *
 {
     if (num_nodes <= 0 || root < 0 || root >= num_nodes) return -1;
     uint8_t *seen = (uint8_t *)calloc((size_t)num_nodes, 1);
-    int32_t *cur = (int32_t *)malloc(sizeof(int32_t) * (size_t)num_nodes);
-    int32_t *nxt = (int32_t *)malloc(sizeof(int32_t) * (size_t)num_nodes);
-    if (!seen || !cur || !nxt) { free(seen); free(cur); free(nxt); return -1; }
-    int64_t n_out = 0, n_seen = 0, scan = 0;
+    int32_t *queue = (int32_t *)malloc(sizeof(int32_t) * (size_t)num_nodes);
+    if (!seen || !queue) { free(seen); free(queue); return -1; }
+    int64_t head = 0, tail = 0, n_out = 0, scan = 0;
     int64_t start = root;
-    while (n_seen < num_nodes) {
-        int64_t n_cur = 1;
-        cur[0] = (int32_t)start;
+    for (;;) {
         seen[start] = 1;
-        while (n_cur > 0) {
-            n_seen += n_cur;
-            for (int64_t i = 0; i < n_cur; ++i)          /* the level, in id order */
-                if (is_train[cur[i]]) seq[n_out++] = cur[i];
-            int64_t n_nxt = 0;
-            for (int64_t i = 0; i < n_cur; ++i) {
-                int64_t lo = rp_at(row_ptr, row_ptr_bits, cur[i]);
-                int64_t hi = rp_at(row_ptr, row_ptr_bits, (int64_t)cur[i] + 1);
-                for (int64_t e = lo; e < hi; ++e) {
-                    int32_t u = col[e];
-                    if (!seen[u]) { seen[u] = 1; nxt[n_nxt++] = u; }
-                }
+        queue[tail++] = (int32_t)start;
+        while (head < tail) {
+            int32_t v = queue[head++];
+            if (is_train[v]) seq[n_out++] = v;
+            int64_t lo = rp_at(row_ptr, row_ptr_bits, v);
+            int64_t hi = rp_at(row_ptr, row_ptr_bits, (int64_t)v + 1);
+            for (int64_t e = lo; e < hi; ++e) {
+                int32_t u = col[e];
+                if (!seen[u]) { seen[u] = 1; queue[tail++] = u; }
             }
-            qsort(nxt, (size_t)n_nxt, sizeof(int32_t), cmp_i32);
-            int32_t *t = cur; cur = nxt; nxt = t;
-            n_cur = n_nxt;
         }
         while (scan < num_nodes && seen[scan]) ++scan;   /* smallest unvisited id */
         if (scan >= num_nodes) break;
         start = scan;
     }
-    free(seen); free(cur); free(nxt);
+    free(seen); free(queue);
     return n_out;
 }
 

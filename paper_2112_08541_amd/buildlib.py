@@ -51,8 +51,9 @@ def build_hip(verbose: bool = False) -> str:
 
 
 def build_all(verbose: bool = False) -> None:
-    from . import inputs
+    from . import inputs, policy_study
     inputs.build(force=True)
+    policy_study.build(force=True)
     build_hip(verbose)
 
 

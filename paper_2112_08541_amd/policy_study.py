@@ -1,0 +1,154 @@
+"""Hit ratio against cache size for the policies the paper compares (Sec. 2.3,
+Sec. 3.2.1, Sec. 3.2.2): static degree-based, LRU, LFU (host simulators in
+csrc/policy_sim.c) and FIFO with random and with proximity-aware seed order (the
+library's GPU cache).  Streams of input nodes come from the library's GPU
+sampler on a synthetic workload.
+
+    python -m paper_2112_08541_amd.policy_study [--config mid] [--batches 200]
+
+Prints a markdown table.  An analysis tool, not part of the minibatch path.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import os
+import subprocess
+import time
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "csrc", "policy_sim.c")
+_LIB = os.path.join(_HERE, "libbgl_policy.so")
+KINDS = {"static": 0, "lru": 1, "lfu": 2}
+
+
+def build(force: bool = False) -> str:
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-o", _LIB, _SRC])
+    return _LIB
+
+
+_lib = None
+
+
+def _sim():
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_LIB)
+        L.psim_create.restype = C.c_void_p
+        L.psim_create.argtypes = [C.c_int, C.c_int64, C.c_int64]
+        L.psim_destroy.argtypes = [C.c_void_p]
+        L.psim_static_fill.argtypes = [C.c_void_p, C.c_void_p, C.c_int64]
+        L.psim_batch.restype = C.c_int64
+        L.psim_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_int64]
+        _lib = L
+    return _lib
+
+
+class PolicySim:
+    """One simulated cache: kind in {"static", "lru", "lfu"}."""
+
+    def __init__(self, kind: str, num_nodes: int, capacity: int, hottest=None):
+        self._h = _sim().psim_create(KINDS[kind], num_nodes, capacity)
+        if kind == "static":
+            hot = np.ascontiguousarray(hottest[:capacity], dtype=np.int32)
+            _sim().psim_static_fill(self._h, hot.ctypes.data, len(hot))
+
+    def batch(self, ids: np.ndarray) -> int:
+        ids = np.ascontiguousarray(ids, dtype=np.int32)
+        return int(_sim().psim_batch(self._h, ids.ctypes.data, len(ids)))
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.psim_destroy(self._h)
+            self._h = None
+
+
+def sample_streams(graph, cfg, seed_batches, rng_seeds):
+    """Input-node lists of every batch, sampled on the GPU."""
+    import torch
+    from . import binding as B
+    smp = B.Sampler(graph, cfg.batch, cfg.fanouts)
+    seeds_dev = torch.from_numpy(np.ascontiguousarray(seed_batches)).cuda()
+    K = len(cfg.fanouts)
+    out = []
+    for b in range(seed_batches.shape[0]):
+        sb = smp.sample(seeds_dev[b], int(rng_seeds[b]))
+        torch.cuda.current_stream().synchronize()
+        n = int(smp.counts_host[K])
+        out.append(sb.input_nodes(n).cpu().numpy())
+    return out
+
+
+def gpu_fifo_hit_ratio(streams, num_nodes, capacity):
+    """The library's FIFO cache (16-byte dummy rows: only hits are counted)."""
+    import torch
+    from . import binding as B
+    feats = torch.zeros((num_nodes, 16), dtype=torch.uint8, device="cuda")
+    cache = B.Cache(capacity, feats, num_nodes=num_nodes, row_bytes=16)
+    cap = max(len(s) for s in streams)
+    out_rows = torch.empty((cap, 16), dtype=torch.uint8, device="cuda")
+    out_slot = torch.empty(cap, dtype=torch.int32, device="cuda")
+    miss_pos = torch.empty(cap, dtype=torch.int32, device="cuda")
+    for s in streams:
+        ids = torch.from_numpy(s).cuda()
+        cache.lookup_gather(ids, len(s), out_rows, out_slot, miss_pos)
+        cache.insert_fifo(ids, miss_pos, -1, out_rows)
+    st = cache.stats()
+    cache.close()
+    return st["hits"] / max(st["lookups"], 1)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", default="mid")
+    ap.add_argument("--batches", type=int, default=200)
+    ap.add_argument("--fractions", default="0.025,0.05,0.1,0.2,0.4")
+    ap.add_argument("--nodes", type=int, default=0, help="run the configuration's shape at this node count")
+    args = ap.parse_args()
+    import torch
+    from . import binding as B
+    from . import inputs
+    cfg = inputs.CONFIGS[args.config]
+    if args.nodes:
+        cfg = inputs.scaled(cfg, args.nodes)
+    t0 = time.time()
+    row_ptr, col, _keep = inputs.make_graph(cfg)          # no feature table: only ids matter here
+    N = cfg.num_nodes
+    graph = B.Graph(row_ptr, col)
+    nb = min(args.batches, cfg.num_batches)
+    rng = np.random.default_rng(cfg.seed + 7)
+    train = rng.choice(N, max(cfg.train_size, nb * cfg.batch), replace=False).astype(np.int32)
+    rng_seeds = rng.integers(0, 2**64, size=nb, dtype=np.uint64)
+    roots = rng.integers(0, N, cfg.po_sequences)
+    shifts = rng.integers(0, len(train), cfg.po_sequences)
+    po = B.order_proximity(graph, train, roots, shifts, nb * cfg.batch).reshape(nb, cfg.batch)
+    rnd = rng.permutation(train)[: nb * cfg.batch].reshape(nb, cfg.batch).astype(np.int32)
+    streams = {"random": sample_streams(graph, cfg, rnd, rng_seeds),
+               "po": sample_streams(graph, cfg, po, rng_seeds)}
+    hottest = np.argsort(-np.bincount(col, minlength=N), kind="stable").astype(np.int32)
+    total = {k: sum(len(s) for s in v) for k, v in streams.items()}
+    print(f"# Cache policy study on the `{cfg.name}` workload ({nb} batches, "
+          f"{total['random'] / nb:.0f} input nodes per batch; generated in {time.time() - t0:.0f} s)\n")
+    print("| cache size (fraction of nodes) | static (in-degree) | LRU | LFU | FIFO, random order | "
+          "FIFO, proximity-aware order | LRU, proximity-aware order |")
+    print("|---|---|---|---|---|---|---|")
+    for frac in [float(x) for x in args.fractions.split(",")]:
+        cap = max(1, int(round(frac * N)))
+        row = []
+        for kind in ("static", "lru", "lfu"):
+            sim = PolicySim(kind, N, cap, hottest)
+            row.append(sum(sim.batch(s) for s in streams["random"]) / total["random"])
+        row.append(gpu_fifo_hit_ratio(streams["random"], N, cap))
+        row.append(gpu_fifo_hit_ratio(streams["po"], N, cap))
+        sim = PolicySim("lru", N, cap)
+        row.append(sum(sim.batch(s) for s in streams["po"]) / total["po"])
+        print(f"| {frac:.3f} ({cap} rows) | " + " | ".join(f"{x:.3f}" for x in row) + " |")
+    torch.cuda.synchronize()
+
+
+if __name__ == "__main__":
+    main()

@@ -6,12 +6,14 @@ import os
 import numpy as np
 import pytest
 import scipy.sparse as sp
-from scipy.sparse.csgraph import shortest_path
+from scipy.sparse.csgraph import breadth_first_order
 
 import oracle
 
 RP = np.array([0, 2, 3, 3, 4, 5, 5], dtype=np.int32)
 COL = np.array([1, 2, 3, 0, 5], dtype=np.int32)
+RP2 = np.array([0, 2, 3, 3, 5, 5], dtype=np.int32)     # 0->{3,1}, 1->{2}, 2->{}, 3->{4,2}, 4->{}
+COL2 = np.array([3, 1, 2, 4, 2], dtype=np.int32)
 
 
 def test_hand_worked_example(golden_dir):
@@ -19,8 +21,9 @@ def test_hand_worked_example(golden_dir):
         if line.startswith("#") or not line.strip():
             continue
         parts = [p.split() for p in line.split("|")]
-        if parts[0][0] == "bfs":
-            got = oracle.bfs_sequence(RP, COL, [int(x) for x in parts[1]], int(parts[0][1]))
+        if parts[0][0] in ("bfs", "bfs2"):
+            rp, col = (RP, COL) if parts[0][0] == "bfs" else (RP2, COL2)
+            got = oracle.bfs_sequence(rp, col, [int(x) for x in parts[1]], int(parts[0][1]))
             assert got.tolist() == [int(x) for x in parts[2]]
         else:
             roots = [int(x) for x in parts[0][2:]]
@@ -38,35 +41,28 @@ def random_graph(rng, N, max_deg):
 
 
 @pytest.mark.parametrize("seed", range(6))
-def test_bfs_sequence_levels_match_scipy_shortest_paths(seed):
-    """Independent check of the order: split the sequence into traversal runs (a new run starts
-    at the smallest node not reached so far); inside a run the distance from the run's root,
-    computed by scipy on the graph without the earlier runs' nodes, never decreases, and ids
-    ascend among equal distances."""
+def test_bfs_sequence_equals_scipy_breadth_first_order_run_by_run(seed):
+    """Library special case: each traversal run must be scipy's breadth_first_order (the
+    FIFO-queue traversal over CSR rows) from the run's root on the graph without the nodes
+    of earlier runs; a new run starts at the smallest node not reached so far."""
     rng = np.random.default_rng(seed)
     N = int(rng.integers(30, 200))
     rp, col = random_graph(rng, N, 4)
     root = int(rng.integers(0, N))
     seq = oracle.bfs_sequence(rp, col, np.arange(N), root).tolist()
     assert sorted(seq) == list(range(N))
-    A = sp.csr_matrix((np.ones(len(col)), col, rp), shape=(N, N))
     done = np.zeros(N, dtype=bool)
-    pos = 0
-    start = root
+    pos, start = 0, root
     while pos < N:
-        assert seq[pos] == start
-        keep = ~done
-        sub = A[keep][:, keep]
-        ids = np.nonzero(keep)[0]
-        d = shortest_path(sub, directed=True, unweighted=True, indices=int(np.searchsorted(ids, start)))
-        reach = ids[np.isfinite(d)]
-        dist = {int(v): int(x) for v, x in zip(ids, d) if np.isfinite(x)}
-        run = seq[pos: pos + len(reach)]
-        assert sorted(run) == sorted(reach.tolist())
-        keys = [(dist[v], v) for v in run]
-        assert keys == sorted(keys)
-        done[reach] = True
-        pos += len(reach)
+        # drop edges into nodes of earlier runs, keep row order, keep node numbering
+        keep_e = ~done[col]
+        rows = np.repeat(np.arange(N), np.diff(rp))
+        rp2 = np.concatenate([[0], np.cumsum(np.bincount(rows[keep_e], minlength=N))]).astype(np.int32)
+        A = sp.csr_matrix((np.ones(int(keep_e.sum())), col[keep_e], rp2), shape=(N, N))
+        run = breadth_first_order(A, start, directed=True, return_predecessors=False).tolist()
+        assert seq[pos: pos + len(run)] == run
+        done[run] = True
+        pos += len(run)
         if pos < N:
             start = int(np.nonzero(~done)[0][0])
 
