@@ -4,29 +4,36 @@
 // the merge (a strictly sequential scan over a few hundred thousand ids) and the
 // shuffling-error statistic run on the host.
 //
-// Canonical BFS order: level by level, ids ascending inside a level, restart at
-// the smallest id not visited yet.  A level-synchronous bitmap BFS gives exactly
-// that: the next level is a bitmap, and compacting a bitmap yields ids in
-// ascending order for free.  Per level: expand (16 lanes walk one frontier
-// node's row, test-and-set the visited bitmap), then count / scan / write to turn
-// the next-level bitmap into the sorted frontier list and to append its training
-// nodes to the sequence.  Restarts: nodes all of whose out-neighbors are visited
-// ("closed") would each be a one-node traversal; all closed nodes below the
-// smallest open node are taken in one step, which is the same order.
+// BFS order is the first-in-first-out queue order (neighbors in CSR row order,
+// restart at the smallest unvisited id).  The queue order of a level is fixed by
+// the previous one: a node's place is given by the first (rank of the parent in
+// its level, edge position in the parent's row) that reaches it.  So a
+// level-synchronous traversal reproduces it exactly: expand (16 lanes walk one
+// frontier node's row; atomicMin of that 64-bit key per newly seen neighbor, and
+// a bit in the next-level bitmap), compact the bitmap to a candidate list, sort
+// the candidates by key (rocPRIM radix sort, a plain library primitive), append
+// the level's training nodes to the sequence.  Restarts: nodes all of whose
+// out-neighbors are visited ("closed") would each be a one-node traversal; all
+// closed nodes below the smallest open node are taken in one step, in id order,
+// which is what the sequential rule does.
 #include <algorithm>
 #include <climits>
+#include <cstring>
 #include <vector>
 
 #include "bgl_internal.h"
+
+#include <rocprim/rocprim.hpp>
 
 namespace {
 
 using namespace bgl;
 
 constexpr int BT = 256;
+constexpr uint64_t NO_KEY = ~0ull;
 
 struct OrderDev {
-    int fsize;      // size of the frontier the last compaction wrote
+    int fsize;      // size of the list the last bitmap compaction wrote
     int seq_len;    // training nodes recorded so far
     int open_min;   // smallest unvisited node that has an unvisited out-neighbor
     int status;
@@ -39,6 +46,13 @@ __global__ void k_fill_u32(uint32_t *p, int64_t n, uint32_t v)
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (; i < n; i += stride) p[i] = v;
+}
+
+__global__ void k_fill_key(uint64_t *p, int64_t n)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = NO_KEY;
 }
 
 __global__ void k_set_bits(const int32_t *ids, int64_t n, int64_t num_nodes, uint32_t *bm, OrderDev *dev)
@@ -77,11 +91,13 @@ __global__ void k_start_at(int32_t node, uint32_t *visited, const uint32_t *trai
     dev->open_min = INT_MAX;
 }
 
-// 16 lanes per frontier node walk its row; a neighbor seen for the first time goes into `next`.
+// 16 lanes per frontier node walk its row.  `visited` holds the earlier levels
+// only; a neighbor outside it gets the smallest (parent rank, edge position) key
+// of this level and a bit in `next`.
 template <typename RP>
 __global__ __launch_bounds__(BT) void k_expand(const RP *__restrict__ row_ptr, const int32_t *__restrict__ col,
                                                const int32_t *__restrict__ frontier, int fsize,
-                                               uint32_t *visited, uint32_t *next)
+                                               const uint32_t *__restrict__ visited, uint32_t *next, uint64_t *key)
 {
     const int64_t g = ((int64_t)blockIdx.x * BT + threadIdx.x) >> 4;
     const int l = threadIdx.x & 15;
@@ -91,64 +107,86 @@ __global__ __launch_bounds__(BT) void k_expand(const RP *__restrict__ row_ptr, c
     for (int64_t e = lo + l; e < hi; e += 16) {
         const uint32_t u = (uint32_t)col[e];
         const uint32_t bit = 1u << (u & 31);
-        if (!(visited[u >> 5] & bit)) {
-            const uint32_t old = atomicOr(&visited[u >> 5], bit);
-            if (!(old & bit)) atomicOr(&next[u >> 5], bit);
-        }
+        if (visited[u >> 5] & bit) continue;
+        const uint64_t k = ((uint64_t)g << 32) | (uint64_t)(e - lo);
+        if (__hip_atomic_load(&key[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) > k)
+            atomicMin((unsigned long long *)&key[u], (unsigned long long)k);
+        if (!(__hip_atomic_load(&next[u >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit))
+            atomicOr(&next[u >> 5], bit);
     }
 }
 
 // Bitmap -> ascending id list, three steps.  One bitmap word per lane.
-__global__ __launch_bounds__(BT) void k_bm_count(const uint32_t *__restrict__ next, const uint32_t *__restrict__ train,
-                                                 int64_t words, int32_t *bs_all, int32_t *bs_tr)
+__global__ __launch_bounds__(BT) void k_bm_count(const uint32_t *__restrict__ next, int64_t words, int32_t *bs)
 {
     __shared__ int sh[BT / kWave];
     const int64_t w = (int64_t)blockIdx.x * BT + threadIdx.x;
-    const uint32_t m = w < words ? next[w] : 0u;
-    const uint32_t t = w < words ? (m & train[w]) : 0u;
-    int ta, tt;
-    (void)block_excl_scan<BT>(__popc(m), sh, ta);
-    (void)block_excl_scan<BT>(__popc(t), sh, tt);
-    if (threadIdx.x == 0) { bs_all[blockIdx.x] = ta; bs_tr[blockIdx.x] = tt; }
+    int tot;
+    (void)block_excl_scan<BT>(w < words ? __popc(next[w]) : 0, sh, tot);
+    if (threadIdx.x == 0) bs[blockIdx.x] = tot;
 }
 
-__global__ __launch_bounds__(1024) void k_bm_scan(int32_t *bs_all, int32_t *bs_tr, int nb, OrderDev *dev,
-                                                  int32_t *seq_base)
+// Exclusive prefix of per-workgroup counts (in place); the total goes to
+// dev->fsize (to_seq = 0) or extends the sequence (to_seq = 1, base in *seq_base).
+__global__ __launch_bounds__(1024) void k_scan_counts(int32_t *bs, int nb, OrderDev *dev, int to_seq, int32_t *seq_base)
 {
     __shared__ int sh[1024 / kWave];
-    int ca = 0, ct = 0;
+    int carry = 0;
     for (int base = 0; base < nb; base += 1024) {
         const int i = base + threadIdx.x;
-        const int a = i < nb ? bs_all[i] : 0, t = i < nb ? bs_tr[i] : 0;
-        int ta, tt;
-        const int ea = block_excl_scan<1024>(a, sh, ta);
-        const int et = block_excl_scan<1024>(t, sh, tt);
-        if (i < nb) { bs_all[i] = ca + ea; bs_tr[i] = ct + et; }
-        ca += ta;
-        ct += tt;
+        int tot;
+        const int ex = block_excl_scan<1024>(i < nb ? bs[i] : 0, sh, tot);
+        if (i < nb) bs[i] = carry + ex;
+        carry += tot;
     }
     if (threadIdx.x == 0) {
-        dev->fsize = ca;
-        *seq_base = dev->seq_len;
-        dev->seq_len += ct;
+        if (to_seq) { *seq_base = dev->seq_len; dev->seq_len += carry; }
+        else dev->fsize = carry;
     }
 }
 
-__global__ __launch_bounds__(BT) void k_bm_write(uint32_t *next, const uint32_t *__restrict__ train, int64_t words,
-                                                 const int32_t *__restrict__ pre_all, const int32_t *__restrict__ pre_tr,
-                                                 const int32_t *__restrict__ seq_base, int32_t *frontier, int32_t *seq)
+__global__ __launch_bounds__(BT) void k_bm_write(uint32_t *next, uint32_t *visited, int64_t words,
+                                                 const int32_t *__restrict__ pre, int32_t *cand)
 {
     __shared__ int sh[BT / kWave];
     const int64_t w = (int64_t)blockIdx.x * BT + threadIdx.x;
     uint32_t m = w < words ? next[w] : 0u;
-    uint32_t t = w < words ? (m & train[w]) : 0u;
-    int ta, tt;
-    int oa = pre_all[blockIdx.x] + block_excl_scan<BT>(__popc(m), sh, ta);
-    int ot = *seq_base + pre_tr[blockIdx.x] + block_excl_scan<BT>(__popc(t), sh, tt);
-    if (m) next[w] = 0;
+    int tot;
+    int o = pre[blockIdx.x] + block_excl_scan<BT>(__popc(m), sh, tot);
+    if (m) { next[w] = 0; visited[w] |= m; }
     const int32_t base = (int32_t)(w * 32);
-    while (m) { frontier[oa++] = base + (__ffs(m) - 1); m &= m - 1; }
-    while (t) { seq[ot++] = base + (__ffs(t) - 1); t &= t - 1; }
+    while (m) { cand[o++] = base + (__ffs(m) - 1); m &= m - 1; }
+}
+
+__global__ __launch_bounds__(BT) void k_gather_keys(const int32_t *__restrict__ cand, int n,
+                                                    const uint64_t *__restrict__ key, uint64_t *out)
+{
+    const int i = blockIdx.x * BT + threadIdx.x;
+    if (i < n) out[i] = key[cand[i]];
+}
+
+// Append the training nodes of a list to the sequence, keeping the list's order.
+__global__ __launch_bounds__(BT) void k_list_count(const int32_t *__restrict__ list, int n,
+                                                   const uint32_t *__restrict__ train, int32_t *bs)
+{
+    __shared__ int sh[BT / kWave];
+    const int i = blockIdx.x * BT + threadIdx.x;
+    int tot;
+    (void)block_excl_scan<BT>((i < n && test_bit(train, (uint32_t)list[i])) ? 1 : 0, sh, tot);
+    if (threadIdx.x == 0) bs[blockIdx.x] = tot;
+}
+
+__global__ __launch_bounds__(BT) void k_list_write(const int32_t *__restrict__ list, int n,
+                                                   const uint32_t *__restrict__ train,
+                                                   const int32_t *__restrict__ pre,
+                                                   const int32_t *__restrict__ seq_base, int32_t *seq)
+{
+    __shared__ int sh[BT / kWave];
+    const int i = blockIdx.x * BT + threadIdx.x;
+    const int flag = (i < n && test_bit(train, (uint32_t)list[i])) ? 1 : 0;
+    int tot;
+    const int ex = block_excl_scan<BT>(flag, sh, tot);
+    if (flag) seq[*seq_base + pre[blockIdx.x] + ex] = list[i];
 }
 
 // Smallest unvisited node with an unvisited out-neighbor other than itself.
@@ -166,8 +204,9 @@ __global__ __launch_bounds__(BT) void k_open_min(const RP *__restrict__ row_ptr,
     }
 }
 
-// Every unvisited node below dev->open_min is closed: visit them all, in id order.
-__global__ __launch_bounds__(BT) void k_take_closed(uint32_t *visited, uint32_t *next, int64_t words, const OrderDev *dev)
+// Every unvisited node below dev->open_min is closed: mark them all for the next compaction.
+__global__ __launch_bounds__(BT) void k_take_closed(const uint32_t *__restrict__ visited, uint32_t *next,
+                                                    int64_t words, const OrderDev *dev)
 {
     const int64_t w = (int64_t)blockIdx.x * BT + threadIdx.x;
     if (w >= words) return;
@@ -176,19 +215,23 @@ __global__ __launch_bounds__(BT) void k_take_closed(uint32_t *visited, uint32_t 
     if (base >= limit) return;
     uint32_t free_bits = ~visited[w];
     if (limit < base + 32) free_bits &= (1u << (uint32_t)(limit - base)) - 1u;
-    if (free_bits) { visited[w] |= free_bits; next[w] = free_bits; }
+    if (free_bits) next[w] = free_bits;
 }
 
 struct OrderWork {
     uint32_t *visited = nullptr, *next = nullptr, *train = nullptr;
-    int32_t *frontier = nullptr, *seq = nullptr, *train_ids = nullptr, *bs_all = nullptr, *bs_tr = nullptr, *seq_base = nullptr;
+    int32_t *frontier = nullptr, *cand = nullptr, *seq = nullptr, *train_ids = nullptr, *bs = nullptr, *seq_base = nullptr;
+    uint64_t *key = nullptr, *keys_in = nullptr, *keys_out = nullptr;
+    void *sort_tmp = nullptr;
+    size_t sort_tmp_bytes = 0;
     OrderDev *dev = nullptr;
     OrderDev *host = nullptr;  // page-locked mirror
     ~OrderWork()
     {
         (void)hipFree(visited); (void)hipFree(next); (void)hipFree(train); (void)hipFree(frontier);
-        (void)hipFree(seq); (void)hipFree(train_ids); (void)hipFree(bs_all); (void)hipFree(bs_tr);
-        (void)hipFree(seq_base); (void)hipFree(dev);
+        (void)hipFree(cand); (void)hipFree(seq); (void)hipFree(train_ids); (void)hipFree(bs);
+        (void)hipFree(seq_base); (void)hipFree(key); (void)hipFree(keys_in); (void)hipFree(keys_out);
+        (void)hipFree(sort_tmp); (void)hipFree(dev);
         if (host) (void)hipHostFree(host);
     }
 };
@@ -203,18 +246,24 @@ int read_dev(OrderWork &w, hipStream_t st)
 int prepare(const bgl_graph *g, const int32_t *train_nodes, int64_t num_train, OrderWork &w, hipStream_t st)
 {
     const int64_t N = g->num_nodes, words = ceil_div(N, 32);
-    const int nb = (int)ceil_div(words, BT);
+    const int64_t nb = std::max(ceil_div(words, BT), ceil_div(N, BT));
     BGL_HIP(hipMalloc((void **)&w.visited, words * 4));
     BGL_HIP(hipMalloc((void **)&w.next, words * 4));
     BGL_HIP(hipMalloc((void **)&w.train, words * 4));
     BGL_HIP(hipMalloc((void **)&w.frontier, N * 4));
+    BGL_HIP(hipMalloc((void **)&w.cand, N * 4));
+    BGL_HIP(hipMalloc((void **)&w.key, N * 8));
+    BGL_HIP(hipMalloc((void **)&w.keys_in, N * 8));
+    BGL_HIP(hipMalloc((void **)&w.keys_out, N * 8));
     BGL_HIP(hipMalloc((void **)&w.seq, std::max<int64_t>(num_train, 1) * 4));
     BGL_HIP(hipMalloc((void **)&w.train_ids, std::max<int64_t>(num_train, 1) * 4));
-    BGL_HIP(hipMalloc((void **)&w.bs_all, (nb + 1) * 4));
-    BGL_HIP(hipMalloc((void **)&w.bs_tr, (nb + 1) * 4));
+    BGL_HIP(hipMalloc((void **)&w.bs, (nb + 1) * 4));
     BGL_HIP(hipMalloc((void **)&w.seq_base, 4));
     BGL_HIP(hipMalloc((void **)&w.dev, sizeof(OrderDev)));
     BGL_HIP(hipHostMalloc((void **)&w.host, sizeof(OrderDev), hipHostMallocDefault));
+    BGL_HIP(rocprim::radix_sort_pairs(nullptr, w.sort_tmp_bytes, w.keys_in, w.keys_out, w.cand, w.frontier,
+                                      (size_t)N, 0, 64, st));
+    BGL_HIP(hipMalloc(&w.sort_tmp, std::max<size_t>(w.sort_tmp_bytes, 16)));
     BGL_HIP(hipMemsetAsync(w.dev, 0, sizeof(OrderDev), st));
     BGL_HIP(hipMemcpyAsync(w.train_ids, train_nodes, num_train * 4, hipMemcpyHostToDevice, st));
     hipLaunchKernelGGL(k_fill_u32, dim3(std::min<int64_t>(ceil_div(words, BT), 4096)), dim3(BT), 0, st, w.train, words, 0u);
@@ -232,35 +281,56 @@ template <typename RP>
 int bfs_sequence(const bgl_graph *g, int64_t root, int64_t num_train, OrderWork &w, hipStream_t st)
 {
     const int64_t N = g->num_nodes, words = ceil_div(N, 32);
-    const int nb = (int)ceil_div(words, BT);
+    const int nbw = (int)ceil_div(words, BT);
     const RP *rp = static_cast<const RP *>(g->row_ptr);
-    hipLaunchKernelGGL(k_reset, dim3(nb), dim3(BT), 0, st, w.visited, w.next, words, N, w.dev);
+    hipLaunchKernelGGL(k_reset, dim3(nbw), dim3(BT), 0, st, w.visited, w.next, words, N, w.dev);
+    hipLaunchKernelGGL(k_fill_key, dim3((unsigned)std::min<int64_t>(ceil_div(N, BT), 8192)), dim3(BT), 0, st, w.key, N);
     hipLaunchKernelGGL(k_start_at, dim3(1), dim3(64), 0, st, (int32_t)root, w.visited, w.train, w.frontier, w.seq, w.dev);
     int64_t visited_count = 1;
     int fsize = 1;
-    auto compact = [&]() {
-        hipLaunchKernelGGL(k_bm_count, dim3(nb), dim3(BT), 0, st, w.next, w.train, words, w.bs_all, w.bs_tr);
-        hipLaunchKernelGGL(k_bm_scan, dim3(1), dim3(1024), 0, st, w.bs_all, w.bs_tr, nb, w.dev, w.seq_base);
-        hipLaunchKernelGGL(k_bm_write, dim3(nb), dim3(BT), 0, st, w.next, w.train, words, w.bs_all, w.bs_tr,
-                           w.seq_base, w.frontier, w.seq);
+    // next-level bitmap -> w.cand (ascending ids), marks them visited; returns the count
+    auto compact = [&](int &count) -> int {
+        hipLaunchKernelGGL(k_bm_count, dim3(nbw), dim3(BT), 0, st, w.next, words, w.bs);
+        hipLaunchKernelGGL(k_scan_counts, dim3(1), dim3(1024), 0, st, w.bs, nbw, w.dev, 0, w.seq_base);
+        hipLaunchKernelGGL(k_bm_write, dim3(nbw), dim3(BT), 0, st, w.next, w.visited, words, w.bs, w.cand);
+        int rc = read_dev(w, st);
+        if (rc != BGL_OK) return rc;
+        count = w.host->fsize;
+        return BGL_OK;
+    };
+    auto append_training = [&](const int32_t *list, int n) {
+        if (n <= 0) return;
+        const int nb = (int)ceil_div(n, BT);
+        hipLaunchKernelGGL(k_list_count, dim3(nb), dim3(BT), 0, st, list, n, w.train, w.bs);
+        hipLaunchKernelGGL(k_scan_counts, dim3(1), dim3(1024), 0, st, w.bs, nb, w.dev, 1, w.seq_base);
+        hipLaunchKernelGGL(k_list_write, dim3(nb), dim3(BT), 0, st, list, n, w.train, w.bs, w.seq_base, w.seq);
     };
     for (;;) {
         while (fsize > 0) {
+            const int parents = fsize;
             hipLaunchKernelGGL((k_expand<RP>), dim3((unsigned)ceil_div((int64_t)fsize * 16, BT)), dim3(BT), 0, st, rp,
-                               g->col, w.frontier, fsize, w.visited, w.next);
-            compact();
-            int rc = read_dev(w, st);
+                               g->col, w.frontier, fsize, w.visited, w.next, w.key);
+            int rc = compact(fsize);
             if (rc != BGL_OK) return rc;
-            fsize = w.host->fsize;
             visited_count += fsize;
+            if (fsize == 0) break;
+            // queue order of the new level: sort the candidates by (parent rank, edge position)
+            hipLaunchKernelGGL(k_gather_keys, dim3((unsigned)ceil_div(fsize, BT)), dim3(BT), 0, st, w.cand, fsize, w.key, w.keys_in);
+            int parent_bits = 1;
+            while ((1ll << parent_bits) < parents) ++parent_bits;
+            size_t tmp = w.sort_tmp_bytes;
+            BGL_HIP(rocprim::radix_sort_pairs(w.sort_tmp, tmp, w.keys_in, w.keys_out, w.cand, w.frontier,
+                                              (size_t)fsize, 0, (unsigned)std::min(64, 32 + parent_bits), st));
+            append_training(w.frontier, fsize);
         }
         if (visited_count >= N) break;
         hipLaunchKernelGGL((k_open_min<RP>), dim3((unsigned)ceil_div(N, BT)), dim3(BT), 0, st, rp, g->col, w.visited, N, w.dev);
-        hipLaunchKernelGGL(k_take_closed, dim3(nb), dim3(BT), 0, st, w.visited, w.next, words, w.dev);
-        compact();
-        int rc = read_dev(w, st);
+        hipLaunchKernelGGL(k_take_closed, dim3(nbw), dim3(BT), 0, st, w.visited, w.next, words, w.dev);
+        int closed = 0;
+        int rc = compact(closed);       // one-node traversals, in id order
         if (rc != BGL_OK) return rc;
-        visited_count += w.host->fsize;
+        visited_count += closed;
+        append_training(w.cand, closed);
         if (w.host->open_min == INT_MAX) break;  // everything that was left was closed
         hipLaunchKernelGGL(k_start_at, dim3(1), dim3(64), 0, st, (int32_t)-1, w.visited, w.train, w.frontier, w.seq, w.dev);
         fsize = 1;
