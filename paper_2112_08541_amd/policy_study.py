@@ -108,6 +108,9 @@ def main():
     ap.add_argument("--batches", type=int, default=200)
     ap.add_argument("--fractions", default="0.025,0.05,0.1,0.2,0.4")
     ap.add_argument("--nodes", type=int, default=0, help="run the configuration's shape at this node count")
+    ap.add_argument("--p-local", type=float, default=None,
+                    help="override the generator's share of edges that stay inside a community")
+    ap.add_argument("--batch", type=int, default=0, help="override the number of seeds per batch")
     args = ap.parse_args()
     import torch
     from . import binding as B
@@ -115,6 +118,11 @@ def main():
     cfg = inputs.CONFIGS[args.config]
     if args.nodes:
         cfg = inputs.scaled(cfg, args.nodes)
+    import dataclasses
+    if args.p_local is not None:
+        cfg = dataclasses.replace(cfg, p_local=args.p_local, name=f"{cfg.name},p_local={args.p_local}")
+    if args.batch:
+        cfg = dataclasses.replace(cfg, batch=args.batch, name=f"{cfg.name},batch={args.batch}")
     t0 = time.time()
     row_ptr, col, _keep = inputs.make_graph(cfg)          # no feature table: only ids matter here
     N = cfg.num_nodes
