@@ -13,12 +13,11 @@
 // the id with a ballot was measured at half the speed, the lookup being latency
 // bound).  An insertion is done by a group of 16 lanes that reads the bucket with
 // one coalesced request, picks a free word with a wavefront ballot and claims it
-// with a CAS.  Because the mark is only needed
-// for full buckets (rare at load <= 1/2), evictions simply blank their word:
-// no tombstones, no rebuilds.  slot_to_entry[slot] remembers the word that maps
-// a slot's occupant, so an eviction needs no search.
+// with a CAS.  Because the mark is only needed for full buckets (rare at load
+// <= 1/2), evictions simply blank their word: no tombstones, no rebuilds.
+// slot_to_entry[slot] remembers the word that maps a slot's occupant, so an
+// eviction needs no search.
 #include <algorithm>
-#include <mutex>
 #include <vector>
 
 #include "bgl_internal.h"
@@ -50,6 +49,7 @@ struct bgl_cache {
     int32_t row_bytes;
     int64_t num_nodes;
     const char *features;   // device-visible backing store
+    bool features_in_hbm;   // backing store is device memory (then the fetch is an HBM gather)
     int device;
     char *buffer;           // capacity * row_bytes
     uint64_t *table;        // num_buckets * BUCKET words
@@ -57,7 +57,7 @@ struct bgl_cache {
     int32_t *slot_to_node;  // capacity
     uint32_t *slot_to_entry;
     CacheDev *dev;
-    int32_t *mbs;           // per-tile miss counts, then their exclusive prefix
+    int32_t *mbs;           // per-tile miss counts of the most recent lookup
     int64_t mbs_cap;
     int32_t *hit_pos;       // hits of the most recent lookup: hit_cap positions, then hit_cap slots
     int64_t hit_cap;
@@ -148,26 +148,12 @@ __global__ __launch_bounds__(KEYS_PER_TILE) void k_probe(const int32_t *__restri
 }
 
 // Counters of an empty lookup (n = 0); with n > 0 k_split_list publishes them.
-__global__ __launch_bounds__(1024) void k_scan_miss(int32_t *mbs, int64_t n, CacheDev *dev,
-                                                    int64_t *n_hit_host)
+__global__ void k_empty_lookup(CacheDev *dev, int64_t *n_hit_host)
 {
-    __shared__ int sh_scan[1024 / kWave];
-    const int nb = (int)((n + KEYS_PER_TILE - 1) / KEYS_PER_TILE);
-    int carry = 0;
-    for (int base = 0; base < nb; base += 1024) {
-        const int idx = base + threadIdx.x;
-        const int v = idx < nb ? mbs[idx] : 0;
-        int tot;
-        const int ex = block_excl_scan<1024>(v, sh_scan, tot);
-        if (idx < nb) mbs[idx] = carry + ex;
-        carry += tot;
-    }
-    if (threadIdx.x == 0) {
-        dev->n_miss_last = carry;
-        dev->n_hit_last = n - carry;
-        dev->lookups += (unsigned long long)n;
-        dev->hits += (unsigned long long)(n - carry);
-        if (n_hit_host) *n_hit_host = n - carry;
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        dev->n_miss_last = 0;
+        dev->n_hit_last = 0;
+        if (n_hit_host) *n_hit_host = 0;
     }
 }
 
@@ -524,6 +510,7 @@ extern "C" int bgl_cache_create(int64_t capacity_rows, int32_t row_bytes,
     c->row_bytes = row_bytes;
     c->num_nodes = num_nodes;
     c->features = feat_dev;
+    c->features_in_hbm = attr.type == hipMemoryTypeDevice;
     c->profiling = 0;
     c->fetch_pending = false;
     for (int s = 0; s < BGL_NUM_STAGES; ++s) { c->prof_ms[s] = 0; c->prof_n[s] = 0; }
@@ -670,7 +657,8 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
         }
         {
             Prof p(c, BGL_STAGE_FETCH_MISS, ss);
-            const int blocks = (int)std::min<int64_t>(copy_blocks(n, q), FETCH_BLOCKS);
+            // the small grid is for the host link only; an HBM-resident store wants the whole chip
+            const int blocks = (int)std::min<int64_t>(copy_blocks(n, q), c->features_in_hbm ? 8192 : FETCH_BLOCKS);
             dispatch_q(q, [&](auto Q) {
                 hipLaunchKernelGGL((k_fetch_miss<decltype(Q)::value>), dim3(blocks),
                                    dim3(COPY_THREADS), 0, ss, miss_pos, ids, q, c->num_nodes,
@@ -683,8 +671,7 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
             c->fetch_pending = true;
         }
     } else {
-        hipLaunchKernelGGL(k_scan_miss, dim3(1), dim3(1024), 0, ms, c->mbs, (int64_t)0, c->dev,
-                           n_hit_dev);
+        hipLaunchKernelGGL(k_empty_lookup, dim3(1), dim3(64), 0, ms, c->dev, n_hit_dev);
     }
     BGL_HIP(hipGetLastError());
     return BGL_OK;
