@@ -371,3 +371,69 @@ def test_pipeline_large_config_full_size():
     """111 M nodes, ~1.6 B edges (int64 offsets, CSR read in place from page-locked host
     memory), fp32 x 128 rows, 25 M-row cache (~64 GB of page-locked host memory, ~30 s)."""
     run_full(_inputs().CONFIGS["large"], 3, 1)
+
+
+# ------------------------------------------------------ argument errors on the GPU side
+def test_sample_workspace_and_argument_errors(B, torch_mod):
+    import ctypes as C
+    rp, col = csr_from_adj(TINY_GRAPHS["path"])
+    g = B.Graph(rp, col)
+    s = B.Sampler(g, 4, [2, 2])
+    seeds = torch_mod.tensor([0, 1, 2, 3], dtype=torch_mod.int32, device="cuda")
+    L = B.lib()
+    st = B.SubgraphStruct()
+    fan = s.fanouts.ctypes.data
+    ws, nbytes = s.workspace.data_ptr(), s.workspace_bytes
+    call = lambda **kw: L.bgl_sample_khop(kw.get("g", g._h), kw.get("seeds", seeds.data_ptr()), kw.get("n", 4),
+                                          kw.get("fan", fan), kw.get("hops", 2), 1, kw.get("ws", ws),
+                                          kw.get("bytes", nbytes), C.byref(st), None, None)
+    assert call() == B.BGL_OK
+    assert call(bytes=nbytes - 1) == B.BGL_ECAPACITY
+    assert call(ws=ws + 64) == B.BGL_EINVAL          # not 256-byte aligned
+    assert call(ws=None) == B.BGL_EINVAL
+    assert call(seeds=None) == B.BGL_EINVAL
+    assert call(hops=0) == B.BGL_EINVAL and call(hops=9) == B.BGL_EINVAL
+    assert call(n=0) == B.BGL_EINVAL
+    big = np.array([65, 2], dtype=np.int32)
+    assert call(fan=big.ctypes.data) == B.BGL_EUNSUPPORTED
+    torch_mod.cuda.synchronize()
+
+
+def test_cache_argument_errors_and_device_resident_store(B, torch_mod):
+    import oracle
+    rng = np.random.default_rng(21)
+    feats = rng.standard_normal((4000, 32)).astype(np.float32)            # 128-byte rows
+    pageable = np.zeros((8, 4), dtype=np.float32)
+    with pytest.raises(B.BglError) as e:
+        B.Cache(4, pageable)                                               # not page-locked
+    assert e.value.code == B.BGL_EINVAL
+    # a backing store in device memory is accepted: the "fetch" is then an HBM gather
+    dev_feats = torch_mod.from_numpy(feats.view(np.uint8).reshape(4000, 128)).cuda()
+    gc = B.Cache(500, dev_feats, num_nodes=4000, row_bytes=128)
+    oc = oracle.Cache(500, feats)
+    out = torch_mod.empty((1500, 128), dtype=torch_mod.uint8, device="cuda")
+    out_slot = torch_mod.empty(1500, dtype=torch_mod.int32, device="cuda")
+    miss_pos = torch_mod.empty(1500, dtype=torch_mod.int32, device="cuda")
+    for b in range(6):
+        ids = rng.permutation(4000)[: int(rng.integers(1, 1500))].astype(np.int32)
+        ids_t = torch_mod.from_numpy(ids).cuda()
+        gc.lookup_gather(ids_t, len(ids), out, out_slot, miss_pos)
+        gc.insert_fifo(ids_t, miss_pos, -1, out)
+        o_out, o_slot, o_miss, o_hit = oc.lookup_gather(ids)
+        oc.insert_fifo(ids, o_miss, o_out)
+        torch_mod.cuda.synchronize()
+        assert int(gc.n_hit_host[0]) == o_hit
+        assert np.array_equal(out[: len(ids)].cpu().numpy(), o_out)
+    assert_state_equal(gc, oc, "device store")
+    # misaligned output rows, pageable hit counter
+    L = B.lib()
+    ids_t = torch_mod.arange(4, dtype=torch_mod.int32, device="cuda")
+    assert L.bgl_cache_lookup_gather(gc._h, ids_t.data_ptr(), 4, out.data_ptr() + 8, out_slot.data_ptr(),
+                                     miss_pos.data_ptr(), None, None, None) == B.BGL_EINVAL
+    word = np.zeros(1, dtype=np.int64)
+    assert L.bgl_cache_lookup_gather(gc._h, ids_t.data_ptr(), 4, out.data_ptr(), out_slot.data_ptr(),
+                                     miss_pos.data_ptr(), word.ctypes.data, None, None) == B.BGL_EINVAL
+    assert L.bgl_cache_lookup_gather(gc._h, ids_t.data_ptr(), -1, out.data_ptr(), out_slot.data_ptr(),
+                                     miss_pos.data_ptr(), None, None, None) == B.BGL_EINVAL
+    assert L.bgl_cache_profile(gc._h, 17, None, None) == B.BGL_EINVAL
+    torch_mod.cuda.synchronize()
