@@ -203,6 +203,26 @@ def main():
                 "note": "last batch of the epoch looked up again after its insertion; not part of value",
             }
 
+    # k-hop sampling on its own (outside the timed region; in the pipeline it hides under the
+    # miss fetch): back-to-back sampling calls, no host round trip in between.
+    reps = min(50, nb)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    smp = pipe.samplers[0]
+    smp.sample(seeds_dev[0], int(w.rng_seeds[0]))
+    torch.cuda.synchronize()
+    e0.record()
+    for b in range(reps):
+        smp.sample(seeds_dev[b], int(w.rng_seeds[b]))
+    e1.record()
+    torch.cuda.synchronize()
+    s_ms = e0.elapsed_time(e1) / reps
+    counts = smp.counts_host.numpy()
+    result["sampling_only"] = {
+        "ms_per_batch": s_ms, "minibatches_per_s": 1e3 / s_ms,
+        "sampled_edges_per_s": float(counts[B.BGL_MAX_HOPS + 1: B.BGL_MAX_HOPS + 1 + len(cfg.fanouts)].sum()) / (s_ms * 1e-3),
+        "note": "bgl_sample_khop alone, %d batches back to back" % reps,
+    }
+
     if cfg.order == "po":
         # Proximity-aware ordering as the library computes it (once per epoch, outside the
         # timed region): 5 BFS sequences over the training set on the GPU, merged on the host.
