@@ -36,6 +36,8 @@ def parse_args():
                     help="leave the per-kernel HIP events out of the timed region")
     ap.add_argument("--all-stage-timers", action="store_true",
                     help="bracket every cache kernel with events (default: hit gather and miss fetch only)")
+    ap.add_argument("--no-write-through", action="store_true",
+                    help="FIFO update copies the rows after the fetch instead of the fetch filling the cache buffer")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run three plain 1 GiB device-to-device copies (the known-size "
                          "kernel that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -95,7 +97,8 @@ def main():
 
     # warm-up on a scratch cache of the same size, so the timed epoch starts from an empty cache
     scratch = new_cache()
-    pipe = MinibatchPipeline(graph, scratch, cfg.batch, cfg.fanouts, cfg.row_bytes)
+    pipe = MinibatchPipeline(graph, scratch, cfg.batch, cfg.fanouts, cfg.row_bytes,
+                             write_through=not args.no_write_through)
     if args.warmup > 0:
         pipe.run(seeds_dev, w.rng_seeds, args.warmup)
     scratch.close()
@@ -185,6 +188,7 @@ def main():
         # part of `value`): the epoch's last batch is looked up again right after its
         # insertion; only the rows its own insertions evicted miss.
         if pipe.last_n:
+            cache.set_write_through(False)       # lookups without inserts follow
             cache.set_profiling(("gather_hit",))
             reps, hits2 = 5, 0
             for _ in range(reps):

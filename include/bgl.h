@@ -203,6 +203,22 @@ int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const int32_t *mis
                           int64_t n_miss, const void *out_rows, void *stream);
 
 /*
+ * Write-through mode (off by default).  When on, the caller promises that every
+ * bgl_cache_lookup_gather is followed, before any other call on the cache, by
+ * bgl_cache_insert_fifo with the same ids and miss_pos and n_miss = -1 (the
+ * paper's workflow: every miss is inserted, Sec. 3.2.3).  The miss fetch then
+ * stores each row it reads both into out_rows and into the buffer slot the FIFO
+ * rule will give it, so the update has no row copy and does not wait for the
+ * fetch: the time between two fetches on the host link shrinks to lookup, lists
+ * and hit gather.  Results are identical to the default mode.  A call sequence
+ * that breaks the promise is rejected with BGL_EINVAL; a stream that reads
+ * out_rows must still pass bgl_cache_wait_rows.  In this mode the cache's single
+ * stream of truth for ordering is main_stream: lookup and insert of one cache
+ * must use the same stream.
+ */
+int bgl_cache_set_write_through(bgl_cache_t *c, int enable);
+
+/*
  * Make `stream` wait (on the device, not the host) until the miss rows of the
  * most recent bgl_cache_lookup_gather are in out_rows.  A no-op when that call
  * ran on a single stream.  Consumers of out_rows other than

@@ -29,7 +29,7 @@ STAGE_NAMES = ["probe", "miss_list", "gather_hit", "fetch_miss", "insert_map", "
 EXPORTS = [
     "bgl_last_error", "bgl_graph_load_csr", "bgl_graph_destroy", "bgl_sample_workspace_bytes",
     "bgl_sample_khop", "bgl_cache_create", "bgl_cache_destroy", "bgl_cache_lookup_gather",
-    "bgl_cache_insert_fifo", "bgl_cache_wait_rows", "bgl_cache_export_state", "bgl_cache_stats",
+    "bgl_cache_insert_fifo", "bgl_cache_set_write_through", "bgl_cache_wait_rows", "bgl_cache_export_state", "bgl_cache_stats",
     "bgl_cache_set_profiling", "bgl_cache_profile",
     "bgl_order_bfs_sequence", "bgl_order_proximity", "bgl_order_choose_sequences",
     "bgl_order_shuffling_error",
@@ -70,6 +70,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     L.bgl_cache_destroy.argtypes = [vp]
     L.bgl_cache_lookup_gather.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, vp]
     L.bgl_cache_insert_fifo.argtypes = [vp, vp, vp, i64, vp, vp]
+    L.bgl_cache_set_write_through.argtypes = [vp, ci]
     L.bgl_cache_wait_rows.argtypes = [vp, vp]
     L.bgl_cache_export_state.argtypes = [vp, vp, C.POINTER(u64), vp]
     L.bgl_cache_stats.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(u64),
@@ -274,6 +275,9 @@ class Cache:
         _check(lib().bgl_cache_insert_fifo(self._h, _dev_ptr(ids, torch.int32),
                                            _dev_ptr(miss_pos, torch.int32), n_miss, _dev_ptr(out_rows),
                                            _stream_handle(stream)))
+
+    def set_write_through(self, enable: bool) -> None:
+        _check(lib().bgl_cache_set_write_through(self._h, 1 if enable else 0))
 
     def wait_rows(self, stream=None) -> None:
         _check(lib().bgl_cache_wait_rows(self._h, _stream_handle(stream)))

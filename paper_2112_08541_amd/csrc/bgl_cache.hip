@@ -66,6 +66,9 @@ struct bgl_cache {
     hipStream_t own_side;
     hipEvent_t ev_listed, ev_miss;
     bool fetch_pending;     // ev_miss marks a miss fetch nobody has waited for yet
+    bool write_through;     // the miss fetch also fills the cache buffer (see bgl_cache_set_write_through)
+    bool awaiting_insert;   // write-through: a lookup's misses are in the buffer but not in the map yet
+    const void *wt_ids, *wt_miss_pos;  // arguments of that lookup
     // profiling
     unsigned profiling;     // bit s set: stage s is bracketed with events
     std::vector<hipEvent_t> prof_ev;  // pairs
@@ -253,23 +256,32 @@ __global__ __launch_bounds__(COPY_THREADS) void k_gather_hits(
 // needs little data in flight compared with HBM, and waves blocked on it would
 // otherwise hold the wave slots the concurrent hit gather needs, so this kernel
 // runs as a small fixed grid that strides over the miss list.
-template <int Q>
+//
+// Write-through variant (WT): the same loaded chunk is also stored into the cache
+// buffer slot the row will get from the FIFO update that follows, so that update
+// needs no row copy: miss r goes to slot (tail + r) mod capacity, ranks that a
+// later miss of the same batch would overwrite are skipped.
+template <int Q, bool WT>
 __global__ __launch_bounds__(COPY_THREADS) void k_fetch_miss(
     const int32_t *__restrict__ miss_pos, const int32_t *__restrict__ ids, int q,
     int64_t num_nodes, const uint4 *__restrict__ features, uint4 *__restrict__ out,
-    const CacheDev *dev)
+    const CacheDev *dev, uint4 *__restrict__ buffer, int64_t capacity, int par)
 {
     const int qq = Q > 0 ? Q : q;
-    const int64_t total = (int64_t)dev->n_miss_last * qq;
+    const int64_t n_miss = dev->n_miss_last;
+    const int64_t total = n_miss * qq;
+    const int64_t start = n_miss > capacity ? n_miss - capacity : 0;
+    const unsigned long long tail = WT ? dev->tail[par] : 0ull;
     const int64_t step = (int64_t)gridDim.x * (COPY_THREADS * COPY_UNROLL);
     for (int64_t base = (int64_t)blockIdx.x * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
          base - threadIdx.x < total; base += step) {
         uint4 v[COPY_UNROLL];
-        int64_t dst[COPY_UNROLL];
+        int64_t dst[COPY_UNROLL], dst2[COPY_UNROLL];
 #pragma unroll
         for (int k = 0; k < COPY_UNROLL; ++k) {
             const int64_t idx = base + k * COPY_THREADS;
             dst[k] = -1;
+            dst2[k] = -1;
             if (idx < total) {
                 int64_t r; int c;
                 RowSplit<Q>::split(idx, q, r, c);
@@ -278,12 +290,16 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_miss(
                 if (id >= 0 && (int64_t)id < num_nodes) {
                     v[k] = features[(int64_t)id * qq + c];
                     dst[k] = (int64_t)row * qq + c;
+                    if (WT && r >= start)
+                        dst2[k] = (int64_t)((tail + (unsigned long long)r) % (unsigned long long)capacity) * qq + c;
                 }
             }
         }
 #pragma unroll
-        for (int k = 0; k < COPY_UNROLL; ++k)
+        for (int k = 0; k < COPY_UNROLL; ++k) {
             if (dst[k] >= 0) out[dst[k]] = v[k];
+            if (WT && dst2[k] >= 0) buffer[dst2[k]] = v[k];
+        }
     }
 }
 
@@ -398,11 +414,14 @@ __device__ __forceinline__ void insert_rows_part(
 __global__ __launch_bounds__(COPY_THREADS) void k_insert_map(
     const int32_t *__restrict__ ids, const int32_t *__restrict__ miss_pos, int64_t n_miss_arg,
     int64_t capacity, int64_t num_nodes, uint64_t *table, uint32_t bucket_mask,
-    int32_t *slot_to_node, uint32_t *slot_to_entry, CacheDev *dev, int par)
+    int32_t *slot_to_node, uint32_t *slot_to_entry, CacheDev *dev, int par, int advance)
 {
     const int64_t n_miss = n_miss_arg >= 0 ? n_miss_arg : dev->n_miss_last;
     const int64_t start = n_miss > capacity ? n_miss - capacity : 0;  // earlier ranks would be overwritten
-    insert_map_part(blockIdx.x, ids, miss_pos, n_miss, start, dev->tail[par], capacity, num_nodes,
+    const unsigned long long tail = dev->tail[par];
+    // write-through mode has no row-copy launch: then this one advances tail
+    if (advance && blockIdx.x == 0 && threadIdx.x == 0) dev->tail[par ^ 1] = tail + (unsigned long long)n_miss;
+    insert_map_part(blockIdx.x, ids, miss_pos, n_miss, start, tail, capacity, num_nodes,
                     table, bucket_mask, slot_to_node, slot_to_entry, dev);
 }
 
@@ -513,6 +532,9 @@ extern "C" int bgl_cache_create(int64_t capacity_rows, int32_t row_bytes,
     c->features_in_hbm = attr.type == hipMemoryTypeDevice;
     c->profiling = 0;
     c->fetch_pending = false;
+    c->write_through = false;
+    c->awaiting_insert = false;
+    c->wt_ids = c->wt_miss_pos = nullptr;
     for (int s = 0; s < BGL_NUM_STAGES; ++s) { c->prof_ms[s] = 0; c->prof_n[s] = 0; }
     c->mbs = nullptr;
     c->mbs_cap = 0;
@@ -621,6 +643,8 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
     }
     const int q = c->row_bytes / 16;
     const bool two_streams = ss != ms;
+    if (c->write_through && c->awaiting_insert)
+        BGL_FAIL(BGL_EINVAL, "write-through mode: the previous lookup's misses have not been inserted yet");
     if (c->fetch_pending) {
         // the previous call's fetch still reads that call's lists
         BGL_HIP(hipStreamWaitEvent(ms, c->ev_miss, 0));
@@ -659,11 +683,20 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
             Prof p(c, BGL_STAGE_FETCH_MISS, ss);
             // the small grid is for the host link only; an HBM-resident store wants the whole chip
             const int blocks = (int)std::min<int64_t>(copy_blocks(n, q), c->features_in_hbm ? 8192 : FETCH_BLOCKS);
+            const int par = (int)(c->insert_calls & 1);
             dispatch_q(q, [&](auto Q) {
-                hipLaunchKernelGGL((k_fetch_miss<decltype(Q)::value>), dim3(blocks),
-                                   dim3(COPY_THREADS), 0, ss, miss_pos, ids, q, c->num_nodes,
-                                   reinterpret_cast<const uint4 *>(c->features),
-                                   reinterpret_cast<uint4 *>(out_rows), c->dev);
+                if (c->write_through)
+                    hipLaunchKernelGGL((k_fetch_miss<decltype(Q)::value, true>), dim3(blocks),
+                                       dim3(COPY_THREADS), 0, ss, miss_pos, ids, q, c->num_nodes,
+                                       reinterpret_cast<const uint4 *>(c->features),
+                                       reinterpret_cast<uint4 *>(out_rows), c->dev,
+                                       reinterpret_cast<uint4 *>(c->buffer), c->capacity, par);
+                else
+                    hipLaunchKernelGGL((k_fetch_miss<decltype(Q)::value, false>), dim3(blocks),
+                                       dim3(COPY_THREADS), 0, ss, miss_pos, ids, q, c->num_nodes,
+                                       reinterpret_cast<const uint4 *>(c->features),
+                                       reinterpret_cast<uint4 *>(out_rows), c->dev,
+                                       reinterpret_cast<uint4 *>(c->buffer), c->capacity, par);
             });
         }
         if (two_streams) {
@@ -674,6 +707,11 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
         hipLaunchKernelGGL(k_empty_lookup, dim3(1), dim3(64), 0, ms, c->dev, n_hit_dev);
     }
     BGL_HIP(hipGetLastError());
+    if (c->write_through) {
+        c->awaiting_insert = true;
+        c->wt_ids = ids;
+        c->wt_miss_pos = miss_pos;
+    }
     return BGL_OK;
 }
 
@@ -690,13 +728,33 @@ extern "C" int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const i
     const int q = c->row_bytes / 16;
     const int64_t eff = std::min<int64_t>(bound, c->capacity);
     const int par = (int)(c->insert_calls & 1);
+    if (c->write_through) {
+        // the rows are already on their way into the buffer: only the map changes here,
+        // and nothing has to wait for the miss fetch
+        if (!c->awaiting_insert || n_miss != -1 || ids != c->wt_ids || miss_pos != c->wt_miss_pos)
+            BGL_FAIL(BGL_EINVAL, "write-through mode: insert_fifo must follow its lookup_gather with the same "
+                                 "ids and miss_pos and n_miss = -1");
+        c->awaiting_insert = false;
+        if (eff > 0) {
+            Prof p(c, BGL_STAGE_INSERT_MAP, st);
+            hipLaunchKernelGGL(k_insert_map, dim3((unsigned)bgl::ceil_div(eff * BUCKET, COPY_THREADS)),
+                               dim3(COPY_THREADS), 0, st, ids, miss_pos, n_miss, c->capacity,
+                               c->num_nodes, c->table, c->num_buckets - 1, c->slot_to_node,
+                               c->slot_to_entry, c->dev, par, 1);
+        } else {
+            hipLaunchKernelGGL(k_advance_tail, dim3(1), dim3(64), 0, st, c->dev, n_miss, par);
+        }
+        c->insert_calls += 1;
+        BGL_HIP(hipGetLastError());
+        return BGL_OK;
+    }
     if (eff > 0) {
         {
             Prof p(c, BGL_STAGE_INSERT_MAP, st);
             hipLaunchKernelGGL(k_insert_map, dim3((unsigned)bgl::ceil_div(eff * BUCKET, COPY_THREADS)),
                                dim3(COPY_THREADS), 0, st, ids, miss_pos, n_miss, c->capacity,
                                c->num_nodes, c->table, c->num_buckets - 1, c->slot_to_node,
-                               c->slot_to_entry, c->dev, par);
+                               c->slot_to_entry, c->dev, par, 0);
         }
         if (c->fetch_pending) BGL_HIP(hipStreamWaitEvent(st, c->ev_miss, 0));  // rows of the misses
         {
@@ -714,6 +772,14 @@ extern "C" int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const i
     }
     c->insert_calls += 1;
     BGL_HIP(hipGetLastError());
+    return BGL_OK;
+}
+
+extern "C" int bgl_cache_set_write_through(bgl_cache_t *c, int enable)
+{
+    if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
+    if (c->awaiting_insert) BGL_FAIL(BGL_EINVAL, "a lookup's misses are still waiting for their insert_fifo");
+    c->write_through = enable != 0;
     return BGL_OK;
 }
 

@@ -9,7 +9,8 @@ main stream.  The cache state still advances strictly batch by batch
 Per batch i, in enqueue order:
   lookup_gather(i)   main: map lookup, miss/hit lists, hit gather; side: miss fetch
   sample(i+1)        main, overlapping the fetch (second sampling workspace)
-  insert_fifo(i)     main, waits for the fetch on the device
+  insert_fifo(i)     main; in write-through mode (default here) only the map update, which
+                     runs under the fetch; otherwise map update, wait for the fetch, row copy
   host waits for sample(i+1)'s sizes only (one event), never for the whole stream
 """
 from __future__ import annotations
@@ -23,8 +24,13 @@ from . import binding as B
 
 
 class MinibatchPipeline:
-    def __init__(self, graph: B.Graph, cache: B.Cache, batch: int, fanouts, row_bytes: int):
+    def __init__(self, graph: B.Graph, cache: B.Cache, batch: int, fanouts, row_bytes: int,
+                 write_through: bool = True):
         self.graph, self.cache = graph, cache
+        # every lookup here is followed by the insert of all its misses, so the miss fetch may
+        # fill the cache buffer itself (bgl_cache_set_write_through)
+        self.write_through = write_through
+        cache.set_write_through(write_through)
         self.fanouts = tuple(int(f) for f in fanouts)
         self.K = len(self.fanouts)
         self.samplers = [B.Sampler(graph, batch, self.fanouts) for _ in range(2)]
@@ -38,6 +44,7 @@ class MinibatchPipeline:
 
     def set_cache(self, cache: B.Cache) -> None:
         self.cache = cache
+        cache.set_write_through(self.write_through)
 
     def run(self, seeds_dev: torch.Tensor, rng_seeds, steps: int,
             on_batch: Optional[Callable] = None):

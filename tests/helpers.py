@@ -8,7 +8,7 @@ class GpuPipeline:
     """sample_khop -> lookup_gather -> insert_fifo on the GPU for one workload."""
 
     def __init__(self, workload, cache_rows=None, placement=None, use_side_stream=True,
-                 device_n_miss=False):
+                 device_n_miss=False, write_through=False):
         import torch
         from paper_2112_08541_amd import binding as B
         self.torch, self.B = torch, B
@@ -33,7 +33,9 @@ class GpuPipeline:
         self.out_slot = torch.empty(self.cap, dtype=torch.int32, device="cuda")
         self.miss_pos = torch.empty(self.cap, dtype=torch.int32, device="cuda")
         self.side = torch.cuda.Stream() if use_side_stream else None
-        self.device_n_miss = device_n_miss
+        self.device_n_miss = device_n_miss or write_through
+        if write_through:
+            self.cache.set_write_through(True)
 
     def run_batch(self, seeds_np, rng_seed, fetch=True):
         torch = self.torch
@@ -48,6 +50,7 @@ class GpuPipeline:
                                  side_stream=self.side)
         if self.device_n_miss:
             self.cache.insert_fifo(ids, self.miss_pos, -1, self.out_rows)
+            self.cache.wait_rows()          # write-through mode: the insert does not wait for the fetch
             torch.cuda.current_stream().synchronize()
             n_hit = int(self.cache.n_hit_host[0])
         else:

@@ -145,13 +145,16 @@ def test_sample_reports_out_of_range_seed(B, torch_mod):
 
 
 # --------------------------------------------------------------------- cache
-def run_cache_stream(B, torch, feats, cap, batches, device_n_miss=False, side=True):
+def run_cache_stream(B, torch, feats, cap, batches, device_n_miss=False, side=True, write_through=False):
     """Feed id batches through GPU cache and oracle cache; compare after every call."""
     import oracle
     N, rb = feats.shape[0], feats.shape[1] * feats.itemsize
     feat_t = torch.from_numpy(feats.view(np.uint8).reshape(N, rb)).pin_memory()
     gc = B.Cache(cap, feat_t, num_nodes=N, row_bytes=rb)
     oc = oracle.Cache(cap, feats)
+    if write_through:
+        gc.set_write_through(True)
+        device_n_miss = True
     side_stream = torch.cuda.Stream() if side else None
     for bi, ids in enumerate(batches):
         n = len(ids)
@@ -215,6 +218,52 @@ def test_cache_random_streams(B, torch_mod, dim, dtype, device_n_miss):
     run_cache_stream(B, torch_mod, feats, cap, batches, device_n_miss=device_n_miss)
 
 
+@pytest.mark.parametrize("dim,dtype", [(4, np.float32), (100, np.float32), (512, np.uint16), (264, np.uint16)])
+@pytest.mark.parametrize("side", [True, False])
+def test_cache_write_through_mode(B, torch_mod, dim, dtype, side):
+    """The miss fetch fills the cache buffer itself; same results as the default mode,
+    including a batch with more misses than slots, an empty batch and tiny capacities."""
+    rng = np.random.default_rng(dim + 1)
+    N = 20000
+    feats = (rng.standard_normal((N, dim)).astype(np.float32) if dtype == np.float32
+             else rng.integers(0, 2**16, (N, dim), dtype=np.uint16))
+    batches = []
+    for b in range(12):
+        size = int(rng.integers(1, 2500)) if b != 5 else 7000
+        batches.append(list(dict.fromkeys((rng.zipf(1.2, size) % N).tolist())))
+    batches.insert(3, [])
+    batches.insert(8, batches[7])
+    run_cache_stream(B, torch_mod, feats, 3000, batches, side=side, write_through=True)
+    run_cache_stream(B, torch_mod, feats, 1, batches[:6], side=side, write_through=True)
+
+
+def test_cache_write_through_rejects_a_broken_call_sequence(B, torch_mod):
+    feats = np.zeros((50, 4), dtype=np.float32)
+    feat_t = torch_mod.from_numpy(feats.view(np.uint8).reshape(50, 16)).pin_memory()
+    gc = B.Cache(8, feat_t, num_nodes=50, row_bytes=16)
+    gc.set_write_through(True)
+    ids = torch_mod.arange(5, dtype=torch_mod.int32, device="cuda")
+    other = torch_mod.arange(5, dtype=torch_mod.int32, device="cuda")
+    out = torch_mod.empty((5, 16), dtype=torch_mod.uint8, device="cuda")
+    out_slot = torch_mod.empty(5, dtype=torch_mod.int32, device="cuda")
+    miss_pos = torch_mod.empty(5, dtype=torch_mod.int32, device="cuda")
+    with pytest.raises(B.BglError):
+        gc.insert_fifo(ids, miss_pos, -1, out)               # no lookup before it
+    gc.lookup_gather(ids, 5, out, out_slot, miss_pos)
+    with pytest.raises(B.BglError):
+        gc.lookup_gather(ids, 5, out, out_slot, miss_pos)    # second lookup without the insert
+    with pytest.raises(B.BglError):
+        gc.insert_fifo(ids, miss_pos, 3, out)                # explicit count
+    with pytest.raises(B.BglError):
+        gc.insert_fifo(other, miss_pos, -1, out)             # other ids
+    with pytest.raises(B.BglError):
+        gc.set_write_through(False)                          # mode change while an insert is owed
+    gc.insert_fifo(ids, miss_pos, -1, out)
+    gc.set_write_through(False)
+    s2n, tail, _ = gc.export_state(False)
+    assert tail == 5 and s2n[:5].tolist() == [0, 1, 2, 3, 4]
+
+
 def test_cache_single_stream_and_tiny_capacity(B, torch_mod):
     rng = np.random.default_rng(3)
     feats = rng.standard_normal((500, 8)).astype(np.float32)
@@ -258,10 +307,10 @@ def test_cache_flags_out_of_range_id(B, torch_mod):
 
 
 # ------------------------------------------------------------ whole pipeline
-def run_config(cfg, n_batches, device_n_miss=False, check_every=1):
+def run_config(cfg, n_batches, device_n_miss=False, check_every=1, write_through=False):
     inputs = _inputs()
     w = inputs.make_workload(cfg, pinned=True)
-    gp = GpuPipeline(w, device_n_miss=device_n_miss)
+    gp = GpuPipeline(w, device_n_miss=device_n_miss, write_through=write_through)
     op = OraclePipeline(w)
     hits = total = 0
     for b in range(n_batches):
@@ -282,6 +331,7 @@ def test_pipeline_tiny_config_all_batches():
     cfg = _inputs().CONFIGS["tiny"]
     run_config(cfg, cfg.num_batches)
     run_config(cfg, cfg.num_batches, device_n_miss=True)
+    run_config(cfg, cfg.num_batches, write_through=True)
 
 
 def test_pipeline_mid_config_full_size():
@@ -289,7 +339,8 @@ def test_pipeline_mid_config_full_size():
     run_config(cfg, 12, device_n_miss=True, check_every=4)
 
 
-def test_overlapped_pipeline_as_benchmarked_matches_oracle(torch_mod, B):
+@pytest.mark.parametrize("write_through", [False, True])
+def test_overlapped_pipeline_as_benchmarked_matches_oracle(torch_mod, B, write_through):
     """The launch configuration bench.py times (two sampling workspaces, next batch sampled
     while the misses are fetched on the side stream, device-side miss count) on the
     full-size mid workload: every batch's outputs and the final cache state."""
@@ -299,11 +350,12 @@ def test_overlapped_pipeline_as_benchmarked_matches_oracle(torch_mod, B):
     w = inputs.make_workload(cfg, pinned=True)
     graph = B.Graph(w.row_ptr, w.col)
     cache = B.Cache(cfg.cache_rows, w.features.ctypes.data, num_nodes=cfg.num_nodes, row_bytes=cfg.row_bytes)
-    pipe = MinibatchPipeline(graph, cache, cfg.batch, cfg.fanouts, cfg.row_bytes)
+    pipe = MinibatchPipeline(graph, cache, cfg.batch, cfg.fanouts, cfg.row_bytes, write_through=write_through)
     seeds_dev = torch_mod.from_numpy(w.seed_batches).cuda()
     got = {}
 
     def grab(i, sb, n, p):
+        p.cache.wait_rows()
         torch_mod.cuda.current_stream().synchronize()
         nf, nnz = sb.sizes()
         n_hit = int(p.cache.n_hit_host[0])
