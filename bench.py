@@ -192,8 +192,7 @@ def main():
             cache.set_profiling(("gather_hit",))
             reps, hits2 = 5, 0
             for _ in range(reps):
-                cache.lookup_gather(pipe.last_ids, pipe.last_n, pipe.out_rows, pipe.out_slot, pipe.miss_pos,
-                                    side_stream=pipe.side)
+                cache.lookup_gather(pipe.last_ids, pipe.last_n, pipe.out_rows, pipe.out_slot, pipe.miss_pos)
                 torch.cuda.synchronize()
                 hits2 += int(cache.n_hit_host[0])
             p2 = cache.profile()

@@ -212,9 +212,7 @@ int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const int32_t *mis
  * fetch: the time between two fetches on the host link shrinks to lookup, lists
  * and hit gather.  Results are identical to the default mode.  A call sequence
  * that breaks the promise is rejected with BGL_EINVAL; a stream that reads
- * out_rows must still pass bgl_cache_wait_rows.  In this mode the cache's single
- * stream of truth for ordering is main_stream: lookup and insert of one cache
- * must use the same stream.
+ * out_rows must still pass bgl_cache_wait_rows.
  */
 int bgl_cache_set_write_through(bgl_cache_t *c, int enable);
 
@@ -225,6 +223,17 @@ int bgl_cache_set_write_through(bgl_cache_t *c, int enable);
  * bgl_cache_insert_fifo (the model's first layer) call this first.
  */
 int bgl_cache_wait_rows(bgl_cache_t *c, void *stream);
+
+/*
+ * Make `stream` wait (on the device) until the lists (out_slot, miss_pos, hit
+ * count) and the hit rows of the most recent bgl_cache_lookup_gather are
+ * complete.  A no-op for that call's main_stream.  bgl_cache_insert_fifo does
+ * this itself when it is given another stream than the lookup's main_stream, and
+ * the next lookup then waits for that update; so the lookups of one cache may run
+ * on one stream (with side_stream = main_stream the whole chain lookup, lists,
+ * hit gather, miss fetch stays in one queue) and the FIFO updates on another.
+ */
+int bgl_cache_wait_lists(bgl_cache_t *c, void *stream);
 
 /*
  * Copy the logical cache state to the host (synchronises the device):

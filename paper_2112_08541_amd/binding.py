@@ -29,7 +29,7 @@ STAGE_NAMES = ["probe", "miss_list", "gather_hit", "fetch_miss", "insert_map", "
 EXPORTS = [
     "bgl_last_error", "bgl_graph_load_csr", "bgl_graph_destroy", "bgl_sample_workspace_bytes",
     "bgl_sample_khop", "bgl_cache_create", "bgl_cache_destroy", "bgl_cache_lookup_gather",
-    "bgl_cache_insert_fifo", "bgl_cache_set_write_through", "bgl_cache_wait_rows", "bgl_cache_export_state", "bgl_cache_stats",
+    "bgl_cache_insert_fifo", "bgl_cache_set_write_through", "bgl_cache_wait_rows", "bgl_cache_wait_lists", "bgl_cache_export_state", "bgl_cache_stats",
     "bgl_cache_set_profiling", "bgl_cache_profile",
     "bgl_order_bfs_sequence", "bgl_order_proximity", "bgl_order_choose_sequences",
     "bgl_order_shuffling_error",
@@ -72,6 +72,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     L.bgl_cache_insert_fifo.argtypes = [vp, vp, vp, i64, vp, vp]
     L.bgl_cache_set_write_through.argtypes = [vp, ci]
     L.bgl_cache_wait_rows.argtypes = [vp, vp]
+    L.bgl_cache_wait_lists.argtypes = [vp, vp]
     L.bgl_cache_export_state.argtypes = [vp, vp, C.POINTER(u64), vp]
     L.bgl_cache_stats.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(u64),
                                   C.POINTER(u64), C.POINTER(i32)]
@@ -261,13 +262,16 @@ class Cache:
     __del__ = close
 
     def lookup_gather(self, ids: torch.Tensor, n: int, out_rows: torch.Tensor, out_slot: torch.Tensor,
-                      miss_pos: torch.Tensor, main_stream=None, side_stream=None) -> None:
+                      miss_pos: torch.Tensor, main_stream=None, side_stream=None,
+                      n_hit_ptr: Optional[int] = None) -> None:
+        """n_hit_ptr: address of a page-locked int64 for the hit count (default: self.n_hit_host)."""
         if n > 0 and (ids.numel() < n or out_slot.numel() < n or miss_pos.numel() < n or
                       out_rows.numel() * out_rows.element_size() < n * self.row_bytes):
             raise ValueError("an argument is smaller than n")
         _check(lib().bgl_cache_lookup_gather(
             self._h, _dev_ptr(ids, torch.int32), n, _dev_ptr(out_rows), _dev_ptr(out_slot, torch.int32),
-            _dev_ptr(miss_pos, torch.int32), self.n_hit_host.data_ptr(), _stream_handle(main_stream),
+            _dev_ptr(miss_pos, torch.int32),
+            self.n_hit_host.data_ptr() if n_hit_ptr is None else n_hit_ptr, _stream_handle(main_stream),
             None if side_stream is None else int(side_stream.cuda_stream)))
 
     def insert_fifo(self, ids: torch.Tensor, miss_pos: torch.Tensor, n_miss: int,
@@ -278,6 +282,9 @@ class Cache:
 
     def set_write_through(self, enable: bool) -> None:
         _check(lib().bgl_cache_set_write_through(self._h, 1 if enable else 0))
+
+    def wait_lists(self, stream=None) -> None:
+        _check(lib().bgl_cache_wait_lists(self._h, _stream_handle(stream)))
 
     def wait_rows(self, stream=None) -> None:
         _check(lib().bgl_cache_wait_rows(self._h, _stream_handle(stream)))

@@ -64,8 +64,15 @@ struct bgl_cache {
     int64_t last_n;         // n of the most recent lookup
     uint64_t insert_calls;  // FIFO updates enqueued so far (selects the live copy of tail)
     hipStream_t own_side;
-    hipEvent_t ev_listed, ev_miss;
-    bool fetch_pending;     // ev_miss marks a miss fetch nobody has waited for yet
+    // Ordering between streams.  ev_listed: lists and hit rows of the last lookup are complete
+    // (recorded on that lookup's main stream); ev_miss: its miss rows are complete (recorded on
+    // the stream the fetch ran on); ev_map: the last FIFO update is complete (recorded on the
+    // update's stream when that is not the lookup's main stream).
+    hipEvent_t ev_listed, ev_miss, ev_map;
+    hipStream_t last_main, fetch_stream, map_stream;
+    bool fetch_pending;     // ev_miss marks a miss fetch that later work may have to wait for
+    bool map_pending;       // ev_map marks a FIFO update the next lookup has to wait for
+    bool ev_listed_valid;   // a lookup has recorded ev_listed
     bool write_through;     // the miss fetch also fills the cache buffer (see bgl_cache_set_write_through)
     bool awaiting_insert;   // write-through: a lookup's misses are in the buffer but not in the map yet
     const void *wt_ids, *wt_miss_pos;  // arguments of that lookup
@@ -532,6 +539,9 @@ extern "C" int bgl_cache_create(int64_t capacity_rows, int32_t row_bytes,
     c->features_in_hbm = attr.type == hipMemoryTypeDevice;
     c->profiling = 0;
     c->fetch_pending = false;
+    c->map_pending = false;
+    c->ev_listed_valid = false;
+    c->last_main = c->fetch_stream = c->map_stream = nullptr;
     c->write_through = false;
     c->awaiting_insert = false;
     c->wt_ids = c->wt_miss_pos = nullptr;
@@ -563,7 +573,8 @@ extern "C" int bgl_cache_create(int64_t capacity_rows, int32_t row_bytes,
 #undef TRY_ALLOC
     if (hipStreamCreateWithFlags(&c->own_side, hipStreamNonBlocking) != hipSuccess ||
         hipEventCreateWithFlags(&c->ev_listed, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&c->ev_miss, hipEventDisableTiming) != hipSuccess) {
+        hipEventCreateWithFlags(&c->ev_miss, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_map, hipEventDisableTiming) != hipSuccess) {
         bgl::set_error("stream/event creation failed");
         return fail(BGL_EHIP);
     }
@@ -587,6 +598,7 @@ extern "C" int bgl_cache_destroy(bgl_cache_t *c)
     for (auto ev : c->prof_ev) (void)hipEventDestroy(ev);
     if (c->ev_listed) (void)hipEventDestroy(c->ev_listed);
     if (c->ev_miss) (void)hipEventDestroy(c->ev_miss);
+    if (c->ev_map) (void)hipEventDestroy(c->ev_map);
     if (c->own_side) (void)hipStreamDestroy(c->own_side);
     (void)hipFree(c->buffer);
     (void)hipFree(c->table);
@@ -645,11 +657,15 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
     const bool two_streams = ss != ms;
     if (c->write_through && c->awaiting_insert)
         BGL_FAIL(BGL_EINVAL, "write-through mode: the previous lookup's misses have not been inserted yet");
-    if (c->fetch_pending) {
+    if (c->fetch_pending && c->fetch_stream != ms) {
         // the previous call's fetch still reads that call's lists
         BGL_HIP(hipStreamWaitEvent(ms, c->ev_miss, 0));
-        c->fetch_pending = false;
     }
+    if (c->map_pending && c->map_stream != ms) BGL_HIP(hipStreamWaitEvent(ms, c->ev_map, 0));
+    c->fetch_pending = false;
+    c->map_pending = false;
+    c->last_main = ms;
+    c->ev_listed_valid = true;
     if (n > 0) {
         {
             Prof p(c, BGL_STAGE_PROBE, ms);
@@ -675,10 +691,8 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
         // queued in the memory pipeline would otherwise stall the gather's HBM
         // reads, and the fetch (milliseconds) loses nothing by starting a few
         // tens of microseconds later.
-        if (two_streams) {
-            BGL_HIP(hipEventRecord(c->ev_listed, ms));
-            BGL_HIP(hipStreamWaitEvent(ss, c->ev_listed, 0));
-        }
+        BGL_HIP(hipEventRecord(c->ev_listed, ms));
+        if (two_streams) BGL_HIP(hipStreamWaitEvent(ss, c->ev_listed, 0));
         {
             Prof p(c, BGL_STAGE_FETCH_MISS, ss);
             // the small grid is for the host link only; an HBM-resident store wants the whole chip
@@ -699,12 +713,12 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
                                        reinterpret_cast<uint4 *>(c->buffer), c->capacity, par);
             });
         }
-        if (two_streams) {
-            BGL_HIP(hipEventRecord(c->ev_miss, ss));
-            c->fetch_pending = true;
-        }
+        BGL_HIP(hipEventRecord(c->ev_miss, ss));
+        c->fetch_pending = true;
+        c->fetch_stream = ss;
     } else {
         hipLaunchKernelGGL(k_empty_lookup, dim3(1), dim3(64), 0, ms, c->dev, n_hit_dev);
+        BGL_HIP(hipEventRecord(c->ev_listed, ms));
     }
     BGL_HIP(hipGetLastError());
     if (c->write_through) {
@@ -728,6 +742,8 @@ extern "C" int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const i
     const int q = c->row_bytes / 16;
     const int64_t eff = std::min<int64_t>(bound, c->capacity);
     const int par = (int)(c->insert_calls & 1);
+    const bool other_stream = st != c->last_main;
+    if (other_stream && c->ev_listed_valid) BGL_HIP(hipStreamWaitEvent(st, c->ev_listed, 0));  // the lookup's lists
     if (c->write_through) {
         // the rows are already on their way into the buffer: only the map changes here,
         // and nothing has to wait for the miss fetch
@@ -746,6 +762,11 @@ extern "C" int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const i
         }
         c->insert_calls += 1;
         BGL_HIP(hipGetLastError());
+        if (other_stream) {
+            BGL_HIP(hipEventRecord(c->ev_map, st));
+            c->map_pending = true;
+            c->map_stream = st;
+        }
         return BGL_OK;
     }
     if (eff > 0) {
@@ -756,7 +777,8 @@ extern "C" int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const i
                                c->num_nodes, c->table, c->num_buckets - 1, c->slot_to_node,
                                c->slot_to_entry, c->dev, par, 0);
         }
-        if (c->fetch_pending) BGL_HIP(hipStreamWaitEvent(st, c->ev_miss, 0));  // rows of the misses
+        if (c->fetch_pending && c->fetch_stream != st)
+            BGL_HIP(hipStreamWaitEvent(st, c->ev_miss, 0));  // rows of the misses
         {
             Prof p(c, BGL_STAGE_INSERT_ROWS, st);
             dispatch_q(q, [&](auto Q) {
@@ -767,11 +789,16 @@ extern "C" int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const i
             });
         }
     } else {
-        if (c->fetch_pending) BGL_HIP(hipStreamWaitEvent(st, c->ev_miss, 0));
+        if (c->fetch_pending && c->fetch_stream != st) BGL_HIP(hipStreamWaitEvent(st, c->ev_miss, 0));
         hipLaunchKernelGGL(k_advance_tail, dim3(1), dim3(64), 0, st, c->dev, n_miss, par);
     }
     c->insert_calls += 1;
     BGL_HIP(hipGetLastError());
+    if (other_stream) {
+        BGL_HIP(hipEventRecord(c->ev_map, st));
+        c->map_pending = true;
+        c->map_stream = st;
+    }
     return BGL_OK;
 }
 
@@ -786,7 +813,17 @@ extern "C" int bgl_cache_set_write_through(bgl_cache_t *c, int enable)
 extern "C" int bgl_cache_wait_rows(bgl_cache_t *c, void *stream)
 {
     if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
-    if (c->fetch_pending) BGL_HIP(hipStreamWaitEvent(static_cast<hipStream_t>(stream), c->ev_miss, 0));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (c->fetch_pending && c->fetch_stream != st) BGL_HIP(hipStreamWaitEvent(st, c->ev_miss, 0));
+    return BGL_OK;
+}
+
+extern "C" int bgl_cache_wait_lists(bgl_cache_t *c, void *stream)
+{
+    if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (c->ev_listed_valid && st != c->last_main)
+        BGL_HIP(hipStreamWaitEvent(st, c->ev_listed, 0));
     return BGL_OK;
 }
 

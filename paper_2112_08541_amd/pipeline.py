@@ -1,17 +1,21 @@
-"""Two-deep minibatch preparation loop over the C ABI (binding calls only).
+"""Minibatch preparation loop over the C ABI (binding calls only).
 
 The paper overlaps the stages of minibatch preparation in an asynchronous
-pipeline (Sec. 3.3); on one GPU that reduces to this: while the misses of batch
-i cross the host link on the cache's side stream, batch i+1 is sampled on the
-main stream.  The cache state still advances strictly batch by batch
-(lookup i, insert i, lookup i+1, ...), so results do not depend on the overlap.
+pipeline (Sec. 3.3).  On one GPU the stage that sets the pace is the miss fetch
+over the host link, so the loop is built to keep the link busy:
 
-Per batch i, in enqueue order:
-  lookup_gather(i)   main: map lookup, miss/hit lists, hit gather; side: miss fetch
-  sample(i+1)        main, overlapping the fetch (second sampling workspace)
-  insert_fifo(i)     main; in write-through mode (default here) only the map update, which
-                     runs under the fetch; otherwise map update, wait for the fetch, row copy
-  host waits for sample(i+1)'s sizes only (one event), never for the whole stream
+  chain stream   lookup(i) -> lists(i) -> hit gather(i) -> miss fetch(i) -> lookup(i+1) ...
+                 one queue, so the next lookup starts the moment a fetch ends
+                 (a hand-over between streams costs ~20 us here)
+  work stream    sample(i+2), map update(i): they run while fetch(i) holds the link;
+                 both wait for hit gather(i), so nothing competes with the gather
+
+The cache is put in write-through mode (every lookup here is followed by the
+insert of all its misses), which makes the FIFO update a map update that needs no
+fetched row.  The cache state still advances strictly batch by batch (lookup i,
+insert i, lookup i+1, ...), so results do not depend on the overlap.  Sampling
+runs up to two batches ahead of the fetch, hence three sampling workspaces.
+The host waits only for each sampling call's sizes.
 """
 from __future__ import annotations
 
@@ -26,21 +30,19 @@ from . import binding as B
 class MinibatchPipeline:
     def __init__(self, graph: B.Graph, cache: B.Cache, batch: int, fanouts, row_bytes: int,
                  write_through: bool = True):
-        self.graph, self.cache = graph, cache
-        # every lookup here is followed by the insert of all its misses, so the miss fetch may
-        # fill the cache buffer itself (bgl_cache_set_write_through)
-        self.write_through = write_through
-        cache.set_write_through(write_through)
+        self.graph = graph
         self.fanouts = tuple(int(f) for f in fanouts)
         self.K = len(self.fanouts)
-        self.samplers = [B.Sampler(graph, batch, self.fanouts) for _ in range(2)]
+        self.samplers = [B.Sampler(graph, batch, self.fanouts) for _ in range(3)]
         self.cap = int(min(graph.num_nodes, batch * np.prod([1 + f for f in self.fanouts])))
         self.out_rows = torch.empty((self.cap, row_bytes), dtype=torch.uint8, device="cuda")
         self.out_slot = torch.empty(self.cap, dtype=torch.int32, device="cuda")
         self.miss_pos = torch.empty(self.cap, dtype=torch.int32, device="cuda")
-        self.side = torch.cuda.Stream()
-        self.main = torch.cuda.current_stream()
-        self.last_ids, self.last_n = None, 0    # input nodes of the most recent batch
+        self.chain = torch.cuda.Stream()          # lookups, hit gathers, miss fetches
+        self.work = torch.cuda.current_stream()   # sampling, map updates
+        self.write_through = write_through
+        self.last_ids, self.last_n = None, 0      # input nodes of the most recent batch
+        self.set_cache(cache)
 
     def set_cache(self, cache: B.Cache) -> None:
         self.cache = cache
@@ -50,41 +52,50 @@ class MinibatchPipeline:
             on_batch: Optional[Callable] = None):
         """Prepare `steps` minibatches; batch i uses seeds_dev[i % len] and rng_seeds[i % len]
         (xor the pass number, so that a second pass over the seeds samples differently).
-        on_batch(i, sampled_batch, n, pipeline) is called after insert_fifo(i) has been
-        enqueued; work it enqueues on the main stream sees batch i's complete outputs.
+        on_batch(i, sampled_batch, n, pipeline) is called after lookup_gather(i) and
+        insert_fifo(i) have been enqueued; work it enqueues on the chain stream after
+        cache.wait_rows(chain) sees batch i's complete outputs.
         Returns (n_input per batch, n_hit per batch)."""
         nb = seeds_dev.shape[0]
-        K, cache, main = self.K, self.cache, self.main
-        n_list, hit_list = [], []
-        smp = self.samplers[0]
-        sb = smp.sample(seeds_dev[0], int(rng_seeds[0]))
-        main.synchronize()
-        n = int(smp.counts_host[K])
-        status = int(smp.counts_host[B.BGL_COUNTS_LEN - 1])
-        ev = torch.cuda.Event()
-        for i in range(steps):
+        K, cache, chain, work = self.K, self.cache, self.chain, self.work
+        n_hits = torch.zeros(max(steps, 1), dtype=torch.int64).pin_memory()
+        n_list = []
+        sampled_ev = [torch.cuda.Event() for _ in range(3)]
+
+        def sample(i):
+            smp = self.samplers[i % 3]
+            b = i % nb
+            sb = smp.sample(seeds_dev[b], int(rng_seeds[b]) ^ (i // nb), stream=work)
+            sampled_ev[i % 3].record(work)
+            return sb
+
+        def sizes(i):
+            sampled_ev[i % 3].synchronize()
+            smp = self.samplers[i % 3]
+            status = int(smp.counts_host[B.BGL_COUNTS_LEN - 1])
             if status != 0:
                 raise B.BglError(status, "sampling reported an error on the device")
+            return int(smp.counts_host[K])
+
+        sbs = {0: sample(0)}
+        if steps > 1:
+            sbs[1] = sample(1)
+        for i in range(steps):
+            n = sizes(i)
+            sb = sbs.pop(i)
             ids = sb.input_nodes(self.cap)
+            chain.wait_event(sampled_ev[i % 3])
             cache.lookup_gather(ids, n, self.out_rows, self.out_slot, self.miss_pos,
-                                main_stream=main, side_stream=self.side)
-            nxt = i + 1
-            if nxt < steps:
-                b = nxt % nb
-                smp = self.samplers[nxt % 2]
-                sb_next = smp.sample(seeds_dev[b], int(rng_seeds[b]) ^ (nxt // nb), stream=main)
-                ev.record(main)
-            cache.insert_fifo(ids, self.miss_pos, -1, self.out_rows, stream=main)
+                                main_stream=chain, side_stream=chain,
+                                n_hit_ptr=n_hits.data_ptr() + 8 * i)
+            if i + 2 < steps:
+                # workspace (i+2) % 3 was batch i-1's; its fetch ended before hit gather(i)
+                cache.wait_lists(work)
+                sbs[i + 2] = sample(i + 2)
+            cache.insert_fifo(ids, self.miss_pos, -1, self.out_rows, stream=work)
             n_list.append(n)
             self.last_ids, self.last_n = ids, n
             if on_batch is not None:
                 on_batch(i, sb, n, self)
-            if nxt < steps:
-                ev.synchronize()      # sizes of batch i+1 and the hit count of batch i are on the host
-                hit_list.append(int(cache.n_hit_host[0]))
-                n = int(smp.counts_host[K])
-                status = int(smp.counts_host[B.BGL_COUNTS_LEN - 1])
-                sb = sb_next
         torch.cuda.synchronize()
-        hit_list.append(int(cache.n_hit_host[0]))
-        return n_list, hit_list
+        return n_list, [int(x) for x in n_hits[:steps]]
