@@ -41,6 +41,11 @@ def parse_args():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run three plain 1 GiB device-to-device copies (the known-size "
                          "kernel that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--two-level", type=float, default=0.0, metavar="FRACTION",
+                    help="also time the same batches with a FIFO tier in host memory (this fraction of the "
+                         "nodes) between the GPU cache and a feature store in ordinary host memory; "
+                         "reported beside the headline, not part of it")
+    ap.add_argument("--tier-threads", type=int, default=0, help="host threads of that tier (0 = min(cores, 16))")
     ap.add_argument("--cpu-batches", type=int, default=100,
                     help="batches of the same workload the oracle is timed on")
     return ap.parse_args()
@@ -225,6 +230,37 @@ def main():
         "sampled_edges_per_s": float(counts[B.BGL_MAX_HOPS + 1: B.BGL_MAX_HOPS + 1 + len(cfg.fanouts)].sum()) / (s_ms * 1e-3),
         "note": "bgl_sample_khop alone, %d batches back to back" % reps,
     }
+
+    if args.two_level > 0:
+        # Two-level cache (Sec. 3.2.3) on the same batches, outside the timed region of `value`:
+        # the feature table in ordinary host memory plays the graph store, the tier is a FIFO
+        # cache in page-locked memory in front of it.  The lookup blocks the host while the
+        # tier serves the GPU cache's misses.
+        store = np.array(w.features.view(np.uint8).reshape(cfg.num_nodes, rb), copy=True)
+        tier_rows = max(1, int(args.two_level * cfg.num_nodes))
+        steps2 = min(args.steps, 100)
+        tier = B.HostTier(store, tier_rows, pipe.cap, args.tier_threads)
+        c2 = B.Cache(cfg.cache_rows, None, num_nodes=cfg.num_nodes, row_bytes=rb)
+        pipe2 = MinibatchPipeline(graph, c2, cfg.batch, cfg.fanouts, rb, write_through=True, tier=tier)
+        torch.cuda.synchronize()
+        q0 = time.perf_counter()
+        n2, h2 = pipe2.run(seeds_dev, w.rng_seeds, steps2)
+        q1 = time.perf_counter()
+        n2, h2, t2 = np.array(n2), np.array(h2), np.array(pipe2.tier_hits)
+        ts = tier.stats()
+        result["two_level"] = {
+            "minibatches_per_s": steps2 / (q1 - q0), "ms_per_batch": 1e3 * (q1 - q0) / steps2, "steps": steps2,
+            "tier_rows": tier_rows, "tier_fraction_of_nodes": args.two_level, "host_threads": ts["threads"],
+            "gpu_hit_ratio": float(h2.sum()) / float(n2.sum()),
+            "tier_hit_ratio_of_gpu_misses": float(t2.sum()) / float((n2 - h2).sum()),
+            "store_rows_per_batch": float((n2 - h2 - t2).sum()) / steps2,
+            "store_GBps": float((n2 - h2 - t2).sum()) * rb / (q1 - q0) / 1e9,
+            "rows_kept_aside": ts["kept_aside"],
+            "note": "epoch from two empty levels; store = feature table in ordinary host memory",
+        }
+        c2.close()
+        tier.close()
+        del store
 
     if cfg.order == "po":
         # Proximity-aware ordering as the library computes it (once per epoch, outside the

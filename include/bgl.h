@@ -49,6 +49,7 @@ extern "C" {
 
 typedef struct bgl_graph bgl_graph_t;
 typedef struct bgl_cache bgl_cache_t;
+typedef struct bgl_host_tier bgl_host_tier_t;
 
 const char *bgl_last_error(void);
 
@@ -145,8 +146,10 @@ int bgl_sample_khop(const bgl_graph_t *g, const int32_t *seeds, int32_t num_seed
  *                  place by kernels over the host link) or in device memory.
  *                  Must stay alive and unchanged until bgl_cache_destroy
  *                  (features do not change during training, Sec. 4).
+ *                  May be null for a cache whose misses are only ever served
+ *                  through a host tier (bgl_cache_lookup_gather_tiered).
  * Errors: BGL_EINVAL (capacity_rows < 1, row_bytes < 16 or not a multiple of
- * 16, null/misaligned/pageable features, num_nodes < 1), BGL_ENOMEM, BGL_EHIP.
+ * 16, misaligned/pageable features, num_nodes < 1), BGL_ENOMEM, BGL_EHIP.
  */
 int bgl_cache_create(int64_t capacity_rows, int32_t row_bytes, const void *host_features,
                      int64_t num_nodes, bgl_cache_t **out);
@@ -272,6 +275,67 @@ int bgl_cache_stats(bgl_cache_t *c, uint64_t *lookups, uint64_t *hits, uint64_t 
 #define BGL_ALL_STAGES ((1 << BGL_NUM_STAGES) - 1)
 int bgl_cache_set_profiling(bgl_cache_t *c, int stage_mask);
 int bgl_cache_profile(bgl_cache_t *c, int stage, double *total_ms, int64_t *launches);
+
+/* ------------------------------------------------------------- host tier */
+
+/*
+ * Second cache level in host memory (Sec. 3.2.3: a CPU cache with the same
+ * policy as the GPU cache sits between it and the feature store).  The tier is
+ * a FIFO cache of capacity_rows rows in page-locked memory, which the GPU reads
+ * in place; rows it does not hold are copied in from `store` by host threads.
+ *   store           the feature store: num_nodes rows of row_bytes bytes in
+ *                   ordinary host memory (pageable or a mapped file will do);
+ *                   stays alive and unchanged until bgl_host_tier_destroy
+ *   max_batch_rows  the largest n a tiered lookup will be called with (sizes the
+ *                   page-locked lists and max_batch_rows staging rows)
+ *   num_threads     host threads for the tier's loops; 0 = min(cores, 16)
+ * Errors: BGL_EINVAL (null store, sizes out of range, row_bytes not a multiple
+ * of 16), BGL_ENOMEM (page-locked or host allocation failed), BGL_EHIP.
+ */
+int bgl_host_tier_create(const void *store, int64_t num_nodes, int32_t row_bytes,
+                         int64_t capacity_rows, int64_t max_batch_rows, int32_t num_threads,
+                         bgl_host_tier_t **out);
+/* Waits for the device to go idle first: kernels may still be reading the rows. */
+int bgl_host_tier_destroy(bgl_host_tier_t *t);
+
+/*
+ * bgl_cache_lookup_gather with the host tier behind the GPU cache (workflow of
+ * Sec. 3.2.3: GPU cache map, then the CPU cache for the GPU's misses, then the
+ * feature store; both levels updated first-in first-out).  Arguments as for
+ * bgl_cache_lookup_gather, except:
+ *   n_hit   ordinary host array of 2, set before return: hits in the GPU cache,
+ *           hits in the host tier (of the GPU cache's n - n_hit[0] misses)
+ * The tier handles the GPU cache's misses, in miss_pos order, as one FIFO batch:
+ * looked up against the tier's state at entry, then its own misses inserted in
+ * that order (the rule of bgl_cache_insert_fifo, tail advancing by their
+ * number).  The call blocks the host until the lists are known and the store
+ * rows are copied; the kernels that move rows found in the tier run on
+ * side_stream during that copy.  On return the fetch of all miss rows is
+ * enqueued on side_stream (bgl_cache_wait_rows as usual) and the tier is already
+ * updated; the GPU cache still needs its bgl_cache_insert_fifo.  ids must be
+ * distinct.  One tier serves one cache's calls in order; it is not thread-safe.
+ * Errors: as bgl_cache_lookup_gather, plus BGL_EINVAL (cache and tier differ in
+ * row_bytes or num_nodes; an id outside [0, num_nodes): no level is changed),
+ * BGL_ECAPACITY (n > max_batch_rows).
+ */
+int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t, const int32_t *ids, int64_t n,
+                                   void *out_rows, int32_t *out_slot, int32_t *miss_pos,
+                                   int64_t *n_hit, void *main_stream, void *side_stream);
+
+/*
+ * Tier state for tests: slot_to_node (capacity_rows ints, -1 = empty), the
+ * running tail, the tier's rows (capacity_rows * row_bytes bytes).  Any pointer
+ * may be null.  Host memory; call after the kernels that read the tier are done.
+ */
+int bgl_host_tier_export_state(bgl_host_tier_t *t, int32_t *slot_to_node, uint64_t *tail,
+                               void *buffer_rows);
+/*
+ * Lifetime counters: ids looked up, ids found, found rows that had to be copied
+ * aside because the same batch's insertions reused their slot; and the thread
+ * count in use.  Pointers may be null.
+ */
+int bgl_host_tier_stats(bgl_host_tier_t *t, uint64_t *lookups, uint64_t *hits, uint64_t *kept_aside,
+                        int32_t *threads);
 
 /* --------------------------------------------------------------- ordering */
 

@@ -31,6 +31,8 @@ EXPORTS = [
     "bgl_sample_khop", "bgl_cache_create", "bgl_cache_destroy", "bgl_cache_lookup_gather",
     "bgl_cache_insert_fifo", "bgl_cache_set_write_through", "bgl_cache_wait_rows", "bgl_cache_wait_lists", "bgl_cache_export_state", "bgl_cache_stats",
     "bgl_cache_set_profiling", "bgl_cache_profile",
+    "bgl_host_tier_create", "bgl_host_tier_destroy", "bgl_cache_lookup_gather_tiered",
+    "bgl_host_tier_export_state", "bgl_host_tier_stats",
     "bgl_order_bfs_sequence", "bgl_order_proximity", "bgl_order_choose_sequences",
     "bgl_order_shuffling_error",
 ]
@@ -73,6 +75,11 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     L.bgl_cache_set_write_through.argtypes = [vp, ci]
     L.bgl_cache_wait_rows.argtypes = [vp, vp]
     L.bgl_cache_wait_lists.argtypes = [vp, vp]
+    L.bgl_host_tier_create.argtypes = [vp, i64, i32, i64, i64, i32, C.POINTER(vp)]
+    L.bgl_host_tier_destroy.argtypes = [vp]
+    L.bgl_cache_lookup_gather_tiered.argtypes = [vp, vp, vp, i64, vp, vp, vp, C.POINTER(i64), vp, vp]
+    L.bgl_host_tier_export_state.argtypes = [vp, vp, C.POINTER(C.c_uint64), vp]
+    L.bgl_host_tier_stats.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(u64), C.POINTER(i32)]
     L.bgl_cache_export_state.argtypes = [vp, vp, C.POINTER(u64), vp]
     L.bgl_cache_stats.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(u64),
                                   C.POINTER(u64), C.POINTER(i32)]
@@ -233,7 +240,11 @@ class Cache:
     def __init__(self, capacity_rows: int, features, num_nodes: Optional[int] = None,
                  row_bytes: Optional[int] = None):
         _require_gpu()
-        if isinstance(features, int):  # raw address of page-locked or device memory
+        if features is None:           # misses are served through a HostTier only
+            if num_nodes is None or row_bytes is None:
+                raise ValueError("num_nodes and row_bytes are required without a backing store")
+            nn, rb, ptr = num_nodes, row_bytes, None
+        elif isinstance(features, int):  # raw address of page-locked or device memory
             if num_nodes is None or row_bytes is None:
                 raise ValueError("num_nodes and row_bytes are required with a raw address")
             nn, rb, ptr = num_nodes, row_bytes, features
@@ -273,6 +284,20 @@ class Cache:
             _dev_ptr(miss_pos, torch.int32),
             self.n_hit_host.data_ptr() if n_hit_ptr is None else n_hit_ptr, _stream_handle(main_stream),
             None if side_stream is None else int(side_stream.cuda_stream)))
+
+    def lookup_gather_tiered(self, tier: "HostTier", ids: torch.Tensor, n: int, out_rows: torch.Tensor,
+                             out_slot: torch.Tensor, miss_pos: torch.Tensor, main_stream=None,
+                             side_stream=None):
+        """Returns (hits in this cache, hits in the tier)."""
+        if n > 0 and (ids.numel() < n or out_slot.numel() < n or miss_pos.numel() < n or
+                      out_rows.numel() * out_rows.element_size() < n * self.row_bytes):
+            raise ValueError("an argument is smaller than n")
+        n_hit = (C.c_int64 * 2)(0, 0)
+        _check(lib().bgl_cache_lookup_gather_tiered(
+            self._h, tier._h, _dev_ptr(ids, torch.int32), n, _dev_ptr(out_rows),
+            _dev_ptr(out_slot, torch.int32), _dev_ptr(miss_pos, torch.int32), n_hit,
+            _stream_handle(main_stream), None if side_stream is None else int(side_stream.cuda_stream)))
+        return int(n_hit[0]), int(n_hit[1])
 
     def insert_fifo(self, ids: torch.Tensor, miss_pos: torch.Tensor, n_miss: int,
                     out_rows: torch.Tensor, stream=None) -> None:
@@ -324,6 +349,44 @@ class Cache:
         _check(lib().bgl_cache_profile(self._h, 100, C.byref(ms), C.byref(n)))
         out["event_overhead"] = (ms.value, 1)
         return out
+
+
+class HostTier:
+    """bgl_host_tier_* calls: FIFO cache level in page-locked host memory in front of `store`
+    (a C-contiguous numpy array of num_nodes rows, ordinary host memory)."""
+
+    def __init__(self, store: np.ndarray, capacity_rows: int, max_batch_rows: int, num_threads: int = 0):
+        _require_gpu()
+        if not store.flags["C_CONTIGUOUS"]:
+            raise ValueError("store must be C-contiguous")
+        self._store = store
+        self.num_nodes = int(store.shape[0])
+        self.row_bytes = int(store.strides[0])
+        self.capacity = int(capacity_rows)
+        h = C.c_void_p()
+        _check(lib().bgl_host_tier_create(store.ctypes.data, self.num_nodes, self.row_bytes, self.capacity,
+                                          int(max_batch_rows), int(num_threads), C.byref(h)))
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None) and lib is not None:
+            lib().bgl_host_tier_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def export_state(self, with_buffer: bool = True):
+        s2n = np.empty(self.capacity, dtype=np.int32)
+        tail = C.c_uint64(0)
+        buf = np.empty((self.capacity, self.row_bytes), dtype=np.uint8) if with_buffer else None
+        _check(lib().bgl_host_tier_export_state(self._h, s2n.ctypes.data, C.byref(tail),
+                                                buf.ctypes.data if with_buffer else None))
+        return s2n, int(tail.value), buf
+
+    def stats(self):
+        lk, ht, ka, th = C.c_uint64(0), C.c_uint64(0), C.c_uint64(0), C.c_int32(0)
+        _check(lib().bgl_host_tier_stats(self._h, C.byref(lk), C.byref(ht), C.byref(ka), C.byref(th)))
+        return dict(lookups=lk.value, hits=ht.value, kept_aside=ka.value, threads=th.value)
 
 
 def order_bfs_sequence(graph: Graph, train_nodes, root: int, stream=None) -> np.ndarray:

@@ -20,6 +20,7 @@
 #include <algorithm>
 #include <vector>
 
+#include "bgl_host_tier.h"
 #include "bgl_internal.h"
 
 namespace {
@@ -69,6 +70,7 @@ struct bgl_cache {
     // the stream the fetch ran on); ev_map: the last FIFO update is complete (recorded on the
     // update's stream when that is not the lookup's main stream).
     hipEvent_t ev_listed, ev_miss, ev_map;
+    hipEvent_t ev_ids;      // tiered lookup: the missed ids have reached the host
     hipStream_t last_main, fetch_stream, map_stream;
     bool fetch_pending;     // ev_miss marks a miss fetch that later work may have to wait for
     bool map_pending;       // ev_map marks a FIFO update the next lookup has to wait for
@@ -310,6 +312,58 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_miss(
     }
 }
 
+// Tiered lookup: the ids of the misses, in rank order, for the host tier
+// (page-locked host memory, complete for the host once the kernel has ended).
+__global__ __launch_bounds__(KEYS_PER_TILE) void k_export_miss_ids(const int32_t *__restrict__ miss_pos,
+                                                                   const int32_t *__restrict__ ids,
+                                                                   const CacheDev *dev, int32_t *out_ids)
+{
+    const int64_t r = (int64_t)blockIdx.x * KEYS_PER_TILE + threadIdx.x;
+    if (r < dev->n_miss_last) out_ids[r] = ids[miss_pos[r]];
+}
+
+// Tiered lookup: out[miss_pos[r]] = rows[src[k]] for the k-th listed miss, r =
+// rank[k]; rows is the host tier's page-locked region.  Same launch shape and
+// write-through rule as k_fetch_miss.
+template <int Q, bool WT>
+__global__ __launch_bounds__(COPY_THREADS) void k_fetch_rows(
+    const int32_t *__restrict__ rank, const int64_t *__restrict__ src, int64_t count,
+    const int32_t *__restrict__ miss_pos, int q, const uint4 *__restrict__ rows,
+    uint4 *__restrict__ out, const CacheDev *dev, uint4 *__restrict__ buffer, int64_t capacity, int par)
+{
+    const int qq = Q > 0 ? Q : q;
+    const int64_t n_miss = dev->n_miss_last;
+    const int64_t total = count * qq;
+    const int64_t start = n_miss > capacity ? n_miss - capacity : 0;
+    const unsigned long long tail = WT ? dev->tail[par] : 0ull;
+    const int64_t step = (int64_t)gridDim.x * (COPY_THREADS * COPY_UNROLL);
+    for (int64_t base = (int64_t)blockIdx.x * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
+         base - threadIdx.x < total; base += step) {
+        uint4 v[COPY_UNROLL];
+        int64_t dst[COPY_UNROLL], dst2[COPY_UNROLL];
+#pragma unroll
+        for (int k = 0; k < COPY_UNROLL; ++k) {
+            const int64_t idx = base + k * COPY_THREADS;
+            dst[k] = -1;
+            dst2[k] = -1;
+            if (idx < total) {
+                int64_t l; int c;
+                RowSplit<Q>::split(idx, q, l, c);
+                const int64_t r = rank[l];
+                v[k] = rows[src[l] * qq + c];
+                dst[k] = (int64_t)miss_pos[r] * qq + c;
+                if (WT && r >= start)
+                    dst2[k] = (int64_t)((tail + (unsigned long long)r) % (unsigned long long)capacity) * qq + c;
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < COPY_UNROLL; ++k) {
+            if (dst[k] >= 0) out[dst[k]] = v[k];
+            if (WT && dst2[k] >= 0) buffer[dst2[k]] = v[k];
+        }
+    }
+}
+
 // Map update: 16 lanes per inserted row.  Evict the slot's occupant (blank its
 // word, found through slot_to_entry), then read the new id's bucket with one
 // coalesced request, pick a free word with a wavefront ballot and claim it with
@@ -514,21 +568,23 @@ extern "C" int bgl_cache_create(int64_t capacity_rows, int32_t row_bytes,
     if (row_bytes < 16 || row_bytes % 16 != 0)
         BGL_FAIL(BGL_EINVAL, "row_bytes must be a positive multiple of 16 (got %d)", row_bytes);
     if (num_nodes < 1 || num_nodes > INT32_MAX) BGL_FAIL(BGL_EINVAL, "num_nodes out of range");
-    if (!host_features || !bgl::aligned(host_features, 16))
-        BGL_FAIL(BGL_EINVAL, "host_features is null or not 16-byte aligned");
+    if (!bgl::aligned(host_features, 16)) BGL_FAIL(BGL_EINVAL, "host_features is not 16-byte aligned");
 
     hipPointerAttribute_t attr;
-    if (hipPointerGetAttributes(&attr, host_features) != hipSuccess) {
-        (void)hipGetLastError();
-        BGL_FAIL(BGL_EINVAL, "host_features is neither page-locked host memory nor device memory");
-    }
+    attr.type = hipMemoryTypeHost;
     const char *feat_dev = nullptr;
-    if (attr.type == hipMemoryTypeHost || attr.type == hipMemoryTypeDevice ||
-        attr.type == hipMemoryTypeManaged) {
-        feat_dev = static_cast<const char *>(attr.devicePointer);
+    if (host_features) {  // null: misses are served through a host tier only
+        if (hipPointerGetAttributes(&attr, host_features) != hipSuccess) {
+            (void)hipGetLastError();
+            BGL_FAIL(BGL_EINVAL, "host_features is neither page-locked host memory nor device memory");
+        }
+        if (attr.type == hipMemoryTypeHost || attr.type == hipMemoryTypeDevice ||
+            attr.type == hipMemoryTypeManaged) {
+            feat_dev = static_cast<const char *>(attr.devicePointer);
+        }
+        if (!feat_dev)
+            BGL_FAIL(BGL_EINVAL, "host_features is neither page-locked host memory nor device memory");
     }
-    if (!feat_dev)
-        BGL_FAIL(BGL_EINVAL, "host_features is neither page-locked host memory nor device memory");
 
     bgl_cache *c = new (std::nothrow) bgl_cache();
     if (!c) BGL_FAIL(BGL_ENOMEM, "out of host memory");
@@ -574,7 +630,8 @@ extern "C" int bgl_cache_create(int64_t capacity_rows, int32_t row_bytes,
     if (hipStreamCreateWithFlags(&c->own_side, hipStreamNonBlocking) != hipSuccess ||
         hipEventCreateWithFlags(&c->ev_listed, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&c->ev_miss, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&c->ev_map, hipEventDisableTiming) != hipSuccess) {
+        hipEventCreateWithFlags(&c->ev_map, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_ids, hipEventDisableTiming) != hipSuccess) {
         bgl::set_error("stream/event creation failed");
         return fail(BGL_EHIP);
     }
@@ -599,6 +656,7 @@ extern "C" int bgl_cache_destroy(bgl_cache_t *c)
     if (c->ev_listed) (void)hipEventDestroy(c->ev_listed);
     if (c->ev_miss) (void)hipEventDestroy(c->ev_miss);
     if (c->ev_map) (void)hipEventDestroy(c->ev_map);
+    if (c->ev_ids) (void)hipEventDestroy(c->ev_ids);
     if (c->own_side) (void)hipStreamDestroy(c->own_side);
     (void)hipFree(c->buffer);
     (void)hipFree(c->table);
@@ -611,17 +669,13 @@ extern "C" int bgl_cache_destroy(bgl_cache_t *c)
     return BGL_OK;
 }
 
-extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64_t n,
-                                       void *out_rows, int32_t *out_slot, int32_t *miss_pos,
-                                       int64_t *n_hit_host, void *main_stream, void *side_stream)
+namespace {
+
+// First half of a lookup on stream ms: map lookup, lists, optional export of the
+// missed ids to the host (followed by ev_ids), hit gather, ev_listed.
+int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, int32_t *out_slot,
+                 int32_t *miss_pos, int64_t *n_hit_dev, hipStream_t ms, int32_t *export_ids)
 {
-    if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
-    if (n < 0 || n > INT32_MAX) BGL_FAIL(BGL_EINVAL, "n must be in [0, 2^31) (got %lld)", (long long)n);
-    if (n > 0 && (!ids || !out_rows || !out_slot || !miss_pos))
-        BGL_FAIL(BGL_EINVAL, "ids, out_rows, out_slot and miss_pos must not be null");
-    if (!bgl::aligned(out_rows, 16)) BGL_FAIL(BGL_EINVAL, "out_rows is not 16-byte aligned");
-    hipStream_t ms = static_cast<hipStream_t>(main_stream);
-    hipStream_t ss = side_stream ? static_cast<hipStream_t>(side_stream) : c->own_side;
     const int64_t tiles = bgl::ceil_div(n, KEYS_PER_TILE);
     if (tiles + 1 > c->mbs_cap) {
         BGL_HIP(hipStreamSynchronize(ms));
@@ -642,21 +696,7 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
         c->hit_cap = cap;
     }
     c->last_n = n;
-    // the hit count goes straight into the caller's page-locked word (no copy launch)
-    int64_t *n_hit_dev = nullptr;
-    if (n_hit_host) {
-        hipPointerAttribute_t attr;
-        if (hipPointerGetAttributes(&attr, n_hit_host) != hipSuccess || attr.type != hipMemoryTypeHost ||
-            !attr.devicePointer) {
-            (void)hipGetLastError();
-            BGL_FAIL(BGL_EINVAL, "n_hit_host must be page-locked host memory");
-        }
-        n_hit_dev = static_cast<int64_t *>(attr.devicePointer);
-    }
     const int q = c->row_bytes / 16;
-    const bool two_streams = ss != ms;
-    if (c->write_through && c->awaiting_insert)
-        BGL_FAIL(BGL_EINVAL, "write-through mode: the previous lookup's misses have not been inserted yet");
     if (c->fetch_pending && c->fetch_stream != ms) {
         // the previous call's fetch still reads that call's lists
         BGL_HIP(hipStreamWaitEvent(ms, c->ev_miss, 0));
@@ -677,7 +717,11 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
             hipLaunchKernelGGL(k_split_list, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), 0, ms, out_slot,
                                n, c->mbs, miss_pos, c->hit_pos, c->hit_pos + c->hit_cap, c->dev,
                                n_hit_dev);
+            if (export_ids)
+                hipLaunchKernelGGL(k_export_miss_ids, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), 0, ms,
+                                   miss_pos, ids, c->dev, export_ids);
         }
+        if (export_ids) BGL_HIP(hipEventRecord(c->ev_ids, ms));
         {
             Prof p(c, BGL_STAGE_GATHER_HIT, ms);
             dispatch_q(q, [&](auto Q) {
@@ -687,12 +731,58 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
                                    reinterpret_cast<uint4 *>(out_rows), c->dev);
             });
         }
-        // The miss fetch starts once the hit gather is done: host-link reads
-        // queued in the memory pipeline would otherwise stall the gather's HBM
-        // reads, and the fetch (milliseconds) loses nothing by starting a few
-        // tens of microseconds later.
-        BGL_HIP(hipEventRecord(c->ev_listed, ms));
-        if (two_streams) BGL_HIP(hipStreamWaitEvent(ss, c->ev_listed, 0));
+    } else {
+        hipLaunchKernelGGL(k_empty_lookup, dim3(1), dim3(64), 0, ms, c->dev, n_hit_dev);
+        if (export_ids) BGL_HIP(hipEventRecord(c->ev_ids, ms));
+    }
+    // The miss fetch starts once the hit gather is done: host-link reads
+    // queued in the memory pipeline would otherwise stall the gather's HBM
+    // reads, and the fetch (milliseconds) loses nothing by starting a few
+    // tens of microseconds later.
+    BGL_HIP(hipEventRecord(c->ev_listed, ms));
+    return BGL_OK;
+}
+
+int check_lookup_args(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, int32_t *out_slot,
+                      int32_t *miss_pos)
+{
+    if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
+    if (n < 0 || n > INT32_MAX) BGL_FAIL(BGL_EINVAL, "n must be in [0, 2^31) (got %lld)", (long long)n);
+    if (n > 0 && (!ids || !out_rows || !out_slot || !miss_pos))
+        BGL_FAIL(BGL_EINVAL, "ids, out_rows, out_slot and miss_pos must not be null");
+    if (!bgl::aligned(out_rows, 16)) BGL_FAIL(BGL_EINVAL, "out_rows is not 16-byte aligned");
+    if (c->write_through && c->awaiting_insert)
+        BGL_FAIL(BGL_EINVAL, "write-through mode: the previous lookup's misses have not been inserted yet");
+    return BGL_OK;
+}
+
+}  // namespace
+
+extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64_t n,
+                                       void *out_rows, int32_t *out_slot, int32_t *miss_pos,
+                                       int64_t *n_hit_host, void *main_stream, void *side_stream)
+{
+    int rc = check_lookup_args(c, ids, n, out_rows, out_slot, miss_pos);
+    if (rc != BGL_OK) return rc;
+    if (!c->features) BGL_FAIL(BGL_EINVAL, "the cache has no backing store: use bgl_cache_lookup_gather_tiered");
+    hipStream_t ms = static_cast<hipStream_t>(main_stream);
+    hipStream_t ss = side_stream ? static_cast<hipStream_t>(side_stream) : c->own_side;
+    // the hit count goes straight into the caller's page-locked word (no copy launch)
+    int64_t *n_hit_dev = nullptr;
+    if (n_hit_host) {
+        hipPointerAttribute_t attr;
+        if (hipPointerGetAttributes(&attr, n_hit_host) != hipSuccess || attr.type != hipMemoryTypeHost ||
+            !attr.devicePointer) {
+            (void)hipGetLastError();
+            BGL_FAIL(BGL_EINVAL, "n_hit_host must be page-locked host memory");
+        }
+        n_hit_dev = static_cast<int64_t *>(attr.devicePointer);
+    }
+    const int q = c->row_bytes / 16;
+    rc = lookup_phase(c, ids, n, out_rows, out_slot, miss_pos, n_hit_dev, ms, nullptr);
+    if (rc != BGL_OK) return rc;
+    if (n > 0) {
+        if (ss != ms) BGL_HIP(hipStreamWaitEvent(ss, c->ev_listed, 0));
         {
             Prof p(c, BGL_STAGE_FETCH_MISS, ss);
             // the small grid is for the host link only; an HBM-resident store wants the whole chip
@@ -716,11 +806,75 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
         BGL_HIP(hipEventRecord(c->ev_miss, ss));
         c->fetch_pending = true;
         c->fetch_stream = ss;
-    } else {
-        hipLaunchKernelGGL(k_empty_lookup, dim3(1), dim3(64), 0, ms, c->dev, n_hit_dev);
-        BGL_HIP(hipEventRecord(c->ev_listed, ms));
     }
     BGL_HIP(hipGetLastError());
+    if (c->write_through) {
+        c->awaiting_insert = true;
+        c->wt_ids = ids;
+        c->wt_miss_pos = miss_pos;
+    }
+    return BGL_OK;
+}
+
+extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t, const int32_t *ids,
+                                              int64_t n, void *out_rows, int32_t *out_slot,
+                                              int32_t *miss_pos, int64_t *n_hit, void *main_stream,
+                                              void *side_stream)
+{
+    int rc = check_lookup_args(c, ids, n, out_rows, out_slot, miss_pos);
+    if (rc != BGL_OK) return rc;
+    if (!t) BGL_FAIL(BGL_EINVAL, "tier handle is null");
+    if (bgl::tier_row_bytes(t) != c->row_bytes || bgl::tier_num_nodes(t) != c->num_nodes)
+        BGL_FAIL(BGL_EINVAL, "cache and host tier differ in row_bytes or num_nodes");
+    if (n > bgl::tier_max_batch(t))
+        BGL_FAIL(BGL_ECAPACITY, "n = %lld exceeds the tier's max_batch_rows", (long long)n);
+    hipStream_t ms = static_cast<hipStream_t>(main_stream);
+    hipStream_t ss = side_stream ? static_cast<hipStream_t>(side_stream) : c->own_side;
+    const int q = c->row_bytes / 16;
+    rc = lookup_phase(c, ids, n, out_rows, out_slot, miss_pos, bgl::tier_count_device(t), ms,
+                      bgl::tier_ids_device(t));
+    if (rc != BGL_OK) return rc;
+    BGL_HIP(hipGetLastError());
+    // the host continues as soon as the ids are there; the hit gather runs meanwhile
+    BGL_HIP(hipEventSynchronize(c->ev_ids));
+    const int64_t n_hit_gpu = *bgl::tier_count_host(t);
+    bgl::TierPlan plan;
+    rc = bgl::tier_lookup(t, n - n_hit_gpu, &plan);
+    if (rc != BGL_OK) return rc;
+    if (ss != ms) BGL_HIP(hipStreamWaitEvent(ss, c->ev_listed, 0));
+    const int par = (int)(c->insert_calls & 1);
+    auto fetch = [&](const int32_t *rank, const int64_t *src, int64_t count) {
+        if (count == 0) return;
+        Prof p(c, BGL_STAGE_FETCH_MISS, ss);
+        const int blocks = (int)std::min<int64_t>(copy_blocks(count, q), FETCH_BLOCKS);
+        dispatch_q(q, [&](auto Q) {
+            if (c->write_through)
+                hipLaunchKernelGGL((k_fetch_rows<decltype(Q)::value, true>), dim3(blocks), dim3(COPY_THREADS),
+                                   0, ss, rank, src, count, miss_pos, q,
+                                   reinterpret_cast<const uint4 *>(bgl::tier_rows_device(t)),
+                                   reinterpret_cast<uint4 *>(out_rows), c->dev,
+                                   reinterpret_cast<uint4 *>(c->buffer), c->capacity, par);
+            else
+                hipLaunchKernelGGL((k_fetch_rows<decltype(Q)::value, false>), dim3(blocks), dim3(COPY_THREADS),
+                                   0, ss, rank, src, count, miss_pos, q,
+                                   reinterpret_cast<const uint4 *>(bgl::tier_rows_device(t)),
+                                   reinterpret_cast<uint4 *>(out_rows), c->dev,
+                                   reinterpret_cast<uint4 *>(c->buffer), c->capacity, par);
+        });
+    };
+    // rows the tier holds cross the link while the host copies the others in from the store
+    fetch(plan.hit_rank, plan.hit_src, plan.n_hit);
+    rc = bgl::tier_insert(t);
+    if (rc != BGL_OK) return rc;
+    fetch(plan.miss_rank, plan.miss_src, plan.n_miss);
+    BGL_HIP(hipEventRecord(c->ev_miss, ss));
+    BGL_HIP(hipGetLastError());
+    c->fetch_pending = true;
+    c->fetch_stream = ss;
+    if (n_hit) {
+        n_hit[0] = n_hit_gpu;
+        n_hit[1] = plan.n_hit;
+    }
     if (c->write_through) {
         c->awaiting_insert = true;
         c->wt_ids = ids;

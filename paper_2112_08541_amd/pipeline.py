@@ -29,7 +29,7 @@ from . import binding as B
 
 class MinibatchPipeline:
     def __init__(self, graph: B.Graph, cache: B.Cache, batch: int, fanouts, row_bytes: int,
-                 write_through: bool = True):
+                 write_through: bool = True, tier: Optional[B.HostTier] = None):
         self.graph = graph
         self.fanouts = tuple(int(f) for f in fanouts)
         self.K = len(self.fanouts)
@@ -41,6 +41,7 @@ class MinibatchPipeline:
         self.chain = torch.cuda.Stream()          # lookups, hit gathers, miss fetches
         self.work = torch.cuda.current_stream()   # sampling, map updates
         self.write_through = write_through
+        self.tier = tier                          # second cache level in host memory (Sec. 3.2.3), or None
         self.last_ids, self.last_n = None, 0      # input nodes of the most recent batch
         self.set_cache(cache)
 
@@ -60,6 +61,7 @@ class MinibatchPipeline:
         K, cache, chain, work = self.K, self.cache, self.chain, self.work
         n_hits = torch.zeros(max(steps, 1), dtype=torch.int64).pin_memory()
         n_list = []
+        self.tier_hits = []
         sampled_ev = [torch.cuda.Event() for _ in range(3)]
 
         def sample(i):
@@ -85,9 +87,15 @@ class MinibatchPipeline:
             sb = sbs.pop(i)
             ids = sb.input_nodes(self.cap)
             chain.wait_event(sampled_ev[i % 3])
-            cache.lookup_gather(ids, n, self.out_rows, self.out_slot, self.miss_pos,
-                                main_stream=chain, side_stream=chain,
-                                n_hit_ptr=n_hits.data_ptr() + 8 * i)
+            if self.tier is None:
+                cache.lookup_gather(ids, n, self.out_rows, self.out_slot, self.miss_pos,
+                                    main_stream=chain, side_stream=chain,
+                                    n_hit_ptr=n_hits.data_ptr() + 8 * i)
+            else:
+                # blocks until the host tier has served the GPU cache's misses
+                n_hits[i], h2 = cache.lookup_gather_tiered(self.tier, ids, n, self.out_rows, self.out_slot,
+                                                           self.miss_pos, main_stream=chain, side_stream=chain)
+                self.tier_hits.append(h2)
             if i + 2 < steps:
                 # workspace (i+2) % 3 was batch i-1's; its fetch ended before hit gather(i)
                 cache.wait_lists(work)

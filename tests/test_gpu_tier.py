@@ -1,0 +1,212 @@
+"""GPU parity for the two-level cache (GPU cache, then the FIFO tier in host
+memory, then the feature store; Sec. 3.2.3) against two oracle caches chained
+the same way: the second one sees the first one's misses, in order, as its
+batch.  Bytes, slots, lists and both levels' states must be equal."""
+import numpy as np
+import pytest
+
+from helpers import assert_state_equal
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch_mod():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return torch
+
+
+@pytest.fixture(scope="module")
+def B(torch_mod):
+    from paper_2112_08541_amd import binding
+    binding.lib()
+    return binding
+
+
+def assert_tier_state_equal(tier, oc2, what):
+    s2n, tail, buf = tier.export_state(True)
+    o_s2n = oc2.slot_to_node
+    assert tail == oc2.tail, what
+    assert np.array_equal(s2n, o_s2n), what
+    live = o_s2n >= 0
+    assert np.array_equal(buf[live], oc2.buffer[live]), what
+
+
+def run_tiered_stream(B, torch, feats, cap1, cap2, batches, write_through, threads, side=True):
+    import oracle
+    N, rb = feats.shape[0], feats.shape[1] * feats.itemsize
+    store = np.ascontiguousarray(feats.view(np.uint8).reshape(N, rb))      # ordinary host memory
+    max_n = max(max((len(b) for b in batches), default=1), 1)
+    gc = B.Cache(cap1, None, num_nodes=N, row_bytes=rb)
+    tier = B.HostTier(store, cap2, max_n, threads)
+    oc1, oc2 = oracle.Cache(cap1, feats), oracle.Cache(cap2, feats)
+    if write_through:
+        gc.set_write_through(True)
+    side_stream = torch.cuda.Stream() if side else None
+    for bi, ids in enumerate(batches):
+        n = len(ids)
+        ids_t = (torch.tensor(ids, dtype=torch.int32, device="cuda") if n
+                 else torch.empty(1, dtype=torch.int32, device="cuda"))
+        out = torch.full((max(n, 1), rb), 0xCD, dtype=torch.uint8, device="cuda")
+        out_slot = torch.full((max(n, 1),), -7, dtype=torch.int32, device="cuda")
+        miss_pos = torch.full((max(n, 1),), -7, dtype=torch.int32, device="cuda")
+        h1, h2 = gc.lookup_gather_tiered(tier, ids_t, n, out, out_slot, miss_pos, side_stream=side_stream)
+        gc.insert_fifo(ids_t, miss_pos, -1, out)
+        gc.wait_rows()
+        torch.cuda.synchronize()
+        # oracle: level 1, then level 2 on level 1's misses, both updated first-in first-out
+        o_out, o_slot, o_miss, o_hit = oc1.lookup_gather(ids)
+        mids = np.asarray(ids, dtype=np.int32)[o_miss] if n else np.empty(0, np.int32)
+        o2_out, o2_slot, o2_miss, o2_hit = oc2.lookup_gather(mids)
+        oc2.insert_fifo(mids, o2_miss, o2_out)
+        oc1.insert_fifo(ids, o_miss, o_out)
+        what = f"batch {bi}"
+        assert (h1, h2) == (o_hit, o2_hit), what
+        assert np.array_equal(out_slot[:n].cpu().numpy(), o_slot), what
+        assert np.array_equal(miss_pos[: n - h1].cpu().numpy(), o_miss), what
+        assert np.array_equal(out[:n].cpu().numpy(), o_out), what
+        assert np.array_equal(o2_out, o_out[o_miss]), what     # the tier level returns the store's bytes
+        assert_state_equal(gc, oc1, what)
+        assert_tier_state_equal(tier, oc2, what)
+    st = tier.stats()
+    assert (st["lookups"], st["hits"]) == oc2.stats()
+    return gc, tier
+
+
+def zipf_batches(rng, N, count, lo, hi, big=None):
+    batches = []
+    for b in range(count):
+        size = int(rng.integers(lo, hi)) if b != 5 or big is None else big
+        batches.append(list(dict.fromkeys((rng.zipf(1.2, size) % N).tolist())))
+    batches.insert(3, [])
+    batches.insert(8, batches[7])
+    return batches
+
+
+@pytest.mark.parametrize("dim,dtype", [(4, np.float32), (100, np.float32), (128, np.float32), (264, np.uint16)])
+@pytest.mark.parametrize("write_through", [False, True])
+def test_tiered_random_streams(B, torch_mod, dim, dtype, write_through):
+    rng = np.random.default_rng(100 + dim)
+    N = 20000
+    feats = (rng.standard_normal((N, dim)).astype(np.float32) if dtype == np.float32
+             else rng.integers(0, 2**16, (N, dim), dtype=np.uint16))
+    # batch 5 has more misses than either level has slots
+    batches = zipf_batches(rng, N, 14, 1, 2500, big=9000)
+    run_tiered_stream(B, torch_mod, feats, 1500, 4000, batches, write_through, threads=4)
+
+
+@pytest.mark.parametrize("cap1,cap2,threads", [(64, 300, 1), (1, 1, 3), (500, 100, 2), (3000, 18000, 0)])
+def test_tiered_capacity_corners(B, torch_mod, cap1, cap2, threads):
+    """A tier smaller than a batch's misses (rows pass through staging, found rows are kept
+    aside before their slot is reused), single slots, a tier smaller than the GPU cache,
+    a tier that ends up holding nearly the whole store."""
+    rng = np.random.default_rng(cap1 * 7 + cap2)
+    N = 20000
+    feats = rng.standard_normal((N, 100)).astype(np.float32)
+    batches = zipf_batches(rng, N, 12, 200, 3000)
+    _, tier = run_tiered_stream(B, torch_mod, feats, cap1, cap2, batches, True, threads, side=(threads != 2))
+    if cap2 == 300:
+        assert tier.stats()["kept_aside"] > 0      # the corner this size is here for
+    assert tier.stats()["threads"] == (threads or tier.stats()["threads"])
+
+
+def test_tiered_uniform_ids_many_chunks(B, torch_mod):
+    """Batches long enough for many host tasks and several fetch grid strides."""
+    rng = np.random.default_rng(5)
+    N = 300000
+    feats = rng.integers(0, 2**32, (N, 25 * 4), dtype=np.uint32).view(np.float32)
+    batches = [rng.permutation(N)[: int(rng.integers(60000, 90000))].tolist() for _ in range(5)]
+    run_tiered_stream(B, torch_mod, feats, 40000, 120000, batches, True, threads=0)
+
+
+def test_tiered_argument_errors(B, torch_mod):
+    torch = torch_mod
+    N, rb = 1000, 64
+    store = np.random.default_rng(1).integers(0, 255, (N, rb), dtype=np.uint8)
+    gc = B.Cache(100, None, num_nodes=N, row_bytes=rb)
+    tier = B.HostTier(store, 200, 50, 2)
+    ids = torch.arange(60, dtype=torch.int32, device="cuda")
+    out = torch.zeros((60, rb), dtype=torch.uint8, device="cuda")
+    slot = torch.zeros(60, dtype=torch.int32, device="cuda")
+    mp = torch.zeros(60, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.BglError) as e:      # the cache has no store of its own
+        gc.lookup_gather(ids, 10, out, slot, mp)
+    assert e.value.code == B.BGL_EINVAL
+    with pytest.raises(B.BglError) as e:      # more ids than the tier was sized for
+        gc.lookup_gather_tiered(tier, ids, 60, out, slot, mp)
+    assert e.value.code == B.BGL_ECAPACITY
+    other = B.HostTier(np.zeros((N, 32), dtype=np.uint8), 10, 50, 1)
+    with pytest.raises(B.BglError) as e:      # row width differs
+        gc.lookup_gather_tiered(other, ids, 10, out, slot, mp)
+    assert e.value.code == B.BGL_EINVAL
+    bad = ids.clone()
+    bad[3] = N + 5
+    with pytest.raises(B.BglError) as e:      # id out of range: nothing changes
+        gc.lookup_gather_tiered(tier, bad, 10, out, slot, mp)
+    assert e.value.code == B.BGL_EINVAL
+    torch.cuda.synchronize()
+    s2n, tail, _ = tier.export_state(False)
+    assert tail == 0 and (s2n == -1).all()
+    assert gc.export_state(False)[1] == 0
+    # and the pair still works afterwards
+    h1, h2 = gc.lookup_gather_tiered(tier, ids, 10, out, slot, mp)
+    gc.insert_fifo(ids, mp, -1, out)
+    gc.wait_rows()
+    torch.cuda.synchronize()
+    assert (h1, h2) == (0, 0)
+    assert np.array_equal(out[:10].cpu().numpy(), store[:10])
+    h1, h2 = gc.lookup_gather_tiered(tier, ids, 20, out, slot, mp)
+    gc.insert_fifo(ids, mp, -1, out)
+    torch.cuda.synchronize()
+    assert (h1, h2) == (10, 0)
+
+
+def test_tiered_pipeline_as_benchmarked_matches_oracle(torch_mod, B):
+    """The configuration `bench.py --two-level` times, on the full-size mid workload: sampling
+    ahead, tiered lookups on the chain stream, write-through GPU cache.  Every batch's
+    outputs and both levels' final states."""
+    import oracle
+    from helpers import OraclePipeline, assert_batch_equal
+    from paper_2112_08541_amd import inputs
+    from paper_2112_08541_amd.pipeline import MinibatchPipeline
+    torch = torch_mod
+    cfg = inputs.CONFIGS["mid"]
+    w = inputs.make_workload(cfg, pinned=False)
+    rb = cfg.row_bytes
+    store = np.ascontiguousarray(w.features.view(np.uint8).reshape(cfg.num_nodes, rb))
+    graph = B.Graph(w.row_ptr, w.col)
+    cache = B.Cache(cfg.cache_rows, None, num_nodes=cfg.num_nodes, row_bytes=rb)
+    tier_rows = int(0.3 * cfg.num_nodes)
+    pipe = MinibatchPipeline(graph, cache, cfg.batch, cfg.fanouts, rb, write_through=True, tier=None)
+    tier = B.HostTier(store, tier_rows, pipe.cap, 0)
+    pipe.tier = tier
+    seeds_dev = torch.from_numpy(w.seed_batches).cuda()
+    got = {}
+
+    def grab(i, sb, n, p):
+        torch.cuda.synchronize()
+        c = p.samplers[i % 3].counts_host.numpy()
+        K = len(cfg.fanouts)
+        nf, nnz = c[: K + 1].astype(np.int64), c[B.BGL_MAX_HOPS + 1: B.BGL_MAX_HOPS + 1 + K].astype(np.int64)
+        n_hit = n - int((p.out_slot[:n] < 0).sum())
+        got[i] = dict(n_frontier=nf, nnz=nnz, n=n, n_hit=n_hit,
+                      input_nodes=sb.input_nodes(n).cpu().numpy(),
+                      row_ptr=[sb.row_ptr(h, int(nf[h])).cpu().numpy() for h in range(len(nnz))],
+                      col_local=[sb.col_local(h, int(nnz[h])).cpu().numpy() for h in range(len(nnz))],
+                      out_slot=p.out_slot[:n].cpu().numpy(), miss_pos=p.miss_pos[: n - n_hit].cpu().numpy(),
+                      out_rows=p.out_rows[:n].cpu().numpy())
+
+    steps = 6
+    n_list, hit_list = pipe.run(seeds_dev, w.rng_seeds, steps, on_batch=grab)
+    op = OraclePipeline(w)
+    oc2 = oracle.Cache(tier_rows, w.features)
+    for b in range(steps):
+        o = op.run_batch(w.seed_batches[b], w.rng_seeds[b])
+        assert_batch_equal(got[b], o, f"tiered batch {b}")
+        mids = o["input_nodes"][o["miss_pos"]]
+        o2_out, _, o2_miss, o2_hit = oc2.lookup_gather(mids)
+        oc2.insert_fifo(mids, o2_miss, o2_out)
+        assert (n_list[b], hit_list[b], pipe.tier_hits[b]) == (o["n"], o["n_hit"], o2_hit)
+    assert_state_equal(cache, op.cache, "tiered pipeline")
+    assert_tier_state_equal(tier, oc2, "tiered pipeline")
