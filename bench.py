@@ -41,6 +41,8 @@ def parse_args():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run three plain 1 GiB device-to-device copies (the known-size "
                          "kernel that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--graph-placement", choices=("config", "device", "host_pinned"), default="config",
+                    help="where the CSR lives: as the configuration says (default), in HBM, or in page-locked host memory")
     ap.add_argument("--two-level", type=float, default=0.0, metavar="FRACTION",
                     help="also time the same batches with a FIFO tier in host memory (this fraction of the "
                          "nodes) between the GPU cache and a feature store in ordinary host memory; "
@@ -92,7 +94,8 @@ def main():
     torch.cuda.set_device(0)
     w = inputs.make_workload(cfg, pinned=True)
     feat_t = w.features.ctypes.data      # address of the page-locked feature table
-    placement = B.BGL_HOST_PINNED if cfg.graph_placement == "host_pinned" else B.BGL_DEVICE
+    where = cfg.graph_placement if args.graph_placement == "config" else args.graph_placement
+    placement = B.BGL_HOST_PINNED if where == "host_pinned" else B.BGL_DEVICE
     graph = B.Graph(w.row_ptr, w.col, placement)
     seeds_dev = torch.from_numpy(w.seed_batches).cuda()      # inputs resident in HBM
     nb = cfg.num_batches
@@ -146,7 +149,8 @@ def main():
             "workload": f"{cfg.name}: N={cfg.num_nodes} E={w.num_edges} power-law graph, "
                         f"{cfg.feat_dtype} x {cfg.feat_dim} features, batch {cfg.batch}, "
                         f"fanout {list(cfg.fanouts)}, FIFO cache {cfg.cache_rows} rows, "
-                        f"{cfg.order} seed order, epoch from an empty cache",
+                        f"{cfg.order} seed order, epoch from an empty cache"
+                        + ("" if args.graph_placement == "config" else f", CSR placement {where}"),
             "row_bytes": rb,
             "mean_input_nodes": tot_n / args.steps,
             "hit_ratio_cumulative": tot_hit / max(tot_n, 1),
