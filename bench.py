@@ -43,6 +43,9 @@ def parse_args():
                          "kernel that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--graph-placement", choices=("config", "device", "host_pinned"), default="config",
                     help="where the CSR lives: as the configuration says (default), in HBM, or in page-locked host memory")
+    ap.add_argument("--feature-placement", choices=("host_pinned", "device"), default="host_pinned",
+                    help="where the feature table lives: page-locked host memory (the path this benchmark is "
+                         "about, default) or a copy in HBM (then a miss is an HBM gather; context only)")
     ap.add_argument("--two-level", type=float, default=0.0, metavar="FRACTION",
                     help="also time the same batches with a FIFO tier in host memory (this fraction of the "
                          "nodes) between the GPU cache and a feature store in ordinary host memory; "
@@ -94,6 +97,14 @@ def main():
     torch.cuda.set_device(0)
     w = inputs.make_workload(cfg, pinned=True)
     feat_t = w.features.ctypes.data      # address of the page-locked feature table
+    feat_dev = None
+    if args.feature_placement == "device":
+        feat_dev = torch.empty((cfg.num_nodes, cfg.row_bytes), dtype=torch.uint8, device="cuda")
+        step = max(1, (1 << 30) // cfg.row_bytes)
+        fb = w.features.view(np.uint8).reshape(cfg.num_nodes, cfg.row_bytes)
+        for lo in range(0, cfg.num_nodes, step):
+            feat_dev[lo:lo + step].copy_(torch.from_numpy(fb[lo:lo + step]))
+        feat_t = feat_dev.data_ptr()
     where = cfg.graph_placement if args.graph_placement == "config" else args.graph_placement
     placement = B.BGL_HOST_PINNED if where == "host_pinned" else B.BGL_DEVICE
     graph = B.Graph(w.row_ptr, w.col, placement)
@@ -150,7 +161,8 @@ def main():
                         f"{cfg.feat_dtype} x {cfg.feat_dim} features, batch {cfg.batch}, "
                         f"fanout {list(cfg.fanouts)}, FIFO cache {cfg.cache_rows} rows, "
                         f"{cfg.order} seed order, epoch from an empty cache"
-                        + ("" if args.graph_placement == "config" else f", CSR placement {where}"),
+                        + ("" if args.graph_placement == "config" else f", CSR placement {where}")
+                        + ("" if feat_dev is None else ", feature table in HBM"),
             "row_bytes": rb,
             "mean_input_nodes": tot_n / args.steps,
             "hit_ratio_cumulative": tot_hit / max(tot_n, 1),

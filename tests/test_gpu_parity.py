@@ -377,6 +377,30 @@ def test_overlapped_pipeline_as_benchmarked_matches_oracle(torch_mod, B, write_t
     assert_state_equal(cache, op.cache, "overlapped")
 
 
+def test_overlapped_pipeline_full_epoch_counts_and_final_state(torch_mod, B):
+    """The whole benchmarked epoch (mid, 200 batches, overlapped, write-through): per-batch
+    input and hit counts, the last batch's rows, and the cache state at the end."""
+    from paper_2112_08541_amd.pipeline import MinibatchPipeline
+    inputs = _inputs()
+    cfg = inputs.CONFIGS["mid"]
+    w = inputs.make_workload(cfg, pinned=True)
+    graph = B.Graph(w.row_ptr, w.col)
+    cache = B.Cache(cfg.cache_rows, w.features.ctypes.data, num_nodes=cfg.num_nodes, row_bytes=cfg.row_bytes)
+    pipe = MinibatchPipeline(graph, cache, cfg.batch, cfg.fanouts, cfg.row_bytes)
+    seeds_dev = torch_mod.from_numpy(w.seed_batches).cuda()
+    steps = cfg.num_batches
+    n_list, hit_list = pipe.run(seeds_dev, w.rng_seeds, steps)
+    last_rows = pipe.out_rows[: n_list[-1]].cpu().numpy()
+    last_ids = pipe.last_ids[: n_list[-1]].cpu().numpy()
+    op = OraclePipeline(w)
+    for b in range(steps):
+        o = op.run_batch(w.seed_batches[b], w.rng_seeds[b])
+        assert (n_list[b], hit_list[b]) == (o["n"], o["n_hit"]), f"batch {b}"
+    assert np.array_equal(last_ids, o["input_nodes"])
+    assert np.array_equal(last_rows, o["out_rows"])
+    assert_state_equal(cache, op.cache, "full epoch")
+
+
 def test_pipeline_bfs_order_config_full_size_and_locality():
     inputs = _inputs()
     po = run_config(inputs.CONFIGS["bfs"], 10, check_every=5)
