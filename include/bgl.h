@@ -283,14 +283,17 @@ int bgl_cache_profile(bgl_cache_t *c, int stage, double *total_ms, int64_t *laun
  * policy as the GPU cache sits between it and the feature store).  The tier is
  * a FIFO cache of capacity_rows rows in page-locked memory, which the GPU reads
  * in place; rows it does not hold are copied in from `store` by host threads.
+ * Its map (node -> row, 4 bytes per node) and slot tables live in device memory
+ * of the current device and are looked up and updated by kernels.
  *   store           the feature store: num_nodes rows of row_bytes bytes in
  *                   ordinary host memory (pageable or a mapped file will do);
  *                   stays alive and unchanged until bgl_host_tier_destroy
- *   max_batch_rows  the largest n a tiered lookup will be called with (sizes the
- *                   page-locked lists and max_batch_rows staging rows)
- *   num_threads     host threads for the tier's loops; 0 = min(cores, 16)
+ *   max_batch_rows  the largest n a tiered lookup will be called with; the
+ *                   page-locked region holds capacity_rows + max_batch_rows rows
+ *   num_threads     host threads that copy rows (the calling thread drives the
+ *                   GPU meanwhile); 0 = min(cores, 16) - 1
  * Errors: BGL_EINVAL (null store, sizes out of range, row_bytes not a multiple
- * of 16), BGL_ENOMEM (page-locked or host allocation failed), BGL_EHIP.
+ * of 16), BGL_ENOMEM (page-locked, host or device allocation failed), BGL_EHIP.
  */
 int bgl_host_tier_create(const void *store, int64_t num_nodes, int32_t row_bytes,
                          int64_t capacity_rows, int64_t max_batch_rows, int32_t num_threads,
@@ -310,10 +313,12 @@ int bgl_host_tier_destroy(bgl_host_tier_t *t);
  * that order (the rule of bgl_cache_insert_fifo, tail advancing by their
  * number).  The call blocks the host until the lists are known and the store
  * rows are copied; the kernels that move rows found in the tier run on
- * side_stream during that copy.  On return the fetch of all miss rows is
- * enqueued on side_stream (bgl_cache_wait_rows as usual) and the tier is already
- * updated; the GPU cache still needs its bgl_cache_insert_fifo.  ids must be
- * distinct.  One tier serves one cache's calls in order; it is not thread-safe.
+ * side_stream during that copy, and the copied rows follow chunk by chunk.  On
+ * return the fetch of all miss rows is enqueued on side_stream
+ * (bgl_cache_wait_rows as usual) and the tier's update on main_stream; the GPU
+ * cache still needs its bgl_cache_insert_fifo.  ids, out_slot and miss_pos must
+ * stay untouched until main_stream has passed this call.  ids must be distinct.
+ * One tier serves one cache's calls in order; it is not thread-safe.
  * Errors: as bgl_cache_lookup_gather, plus BGL_EINVAL (cache and tier differ in
  * row_bytes or num_nodes; an id outside [0, num_nodes): no level is changed),
  * BGL_ECAPACITY (n > max_batch_rows).
@@ -324,18 +329,18 @@ int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t, const int
 
 /*
  * Tier state for tests: slot_to_node (capacity_rows ints, -1 = empty), the
- * running tail, the tier's rows (capacity_rows * row_bytes bytes).  Any pointer
- * may be null.  Host memory; call after the kernels that read the tier are done.
+ * running tail, the tier's rows by slot (capacity_rows * row_bytes bytes, zeros
+ * for empty slots).  Any pointer may be null.  Host memory; waits for the device.
  */
 int bgl_host_tier_export_state(bgl_host_tier_t *t, int32_t *slot_to_node, uint64_t *tail,
                                void *buffer_rows);
 /*
- * Lifetime counters: ids looked up, ids found, found rows that had to be copied
- * aside because the same batch's insertions reused their slot; and the thread
+ * Lifetime counters: ids looked up, ids found, host wall time spent copying rows
+ * from the store (milliseconds) over `batches` served batches; and the thread
  * count in use.  Pointers may be null.
  */
-int bgl_host_tier_stats(bgl_host_tier_t *t, uint64_t *lookups, uint64_t *hits, uint64_t *kept_aside,
-                        int32_t *threads);
+int bgl_host_tier_stats(bgl_host_tier_t *t, uint64_t *lookups, uint64_t *hits, double *copy_ms,
+                        uint64_t *batches, int32_t *threads);
 
 /* --------------------------------------------------------------- ordering */
 

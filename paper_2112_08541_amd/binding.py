@@ -79,7 +79,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     L.bgl_host_tier_destroy.argtypes = [vp]
     L.bgl_cache_lookup_gather_tiered.argtypes = [vp, vp, vp, i64, vp, vp, vp, C.POINTER(i64), vp, vp]
     L.bgl_host_tier_export_state.argtypes = [vp, vp, C.POINTER(C.c_uint64), vp]
-    L.bgl_host_tier_stats.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(u64), C.POINTER(i32)]
+    L.bgl_host_tier_stats.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(C.c_double), C.POINTER(u64), C.POINTER(i32)]
     L.bgl_cache_export_state.argtypes = [vp, vp, C.POINTER(u64), vp]
     L.bgl_cache_stats.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(u64),
                                   C.POINTER(u64), C.POINTER(i32)]
@@ -384,9 +384,9 @@ class HostTier:
         return s2n, int(tail.value), buf
 
     def stats(self):
-        lk, ht, ka, th = C.c_uint64(0), C.c_uint64(0), C.c_uint64(0), C.c_int32(0)
-        _check(lib().bgl_host_tier_stats(self._h, C.byref(lk), C.byref(ht), C.byref(ka), C.byref(th)))
-        return dict(lookups=lk.value, hits=ht.value, kept_aside=ka.value, threads=th.value)
+        lk, ht, nb, th, ms = C.c_uint64(0), C.c_uint64(0), C.c_uint64(0), C.c_int32(0), C.c_double(0)
+        _check(lib().bgl_host_tier_stats(self._h, C.byref(lk), C.byref(ht), C.byref(ms), C.byref(nb), C.byref(th)))
+        return dict(lookups=lk.value, hits=ht.value, copy_ms=ms.value, batches=nb.value, threads=th.value)
 
 
 def order_bfs_sequence(graph: Graph, train_nodes, root: int, stream=None) -> np.ndarray:

@@ -227,6 +227,9 @@ constexpr int COPY_UNROLL = 4;
 // flight saturate the host link; much more than that queues host reads in front
 // of the concurrent hit gather's HBM reads and slows it by an order of magnitude.
 constexpr int FETCH_BLOCKS = 64;
+// Tiered lookup: rows the host threads copy per chunk before that chunk's fetch is launched.
+constexpr int64_t TIER_CHUNK_ROWS = 49152;
+constexpr int64_t TIER_FIRST_CHUNK_ROWS = 4096;
 
 // out[i] = buffer[out_slot[i]] for every hit i (taken from the hit list, so the
 // work is proportional to the hits).  Consecutive lanes take consecutive
@@ -312,24 +315,17 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_miss(
     }
 }
 
-// Tiered lookup: the ids of the misses, in rank order, for the host tier
-// (page-locked host memory, complete for the host once the kernel has ended).
-__global__ __launch_bounds__(KEYS_PER_TILE) void k_export_miss_ids(const int32_t *__restrict__ miss_pos,
-                                                                   const int32_t *__restrict__ ids,
-                                                                   const CacheDev *dev, int32_t *out_ids)
-{
-    const int64_t r = (int64_t)blockIdx.x * KEYS_PER_TILE + threadIdx.x;
-    if (r < dev->n_miss_last) out_ids[r] = ids[miss_pos[r]];
-}
-
-// Tiered lookup: out[miss_pos[r]] = rows[src[k]] for the k-th listed miss, r =
-// rank[k]; rows is the host tier's page-locked region.  Same launch shape and
+// Tiered lookup: out[miss_pos[r]] = rows[p] for listed misses l0 <= l < l0 + count
+// of the GPU cache, r = rank[l]; rows is the host tier's page-locked ring and
+// p = pos[l] (rows the tier held) or, with SEQ, (ptail + l) mod ring (rows the
+// host threads have just brought in, in list order).  Same launch shape and
 // write-through rule as k_fetch_miss.
-template <int Q, bool WT>
+template <int Q, bool WT, bool SEQ>
 __global__ __launch_bounds__(COPY_THREADS) void k_fetch_rows(
-    const int32_t *__restrict__ rank, const int64_t *__restrict__ src, int64_t count,
-    const int32_t *__restrict__ miss_pos, int q, const uint4 *__restrict__ rows,
-    uint4 *__restrict__ out, const CacheDev *dev, uint4 *__restrict__ buffer, int64_t capacity, int par)
+    const int32_t *__restrict__ rank, const int32_t *__restrict__ pos, int64_t l0, int64_t count,
+    unsigned long long ptail, int64_t ring, const int32_t *__restrict__ miss_pos, int q,
+    const uint4 *__restrict__ rows, uint4 *__restrict__ out, const CacheDev *dev,
+    uint4 *__restrict__ buffer, int64_t capacity, int par)
 {
     const int qq = Q > 0 ? Q : q;
     const int64_t n_miss = dev->n_miss_last;
@@ -349,8 +345,11 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_rows(
             if (idx < total) {
                 int64_t l; int c;
                 RowSplit<Q>::split(idx, q, l, c);
+                l += l0;
                 const int64_t r = rank[l];
-                v[k] = rows[src[l] * qq + c];
+                const int64_t p = SEQ ? (int64_t)((ptail + (unsigned long long)l) % (unsigned long long)ring)
+                                      : (int64_t)pos[l];
+                v[k] = rows[p * qq + c];
                 dst[k] = (int64_t)miss_pos[r] * qq + c;
                 if (WT && r >= start)
                     dst2[k] = (int64_t)((tail + (unsigned long long)r) % (unsigned long long)capacity) * qq + c;
@@ -671,10 +670,10 @@ extern "C" int bgl_cache_destroy(bgl_cache_t *c)
 
 namespace {
 
-// First half of a lookup on stream ms: map lookup, lists, optional export of the
-// missed ids to the host (followed by ev_ids), hit gather, ev_listed.
+// First half of a lookup on stream ms: map lookup, lists, with a host tier its
+// lookup for the misses (followed by ev_ids), hit gather, ev_listed.
 int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, int32_t *out_slot,
-                 int32_t *miss_pos, int64_t *n_hit_dev, hipStream_t ms, int32_t *export_ids)
+                 int32_t *miss_pos, int64_t *n_hit_dev, hipStream_t ms, bgl_host_tier *tier)
 {
     const int64_t tiles = bgl::ceil_div(n, KEYS_PER_TILE);
     if (tiles + 1 > c->mbs_cap) {
@@ -717,11 +716,12 @@ int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, in
             hipLaunchKernelGGL(k_split_list, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), 0, ms, out_slot,
                                n, c->mbs, miss_pos, c->hit_pos, c->hit_pos + c->hit_cap, c->dev,
                                n_hit_dev);
-            if (export_ids)
-                hipLaunchKernelGGL(k_export_miss_ids, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), 0, ms,
-                                   miss_pos, ids, c->dev, export_ids);
         }
-        if (export_ids) BGL_HIP(hipEventRecord(c->ev_ids, ms));
+        if (tier) {
+            const int rc = bgl::tier_enqueue_lookup(tier, ids, miss_pos, &c->dev->n_miss_last, n, ms);
+            if (rc != BGL_OK) return rc;
+            BGL_HIP(hipEventRecord(c->ev_ids, ms));
+        }
         {
             Prof p(c, BGL_STAGE_GATHER_HIT, ms);
             dispatch_q(q, [&](auto Q) {
@@ -733,7 +733,11 @@ int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, in
         }
     } else {
         hipLaunchKernelGGL(k_empty_lookup, dim3(1), dim3(64), 0, ms, c->dev, n_hit_dev);
-        if (export_ids) BGL_HIP(hipEventRecord(c->ev_ids, ms));
+        if (tier) {
+            const int rc = bgl::tier_enqueue_lookup(tier, ids, miss_pos, &c->dev->n_miss_last, 0, ms);
+            if (rc != BGL_OK) return rc;
+            BGL_HIP(hipEventRecord(c->ev_ids, ms));
+        }
     }
     // The miss fetch starts once the hit gather is done: host-link reads
     // queued in the memory pipeline would otherwise stall the gather's HBM
@@ -831,48 +835,65 @@ extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t
     hipStream_t ms = static_cast<hipStream_t>(main_stream);
     hipStream_t ss = side_stream ? static_cast<hipStream_t>(side_stream) : c->own_side;
     const int q = c->row_bytes / 16;
-    rc = lookup_phase(c, ids, n, out_rows, out_slot, miss_pos, bgl::tier_count_device(t), ms,
-                      bgl::tier_ids_device(t));
+    rc = lookup_phase(c, ids, n, out_rows, out_slot, miss_pos, bgl::tier_count_device(t), ms, t);
     if (rc != BGL_OK) return rc;
     BGL_HIP(hipGetLastError());
-    // the host continues as soon as the ids are there; the hit gather runs meanwhile
+    // the host continues as soon as the lists are there; the hit gather runs meanwhile
     BGL_HIP(hipEventSynchronize(c->ev_ids));
-    const int64_t n_hit_gpu = *bgl::tier_count_host(t);
     bgl::TierPlan plan;
-    rc = bgl::tier_lookup(t, n - n_hit_gpu, &plan);
+    rc = bgl::tier_begin(t, n, &plan);
     if (rc != BGL_OK) return rc;
     if (ss != ms) BGL_HIP(hipStreamWaitEvent(ss, c->ev_listed, 0));
     const int par = (int)(c->insert_calls & 1);
-    auto fetch = [&](const int32_t *rank, const int64_t *src, int64_t count) {
+    const uint4 *rows = reinterpret_cast<const uint4 *>(bgl::tier_rows_device(t));
+    auto fetch = [&](auto seq, const int32_t *rank, const int32_t *pos, int64_t l0, int64_t count) {
         if (count == 0) return;
         Prof p(c, BGL_STAGE_FETCH_MISS, ss);
         const int blocks = (int)std::min<int64_t>(copy_blocks(count, q), FETCH_BLOCKS);
         dispatch_q(q, [&](auto Q) {
             if (c->write_through)
-                hipLaunchKernelGGL((k_fetch_rows<decltype(Q)::value, true>), dim3(blocks), dim3(COPY_THREADS),
-                                   0, ss, rank, src, count, miss_pos, q,
-                                   reinterpret_cast<const uint4 *>(bgl::tier_rows_device(t)),
+                hipLaunchKernelGGL((k_fetch_rows<decltype(Q)::value, true, decltype(seq)::value>), dim3(blocks),
+                                   dim3(COPY_THREADS), 0, ss, rank, pos, l0, count,
+                                   (unsigned long long)plan.ptail, plan.ring, miss_pos, q, rows,
                                    reinterpret_cast<uint4 *>(out_rows), c->dev,
                                    reinterpret_cast<uint4 *>(c->buffer), c->capacity, par);
             else
-                hipLaunchKernelGGL((k_fetch_rows<decltype(Q)::value, false>), dim3(blocks), dim3(COPY_THREADS),
-                                   0, ss, rank, src, count, miss_pos, q,
-                                   reinterpret_cast<const uint4 *>(bgl::tier_rows_device(t)),
+                hipLaunchKernelGGL((k_fetch_rows<decltype(Q)::value, false, decltype(seq)::value>), dim3(blocks),
+                                   dim3(COPY_THREADS), 0, ss, rank, pos, l0, count,
+                                   (unsigned long long)plan.ptail, plan.ring, miss_pos, q, rows,
                                    reinterpret_cast<uint4 *>(out_rows), c->dev,
                                    reinterpret_cast<uint4 *>(c->buffer), c->capacity, par);
         });
     };
-    // rows the tier holds cross the link while the host copies the others in from the store
-    fetch(plan.hit_rank, plan.hit_src, plan.n_hit);
-    rc = bgl::tier_insert(t);
-    if (rc != BGL_OK) return rc;
-    fetch(plan.miss_rank, plan.miss_src, plan.n_miss);
+    // Rows the tier holds cross the link while host threads bring the others in from the
+    // store, a chunk at a time; each chunk is fetched as soon as it is in place.
+    fetch(std::false_type{}, plan.hit_rank, plan.hit_pos, 0, plan.n_hit);
+    // (small chunks first, so the link starts early; the copy threads outrun the link)
+    if (plan.n_miss > 0) {
+        rc = bgl::tier_copy_start(t);
+        if (rc != BGL_OK) { bgl::tier_abort(t); return rc; }
+        int64_t chunk = plan.n_hit > TIER_CHUNK_ROWS ? TIER_CHUNK_ROWS : TIER_FIRST_CHUNK_ROWS;
+        for (int64_t launched = 0; launched < plan.n_miss;) {
+            const int64_t ready = bgl::tier_copy_progress(t);
+            if (ready - launched >= chunk || ready == plan.n_miss) {
+                fetch(std::true_type{}, plan.miss_rank, nullptr, launched, ready - launched);
+                launched = ready;
+                chunk = std::min<int64_t>(2 * chunk, TIER_CHUNK_ROWS);
+            } else {
+                __builtin_ia32_pause();
+            }
+        }
+        bgl::tier_copy_wait(t);
+    }
     BGL_HIP(hipEventRecord(c->ev_miss, ss));
+    // the tier's map changes after this call's lists are final and before the next lookup
+    rc = bgl::tier_enqueue_update(t, ids, miss_pos, ms);
+    if (rc != BGL_OK) return rc;
     BGL_HIP(hipGetLastError());
     c->fetch_pending = true;
     c->fetch_stream = ss;
     if (n_hit) {
-        n_hit[0] = n_hit_gpu;
+        n_hit[0] = plan.n_hit_gpu;
         n_hit[1] = plan.n_hit;
     }
     if (c->write_through) {

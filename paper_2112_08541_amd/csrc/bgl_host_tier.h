@@ -1,8 +1,10 @@
 // Second cache level in host memory (BGL paper, Sec. 3.2.3: a CPU cache with the
 // same FIFO policy sits behind the GPU cache, in front of the feature store).
-// Internal interface between the tier (host threads) and the GPU cache's tiered
-// lookup, which launches the kernels that read the tier's page-locked rows.
+// Internal interface between the tier and the GPU cache's tiered lookup, which
+// owns the stream order and launches the kernels that read the tier's rows.
 #pragma once
+
+#include <hip/hip_runtime.h>
 
 #include <cstdint>
 
@@ -12,34 +14,39 @@ namespace bgl {
 
 struct TierPlan {
     // Misses of the GPU cache are numbered by rank r (their order in miss_pos).
-    // Ranks found in the tier and ranks fetched from the store, each in rank
-    // order, with the row of the page-locked region (tier buffer rows first,
-    // staging rows behind them) that holds each one's features.
-    const int32_t *hit_rank;   // device-visible, n_hit entries
-    const int64_t *hit_src;
+    int64_t n_hit_gpu;         // hits in the GPU cache (read back with the tier's counts)
+    const int32_t *hit_rank;   // device: ranks the tier holds, ascending ...
+    const int32_t *hit_pos;    // ... and the ring position of each one's row
     int64_t n_hit;
-    const int32_t *miss_rank;  // device-visible, n_miss entries
-    const int64_t *miss_src;
-    int64_t n_miss;
+    const int32_t *miss_rank;  // device: ranks it does not hold, ascending; the j-th one's row
+    int64_t n_miss;            // goes to ring position (ptail + j) mod ring
+    uint64_t ptail;
+    int64_t ring;
 };
 
-// Page-locked list the GPU writes the missed node ids to (device-visible
-// address) and its host view; capacity max_batch_rows ids.
-int32_t *tier_ids_device(bgl_host_tier *t);
-// Page-locked word for the GPU cache's hit count (device-visible address, host view).
+// Page-locked words the device writes counts to: [0] hits in the GPU cache
+// (the cache's lookup writes it), [1] tier hits, [2] tier misses, [3] bad-id flag.
 int64_t *tier_count_device(bgl_host_tier *t);
-const volatile int64_t *tier_count_host(bgl_host_tier *t);
 const char *tier_rows_device(bgl_host_tier *t);
 int64_t tier_max_batch(const bgl_host_tier *t);
 int32_t tier_row_bytes(const bgl_host_tier *t);
 int64_t tier_num_nodes(const bgl_host_tier *t);
 
-// Step 1 (reads only): look the m ids up, list hits and misses, and move every
-// hit row that step 2 is about to overwrite into the staging rows.  After it the
-// rows of plan->hit_* may be read by the GPU.  Returns a BGL status.
-int tier_lookup(bgl_host_tier *t, int64_t m, TierPlan *plan);
-// Step 2: bring the missed rows in from the store and enter them first-in
-// first-out.  After it the rows of plan->miss_* may be read.
-int tier_insert(bgl_host_tier *t);
+// Enqueue on st: look ids[miss_pos[r]], r < *n_ranks_dev <= n_upper, up in the
+// tier's map, build the lists, send the missing ids and the counts to the host.
+int tier_enqueue_lookup(bgl_host_tier *t, const int32_t *ids, const int32_t *miss_pos,
+                        const long long *n_ranks_dev, int64_t n_upper, hipStream_t st);
+// Once st has passed that point: read the counts (n = size of the GPU cache's
+// lookup), check the ids.  Nothing has changed yet if this fails.
+int tier_begin(bgl_host_tier *t, int64_t n, TierPlan *plan);
+// Host threads start copying the rows of the tier misses, in list order, from the store
+// to their ring positions; tier_copy_progress tells how many leading rows are in place
+// (monotone, reaches n_miss); tier_copy_wait ends the job.
+int tier_copy_start(bgl_host_tier *t);
+int64_t tier_copy_progress(bgl_host_tier *t);
+void tier_copy_wait(bgl_host_tier *t);
+// Enqueue the first-in first-out update of the map on st and close the batch.
+int tier_enqueue_update(bgl_host_tier *t, const int32_t *ids, const int32_t *miss_pos, hipStream_t st);
+void tier_abort(bgl_host_tier *t);
 
 }  // namespace bgl

@@ -2,15 +2,25 @@
 // the GPU cache uses the same policy as the GPU cache, i.e. FIFO; the misses of
 // both levels come from the feature store, the graph store servers' stand-in).
 //
-// Host code only.  The tier's rows live in page-locked memory that kernels read
-// in place over the host link, so a row found here is never copied by the CPU; a
-// row brought in from the store is copied once, into the slot FIFO assigns to it
-// (or into a staging row when it does not enter the tier), and read from there.
-// Node ids are dense, so the map is a plain array node -> slot (4 bytes per
-// node of host memory).  The loops over a batch's ids run on a small pool of
-// threads; a batch's ids are distinct, which makes every parallel loop here
-// write disjoint entries.
+// Only the tier's ROWS live in host memory (page-locked, read in place by the
+// fetch kernels over the host link, never copied by the CPU once they are
+// there).  Its bookkeeping lives in HBM, where random access is cheap: node ids
+// are dense, so the map is a plain array node -> row position (4 bytes per
+// node), looked up by a kernel for the GPU cache's misses right behind that
+// cache's own lookup; the same kernels list the rows the tier holds and the ids
+// it does not.  The host only feeds rows: its threads copy the missing rows
+// from the store into the positions first-in first-out assigns, in chunks, and
+// each chunk's fetch kernel is launched as soon as its rows are in place.
+//
+// Rows sit in a ring of capacity_rows + max_batch_rows positions, filled in
+// insertion order.  The newest capacity_rows insertions are the tier's content
+// (logical slot = insertion number mod capacity_rows, as in the GPU cache); a
+// row's position is reused only after capacity_rows + max_batch_rows further
+// insertions, so a row found by a batch's lookup is still intact after that
+// same batch's insertions have evicted it, and no copy ever has to wait for a
+// fetch.
 #include <atomic>
+#include <chrono>
 #include <condition_variable>
 #include <cstring>
 #include <functional>
@@ -24,12 +34,18 @@
 
 namespace {
 
-// parallel_for over [0, n) in chunks; the caller works too and returns when all chunks are done.
+// A few host threads that run one job at a time: tasks 0..tasks-1, claimed in
+// increasing order.  run() also works on the calling thread and returns when
+// all tasks are done; start() returns at once, done_prefix() tells how many
+// leading tasks are complete (the caller launches work on them meanwhile) and
+// wait() ends the job.
 class Pool {
 public:
+    using Fn = std::function<void(int64_t)>;
+
     explicit Pool(int threads)
     {
-        for (int i = 1; i < threads; ++i) workers_.emplace_back([this] { loop(); });
+        for (int i = 0; i < std::max(threads, 1); ++i) workers_.emplace_back([this] { loop(); });
     }
     ~Pool()
     {
@@ -40,31 +56,41 @@ public:
         cv_.notify_all();
         for (auto &t : workers_) t.join();
     }
-    int threads() const { return (int)workers_.size() + 1; }
+    int threads() const { return (int)workers_.size(); }
 
-    void run(int64_t n, int64_t chunk, const std::function<void(int64_t, int64_t, int64_t)> &fn)
+    void start(int64_t tasks, const Fn &fn)
     {
-        if (n <= 0) return;
-        const int64_t chunks = (n + chunk - 1) / chunk;
-        if (chunks == 1 || workers_.empty()) {
-            for (int64_t k = 0; k < chunks; ++k) fn(k, k * chunk, std::min(n, (k + 1) * chunk));
-            return;
-        }
+        if ((int64_t)done_.size() < tasks) done_ = std::vector<std::atomic<uint8_t>>((size_t)tasks);
+        for (int64_t k = 0; k < tasks; ++k) done_[(size_t)k].store(0, std::memory_order_relaxed);
+        prefix_ = 0;
         {
             std::lock_guard<std::mutex> lk(m_);
             fn_ = &fn;
-            n_ = n;
-            chunk_ = chunk;
-            chunks_ = chunks;
+            tasks_ = tasks;
             next_.store(0);
             busy_ = (int)workers_.size();
             ++gen_;
         }
         cv_.notify_all();
-        work();
+    }
+    // number of leading tasks that are complete (their writes are visible to the caller)
+    int64_t done_prefix()
+    {
+        while (prefix_ < tasks_ && done_[(size_t)prefix_].load(std::memory_order_acquire)) ++prefix_;
+        return prefix_;
+    }
+    void wait()
+    {
         std::unique_lock<std::mutex> lk(m_);
-        done_.wait(lk, [this] { return busy_ == 0; });
+        idle_.wait(lk, [this] { return busy_ == 0; });
         fn_ = nullptr;
+    }
+    void run(int64_t tasks, const Fn &fn)
+    {
+        if (tasks <= 0) return;
+        start(tasks, fn);
+        work();
+        wait();
     }
 
 private:
@@ -72,8 +98,9 @@ private:
     {
         for (;;) {
             const int64_t k = next_.fetch_add(1);
-            if (k >= chunks_) return;
-            (*fn_)(k, k * chunk_, std::min(n_, (k + 1) * chunk_));
+            if (k >= tasks_) return;
+            (*fn_)(k);
+            done_[(size_t)k].store(1, std::memory_order_release);
         }
     }
     void loop()
@@ -89,23 +116,131 @@ private:
             work();
             {
                 std::lock_guard<std::mutex> lk(m_);
-                if (--busy_ == 0) done_.notify_one();
+                if (--busy_ == 0) idle_.notify_one();
             }
         }
     }
 
     std::vector<std::thread> workers_;
     std::mutex m_;
-    std::condition_variable cv_, done_;
-    const std::function<void(int64_t, int64_t, int64_t)> *fn_ = nullptr;
-    int64_t n_ = 0, chunk_ = 1, chunks_ = 0;
+    std::condition_variable cv_, idle_;
+    const Fn *fn_ = nullptr;
+    int64_t tasks_ = 0;
     std::atomic<int64_t> next_{0};
+    std::vector<std::atomic<uint8_t>> done_;
+    int64_t prefix_ = 0;
     int busy_ = 0;
     uint64_t gen_ = 0;
     bool stop_ = false;
 };
 
-constexpr int64_t CHUNK = 2048;  // ids per task
+constexpr int TT = 256;            // lookups per workgroup
+constexpr int64_t COPY_TASK = 128;  // rows per host task
+
+using namespace bgl;
+
+__global__ void k_fill_i32(int32_t *p, int64_t n, int32_t v)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = v;
+}
+
+// Map lookup for the GPU cache's misses: rank r (r-th entry of miss_pos) -> row
+// position in the ring or -1; per-workgroup count of the -1s.
+__global__ __launch_bounds__(TT) void k_tier_probe(const int32_t *__restrict__ ids,
+                                                   const int32_t *__restrict__ miss_pos,
+                                                   const long long *__restrict__ n_ranks,
+                                                   int64_t num_nodes, const int32_t *__restrict__ node_pos,
+                                                   int32_t *rank_pos, int32_t *tile_miss, int64_t *counts_host)
+{
+    __shared__ int sh[TT / kWave];
+    const int64_t m = *n_ranks;
+    if ((int64_t)blockIdx.x * TT >= m) return;
+    const int64_t r = (int64_t)blockIdx.x * TT + threadIdx.x;
+    int p = -1;
+    if (r < m) {
+        const int32_t id = ids[miss_pos[r]];
+        if (id < 0 || (int64_t)id >= num_nodes) counts_host[3] = 1;  // the host refuses the batch
+        else if (node_pos) p = node_pos[id];
+        rank_pos[r] = p;
+    }
+    const uint64_t missed = __ballot(r < m && p < 0);
+    if ((threadIdx.x & (kWave - 1)) == 0) sh[threadIdx.x / kWave] = __popcll(missed);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int t = 0;
+#pragma unroll
+        for (int k = 0; k < TT / kWave; ++k) t += sh[k];
+        tile_miss[blockIdx.x] = t;
+    }
+}
+
+// Ordered lists: ranks the tier holds (with their row positions), ranks it does
+// not (and their node ids, written to page-locked host memory for the copy
+// threads).  The last workgroup publishes both counts to the host.
+__global__ __launch_bounds__(TT) void k_tier_lists(const int32_t *__restrict__ ids,
+                                                   const int32_t *__restrict__ miss_pos,
+                                                   const long long *__restrict__ n_ranks,
+                                                   const int32_t *__restrict__ rank_pos,
+                                                   const int32_t *__restrict__ tile_miss,
+                                                   int32_t *hit_rank, int32_t *hit_pos, int32_t *miss_rank,
+                                                   int32_t *miss_ids_host, int64_t *counts_host)
+{
+    __shared__ int sh_scan[TT / kWave];
+    __shared__ int sh_base;
+    const int64_t m = *n_ranks;
+    const int64_t tiles = (m + TT - 1) / TT;
+    if ((int64_t)blockIdx.x >= tiles) {
+        if (m == 0 && blockIdx.x == 0 && threadIdx.x == 0) { counts_host[1] = 0; counts_host[2] = 0; }
+        return;
+    }
+    int part = 0;
+    for (int t = threadIdx.x; t < (int)blockIdx.x; t += TT) part += tile_miss[t];
+    int tot;
+    (void)block_excl_scan<TT>(part, sh_scan, tot);
+    if (threadIdx.x == 0) sh_base = tot;
+    const int64_t r = (int64_t)blockIdx.x * TT + threadIdx.x;
+    const int p = r < m ? rank_pos[r] : 0;
+    const int flag = (r < m && p < 0) ? 1 : 0;
+    const int ex = block_excl_scan<TT>(flag, sh_scan, tot);  // its barriers publish sh_base
+    const int j = sh_base + ex;
+    if (flag) {
+        miss_rank[j] = (int32_t)r;
+        miss_ids_host[j] = ids[miss_pos[r]];
+    } else if (r < m) {
+        hit_rank[r - j] = (int32_t)r;
+        hit_pos[r - j] = p;
+    }
+    if ((int64_t)blockIdx.x == tiles - 1 && threadIdx.x == 0) {
+        const long long n_miss = sh_base + tot;
+        counts_host[1] = m - n_miss;
+        counts_host[2] = n_miss;
+    }
+}
+
+// First-in first-out update of the bookkeeping: miss j >= start takes logical
+// slot (tail + j) mod capacity and ring position (ptail + j) mod ring; the
+// slot's former occupant leaves the map.  The ids of a batch are distinct and an
+// occupant is never one of them, so no two lanes write the same entry.
+__global__ __launch_bounds__(TT) void k_tier_update(const int32_t *__restrict__ ids,
+                                                    const int32_t *__restrict__ miss_pos,
+                                                    const int32_t *__restrict__ miss_rank, int64_t start,
+                                                    int64_t n_miss, unsigned long long tail,
+                                                    unsigned long long ptail, int64_t capacity, int64_t ring,
+                                                    int32_t *node_pos, int32_t *slot_node, int32_t *slot_pos)
+{
+    const int64_t j = start + (int64_t)blockIdx.x * TT + threadIdx.x;
+    if (j >= n_miss) return;
+    const int32_t id = ids[miss_pos[miss_rank[j]]];
+    const int64_t s = (int64_t)((tail + (unsigned long long)j) % (unsigned long long)capacity);
+    const int32_t pp = (int32_t)((ptail + (unsigned long long)j) % (unsigned long long)ring);
+    const int32_t old = slot_node[s];
+    if (old >= 0) node_pos[old] = -1;
+    slot_node[s] = id;
+    slot_pos[s] = pp;
+    node_pos[id] = pp;
+}
 
 }  // namespace
 
@@ -113,153 +248,139 @@ struct bgl_host_tier {
     const char *store = nullptr;  // num_nodes rows, ordinary host memory
     int64_t num_nodes = 0;
     int32_t row_bytes = 0;
-    int64_t capacity = 0;
+    int64_t capacity = 0;   // logical slots
     int64_t max_batch = 0;
-    // page-locked: capacity tier rows, then max_batch staging rows
-    char *rows = nullptr;
+    int64_t ring = 0;       // row positions = capacity + max_batch
+    int device = 0;
+    char *rows = nullptr;   // page-locked, ring rows
     char *rows_dev = nullptr;
-    // page-locked lists: ids | hit_rank | miss_rank | hit_src | miss_src | GPU hit count
-    char *lists = nullptr;
-    char *lists_dev = nullptr;
-    int32_t *ids = nullptr, *hit_rank = nullptr, *miss_rank = nullptr;
-    int64_t *hit_src = nullptr, *miss_src = nullptr;
-    std::vector<int32_t> node_to_slot, slot_to_node, slot_rank;
-    std::vector<uint32_t> slot_epoch;  // batch number of the last lookup that found the slot's row
-    std::vector<int64_t> src_row;      // per rank, while a batch is being served
-    std::vector<int64_t> chunk_hits;
-    uint64_t tail = 0;
-    uint32_t epoch = 0;
+    char *pinned = nullptr;  // page-locked: counts[8] | miss ids[max_batch]
+    char *pinned_dev = nullptr;
+    // device: bookkeeping and per-batch lists
+    int32_t *node_pos = nullptr, *slot_node = nullptr, *slot_pos = nullptr;
+    int32_t *rank_pos = nullptr, *tile_miss = nullptr, *hit_rank = nullptr, *hit_pos = nullptr, *miss_rank = nullptr;
+    uint64_t tail = 0;      // insertions so far (host mirrors of what the kernels are told)
+    uint64_t ptail = 0;     // next ring position
     uint64_t lookups = 0, hits = 0;
-    std::atomic<uint64_t> kept_aside{0};  // found rows copied to staging before their slot was reused
-    // between tier_lookup and tier_insert
+    double copy_ms = 0;
+    uint64_t batches = 0;
+    // the batch being served
     int64_t cur_m = 0, cur_hit = 0, cur_miss = 0;
     bool serving = false;
     Pool *pool = nullptr;
+    Pool::Fn copy_fn;
+    std::chrono::steady_clock::time_point copy_t0;
+
+    volatile int64_t *counts() const { return reinterpret_cast<volatile int64_t *>(pinned); }
+    const int32_t *miss_ids() const { return reinterpret_cast<const int32_t *>(pinned + 64); }
 };
 
 namespace bgl {
 
-int32_t *tier_ids_device(bgl_host_tier *t) { return reinterpret_cast<int32_t *>(t->lists_dev); }
-int64_t *tier_count_device(bgl_host_tier *t) { return reinterpret_cast<int64_t *>(t->lists_dev + 28 * (size_t)t->max_batch); }
-const volatile int64_t *tier_count_host(bgl_host_tier *t) { return reinterpret_cast<const volatile int64_t *>(t->lists + 28 * (size_t)t->max_batch); }
+int64_t *tier_count_device(bgl_host_tier *t) { return reinterpret_cast<int64_t *>(t->pinned_dev); }
 const char *tier_rows_device(bgl_host_tier *t) { return t->rows_dev; }
 int64_t tier_max_batch(const bgl_host_tier *t) { return t->max_batch; }
 int32_t tier_row_bytes(const bgl_host_tier *t) { return t->row_bytes; }
 int64_t tier_num_nodes(const bgl_host_tier *t) { return t->num_nodes; }
 
-int tier_lookup(bgl_host_tier *t, int64_t m, TierPlan *plan)
+int tier_enqueue_lookup(bgl_host_tier *t, const int32_t *ids, const int32_t *miss_pos,
+                        const long long *n_ranks_dev, int64_t n_upper, hipStream_t st)
 {
-    if (m < 0 || m > t->max_batch) BGL_FAIL(BGL_ECAPACITY, "%lld ids exceed the tier's max_batch_rows %lld",
-                                            (long long)m, (long long)t->max_batch);
-    if (t->serving) BGL_FAIL(BGL_EINVAL, "host tier: the previous batch has not been inserted");
-    t->epoch += 1;
-    if (t->epoch == 0) {  // wrapped: forget old marks
-        std::fill(t->slot_epoch.begin(), t->slot_epoch.end(), 0u);
-        t->epoch = 1;
+    if (t->serving) BGL_FAIL(BGL_EINVAL, "host tier: the previous batch has not been finished");
+    if (n_upper > t->max_batch)
+        BGL_FAIL(BGL_ECAPACITY, "%lld ids exceed the tier's max_batch_rows %lld", (long long)n_upper,
+                 (long long)t->max_batch);
+    t->counts()[3] = 0;  // set by the lookup kernel when it meets an id outside [0, num_nodes)
+    if (n_upper == 0) {
+        t->counts()[1] = 0;
+        t->counts()[2] = 0;
+        return BGL_OK;
     }
-    const uint32_t epoch = t->epoch;
-    const int64_t chunks = bgl::ceil_div(m, CHUNK);
-    t->chunk_hits.assign((size_t)chunks + 1, 0);
-    std::atomic<int> bad{0};
-    // map lookup; a found slot remembers which rank found it
-    t->pool->run(m, CHUNK, [&](int64_t k, int64_t lo, int64_t hi) {
-        int64_t h = 0;
-        for (int64_t r = lo; r < hi; ++r) {
-            const int32_t id = t->ids[r];
-            if (id < 0 || (int64_t)id >= t->num_nodes) { bad.store(1); t->src_row[r] = -1; continue; }
-            const int32_t s = t->node_to_slot[id];
-            t->src_row[r] = s;
-            if (s >= 0) {
-                t->slot_epoch[s] = epoch;
-                t->slot_rank[s] = (int32_t)r;
-                ++h;
-            }
-        }
-        t->chunk_hits[(size_t)k] = h;
-    });
-    if (bad.load()) BGL_FAIL(BGL_EINVAL, "host tier: node id outside [0, num_nodes)");
-    int64_t n_hit = 0;
-    for (int64_t k = 0; k < chunks; ++k) {
-        const int64_t h = t->chunk_hits[(size_t)k];
-        t->chunk_hits[(size_t)k] = n_hit;
-        n_hit += h;
-    }
-    const int64_t n_miss = m - n_hit;
-    // Rows found now whose slot this batch's insertions will reuse: keep a copy in the
-    // staging row of their rank, so the copy from the store may overwrite the slot at once.
-    const int64_t start = n_miss > t->capacity ? n_miss - t->capacity : 0;
-    const size_t rb = (size_t)t->row_bytes;
-    t->pool->run(n_miss - start, CHUNK, [&](int64_t, int64_t lo, int64_t hi) {
-        for (int64_t j = start + lo; j < start + hi; ++j) {
-            const int64_t s = (int64_t)((t->tail + (uint64_t)j) % (uint64_t)t->capacity);
-            if (t->slot_epoch[(size_t)s] == epoch) {
-                const int64_t r = t->slot_rank[(size_t)s];
-                std::memcpy(t->rows + (size_t)(t->capacity + r) * rb, t->rows + (size_t)s * rb, rb);
-                t->src_row[(size_t)r] = t->capacity + r;
-                t->kept_aside.fetch_add(1, std::memory_order_relaxed);
-            }
-        }
-    });
-    // ordered lists of both kinds
-    t->pool->run(m, CHUNK, [&](int64_t k, int64_t lo, int64_t hi) {
-        int64_t h = t->chunk_hits[(size_t)k];
-        int64_t ms = lo - h;
-        for (int64_t r = lo; r < hi; ++r) {
-            const int64_t s = t->src_row[(size_t)r];
-            if (s >= 0) {
-                t->hit_rank[h] = (int32_t)r;
-                t->hit_src[h] = s;
-                ++h;
-            } else {
-                t->miss_rank[ms++] = (int32_t)r;
-            }
-        }
-    });
+    const unsigned tiles = (unsigned)bgl::ceil_div(n_upper, TT);
+    hipLaunchKernelGGL(k_tier_probe, dim3(tiles), dim3(TT), 0, st, ids, miss_pos, n_ranks_dev, t->num_nodes,
+                       t->node_pos, t->rank_pos, t->tile_miss, reinterpret_cast<int64_t *>(t->pinned_dev));
+    hipLaunchKernelGGL(k_tier_lists, dim3(tiles), dim3(TT), 0, st, ids, miss_pos, n_ranks_dev, t->rank_pos,
+                       t->tile_miss, t->hit_rank, t->hit_pos, t->miss_rank,
+                       reinterpret_cast<int32_t *>(t->pinned_dev + 64),
+                       reinterpret_cast<int64_t *>(t->pinned_dev));
+    BGL_HIP(hipGetLastError());
+    return BGL_OK;
+}
+
+int tier_begin(bgl_host_tier *t, int64_t n, TierPlan *plan)
+{
+    const int64_t n_hit_gpu = t->counts()[0];
+    const int64_t m = n - n_hit_gpu;
+    const int64_t n_hit = t->counts()[1], n_miss = t->counts()[2];
+    if (n_hit_gpu < 0 || m < 0 || n_hit + n_miss != m)
+        BGL_FAIL(BGL_EHIP, "host tier: inconsistent counts from the device (%lld, %lld, %lld of %lld)",
+                 (long long)n_hit_gpu, (long long)n_hit, (long long)n_miss, (long long)n);
+    if (t->counts()[3] != 0) BGL_FAIL(BGL_EINVAL, "host tier: node id outside [0, num_nodes)");
     t->cur_m = m;
     t->cur_hit = n_hit;
     t->cur_miss = n_miss;
     t->serving = true;
-    const size_t mb = (size_t)t->max_batch;
-    plan->hit_rank = reinterpret_cast<const int32_t *>(t->lists_dev + 4 * mb);
-    plan->miss_rank = reinterpret_cast<const int32_t *>(t->lists_dev + 8 * mb);
-    plan->hit_src = reinterpret_cast<const int64_t *>(t->lists_dev + 12 * mb);
-    plan->miss_src = reinterpret_cast<const int64_t *>(t->lists_dev + 20 * mb);
+    plan->n_hit_gpu = n_hit_gpu;
     plan->n_hit = n_hit;
     plan->n_miss = n_miss;
+    plan->hit_rank = t->hit_rank;
+    plan->hit_pos = t->hit_pos;
+    plan->miss_rank = t->miss_rank;
+    plan->ptail = t->ptail;
+    plan->ring = t->ring;
     return BGL_OK;
 }
 
-int tier_insert(bgl_host_tier *t)
+int tier_copy_start(bgl_host_tier *t)
+{
+    if (!t->serving) BGL_FAIL(BGL_EINVAL, "host tier: no batch is being served");
+    t->copy_t0 = std::chrono::steady_clock::now();
+    t->copy_fn = [t](int64_t k) {
+        const size_t rb = (size_t)t->row_bytes;
+        const int32_t *mi = t->miss_ids();
+        const int64_t hi = std::min<int64_t>(t->cur_miss, (k + 1) * COPY_TASK);
+        for (int64_t j = k * COPY_TASK; j < hi; ++j) {
+            const uint64_t pp = (t->ptail + (uint64_t)j) % (uint64_t)t->ring;
+            std::memcpy(t->rows + (size_t)pp * rb, t->store + (size_t)mi[j] * rb, rb);
+        }
+    };
+    t->pool->start(bgl::ceil_div(t->cur_miss, COPY_TASK), t->copy_fn);
+    return BGL_OK;
+}
+
+int64_t tier_copy_progress(bgl_host_tier *t)
+{
+    return std::min<int64_t>(t->cur_miss, t->pool->done_prefix() * COPY_TASK);
+}
+
+void tier_copy_wait(bgl_host_tier *t)
+{
+    t->pool->wait();
+    t->copy_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t->copy_t0).count();
+}
+
+int tier_enqueue_update(bgl_host_tier *t, const int32_t *ids, const int32_t *miss_pos, hipStream_t st)
 {
     if (!t->serving) BGL_FAIL(BGL_EINVAL, "host tier: no batch is being served");
     const int64_t n_miss = t->cur_miss;
     const int64_t start = n_miss > t->capacity ? n_miss - t->capacity : 0;
-    const size_t rb = (size_t)t->row_bytes;
-    t->pool->run(n_miss, CHUNK / 4, [&](int64_t, int64_t lo, int64_t hi) {
-        for (int64_t j = lo; j < hi; ++j) {
-            const int64_t r = t->miss_rank[j];
-            const int32_t id = t->ids[r];
-            const char *src = t->store + (size_t)id * rb;
-            if (j < start) {  // more misses than slots: the early ones pass through staging only
-                std::memcpy(t->rows + (size_t)(t->capacity + r) * rb, src, rb);
-                t->miss_src[j] = t->capacity + r;
-                continue;
-            }
-            const int64_t s = (int64_t)((t->tail + (uint64_t)j) % (uint64_t)t->capacity);
-            const int32_t old = t->slot_to_node[(size_t)s];
-            if (old >= 0) t->node_to_slot[(size_t)old] = -1;
-            std::memcpy(t->rows + (size_t)s * rb, src, rb);
-            t->slot_to_node[(size_t)s] = id;
-            t->node_to_slot[(size_t)id] = (int32_t)s;
-            t->miss_src[j] = s;
-        }
-    });
+    if (n_miss > start) {  // never with capacity 0
+        hipLaunchKernelGGL(k_tier_update, dim3((unsigned)bgl::ceil_div(n_miss - start, TT)), dim3(TT), 0, st, ids,
+                           miss_pos, t->miss_rank, start, n_miss, (unsigned long long)t->tail,
+                           (unsigned long long)t->ptail, t->capacity, t->ring, t->node_pos, t->slot_node,
+                           t->slot_pos);
+        BGL_HIP(hipGetLastError());
+    }
     t->tail += (uint64_t)n_miss;
+    t->ptail = (t->ptail + (uint64_t)n_miss) % (uint64_t)t->ring;
     t->lookups += (uint64_t)t->cur_m;
     t->hits += (uint64_t)t->cur_hit;
+    t->batches += 1;
     t->serving = false;
     return BGL_OK;
 }
+
+void tier_abort(bgl_host_tier *t) { t->serving = false; }
 
 }  // namespace bgl
 
@@ -273,14 +394,15 @@ extern "C" int bgl_host_tier_create(const void *store, int64_t num_nodes, int32_
     if (num_nodes < 1 || num_nodes > INT32_MAX) BGL_FAIL(BGL_EINVAL, "num_nodes out of range");
     if (row_bytes < 16 || row_bytes % 16 != 0)
         BGL_FAIL(BGL_EINVAL, "row_bytes must be a positive multiple of 16 (got %d)", row_bytes);
-    if (capacity_rows < 1 || capacity_rows > INT32_MAX)
-        BGL_FAIL(BGL_EINVAL, "capacity_rows must be in [1, 2^31) (got %lld)", (long long)capacity_rows);
-    if (max_batch_rows < 1 || max_batch_rows > INT32_MAX)
-        BGL_FAIL(BGL_EINVAL, "max_batch_rows must be in [1, 2^31) (got %lld)", (long long)max_batch_rows);
+    if (capacity_rows < 0 || capacity_rows > INT32_MAX)
+        BGL_FAIL(BGL_EINVAL, "capacity_rows must be in [0, 2^31) (got %lld)", (long long)capacity_rows);
+    if (max_batch_rows < 1 || max_batch_rows > INT32_MAX || capacity_rows + max_batch_rows > INT32_MAX)
+        BGL_FAIL(BGL_EINVAL, "max_batch_rows must be >= 1 and capacity_rows + max_batch_rows < 2^31 (got %lld)",
+                 (long long)max_batch_rows);
     if (num_threads < 0 || num_threads > 256) BGL_FAIL(BGL_EINVAL, "num_threads must be in [0, 256]");
     if (num_threads == 0) {
         const unsigned hw = std::thread::hardware_concurrency();
-        num_threads = (int32_t)std::min<unsigned>(hw ? hw : 1, 16);
+        num_threads = (int32_t)std::max<unsigned>(1, std::min<unsigned>(hw ? hw : 2, 16) - 1);
     }
     bgl_host_tier *t = new (std::nothrow) bgl_host_tier();
     if (!t) BGL_FAIL(BGL_ENOMEM, "out of host memory");
@@ -288,46 +410,70 @@ extern "C" int bgl_host_tier_create(const void *store, int64_t num_nodes, int32_
     t->num_nodes = num_nodes;
     t->row_bytes = row_bytes;
     t->capacity = capacity_rows;
-    t->max_batch = bgl::round_up((size_t)max_batch_rows, 4);  // keeps the 8-byte lists aligned
-    const size_t mb = (size_t)t->max_batch;
-    const size_t row_total = ((size_t)capacity_rows + mb) * (size_t)row_bytes;
+    t->max_batch = max_batch_rows;
+    t->ring = capacity_rows + max_batch_rows;
+    const size_t mb = (size_t)max_batch_rows;
+    const size_t row_total = (size_t)t->ring * (size_t)row_bytes;
     auto fail = [&](int code) { bgl_host_tier_destroy(t); return code; };
-    hipError_t e = hipHostMalloc((void **)&t->rows, row_total, hipHostMallocDefault);
-    if (e != hipSuccess) {
+    hipError_t e;
+    if (hipGetDevice(&t->device) != hipSuccess) { bgl::set_error("hipGetDevice failed"); return fail(BGL_EHIP); }
+    if ((e = hipHostMalloc((void **)&t->rows, row_total, hipHostMallocDefault)) != hipSuccess) {
         (void)hipGetLastError();
         t->rows = nullptr;
         bgl::set_error("page-locked allocation of %zu bytes failed: %s", row_total, hipGetErrorString(e));
         return fail(BGL_ENOMEM);
     }
-    e = hipHostMalloc((void **)&t->lists, 28 * mb + 64, hipHostMallocDefault);
-    if (e != hipSuccess) {
+    if ((e = hipHostMalloc((void **)&t->pinned, 64 + 4 * mb, hipHostMallocDefault)) != hipSuccess) {
         (void)hipGetLastError();
-        t->lists = nullptr;
-        bgl::set_error("page-locked allocation of %zu bytes failed: %s", 28 * mb, hipGetErrorString(e));
+        t->pinned = nullptr;
+        bgl::set_error("page-locked allocation of %zu bytes failed: %s", 64 + 4 * mb, hipGetErrorString(e));
         return fail(BGL_ENOMEM);
     }
     if (hipHostGetDevicePointer((void **)&t->rows_dev, t->rows, 0) != hipSuccess ||
-        hipHostGetDevicePointer((void **)&t->lists_dev, t->lists, 0) != hipSuccess) {
+        hipHostGetDevicePointer((void **)&t->pinned_dev, t->pinned, 0) != hipSuccess) {
         bgl::set_error("hipHostGetDevicePointer failed");
         return fail(BGL_EHIP);
     }
-    t->ids = reinterpret_cast<int32_t *>(t->lists);
-    t->hit_rank = reinterpret_cast<int32_t *>(t->lists + 4 * mb);
-    t->miss_rank = reinterpret_cast<int32_t *>(t->lists + 8 * mb);
-    t->hit_src = reinterpret_cast<int64_t *>(t->lists + 12 * mb);
-    t->miss_src = reinterpret_cast<int64_t *>(t->lists + 20 * mb);
+    std::memset(t->pinned, 0, 64);
+#define TRY_ALLOC(ptr, count)                                                                            \
+    if ((e = hipMalloc((void **)&(ptr), sizeof(int32_t) * (size_t)(count))) != hipSuccess) {              \
+        (void)hipGetLastError();                                                                         \
+        (ptr) = nullptr;                                                                                 \
+        bgl::set_error("hipMalloc of %zu bytes failed: %s", sizeof(int32_t) * (size_t)(count),           \
+                       hipGetErrorString(e));                                                            \
+        return fail(e == hipErrorOutOfMemory ? BGL_ENOMEM : BGL_EHIP);                                   \
+    }
+    if (capacity_rows > 0) {  // capacity 0: nothing is kept, every row passes through the ring
+        TRY_ALLOC(t->node_pos, num_nodes);
+        TRY_ALLOC(t->slot_node, capacity_rows);
+        TRY_ALLOC(t->slot_pos, capacity_rows);
+    }
+    TRY_ALLOC(t->rank_pos, mb);
+    TRY_ALLOC(t->tile_miss, bgl::ceil_div((int64_t)mb, TT) + 1);
+    TRY_ALLOC(t->hit_rank, mb);
+    TRY_ALLOC(t->hit_pos, mb);
+    TRY_ALLOC(t->miss_rank, mb);
+#undef TRY_ALLOC
+    if (capacity_rows > 0) {
+        hipLaunchKernelGGL(k_fill_i32, dim3(2048), dim3(256), 0, 0, t->node_pos, num_nodes, -1);
+        hipLaunchKernelGGL(k_fill_i32, dim3(1024), dim3(256), 0, 0, t->slot_node, capacity_rows, -1);
+        hipLaunchKernelGGL(k_fill_i32, dim3(1024), dim3(256), 0, 0, t->slot_pos, capacity_rows, 0);
+    }
+    if (hipDeviceSynchronize() != hipSuccess) {
+        bgl::set_error("tier initialisation failed: %s", hipGetErrorString(hipGetLastError()));
+        return fail(BGL_EHIP);
+    }
     try {
-        t->node_to_slot.assign((size_t)num_nodes, -1);
-        t->slot_to_node.assign((size_t)capacity_rows, -1);
-        t->slot_rank.assign((size_t)capacity_rows, 0);
-        t->slot_epoch.assign((size_t)capacity_rows, 0u);
-        t->src_row.assign(mb, -1);
         t->pool = new Pool(num_threads);
     } catch (const std::exception &) {
-        bgl::set_error("out of host memory");
+        bgl::set_error("could not start the host threads");
         return fail(BGL_ENOMEM);
     }
-    std::memset(t->rows, 0, (size_t)capacity_rows * (size_t)row_bytes);
+    // touch every page of the ring now rather than inside the first batches' copies
+    t->pool->run((int64_t)bgl::ceil_div((int64_t)row_total, 1 << 20), [&](int64_t k) {
+        const size_t lo = (size_t)k << 20;
+        std::memset(t->rows + lo, 0, std::min<size_t>((size_t)1 << 20, row_total - lo));
+    });
     *out = t;
     return BGL_OK;
 }
@@ -338,7 +484,15 @@ extern "C" int bgl_host_tier_destroy(bgl_host_tier_t *t)
     (void)hipDeviceSynchronize();  // kernels may still read the rows
     delete t->pool;
     if (t->rows) (void)hipHostFree(t->rows);
-    if (t->lists) (void)hipHostFree(t->lists);
+    if (t->pinned) (void)hipHostFree(t->pinned);
+    (void)hipFree(t->node_pos);
+    (void)hipFree(t->slot_node);
+    (void)hipFree(t->slot_pos);
+    (void)hipFree(t->rank_pos);
+    (void)hipFree(t->tile_miss);
+    (void)hipFree(t->hit_rank);
+    (void)hipFree(t->hit_pos);
+    (void)hipFree(t->miss_rank);
     delete t;
     return BGL_OK;
 }
@@ -347,19 +501,33 @@ extern "C" int bgl_host_tier_export_state(bgl_host_tier_t *t, int32_t *slot_to_n
                                           void *buffer_rows)
 {
     if (!t) BGL_FAIL(BGL_EINVAL, "tier handle is null");
-    if (slot_to_node) std::memcpy(slot_to_node, t->slot_to_node.data(), sizeof(int32_t) * (size_t)t->capacity);
+    BGL_HIP(hipDeviceSynchronize());
+    std::vector<int32_t> node((size_t)t->capacity), pos((size_t)t->capacity);
+    if (t->capacity > 0) {
+        BGL_HIP(hipMemcpy(node.data(), t->slot_node, sizeof(int32_t) * (size_t)t->capacity, hipMemcpyDeviceToHost));
+        BGL_HIP(hipMemcpy(pos.data(), t->slot_pos, sizeof(int32_t) * (size_t)t->capacity, hipMemcpyDeviceToHost));
+    }
+    if (slot_to_node) std::memcpy(slot_to_node, node.data(), sizeof(int32_t) * (size_t)t->capacity);
     if (tail) *tail = t->tail;
-    if (buffer_rows) std::memcpy(buffer_rows, t->rows, (size_t)t->capacity * (size_t)t->row_bytes);
+    if (buffer_rows) {
+        const size_t rb = (size_t)t->row_bytes;
+        char *dst = static_cast<char *>(buffer_rows);
+        for (int64_t s = 0; s < t->capacity; ++s) {
+            if (node[(size_t)s] >= 0) std::memcpy(dst + (size_t)s * rb, t->rows + (size_t)pos[(size_t)s] * rb, rb);
+            else std::memset(dst + (size_t)s * rb, 0, rb);
+        }
+    }
     return BGL_OK;
 }
 
-extern "C" int bgl_host_tier_stats(bgl_host_tier_t *t, uint64_t *lookups, uint64_t *hits,
-                                   uint64_t *kept_aside, int32_t *threads)
+extern "C" int bgl_host_tier_stats(bgl_host_tier_t *t, uint64_t *lookups, uint64_t *hits, double *copy_ms,
+                                   uint64_t *batches, int32_t *threads)
 {
     if (!t) BGL_FAIL(BGL_EINVAL, "tier handle is null");
     if (lookups) *lookups = t->lookups;
     if (hits) *hits = t->hits;
-    if (kept_aside) *kept_aside = t->kept_aside.load();
+    if (copy_ms) *copy_ms = t->copy_ms;
+    if (batches) *batches = t->batches;
     if (threads) *threads = t->pool->threads();
     return BGL_OK;
 }

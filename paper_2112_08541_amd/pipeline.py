@@ -50,12 +50,13 @@ class MinibatchPipeline:
         cache.set_write_through(self.write_through)
 
     def run(self, seeds_dev: torch.Tensor, rng_seeds, steps: int,
-            on_batch: Optional[Callable] = None):
+            on_batch: Optional[Callable] = None, first_step: int = 0):
         """Prepare `steps` minibatches; batch i uses seeds_dev[i % len] and rng_seeds[i % len]
         (xor the pass number, so that a second pass over the seeds samples differently).
         on_batch(i, sampled_batch, n, pipeline) is called after lookup_gather(i) and
         insert_fifo(i) have been enqueued; work it enqueues on the chain stream after
         cache.wait_rows(chain) sees batch i's complete outputs.
+        first_step offsets the batch numbering (a later pass over the seeds).
         Returns (n_input per batch, n_hit per batch)."""
         nb = seeds_dev.shape[0]
         K, cache, chain, work = self.K, self.cache, self.chain, self.work
@@ -66,8 +67,8 @@ class MinibatchPipeline:
 
         def sample(i):
             smp = self.samplers[i % 3]
-            b = i % nb
-            sb = smp.sample(seeds_dev[b], int(rng_seeds[b]) ^ (i // nb), stream=work)
+            b = (first_step + i) % nb
+            sb = smp.sample(seeds_dev[b], int(rng_seeds[b]) ^ ((first_step + i) // nb), stream=work)
             sampled_ev[i % 3].record(work)
             return sb
 

@@ -95,12 +95,13 @@ def test_null_handles_are_rejected_without_touching_the_gpu(L):
     # host tier
     assert L.bgl_host_tier_create(None, 4, 16, 4, 4, 1, C.byref(h)) == B.BGL_EINVAL
     assert L.bgl_host_tier_create(feats.ctypes.data, 4, 20, 4, 4, 1, C.byref(h)) == B.BGL_EINVAL
-    assert L.bgl_host_tier_create(feats.ctypes.data, 4, 16, 0, 4, 1, C.byref(h)) == B.BGL_EINVAL
+    assert L.bgl_host_tier_create(feats.ctypes.data, 4, 16, -1, 4, 1, C.byref(h)) == B.BGL_EINVAL
     assert L.bgl_host_tier_create(feats.ctypes.data, 4, 16, 4, 0, 1, C.byref(h)) == B.BGL_EINVAL
+    assert L.bgl_host_tier_create(feats.ctypes.data, 4, 16, 2**31 - 2, 8, 1, C.byref(h)) == B.BGL_EINVAL
     assert L.bgl_host_tier_create(feats.ctypes.data, 4, 16, 4, 4, -1, C.byref(h)) == B.BGL_EINVAL
     assert L.bgl_host_tier_destroy(None) == B.BGL_OK
     assert L.bgl_host_tier_export_state(None, None, None, None) == B.BGL_EINVAL
-    assert L.bgl_host_tier_stats(None, None, None, None, None) == B.BGL_EINVAL
+    assert L.bgl_host_tier_stats(None, None, None, None, None, None) == B.BGL_EINVAL
     assert L.bgl_cache_lookup_gather_tiered(None, None, None, 0, None, None, None, None, None, None) == B.BGL_EINVAL
     assert L.bgl_cache_create(4, 16, feats.ctypes.data, 0, C.byref(h)) == B.BGL_EINVAL
 
