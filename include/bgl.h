@@ -282,14 +282,20 @@ int bgl_cache_profile(bgl_cache_t *c, int stage, double *total_ms, int64_t *laun
  * Second cache level in host memory (Sec. 3.2.3: a CPU cache with the same
  * policy as the GPU cache sits between it and the feature store).  The tier is
  * a FIFO cache of capacity_rows rows in page-locked memory, which the GPU reads
- * in place; rows it does not hold are copied in from `store` by host threads.
- * Its map (node -> row, 4 bytes per node) and slot tables live in device memory
- * of the current device and are looked up and updated by kernels.
+ * in place; rows it does not hold are copied in from `store` by host threads,
+ * packed in miss order, and read by the GPU as a stream from there.  Its map
+ * (node -> row, 4 bytes per node) and slot tables live in device memory of the
+ * current device and are looked up and updated by kernels.
  *   store           the feature store: num_nodes rows of row_bytes bytes in
- *                   ordinary host memory (pageable or a mapped file will do);
- *                   stays alive and unchanged until bgl_host_tier_destroy
+ *                   host memory of any kind (pageable, a mapped file,
+ *                   page-locked); stays alive and unchanged until
+ *                   bgl_host_tier_destroy
+ *   capacity_rows   0 is allowed: nothing is kept, every miss row just passes
+ *                   through the page-locked ring.  That alone pays when
+ *                   row_bytes is not a multiple of 128: rows read in place move
+ *                   whole 128-byte lines over the link, packed rows do not
  *   max_batch_rows  the largest n a tiered lookup will be called with; the
- *                   page-locked region holds capacity_rows + max_batch_rows rows
+ *                   page-locked ring holds capacity_rows + max_batch_rows rows
  *   num_threads     host threads that copy rows (the calling thread drives the
  *                   GPU meanwhile); 0 = min(cores, 16) - 1
  * Errors: BGL_EINVAL (null store, sizes out of range, row_bytes not a multiple

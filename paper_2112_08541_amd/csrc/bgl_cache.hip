@@ -229,7 +229,7 @@ constexpr int COPY_UNROLL = 4;
 constexpr int FETCH_BLOCKS = 64;
 // Tiered lookup: rows the host threads copy per chunk before that chunk's fetch is launched.
 constexpr int64_t TIER_CHUNK_ROWS = 49152;
-constexpr int64_t TIER_FIRST_CHUNK_ROWS = 4096;
+constexpr int64_t TIER_FIRST_CHUNK_ROWS = 3072;
 
 // out[i] = buffer[out_slot[i]] for every hit i (taken from the hit list, so the
 // work is proportional to the hits).  Consecutive lanes take consecutive
@@ -838,11 +838,22 @@ extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t
     rc = lookup_phase(c, ids, n, out_rows, out_slot, miss_pos, bgl::tier_count_device(t), ms, t);
     if (rc != BGL_OK) return rc;
     BGL_HIP(hipGetLastError());
+    struct Guard {  // whatever goes wrong below, the copy threads are released and the batch is dropped
+        bgl_host_tier *t;
+        bool armed = true;
+        ~Guard() { if (armed) bgl::tier_abort(t); }
+    } guard{t};
     // the host continues as soon as the lists are there; the hit gather runs meanwhile
     BGL_HIP(hipEventSynchronize(c->ev_ids));
     bgl::TierPlan plan;
     rc = bgl::tier_begin(t, n, &plan);
     if (rc != BGL_OK) return rc;
+    // (Waking the copy threads earlier, to have them spin until the ids arrive, was measured:
+    // slower, the spinning threads get in the way of the wait for the lookup.)
+    if (plan.n_miss > 0) {
+        rc = bgl::tier_copy_start(t);
+        if (rc != BGL_OK) return rc;
+    }
     if (ss != ms) BGL_HIP(hipStreamWaitEvent(ss, c->ev_listed, 0));
     const int par = (int)(c->insert_calls & 1);
     const uint4 *rows = reinterpret_cast<const uint4 *>(bgl::tier_rows_device(t));
@@ -868,10 +879,9 @@ extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t
     // Rows the tier holds cross the link while host threads bring the others in from the
     // store, a chunk at a time; each chunk is fetched as soon as it is in place.
     fetch(std::false_type{}, plan.hit_rank, plan.hit_pos, 0, plan.n_hit);
-    // (small chunks first, so the link starts early; the copy threads outrun the link)
-    if (plan.n_miss > 0) {
-        rc = bgl::tier_copy_start(t);
-        if (rc != BGL_OK) { bgl::tier_abort(t); return rc; }
+    // Small chunks first, so that the link starts early; the copy threads outrun the link
+    // only by a little, so the chunks grow until a launch is a few per cent of its kernel.
+    {
         int64_t chunk = plan.n_hit > TIER_CHUNK_ROWS ? TIER_CHUNK_ROWS : TIER_FIRST_CHUNK_ROWS;
         for (int64_t launched = 0; launched < plan.n_miss;) {
             const int64_t ready = bgl::tier_copy_progress(t);
@@ -889,6 +899,7 @@ extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t
     // the tier's map changes after this call's lists are final and before the next lookup
     rc = bgl::tier_enqueue_update(t, ids, miss_pos, ms);
     if (rc != BGL_OK) return rc;
+    guard.armed = false;
     BGL_HIP(hipGetLastError());
     c->fetch_pending = true;
     c->fetch_stream = ss;

@@ -47,6 +47,7 @@ int64_t tier_copy_progress(bgl_host_tier *t);
 void tier_copy_wait(bgl_host_tier *t);
 // Enqueue the first-in first-out update of the map on st and close the batch.
 int tier_enqueue_update(bgl_host_tier *t, const int32_t *ids, const int32_t *miss_pos, hipStream_t st);
+// Give up on the batch (after a failed tier_begin or launch).
 void tier_abort(bgl_host_tier *t);
 
 }  // namespace bgl

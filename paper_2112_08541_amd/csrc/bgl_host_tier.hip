@@ -269,6 +269,7 @@ struct bgl_host_tier {
     bool serving = false;
     Pool *pool = nullptr;
     Pool::Fn copy_fn;
+    bool copying = false;
     std::chrono::steady_clock::time_point copy_t0;
 
     volatile int64_t *counts() const { return reinterpret_cast<volatile int64_t *>(pinned); }
@@ -344,6 +345,7 @@ int tier_copy_start(bgl_host_tier *t)
             std::memcpy(t->rows + (size_t)pp * rb, t->store + (size_t)mi[j] * rb, rb);
         }
     };
+    t->copying = true;
     t->pool->start(bgl::ceil_div(t->cur_miss, COPY_TASK), t->copy_fn);
     return BGL_OK;
 }
@@ -355,6 +357,8 @@ int64_t tier_copy_progress(bgl_host_tier *t)
 
 void tier_copy_wait(bgl_host_tier *t)
 {
+    if (!t->copying) return;
+    t->copying = false;
     t->pool->wait();
     t->copy_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t->copy_t0).count();
 }
@@ -380,7 +384,11 @@ int tier_enqueue_update(bgl_host_tier *t, const int32_t *ids, const int32_t *mis
     return BGL_OK;
 }
 
-void tier_abort(bgl_host_tier *t) { t->serving = false; }
+void tier_abort(bgl_host_tier *t)
+{
+    tier_copy_wait(t);  // copies already under way land in ring positions nothing refers to
+    t->serving = false;
+}
 
 }  // namespace bgl
 
