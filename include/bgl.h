@@ -256,11 +256,14 @@ int bgl_cache_stats(bgl_cache_t *c, uint64_t *lookups, uint64_t *hits, uint64_t 
 
 /*
  * Per-kernel timing for measurements.  `stage_mask` has bit (1 << stage) set for
- * every stage whose kernels the cache shall bracket with HIP events on the
- * stream they run on (0 = off, BGL_ALL_STAGES = all); every event pair costs a
- * few microseconds of launch gap on that stream.  bgl_cache_profile synchronises
- * the device and returns the summed milliseconds and the number of launches of
- * one stage since profiling was (re-)enabled.
+ * every stage the cache shall time (0 = off, BGL_ALL_STAGES = all).  A stage that
+ * is one kernel per launch (all but BGL_STAGE_MISS_LIST) is timed by the kernel
+ * dispatch itself, which records the kernel's begin and end on the device into a
+ * pair of events: the figure is the kernel's own duration, the one a kernel
+ * trace shows.  BGL_STAGE_MISS_LIST (several small kernels) is bracketed by two
+ * event records on its stream, which also times the launch gaps around them.
+ * bgl_cache_profile synchronises the device and returns the summed milliseconds
+ * and the number of launches of one stage since profiling was (re-)enabled.
  */
 #define BGL_STAGE_PROBE 0       /* map lookup */
 #define BGL_STAGE_MISS_LIST 1   /* ordered list of miss positions + counters */
@@ -269,8 +272,9 @@ int bgl_cache_stats(bgl_cache_t *c, uint64_t *lookups, uint64_t *hits, uint64_t 
 #define BGL_STAGE_INSERT_MAP 4  /* evict + enter ids in the map */
 #define BGL_STAGE_INSERT_ROWS 5 /* out_rows -> cache buffer */
 #define BGL_NUM_STAGES 6
-/* pseudo stage: what an event pair reads around a kernel that does nothing
- * (measured when profiling is enabled); total_ms is that single figure */
+/* pseudo stage: what two event records read around a kernel that does nothing
+ * (measured when profiling is enabled; the share of BGL_STAGE_MISS_LIST that is
+ * not kernel time); total_ms is that single figure */
 #define BGL_STAGE_EVENT_OVERHEAD 100
 #define BGL_ALL_STAGES ((1 << BGL_NUM_STAGES) - 1)
 int bgl_cache_set_profiling(bgl_cache_t *c, int stage_mask);

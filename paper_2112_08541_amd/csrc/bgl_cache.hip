@@ -20,6 +20,8 @@
 #include <algorithm>
 #include <vector>
 
+#include <hip/hip_ext.h>
+
 #include "bgl_host_tier.h"
 #include "bgl_internal.h"
 
@@ -79,7 +81,8 @@ struct bgl_cache {
     bool awaiting_insert;   // write-through: a lookup's misses are in the buffer but not in the map yet
     const void *wt_ids, *wt_miss_pos;  // arguments of that lookup
     // profiling
-    unsigned profiling;     // bit s set: stage s is bracketed with events
+    unsigned profiling;     // bit s set: stage s is timed
+    hipEvent_t timed_start, timed_stop;  // events the next launch() hands to the kernel dispatch itself
     std::vector<hipEvent_t> prof_ev;  // pairs
     struct Rec { int stage; int ev; };
     std::vector<Rec> prof_rec;
@@ -509,22 +512,49 @@ __global__ void k_advance_tail(CacheDev *dev, int64_t n_miss_arg, int par)
 __global__ void k_noop() {}
 
 // ------------------------------------------------------------------ host helpers
+// Stage timers.  A stage that is one kernel is timed by the dispatch itself: the
+// pair of events goes into the launch (launch() below) and records the kernel's
+// own begin and end on the device.  A stage of several launches (exact = false)
+// is bracketed by two event records on the stream, which also times the launch
+// gaps around it.
 struct Prof {
     bgl_cache *c;
     hipStream_t st;
     int ev = -1;
-    Prof(bgl_cache *c_, int stage, hipStream_t st_) : c(c_), st(st_)
+    bool exact;
+    Prof(bgl_cache *c_, int stage, hipStream_t st_, bool exact_ = true) : c(c_), st(st_), exact(exact_)
     {
         if (!(c->profiling & (1u << stage)) || c->prof_rec.size() >= PROF_RING) return;
         ev = (int)c->prof_rec.size() * 2;
         c->prof_rec.push_back({stage, ev});
-        (void)hipEventRecord(c->prof_ev[ev], st);
+        if (exact) {
+            c->timed_start = c->prof_ev[ev];
+            c->timed_stop = c->prof_ev[ev + 1];
+        } else {
+            (void)hipEventRecord(c->prof_ev[ev], st);
+        }
     }
     ~Prof()
     {
-        if (ev >= 0) (void)hipEventRecord(c->prof_ev[ev + 1], st);
+        if (ev < 0) return;
+        if (exact) c->timed_start = c->timed_stop = nullptr;  // (already taken by the launch)
+        else (void)hipEventRecord(c->prof_ev[ev + 1], st);
     }
 };
+
+// Kernel launch; inside a Prof scope of a one-kernel stage the dispatch records its
+// own begin and end into that scope's events.
+template <typename... P, typename... A>
+void launch(bgl_cache *c, hipStream_t st, void (*kernel)(P...), dim3 grid, dim3 block, A &&...a)
+{
+    if (c->timed_start) {
+        hipEvent_t e0 = c->timed_start, e1 = c->timed_stop;
+        c->timed_start = c->timed_stop = nullptr;
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, st, e0, e1, 0, static_cast<P>(a)...);
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, 0, st, static_cast<P>(a)...);
+    }
+}
 
 void drain_profile(bgl_cache *c)
 {
@@ -593,6 +623,7 @@ extern "C" int bgl_cache_create(int64_t capacity_rows, int32_t row_bytes,
     c->features = feat_dev;
     c->features_in_hbm = attr.type == hipMemoryTypeDevice;
     c->profiling = 0;
+    c->timed_start = c->timed_stop = nullptr;
     c->fetch_pending = false;
     c->map_pending = false;
     c->ev_listed_valid = false;
@@ -708,11 +739,11 @@ int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, in
     if (n > 0) {
         {
             Prof p(c, BGL_STAGE_PROBE, ms);
-            hipLaunchKernelGGL(k_probe, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), 0, ms, ids, n, c->num_nodes,
-                               c->table, c->num_buckets - 1, out_slot, c->mbs, c->dev);
+            launch(c, ms, k_probe, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), ids, n, c->num_nodes, c->table,
+                   c->num_buckets - 1, out_slot, c->mbs, c->dev);
         }
         {
-            Prof p(c, BGL_STAGE_MISS_LIST, ms);
+            Prof p(c, BGL_STAGE_MISS_LIST, ms, false);
             hipLaunchKernelGGL(k_split_list, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), 0, ms, out_slot,
                                n, c->mbs, miss_pos, c->hit_pos, c->hit_pos + c->hit_cap, c->dev,
                                n_hit_dev);
@@ -725,10 +756,9 @@ int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, in
         {
             Prof p(c, BGL_STAGE_GATHER_HIT, ms);
             dispatch_q(q, [&](auto Q) {
-                hipLaunchKernelGGL((k_gather_hits<decltype(Q)::value>), dim3(copy_blocks(n, q)),
-                                   dim3(COPY_THREADS), 0, ms, c->hit_pos, c->hit_pos + c->hit_cap, q,
-                                   reinterpret_cast<const uint4 *>(c->buffer),
-                                   reinterpret_cast<uint4 *>(out_rows), c->dev);
+                launch(c, ms, k_gather_hits<decltype(Q)::value>, dim3(copy_blocks(n, q)), dim3(COPY_THREADS),
+                       c->hit_pos, c->hit_pos + c->hit_cap, q, reinterpret_cast<const uint4 *>(c->buffer),
+                       reinterpret_cast<uint4 *>(out_rows), c->dev);
             });
         }
     } else {
@@ -793,18 +823,11 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
             const int blocks = (int)std::min<int64_t>(copy_blocks(n, q), c->features_in_hbm ? 8192 : FETCH_BLOCKS);
             const int par = (int)(c->insert_calls & 1);
             dispatch_q(q, [&](auto Q) {
-                if (c->write_through)
-                    hipLaunchKernelGGL((k_fetch_miss<decltype(Q)::value, true>), dim3(blocks),
-                                       dim3(COPY_THREADS), 0, ss, miss_pos, ids, q, c->num_nodes,
-                                       reinterpret_cast<const uint4 *>(c->features),
-                                       reinterpret_cast<uint4 *>(out_rows), c->dev,
-                                       reinterpret_cast<uint4 *>(c->buffer), c->capacity, par);
-                else
-                    hipLaunchKernelGGL((k_fetch_miss<decltype(Q)::value, false>), dim3(blocks),
-                                       dim3(COPY_THREADS), 0, ss, miss_pos, ids, q, c->num_nodes,
-                                       reinterpret_cast<const uint4 *>(c->features),
-                                       reinterpret_cast<uint4 *>(out_rows), c->dev,
-                                       reinterpret_cast<uint4 *>(c->buffer), c->capacity, par);
+                auto k = c->write_through ? k_fetch_miss<decltype(Q)::value, true>
+                                          : k_fetch_miss<decltype(Q)::value, false>;
+                launch(c, ss, k, dim3(blocks), dim3(COPY_THREADS), miss_pos, ids, q, c->num_nodes,
+                       reinterpret_cast<const uint4 *>(c->features), reinterpret_cast<uint4 *>(out_rows), c->dev,
+                       reinterpret_cast<uint4 *>(c->buffer), c->capacity, par);
             });
         }
         BGL_HIP(hipEventRecord(c->ev_miss, ss));
@@ -862,18 +885,12 @@ extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t
         Prof p(c, BGL_STAGE_FETCH_MISS, ss);
         const int blocks = (int)std::min<int64_t>(copy_blocks(count, q), FETCH_BLOCKS);
         dispatch_q(q, [&](auto Q) {
-            if (c->write_through)
-                hipLaunchKernelGGL((k_fetch_rows<decltype(Q)::value, true, decltype(seq)::value>), dim3(blocks),
-                                   dim3(COPY_THREADS), 0, ss, rank, pos, l0, count,
-                                   (unsigned long long)plan.ptail, plan.ring, miss_pos, q, rows,
-                                   reinterpret_cast<uint4 *>(out_rows), c->dev,
-                                   reinterpret_cast<uint4 *>(c->buffer), c->capacity, par);
-            else
-                hipLaunchKernelGGL((k_fetch_rows<decltype(Q)::value, false, decltype(seq)::value>), dim3(blocks),
-                                   dim3(COPY_THREADS), 0, ss, rank, pos, l0, count,
-                                   (unsigned long long)plan.ptail, plan.ring, miss_pos, q, rows,
-                                   reinterpret_cast<uint4 *>(out_rows), c->dev,
-                                   reinterpret_cast<uint4 *>(c->buffer), c->capacity, par);
+            auto k = c->write_through ? k_fetch_rows<decltype(Q)::value, true, decltype(seq)::value>
+                                      : k_fetch_rows<decltype(Q)::value, false, decltype(seq)::value>;
+            launch(c, ss, k, dim3(blocks), dim3(COPY_THREADS), rank, pos, l0, count,
+                   (unsigned long long)plan.ptail, plan.ring, miss_pos, q, rows,
+                   reinterpret_cast<uint4 *>(out_rows), c->dev, reinterpret_cast<uint4 *>(c->buffer), c->capacity,
+                   par);
         });
     };
     // Rows the tier holds cross the link while host threads bring the others in from the
@@ -939,10 +956,9 @@ extern "C" int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const i
         c->awaiting_insert = false;
         if (eff > 0) {
             Prof p(c, BGL_STAGE_INSERT_MAP, st);
-            hipLaunchKernelGGL(k_insert_map, dim3((unsigned)bgl::ceil_div(eff * BUCKET, COPY_THREADS)),
-                               dim3(COPY_THREADS), 0, st, ids, miss_pos, n_miss, c->capacity,
-                               c->num_nodes, c->table, c->num_buckets - 1, c->slot_to_node,
-                               c->slot_to_entry, c->dev, par, 1);
+            launch(c, st, k_insert_map, dim3((unsigned)bgl::ceil_div(eff * BUCKET, COPY_THREADS)),
+                   dim3(COPY_THREADS), ids, miss_pos, n_miss, c->capacity, c->num_nodes, c->table,
+                   c->num_buckets - 1, c->slot_to_node, c->slot_to_entry, c->dev, par, 1);
         } else {
             hipLaunchKernelGGL(k_advance_tail, dim3(1), dim3(64), 0, st, c->dev, n_miss, par);
         }
@@ -958,20 +974,18 @@ extern "C" int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const i
     if (eff > 0) {
         {
             Prof p(c, BGL_STAGE_INSERT_MAP, st);
-            hipLaunchKernelGGL(k_insert_map, dim3((unsigned)bgl::ceil_div(eff * BUCKET, COPY_THREADS)),
-                               dim3(COPY_THREADS), 0, st, ids, miss_pos, n_miss, c->capacity,
-                               c->num_nodes, c->table, c->num_buckets - 1, c->slot_to_node,
-                               c->slot_to_entry, c->dev, par, 0);
+            launch(c, st, k_insert_map, dim3((unsigned)bgl::ceil_div(eff * BUCKET, COPY_THREADS)),
+                   dim3(COPY_THREADS), ids, miss_pos, n_miss, c->capacity, c->num_nodes, c->table,
+                   c->num_buckets - 1, c->slot_to_node, c->slot_to_entry, c->dev, par, 0);
         }
         if (c->fetch_pending && c->fetch_stream != st)
             BGL_HIP(hipStreamWaitEvent(st, c->ev_miss, 0));  // rows of the misses
         {
             Prof p(c, BGL_STAGE_INSERT_ROWS, st);
             dispatch_q(q, [&](auto Q) {
-                hipLaunchKernelGGL((k_insert_rows<decltype(Q)::value>), dim3(copy_blocks(eff, q)),
-                                   dim3(COPY_THREADS), 0, st, miss_pos, n_miss, c->capacity, q,
-                                   reinterpret_cast<const uint4 *>(out_rows),
-                                   reinterpret_cast<uint4 *>(c->buffer), c->dev, par);
+                launch(c, st, k_insert_rows<decltype(Q)::value>, dim3(copy_blocks(eff, q)), dim3(COPY_THREADS),
+                       miss_pos, n_miss, c->capacity, q, reinterpret_cast<const uint4 *>(out_rows),
+                       reinterpret_cast<uint4 *>(c->buffer), c->dev, par);
             });
         }
     } else {
