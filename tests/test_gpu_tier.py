@@ -33,12 +33,15 @@ def assert_tier_state_equal(tier, oc2, what):
     assert np.array_equal(buf[live], oc2.buffer[live]), what
 
 
-def run_tiered_stream(B, torch, feats, cap1, cap2, batches, write_through, threads, side=True):
+def run_tiered_stream(B, torch, feats, cap1, cap2, batches, write_through, threads, side=True,
+                      cache_has_store=False):
     import oracle
     N, rb = feats.shape[0], feats.shape[1] * feats.itemsize
     store = np.ascontiguousarray(feats.view(np.uint8).reshape(N, rb))      # ordinary host memory
     max_n = max(max((len(b) for b in batches), default=1), 1)
-    gc = B.Cache(cap1, None, num_nodes=N, row_bytes=rb)
+    # as in bench.py's staged miss path: the cache keeps its own page-locked table
+    pinned = torch.from_numpy(store).pin_memory() if cache_has_store else None
+    gc = B.Cache(cap1, pinned, num_nodes=N, row_bytes=rb)
     tier = B.HostTier(store, cap2, max_n, threads)
     # capacity 0: the tier keeps nothing (every miss row just passes through its ring)
     oc1, oc2 = oracle.Cache(cap1, feats), (oracle.Cache(cap2, feats) if cap2 > 0 else None)
@@ -78,7 +81,9 @@ def run_tiered_stream(B, torch, feats, cap1, cap2, batches, write_through, threa
     if oc2 is not None:
         assert (st["lookups"], st["hits"]) == oc2.stats()
     else:
-        assert st["hits"] == 0 and tier.export_state(True)[1] == sum(len(b) for b in batches) - gc.stats()["hits"]
+        total_miss = sum(len(b) for b in batches) - gc.stats()["hits"]
+        passed = tier.export_state(True)[1]          # rows that went through the ring
+        assert st["hits"] == 0 and passed == total_miss
     return gc, tier
 
 
@@ -116,6 +121,20 @@ def test_tiered_capacity_corners(B, torch_mod, cap1, cap2, threads):
     batches = zipf_batches(rng, N, 12, 200, 3000)
     _, tier = run_tiered_stream(B, torch_mod, feats, cap1, cap2, batches, True, threads, side=(threads != 2))
     assert tier.stats()["threads"] == (threads or tier.stats()["threads"])
+
+
+@pytest.mark.parametrize("write_through", [False, True])
+@pytest.mark.parametrize("side", [False, True])
+def test_staging_only_large_batches(B, torch_mod, write_through, side):
+    """Capacity 0 (every miss row passes through the ring) with batches of several chunks, hits
+    that the same batch's insertions evict (small GPU cache), an empty batch, a repeat."""
+    rng = np.random.default_rng(77)
+    N = 200000
+    feats = rng.integers(0, 2**32, (N, 25 * 4), dtype=np.uint32).view(np.float32)
+    batches = [rng.permutation(N)[: int(k)].tolist() for k in (70000, 300, 90000, 26000, 60000, 24576, 24577, 80000)]
+    batches.insert(2, [])
+    batches.insert(5, batches[4])     # immediate repeat: hits everywhere the cache kept them
+    run_tiered_stream(B, torch_mod, feats, 50000, 0, batches, write_through, 0, side=side, cache_has_store=True)
 
 
 def test_tiered_uniform_ids_many_chunks(B, torch_mod):
@@ -181,11 +200,14 @@ def test_tiered_pipeline_as_benchmarked_matches_oracle(torch_mod, B, tier_fracti
     from paper_2112_08541_amd.pipeline import MinibatchPipeline
     torch = torch_mod
     cfg = inputs.CONFIGS["mid"]
-    w = inputs.make_workload(cfg, pinned=False)
+    staging_only = tier_fraction == 0.0
+    w = inputs.make_workload(cfg, pinned=staging_only)
     rb = cfg.row_bytes
     store = np.ascontiguousarray(w.features.view(np.uint8).reshape(cfg.num_nodes, rb))
     graph = B.Graph(w.row_ptr, w.col)
-    cache = B.Cache(cfg.cache_rows, None, num_nodes=cfg.num_nodes, row_bytes=rb)
+    # as in bench.py: the staging-only path keeps the cache's own page-locked table
+    cache = B.Cache(cfg.cache_rows, w.features.ctypes.data if staging_only else None,
+                    num_nodes=cfg.num_nodes, row_bytes=rb)
     tier_rows = int(tier_fraction * cfg.num_nodes)
     pipe = MinibatchPipeline(graph, cache, cfg.batch, cfg.fanouts, rb, write_through=True, tier=None)
     tier = B.HostTier(store, tier_rows, pipe.cap, 0)
