@@ -123,16 +123,38 @@ def main():
     scratch = new_cache()
     pipe = MinibatchPipeline(graph, scratch, cfg.batch, cfg.fanouts, cfg.row_bytes,
                              write_through=not args.no_write_through)
+    # Miss path.  Staging pays when rows are not multiples of 128 bytes and batches are large,
+    # provided the box has the host cores for the copy threads: "auto" tries both in the warm-up
+    # (each from an empty scratch cache, untimed for the benchmark) and keeps the faster one.
     miss_path = args.miss_path
-    if miss_path == "auto":
-        miss_path = "staged" if (cfg.row_bytes % 128 != 0 and pipe.cap >= 65536 and feat_dev is None) else "zero_copy"
+    eligible = cfg.row_bytes % 128 != 0 and pipe.cap >= 65536 and feat_dev is None
     stage_ring = None
-    if miss_path == "staged":
+    trial = {}
+    if miss_path == "staged" or (miss_path == "auto" and eligible):
         # capacity 0: nothing is kept in host memory, every miss row passes through the ring
         stage_ring = B.HostTier(w.features.view(np.uint8).reshape(cfg.num_nodes, cfg.row_bytes), 0, pipe.cap,
                                 args.tier_threads)
-        pipe.tier = stage_ring
-    if args.warmup > 0:
+    if miss_path == "auto":
+        miss_path = "zero_copy"
+        if stage_ring is not None and args.warmup > 0:
+            for name, tier in (("zero_copy", None), ("staged", stage_ring)):
+                pipe.tier = tier
+                pipe.run(seeds_dev, w.rng_seeds, min(3, args.warmup))
+                scratch.close()
+                scratch = new_cache()
+                pipe.set_cache(scratch)
+                torch.cuda.synchronize()
+                q0 = time.perf_counter()
+                pipe.run(seeds_dev, w.rng_seeds, args.warmup)
+                trial[name] = 1e3 * (time.perf_counter() - q0) / args.warmup
+                scratch.close()
+                scratch = new_cache()
+                pipe.set_cache(scratch)
+            miss_path = min(trial, key=trial.get)
+        elif stage_ring is not None:
+            miss_path = "staged"
+    pipe.tier = stage_ring if miss_path == "staged" else None
+    if args.warmup > 0 and not trial:
         pipe.run(seeds_dev, w.rng_seeds, args.warmup)
     scratch.close()
 
@@ -181,6 +203,8 @@ def main():
             "mean_input_nodes": tot_n / args.steps,
             "hit_ratio_cumulative": tot_hit / max(tot_n, 1),
             "hit_ratio_steady_state": steady_ratio,
+            "miss_path": miss_path,
+            "miss_path_trial_ms_per_batch": trial or None,
             "gathered_feature_GBps": rb * tot_n / elapsed / 1e9,
         },
     }
