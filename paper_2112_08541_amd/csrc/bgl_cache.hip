@@ -87,6 +87,7 @@ struct bgl_cache {
     struct Rec { int stage; int ev; };
     std::vector<Rec> prof_rec;
     double prof_overhead_ms;  // event pair around an (almost) empty kernel
+    int64_t prof_dropped;     // timed launches that got no events (event creation failed)
     double prof_ms[BGL_NUM_STAGES];
     int64_t prof_n[BGL_NUM_STAGES];
 };
@@ -524,7 +525,18 @@ struct Prof {
     bool exact;
     Prof(bgl_cache *c_, int stage, hipStream_t st_, bool exact_ = true) : c(c_), st(st_), exact(exact_)
     {
-        if (!(c->profiling & (1u << stage)) || c->prof_rec.size() >= PROF_RING) return;
+        if (!(c->profiling & (1u << stage))) return;
+        if (2 * (c->prof_rec.size() + 1) > c->prof_ev.size()) {  // more timed launches than events: add some
+            const size_t old = c->prof_ev.size();
+            c->prof_ev.resize(old + 2 * PROF_RING, nullptr);
+            for (size_t k = old; k < c->prof_ev.size(); ++k)
+                if (hipEventCreate(&c->prof_ev[k]) != hipSuccess) {
+                    for (size_t j = old; j < k; ++j) (void)hipEventDestroy(c->prof_ev[j]);
+                    c->prof_ev.resize(old);
+                    c->prof_dropped += 1;
+                    return;
+                }
+        }
         ev = (int)c->prof_rec.size() * 2;
         c->prof_rec.push_back({stage, ev});
         if (exact) {
@@ -623,6 +635,7 @@ extern "C" int bgl_cache_create(int64_t capacity_rows, int32_t row_bytes,
     c->features = feat_dev;
     c->features_in_hbm = attr.type == hipMemoryTypeDevice;
     c->profiling = 0;
+    c->prof_dropped = 0;
     c->timed_start = c->timed_stop = nullptr;
     c->fetch_pending = false;
     c->map_pending = false;
@@ -1072,6 +1085,7 @@ extern "C" int bgl_cache_set_profiling(bgl_cache_t *c, int enable)
     }
     c->prof_rec.clear();
     c->prof_rec.reserve(PROF_RING);
+    c->prof_dropped = 0;
     for (int s = 0; s < BGL_NUM_STAGES; ++s) { c->prof_ms[s] = 0; c->prof_n[s] = 0; }
     c->profiling = (unsigned)enable;
     if (enable) {
@@ -1104,6 +1118,9 @@ extern "C" int bgl_cache_profile(bgl_cache_t *c, int stage, double *total_ms, in
     if (stage < 0 || stage >= BGL_NUM_STAGES) BGL_FAIL(BGL_EINVAL, "unknown stage %d", stage);
     BGL_HIP(hipDeviceSynchronize());
     drain_profile(c);
+    if (c->prof_dropped > 0)
+        BGL_FAIL(BGL_ENOMEM, "%lld timed launches could not get events; the stage totals are incomplete",
+                 (long long)c->prof_dropped);
     if (total_ms) *total_ms = c->prof_ms[stage];
     if (launches) *launches = c->prof_n[stage];
     return BGL_OK;
