@@ -183,7 +183,9 @@ __global__ __launch_bounds__(KEYS_PER_TILE) void k_split_list(const int32_t *__r
                                                               const int32_t *__restrict__ mbs,
                                                               int32_t *miss_pos, int32_t *hit_pos,
                                                               int32_t *hit_slot, CacheDev *dev,
-                                                              int64_t *n_hit_host)
+                                                              int64_t *n_hit_host,
+                                                              const int32_t *__restrict__ ids,
+                                                              int64_t num_nodes, int32_t *miss_ids_host)
 {
     __shared__ int sh_scan[KEYS_PER_TILE / kWave];
     __shared__ int sh_base;
@@ -197,8 +199,14 @@ __global__ __launch_bounds__(KEYS_PER_TILE) void k_split_list(const int32_t *__r
     const int flag = (i < n && slot < 0) ? 1 : 0;
     const int ex = block_excl_scan<KEYS_PER_TILE>(flag, sh_scan, tot);  // its barriers publish sh_base
     const int mrank = sh_base + ex;
-    if (flag) miss_pos[mrank] = (int32_t)i;
-    else if (i < n) {
+    if (flag) {
+        miss_pos[mrank] = (int32_t)i;
+        if (miss_ids_host) {  // a host tier that keeps nothing: it only wants the ids of the misses, in order
+            const int32_t id = ids[i];
+            miss_ids_host[mrank] = id;
+            if (id < 0 || (int64_t)id >= num_nodes) n_hit_host[3] = 1;  // the host refuses the batch
+        }
+    } else if (i < n) {
         hit_pos[i - mrank] = (int32_t)i;
         hit_slot[i - mrank] = slot;
     }
@@ -210,6 +218,10 @@ __global__ __launch_bounds__(KEYS_PER_TILE) void k_split_list(const int32_t *__r
         dev->hits += (unsigned long long)(n - n_miss);
         // page-locked host memory: visible to the host once the kernel has completed
         if (n_hit_host) *n_hit_host = n - n_miss;
+        if (miss_ids_host) {  // the tier's counts: nothing found there, everything to be brought in
+            n_hit_host[1] = 0;
+            n_hit_host[2] = n_miss;
+        }
     }
 }
 
@@ -320,7 +332,8 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_miss(
 }
 
 // Tiered lookup: out[miss_pos[r]] = rows[p] for listed misses l0 <= l < l0 + count
-// of the GPU cache, r = rank[l]; rows is the host tier's page-locked ring and
+// of the GPU cache, r = rank[l] (r = l without a list: a tier that keeps nothing
+// lists every miss); rows is the host tier's page-locked ring and
 // p = pos[l] (rows the tier held) or, with SEQ, (ptail + l) mod ring (rows the
 // host threads have just brought in, in list order).  Same launch shape and
 // write-through rule as k_fetch_miss.
@@ -350,7 +363,7 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_rows(
                 int64_t l; int c;
                 RowSplit<Q>::split(idx, q, l, c);
                 l += l0;
-                const int64_t r = rank[l];
+                const int64_t r = rank ? rank[l] : l;
                 const int64_t p = SEQ ? (int64_t)((ptail + (unsigned long long)l) % (unsigned long long)ring)
                                       : (int64_t)pos[l];
                 v[k] = rows[p * qq + c];
@@ -740,6 +753,7 @@ int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, in
     }
     c->last_n = n;
     const int q = c->row_bytes / 16;
+    if (tier) bgl::tier_prepare(tier);
     if (c->fetch_pending && c->fetch_stream != ms) {
         // the previous call's fetch still reads that call's lists
         BGL_HIP(hipStreamWaitEvent(ms, c->ev_miss, 0));
@@ -759,7 +773,7 @@ int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, in
             Prof p(c, BGL_STAGE_MISS_LIST, ms, false);
             hipLaunchKernelGGL(k_split_list, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), 0, ms, out_slot,
                                n, c->mbs, miss_pos, c->hit_pos, c->hit_pos + c->hit_cap, c->dev,
-                               n_hit_dev);
+                               n_hit_dev, ids, c->num_nodes, tier ? bgl::tier_ids_device_if_passthrough(tier) : nullptr);
         }
         if (tier) {
             const int rc = bgl::tier_enqueue_lookup(tier, ids, miss_pos, &c->dev->n_miss_last, n, ms);

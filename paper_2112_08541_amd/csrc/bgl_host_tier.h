@@ -18,7 +18,7 @@ struct TierPlan {
     const int32_t *hit_rank;   // device: ranks the tier holds, ascending ...
     const int32_t *hit_pos;    // ... and the ring position of each one's row
     int64_t n_hit;
-    const int32_t *miss_rank;  // device: ranks it does not hold, ascending; the j-th one's row
+    const int32_t *miss_rank;  // device: ranks it does not hold, ascending (null: all of them); the j-th one's row
     int64_t n_miss;            // goes to ring position (ptail + j) mod ring
     uint64_t ptail;
     int64_t ring;
@@ -29,6 +29,12 @@ struct TierPlan {
 int64_t *tier_count_device(bgl_host_tier *t);
 const char *tier_rows_device(bgl_host_tier *t);
 int64_t tier_max_batch(const bgl_host_tier *t);
+// A tier of capacity 0 has no map to look anything up in: the cache's own list kernel writes the ids
+// of its misses, in order, to this page-locked list (device-visible address) and the counts
+// [1] = 0, [2] = number of misses, [3] |= bad id.  Null for a real tier.
+int32_t *tier_ids_device_if_passthrough(bgl_host_tier *t);
+// Before the lookup kernels of a batch are enqueued: clear the words they only ever set.
+void tier_prepare(bgl_host_tier *t);
 int32_t tier_row_bytes(const bgl_host_tier *t);
 int64_t tier_num_nodes(const bgl_host_tier *t);
 

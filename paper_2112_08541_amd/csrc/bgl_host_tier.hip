@@ -281,6 +281,10 @@ namespace bgl {
 int64_t *tier_count_device(bgl_host_tier *t) { return reinterpret_cast<int64_t *>(t->pinned_dev); }
 const char *tier_rows_device(bgl_host_tier *t) { return t->rows_dev; }
 int64_t tier_max_batch(const bgl_host_tier *t) { return t->max_batch; }
+int32_t *tier_ids_device_if_passthrough(bgl_host_tier *t)
+{
+    return t->capacity == 0 ? reinterpret_cast<int32_t *>(t->pinned_dev + 64) : nullptr;
+}
 int32_t tier_row_bytes(const bgl_host_tier *t) { return t->row_bytes; }
 int64_t tier_num_nodes(const bgl_host_tier *t) { return t->num_nodes; }
 
@@ -291,7 +295,7 @@ int tier_enqueue_lookup(bgl_host_tier *t, const int32_t *ids, const int32_t *mis
     if (n_upper > t->max_batch)
         BGL_FAIL(BGL_ECAPACITY, "%lld ids exceed the tier's max_batch_rows %lld", (long long)n_upper,
                  (long long)t->max_batch);
-    t->counts()[3] = 0;  // set by the lookup kernel when it meets an id outside [0, num_nodes)
+    if (t->capacity == 0) return BGL_OK;  // the cache's own list kernel has sent ids and counts (tier_prepare)
     if (n_upper == 0) {
         t->counts()[1] = 0;
         t->counts()[2] = 0;
@@ -306,6 +310,14 @@ int tier_enqueue_lookup(bgl_host_tier *t, const int32_t *ids, const int32_t *mis
                        reinterpret_cast<int64_t *>(t->pinned_dev));
     BGL_HIP(hipGetLastError());
     return BGL_OK;
+}
+
+void tier_prepare(bgl_host_tier *t)
+{
+    // set by the lookup kernels when they meet an id outside [0, num_nodes)
+    t->counts()[3] = 0;
+    t->counts()[1] = 0;
+    t->counts()[2] = 0;
 }
 
 int tier_begin(bgl_host_tier *t, int64_t n, TierPlan *plan)
@@ -326,7 +338,7 @@ int tier_begin(bgl_host_tier *t, int64_t n, TierPlan *plan)
     plan->n_miss = n_miss;
     plan->hit_rank = t->hit_rank;
     plan->hit_pos = t->hit_pos;
-    plan->miss_rank = t->miss_rank;
+    plan->miss_rank = t->capacity > 0 ? t->miss_rank : nullptr;  // capacity 0: every rank, in order
     plan->ptail = t->ptail;
     plan->ring = t->ring;
     return BGL_OK;
