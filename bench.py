@@ -46,8 +46,9 @@ def parse_args():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run three plain 1 GiB device-to-device copies (the known-size "
                          "kernel that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
-    ap.add_argument("--graph-placement", choices=("config", "device", "host_pinned"), default="config",
-                    help="where the CSR lives: as the configuration says (default), in HBM, or in page-locked host memory")
+    ap.add_argument("--graph-placement", choices=("config", "device", "host_pinned", "host_pinned_col"), default="config",
+                    help="where the CSR lives: as the configuration says (default), in HBM, in page-locked host "
+                         "memory, or column ids in page-locked host memory with the row offsets in HBM")
     ap.add_argument("--feature-placement", choices=("host_pinned", "device"), default="host_pinned",
                     help="where the feature table lives: page-locked host memory (the path this benchmark is "
                          "about, default) or a copy in HBM (then a miss is an HBM gather; context only)")
@@ -111,7 +112,7 @@ def main():
             feat_dev[lo:lo + step].copy_(torch.from_numpy(fb[lo:lo + step]))
         feat_t = feat_dev.data_ptr()
     where = cfg.graph_placement if args.graph_placement == "config" else args.graph_placement
-    placement = B.BGL_HOST_PINNED if where == "host_pinned" else B.BGL_DEVICE
+    placement = {"host_pinned": B.BGL_HOST_PINNED, "host_pinned_col": B.BGL_HOST_PINNED_COL}.get(where, B.BGL_DEVICE)
     graph = B.Graph(w.row_ptr, w.col, placement)
     seeds_dev = torch.from_numpy(w.seed_batches).cuda()      # inputs resident in HBM
     nb = cfg.num_batches

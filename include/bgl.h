@@ -46,6 +46,7 @@ extern "C" {
 /* Where bgl_graph_load_csr keeps the CSR arrays. */
 #define BGL_DEVICE 0      /* copy both arrays into HBM */
 #define BGL_HOST_PINNED 1 /* caller's arrays are page-locked; kernels read them in place */
+#define BGL_HOST_PINNED_COL 2 /* col_idx as BGL_HOST_PINNED; row_ptr is copied into HBM */
 
 typedef struct bgl_graph bgl_graph_t;
 typedef struct bgl_cache bgl_cache_t;
@@ -63,7 +64,10 @@ const char *bgl_last_error(void);
  *   placement    BGL_DEVICE: arrays are copied to HBM, the caller may free its
  *                copies on return.  BGL_HOST_PINNED: arrays must be page-locked
  *                (hipHostMalloc or equivalent) and stay alive and unchanged
- *                until bgl_graph_destroy.
+ *                until bgl_graph_destroy.  BGL_HOST_PINNED_COL: the same for
+ *                col_idx only; row_ptr (4 or 8 bytes per node) is copied to
+ *                HBM, which takes the offset reads of sampling off the host
+ *                link, and the caller may free its row_ptr on return.
  * Validated on the host: row_ptr[0] == 0, non-decreasing, row_ptr[N] ==
  * num_edges, every degree < 2^31, every column id in [0, num_nodes).
  * Errors: BGL_EINVAL (null pointers, bad sizes, failed validation, memory not

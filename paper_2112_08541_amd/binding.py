@@ -21,7 +21,7 @@ BGL_OK, BGL_EINVAL, BGL_ENOMEM, BGL_EHIP, BGL_ECAPACITY, BGL_EUNSUPPORTED = 0, -
 BGL_MAX_HOPS = 8
 BGL_MAX_FANOUT = 64
 BGL_COUNTS_LEN = 2 * BGL_MAX_HOPS + 2
-BGL_DEVICE, BGL_HOST_PINNED = 0, 1
+BGL_DEVICE, BGL_HOST_PINNED, BGL_HOST_PINNED_COL = 0, 1, 2
 (STAGE_PROBE, STAGE_MISS_LIST, STAGE_GATHER_HIT, STAGE_FETCH_MISS,
  STAGE_INSERT_MAP, STAGE_INSERT_ROWS) = range(6)
 STAGE_NAMES = ["probe", "miss_list", "gather_hit", "fetch_miss", "insert_map", "insert_rows"]
@@ -155,7 +155,7 @@ class Graph:
         self.num_nodes = int(row_ptr.shape[0]) - 1
         self.num_edges = int(col_idx.shape[0])
         self.placement = placement
-        self._keep = (row_ptr, col_idx) if placement == BGL_HOST_PINNED else None
+        self._keep = (row_ptr, col_idx) if placement != BGL_DEVICE else None
         h = C.c_void_p()
         _check(lib().bgl_graph_load_csr(_host_ptr(row_ptr), bits, _host_ptr(col_idx), self.num_nodes,
                                         self.num_edges, placement, C.byref(h)))

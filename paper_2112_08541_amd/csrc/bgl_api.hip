@@ -71,7 +71,7 @@ extern "C" int bgl_graph_load_csr(const void *row_ptr, int row_ptr_bits, const i
     if (row_ptr_bits == 32 && num_edges > INT32_MAX)
         BGL_FAIL(BGL_EINVAL, "num_edges needs 64-bit row offsets");
     if (num_edges > 0 && !col_idx) BGL_FAIL(BGL_EINVAL, "col_idx is null");
-    if (placement != BGL_DEVICE && placement != BGL_HOST_PINNED)
+    if (placement != BGL_DEVICE && placement != BGL_HOST_PINNED && placement != BGL_HOST_PINNED_COL)
         BGL_FAIL(BGL_EINVAL, "unknown placement %d", placement);
 
     int rc = row_ptr_bits == 64
@@ -105,6 +105,22 @@ extern "C" int bgl_graph_load_csr(const void *row_ptr, int row_ptr_bits, const i
         }
         g->row_ptr = g->owned_row_ptr;
         g->col = static_cast<const int32_t *>(g->owned_col);
+    } else if (placement == BGL_HOST_PINNED_COL) {
+        // offsets (8 or 4 bytes per node) in HBM, the column ids stay where they are
+        const void *col_dev = nullptr;
+        if (num_edges > 0 && device_view(col_idx, &col_dev) != BGL_OK) {
+            delete g;
+            BGL_FAIL(BGL_EINVAL, "BGL_HOST_PINNED_COL needs a page-locked col_idx");
+        }
+        hipError_t e;
+        if ((e = hipMalloc(&g->owned_row_ptr, rp_bytes)) != hipSuccess ||
+            (e = hipMemcpy(g->owned_row_ptr, row_ptr, rp_bytes, hipMemcpyHostToDevice)) != hipSuccess) {
+            bgl::set_error("copying the row offsets to the device failed: %s", hipGetErrorString(e));
+            bgl_graph_destroy(g);
+            return e == hipErrorOutOfMemory ? BGL_ENOMEM : BGL_EHIP;
+        }
+        g->row_ptr = g->owned_row_ptr;
+        g->col = static_cast<const int32_t *>(col_dev);
     } else {
         const void *rp_dev = nullptr, *col_dev = nullptr;
         if (device_view(row_ptr, &rp_dev) != BGL_OK ||

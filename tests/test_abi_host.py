@@ -88,6 +88,7 @@ def test_null_handles_are_rejected_without_touching_the_gpu(L):
     bad_col = np.array([1, 2], dtype=np.int32)
     assert L.bgl_graph_load_csr(rp.ctypes.data, 32, bad_col.ctypes.data, 2, 2, 0, C.byref(h)) == B.BGL_EINVAL
     assert L.bgl_graph_load_csr(rp.ctypes.data, 32, col.ctypes.data, 2, 2, 7, C.byref(h)) == B.BGL_EINVAL
+    assert (B.BGL_DEVICE, B.BGL_HOST_PINNED, B.BGL_HOST_PINNED_COL) == (0, 1, 2)
     feats = np.zeros((4, 4), dtype=np.float32)
     assert L.bgl_cache_create(0, 16, feats.ctypes.data, 4, C.byref(h)) == B.BGL_EINVAL
     assert L.bgl_cache_create(4, 20, feats.ctypes.data, 4, C.byref(h)) == B.BGL_EINVAL

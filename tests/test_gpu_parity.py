@@ -119,8 +119,9 @@ def test_sample_high_degree_hub_and_host_pinned_graph(B, torch_mod):
     col_t = torch_mod.from_numpy(col).pin_memory()
     seeds = [100, 7, 3, 4000]
     for fan in ([15, 10], [64, 64]):
-        res = gpu_sample(B, torch_mod, rp_t, col_t, seeds, fan, 99, B.BGL_HOST_PINNED)
-        assert_sample_equal(res, oracle.sample_khop(rp, col, seeds, fan, 99))
+        for placement in (B.BGL_HOST_PINNED, B.BGL_HOST_PINNED_COL):
+            res = gpu_sample(B, torch_mod, rp_t, col_t, seeds, fan, 99, placement)
+            assert_sample_equal(res, oracle.sample_khop(rp, col, seeds, fan, 99))
 
 
 def test_sample_is_deterministic_and_seed_sensitive(B, torch_mod):
