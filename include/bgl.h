@@ -201,9 +201,11 @@ int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64_t n, void 
  *   n_miss          number of entries of miss_pos to insert, or -1 to use the
  *                   miss count the last bgl_cache_lookup_gather left on the
  *                   device (no host round trip)
- * Must be enqueued after the lookup_gather that produced its inputs (same
- * stream, or ordered by the caller).  The map update is enqueued first and does
- * not wait for that call's miss fetch; the row copy waits for it on the device.
+ * Called after the lookup_gather that produced its inputs.  On that call's
+ * main_stream it is in stream order; on any other stream it first waits (on
+ * the device) for that call's lists and hit gather, and the next lookup waits
+ * for it.  The map update is enqueued first and does not wait for the miss
+ * fetch; the row copy waits for it on the device.
  * Errors: BGL_EINVAL, BGL_EHIP.
  */
 int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const int32_t *miss_pos,
