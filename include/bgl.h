@@ -335,13 +335,26 @@ int bgl_host_tier_destroy(bgl_host_tier_t *t);
  * cache still needs its bgl_cache_insert_fifo.  ids, out_slot and miss_pos must
  * stay untouched until main_stream has passed this call.  ids must be distinct.
  * One tier serves one cache's calls in order; it is not thread-safe.
+ *   early_lookup    0: lookup_stream is ignored.  1 (needs a tier of capacity 0
+ *           and write-through mode): the map lookup and the lists run on
+ *           lookup_stream instead of main_stream, i.e. without waiting for the
+ *           previous call's miss fetch when that is what main_stream is busy
+ *           with, so the host has the missing ids and packs rows while that
+ *           fetch is still on the link; the hit gather and everything after it
+ *           stay on main_stream and side_stream.  ids must be ready in
+ *           lookup_stream order; the previous call's bgl_cache_insert_fifo must
+ *           have been enqueued (on lookup_stream, or it is waited for); out_slot
+ *           and miss_pos are overwritten as soon as lookup_stream gets there, so
+ *           whoever reads the previous call's out_slot / miss_pos must be done
+ *           in lookup_stream order too.
  * Errors: as bgl_cache_lookup_gather, plus BGL_EINVAL (cache and tier differ in
  * row_bytes or num_nodes; an id outside [0, num_nodes): no level is changed),
  * BGL_ECAPACITY (n > max_batch_rows).
  */
 int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t, const int32_t *ids, int64_t n,
                                    void *out_rows, int32_t *out_slot, int32_t *miss_pos,
-                                   int64_t *n_hit, void *main_stream, void *side_stream);
+                                   int64_t *n_hit, void *main_stream, void *side_stream,
+                                   void *lookup_stream, int early_lookup);
 
 /*
  * Tier state for tests: slot_to_node (capacity_rows ints, -1 = empty), the

@@ -77,7 +77,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     L.bgl_cache_wait_lists.argtypes = [vp, vp]
     L.bgl_host_tier_create.argtypes = [vp, i64, i32, i64, i64, i32, C.POINTER(vp)]
     L.bgl_host_tier_destroy.argtypes = [vp]
-    L.bgl_cache_lookup_gather_tiered.argtypes = [vp, vp, vp, i64, vp, vp, vp, C.POINTER(i64), vp, vp]
+    L.bgl_cache_lookup_gather_tiered.argtypes = [vp, vp, vp, i64, vp, vp, vp, C.POINTER(i64), vp, vp, vp, ci]
     L.bgl_host_tier_export_state.argtypes = [vp, vp, C.POINTER(C.c_uint64), vp]
     L.bgl_host_tier_stats.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(C.c_double), C.POINTER(u64), C.POINTER(i32)]
     L.bgl_cache_export_state.argtypes = [vp, vp, C.POINTER(u64), vp]
@@ -287,8 +287,9 @@ class Cache:
 
     def lookup_gather_tiered(self, tier: "HostTier", ids: torch.Tensor, n: int, out_rows: torch.Tensor,
                              out_slot: torch.Tensor, miss_pos: torch.Tensor, main_stream=None,
-                             side_stream=None):
-        """Returns (hits in this cache, hits in the tier)."""
+                             side_stream=None, lookup_stream=None):
+        """Returns (hits in this cache, hits in the tier).  lookup_stream: run the map lookup and
+        the lists there (early lookup; tier of capacity 0 and write-through mode only)."""
         if n > 0 and (ids.numel() < n or out_slot.numel() < n or miss_pos.numel() < n or
                       out_rows.numel() * out_rows.element_size() < n * self.row_bytes):
             raise ValueError("an argument is smaller than n")
@@ -296,7 +297,8 @@ class Cache:
         _check(lib().bgl_cache_lookup_gather_tiered(
             self._h, tier._h, _dev_ptr(ids, torch.int32), n, _dev_ptr(out_rows),
             _dev_ptr(out_slot, torch.int32), _dev_ptr(miss_pos, torch.int32), n_hit,
-            _stream_handle(main_stream), None if side_stream is None else int(side_stream.cuda_stream)))
+            _stream_handle(main_stream), None if side_stream is None else int(side_stream.cuda_stream),
+            None if lookup_stream is None else _stream_handle(lookup_stream), 0 if lookup_stream is None else 1))
         return int(n_hit[0]), int(n_hit[1])
 
     def insert_fifo(self, ids: torch.Tensor, miss_pos: torch.Tensor, n_miss: int,

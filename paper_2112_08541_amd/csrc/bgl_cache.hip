@@ -65,6 +65,9 @@ struct bgl_cache {
     int32_t *hit_pos;       // hits of the most recent lookup: hit_cap positions, then hit_cap slots
     int64_t hit_cap;
     int64_t last_n;         // n of the most recent lookup
+    int32_t *mpos_copy[2];  // early lookups: the library's own copy of miss_pos, alternating between calls
+    int64_t mpos_cap[2];
+    uint64_t lookup_calls;
     uint64_t insert_calls;  // FIFO updates enqueued so far (selects the live copy of tail)
     hipStream_t own_side;
     // Ordering between streams.  ev_listed: lists and hit rows of the last lookup are complete
@@ -185,7 +188,8 @@ __global__ __launch_bounds__(KEYS_PER_TILE) void k_split_list(const int32_t *__r
                                                               int32_t *hit_slot, CacheDev *dev,
                                                               int64_t *n_hit_host,
                                                               const int32_t *__restrict__ ids,
-                                                              int64_t num_nodes, int32_t *miss_ids_host)
+                                                              int64_t num_nodes, int32_t *miss_ids_host,
+                                                              int32_t *miss_pos_copy)
 {
     __shared__ int sh_scan[KEYS_PER_TILE / kWave];
     __shared__ int sh_base;
@@ -201,6 +205,7 @@ __global__ __launch_bounds__(KEYS_PER_TILE) void k_split_list(const int32_t *__r
     const int mrank = sh_base + ex;
     if (flag) {
         miss_pos[mrank] = (int32_t)i;
+        if (miss_pos_copy) miss_pos_copy[mrank] = (int32_t)i;
         if (miss_ids_host) {  // a host tier that keeps nothing: it only wants the ids of the misses, in order
             const int32_t id = ids[i];
             miss_ids_host[mrank] = id;
@@ -232,7 +237,7 @@ template <int Q>
 struct RowSplit {
     __device__ __forceinline__ static void split(int64_t idx, int q, int64_t &row, int &c)
     {
-        if (Q > 0) { row = idx / Q; c = (int)(idx - row * Q); }
+        if constexpr (Q > 0) { row = idx / Q; c = (int)(idx - row * Q); }
         else { row = idx / q; c = (int)(idx - row * q); }
     }
 };
@@ -342,10 +347,9 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_rows(
     const int32_t *__restrict__ rank, const int32_t *__restrict__ pos, int64_t l0, int64_t count,
     unsigned long long ptail, int64_t ring, const int32_t *__restrict__ miss_pos, int q,
     const uint4 *__restrict__ rows, uint4 *__restrict__ out, const CacheDev *dev,
-    uint4 *__restrict__ buffer, int64_t capacity, int par)
+    uint4 *__restrict__ buffer, int64_t capacity, int par, int64_t n_miss)
 {
     const int qq = Q > 0 ? Q : q;
-    const int64_t n_miss = dev->n_miss_last;
     const int64_t total = count * qq;
     const int64_t start = n_miss > capacity ? n_miss - capacity : 0;
     const unsigned long long tail = WT ? dev->tail[par] : 0ull;
@@ -663,6 +667,9 @@ extern "C" int bgl_cache_create(int64_t capacity_rows, int32_t row_bytes,
     c->hit_pos = nullptr;
     c->hit_cap = 0;
     c->last_n = 0;
+    c->mpos_copy[0] = c->mpos_copy[1] = nullptr;
+    c->mpos_cap[0] = c->mpos_cap[1] = 0;
+    c->lookup_calls = 0;
     c->insert_calls = 0;
     // load <= 1/2 of the 15 usable words per bucket
     uint64_t nbk = 1;
@@ -721,20 +728,28 @@ extern "C" int bgl_cache_destroy(bgl_cache_t *c)
     (void)hipFree(c->dev);
     (void)hipFree(c->mbs);
     (void)hipFree(c->hit_pos);
+    (void)hipFree(c->mpos_copy[0]);
+    (void)hipFree(c->mpos_copy[1]);
     delete c;
     return BGL_OK;
 }
 
 namespace {
 
-// First half of a lookup on stream ms: map lookup, lists, with a host tier its
-// lookup for the misses (followed by ev_ids), hit gather, ev_listed.
+// First half of a lookup: map lookup and lists on stream ls, with a host tier its
+// lookup for the misses (followed by ev_ids), then the hit gather on stream ms,
+// ev_listed.  ls == ms unless the lookup runs early (see the tiered call): then
+// the lists go to *mpos_used, the library's own copy of miss_pos, because the
+// caller's miss_pos of the previous call is still being read by that call's
+// fetch while this one's lists are written.
 int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, int32_t *out_slot,
-                 int32_t *miss_pos, int64_t *n_hit_dev, hipStream_t ms, bgl_host_tier *tier)
+                 int32_t *miss_pos, int64_t *n_hit_dev, hipStream_t ms, hipStream_t ls, bgl_host_tier *tier,
+                 const int32_t **mpos_used)
 {
+    const bool early = ls != ms;
     const int64_t tiles = bgl::ceil_div(n, KEYS_PER_TILE);
     if (tiles + 1 > c->mbs_cap) {
-        BGL_HIP(hipStreamSynchronize(ms));
+        BGL_HIP(hipDeviceSynchronize());
         (void)hipFree(c->mbs);
         c->mbs = nullptr;
         c->mbs_cap = 0;
@@ -743,7 +758,7 @@ int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, in
         c->mbs_cap = cap;
     }
     if (n > c->hit_cap) {
-        BGL_HIP(hipStreamSynchronize(ms));
+        BGL_HIP(hipDeviceSynchronize());
         (void)hipFree(c->hit_pos);
         c->hit_pos = nullptr;
         c->hit_cap = 0;
@@ -751,50 +766,67 @@ int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, in
         BGL_HIP(hipMalloc((void **)&c->hit_pos, 2 * sizeof(int32_t) * (size_t)cap));  // positions, then slots
         c->hit_cap = cap;
     }
+    int32_t *mpos_copy = nullptr;
+    if (early) {
+        const int g = (int)(c->lookup_calls & 1);
+        if (n > c->mpos_cap[g]) {
+            BGL_HIP(hipDeviceSynchronize());
+            (void)hipFree(c->mpos_copy[g]);
+            c->mpos_copy[g] = nullptr;
+            c->mpos_cap[g] = 0;
+            const int64_t cap = std::max<int64_t>(n + n / 2, 4096);
+            BGL_HIP(hipMalloc((void **)&c->mpos_copy[g], sizeof(int32_t) * (size_t)cap));
+            c->mpos_cap[g] = cap;
+        }
+        mpos_copy = c->mpos_copy[g];
+    }
+    *mpos_used = early ? mpos_copy : miss_pos;
+    c->lookup_calls += 1;
     c->last_n = n;
     const int q = c->row_bytes / 16;
     if (tier) bgl::tier_prepare(tier);
-    if (c->fetch_pending && c->fetch_stream != ms) {
+    if (c->map_pending && c->map_stream != ls) BGL_HIP(hipStreamWaitEvent(ls, c->ev_map, 0));
+    if (!early && c->fetch_pending && c->fetch_stream != ms) {
         // the previous call's fetch still reads that call's lists
         BGL_HIP(hipStreamWaitEvent(ms, c->ev_miss, 0));
     }
-    if (c->map_pending && c->map_stream != ms) BGL_HIP(hipStreamWaitEvent(ms, c->ev_map, 0));
+    if (n > 0) {
+        {
+            Prof p(c, BGL_STAGE_PROBE, ls);
+            launch(c, ls, k_probe, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), ids, n, c->num_nodes, c->table,
+                   c->num_buckets - 1, out_slot, c->mbs, c->dev);
+        }
+        {
+            Prof p(c, BGL_STAGE_MISS_LIST, ls, false);
+            hipLaunchKernelGGL(k_split_list, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), 0, ls, out_slot,
+                               n, c->mbs, miss_pos, c->hit_pos, c->hit_pos + c->hit_cap, c->dev,
+                               n_hit_dev, ids, c->num_nodes,
+                               tier ? bgl::tier_ids_device_if_passthrough(tier) : nullptr, mpos_copy);
+        }
+    } else {
+        hipLaunchKernelGGL(k_empty_lookup, dim3(1), dim3(64), 0, ls, c->dev, n_hit_dev);
+    }
+    if (tier) {
+        const int rc = bgl::tier_enqueue_lookup(tier, ids, miss_pos, &c->dev->n_miss_last, n, ls);
+        if (rc != BGL_OK) return rc;
+        BGL_HIP(hipEventRecord(c->ev_ids, ls));
+    }
+    if (early) {
+        // the hit gather reads rows the previous fetch may still be writing, and needs the lists
+        if (c->fetch_pending && c->fetch_stream != ms) BGL_HIP(hipStreamWaitEvent(ms, c->ev_miss, 0));
+        BGL_HIP(hipStreamWaitEvent(ms, c->ev_ids, 0));
+    }
     c->fetch_pending = false;
     c->map_pending = false;
     c->last_main = ms;
     c->ev_listed_valid = true;
     if (n > 0) {
-        {
-            Prof p(c, BGL_STAGE_PROBE, ms);
-            launch(c, ms, k_probe, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), ids, n, c->num_nodes, c->table,
-                   c->num_buckets - 1, out_slot, c->mbs, c->dev);
-        }
-        {
-            Prof p(c, BGL_STAGE_MISS_LIST, ms, false);
-            hipLaunchKernelGGL(k_split_list, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), 0, ms, out_slot,
-                               n, c->mbs, miss_pos, c->hit_pos, c->hit_pos + c->hit_cap, c->dev,
-                               n_hit_dev, ids, c->num_nodes, tier ? bgl::tier_ids_device_if_passthrough(tier) : nullptr);
-        }
-        if (tier) {
-            const int rc = bgl::tier_enqueue_lookup(tier, ids, miss_pos, &c->dev->n_miss_last, n, ms);
-            if (rc != BGL_OK) return rc;
-            BGL_HIP(hipEventRecord(c->ev_ids, ms));
-        }
-        {
-            Prof p(c, BGL_STAGE_GATHER_HIT, ms);
-            dispatch_q(q, [&](auto Q) {
-                launch(c, ms, k_gather_hits<decltype(Q)::value>, dim3(copy_blocks(n, q)), dim3(COPY_THREADS),
-                       c->hit_pos, c->hit_pos + c->hit_cap, q, reinterpret_cast<const uint4 *>(c->buffer),
-                       reinterpret_cast<uint4 *>(out_rows), c->dev);
-            });
-        }
-    } else {
-        hipLaunchKernelGGL(k_empty_lookup, dim3(1), dim3(64), 0, ms, c->dev, n_hit_dev);
-        if (tier) {
-            const int rc = bgl::tier_enqueue_lookup(tier, ids, miss_pos, &c->dev->n_miss_last, 0, ms);
-            if (rc != BGL_OK) return rc;
-            BGL_HIP(hipEventRecord(c->ev_ids, ms));
-        }
+        Prof p(c, BGL_STAGE_GATHER_HIT, ms);
+        dispatch_q(q, [&](auto Q) {
+            launch(c, ms, k_gather_hits<decltype(Q)::value>, dim3(copy_blocks(n, q)), dim3(COPY_THREADS),
+                   c->hit_pos, c->hit_pos + c->hit_cap, q, reinterpret_cast<const uint4 *>(c->buffer),
+                   reinterpret_cast<uint4 *>(out_rows), c->dev);
+        });
     }
     // The miss fetch starts once the hit gather is done: host-link reads
     // queued in the memory pipeline would otherwise stall the gather's HBM
@@ -840,7 +872,8 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
         n_hit_dev = static_cast<int64_t *>(attr.devicePointer);
     }
     const int q = c->row_bytes / 16;
-    rc = lookup_phase(c, ids, n, out_rows, out_slot, miss_pos, n_hit_dev, ms, nullptr);
+    const int32_t *mpos = nullptr;
+    rc = lookup_phase(c, ids, n, out_rows, out_slot, miss_pos, n_hit_dev, ms, ms, nullptr, &mpos);
     if (rc != BGL_OK) return rc;
     if (n > 0) {
         if (ss != ms) BGL_HIP(hipStreamWaitEvent(ss, c->ev_listed, 0));
@@ -873,7 +906,7 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
 extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t, const int32_t *ids,
                                               int64_t n, void *out_rows, int32_t *out_slot,
                                               int32_t *miss_pos, int64_t *n_hit, void *main_stream,
-                                              void *side_stream)
+                                              void *side_stream, void *lookup_stream, int early_lookup)
 {
     int rc = check_lookup_args(c, ids, n, out_rows, out_slot, miss_pos);
     if (rc != BGL_OK) return rc;
@@ -885,7 +918,17 @@ extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t
     hipStream_t ms = static_cast<hipStream_t>(main_stream);
     hipStream_t ss = side_stream ? static_cast<hipStream_t>(side_stream) : c->own_side;
     const int q = c->row_bytes / 16;
-    rc = lookup_phase(c, ids, n, out_rows, out_slot, miss_pos, bgl::tier_count_device(t), ms, t);
+    // Early lookup: only with a tier that keeps nothing (a real tier's lists are still read by the
+    // previous fetch) and in write-through mode (otherwise the previous call's row copy still
+    // reads the caller's miss_pos).
+    hipStream_t ls = ms;
+    if (early_lookup && static_cast<hipStream_t>(lookup_stream) != ms) {
+        if (bgl::tier_capacity(t) != 0 || !c->write_through)
+            BGL_FAIL(BGL_EINVAL, "early_lookup needs a tier of capacity 0 and write-through mode");
+        ls = static_cast<hipStream_t>(lookup_stream);
+    }
+    const int32_t *mpos = nullptr;
+    rc = lookup_phase(c, ids, n, out_rows, out_slot, miss_pos, bgl::tier_count_device(t), ms, ls, t, &mpos);
     if (rc != BGL_OK) return rc;
     BGL_HIP(hipGetLastError());
     struct Guard {  // whatever goes wrong below, the copy threads are released and the batch is dropped
@@ -915,9 +958,9 @@ extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t
             auto k = c->write_through ? k_fetch_rows<decltype(Q)::value, true, decltype(seq)::value>
                                       : k_fetch_rows<decltype(Q)::value, false, decltype(seq)::value>;
             launch(c, ss, k, dim3(blocks), dim3(COPY_THREADS), rank, pos, l0, count,
-                   (unsigned long long)plan.ptail, plan.ring, miss_pos, q, rows,
+                   (unsigned long long)plan.ptail, plan.ring, mpos, q, rows,
                    reinterpret_cast<uint4 *>(out_rows), c->dev, reinterpret_cast<uint4 *>(c->buffer), c->capacity,
-                   par);
+                   par, n - plan.n_hit_gpu);
         });
     };
     // Rows the tier holds cross the link while host threads bring the others in from the
@@ -926,7 +969,8 @@ extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t
     // Small chunks first, so that the link starts early; the copy threads outrun the link
     // only by a little, so the chunks grow until a launch is a few per cent of its kernel.
     {
-        int64_t chunk = plan.n_hit > TIER_CHUNK_ROWS ? TIER_CHUNK_ROWS : TIER_FIRST_CHUNK_ROWS;
+        // (an early lookup is ahead of the link anyway: full chunks from the start)
+        int64_t chunk = (plan.n_hit > TIER_CHUNK_ROWS || ls != ms) ? TIER_CHUNK_ROWS : TIER_FIRST_CHUNK_ROWS;
         for (int64_t launched = 0; launched < plan.n_miss;) {
             const int64_t ready = bgl::tier_copy_progress(t);
             if (ready - launched >= chunk || ready == plan.n_miss) {

@@ -29,6 +29,7 @@ struct TierPlan {
 int64_t *tier_count_device(bgl_host_tier *t);
 const char *tier_rows_device(bgl_host_tier *t);
 int64_t tier_max_batch(const bgl_host_tier *t);
+int64_t tier_capacity(const bgl_host_tier *t);
 // A tier of capacity 0 has no map to look anything up in: the cache's own list kernel writes the ids
 // of its misses, in order, to this page-locked list (device-visible address) and the counts
 // [1] = 0, [2] = number of misses, [3] |= bad id.  Null for a real tier.

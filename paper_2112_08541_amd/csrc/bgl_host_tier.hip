@@ -182,6 +182,7 @@ namespace bgl {
 int64_t *tier_count_device(bgl_host_tier *t) { return reinterpret_cast<int64_t *>(t->pinned_dev); }
 const char *tier_rows_device(bgl_host_tier *t) { return t->rows_dev; }
 int64_t tier_max_batch(const bgl_host_tier *t) { return t->max_batch; }
+int64_t tier_capacity(const bgl_host_tier *t) { return t->capacity; }
 int32_t *tier_ids_device_if_passthrough(bgl_host_tier *t)
 {
     return t->capacity == 0 ? reinterpret_cast<int32_t *>(t->pinned_dev + 64) : nullptr;
@@ -317,7 +318,7 @@ extern "C" int bgl_host_tier_create(const void *store, int64_t num_nodes, int32_
         BGL_FAIL(BGL_EINVAL, "row_bytes must be a positive multiple of 16 (got %d)", row_bytes);
     if (capacity_rows < 0 || capacity_rows > INT32_MAX)
         BGL_FAIL(BGL_EINVAL, "capacity_rows must be in [0, 2^31) (got %lld)", (long long)capacity_rows);
-    if (max_batch_rows < 1 || max_batch_rows > INT32_MAX || capacity_rows + max_batch_rows > INT32_MAX)
+    if (max_batch_rows < 1 || max_batch_rows > INT32_MAX / 2 || capacity_rows + max_batch_rows > INT32_MAX)
         BGL_FAIL(BGL_EINVAL, "max_batch_rows must be >= 1 and capacity_rows + max_batch_rows < 2^31 (got %lld)",
                  (long long)max_batch_rows);
     if (num_threads < 0 || num_threads > 256) BGL_FAIL(BGL_EINVAL, "num_threads must be in [0, 256]");
@@ -332,7 +333,8 @@ extern "C" int bgl_host_tier_create(const void *store, int64_t num_nodes, int32_
     t->row_bytes = row_bytes;
     t->capacity = capacity_rows;
     t->max_batch = max_batch_rows;
-    t->ring = capacity_rows + max_batch_rows;
+    // a tier that keeps nothing may be filled for the next batch while the previous one is still fetched
+    t->ring = capacity_rows > 0 ? capacity_rows + max_batch_rows : 2 * max_batch_rows;
     const size_t mb = (size_t)max_batch_rows;
     const size_t row_total = (size_t)t->ring * (size_t)row_bytes;
     auto fail = [&](int code) { bgl_host_tier_destroy(t); return code; };

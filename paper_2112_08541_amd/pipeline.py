@@ -8,7 +8,10 @@ over the host link, so the loop is built to keep the link busy:
                  one queue, so the next lookup starts the moment a fetch ends
                  (a hand-over between streams costs ~20 us here)
   work stream    sample(i+2), map update(i): they run while fetch(i) holds the link;
-                 both wait for hit gather(i), so nothing competes with the gather
+                 both wait for hit gather(i), so nothing competes with the gather.
+                 With a staging ring (a host tier of capacity 0) also lookup(i+1) and
+                 lists(i+1), right behind map update(i): the host then packs batch i+1's
+                 miss rows while fetch(i) is still on the link
 
 The cache is put in write-through mode (every lookup here is followed by the
 insert of all its misses), which makes the FIFO update a map update that needs no
@@ -93,15 +96,23 @@ class MinibatchPipeline:
                                     main_stream=chain, side_stream=chain,
                                     n_hit_ptr=n_hits.data_ptr() + 8 * i)
             else:
-                # blocks until the host tier has served the GPU cache's misses
+                # Blocks until the host tier has served the GPU cache's misses.  With a tier that keeps
+                # nothing the map lookup runs early, on the work stream (behind the previous batch's map
+                # update), so the host packs this batch's rows while the previous fetch is on the link.
+                early = self.tier.capacity == 0 and self.write_through
                 n_hits[i], h2 = cache.lookup_gather_tiered(self.tier, ids, n, self.out_rows, self.out_slot,
-                                                           self.miss_pos, main_stream=chain, side_stream=chain)
+                                                           self.miss_pos, main_stream=chain, side_stream=chain,
+                                                           lookup_stream=work if early else None)
                 self.tier_hits.append(h2)
+            if self.tier is not None:
+                # the host was held back by the call: the map update first, the next lookup is waiting for it
+                cache.insert_fifo(ids, self.miss_pos, -1, self.out_rows, stream=work)
             if i + 2 < steps:
                 # workspace (i+2) % 3 was batch i-1's; its fetch ended before hit gather(i)
                 cache.wait_lists(work)
                 sbs[i + 2] = sample(i + 2)
-            cache.insert_fifo(ids, self.miss_pos, -1, self.out_rows, stream=work)
+            if self.tier is None:
+                cache.insert_fifo(ids, self.miss_pos, -1, self.out_rows, stream=work)
             n_list.append(n)
             self.last_ids, self.last_n = ids, n
             if on_batch is not None:

@@ -34,7 +34,7 @@ def assert_tier_state_equal(tier, oc2, what):
 
 
 def run_tiered_stream(B, torch, feats, cap1, cap2, batches, write_through, threads, side=True,
-                      cache_has_store=False):
+                      cache_has_store=False, early=None):
     import oracle
     N, rb = feats.shape[0], feats.shape[1] * feats.itemsize
     store = np.ascontiguousarray(feats.view(np.uint8).reshape(N, rb))      # ordinary host memory
@@ -48,6 +48,9 @@ def run_tiered_stream(B, torch, feats, cap1, cap2, batches, write_through, threa
     if write_through:
         gc.set_write_through(True)
     side_stream = torch.cuda.Stream() if side else None
+    # early lookup: the map lookup and the lists run on a stream of their own ("own"), or on the
+    # one that also carries the map updates ("with_insert", as the benchmarked pipeline does)
+    lookup_stream = torch.cuda.Stream() if early else None
     for bi, ids in enumerate(batches):
         n = len(ids)
         ids_t = (torch.tensor(ids, dtype=torch.int32, device="cuda") if n
@@ -55,8 +58,11 @@ def run_tiered_stream(B, torch, feats, cap1, cap2, batches, write_through, threa
         out = torch.full((max(n, 1), rb), 0xCD, dtype=torch.uint8, device="cuda")
         out_slot = torch.full((max(n, 1),), -7, dtype=torch.int32, device="cuda")
         miss_pos = torch.full((max(n, 1),), -7, dtype=torch.int32, device="cuda")
-        h1, h2 = gc.lookup_gather_tiered(tier, ids_t, n, out, out_slot, miss_pos, side_stream=side_stream)
-        gc.insert_fifo(ids_t, miss_pos, -1, out)
+        if lookup_stream is not None:
+            lookup_stream.wait_stream(torch.cuda.current_stream())      # ids_t and the filled outputs
+        h1, h2 = gc.lookup_gather_tiered(tier, ids_t, n, out, out_slot, miss_pos, side_stream=side_stream,
+                                         lookup_stream=lookup_stream)
+        gc.insert_fifo(ids_t, miss_pos, -1, out, stream=lookup_stream if early == "with_insert" else None)
         gc.wait_rows()
         torch.cuda.synchronize()
         # oracle: level 1, then level 2 on level 1's misses, both updated first-in first-out
@@ -123,9 +129,9 @@ def test_tiered_capacity_corners(B, torch_mod, cap1, cap2, threads):
     assert tier.stats()["threads"] == (threads or tier.stats()["threads"])
 
 
-@pytest.mark.parametrize("write_through", [False, True])
+@pytest.mark.parametrize("write_through,early", [(False, None), (True, None), (True, "own"), (True, "with_insert")])
 @pytest.mark.parametrize("side", [False, True])
-def test_staging_only_large_batches(B, torch_mod, write_through, side):
+def test_staging_only_large_batches(B, torch_mod, write_through, side, early):
     """Capacity 0 (every miss row passes through the ring) with batches of several chunks, hits
     that the same batch's insertions evict (small GPU cache), an empty batch, a repeat."""
     rng = np.random.default_rng(77)
@@ -134,7 +140,8 @@ def test_staging_only_large_batches(B, torch_mod, write_through, side):
     batches = [rng.permutation(N)[: int(k)].tolist() for k in (70000, 300, 90000, 26000, 60000, 24576, 24577, 80000)]
     batches.insert(2, [])
     batches.insert(5, batches[4])     # immediate repeat: hits everywhere the cache kept them
-    run_tiered_stream(B, torch_mod, feats, 50000, 0, batches, write_through, 0, side=side, cache_has_store=True)
+    run_tiered_stream(B, torch_mod, feats, 50000, 0, batches, write_through, 0, side=side, cache_has_store=True,
+                      early=early)
 
 
 def test_tiered_uniform_ids_many_chunks(B, torch_mod):
@@ -165,6 +172,9 @@ def test_tiered_argument_errors(B, torch_mod):
     other = B.HostTier(np.zeros((N, 32), dtype=np.uint8), 10, 50, 1)
     with pytest.raises(B.BglError) as e:      # row width differs
         gc.lookup_gather_tiered(other, ids, 10, out, slot, mp)
+    assert e.value.code == B.BGL_EINVAL
+    with pytest.raises(B.BglError) as e:      # early lookup needs capacity 0 and write-through mode
+        gc.lookup_gather_tiered(tier, ids, 10, out, slot, mp, lookup_stream=torch.cuda.Stream())
     assert e.value.code == B.BGL_EINVAL
     bad = ids.clone()
     bad[3] = N + 5
