@@ -78,6 +78,7 @@ struct bgl_cache {
     hipEvent_t ev_ids;      // tiered lookup: the missed ids have reached the host
     hipStream_t last_main, fetch_stream, map_stream;
     bool fetch_pending;     // ev_miss marks a miss fetch that later work may have to wait for
+    bool fetch_reads_caller_lists;  // that fetch reads the caller's miss_pos (not the library's copy)
     bool map_pending;       // ev_map marks a FIFO update the next lookup has to wait for
     bool ev_listed_valid;   // a lookup has recorded ev_listed
     bool write_through;     // the miss fetch also fills the cache buffer (see bgl_cache_set_write_through)
@@ -655,6 +656,7 @@ extern "C" int bgl_cache_create(int64_t capacity_rows, int32_t row_bytes,
     c->prof_dropped = 0;
     c->timed_start = c->timed_stop = nullptr;
     c->fetch_pending = false;
+    c->fetch_reads_caller_lists = true;
     c->map_pending = false;
     c->ev_listed_valid = false;
     c->last_main = c->fetch_stream = c->map_stream = nullptr;
@@ -790,6 +792,10 @@ int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, in
         // the previous call's fetch still reads that call's lists
         BGL_HIP(hipStreamWaitEvent(ms, c->ev_miss, 0));
     }
+    if (early && c->fetch_pending && c->fetch_reads_caller_lists) {
+        // so does it when that call was not an early one: then this one cannot be early either
+        BGL_HIP(hipStreamWaitEvent(ls, c->ev_miss, 0));
+    }
     if (n > 0) {
         {
             Prof p(c, BGL_STAGE_PROBE, ls);
@@ -893,6 +899,7 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
         BGL_HIP(hipEventRecord(c->ev_miss, ss));
         c->fetch_pending = true;
         c->fetch_stream = ss;
+        c->fetch_reads_caller_lists = true;
     }
     BGL_HIP(hipGetLastError());
     if (c->write_through) {
@@ -991,6 +998,7 @@ extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t
     BGL_HIP(hipGetLastError());
     c->fetch_pending = true;
     c->fetch_stream = ss;
+    c->fetch_reads_caller_lists = mpos == miss_pos;
     if (n_hit) {
         n_hit[0] = plan.n_hit_gpu;
         n_hit[1] = plan.n_hit;
@@ -1035,11 +1043,10 @@ extern "C" int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const i
         }
         c->insert_calls += 1;
         BGL_HIP(hipGetLastError());
-        if (other_stream) {
-            BGL_HIP(hipEventRecord(c->ev_map, st));
-            c->map_pending = true;
-            c->map_stream = st;
-        }
+        // (recorded on every stream: the next lookup may run on another one than this call's lookup did)
+        BGL_HIP(hipEventRecord(c->ev_map, st));
+        c->map_pending = true;
+        c->map_stream = st;
         return BGL_OK;
     }
     if (eff > 0) {
@@ -1065,11 +1072,9 @@ extern "C" int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const i
     }
     c->insert_calls += 1;
     BGL_HIP(hipGetLastError());
-    if (other_stream) {
-        BGL_HIP(hipEventRecord(c->ev_map, st));
-        c->map_pending = true;
-        c->map_stream = st;
-    }
+    BGL_HIP(hipEventRecord(c->ev_map, st));
+    c->map_pending = true;
+    c->map_stream = st;
     return BGL_OK;
 }
 

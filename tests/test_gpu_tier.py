@@ -48,8 +48,9 @@ def run_tiered_stream(B, torch, feats, cap1, cap2, batches, write_through, threa
     if write_through:
         gc.set_write_through(True)
     side_stream = torch.cuda.Stream() if side else None
-    # early lookup: the map lookup and the lists run on a stream of their own ("own"), or on the
-    # one that also carries the map updates ("with_insert", as the benchmarked pipeline does)
+    # early lookup: the map lookup and the lists run on a stream of their own ("own"), on the
+    # one that also carries the map updates ("with_insert", as the benchmarked pipeline does), or only
+    # every other call ("alternate")
     lookup_stream = torch.cuda.Stream() if early else None
     for bi, ids in enumerate(batches):
         n = len(ids)
@@ -60,8 +61,9 @@ def run_tiered_stream(B, torch, feats, cap1, cap2, batches, write_through, threa
         miss_pos = torch.full((max(n, 1),), -7, dtype=torch.int32, device="cuda")
         if lookup_stream is not None:
             lookup_stream.wait_stream(torch.cuda.current_stream())      # ids_t and the filled outputs
+        use_ls = lookup_stream if (early != "alternate" or bi % 2 == 1) else None
         h1, h2 = gc.lookup_gather_tiered(tier, ids_t, n, out, out_slot, miss_pos, side_stream=side_stream,
-                                         lookup_stream=lookup_stream)
+                                         lookup_stream=use_ls)
         gc.insert_fifo(ids_t, miss_pos, -1, out, stream=lookup_stream if early == "with_insert" else None)
         gc.wait_rows()
         torch.cuda.synchronize()
@@ -129,7 +131,8 @@ def test_tiered_capacity_corners(B, torch_mod, cap1, cap2, threads):
     assert tier.stats()["threads"] == (threads or tier.stats()["threads"])
 
 
-@pytest.mark.parametrize("write_through,early", [(False, None), (True, None), (True, "own"), (True, "with_insert")])
+@pytest.mark.parametrize("write_through,early", [(False, None), (True, None), (True, "own"), (True, "with_insert"),
+                                                 (True, "alternate")])
 @pytest.mark.parametrize("side", [False, True])
 def test_staging_only_large_batches(B, torch_mod, write_through, side, early):
     """Capacity 0 (every miss row passes through the ring) with batches of several chunks, hits
