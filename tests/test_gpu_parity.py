@@ -378,9 +378,12 @@ def test_overlapped_pipeline_as_benchmarked_matches_oracle(torch_mod, B, write_t
     assert_state_equal(cache, op.cache, "overlapped")
 
 
-def test_overlapped_pipeline_full_epoch_counts_and_final_state(torch_mod, B):
-    """The whole benchmarked epoch (mid, 200 batches, overlapped, write-through): per-batch
-    input and hit counts, the last batch's rows, and the cache state at the end."""
+@pytest.mark.parametrize("miss_path", ["zero_copy", "staged"])
+def test_overlapped_pipeline_full_epoch_counts_and_final_state(torch_mod, B, miss_path):
+    """The whole benchmarked epoch (mid, 200 batches, overlapped, write-through) on both miss
+    paths (staged = the ring of a host tier that keeps nothing, with the early lookup, as
+    bench.py runs it): per-batch input and hit counts, the last batch's rows, and the cache
+    state at the end."""
     from paper_2112_08541_amd.pipeline import MinibatchPipeline
     inputs = _inputs()
     cfg = inputs.CONFIGS["mid"]
@@ -388,6 +391,8 @@ def test_overlapped_pipeline_full_epoch_counts_and_final_state(torch_mod, B):
     graph = B.Graph(w.row_ptr, w.col)
     cache = B.Cache(cfg.cache_rows, w.features.ctypes.data, num_nodes=cfg.num_nodes, row_bytes=cfg.row_bytes)
     pipe = MinibatchPipeline(graph, cache, cfg.batch, cfg.fanouts, cfg.row_bytes)
+    if miss_path == "staged":
+        pipe.tier = B.HostTier(w.features.view(np.uint8).reshape(cfg.num_nodes, cfg.row_bytes), 0, pipe.cap, 0)
     seeds_dev = torch_mod.from_numpy(w.seed_batches).cuda()
     steps = cfg.num_batches
     n_list, hit_list = pipe.run(seeds_dev, w.rng_seeds, steps)
