@@ -105,6 +105,29 @@ def test_sample_random_graph_all_group_widths(B, torch_mod, fanouts):
         assert_sample_equal(res, oracle.sample_khop(rp, col, seeds, list(fanouts), s))
 
 
+def test_sample_random_cases_property(B, torch_mod):
+    """Seeded random graphs, seed lists, fanout lists and call seeds (hypothesis draws them;
+    derandomized, so every run sees the same cases): sampled ids, CSR blocks and sizes equal
+    the oracle's."""
+    import oracle
+    from hypothesis import given, settings, strategies as st, HealthCheck
+
+    @settings(max_examples=40, deadline=None, derandomize=True, suppress_health_check=list(HealthCheck))
+    @given(st.integers(1, 400), st.integers(0, 30), st.lists(st.integers(1, 20), min_size=1, max_size=4),
+           st.integers(1, 300), st.integers(0, 2**64 - 1), st.booleans(), st.integers(0, 2**31))
+    def run(n_nodes, max_deg, fanouts, n_seeds, call_seed, wide_offsets, graph_seed):
+        rng = np.random.default_rng(graph_seed)
+        deg = rng.integers(0, max_deg + 1, n_nodes)
+        rp = np.zeros(n_nodes + 1, dtype=np.int64 if wide_offsets else np.int32)
+        rp[1:] = np.cumsum(deg)
+        col = rng.integers(0, n_nodes, int(rp[-1])).astype(np.int32)       # may be empty
+        seeds = rng.integers(0, n_nodes, n_seeds).astype(np.int32)
+        res = gpu_sample(B, torch_mod, rp, col, seeds.tolist(), fanouts, call_seed)
+        assert_sample_equal(res, oracle.sample_khop(rp, col, seeds, fanouts, call_seed))
+
+    run()
+
+
 def test_sample_high_degree_hub_and_host_pinned_graph(B, torch_mod):
     import oracle
     rng = np.random.default_rng(11)

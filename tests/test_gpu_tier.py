@@ -257,3 +257,25 @@ def test_tiered_pipeline_as_benchmarked_matches_oracle(torch_mod, B, tier_fracti
     assert_state_equal(cache, op.cache, "tiered pipeline")
     if oc2 is not None:
         assert_tier_state_equal(tier, oc2, "tiered pipeline")
+
+
+def test_tiered_random_cases_property(B, torch_mod):
+    """Seeded random store sizes, row widths (any multiple of 16 bytes), capacities of both
+    levels (the tier's may be 0), batch sequences and call modes (hypothesis draws them,
+    derandomized): the pair of caches follows the two chained oracle caches."""
+    from hypothesis import given, settings, strategies as st, HealthCheck
+
+    @settings(max_examples=25, deadline=None, derandomize=True, suppress_health_check=list(HealthCheck))
+    @given(st.integers(50, 5000), st.integers(1, 65), st.integers(1, 3000), st.sampled_from([0, 0, 1, 17, 300, 4000]),
+           st.lists(st.integers(0, 2500), min_size=1, max_size=8), st.booleans(), st.booleans(),
+           st.sampled_from([None, "own", "with_insert", "alternate"]), st.integers(1, 5), st.integers(0, 2**31))
+    def run(n_nodes, row_chunks, cap1, cap2, sizes, write_through, side, early, threads, seed):
+        rng = np.random.default_rng(seed)
+        feats = rng.integers(0, 2**32, (n_nodes, row_chunks * 4), dtype=np.uint32)
+        batches = [rng.permutation(n_nodes)[: min(k, n_nodes)].tolist() for k in sizes]
+        if early is not None and (cap2 != 0 or not write_through):
+            early = None                      # the library refuses early lookups there (tested elsewhere)
+        run_tiered_stream(B, torch_mod, feats, cap1, cap2, batches, write_through, threads, side=side,
+                          cache_has_store=(cap2 == 0), early=early)
+
+    run()
