@@ -22,6 +22,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+LINK_SAMPLE_EVERY = 10          # the miss fetch is timed in every 10th batch of the timed epoch
 HOST_LINK_NOMINAL_GBS = 64.0   # PCIe Gen5 x16, one direction, nominal
 
 
@@ -162,9 +163,11 @@ def main():
     cache = new_cache()
     pipe.set_cache(cache)
     if not args.no_stage_timers:
-        # In the timed region only the hit gather is timed unless asked otherwise: a timed launch
-        # costs the stream ~10 us, which the 6-9 fetch launches of a batch would feel.
-        cache.set_profiling(True if args.all_stage_timers else ("gather_hit",))
+        # The hit gather is timed in every batch, the miss fetch in every 10th only: a timed launch
+        # holds its stream up for ~10 us, which the 6-9 fetch launches of a batch would feel.
+        cache.set_profiling(True if args.all_stage_timers else ("gather_hit", "fetch_miss"))
+        if not args.all_stage_timers:
+            cache.set_profiling_every("fetch_miss", LINK_SAMPLE_EVERY)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     n_list, hit_list = pipe.run(seeds_dev, w.rng_seeds, args.steps)   # ends with a device synchronise
@@ -232,24 +235,23 @@ def main():
             "avg_launch_us": 1e3 * g_kernel_ms / max(g_n, 1), "launches": g_n,
             "timing": "begin/end of each kernel recorded on the device by its own dispatch (hipExtLaunchKernelGGL events)",
         }
-        result["stage_ms_per_step"] = {k: (v[0] / args.steps if k != "event_overhead" else v[0])
-                                       for k, v in prof.items() if v[1] > 0}
-        # Host link: the miss fetch kernels, timed the same way, on further batches right after the
-        # timed epoch (the pipeline simply goes on; not part of `value`).
-        link_steps = min(20, args.steps)
-        cache.set_profiling(("fetch_miss",))
-        n3, h3 = pipe.run(seeds_dev, w.rng_seeds, link_steps, first_step=args.steps)
-        f_ms, f_n = cache.profile()["fetch_miss"]
-        miss3 = int(np.sum(n3) - np.sum(h3))
+        result["stage_ms_per_step"] = {k: (v[0] / args.steps if k not in ("event_overhead", "fetch_miss") else v[0])
+                                       for k, v in prof.items() if v[1] > 0 and k != "fetch_miss"}
+        # Host link: the miss fetch kernels of the sampled batches of the timed epoch
+        every = 1 if args.all_stage_timers else LINK_SAMPLE_EVERY
+        sampled = [i for i in range(args.steps) if (i + 1) % every == 0]      # the cache counts its lookups from 1
+        f_ms, f_n = prof["fetch_miss"]
+        miss3 = int(sum(n_arr[i] - h_arr[i] for i in sampled))
         link = miss3 * rb / (f_ms * 1e-3) / 1e9 if f_ms > 0 else 0.0
         h2d = measure_h2d_peak(torch)
         result["host_link"] = {
             "kernel": "k_fetch_rows" if miss_path == "staged" else "k_fetch_miss", "achieved": link, "unit": "GB/s",
             "nominal_peak": HOST_LINK_NOMINAL_GBS, "measured_h2d_copy_peak": h2d,
             "frac_of_nominal": link / HOST_LINK_NOMINAL_GBS, "frac_of_measured": link / h2d,
-            "avg_launch_us": 1e3 * f_ms / max(f_n, 1), "launches_per_step": f_n / link_steps,
-            "link_ms_per_step": f_ms / link_steps,
-            "note": "%d batches after the timed epoch, fetch kernels timed by their dispatches" % link_steps,
+            "avg_launch_us": 1e3 * f_ms / max(f_n, 1), "launches_per_step": f_n / max(len(sampled), 1),
+            "link_ms_per_step": f_ms / max(len(sampled), 1),
+            "note": "fetch kernels of every %d-th batch of the timed epoch (%d batches), timed by their dispatches"
+                    % (every, len(sampled)),
         }
 
         # The same kernel on a launch that is mostly hits (outside the timed region, not

@@ -285,6 +285,13 @@ int bgl_cache_stats(bgl_cache_t *c, uint64_t *lookups, uint64_t *hits, uint64_t 
 #define BGL_ALL_STAGES ((1 << BGL_NUM_STAGES) - 1)
 int bgl_cache_set_profiling(bgl_cache_t *c, int stage_mask);
 int bgl_cache_profile(bgl_cache_t *c, int stage, double *total_ms, int64_t *launches);
+/*
+ * Time `stage` only in every `every`-th call (lookups and FIFO updates are counted
+ * separately, from the cache's creation, starting at 1): a timed launch holds its
+ * stream up for a few microseconds, which a stage of many launches per call would
+ * feel.  Default 1.  Errors: BGL_EINVAL.
+ */
+int bgl_cache_set_profiling_every(bgl_cache_t *c, int stage, int every);
 
 /* ------------------------------------------------------------- host tier */
 

@@ -30,7 +30,7 @@ EXPORTS = [
     "bgl_last_error", "bgl_graph_load_csr", "bgl_graph_destroy", "bgl_sample_workspace_bytes",
     "bgl_sample_khop", "bgl_cache_create", "bgl_cache_destroy", "bgl_cache_lookup_gather",
     "bgl_cache_insert_fifo", "bgl_cache_set_write_through", "bgl_cache_wait_rows", "bgl_cache_wait_lists", "bgl_cache_export_state", "bgl_cache_stats",
-    "bgl_cache_set_profiling", "bgl_cache_profile",
+    "bgl_cache_set_profiling", "bgl_cache_profile", "bgl_cache_set_profiling_every",
     "bgl_host_tier_create", "bgl_host_tier_destroy", "bgl_cache_lookup_gather_tiered",
     "bgl_host_tier_export_state", "bgl_host_tier_stats",
     "bgl_order_bfs_sequence", "bgl_order_proximity", "bgl_order_choose_sequences",
@@ -85,6 +85,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
                                   C.POINTER(u64), C.POINTER(i32)]
     L.bgl_cache_set_profiling.argtypes = [vp, ci]
     L.bgl_cache_profile.argtypes = [vp, ci, C.POINTER(C.c_double), C.POINTER(i64)]
+    L.bgl_cache_set_profiling_every.argtypes = [vp, ci, ci]
     L.bgl_order_bfs_sequence.argtypes = [vp, vp, i64, i64, vp, vp]
     L.bgl_order_proximity.argtypes = [vp, vp, i64, i32, vp, vp, i64, vp, vp]
     L.bgl_order_choose_sequences.argtypes = [vp, vp, i64, i32, vp, vp, i32, vp, i32, C.c_double,
@@ -340,6 +341,10 @@ class Cache:
         else:
             mask = sum(1 << STAGE_NAMES.index(s) for s in stages)
         _check(lib().bgl_cache_set_profiling(self._h, mask))
+
+    def set_profiling_every(self, stage: str, every: int) -> None:
+        """Time `stage` only in every `every`-th call (counted from the cache's creation, from 1)."""
+        _check(lib().bgl_cache_set_profiling_every(self._h, STAGE_NAMES.index(stage), int(every)))
 
     def profile(self):
         out = {}

@@ -92,6 +92,7 @@ struct bgl_cache {
     std::vector<Rec> prof_rec;
     double prof_overhead_ms;  // event pair around an (almost) empty kernel
     int64_t prof_dropped;     // timed launches that got no events (event creation failed)
+    int prof_every[BGL_NUM_STAGES];  // stage s is timed only in calls whose ordinal is a multiple of this
     double prof_ms[BGL_NUM_STAGES];
     int64_t prof_n[BGL_NUM_STAGES];
 };
@@ -544,6 +545,8 @@ struct Prof {
     Prof(bgl_cache *c_, int stage, hipStream_t st_, bool exact_ = true) : c(c_), st(st_), exact(exact_)
     {
         if (!(c->profiling & (1u << stage))) return;
+        const uint64_t call = stage >= BGL_STAGE_INSERT_MAP ? c->insert_calls + 1 : c->lookup_calls;
+        if (c->prof_every[stage] > 1 && call % (uint64_t)c->prof_every[stage] != 0) return;
         if (2 * (c->prof_rec.size() + 1) > c->prof_ev.size()) {  // more timed launches than events: add some
             const size_t old = c->prof_ev.size();
             c->prof_ev.resize(old + 2 * PROF_RING, nullptr);
@@ -654,6 +657,7 @@ extern "C" int bgl_cache_create(int64_t capacity_rows, int32_t row_bytes,
     c->features_in_hbm = attr.type == hipMemoryTypeDevice;
     c->profiling = 0;
     c->prof_dropped = 0;
+    for (int st = 0; st < BGL_NUM_STAGES; ++st) c->prof_every[st] = 1;
     c->timed_start = c->timed_stop = nullptr;
     c->fetch_pending = false;
     c->fetch_reads_caller_lists = true;
@@ -1167,6 +1171,15 @@ extern "C" int bgl_cache_set_profiling(bgl_cache_t *c, int enable)
         }
         c->prof_overhead_ms = sum / reps;
     }
+    return BGL_OK;
+}
+
+extern "C" int bgl_cache_set_profiling_every(bgl_cache_t *c, int stage, int every)
+{
+    if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
+    if (stage < 0 || stage >= BGL_NUM_STAGES) BGL_FAIL(BGL_EINVAL, "unknown stage %d", stage);
+    if (every < 1) BGL_FAIL(BGL_EINVAL, "every must be >= 1 (got %d)", every);
+    c->prof_every[stage] = every;
     return BGL_OK;
 }
 
