@@ -58,7 +58,9 @@ class MinibatchPipeline:
         (xor the pass number, so that a second pass over the seeds samples differently).
         on_batch(i, sampled_batch, n, pipeline) is called after lookup_gather(i) and
         insert_fifo(i) have been enqueued; work it enqueues on the chain stream after
-        cache.wait_rows(chain) sees batch i's complete outputs.
+        cache.wait_rows(chain) sees batch i's complete outputs (out_slot and miss_pos are
+        rewritten by the next batch's lookup, which with a staging ring runs on the work
+        stream: whoever needs them beyond on_batch enqueues its reads there).
         first_step offsets the batch numbering (a later pass over the seeds).
         Returns (n_input per batch, n_hit per batch)."""
         nb = seeds_dev.shape[0]
