@@ -18,13 +18,11 @@
 // row's position is reused only after capacity_rows + max_batch_rows further
 // insertions, so a row found by a batch's lookup is still intact after that
 // same batch's insertions have evicted it, and no copy ever has to wait for a
-// fetch.
-#include <atomic>
+// fetch.  A tier that keeps nothing (capacity 0: rows only pass through, packed,
+// on their way over the link) has a ring of two batches, so that the next batch
+// can be packed while the previous one is still being fetched.
 #include <chrono>
-#include <condition_variable>
 #include <cstring>
-#include <functional>
-#include <mutex>
 #include <new>
 #include <thread>
 #include <vector>
@@ -151,7 +149,7 @@ struct bgl_host_tier {
     int32_t row_bytes = 0;
     int64_t capacity = 0;   // logical slots
     int64_t max_batch = 0;
-    int64_t ring = 0;       // row positions = capacity + max_batch
+    int64_t ring = 0;       // row positions: capacity + max_batch, or 2 * max_batch with capacity 0
     int device = 0;
     char *rows = nullptr;   // page-locked, ring rows
     char *rows_dev = nullptr;
