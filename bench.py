@@ -211,6 +211,7 @@ def main():
             "hit_ratio_steady_state": steady_ratio,
             "miss_path": miss_path,
             "miss_path_trial_ms_per_batch": trial or None,
+            "host_copy_threads": (stage_ring.stats()["threads"] if miss_path == "staged" else 0),
             "gathered_feature_GBps": rb * tot_n / elapsed / 1e9,
         },
     }
