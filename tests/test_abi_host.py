@@ -145,3 +145,14 @@ def test_proximity_order_uses_each_training_node_once():
     assert seeds.shape == (10, 64)
     flat = seeds.reshape(-1)
     assert len(np.unique(flat)) == len(flat)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on exactly one GPU: bench.py --gpus N > 1 must say so and exit."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert p.returncode != 0
+    assert "one GPU" in p.stderr and p.stdout.strip() == ""
