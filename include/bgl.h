@@ -190,6 +190,26 @@ int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64_t n, void 
                             void *main_stream, void *side_stream);
 
 /*
+ * bgl_cache_lookup_gather with the map lookup and the lists on lookup_stream
+ * instead of main_stream (write-through mode only).  When main_stream is the
+ * stream that also carries the miss fetches, a plain lookup starts only when the
+ * previous call's fetch has left the link; this one does not wait for it: only
+ * the hit gather and the fetch stay in main_stream / side_stream order (the
+ * gather may need rows the previous fetch is still writing).  The fetch reads
+ * the library's own copy of the miss list, so the previous call's fetch is not
+ * disturbed by this call's lists.  Conditions: ids ready in lookup_stream order
+ * and untouched until this call's fetch is done; the previous call's
+ * bgl_cache_insert_fifo already enqueued (this call waits for it on the
+ * device); out_slot and miss_pos are rewritten as soon as lookup_stream gets
+ * there, so readers of the previous call's lists must be done in lookup_stream
+ * order.  With lookup_stream == main_stream it is bgl_cache_lookup_gather.
+ * Errors: as bgl_cache_lookup_gather, plus BGL_EINVAL (write-through mode is off).
+ */
+int bgl_cache_lookup_gather_early(bgl_cache_t *c, const int32_t *ids, int64_t n, void *out_rows,
+                                  int32_t *out_slot, int32_t *miss_pos, int64_t *n_hit_host,
+                                  void *main_stream, void *side_stream, void *lookup_stream);
+
+/*
  * Cache update of Sec. 3.2.3 (last step) with the FIFO rule of Sec. 4: the
  * buffer is a circular queue with a running `tail`; miss number r of this call
  * (in miss_pos order) takes slot (tail + r) mod capacity, the node that held

@@ -41,6 +41,7 @@ struct CacheDev {          // device-resident scalars
     unsigned long long tail[2];
     unsigned long long lookups, hits;
     long long n_miss_last;  // miss count of the most recent lookup
+    long long n_miss_gen[2];  // the same, kept per call parity for early lookups (the previous call's fetch still reads its own)
     long long n_hit_last;   // hit count of the most recent lookup
     int status;
 };
@@ -75,7 +76,7 @@ struct bgl_cache {
     // the stream the fetch ran on); ev_map: the last FIFO update is complete (recorded on the
     // update's stream when that is not the lookup's main stream).
     hipEvent_t ev_listed, ev_miss, ev_map;
-    hipEvent_t ev_ids;      // tiered lookup: the missed ids have reached the host
+    hipEvent_t ev_ids;      // the lists of a lookup are complete (tiered: the missed ids have reached the host)
     hipStream_t last_main, fetch_stream, map_stream;
     bool fetch_pending;     // ev_miss marks a miss fetch that later work may have to wait for
     bool fetch_reads_caller_lists;  // that fetch reads the caller's miss_pos (not the library's copy)
@@ -169,10 +170,11 @@ __global__ __launch_bounds__(KEYS_PER_TILE) void k_probe(const int32_t *__restri
 }
 
 // Counters of an empty lookup (n = 0); with n > 0 k_split_list publishes them.
-__global__ void k_empty_lookup(CacheDev *dev, int64_t *n_hit_host)
+__global__ void k_empty_lookup(CacheDev *dev, int64_t *n_hit_host, int gen)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
         dev->n_miss_last = 0;
+        dev->n_miss_gen[gen] = 0;
         dev->n_hit_last = 0;
         if (n_hit_host) *n_hit_host = 0;
     }
@@ -191,7 +193,7 @@ __global__ __launch_bounds__(KEYS_PER_TILE) void k_split_list(const int32_t *__r
                                                               int64_t *n_hit_host,
                                                               const int32_t *__restrict__ ids,
                                                               int64_t num_nodes, int32_t *miss_ids_host,
-                                                              int32_t *miss_pos_copy)
+                                                              int32_t *miss_pos_copy, int gen)
 {
     __shared__ int sh_scan[KEYS_PER_TILE / kWave];
     __shared__ int sh_base;
@@ -220,6 +222,7 @@ __global__ __launch_bounds__(KEYS_PER_TILE) void k_split_list(const int32_t *__r
     if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
         const long long n_miss = sh_base + tot;
         dev->n_miss_last = n_miss;
+        dev->n_miss_gen[gen] = n_miss;
         dev->n_hit_last = n - n_miss;
         dev->lookups += (unsigned long long)n;
         dev->hits += (unsigned long long)(n - n_miss);
@@ -300,10 +303,10 @@ template <int Q, bool WT>
 __global__ __launch_bounds__(COPY_THREADS) void k_fetch_miss(
     const int32_t *__restrict__ miss_pos, const int32_t *__restrict__ ids, int q,
     int64_t num_nodes, const uint4 *__restrict__ features, uint4 *__restrict__ out,
-    const CacheDev *dev, uint4 *__restrict__ buffer, int64_t capacity, int par)
+    const CacheDev *dev, uint4 *__restrict__ buffer, int64_t capacity, int par, int gen)
 {
     const int qq = Q > 0 ? Q : q;
-    const int64_t n_miss = dev->n_miss_last;
+    const int64_t n_miss = dev->n_miss_gen[gen];
     const int64_t total = n_miss * qq;
     const int64_t start = n_miss > capacity ? n_miss - capacity : 0;
     const unsigned long long tail = WT ? dev->tail[par] : 0ull;
@@ -750,9 +753,11 @@ namespace {
 // fetch while this one's lists are written.
 int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, int32_t *out_slot,
                  int32_t *miss_pos, int64_t *n_hit_dev, hipStream_t ms, hipStream_t ls, bgl_host_tier *tier,
-                 const int32_t **mpos_used)
+                 const int32_t **mpos_used, int *gen_used)
 {
     const bool early = ls != ms;
+    const int gen = (int)(c->lookup_calls & 1);  // which copy of the per-call device state this call owns
+    *gen_used = gen;
     const int64_t tiles = bgl::ceil_div(n, KEYS_PER_TILE);
     if (tiles + 1 > c->mbs_cap) {
         BGL_HIP(hipDeviceSynchronize());
@@ -774,7 +779,7 @@ int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, in
     }
     int32_t *mpos_copy = nullptr;
     if (early) {
-        const int g = (int)(c->lookup_calls & 1);
+        const int g = gen;
         if (n > c->mpos_cap[g]) {
             BGL_HIP(hipDeviceSynchronize());
             (void)hipFree(c->mpos_copy[g]);
@@ -811,16 +816,16 @@ int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, in
             hipLaunchKernelGGL(k_split_list, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), 0, ls, out_slot,
                                n, c->mbs, miss_pos, c->hit_pos, c->hit_pos + c->hit_cap, c->dev,
                                n_hit_dev, ids, c->num_nodes,
-                               tier ? bgl::tier_ids_device_if_passthrough(tier) : nullptr, mpos_copy);
+                               tier ? bgl::tier_ids_device_if_passthrough(tier) : nullptr, mpos_copy, gen);
         }
     } else {
-        hipLaunchKernelGGL(k_empty_lookup, dim3(1), dim3(64), 0, ls, c->dev, n_hit_dev);
+        hipLaunchKernelGGL(k_empty_lookup, dim3(1), dim3(64), 0, ls, c->dev, n_hit_dev, gen);
     }
     if (tier) {
         const int rc = bgl::tier_enqueue_lookup(tier, ids, miss_pos, &c->dev->n_miss_last, n, ls);
         if (rc != BGL_OK) return rc;
-        BGL_HIP(hipEventRecord(c->ev_ids, ls));
     }
+    if (tier || early) BGL_HIP(hipEventRecord(c->ev_ids, ls));  // the lists are complete
     if (early) {
         // the hit gather reads rows the previous fetch may still be writing, and needs the lists
         if (c->fetch_pending && c->fetch_stream != ms) BGL_HIP(hipStreamWaitEvent(ms, c->ev_miss, 0));
@@ -861,12 +866,16 @@ int check_lookup_args(bgl_cache *c, const int32_t *ids, int64_t n, void *out_row
 
 }  // namespace
 
-extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64_t n,
-                                       void *out_rows, int32_t *out_slot, int32_t *miss_pos,
-                                       int64_t *n_hit_host, void *main_stream, void *side_stream)
+namespace {
+
+int lookup_gather_impl(bgl_cache_t *c, const int32_t *ids, int64_t n, void *out_rows, int32_t *out_slot,
+                       int32_t *miss_pos, int64_t *n_hit_host, void *main_stream, void *side_stream,
+                       void *lookup_stream, bool early)
 {
     int rc = check_lookup_args(c, ids, n, out_rows, out_slot, miss_pos);
     if (rc != BGL_OK) return rc;
+    if (early && !c->write_through)
+        BGL_FAIL(BGL_EINVAL, "an early lookup needs write-through mode");
     if (!c->features) BGL_FAIL(BGL_EINVAL, "the cache has no backing store: use bgl_cache_lookup_gather_tiered");
     hipStream_t ms = static_cast<hipStream_t>(main_stream);
     hipStream_t ss = side_stream ? static_cast<hipStream_t>(side_stream) : c->own_side;
@@ -882,8 +891,10 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
         n_hit_dev = static_cast<int64_t *>(attr.devicePointer);
     }
     const int q = c->row_bytes / 16;
+    hipStream_t ls = early ? static_cast<hipStream_t>(lookup_stream) : ms;
     const int32_t *mpos = nullptr;
-    rc = lookup_phase(c, ids, n, out_rows, out_slot, miss_pos, n_hit_dev, ms, ms, nullptr, &mpos);
+    int gen = 0;
+    rc = lookup_phase(c, ids, n, out_rows, out_slot, miss_pos, n_hit_dev, ms, ls, nullptr, &mpos, &gen);
     if (rc != BGL_OK) return rc;
     if (n > 0) {
         if (ss != ms) BGL_HIP(hipStreamWaitEvent(ss, c->ev_listed, 0));
@@ -895,15 +906,15 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
             dispatch_q(q, [&](auto Q) {
                 auto k = c->write_through ? k_fetch_miss<decltype(Q)::value, true>
                                           : k_fetch_miss<decltype(Q)::value, false>;
-                launch(c, ss, k, dim3(blocks), dim3(COPY_THREADS), miss_pos, ids, q, c->num_nodes,
+                launch(c, ss, k, dim3(blocks), dim3(COPY_THREADS), mpos, ids, q, c->num_nodes,
                        reinterpret_cast<const uint4 *>(c->features), reinterpret_cast<uint4 *>(out_rows), c->dev,
-                       reinterpret_cast<uint4 *>(c->buffer), c->capacity, par);
+                       reinterpret_cast<uint4 *>(c->buffer), c->capacity, par, gen);
             });
         }
         BGL_HIP(hipEventRecord(c->ev_miss, ss));
         c->fetch_pending = true;
         c->fetch_stream = ss;
-        c->fetch_reads_caller_lists = true;
+        c->fetch_reads_caller_lists = mpos == miss_pos;
     }
     BGL_HIP(hipGetLastError());
     if (c->write_through) {
@@ -912,6 +923,25 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
         c->wt_miss_pos = miss_pos;
     }
     return BGL_OK;
+}
+
+}  // namespace
+
+extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64_t n,
+                                       void *out_rows, int32_t *out_slot, int32_t *miss_pos,
+                                       int64_t *n_hit_host, void *main_stream, void *side_stream)
+{
+    return lookup_gather_impl(c, ids, n, out_rows, out_slot, miss_pos, n_hit_host, main_stream, side_stream,
+                              nullptr, false);
+}
+
+extern "C" int bgl_cache_lookup_gather_early(bgl_cache_t *c, const int32_t *ids, int64_t n,
+                                             void *out_rows, int32_t *out_slot, int32_t *miss_pos,
+                                             int64_t *n_hit_host, void *main_stream, void *side_stream,
+                                             void *lookup_stream)
+{
+    return lookup_gather_impl(c, ids, n, out_rows, out_slot, miss_pos, n_hit_host, main_stream, side_stream,
+                              lookup_stream, static_cast<hipStream_t>(lookup_stream) != static_cast<hipStream_t>(main_stream));
 }
 
 extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t, const int32_t *ids,
@@ -939,7 +969,8 @@ extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t
         ls = static_cast<hipStream_t>(lookup_stream);
     }
     const int32_t *mpos = nullptr;
-    rc = lookup_phase(c, ids, n, out_rows, out_slot, miss_pos, bgl::tier_count_device(t), ms, ls, t, &mpos);
+    int gen = 0;
+    rc = lookup_phase(c, ids, n, out_rows, out_slot, miss_pos, bgl::tier_count_device(t), ms, ls, t, &mpos, &gen);
     if (rc != BGL_OK) return rc;
     BGL_HIP(hipGetLastError());
     struct Guard {  // whatever goes wrong below, the copy threads are released and the batch is dropped

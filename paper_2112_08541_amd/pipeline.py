@@ -9,9 +9,10 @@ over the host link, so the loop is built to keep the link busy:
                  (a hand-over between streams costs ~20 us here)
   work stream    sample(i+2), map update(i): they run while fetch(i) holds the link;
                  both wait for hit gather(i), so nothing competes with the gather.
-                 With a staging ring (a host tier of capacity 0) also lookup(i+1) and
-                 lists(i+1), right behind map update(i): the host then packs batch i+1's
-                 miss rows while fetch(i) is still on the link
+                 In write-through mode also lookup(i+1) and lists(i+1), right behind
+                 map update(i) (then only the hit gather sits between two fetches); with
+                 a staging ring (a host tier of capacity 0) the host then packs batch
+                 i+1's miss rows while fetch(i) is still on the link
 
 The cache is put in write-through mode (every lookup here is followed by the
 insert of all its misses), which makes the FIFO update a map update that needs no
@@ -44,6 +45,8 @@ class MinibatchPipeline:
         self.chain = torch.cuda.Stream()          # lookups, hit gathers, miss fetches
         self.work = torch.cuda.current_stream()   # sampling, map updates
         self.write_through = write_through
+        # an early lookup adds two hand-overs between streams: it pays for batches of many thousand ids
+        self.early_ok = self.cap >= 65536
         self.tier = tier                          # second cache level in host memory (Sec. 3.2.3), or None
         self.last_ids, self.last_n = None, 0      # input nodes of the most recent batch
         self.set_cache(cache)
@@ -94,14 +97,16 @@ class MinibatchPipeline:
             ids = sb.input_nodes(self.cap)
             chain.wait_event(sampled_ev[i % 3])
             if self.tier is None:
+                # in write-through mode the map lookup and the lists run early, on the work stream
                 cache.lookup_gather(ids, n, self.out_rows, self.out_slot, self.miss_pos,
                                     main_stream=chain, side_stream=chain,
-                                    n_hit_ptr=n_hits.data_ptr() + 8 * i)
+                                    n_hit_ptr=n_hits.data_ptr() + 8 * i,
+                                    lookup_stream=work if (self.write_through and self.early_ok) else None)
             else:
                 # Blocks until the host tier has served the GPU cache's misses.  With a tier that keeps
                 # nothing the map lookup runs early, on the work stream (behind the previous batch's map
                 # update), so the host packs this batch's rows while the previous fetch is on the link.
-                early = self.tier.capacity == 0 and self.write_through
+                early = self.tier.capacity == 0 and self.write_through and self.early_ok
                 n_hits[i], h2 = cache.lookup_gather_tiered(self.tier, ids, n, self.out_rows, self.out_slot,
                                                            self.miss_pos, main_stream=chain, side_stream=chain,
                                                            lookup_stream=work if early else None)

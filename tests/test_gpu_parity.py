@@ -169,8 +169,11 @@ def test_sample_reports_out_of_range_seed(B, torch_mod):
 
 
 # --------------------------------------------------------------------- cache
-def run_cache_stream(B, torch, feats, cap, batches, device_n_miss=False, side=True, write_through=False):
-    """Feed id batches through GPU cache and oracle cache; compare after every call."""
+def run_cache_stream(B, torch, feats, cap, batches, device_n_miss=False, side=True, write_through=False,
+                     early=None):
+    """Feed id batches through GPU cache and oracle cache; compare after every call.
+    early: "own" / "with_insert" / "alternate" = map lookup and lists on a stream of their own,
+    on the one that also carries the FIFO updates, or only in every other call."""
     import oracle
     N, rb = feats.shape[0], feats.shape[1] * feats.itemsize
     feat_t = torch.from_numpy(feats.view(np.uint8).reshape(N, rb)).pin_memory()
@@ -180,16 +183,20 @@ def run_cache_stream(B, torch, feats, cap, batches, device_n_miss=False, side=Tr
         gc.set_write_through(True)
         device_n_miss = True
     side_stream = torch.cuda.Stream() if side else None
+    lookup_stream = torch.cuda.Stream() if early else None
     for bi, ids in enumerate(batches):
         n = len(ids)
         ids_t = torch.tensor(ids, dtype=torch.int32, device="cuda") if n else torch.empty(1, dtype=torch.int32, device="cuda")
         out = torch.full((max(n, 1), rb), 0xCD, dtype=torch.uint8, device="cuda")
         out_slot = torch.full((max(n, 1),), -7, dtype=torch.int32, device="cuda")
         miss_pos = torch.full((max(n, 1),), -7, dtype=torch.int32, device="cuda")
-        gc.lookup_gather(ids_t, n, out, out_slot, miss_pos, side_stream=side_stream)
+        if lookup_stream is not None:
+            lookup_stream.wait_stream(torch.cuda.current_stream())      # ids_t and the filled outputs
+        use_ls = lookup_stream if (early != "alternate" or bi % 2 == 1) else None
+        gc.lookup_gather(ids_t, n, out, out_slot, miss_pos, side_stream=side_stream, lookup_stream=use_ls)
         o_out, o_slot, o_miss, o_hit = oc.lookup_gather(ids)
         if device_n_miss:
-            gc.insert_fifo(ids_t, miss_pos, -1, out)
+            gc.insert_fifo(ids_t, miss_pos, -1, out, stream=lookup_stream if early == "with_insert" else None)
             torch.cuda.synchronize()
             n_hit = int(gc.n_hit_host[0])
         else:
@@ -259,6 +266,38 @@ def test_cache_write_through_mode(B, torch_mod, dim, dtype, side):
     batches.insert(8, batches[7])
     run_cache_stream(B, torch_mod, feats, 3000, batches, side=side, write_through=True)
     run_cache_stream(B, torch_mod, feats, 1, batches[:6], side=side, write_through=True)
+
+
+@pytest.mark.parametrize("early", ["own", "with_insert", "alternate"])
+@pytest.mark.parametrize("side", [True, False])
+def test_cache_early_lookup(B, torch_mod, early, side):
+    """bgl_cache_lookup_gather_early: the map lookup and the lists on another stream than the hit
+    gather and the miss fetch.  Same results as the plain call, also when the two kinds of call
+    alternate, with batches of more misses than slots and an empty batch."""
+    rng = np.random.default_rng(91)
+    N = 20000
+    feats = rng.standard_normal((N, 100)).astype(np.float32)
+    batches = []
+    for b in range(12):
+        size = int(rng.integers(1, 2500)) if b != 5 else 7000
+        batches.append(list(dict.fromkeys((rng.zipf(1.2, size) % N).tolist())))
+    batches.insert(3, [])
+    batches.insert(8, batches[7])
+    run_cache_stream(B, torch_mod, feats, 3000, batches, side=side, write_through=True, early=early)
+    run_cache_stream(B, torch_mod, feats, 64, batches[:7], side=side, write_through=True, early=early)
+
+
+def test_cache_early_lookup_needs_write_through(B, torch_mod):
+    torch = torch_mod
+    feats = torch.zeros((100, 64), dtype=torch.uint8).pin_memory()
+    gc = B.Cache(10, feats, num_nodes=100, row_bytes=64)
+    ids = torch.arange(8, dtype=torch.int32, device="cuda")
+    out = torch.zeros((8, 64), dtype=torch.uint8, device="cuda")
+    slot = torch.zeros(8, dtype=torch.int32, device="cuda")
+    mp = torch.zeros(8, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.BglError) as e:
+        gc.lookup_gather(ids, 8, out, slot, mp, lookup_stream=torch.cuda.Stream())
+    assert e.value.code == B.BGL_EINVAL
 
 
 def test_cache_write_through_rejects_a_broken_call_sequence(B, torch_mod):
