@@ -61,6 +61,12 @@ def run_tiered_stream(B, torch, feats, cap1, cap2, batches, write_through, threa
         miss_pos = torch.full((max(n, 1),), -7, dtype=torch.int32, device="cuda")
         if lookup_stream is not None:
             lookup_stream.wait_stream(torch.cuda.current_stream())      # ids_t and the filled outputs
+        # hold one of the streams up for a while (a spin kernel that ends by itself), a different one
+        # each batch: a missing wait between the streams then shows as a wrong result
+        streams = [st for st in (lookup_stream, torch.cuda.current_stream(), side_stream) if st is not None]
+        if len(streams) > 1:
+            with torch.cuda.stream(streams[bi % len(streams)]):
+                torch.cuda._sleep(2_000_000)
         use_ls = lookup_stream if (early != "alternate" or bi % 2 == 1) else None
         h1, h2 = gc.lookup_gather_tiered(tier, ids_t, n, out, out_slot, miss_pos, side_stream=side_stream,
                                          lookup_stream=use_ls)
