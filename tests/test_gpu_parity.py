@@ -463,7 +463,17 @@ def test_overlapped_pipeline_full_epoch_counts_and_final_state(torch_mod, B, mis
         pipe.tier = B.HostTier(w.features.view(np.uint8).reshape(cfg.num_nodes, cfg.row_bytes), 0, pipe.cap, 0)
     seeds_dev = torch_mod.from_numpy(w.seed_batches).cuda()
     steps = cfg.num_batches
-    n_list, hit_list = pipe.run(seeds_dev, w.rng_seeds, steps)
+
+    def jitter(i, sb, n, p):
+        # shift the streams against each other now and then (spin kernels that end by themselves)
+        if i % 7 == 3:
+            with torch_mod.cuda.stream(p.chain):
+                torch_mod.cuda._sleep(3_000_000)
+        if i % 5 == 1:
+            with torch_mod.cuda.stream(p.work):
+                torch_mod.cuda._sleep(3_000_000)
+
+    n_list, hit_list = pipe.run(seeds_dev, w.rng_seeds, steps, on_batch=jitter)
     last_rows = pipe.out_rows[: n_list[-1]].cpu().numpy()
     last_ids = pipe.last_ids[: n_list[-1]].cpu().numpy()
     op = OraclePipeline(w)
