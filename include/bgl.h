@@ -332,7 +332,7 @@ int bgl_cache_set_profiling_every(bgl_cache_t *c, int stage, int every);
  *                   row_bytes is not a multiple of 128: rows read in place move
  *                   whole 128-byte lines over the link, packed rows do not
  *   max_batch_rows  the largest n a tiered lookup will be called with; the
- *                   page-locked ring holds capacity_rows + max_batch_rows rows
+ *                   page-locked ring holds capacity_rows + 2 * max_batch_rows rows
  *   num_threads     host threads that copy rows (the calling thread drives the
  *                   GPU meanwhile); 0 = min(cores, 16) - 1
  * Errors: BGL_EINVAL (null store, sizes out of range, row_bytes not a multiple
@@ -362,8 +362,8 @@ int bgl_host_tier_destroy(bgl_host_tier_t *t);
  * cache still needs its bgl_cache_insert_fifo.  ids, out_slot and miss_pos must
  * stay untouched until main_stream has passed this call.  ids must be distinct.
  * One tier serves one cache's calls in order; it is not thread-safe.
- *   early_lookup    0: lookup_stream is ignored.  1 (needs a tier of capacity 0
- *           and write-through mode): the map lookup and the lists run on
+ *   early_lookup    0: lookup_stream is ignored.  1 (needs write-through mode):
+ *           the map lookups of both levels and the lists run on
  *           lookup_stream instead of main_stream, i.e. without waiting for the
  *           previous call's miss fetch when that is what main_stream is busy
  *           with, so the host has the missing ids and packs rows while that

@@ -822,7 +822,7 @@ int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, in
         hipLaunchKernelGGL(k_empty_lookup, dim3(1), dim3(64), 0, ls, c->dev, n_hit_dev, gen);
     }
     if (tier) {
-        const int rc = bgl::tier_enqueue_lookup(tier, ids, miss_pos, &c->dev->n_miss_last, n, ls);
+        const int rc = bgl::tier_enqueue_lookup(tier, ids, miss_pos, &c->dev->n_miss_last, n, gen, ls);
         if (rc != BGL_OK) return rc;
     }
     if (tier || early) BGL_HIP(hipEventRecord(c->ev_ids, ls));  // the lists are complete
@@ -959,13 +959,11 @@ extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t
     hipStream_t ms = static_cast<hipStream_t>(main_stream);
     hipStream_t ss = side_stream ? static_cast<hipStream_t>(side_stream) : c->own_side;
     const int q = c->row_bytes / 16;
-    // Early lookup: only with a tier that keeps nothing (a real tier's lists are still read by the
-    // previous fetch) and in write-through mode (otherwise the previous call's row copy still
-    // reads the caller's miss_pos).
+    // Early lookup: only in write-through mode (otherwise the previous call's row copy still reads
+    // the caller's miss_pos).
     hipStream_t ls = ms;
     if (early_lookup && static_cast<hipStream_t>(lookup_stream) != ms) {
-        if (bgl::tier_capacity(t) != 0 || !c->write_through)
-            BGL_FAIL(BGL_EINVAL, "early_lookup needs a tier of capacity 0 and write-through mode");
+        if (!c->write_through) BGL_FAIL(BGL_EINVAL, "early_lookup needs write-through mode");
         ls = static_cast<hipStream_t>(lookup_stream);
     }
     const int32_t *mpos = nullptr;
@@ -1026,8 +1024,9 @@ extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t
         bgl::tier_copy_wait(t);
     }
     BGL_HIP(hipEventRecord(c->ev_miss, ss));
-    // the tier's map changes after this call's lists are final and before the next lookup
-    rc = bgl::tier_enqueue_update(t, ids, miss_pos, ms);
+    // the tier's map changes after this call's lists are final and before the next lookup,
+    // which runs on the lookup stream
+    rc = bgl::tier_enqueue_update(t, ids, miss_pos, ls);
     if (rc != BGL_OK) return rc;
     guard.armed = false;
     BGL_HIP(hipGetLastError());

@@ -41,8 +41,9 @@ int64_t tier_num_nodes(const bgl_host_tier *t);
 
 // Enqueue on st: look ids[miss_pos[r]], r < *n_ranks_dev <= n_upper, up in the
 // tier's map, build the lists, send the missing ids and the counts to the host.
+// gen (0/1, alternating between calls) selects the copy of the lists this batch owns.
 int tier_enqueue_lookup(bgl_host_tier *t, const int32_t *ids, const int32_t *miss_pos,
-                        const long long *n_ranks_dev, int64_t n_upper, hipStream_t st);
+                        const long long *n_ranks_dev, int64_t n_upper, int gen, hipStream_t st);
 // Once st has passed that point: read the counts (n = size of the GPU cache's
 // lookup), check the ids.  Nothing has changed yet if this fails.
 int tier_begin(bgl_host_tier *t, int64_t n, TierPlan *plan);

@@ -12,15 +12,15 @@
 // from the store into the positions first-in first-out assigns, in chunks, and
 // each chunk's fetch kernel is launched as soon as its rows are in place.
 //
-// Rows sit in a ring of capacity_rows + max_batch_rows positions, filled in
+// Rows sit in a ring of capacity_rows + 2 * max_batch_rows positions, filled in
 // insertion order.  The newest capacity_rows insertions are the tier's content
 // (logical slot = insertion number mod capacity_rows, as in the GPU cache); a
-// row's position is reused only after capacity_rows + max_batch_rows further
+// row's position is reused only after capacity_rows + 2 * max_batch_rows further
 // insertions, so a row found by a batch's lookup is still intact after that
-// same batch's insertions have evicted it, and no copy ever has to wait for a
-// fetch.  A tier that keeps nothing (capacity 0: rows only pass through, packed,
-// on their way over the link) has a ring of two batches, so that the next batch
-// can be packed while the previous one is still being fetched.
+// batch's and the next batch's insertions (which an early lookup brings in while
+// this batch is still being fetched) have evicted it, and no copy ever has to
+// wait for a fetch.  A tier that keeps nothing (capacity 0) is just the ring:
+// rows pass through, packed, on their way over the link.
 #include <chrono>
 #include <cstring>
 #include <new>
@@ -149,7 +149,7 @@ struct bgl_host_tier {
     int32_t row_bytes = 0;
     int64_t capacity = 0;   // logical slots
     int64_t max_batch = 0;
-    int64_t ring = 0;       // row positions: capacity + max_batch, or 2 * max_batch with capacity 0
+    int64_t ring = 0;       // row positions: capacity + 2 * max_batch
     int device = 0;
     char *rows = nullptr;   // page-locked, ring rows
     char *rows_dev = nullptr;
@@ -157,7 +157,11 @@ struct bgl_host_tier {
     char *pinned_dev = nullptr;
     // device: bookkeeping and per-batch lists
     int32_t *node_pos = nullptr, *slot_node = nullptr, *slot_pos = nullptr;
-    int32_t *rank_pos = nullptr, *tile_miss = nullptr, *hit_rank = nullptr, *hit_pos = nullptr, *miss_rank = nullptr;
+    int32_t *rank_pos = nullptr, *tile_miss = nullptr;
+    // the lists a batch's fetch kernels read, alternating between calls: an early lookup writes the next
+    // batch's while the previous batch's are still in use
+    int32_t *hit_rank[2] = {nullptr, nullptr}, *hit_pos[2] = {nullptr, nullptr}, *miss_rank[2] = {nullptr, nullptr};
+    int cur_gen = 0;
     uint64_t tail = 0;      // insertions so far (host mirrors of what the kernels are told)
     uint64_t ptail = 0;     // next ring position
     uint64_t lookups = 0, hits = 0;
@@ -189,8 +193,9 @@ int32_t tier_row_bytes(const bgl_host_tier *t) { return t->row_bytes; }
 int64_t tier_num_nodes(const bgl_host_tier *t) { return t->num_nodes; }
 
 int tier_enqueue_lookup(bgl_host_tier *t, const int32_t *ids, const int32_t *miss_pos,
-                        const long long *n_ranks_dev, int64_t n_upper, hipStream_t st)
+                        const long long *n_ranks_dev, int64_t n_upper, int gen, hipStream_t st)
 {
+    t->cur_gen = gen & 1;
     if (t->serving) BGL_FAIL(BGL_EINVAL, "host tier: the previous batch has not been finished");
     if (n_upper > t->max_batch)
         BGL_FAIL(BGL_ECAPACITY, "%lld ids exceed the tier's max_batch_rows %lld", (long long)n_upper,
@@ -205,7 +210,7 @@ int tier_enqueue_lookup(bgl_host_tier *t, const int32_t *ids, const int32_t *mis
     hipLaunchKernelGGL(k_tier_probe, dim3(tiles), dim3(TT), 0, st, ids, miss_pos, n_ranks_dev, t->num_nodes,
                        t->node_pos, t->rank_pos, t->tile_miss, reinterpret_cast<int64_t *>(t->pinned_dev));
     hipLaunchKernelGGL(k_tier_lists, dim3(tiles), dim3(TT), 0, st, ids, miss_pos, n_ranks_dev, t->rank_pos,
-                       t->tile_miss, t->hit_rank, t->hit_pos, t->miss_rank,
+                       t->tile_miss, t->hit_rank[t->cur_gen], t->hit_pos[t->cur_gen], t->miss_rank[t->cur_gen],
                        reinterpret_cast<int32_t *>(t->pinned_dev + 64),
                        reinterpret_cast<int64_t *>(t->pinned_dev));
     BGL_HIP(hipGetLastError());
@@ -236,9 +241,9 @@ int tier_begin(bgl_host_tier *t, int64_t n, TierPlan *plan)
     plan->n_hit_gpu = n_hit_gpu;
     plan->n_hit = n_hit;
     plan->n_miss = n_miss;
-    plan->hit_rank = t->hit_rank;
-    plan->hit_pos = t->hit_pos;
-    plan->miss_rank = t->capacity > 0 ? t->miss_rank : nullptr;  // capacity 0: every rank, in order
+    plan->hit_rank = t->hit_rank[t->cur_gen];
+    plan->hit_pos = t->hit_pos[t->cur_gen];
+    plan->miss_rank = t->capacity > 0 ? t->miss_rank[t->cur_gen] : nullptr;  // capacity 0: every rank, in order
     plan->ptail = t->ptail;
     plan->ring = t->ring;
     return BGL_OK;
@@ -282,7 +287,7 @@ int tier_enqueue_update(bgl_host_tier *t, const int32_t *ids, const int32_t *mis
     const int64_t start = n_miss > t->capacity ? n_miss - t->capacity : 0;
     if (n_miss > start) {  // never with capacity 0
         hipLaunchKernelGGL(k_tier_update, dim3((unsigned)bgl::ceil_div(n_miss - start, TT)), dim3(TT), 0, st, ids,
-                           miss_pos, t->miss_rank, start, n_miss, (unsigned long long)t->tail,
+                           miss_pos, t->miss_rank[t->cur_gen], start, n_miss, (unsigned long long)t->tail,
                            (unsigned long long)t->ptail, t->capacity, t->ring, t->node_pos, t->slot_node,
                            t->slot_pos);
         BGL_HIP(hipGetLastError());
@@ -316,7 +321,7 @@ extern "C" int bgl_host_tier_create(const void *store, int64_t num_nodes, int32_
         BGL_FAIL(BGL_EINVAL, "row_bytes must be a positive multiple of 16 (got %d)", row_bytes);
     if (capacity_rows < 0 || capacity_rows > INT32_MAX)
         BGL_FAIL(BGL_EINVAL, "capacity_rows must be in [0, 2^31) (got %lld)", (long long)capacity_rows);
-    if (max_batch_rows < 1 || max_batch_rows > INT32_MAX / 2 || capacity_rows + max_batch_rows > INT32_MAX)
+    if (max_batch_rows < 1 || max_batch_rows > INT32_MAX / 2 || capacity_rows + 2 * max_batch_rows > INT32_MAX)
         BGL_FAIL(BGL_EINVAL, "max_batch_rows must be >= 1 and capacity_rows + max_batch_rows < 2^31 (got %lld)",
                  (long long)max_batch_rows);
     if (num_threads < 0 || num_threads > 256) BGL_FAIL(BGL_EINVAL, "num_threads must be in [0, 256]");
@@ -331,8 +336,9 @@ extern "C" int bgl_host_tier_create(const void *store, int64_t num_nodes, int32_
     t->row_bytes = row_bytes;
     t->capacity = capacity_rows;
     t->max_batch = max_batch_rows;
-    // a tier that keeps nothing may be filled for the next batch while the previous one is still fetched
-    t->ring = capacity_rows > 0 ? capacity_rows + max_batch_rows : 2 * max_batch_rows;
+    // two batches of room beyond the content: the next batch may be brought in (early lookup) while the
+    // previous one is still being fetched
+    t->ring = capacity_rows + 2 * max_batch_rows;
     const size_t mb = (size_t)max_batch_rows;
     const size_t row_total = (size_t)t->ring * (size_t)row_bytes;
     auto fail = [&](int code) { bgl_host_tier_destroy(t); return code; };
@@ -371,9 +377,11 @@ extern "C" int bgl_host_tier_create(const void *store, int64_t num_nodes, int32_
     }
     TRY_ALLOC(t->rank_pos, mb);
     TRY_ALLOC(t->tile_miss, bgl::ceil_div((int64_t)mb, TT) + 1);
-    TRY_ALLOC(t->hit_rank, mb);
-    TRY_ALLOC(t->hit_pos, mb);
-    TRY_ALLOC(t->miss_rank, mb);
+    for (int g = 0; g < 2; ++g) {
+        TRY_ALLOC(t->hit_rank[g], mb);
+        TRY_ALLOC(t->hit_pos[g], mb);
+        TRY_ALLOC(t->miss_rank[g], mb);
+    }
 #undef TRY_ALLOC
     if (capacity_rows > 0) {
         hipLaunchKernelGGL(k_fill_i32, dim3(2048), dim3(256), 0, 0, t->node_pos, num_nodes, -1);
@@ -411,9 +419,11 @@ extern "C" int bgl_host_tier_destroy(bgl_host_tier_t *t)
     (void)hipFree(t->slot_pos);
     (void)hipFree(t->rank_pos);
     (void)hipFree(t->tile_miss);
-    (void)hipFree(t->hit_rank);
-    (void)hipFree(t->hit_pos);
-    (void)hipFree(t->miss_rank);
+    for (int g = 0; g < 2; ++g) {
+        (void)hipFree(t->hit_rank[g]);
+        (void)hipFree(t->hit_pos[g]);
+        (void)hipFree(t->miss_rank[g]);
+    }
     delete t;
     return BGL_OK;
 }

@@ -103,10 +103,10 @@ class MinibatchPipeline:
                                     n_hit_ptr=n_hits.data_ptr() + 8 * i,
                                     lookup_stream=work if (self.write_through and self.early_ok) else None)
             else:
-                # Blocks until the host tier has served the GPU cache's misses.  With a tier that keeps
-                # nothing the map lookup runs early, on the work stream (behind the previous batch's map
-                # update), so the host packs this batch's rows while the previous fetch is on the link.
-                early = self.tier.capacity == 0 and self.write_through and self.early_ok
+                # Blocks until the host tier has served the GPU cache's misses.  The map lookups run
+                # early, on the work stream (behind the previous batch's map update), so the host brings
+                # this batch's rows in while the previous fetch is on the link.
+                early = self.write_through and self.early_ok
                 n_hits[i], h2 = cache.lookup_gather_tiered(self.tier, ids, n, self.out_rows, self.out_slot,
                                                            self.miss_pos, main_stream=chain, side_stream=chain,
                                                            lookup_stream=work if early else None)

@@ -112,15 +112,16 @@ def zipf_batches(rng, N, count, lo, hi, big=None):
 
 
 @pytest.mark.parametrize("dim,dtype", [(4, np.float32), (100, np.float32), (128, np.float32), (264, np.uint16)])
-@pytest.mark.parametrize("write_through", [False, True])
-def test_tiered_random_streams(B, torch_mod, dim, dtype, write_through):
+@pytest.mark.parametrize("write_through,early", [(False, None), (True, None), (True, "own"), (True, "with_insert"),
+                                                 (True, "alternate")])
+def test_tiered_random_streams(B, torch_mod, dim, dtype, write_through, early):
     rng = np.random.default_rng(100 + dim)
     N = 20000
     feats = (rng.standard_normal((N, dim)).astype(np.float32) if dtype == np.float32
              else rng.integers(0, 2**16, (N, dim), dtype=np.uint16))
     # batch 5 has more misses than either level has slots
     batches = zipf_batches(rng, N, 14, 1, 2500, big=9000)
-    run_tiered_stream(B, torch_mod, feats, 1500, 4000, batches, write_through, threads=4)
+    run_tiered_stream(B, torch_mod, feats, 1500, 4000, batches, write_through, threads=4, early=early)
 
 
 @pytest.mark.parametrize("cap1,cap2,threads", [(64, 300, 1), (1, 1, 3), (500, 100, 2), (3000, 18000, 0),
@@ -133,7 +134,8 @@ def test_tiered_capacity_corners(B, torch_mod, cap1, cap2, threads):
     N = 20000
     feats = rng.standard_normal((N, 100)).astype(np.float32)
     batches = zipf_batches(rng, N, 12, 200, 3000)
-    _, tier = run_tiered_stream(B, torch_mod, feats, cap1, cap2, batches, True, threads, side=(threads != 2))
+    _, tier = run_tiered_stream(B, torch_mod, feats, cap1, cap2, batches, True, threads, side=(threads != 2),
+                                early=("with_insert" if threads in (0, 3) else None))
     assert tier.stats()["threads"] == (threads or tier.stats()["threads"])
 
 
@@ -182,7 +184,7 @@ def test_tiered_argument_errors(B, torch_mod):
     with pytest.raises(B.BglError) as e:      # row width differs
         gc.lookup_gather_tiered(other, ids, 10, out, slot, mp)
     assert e.value.code == B.BGL_EINVAL
-    with pytest.raises(B.BglError) as e:      # early lookup needs capacity 0 and write-through mode
+    with pytest.raises(B.BglError) as e:      # early lookup needs write-through mode
         gc.lookup_gather_tiered(tier, ids, 10, out, slot, mp, lookup_stream=torch.cuda.Stream())
     assert e.value.code == B.BGL_EINVAL
     bad = ids.clone()
@@ -279,7 +281,7 @@ def test_tiered_random_cases_property(B, torch_mod):
         rng = np.random.default_rng(seed)
         feats = rng.integers(0, 2**32, (n_nodes, row_chunks * 4), dtype=np.uint32)
         batches = [rng.permutation(n_nodes)[: min(k, n_nodes)].tolist() for k in sizes]
-        if early is not None and (cap2 != 0 or not write_through):
+        if early is not None and not write_through:
             early = None                      # the library refuses early lookups there (tested elsewhere)
         run_tiered_stream(B, torch_mod, feats, cap1, cap2, batches, write_through, threads, side=side,
                           cache_has_store=(cap2 == 0), early=early)
