@@ -341,18 +341,17 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_miss(
     }
 }
 
-// Tiered lookup: out[miss_pos[r]] = rows[p] for listed misses l0 <= l < l0 + count
-// of the GPU cache, r = rank[l] (r = l without a list: a tier that keeps nothing
-// lists every miss); rows is the host tier's page-locked ring and
-// p = pos[l] (rows the tier held) or, with SEQ, (ptail + l) mod ring (rows the
-// host threads have just brought in, in list order).  Same launch shape and
-// write-through rule as k_fetch_miss.
-template <int Q, bool WT, bool SEQ>
+// Tiered lookup: out[miss_pos[r]] = rows[(first + l) mod ring] for listed misses
+// l0 <= l < l0 + count of the GPU cache, r = rank[l] (r = l without a list: a tier
+// that keeps nothing lists every miss).  rows are page-locked host rows that the
+// host threads have just packed in list order: the host tier's ring (rows it
+// brought in from the store) or its staging rows (rows it held).  Same launch
+// shape and write-through rule as k_fetch_miss.
+template <int Q, bool WT>
 __global__ __launch_bounds__(COPY_THREADS) void k_fetch_rows(
-    const int32_t *__restrict__ rank, const int32_t *__restrict__ pos, int64_t l0, int64_t count,
-    unsigned long long ptail, int64_t ring, const int32_t *__restrict__ miss_pos, int q,
-    const uint4 *__restrict__ rows, uint4 *__restrict__ out, const CacheDev *dev,
-    uint4 *__restrict__ buffer, int64_t capacity, int par, int64_t n_miss)
+    const int32_t *__restrict__ rank, int64_t l0, int64_t count, unsigned long long first, int64_t ring,
+    const int32_t *__restrict__ miss_pos, int q, const uint4 *__restrict__ rows, uint4 *__restrict__ out,
+    const CacheDev *dev, uint4 *__restrict__ buffer, int64_t capacity, int par, int64_t n_miss)
 {
     const int qq = Q > 0 ? Q : q;
     const int64_t total = count * qq;
@@ -373,8 +372,7 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_rows(
                 RowSplit<Q>::split(idx, q, l, c);
                 l += l0;
                 const int64_t r = rank ? rank[l] : l;
-                const int64_t p = SEQ ? (int64_t)((ptail + (unsigned long long)l) % (unsigned long long)ring)
-                                      : (int64_t)pos[l];
+                const int64_t p = (int64_t)((first + (unsigned long long)l) % (unsigned long long)ring);
                 v[k] = rows[p * qq + c];
                 dst[k] = (int64_t)miss_pos[r] * qq + c;
                 if (WT && r >= start)
@@ -983,39 +981,45 @@ extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t
     if (rc != BGL_OK) return rc;
     // (Waking the copy threads earlier, to have them spin until the ids arrive, was measured:
     // slower, the spinning threads get in the way of the wait for the lookup.)
-    if (plan.n_miss > 0) {
-        rc = bgl::tier_copy_start(t);
-        if (rc != BGL_OK) return rc;
-    }
     if (ss != ms) BGL_HIP(hipStreamWaitEvent(ss, c->ev_listed, 0));
     const int par = (int)(c->insert_calls & 1);
     const uint4 *rows = reinterpret_cast<const uint4 *>(bgl::tier_rows_device(t));
-    auto fetch = [&](auto seq, const int32_t *rank, const int32_t *pos, int64_t l0, int64_t count) {
+    // out[miss_pos[rank[l]]] = base[(first + l) mod ring] for l0 <= l < l0 + count: packed rows
+    auto fetch = [&](const uint4 *base, unsigned long long first, int64_t ring, const int32_t *rank, int64_t l0,
+                     int64_t count) {
         if (count == 0) return;
         Prof p(c, BGL_STAGE_FETCH_MISS, ss);
         const int blocks = (int)std::min<int64_t>(copy_blocks(count, q), FETCH_BLOCKS);
         dispatch_q(q, [&](auto Q) {
-            auto k = c->write_through ? k_fetch_rows<decltype(Q)::value, true, decltype(seq)::value>
-                                      : k_fetch_rows<decltype(Q)::value, false, decltype(seq)::value>;
-            launch(c, ss, k, dim3(blocks), dim3(COPY_THREADS), rank, pos, l0, count,
-                   (unsigned long long)plan.ptail, plan.ring, mpos, q, rows,
+            auto k = c->write_through ? k_fetch_rows<decltype(Q)::value, true>
+                                      : k_fetch_rows<decltype(Q)::value, false>;
+            launch(c, ss, k, dim3(blocks), dim3(COPY_THREADS), rank, l0, count, first, ring, mpos, q, base,
                    reinterpret_cast<uint4 *>(out_rows), c->dev, reinterpret_cast<uint4 *>(c->buffer), c->capacity,
                    par, n - plan.n_hit_gpu);
         });
     };
-    // Rows the tier holds cross the link while host threads bring the others in from the
-    // store, a chunk at a time; each chunk is fetched as soon as it is in place.
-    fetch(std::false_type{}, plan.hit_rank, plan.hit_pos, 0, plan.n_hit);
-    // Small chunks first, so that the link starts early; the copy threads outrun the link
-    // only by a little, so the chunks grow until a launch is a few per cent of its kernel.
-    {
+    // Host threads pack the rows: first those the tier holds (into staging rows), then the others
+    // (from the store into the ring).  Each chunk is fetched as soon as it is in place.  Small chunks
+    // first, so that the link starts early; the copy threads outrun the link only by a little, so the
+    // chunks grow until a launch is a few per cent of its kernel.
+    if (plan.n_hit + plan.n_miss > 0) {
+        rc = bgl::tier_copy_start(t);
+        if (rc != BGL_OK) return rc;
+        const uint4 *stage = reinterpret_cast<const uint4 *>(plan.stage);
         // (an early lookup is ahead of the link anyway: full chunks from the start)
-        int64_t chunk = (plan.n_hit > TIER_CHUNK_ROWS || ls != ms) ? TIER_CHUNK_ROWS : TIER_FIRST_CHUNK_ROWS;
-        for (int64_t launched = 0; launched < plan.n_miss;) {
+        int64_t chunk = ls != ms ? TIER_CHUNK_ROWS : TIER_FIRST_CHUNK_ROWS;
+        const int64_t total = plan.n_hit + plan.n_miss;
+        for (int64_t launched = 0; launched < total;) {
             const int64_t ready = bgl::tier_copy_progress(t);
-            if (ready - launched >= chunk || ready == plan.n_miss) {
-                fetch(std::true_type{}, plan.miss_rank, nullptr, launched, ready - launched);
-                launched = ready;
+            // a chunk does not straddle the two kinds of rows
+            const int64_t limit = launched < plan.n_hit ? std::min(ready, plan.n_hit) : ready;
+            if (limit - launched >= chunk || (limit > launched && (limit == plan.n_hit || limit == total))) {
+                if (launched < plan.n_hit)
+                    fetch(stage, 0ull, (int64_t)INT64_MAX, plan.hit_rank, launched, limit - launched);
+                else
+                    fetch(rows, (unsigned long long)plan.ptail, plan.ring, plan.miss_rank, launched - plan.n_hit,
+                          limit - launched);
+                launched = limit;
                 chunk = std::min<int64_t>(2 * chunk, TIER_CHUNK_ROWS);
             } else {
                 __builtin_ia32_pause();

@@ -15,8 +15,8 @@ namespace bgl {
 struct TierPlan {
     // Misses of the GPU cache are numbered by rank r (their order in miss_pos).
     int64_t n_hit_gpu;         // hits in the GPU cache (read back with the tier's counts)
-    const int32_t *hit_rank;   // device: ranks the tier holds, ascending ...
-    const int32_t *hit_pos;    // ... and the ring position of each one's row
+    const int32_t *hit_rank;   // device: ranks the tier holds, ascending; the h-th one's row is
+    const char *stage;         // copied to row h of these page-locked staging rows (device-visible address)
     int64_t n_hit;
     const int32_t *miss_rank;  // device: ranks it does not hold, ascending (null: all of them); the j-th one's row
     int64_t n_miss;            // goes to ring position (ptail + j) mod ring
@@ -47,9 +47,10 @@ int tier_enqueue_lookup(bgl_host_tier *t, const int32_t *ids, const int32_t *mis
 // Once st has passed that point: read the counts (n = size of the GPU cache's
 // lookup), check the ids.  Nothing has changed yet if this fails.
 int tier_begin(bgl_host_tier *t, int64_t n, TierPlan *plan);
-// Host threads start copying the rows of the tier misses, in list order, from the store
-// to their ring positions; tier_copy_progress tells how many leading rows are in place
-// (monotone, reaches n_miss); tier_copy_wait ends the job.
+// Host threads start copying: first the rows the tier holds, in list order, into the
+// staging rows, then the rows of the tier misses, in list order, from the store to their
+// ring positions.  tier_copy_progress tells how many leading rows of that sequence are in
+// place (monotone, reaches n_hit + n_miss); tier_copy_wait ends the job.
 int tier_copy_start(bgl_host_tier *t);
 int64_t tier_copy_progress(bgl_host_tier *t);
 void tier_copy_wait(bgl_host_tier *t);
