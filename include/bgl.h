@@ -318,11 +318,12 @@ int bgl_cache_set_profiling_every(bgl_cache_t *c, int stage, int every);
 /*
  * Second cache level in host memory (Sec. 3.2.3: a CPU cache with the same
  * policy as the GPU cache sits between it and the feature store).  The tier is
- * a FIFO cache of capacity_rows rows in page-locked memory, which the GPU reads
- * in place; rows it does not hold are copied in from `store` by host threads,
- * packed in miss order, and read by the GPU as a stream from there.  Its map
- * (node -> row, 4 bytes per node) and slot tables live in device memory of the
- * current device and are looked up and updated by kernels.
+ * a FIFO cache of capacity_rows rows in page-locked memory.  Its map (node ->
+ * row, 4 bytes per node) and slot tables live in device memory of the current
+ * device and are looked up and updated by kernels; host threads only move
+ * rows: the rows the tier holds into page-locked staging rows, the others from
+ * `store` into the tier, both packed in miss order, and the GPU reads them from
+ * there as a stream.
  *   store           the feature store: num_nodes rows of row_bytes bytes in
  *                   host memory of any kind (pageable, a mapped file,
  *                   page-locked); stays alive and unchanged until
@@ -332,7 +333,9 @@ int bgl_cache_set_profiling_every(bgl_cache_t *c, int stage, int every);
  *                   row_bytes is not a multiple of 128: rows read in place move
  *                   whole 128-byte lines over the link, packed rows do not
  *   max_batch_rows  the largest n a tiered lookup will be called with; the
- *                   page-locked ring holds capacity_rows + 2 * max_batch_rows rows
+ *                   page-locked ring holds capacity_rows + 2 * max_batch_rows
+ *                   rows, the staging rows (capacity_rows > 0) another
+ *                   2 * max_batch_rows
  *   num_threads     host threads that copy rows (the calling thread drives the
  *                   GPU meanwhile); 0 = min(cores, 16) - 1
  * Errors: BGL_EINVAL (null store, sizes out of range, row_bytes not a multiple
@@ -354,9 +357,9 @@ int bgl_host_tier_destroy(bgl_host_tier_t *t);
  * The tier handles the GPU cache's misses, in miss_pos order, as one FIFO batch:
  * looked up against the tier's state at entry, then its own misses inserted in
  * that order (the rule of bgl_cache_insert_fifo, tail advancing by their
- * number).  The call blocks the host until the lists are known and the store
- * rows are copied; the kernels that move rows found in the tier run on
- * side_stream during that copy, and the copied rows follow chunk by chunk.  On
+ * number).  The call blocks the host until the lists are known and the rows
+ * are packed; the kernels that move them run on side_stream chunk by chunk
+ * while the host threads are still copying.  On
  * return the fetch of all miss rows is enqueued on side_stream
  * (bgl_cache_wait_rows as usual) and the tier's update on main_stream; the GPU
  * cache still needs its bgl_cache_insert_fifo.  ids, out_slot and miss_pos must
