@@ -47,6 +47,9 @@ def parse_args():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run three plain 1 GiB device-to-device copies (the known-size "
                          "kernel that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--hit-gather-sweep", action="store_true",
+                    help="only time the hit gather of bgl_cache_lookup_gather over row widths, launch sizes and "
+                         "hit densities (lookups into a full cache; one JSON line, not the headline metric)")
     ap.add_argument("--graph-placement", choices=("config", "device", "host_pinned", "host_pinned_col"), default="config",
                     help="where the CSR lives: as the configuration says (default), in HBM, in page-locked host "
                          "memory, or column ids in page-locked host memory with the row offsets in HBM")
@@ -77,6 +80,72 @@ def measure_h2d_peak(torch, nbytes=256 << 20):
     return 4 * nbytes / (time.perf_counter() - t0) / 1e9
 
 
+def hit_gather_sweep(torch, np, B):
+    """The hit gather through the C ABI on lookups into a full cache, per row width, launch size
+    and hit density (all hits, or hits spread among misses as in an epoch).  The backing table is
+    in HBM so that the set-up is quick; only the gather kernel is timed (by its own dispatch).
+    Before every launch a 512 MiB copy displaces what the caches hold; every launch looks up a
+    fresh random id set; the first launch of a case is checked against the table."""
+    cases = [  # row_bytes, cache rows, ids per lookup, fraction of them that hit
+        (400, 490_000, 426_000, 0.315),      # `mid`: 134 K hits among 426 K ids
+        (400, 490_000, 490_000, 1.0),
+        (400, 4_000_000, 1_000_000, 1.0),
+        (400, 4_000_000, 4_000_000, 1.0),
+        (512, 4_000_000, 1_000_000, 1.0),
+        (512, 4_000_000, 4_000_000, 1.0),
+        (1024, 4_000_000, 285_000, 0.37),    # `wide`: 106 K hits among 285 K ids
+        (1024, 4_000_000, 250_000, 1.0),
+        (1024, 4_000_000, 1_000_000, 1.0),
+        (1024, 4_000_000, 4_000_000, 1.0),
+    ]
+    flush_a = torch.zeros(512 << 20, dtype=torch.uint8, device="cuda")
+    flush_b = torch.empty_like(flush_a)
+    out, built = [], {}
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20211208)
+    for rb, cap, n, frac in cases:
+        if (rb, cap) not in built:
+            built.clear()                        # frees the previous table and cache
+            torch.cuda.empty_cache()
+            nodes = 2 * cap                      # ids >= cap are never inserted: they miss
+            table = torch.empty((nodes, rb), dtype=torch.uint8, device="cuda")
+            table.view(torch.int32).random_(generator=gen)
+            cache = B.Cache(cap, table.data_ptr(), num_nodes=nodes, row_bytes=rb)
+            rows = torch.empty((cap, rb), dtype=torch.uint8, device="cuda")
+            slot = torch.empty(cap, dtype=torch.int32, device="cuda")
+            mpos = torch.empty(cap, dtype=torch.int32, device="cuda")
+            ids = torch.arange(cap, dtype=torch.int32, device="cuda")
+            cache.lookup_gather(ids, cap, rows, slot, mpos)       # all miss
+            cache.insert_fifo(ids, mpos, -1, rows)                 # the cache now holds ids 0 .. cap-1
+            built[(rb, cap)] = (table, cache, rows, slot, mpos)
+        table, cache, rows, slot, mpos = built[(rb, cap)]
+        n_hit = int(round(n * frac))
+        reps, hits = 5, 0
+        cache.set_profiling(("gather_hit",))     # (re-)enabling resets the timers
+        for r in range(reps):
+            ids = torch.randperm(cap, device="cuda", generator=gen)[:n_hit].to(torch.int32)
+            if n_hit < n:                        # spread the hits among ids that miss
+                ids = torch.cat([ids, cap + torch.randperm(cap, device="cuda", generator=gen)[:n - n_hit].to(torch.int32)])
+                ids = ids[torch.randperm(n, device="cuda", generator=gen)].contiguous()
+            flush_b.copy_(flush_a)
+            torch.cuda.synchronize()
+            cache.lookup_gather(ids, n, rows, slot, mpos)
+            torch.cuda.synchronize()
+            hits += int(cache.n_hit_host[0])
+            if r == 0:
+                assert int(cache.n_hit_host[0]) == n_hit
+                sample = torch.randperm(n, device="cuda", generator=gen)[:65536]
+                assert torch.equal(rows[sample], table[ids[sample].long()]), "gathered rows differ from the table"
+        ms, launches = cache.profile()["gather_hit"]
+        gbps = 2.0 * rb * hits / (ms * 1e-3) / 1e9
+        out.append({"row_bytes": rb, "cache_rows": cap, "cache_buffer_MB": cap * rb / 1e6, "ids_per_lookup": n,
+                    "hits_per_lookup": n_hit, "bytes_per_launch": 2.0 * rb * n_hit, "launches": launches,
+                    "avg_launch_us": 1e3 * ms / launches, "achieved_GBps": gbps, "frac_of_hbm_peak": gbps / HBM_PEAK_GBS})
+    return {"hit_gather_sweep": out, "kernel": "k_gather_hits", "peak_GBps": HBM_PEAK_GBS,
+            "bytes": "2 x row_bytes x hits (algorithmic: every hit row read once and written once)",
+            "timing": "begin/end of each kernel recorded on the device by its own dispatch"}
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -97,6 +166,10 @@ def main():
         print(json.dumps({"calibrate_copy_bytes": 1 << 30, "copies": 3}))
         return 0
     from paper_2112_08541_amd import binding as B
+    if args.hit_gather_sweep:
+        torch.cuda.set_device(0)
+        print(json.dumps(hit_gather_sweep(torch, np, B)))
+        return 0
     from paper_2112_08541_amd import inputs
     from paper_2112_08541_amd.pipeline import MinibatchPipeline
 
