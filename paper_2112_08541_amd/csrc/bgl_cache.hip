@@ -1009,11 +1009,22 @@ extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t
         // (an early lookup is ahead of the link anyway: full chunks from the start)
         int64_t chunk = ls != ms ? TIER_CHUNK_ROWS : TIER_FIRST_CHUNK_ROWS;
         const int64_t total = plan.n_hit + plan.n_miss;
+        bool gather_done = false;
         for (int64_t launched = 0; launched < total;) {
             const int64_t ready = bgl::tier_copy_progress(t);
             // a chunk does not straddle the two kinds of rows
             const int64_t limit = launched < plan.n_hit ? std::min(ready, plan.n_hit) : ready;
-            if (limit - launched >= chunk || (limit > launched && (limit == plan.n_hit || limit == total))) {
+            bool go = limit > launched && (limit == plan.n_hit || limit == total);
+            if (!go && limit - launched >= chunk) {
+                // An early lookup's fetch cannot start before its hit gather has run, which waits for
+                // the previous call's fetch: until then the packed rows pile up for one larger launch.
+                if (ls != ms && !gather_done) {
+                    gather_done = hipEventQuery(c->ev_listed) == hipSuccess;
+                    (void)hipGetLastError();  // "not ready" is no error
+                }
+                go = gather_done || ls == ms;
+            }
+            if (go) {
                 if (launched < plan.n_hit)
                     fetch(stage, 0ull, (int64_t)INT64_MAX, plan.hit_rank, launched, limit - launched);
                 else
