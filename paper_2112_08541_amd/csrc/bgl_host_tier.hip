@@ -199,11 +199,11 @@ int64_t tier_num_nodes(const bgl_host_tier *t) { return t->num_nodes; }
 int tier_enqueue_lookup(bgl_host_tier *t, const int32_t *ids, const int32_t *miss_pos,
                         const long long *n_ranks_dev, int64_t n_upper, int gen, hipStream_t st)
 {
-    t->cur_gen = gen & 1;
     if (t->serving) BGL_FAIL(BGL_EINVAL, "host tier: the previous batch has not been finished");
     if (n_upper > t->max_batch)
         BGL_FAIL(BGL_ECAPACITY, "%lld ids exceed the tier's max_batch_rows %lld", (long long)n_upper,
                  (long long)t->max_batch);
+    t->cur_gen = gen & 1;
     if (t->capacity == 0) return BGL_OK;  // the cache's own list kernel has sent ids and counts (tier_prepare)
     if (n_upper == 0) {
         t->counts()[1] = 0;
@@ -338,7 +338,7 @@ extern "C" int bgl_host_tier_create(const void *store, int64_t num_nodes, int32_
     if (capacity_rows < 0 || capacity_rows > INT32_MAX)
         BGL_FAIL(BGL_EINVAL, "capacity_rows must be in [0, 2^31) (got %lld)", (long long)capacity_rows);
     if (max_batch_rows < 1 || max_batch_rows > INT32_MAX / 2 || capacity_rows + 2 * max_batch_rows > INT32_MAX)
-        BGL_FAIL(BGL_EINVAL, "max_batch_rows must be >= 1 and capacity_rows + max_batch_rows < 2^31 (got %lld)",
+        BGL_FAIL(BGL_EINVAL, "max_batch_rows must be >= 1 and capacity_rows + 2 * max_batch_rows < 2^31 (got %lld)",
                  (long long)max_batch_rows);
     if (num_threads < 0 || num_threads > 256) BGL_FAIL(BGL_EINVAL, "num_threads must be in [0, 256]");
     if (num_threads == 0) {
