@@ -61,7 +61,7 @@ struct bgl_cache {
     int32_t *slot_to_node;  // capacity
     uint32_t *slot_to_entry;
     CacheDev *dev;
-    int32_t *mbs;           // per-tile miss counts of the most recent lookup
+    int32_t *mbs;           // per-tile miss counts of the most recent lookup (mbs_cap of them), then mbs_cap prefixes
     int64_t mbs_cap;
     int32_t *hit_pos;       // hits of the most recent lookup: hit_cap positions, then hit_cap slots
     int64_t hit_cap;
@@ -169,6 +169,12 @@ __global__ __launch_bounds__(KEYS_PER_TILE) void k_probe(const int32_t *__restri
     }
 }
 
+__global__ __launch_bounds__(kScanThreads) void k_scan_tiles(const int32_t *mbs, int64_t tiles, int32_t *prefix)
+{
+    __shared__ int sh[kScanThreads / kWave];
+    scan_tile_counts<kScanThreads>(mbs, tiles, prefix, sh);
+}
+
 // Counters of an empty lookup (n = 0); with n > 0 k_split_list publishes them.
 __global__ void k_empty_lookup(CacheDev *dev, int64_t *n_hit_host, int gen)
 {
@@ -183,11 +189,13 @@ __global__ void k_empty_lookup(CacheDev *dev, int64_t *n_hit_host, int gen)
 // Ordered lists of the miss positions and of the hits (position and slot side by
 // side, so the gather needs no dependent lookup).  A hit's rank is its position
 // minus the number of misses before it.  Every workgroup sums the miss counts of
-// the tiles before it (a few thousand ints at most); the last one also
-// publishes the call's counters.
+// the tiles before it (a few thousand ints at most), or reads the sum from
+// tile_prefix where the call has so many tiles that k_scan_tiles ran first; the
+// last one also publishes the call's counters.
 __global__ __launch_bounds__(KEYS_PER_TILE) void k_split_list(const int32_t *__restrict__ out_slot,
                                                               int64_t n,
                                                               const int32_t *__restrict__ mbs,
+                                                              const int32_t *__restrict__ tile_prefix,
                                                               int32_t *miss_pos, int32_t *hit_pos,
                                                               int32_t *hit_slot, CacheDev *dev,
                                                               int64_t *n_hit_host,
@@ -197,11 +205,15 @@ __global__ __launch_bounds__(KEYS_PER_TILE) void k_split_list(const int32_t *__r
 {
     __shared__ int sh_scan[KEYS_PER_TILE / kWave];
     __shared__ int sh_base;
-    int part = 0;
-    for (int t = threadIdx.x; t < (int)blockIdx.x; t += KEYS_PER_TILE) part += mbs[t];
     int tot;
-    (void)block_excl_scan<KEYS_PER_TILE>(part, sh_scan, tot);
-    if (threadIdx.x == 0) sh_base = tot;
+    if (tile_prefix) {
+        if (threadIdx.x == 0) sh_base = tile_prefix[blockIdx.x];
+    } else {
+        int part = 0;
+        for (int t = threadIdx.x; t < (int)blockIdx.x; t += KEYS_PER_TILE) part += mbs[t];
+        (void)block_excl_scan<KEYS_PER_TILE>(part, sh_scan, tot);
+        if (threadIdx.x == 0) sh_base = tot;
+    }
     const int64_t i = (int64_t)blockIdx.x * KEYS_PER_TILE + threadIdx.x;
     const int slot = i < n ? out_slot[i] : 0;
     const int flag = (i < n && slot < 0) ? 1 : 0;
@@ -763,7 +775,7 @@ int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, in
         c->mbs = nullptr;
         c->mbs_cap = 0;
         const int64_t cap = std::max<int64_t>(2 * tiles + 1, 1024);
-        BGL_HIP(hipMalloc((void **)&c->mbs, sizeof(int32_t) * (size_t)cap));
+        BGL_HIP(hipMalloc((void **)&c->mbs, 2 * sizeof(int32_t) * (size_t)cap));  // counts, then their prefixes
         c->mbs_cap = cap;
     }
     if (n > c->hit_cap) {
@@ -811,8 +823,13 @@ int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, in
         }
         {
             Prof p(c, BGL_STAGE_MISS_LIST, ls, false);
+            int32_t *tile_prefix = nullptr;
+            if (tiles >= kSelfSumTiles) {
+                tile_prefix = c->mbs + c->mbs_cap;
+                hipLaunchKernelGGL(k_scan_tiles, dim3(1), dim3(kScanThreads), 0, ls, c->mbs, tiles, tile_prefix);
+            }
             hipLaunchKernelGGL(k_split_list, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), 0, ls, out_slot,
-                               n, c->mbs, miss_pos, c->hit_pos, c->hit_pos + c->hit_cap, c->dev,
+                               n, c->mbs, tile_prefix, miss_pos, c->hit_pos, c->hit_pos + c->hit_cap, c->dev,
                                n_hit_dev, ids, c->num_nodes,
                                tier ? bgl::tier_ids_device_if_passthrough(tier) : nullptr, mpos_copy, gen);
         }

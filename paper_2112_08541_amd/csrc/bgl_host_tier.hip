@@ -76,6 +76,13 @@ __global__ __launch_bounds__(TT) void k_tier_probe(const int32_t *__restrict__ i
     }
 }
 
+__global__ __launch_bounds__(kScanThreads) void k_tier_scan_tiles(const long long *__restrict__ n_ranks,
+                                                                  const int32_t *tile_miss, int32_t *prefix)
+{
+    __shared__ int sh[kScanThreads / kWave];
+    scan_tile_counts<kScanThreads>(tile_miss, (*n_ranks + TT - 1) / TT, prefix, sh);
+}
+
 // Ordered lists: ranks the tier holds, ranks it does not; the ring positions of
 // the former and the node ids of the latter go to page-locked host memory for
 // the copy threads.  The last workgroup publishes both counts to the host.
@@ -84,6 +91,7 @@ __global__ __launch_bounds__(TT) void k_tier_lists(const int32_t *__restrict__ i
                                                    const long long *__restrict__ n_ranks,
                                                    const int32_t *__restrict__ rank_pos,
                                                    const int32_t *__restrict__ tile_miss,
+                                                   const int32_t *__restrict__ tile_prefix,
                                                    int32_t *hit_rank, int32_t *hit_pos_host, int32_t *miss_rank,
                                                    int32_t *miss_ids_host, int64_t *counts_host)
 {
@@ -95,11 +103,15 @@ __global__ __launch_bounds__(TT) void k_tier_lists(const int32_t *__restrict__ i
         if (m == 0 && blockIdx.x == 0 && threadIdx.x == 0) { counts_host[1] = 0; counts_host[2] = 0; }
         return;
     }
-    int part = 0;
-    for (int t = threadIdx.x; t < (int)blockIdx.x; t += TT) part += tile_miss[t];
     int tot;
-    (void)block_excl_scan<TT>(part, sh_scan, tot);
-    if (threadIdx.x == 0) sh_base = tot;
+    if (tile_prefix) {  // calls of many tiles: k_tier_scan_tiles has summed the counts
+        if (threadIdx.x == 0) sh_base = tile_prefix[blockIdx.x];
+    } else {
+        int part = 0;
+        for (int t = threadIdx.x; t < (int)blockIdx.x; t += TT) part += tile_miss[t];
+        (void)block_excl_scan<TT>(part, sh_scan, tot);
+        if (threadIdx.x == 0) sh_base = tot;
+    }
     const int64_t r = (int64_t)blockIdx.x * TT + threadIdx.x;
     const int p = r < m ? rank_pos[r] : 0;
     const int flag = (r < m && p < 0) ? 1 : 0;
@@ -213,8 +225,14 @@ int tier_enqueue_lookup(bgl_host_tier *t, const int32_t *ids, const int32_t *mis
     const unsigned tiles = (unsigned)bgl::ceil_div(n_upper, TT);
     hipLaunchKernelGGL(k_tier_probe, dim3(tiles), dim3(TT), 0, st, ids, miss_pos, n_ranks_dev, t->num_nodes,
                        t->node_pos, t->rank_pos, t->tile_miss, reinterpret_cast<int64_t *>(t->pinned_dev));
+    int32_t *tile_prefix = nullptr;
+    if (tiles >= kSelfSumTiles) {
+        tile_prefix = t->tile_miss + bgl::ceil_div(t->max_batch, TT) + 1;
+        hipLaunchKernelGGL(k_tier_scan_tiles, dim3(1), dim3(kScanThreads), 0, st, n_ranks_dev, t->tile_miss,
+                           tile_prefix);
+    }
     hipLaunchKernelGGL(k_tier_lists, dim3(tiles), dim3(TT), 0, st, ids, miss_pos, n_ranks_dev, t->rank_pos,
-                       t->tile_miss, t->hit_rank[t->cur_gen],
+                       t->tile_miss, tile_prefix, t->hit_rank[t->cur_gen],
                        reinterpret_cast<int32_t *>(t->pinned_dev + 64 + 4 * (size_t)t->max_batch),
                        t->miss_rank[t->cur_gen], reinterpret_cast<int32_t *>(t->pinned_dev + 64),
                        reinterpret_cast<int64_t *>(t->pinned_dev));
@@ -405,7 +423,7 @@ extern "C" int bgl_host_tier_create(const void *store, int64_t num_nodes, int32_
         TRY_ALLOC(t->slot_pos, capacity_rows);
     }
     TRY_ALLOC(t->rank_pos, mb);
-    TRY_ALLOC(t->tile_miss, bgl::ceil_div((int64_t)mb, TT) + 1);
+    TRY_ALLOC(t->tile_miss, 2 * (bgl::ceil_div((int64_t)mb, TT) + 1));  // counts, then their prefixes
     for (int g = 0; g < 2; ++g) {
         TRY_ALLOC(t->hit_rank[g], mb);
         TRY_ALLOC(t->miss_rank[g], mb);

@@ -103,5 +103,27 @@ __device__ __forceinline__ int block_excl_scan(int v, int *sh, int &total)
     return base + inc - v;
 }
 
+// Exclusive prefix sums of `tiles` per-tile counts, computed by ONE workgroup of
+// THREADS threads (prefix may alias counts).  The list kernels use it for calls of
+// many tiles, where every workgroup summing its predecessors' counts itself
+// would make the work quadratic in the tile count.
+template <int THREADS>
+__device__ __forceinline__ void scan_tile_counts(const int32_t *counts, int64_t tiles, int32_t *prefix, int *sh)
+{
+    int carry = 0;
+    for (int64_t base = 0; base < tiles; base += THREADS) {
+        const int64_t t = base + threadIdx.x;
+        const int v = t < tiles ? counts[t] : 0;
+        int tot;
+        const int ex = block_excl_scan<THREADS>(v, sh, tot);
+        if (t < tiles) prefix[t] = carry + ex;
+        carry += tot;
+    }
+}
+
+constexpr int kScanThreads = 1024;
+// From this many tiles on the list kernels read prefixes made by scan_tile_counts.
+constexpr int64_t kSelfSumTiles = 4096;
+
 }  // namespace bgl
 #endif

@@ -342,6 +342,18 @@ def test_cache_single_stream_and_tiny_capacity(B, torch_mod):
     run_cache_stream(B, torch_mod, feats, 500, batches)
 
 
+@pytest.mark.parametrize("write_through,early", [(False, None), (True, "with_insert")])
+def test_cache_lookups_of_many_tiles(B, torch_mod, write_through, early):
+    """Lookups of more than 4096 tiles of 256 ids: the list kernel then takes the tiles' prefix
+    sums from a scan kernel instead of summing its predecessors' counts in every workgroup."""
+    rng = np.random.default_rng(77)
+    N, cap = 3_000_000, 1_200_000
+    feats = rng.integers(0, 2**31, (N, 4), dtype=np.int32).view(np.float32)      # 16-byte rows, compared as bytes
+    perm = rng.permutation(N).astype(np.int32)
+    batches = [perm[:1_300_000], perm[900_000:2_000_001], perm[:1_048_576], perm[5:1_048_576], rng.permutation(N)[:2_100_000]]
+    run_cache_stream(B, torch_mod, feats, cap, batches, device_n_miss=True, write_through=write_through, early=early)
+
+
 def test_cache_long_churn_keeps_map_exact(B, torch_mod):
     """Many times the capacity flows through a small cache: every eviction blanks a
     map word and every insertion reuses one; lookups must stay exact."""

@@ -124,6 +124,17 @@ def test_tiered_random_streams(B, torch_mod, dim, dtype, write_through, early):
     run_tiered_stream(B, torch_mod, feats, 1500, 4000, batches, write_through, threads=4, early=early)
 
 
+@pytest.mark.parametrize("cap2", [0, 900_000])
+def test_tiered_lookups_of_many_tiles(B, torch_mod, cap2):
+    """More than 4096 tiles of 256 ids in both levels' list kernels (prefix sums from a scan kernel)."""
+    rng = np.random.default_rng(78)
+    N = 3_000_000
+    feats = rng.integers(0, 2**31, (N, 4), dtype=np.int32).view(np.float32)      # 16-byte rows, compared as bytes
+    perm = rng.permutation(N).astype(np.int32)
+    batches = [perm[:1_300_000], perm[600_000:2_000_001], perm[:1_200_000]]
+    run_tiered_stream(B, torch_mod, feats, 200_000, cap2, batches, True, threads=0, early="with_insert")
+
+
 @pytest.mark.parametrize("cap1,cap2,threads", [(64, 300, 1), (1, 1, 3), (500, 100, 2), (3000, 18000, 0),
                                                (1500, 0, 0), (1, 0, 1)])
 def test_tiered_capacity_corners(B, torch_mod, cap1, cap2, threads):
