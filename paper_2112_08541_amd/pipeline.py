@@ -13,6 +13,10 @@ over the host link, so the loop is built to keep the link busy:
                  map update(i) (then only the hit gather sits between two fetches); with
                  a staging ring (a host tier of capacity 0) the host then packs batch
                  i+1's miss rows while fetch(i) is still on the link
+  sampling stream  only with such a ring or tier: sample(i+2) runs there, so that
+                 lookup(i+1) need not queue behind it and the host gets the missed ids
+                 at once; every row is then packed before the link is free, and one
+                 launch fetches the batch
 
 The cache is put in write-through mode (every lookup here is followed by the
 insert of all its misses), which makes the FIFO update a map update that needs no
@@ -43,10 +47,15 @@ class MinibatchPipeline:
         self.out_slot = torch.empty(self.cap, dtype=torch.int32, device="cuda")
         self.miss_pos = torch.empty(self.cap, dtype=torch.int32, device="cuda")
         self.chain = torch.cuda.Stream()          # lookups, hit gathers, miss fetches
-        self.work = torch.cuda.current_stream()   # sampling, map updates
+        self.work = torch.cuda.current_stream()   # map updates, early lookups, (sampling)
         self.write_through = write_through
         # an early lookup adds two hand-overs between streams: it pays for batches of many thousand ids
         self.early_ok = self.cap >= 65536
+        # With early lookups and host threads that pack the miss rows, sampling gets a stream of its
+        # own: the next batch's lookup then follows the map update at once instead of queueing behind
+        # the sampling of the batch after it, and the host has the missed ids half a millisecond sooner
+        # (all rows are then packed before the link is free, and one launch fetches them).
+        self.samp_stream = torch.cuda.Stream()
         self.tier = tier                          # second cache level in host memory (Sec. 3.2.3), or None
         self.last_ids, self.last_n = None, 0      # input nodes of the most recent batch
         self.set_cache(cache)
@@ -68,6 +77,7 @@ class MinibatchPipeline:
         Returns (n_input per batch, n_hit per batch)."""
         nb = seeds_dev.shape[0]
         K, cache, chain, work = self.K, self.cache, self.chain, self.work
+        samp = self.samp_stream if (self.tier is not None and self.write_through and self.early_ok) else work
         n_hits = torch.zeros(max(steps, 1), dtype=torch.int64).pin_memory()
         n_list = []
         self.tier_hits = []
@@ -76,8 +86,8 @@ class MinibatchPipeline:
         def sample(i):
             smp = self.samplers[i % 3]
             b = (first_step + i) % nb
-            sb = smp.sample(seeds_dev[b], int(rng_seeds[b]) ^ ((first_step + i) // nb), stream=work)
-            sampled_ev[i % 3].record(work)
+            sb = smp.sample(seeds_dev[b], int(rng_seeds[b]) ^ ((first_step + i) // nb), stream=samp)
+            sampled_ev[i % 3].record(samp)
             return sb
 
         def sizes(i):
@@ -88,6 +98,8 @@ class MinibatchPipeline:
                 raise B.BglError(status, "sampling reported an error on the device")
             return int(smp.counts_host[K])
 
+        if samp is not work:
+            samp.wait_stream(work)      # the seeds, and whatever the caller enqueued before
         sbs = {0: sample(0)}
         if steps > 1:
             sbs[1] = sample(1)
@@ -96,6 +108,8 @@ class MinibatchPipeline:
             sb = sbs.pop(i)
             ids = sb.input_nodes(self.cap)
             chain.wait_event(sampled_ev[i % 3])
+            if samp is not work:
+                work.wait_event(sampled_ev[i % 3])
             if self.tier is None:
                 # in write-through mode the map lookup and the lists run early, on the work stream
                 cache.lookup_gather(ids, n, self.out_rows, self.out_slot, self.miss_pos,
@@ -116,7 +130,7 @@ class MinibatchPipeline:
                 cache.insert_fifo(ids, self.miss_pos, -1, self.out_rows, stream=work)
             if i + 2 < steps:
                 # workspace (i+2) % 3 was batch i-1's; its fetch ended before hit gather(i)
-                cache.wait_lists(work)
+                cache.wait_lists(samp)
                 sbs[i + 2] = sample(i + 2)
             if self.tier is None:
                 cache.insert_fifo(ids, self.miss_pos, -1, self.out_rows, stream=work)
