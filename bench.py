@@ -8,7 +8,9 @@ host memory, FIFO insertion.  Workload: the "mid" configuration (2.45 M nodes,
 the nodes, one epoch of 200 random-order batches starting from an empty cache),
 a synthetic stand-in with the shape of Ogbn-products.
 
-Prints ONE JSON line; see the design doc for how each field is measured.
+Prints ONE JSON line: the headline value, the roofline of the hit gather (kernel time
+recorded by the kernel's own dispatch), the host-link rate of the miss fetch, and the CPU
+oracle timed on the same box.
 """
 from __future__ import annotations
 

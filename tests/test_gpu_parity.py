@@ -610,3 +610,32 @@ def test_cache_argument_errors_and_device_resident_store(B, torch_mod):
                                      miss_pos.data_ptr(), None, None, None) == B.BGL_EINVAL
     assert L.bgl_cache_profile(gc._h, 17, None, None) == B.BGL_EINVAL
     torch_mod.cuda.synchronize()
+
+
+def test_bench_line_contract_on_the_tiny_config():
+    """bench.py prints ONE JSON line with the agreed fields (here on the small configuration;
+    the benchmark itself defaults to `mid`)."""
+    import json
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--config", "tiny", "--steps", "20",
+                        "--warmup", "3", "--cpu-batches", "5"], capture_output=True, text=True, timeout=600)
+    assert p.returncode == 0, p.stderr[-2000:]
+    lines = [l for l in p.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    r = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline", "host_link"):
+        assert key in r, key
+    assert r["n_gpus"] == 1 and r["steps"] == 20 and r["warmup"] == 3 and r["unit"] == "minibatches/s"
+    assert r["vs_baseline"] is None and r["data"] == "synthetic" and "workload" in r["config"]
+    assert abs(r["value"] - 1e3 / r["ms_per_step"]) < 1e-6 * r["value"]
+    roof = r["roofline"]
+    for key in ("bound", "achieved", "peak", "unit", "frac", "traffic"):
+        assert key in roof, key
+    assert roof["bound"] == "hbm" and roof["peak"] == 8000.0 and roof["unit"] == "GB/s"
+    assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-12 and roof["achieved"] > 0
+    cpu = r["cpu_baseline"]
+    assert cpu["kind"] == "oracle" and cpu["cores"] == 1 and cpu["value"] > 0 and cpu["unit"] == r["unit"]
+    assert 0.0 < r["config"]["hit_ratio_cumulative"] < 1.0
