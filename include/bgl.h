@@ -361,7 +361,8 @@ int bgl_host_tier_destroy(bgl_host_tier_t *t);
  * are packed; the kernels that move them run on side_stream chunk by chunk
  * while the host threads are still copying.  On
  * return the fetch of all miss rows is enqueued on side_stream
- * (bgl_cache_wait_rows as usual) and the tier's update on main_stream; the GPU
+ * (bgl_cache_wait_rows as usual) and the tier's update on main_stream (on
+ * lookup_stream with early_lookup); the GPU
  * cache still needs its bgl_cache_insert_fifo.  ids, out_slot and miss_pos must
  * stay untouched until main_stream has passed this call.  ids must be distinct.
  * One tier serves one cache's calls in order; it is not thread-safe.
@@ -406,10 +407,11 @@ int bgl_host_tier_stats(bgl_host_tier_t *t, uint64_t *lookups, uint64_t *hits, d
 /*
  * One BFS sequence of the training nodes (Sec. 3.2.2: training-node sequences
  * generated in BFS order).  The traversal runs on the GPU over the registered
- * graph.  Canonical order: level by level from `root`, ids ascending inside a
- * level; when a traversal is exhausted it restarts at the smallest node id not
- * visited yet, so small components end up at the end of the sequence.  Only the
- * training nodes are recorded.
+ * graph.  Canonical order: the first-in first-out queue traversal from `root`,
+ * the not yet visited out-neighbors of a node entering the queue in the order of
+ * its CSR row; when the queue runs empty the traversal restarts at the smallest
+ * node id not visited yet, so small components end up at the end of the
+ * sequence.  Only the training nodes are recorded.
  *   train_nodes   host, num_train distinct node ids
  *   seq           host, receives num_train ids
  * Synchronous (returns when seq is filled).
