@@ -245,6 +245,7 @@ def main():
         if not args.all_stage_timers:
             cache.set_profiling_every("gather_hit", GATHER_SAMPLE_EVERY)
             cache.set_profiling_every("fetch_miss", LINK_SAMPLE_EVERY)
+    ring_before = stage_ring.stats() if miss_path == "staged" else None
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     n_list, hit_list = pipe.run(seeds_dev, w.rng_seeds, args.steps)   # ends with a device synchronise
@@ -289,6 +290,8 @@ def main():
             "miss_path": miss_path,
             "miss_path_trial_ms_per_batch": trial or None,
             "host_copy_threads": (stage_ring.stats()["threads"] if miss_path == "staged" else 0),
+            "host_copy_ms_per_batch": ((stage_ring.stats()["copy_ms"] - ring_before["copy_ms"]) / args.steps
+                                       if miss_path == "staged" else None),
             "gathered_feature_GBps": rb * tot_n / elapsed / 1e9,
         },
     }

@@ -395,9 +395,10 @@ int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t, const int
 int bgl_host_tier_export_state(bgl_host_tier_t *t, int32_t *slot_to_node, uint64_t *tail,
                                void *buffer_rows);
 /*
- * Lifetime counters: ids looked up, ids found, host wall time spent copying rows
- * from the store (milliseconds) over `batches` served batches; and the thread
- * count in use.  Pointers may be null.
+ * Lifetime counters: ids looked up, ids found, host wall time spent packing rows
+ * (milliseconds, per batch from the start of its copies to the moment the
+ * calling thread sees the last row in place) over `batches` served batches; and
+ * the thread count in use.  Pointers may be null.
  */
 int bgl_host_tier_stats(bgl_host_tier_t *t, uint64_t *lookups, uint64_t *hits, double *copy_ms,
                         uint64_t *batches, int32_t *threads);
