@@ -346,6 +346,7 @@ def main():
         if pipe.last_n:
             cache.set_write_through(False)       # lookups without inserts follow
             cache.set_profiling(("gather_hit",))
+            cache.set_profiling_every("gather_hit", 1)
             reps, hits2 = 5, 0
             for _ in range(reps):
                 cache.lookup_gather(pipe.last_ids, pipe.last_n, pipe.out_rows, pipe.out_slot, pipe.miss_pos)
