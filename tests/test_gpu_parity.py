@@ -639,3 +639,6 @@ def test_bench_line_contract_on_the_tiny_config():
     cpu = r["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] == 1 and cpu["value"] > 0 and cpu["unit"] == r["unit"]
     assert 0.0 < r["config"]["hit_ratio_cumulative"] < 1.0
+    assert roof["launches"] == 20 // 4           # the hit gather is timed in every 4th batch
+    rep = r["roofline_repeat_lookup"]
+    assert rep["launches"] == 5 and 0.0 < rep["frac"] < 1.0
