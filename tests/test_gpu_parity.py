@@ -642,3 +642,46 @@ def test_bench_line_contract_on_the_tiny_config():
     assert roof["launches"] == 20 // 4           # the hit gather is timed in every 4th batch
     rep = r["roofline_repeat_lookup"]
     assert rep["launches"] == 5 and 0.0 < rep["frac"] < 1.0
+
+
+def test_stage_timers_count_their_launches_and_leave_results_alone(B, torch_mod):
+    """bgl_cache_set_profiling / _every / bgl_cache_profile: every timed stage reports one launch per
+    call (or per `every`-th call), with a plausible duration, and the rows are the table's."""
+    torch = torch_mod
+    rng = np.random.default_rng(11)
+    N, cap, rb = 50_000, 8_000, 64
+    table = torch.from_numpy(rng.integers(0, 256, (N, rb), dtype=np.uint8)).pin_memory()
+    cache = B.Cache(cap, table, num_nodes=N, row_bytes=rb)
+    out = torch.empty((6_000, rb), dtype=torch.uint8, device="cuda")
+    slot = torch.empty(6_000, dtype=torch.int32, device="cuda")
+    mpos = torch.empty(6_000, dtype=torch.int32, device="cuda")
+
+    def batches(count):
+        for _ in range(count):
+            ids = torch.from_numpy(rng.permutation(N)[:6_000].astype(np.int32)).cuda()
+            cache.lookup_gather(ids, 6_000, out, slot, mpos)
+            cache.insert_fifo(ids, mpos, -1, out)
+            torch.cuda.synchronize()
+            assert torch.equal(out.cpu(), table[ids.cpu().long()])
+
+    cache.set_profiling(True)
+    batches(6)
+    prof = cache.profile()
+    for stage in B.STAGE_NAMES:
+        ms, launches = prof[stage]
+        assert launches == 6, stage
+        assert 0.0 < ms < 50.0, (stage, ms)
+    # only some stages, the hit gather in every 3rd lookup only (lookups are counted from creation: 7 .. 12)
+    cache.set_profiling(("gather_hit", "fetch_miss"))
+    cache.set_profiling_every("gather_hit", 3)
+    batches(6)
+    prof = cache.profile()
+    assert prof["gather_hit"][1] == 2 and prof["fetch_miss"][1] == 6
+    assert prof["probe"][1] == 0 and prof["insert_map"][1] == 0
+    cache.set_profiling(False)
+    batches(2)
+    assert all(cache.profile()[stage][1] == 0 for stage in B.STAGE_NAMES)
+    with pytest.raises(B.BglError):
+        cache.set_profiling_every("gather_hit", 0)
+    rc = B.lib().bgl_cache_set_profiling_every(cache._h, 99, 1)
+    assert rc == B.BGL_EINVAL
