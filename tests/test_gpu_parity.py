@@ -388,9 +388,10 @@ def test_cache_flags_out_of_range_id(B, torch_mod):
 
 
 # ------------------------------------------------------------ whole pipeline
-def run_config(cfg, n_batches, device_n_miss=False, check_every=1, write_through=False):
+def run_config(cfg, n_batches, device_n_miss=False, check_every=1, write_through=False, w=None):
     inputs = _inputs()
-    w = inputs.make_workload(cfg, pinned=True)
+    if w is None:
+        w = inputs.make_workload(cfg, pinned=True)
     gp = GpuPipeline(w, device_n_miss=device_n_miss, write_through=write_through)
     op = OraclePipeline(w)
     hits = total = 0
@@ -425,11 +426,18 @@ def test_overlapped_pipeline_as_benchmarked_matches_oracle(torch_mod, B, write_t
     """The launch configuration bench.py times (two sampling workspaces, next batch sampled
     while the misses are fetched on the side stream, device-side miss count) on the
     full-size mid workload: every batch's outputs and the final cache state."""
-    from paper_2112_08541_amd.pipeline import MinibatchPipeline
     inputs = _inputs()
-    cfg = inputs.CONFIGS["mid"]
-    w = inputs.make_workload(cfg, pinned=True)
-    graph = B.Graph(w.row_ptr, w.col)
+    w = inputs.make_workload(inputs.CONFIGS["mid"], pinned=True)
+    run_overlapped_against_oracle(torch_mod, B, w, 8, write_through)
+
+
+def run_overlapped_against_oracle(torch_mod, B, w, steps, write_through=True):
+    """MinibatchPipeline as bench.py sets it up for the workload's configuration (graph placement
+    included); every batch's sampled blocks, lists and rows, and the final cache state."""
+    from paper_2112_08541_amd.pipeline import MinibatchPipeline
+    cfg = w.cfg
+    placement = B.BGL_HOST_PINNED if cfg.graph_placement == "host_pinned" else B.BGL_DEVICE
+    graph = B.Graph(w.row_ptr, w.col, placement)
     cache = B.Cache(cfg.cache_rows, w.features.ctypes.data, num_nodes=cfg.num_nodes, row_bytes=cfg.row_bytes)
     pipe = MinibatchPipeline(graph, cache, cfg.batch, cfg.fanouts, cfg.row_bytes, write_through=write_through)
     seeds_dev = torch_mod.from_numpy(w.seed_batches).cuda()
@@ -448,7 +456,6 @@ def test_overlapped_pipeline_as_benchmarked_matches_oracle(torch_mod, B, write_t
                       out_slot=p.out_slot[:n].cpu().numpy(), miss_pos=p.miss_pos[: n - n_hit].cpu().numpy(),
                       out_rows=p.out_rows[:n].cpu().numpy())
 
-    steps = 8
     n_list, hit_list = pipe.run(seeds_dev, w.rng_seeds, steps, on_batch=grab)
     op = OraclePipeline(w)
     for b in range(steps):
@@ -525,25 +532,29 @@ def test_pipeline_wide_shape_scaled():
 SKIP_FULL = os.environ.get("BGL_SKIP_FULL_SIZE", "") not in ("", "0")
 
 
-def run_full(cfg, n_batches, check_every):
+def run_full(cfg, n_batches, check_every, overlapped_steps, torch_mod, B):
+    """One batch after the other with a check of every output, then the overlapped pipeline
+    as bench.py runs this configuration, on the same full-size workload."""
     try:
-        return run_config(cfg, n_batches, device_n_miss=True, check_every=check_every)
+        w = _inputs().make_workload(cfg, pinned=True)
+        run_config(cfg, n_batches, device_n_miss=True, check_every=check_every, w=w)
     except MemoryError as e:  # the box cannot page-lock this much host memory
         pytest.skip(f"not enough page-locked host memory for {cfg.name}: {e}")
+    run_overlapped_against_oracle(torch_mod, B, w, overlapped_steps)
 
 
 @pytest.mark.skipif(SKIP_FULL, reason="BGL_SKIP_FULL_SIZE is set")
-def test_pipeline_wide_config_full_size():
+def test_pipeline_wide_config_full_size(torch_mod, B):
     """30 M nodes, ~600 M edges, bf16 x 512 rows, 4,096 seeds, fanout 25/10, 4.5 M-row cache
     (~33 GB of page-locked host memory, ~20 s)."""
-    run_full(_inputs().CONFIGS["wide"], 4, 2)
+    run_full(_inputs().CONFIGS["wide"], 4, 2, 5, torch_mod, B)
 
 
 @pytest.mark.skipif(SKIP_FULL, reason="BGL_SKIP_FULL_SIZE is set")
-def test_pipeline_large_config_full_size():
+def test_pipeline_large_config_full_size(torch_mod, B):
     """111 M nodes, ~1.6 B edges (int64 offsets, CSR read in place from page-locked host
     memory), fp32 x 128 rows, 25 M-row cache (~64 GB of page-locked host memory, ~30 s)."""
-    run_full(_inputs().CONFIGS["large"], 3, 1)
+    run_full(_inputs().CONFIGS["large"], 3, 1, 6, torch_mod, B)
 
 
 # ------------------------------------------------------ argument errors on the GPU side
