@@ -238,13 +238,16 @@ def main():
 
     cache = new_cache()
     pipe.set_cache(cache)
+    # (a run of a few batches times every one of them)
+    g_every = 1 if (args.all_stage_timers or args.steps < 2 * GATHER_SAMPLE_EVERY) else GATHER_SAMPLE_EVERY
+    l_every = 1 if (args.all_stage_timers or args.steps < 2 * LINK_SAMPLE_EVERY) else LINK_SAMPLE_EVERY
     if not args.no_stage_timers:
         # A timed launch holds its stream up for ~10 us, so the hit gather is timed in every 4th
         # batch only and the miss fetch (several launches per batch) in every 10th.
         cache.set_profiling(True if args.all_stage_timers else ("gather_hit", "fetch_miss"))
         if not args.all_stage_timers:
-            cache.set_profiling_every("gather_hit", GATHER_SAMPLE_EVERY)
-            cache.set_profiling_every("fetch_miss", LINK_SAMPLE_EVERY)
+            cache.set_profiling_every("gather_hit", g_every)
+            cache.set_profiling_every("fetch_miss", l_every)
     ring_before = stage_ring.stats() if miss_path == "staged" else None
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -301,7 +304,6 @@ def main():
         # The library has the kernel dispatch itself record the kernel's begin and end on the
         # device, so g_ms is the sum of the kernel's own durations (what a kernel trace shows).
         g_kernel_ms = max(g_ms, 1e-9)
-        g_every = 1 if args.all_stage_timers else GATHER_SAMPLE_EVERY
         g_sampled = [i for i in range(args.steps) if (i + 1) % g_every == 0]  # the cache counts its lookups from 1
         g_hit = int(sum(h_arr[i] for i in g_sampled))
         achieved = 2.0 * rb * g_hit / (g_kernel_ms * 1e-3) / 1e9 if g_n > 0 else 0.0
@@ -324,7 +326,7 @@ def main():
                                            if k != "event_overhead" else v[0])
                                        for k, v in prof.items() if v[1] > 0 and k != "fetch_miss"}
         # Host link: the miss fetch kernels of the sampled batches of the timed epoch
-        every = 1 if args.all_stage_timers else LINK_SAMPLE_EVERY
+        every = l_every
         sampled = [i for i in range(args.steps) if (i + 1) % every == 0]      # the cache counts its lookups from 1
         f_ms, f_n = prof["fetch_miss"]
         miss3 = int(sum(n_arr[i] - h_arr[i] for i in sampled))
