@@ -368,7 +368,10 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_rows(
     const int qq = Q > 0 ? Q : q;
     const int64_t total = count * qq;
     const int64_t start = n_miss > capacity ? n_miss - capacity : 0;
-    const unsigned long long tail = WT ? dev->tail[par] : 0ull;
+    // the two wrap-arounds without a division per chunk: the launch covers less than one turn of
+    // the ring, and the ranks it stores (start <= r < n_miss) less than one turn of the buffer
+    const int64_t first_pos = (int64_t)((first + (unsigned long long)l0) % (unsigned long long)ring) - l0;
+    const int64_t tail_slot = WT ? (int64_t)((dev->tail[par] + (unsigned long long)start) % (unsigned long long)capacity) - start : 0;
     const int64_t step = (int64_t)gridDim.x * (COPY_THREADS * COPY_UNROLL);
     for (int64_t base = (int64_t)blockIdx.x * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
          base - threadIdx.x < total; base += step) {
@@ -384,11 +387,15 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_rows(
                 RowSplit<Q>::split(idx, q, l, c);
                 l += l0;
                 const int64_t r = rank ? rank[l] : l;
-                const int64_t p = (int64_t)((first + (unsigned long long)l) % (unsigned long long)ring);
+                int64_t p = first_pos + l;
+                if (p >= ring) p -= ring;
                 v[k] = rows[p * qq + c];
                 dst[k] = (int64_t)miss_pos[r] * qq + c;
-                if (WT && r >= start)
-                    dst2[k] = (int64_t)((tail + (unsigned long long)r) % (unsigned long long)capacity) * qq + c;
+                if (WT && r >= start) {
+                    int64_t slot = tail_slot + r;
+                    if (slot >= capacity) slot -= capacity;
+                    dst2[k] = slot * qq + c;
+                }
             }
         }
 #pragma unroll
