@@ -40,10 +40,12 @@ def parse_args():
                     help="leave the per-kernel HIP events out of the timed region")
     ap.add_argument("--all-stage-timers", action="store_true",
                     help="bracket every cache kernel with events (default: hit gather and miss fetch only)")
-    ap.add_argument("--miss-path", choices=("auto", "zero_copy", "staged"), default="auto",
+    ap.add_argument("--miss-path", choices=("auto", "zero_copy", "staged", "staged_kernel"), default="auto",
                     help="how miss rows cross the host link: kernels read the page-locked table in place "
-                         "(zero_copy), or host threads pack the rows into a page-locked ring that kernels read "
-                         "as a stream (staged: no partial 128-byte lines on the link); auto = staged when "
+                         "(zero_copy), or host threads pack the rows into a page-locked ring (no partial 128-byte "
+                         "lines on the link) from where plain copies move them into device memory and kernels "
+                         "scatter them (staged), or from where the kernels read them over the link themselves "
+                         "(staged_kernel); auto = the faster of zero_copy and staged in a warm-up trial when "
                          "row_bytes is not a multiple of 128 and batches are large")
     ap.add_argument("--no-write-through", action="store_true",
                     help="FIFO update copies the rows after the fetch instead of the fetch filling the cache buffer")
@@ -69,18 +71,21 @@ def parse_args():
     return ap.parse_args()
 
 
-def measure_h2d_peak(torch, nbytes=256 << 20):
+def measure_h2d_peak(torch, nbytes=256 << 20, windows=4):
     """Pinned-memory host-to-device copy rate on this machine (GB/s), the practical
-    ceiling of the host link that the miss fetch is compared with."""
-    src = torch.empty(nbytes, dtype=torch.uint8).pin_memory()
+    ceiling of the host link that the miss fetch is compared with.  Every timed copy
+    reads another window of the source, so that none is served from the host's caches
+    (the miss rows of a batch are not either)."""
+    src = torch.empty(windows * nbytes, dtype=torch.uint8).pin_memory()
+    src.fill_(1)
     dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
-    dst.copy_(src, non_blocking=True)
+    dst.copy_(src[:nbytes], non_blocking=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(4):
-        dst.copy_(src, non_blocking=True)
+    for k in range(windows):
+        dst.copy_(src[k * nbytes:(k + 1) * nbytes], non_blocking=True)
     torch.cuda.synchronize()
-    return 4 * nbytes / (time.perf_counter() - t0) / 1e9
+    return windows * nbytes / (time.perf_counter() - t0) / 1e9
 
 
 def hit_gather_sweep(torch, np, B):
@@ -208,10 +213,11 @@ def main():
     eligible = cfg.row_bytes % 128 != 0 and pipe.cap >= 65536 and feat_dev is None
     stage_ring = None
     trial = {}
-    if miss_path == "staged" or (miss_path == "auto" and eligible):
+    if miss_path in ("staged", "staged_kernel") or (miss_path == "auto" and eligible):
         # capacity 0: nothing is kept in host memory, every miss row passes through the ring
         stage_ring = B.HostTier(w.features.view(np.uint8).reshape(cfg.num_nodes, cfg.row_bytes), 0, pipe.cap,
                                 args.tier_threads)
+        stage_ring.set_copy_engine(miss_path != "staged_kernel")
     if miss_path == "auto":
         miss_path = "zero_copy"
         if stage_ring is not None and args.warmup > 0:
@@ -231,7 +237,8 @@ def main():
             miss_path = min(trial, key=trial.get)
         elif stage_ring is not None:
             miss_path = "staged"
-    pipe.tier = stage_ring if miss_path == "staged" else None
+    staged = miss_path in ("staged", "staged_kernel")
+    pipe.tier = stage_ring if staged else None
     if args.warmup > 0 and not trial:
         pipe.run(seeds_dev, w.rng_seeds, args.warmup)
     scratch.close()
@@ -244,11 +251,12 @@ def main():
     if not args.no_stage_timers:
         # A timed launch holds its stream up for ~10 us, so the hit gather is timed in every 4th
         # batch only and the miss fetch (several launches per batch) in every 10th.
-        cache.set_profiling(True if args.all_stage_timers else ("gather_hit", "fetch_miss"))
+        cache.set_profiling(True if args.all_stage_timers else ("gather_hit", "fetch_miss", "link_copy"))
         if not args.all_stage_timers:
             cache.set_profiling_every("gather_hit", g_every)
             cache.set_profiling_every("fetch_miss", l_every)
-    ring_before = stage_ring.stats() if miss_path == "staged" else None
+            cache.set_profiling_every("link_copy", l_every)
+    ring_before = stage_ring.stats() if staged else None
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     n_list, hit_list = pipe.run(seeds_dev, w.rng_seeds, args.steps)   # ends with a device synchronise
@@ -292,9 +300,9 @@ def main():
             "hit_ratio_steady_state": steady_ratio,
             "miss_path": miss_path,
             "miss_path_trial_ms_per_batch": trial or None,
-            "host_copy_threads": (stage_ring.stats()["threads"] if miss_path == "staged" else 0),
+            "host_copy_threads": (stage_ring.stats()["threads"] if staged else 0),
             "host_copy_ms_per_batch": ((stage_ring.stats()["copy_ms"] - ring_before["copy_ms"]) / args.steps
-                                       if miss_path == "staged" else None),
+                                       if staged else None),
             "gathered_feature_GBps": rb * tot_n / elapsed / 1e9,
         },
     }
@@ -324,23 +332,31 @@ def main():
         }
         result["stage_ms_per_step"] = {k: (v[0] / (len(g_sampled) if k == "gather_hit" else args.steps)
                                            if k != "event_overhead" else v[0])
-                                       for k, v in prof.items() if v[1] > 0 and k != "fetch_miss"}
+                                       for k, v in prof.items() if v[1] > 0 and k not in ("fetch_miss", "link_copy")}
         # Host link: the miss fetch kernels of the sampled batches of the timed epoch
         every = l_every
         sampled = [i for i in range(args.steps) if (i + 1) % every == 0]      # the cache counts its lookups from 1
-        f_ms, f_n = prof["fetch_miss"]
+        # staged: the link is the copies' (timed by event records on the copy stream), the fetch stage is
+        # the kernels that scatter the landed rows in device memory
+        over_link = "link_copy" if miss_path == "staged" else "fetch_miss"
+        f_ms, f_n = prof[over_link]
         miss3 = int(sum(n_arr[i] - h_arr[i] for i in sampled))
         link = miss3 * rb / (f_ms * 1e-3) / 1e9 if f_ms > 0 else 0.0
         h2d = measure_h2d_peak(torch)
         result["host_link"] = {
-            "kernel": "k_fetch_rows" if miss_path == "staged" else "k_fetch_miss", "achieved": link, "unit": "GB/s",
+            "kernel": {"staged": "hipMemcpyAsync of the packed rows", "staged_kernel": "k_fetch_rows"}.get(miss_path, "k_fetch_miss"),
+            "achieved": link, "unit": "GB/s",
             "nominal_peak": HOST_LINK_NOMINAL_GBS, "measured_h2d_copy_peak": h2d,
             "frac_of_nominal": link / HOST_LINK_NOMINAL_GBS, "frac_of_measured": link / h2d,
             "avg_launch_us": 1e3 * f_ms / max(f_n, 1), "launches_per_step": f_n / max(len(sampled), 1),
             "link_ms_per_step": f_ms / max(len(sampled), 1),
-            "note": "fetch kernels of every %d-th batch of the timed epoch (%d batches), timed by their dispatches"
-                    % (every, len(sampled)),
+            "note": "%s of every %d-th batch of the timed epoch (%d batches), timed by %s"
+                    % ("copies" if miss_path == "staged" else "fetch kernels", every, len(sampled),
+                       "event records around each copy" if miss_path == "staged" else "their dispatches"),
         }
+        if miss_path == "staged":
+            s_ms, s_n = prof["fetch_miss"]
+            result["host_link"]["scatter_kernels_us_per_step"] = 1e3 * s_ms / max(len(sampled), 1)
 
         # The same kernel on a launch that is mostly hits (outside the timed region, not
         # part of `value`): the epoch's last batch is looked up again right after its
@@ -394,6 +410,7 @@ def main():
         tier_rows = int(args.two_level * cfg.num_nodes)
         steps2 = min(args.steps, 100)
         tier = B.HostTier(store, tier_rows, pipe.cap, args.tier_threads)
+        tier.set_copy_engine(args.miss_path != "staged_kernel")
         c2 = B.Cache(cfg.cache_rows, None, num_nodes=cfg.num_nodes, row_bytes=rb)
         pipe2 = MinibatchPipeline(graph, c2, cfg.batch, cfg.fanouts, rb, write_through=True, tier=tier)
         torch.cuda.synchronize()

@@ -283,7 +283,7 @@ int bgl_cache_stats(bgl_cache_t *c, uint64_t *lookups, uint64_t *hits, uint64_t 
 /*
  * Per-kernel timing for measurements.  `stage_mask` has bit (1 << stage) set for
  * every stage the cache shall time (0 = off, BGL_ALL_STAGES = all).  A stage that
- * is one kernel per launch (all but BGL_STAGE_MISS_LIST) is timed by the kernel
+ * is one kernel per launch (all but BGL_STAGE_MISS_LIST and BGL_STAGE_LINK_COPY) is timed by the kernel
  * dispatch itself, which records the kernel's begin and end on the device into a
  * pair of events: the figure is the kernel's own duration, the one a kernel
  * trace shows.  BGL_STAGE_MISS_LIST (several small kernels) is bracketed by two
@@ -297,7 +297,9 @@ int bgl_cache_stats(bgl_cache_t *c, uint64_t *lookups, uint64_t *hits, uint64_t 
 #define BGL_STAGE_FETCH_MISS 3  /* backing store -> out_rows */
 #define BGL_STAGE_INSERT_MAP 4  /* evict + enter ids in the map */
 #define BGL_STAGE_INSERT_ROWS 5 /* out_rows -> cache buffer */
-#define BGL_NUM_STAGES 6
+#define BGL_STAGE_LINK_COPY 6   /* tiered lookup with the copy-engine transport: the copies over the host
+                                   link, each bracketed by two event records on the copy stream */
+#define BGL_NUM_STAGES 7
 /* pseudo stage: what two event records read around a kernel that does nothing
  * (measured when profiling is enabled; the share of BGL_STAGE_MISS_LIST that is
  * not kernel time); total_ms is that single figure */
@@ -346,6 +348,21 @@ int bgl_host_tier_create(const void *store, int64_t num_nodes, int32_t row_bytes
                          bgl_host_tier_t **out);
 /* Waits for the device to go idle first: kernels may still be reading the rows. */
 int bgl_host_tier_destroy(bgl_host_tier_t *t);
+
+/*
+ * Transport of the packed rows (off by default).  Off: kernels on side_stream
+ * read the page-locked rows over the host link and write them to their places,
+ * so the link is idle while those kernels wait for the lookup's hit gather.
+ * On: plain copies on a stream of the tier's own move the packed rows into
+ * device memory (2 * max_batch_rows rows of it, allocated by this call) as soon
+ * as they are packed, independent of the cache's kernels; kernels on
+ * side_stream then scatter them from there.  With early lookups the link then
+ * carries one batch after the other without a pause.  Results are identical.
+ * Waits for the device to go idle.  BGL_STAGE_FETCH_MISS then times the scatter
+ * kernels, BGL_STAGE_LINK_COPY the copies.
+ * Errors: BGL_EINVAL, BGL_ENOMEM, BGL_EHIP.
+ */
+int bgl_host_tier_set_copy_engine(bgl_host_tier_t *t, int enable);
 
 /*
  * bgl_cache_lookup_gather with the host tier behind the GPU cache (workflow of

@@ -23,8 +23,8 @@ BGL_MAX_FANOUT = 64
 BGL_COUNTS_LEN = 2 * BGL_MAX_HOPS + 2
 BGL_DEVICE, BGL_HOST_PINNED, BGL_HOST_PINNED_COL = 0, 1, 2
 (STAGE_PROBE, STAGE_MISS_LIST, STAGE_GATHER_HIT, STAGE_FETCH_MISS,
- STAGE_INSERT_MAP, STAGE_INSERT_ROWS) = range(6)
-STAGE_NAMES = ["probe", "miss_list", "gather_hit", "fetch_miss", "insert_map", "insert_rows"]
+ STAGE_INSERT_MAP, STAGE_INSERT_ROWS, STAGE_LINK_COPY) = range(7)
+STAGE_NAMES = ["probe", "miss_list", "gather_hit", "fetch_miss", "insert_map", "insert_rows", "link_copy"]
 
 EXPORTS = [
     "bgl_last_error", "bgl_graph_load_csr", "bgl_graph_destroy", "bgl_sample_workspace_bytes",
@@ -32,7 +32,7 @@ EXPORTS = [
     "bgl_cache_lookup_gather_early",
     "bgl_cache_insert_fifo", "bgl_cache_set_write_through", "bgl_cache_wait_rows", "bgl_cache_wait_lists", "bgl_cache_export_state", "bgl_cache_stats",
     "bgl_cache_set_profiling", "bgl_cache_profile", "bgl_cache_set_profiling_every",
-    "bgl_host_tier_create", "bgl_host_tier_destroy", "bgl_cache_lookup_gather_tiered",
+    "bgl_host_tier_create", "bgl_host_tier_destroy", "bgl_host_tier_set_copy_engine", "bgl_cache_lookup_gather_tiered",
     "bgl_host_tier_export_state", "bgl_host_tier_stats",
     "bgl_order_bfs_sequence", "bgl_order_proximity", "bgl_order_choose_sequences",
     "bgl_order_shuffling_error",
@@ -79,6 +79,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     L.bgl_cache_wait_lists.argtypes = [vp, vp]
     L.bgl_host_tier_create.argtypes = [vp, i64, i32, i64, i64, i32, C.POINTER(vp)]
     L.bgl_host_tier_destroy.argtypes = [vp]
+    L.bgl_host_tier_set_copy_engine.argtypes = [vp, ci]
     L.bgl_cache_lookup_gather_tiered.argtypes = [vp, vp, vp, i64, vp, vp, vp, C.POINTER(i64), vp, vp, vp, ci]
     L.bgl_host_tier_export_state.argtypes = [vp, vp, C.POINTER(C.c_uint64), vp]
     L.bgl_host_tier_stats.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(C.c_double), C.POINTER(u64), C.POINTER(i32)]
@@ -387,6 +388,11 @@ class HostTier:
             self._h = None
 
     __del__ = close
+
+    def set_copy_engine(self, enable: bool) -> None:
+        """Packed rows cross the link as plain copies into device memory (then scattered by kernels)
+        instead of being read over the link by the kernels themselves."""
+        _check(lib().bgl_host_tier_set_copy_engine(self._h, 1 if enable else 0))
 
     def export_state(self, with_buffer: bool = True):
         s2n = np.empty(self.capacity, dtype=np.int32)

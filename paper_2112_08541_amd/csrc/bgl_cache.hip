@@ -268,6 +268,8 @@ constexpr int FETCH_BLOCKS = 64;
 // Tiered lookup: rows the host threads copy per chunk before that chunk's fetch is launched.
 constexpr int64_t TIER_CHUNK_ROWS = 49152;
 constexpr int64_t TIER_FIRST_CHUNK_ROWS = 3072;
+// The same with the copy-engine transport: rows per copy (a copy costs the link a few microseconds of gap).
+constexpr int64_t TIER_COPY_ROWS = 98304;
 
 // out[i] = buffer[out_slot[i]] for every hit i (taken from the hit list, so the
 // work is proportional to the hits).  Consecutive lanes take consecutive
@@ -565,7 +567,8 @@ struct Prof {
     Prof(bgl_cache *c_, int stage, hipStream_t st_, bool exact_ = true) : c(c_), st(st_), exact(exact_)
     {
         if (!(c->profiling & (1u << stage))) return;
-        const uint64_t call = stage >= BGL_STAGE_INSERT_MAP ? c->insert_calls + 1 : c->lookup_calls;
+        const bool of_update = stage == BGL_STAGE_INSERT_MAP || stage == BGL_STAGE_INSERT_ROWS;
+        const uint64_t call = of_update ? c->insert_calls + 1 : c->lookup_calls;
         if (c->prof_every[stage] > 1 && call % (uint64_t)c->prof_every[stage] != 0) return;
         if (2 * (c->prof_rec.size() + 1) > c->prof_ev.size()) {  // more timed launches than events: add some
             const size_t old = c->prof_ev.size();
@@ -1026,6 +1029,73 @@ extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t
     // (from the store into the ring).  Each chunk is fetched as soon as it is in place.  Small chunks
     // first, so that the link starts early; the copy threads outrun the link only by a little, so the
     // chunks grow until a launch is a few per cent of its kernel.
+    char *land = bgl::tier_landing(t, gen);
+    if (land && plan.n_hit + plan.n_miss > 0) {
+        // Copy-engine transport: the packed rows go to device memory with plain copies on the tier's
+        // copy stream, as soon as they are packed and whatever the kernels of this cache are doing
+        // (the previous call's rows may still be on their way); kernels on side_stream then scatter
+        // them from there, after the hit gather.  The link carries one batch after the other.
+        const int64_t total = plan.n_hit + plan.n_miss;
+        const size_t rb = (size_t)c->row_bytes;
+        hipStream_t cs = bgl::tier_copy_stream(t);
+        rc = bgl::tier_copy_start(t);
+        if (rc != BGL_OK) return rc;
+        const char *ring_rows = bgl::tier_rows_device(t);
+        auto copy = [&](char *dst, const char *src, int64_t count) -> int {
+            Prof p(c, BGL_STAGE_LINK_COPY, cs, false);
+            BGL_HIP(hipMemcpyAsync(dst, src, (size_t)count * rb, hipMemcpyDefault, cs));
+            return BGL_OK;
+        };
+        // rows x0 <= x < x1 of the packed sequence: the tier's hits (staging rows), then its misses (ring)
+        auto copy_rows = [&](int64_t x0, int64_t x1) -> int {
+            if (x0 < plan.n_hit) {
+                const int64_t e = std::min(x1, plan.n_hit);
+                const int r1 = copy(land + (size_t)x0 * rb, plan.stage + (size_t)x0 * rb, e - x0);
+                if (r1 != BGL_OK) return r1;
+            }
+            const int64_t a = std::max(x0, plan.n_hit) - plan.n_hit, b = x1 - plan.n_hit;
+            if (b > a) {
+                const int64_t pos = (int64_t)((plan.ptail + (uint64_t)a) % (uint64_t)plan.ring);
+                const int64_t len1 = std::min(b - a, plan.ring - pos);  // up to the end of the ring
+                const int r1 = copy(land + (size_t)(plan.n_hit + a) * rb, ring_rows + (size_t)pos * rb, len1);
+                if (r1 != BGL_OK) return r1;
+                if (len1 < b - a) {
+                    const int r2 = copy(land + (size_t)(plan.n_hit + a + len1) * rb, ring_rows, b - a - len1);
+                    if (r2 != BGL_OK) return r2;
+                }
+            }
+            return BGL_OK;
+        };
+        int64_t chunk = ls != ms ? TIER_COPY_ROWS : TIER_FIRST_CHUNK_ROWS;
+        for (int64_t launched = 0; launched < total;) {
+            const int64_t ready = bgl::tier_copy_progress(t);
+            if (ready - launched >= chunk || (ready > launched && ready == total)) {
+                rc = copy_rows(launched, ready);
+                if (rc != BGL_OK) return rc;
+                launched = ready;
+                chunk = std::min<int64_t>(2 * chunk, TIER_COPY_ROWS);
+            } else {
+                __builtin_ia32_pause();
+            }
+        }
+        bgl::tier_copy_wait(t);
+        BGL_HIP(hipEventRecord(bgl::tier_copy_event(t), cs));
+        BGL_HIP(hipStreamWaitEvent(ss, bgl::tier_copy_event(t), 0));
+        auto scatter = [&](const char *src, const int32_t *rank, int64_t count) {
+            if (count == 0) return;
+            Prof p(c, BGL_STAGE_FETCH_MISS, ss);
+            const int blocks = (int)std::min<int64_t>(copy_blocks(count, q), 8192);  // device memory: the whole chip
+            dispatch_q(q, [&](auto Q) {
+                auto k = c->write_through ? k_fetch_rows<decltype(Q)::value, true>
+                                          : k_fetch_rows<decltype(Q)::value, false>;
+                launch(c, ss, k, dim3(blocks), dim3(COPY_THREADS), rank, (int64_t)0, count, 0ull, (int64_t)INT64_MAX,
+                       mpos, q, reinterpret_cast<const uint4 *>(src), reinterpret_cast<uint4 *>(out_rows), c->dev,
+                       reinterpret_cast<uint4 *>(c->buffer), c->capacity, par, n - plan.n_hit_gpu);
+            });
+        };
+        scatter(land, plan.hit_rank, plan.n_hit);
+        scatter(land + (size_t)plan.n_hit * rb, plan.miss_rank, plan.n_miss);
+    } else
     if (plan.n_hit + plan.n_miss > 0) {
         rc = bgl::tier_copy_start(t);
         if (rc != BGL_OK) return rc;

@@ -54,6 +54,12 @@ int tier_begin(bgl_host_tier *t, int64_t n, TierPlan *plan);
 int tier_copy_start(bgl_host_tier *t);
 int64_t tier_copy_progress(bgl_host_tier *t);
 void tier_copy_wait(bgl_host_tier *t);
+// Copy-engine transport (bgl_host_tier_set_copy_engine): the packed rows of the batch whose lists
+// have parity gen are copied into tier_landing(t, gen) (device memory, max_batch rows) on
+// tier_copy_stream(t) before kernels scatter them; null when the transport is off.
+char *tier_landing(bgl_host_tier *t, int gen);
+hipStream_t tier_copy_stream(bgl_host_tier *t);
+hipEvent_t tier_copy_event(bgl_host_tier *t);
 // Enqueue the first-in first-out update of the map on st and close the batch.
 int tier_enqueue_update(bgl_host_tier *t, const int32_t *ids, const int32_t *miss_pos, hipStream_t st);
 // Give up on the batch (after a failed tier_begin or launch).

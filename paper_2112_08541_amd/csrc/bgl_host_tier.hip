@@ -170,6 +170,10 @@ struct bgl_host_tier {
     char *stage = nullptr;   // page-locked: 2 x max_batch rows (one half per call parity): found rows, packed
     char *stage_dev = nullptr;
     char *pinned_dev = nullptr;
+    // copy-engine transport: device memory the packed rows land in (one per call parity), its stream and event
+    char *landing[2] = {nullptr, nullptr};
+    hipStream_t copy_stream = nullptr;
+    hipEvent_t copy_event = nullptr;
     // device: bookkeeping and per-batch lists
     int32_t *node_pos = nullptr, *slot_node = nullptr, *slot_pos = nullptr;
     int32_t *rank_pos = nullptr, *tile_miss = nullptr;
@@ -207,6 +211,9 @@ int32_t *tier_ids_device_if_passthrough(bgl_host_tier *t)
     return t->capacity == 0 ? reinterpret_cast<int32_t *>(t->pinned_dev + 64) : nullptr;
 }
 int32_t tier_row_bytes(const bgl_host_tier *t) { return t->row_bytes; }
+char *tier_landing(bgl_host_tier *t, int gen) { return t->landing[gen & 1]; }
+hipStream_t tier_copy_stream(bgl_host_tier *t) { return t->copy_stream; }
+hipEvent_t tier_copy_event(bgl_host_tier *t) { return t->copy_event; }
 int64_t tier_num_nodes(const bgl_host_tier *t) { return t->num_nodes; }
 
 int tier_enqueue_lookup(bgl_host_tier *t, const int32_t *ids, const int32_t *miss_pos,
@@ -470,11 +477,45 @@ extern "C" int bgl_host_tier_create(const void *store, int64_t num_nodes, int32_
     return BGL_OK;
 }
 
+extern "C" int bgl_host_tier_set_copy_engine(bgl_host_tier_t *t, int enable)
+{
+    if (!t) BGL_FAIL(BGL_EINVAL, "tier handle is null");
+    if (t->serving) BGL_FAIL(BGL_EINVAL, "host tier: a batch is being served");
+    BGL_HIP(hipDeviceSynchronize());  // earlier batches may still use what this call changes
+    if (!enable) {
+        for (int g = 0; g < 2; ++g) {
+            (void)hipFree(t->landing[g]);
+            t->landing[g] = nullptr;
+        }
+        return BGL_OK;
+    }
+    if (t->landing[0]) return BGL_OK;
+    if (!t->copy_stream) BGL_HIP(hipStreamCreateWithFlags(&t->copy_stream, hipStreamNonBlocking));
+    if (!t->copy_event) BGL_HIP(hipEventCreateWithFlags(&t->copy_event, hipEventDisableTiming));
+    const size_t bytes = (size_t)t->max_batch * (size_t)t->row_bytes;
+    for (int g = 0; g < 2; ++g) {
+        const hipError_t e = hipMalloc((void **)&t->landing[g], bytes);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            t->landing[g] = nullptr;
+            (void)hipFree(t->landing[0]);
+            t->landing[0] = nullptr;
+            bgl::set_error("hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+            return e == hipErrorOutOfMemory ? BGL_ENOMEM : BGL_EHIP;
+        }
+    }
+    return BGL_OK;
+}
+
 extern "C" int bgl_host_tier_destroy(bgl_host_tier_t *t)
 {
     if (!t) return BGL_OK;
     (void)hipDeviceSynchronize();  // kernels may still read the rows
     delete t->pool;
+    (void)hipFree(t->landing[0]);
+    (void)hipFree(t->landing[1]);
+    if (t->copy_event) (void)hipEventDestroy(t->copy_event);
+    if (t->copy_stream) (void)hipStreamDestroy(t->copy_stream);
     if (t->rows) (void)hipHostFree(t->rows);
     if (t->pinned) (void)hipHostFree(t->pinned);
     if (t->stage) (void)hipHostFree(t->stage);

@@ -104,6 +104,7 @@ def test_null_handles_are_rejected_without_touching_the_gpu(L):
     assert L.bgl_host_tier_destroy(None) == B.BGL_OK
     assert L.bgl_host_tier_export_state(None, None, None, None) == B.BGL_EINVAL
     assert L.bgl_host_tier_stats(None, None, None, None, None, None) == B.BGL_EINVAL
+    assert L.bgl_host_tier_set_copy_engine(None, 1) == B.BGL_EINVAL
     assert L.bgl_cache_lookup_gather_tiered(None, None, None, 0, None, None, None, None, None, None, None, 0) == B.BGL_EINVAL
     assert L.bgl_cache_create(4, 16, feats.ctypes.data, 0, C.byref(h)) == B.BGL_EINVAL
 

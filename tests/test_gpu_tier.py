@@ -34,7 +34,7 @@ def assert_tier_state_equal(tier, oc2, what):
 
 
 def run_tiered_stream(B, torch, feats, cap1, cap2, batches, write_through, threads, side=True,
-                      cache_has_store=False, early=None):
+                      cache_has_store=False, early=None, copy_engine=False):
     import oracle
     N, rb = feats.shape[0], feats.shape[1] * feats.itemsize
     store = np.ascontiguousarray(feats.view(np.uint8).reshape(N, rb))      # ordinary host memory
@@ -43,6 +43,8 @@ def run_tiered_stream(B, torch, feats, cap1, cap2, batches, write_through, threa
     pinned = torch.from_numpy(store).pin_memory() if cache_has_store else None
     gc = B.Cache(cap1, pinned, num_nodes=N, row_bytes=rb)
     tier = B.HostTier(store, cap2, max_n, threads)
+    if copy_engine:     # the packed rows cross the link as plain copies into device memory
+        tier.set_copy_engine(True)
     # capacity 0: the tier keeps nothing (every miss row just passes through its ring)
     oc1, oc2 = oracle.Cache(cap1, feats), (oracle.Cache(cap2, feats) if cap2 > 0 else None)
     if write_through:
@@ -114,14 +116,16 @@ def zipf_batches(rng, N, count, lo, hi, big=None):
 @pytest.mark.parametrize("dim,dtype", [(4, np.float32), (100, np.float32), (128, np.float32), (264, np.uint16)])
 @pytest.mark.parametrize("write_through,early", [(False, None), (True, None), (True, "own"), (True, "with_insert"),
                                                  (True, "alternate")])
-def test_tiered_random_streams(B, torch_mod, dim, dtype, write_through, early):
+@pytest.mark.parametrize("copy_engine", [False, True])
+def test_tiered_random_streams(B, torch_mod, dim, dtype, write_through, early, copy_engine):
     rng = np.random.default_rng(100 + dim)
     N = 20000
     feats = (rng.standard_normal((N, dim)).astype(np.float32) if dtype == np.float32
              else rng.integers(0, 2**16, (N, dim), dtype=np.uint16))
     # batch 5 has more misses than either level has slots
     batches = zipf_batches(rng, N, 14, 1, 2500, big=9000)
-    run_tiered_stream(B, torch_mod, feats, 1500, 4000, batches, write_through, threads=4, early=early)
+    run_tiered_stream(B, torch_mod, feats, 1500, 4000, batches, write_through, threads=4, early=early,
+                      copy_engine=copy_engine)
 
 
 @pytest.mark.parametrize("cap2", [0, 900_000])
@@ -132,7 +136,8 @@ def test_tiered_lookups_of_many_tiles(B, torch_mod, cap2):
     feats = rng.integers(0, 2**31, (N, 4), dtype=np.int32).view(np.float32)      # 16-byte rows, compared as bytes
     perm = rng.permutation(N).astype(np.int32)
     batches = [perm[:1_300_000], perm[600_000:2_000_001], perm[:1_200_000]]
-    run_tiered_stream(B, torch_mod, feats, 200_000, cap2, batches, True, threads=0, early="with_insert")
+    run_tiered_stream(B, torch_mod, feats, 200_000, cap2, batches, True, threads=0, early="with_insert",
+                      copy_engine=(cap2 == 0))
 
 
 @pytest.mark.parametrize("cap1,cap2,threads", [(64, 300, 1), (1, 1, 3), (500, 100, 2), (3000, 18000, 0),
@@ -146,14 +151,15 @@ def test_tiered_capacity_corners(B, torch_mod, cap1, cap2, threads):
     feats = rng.standard_normal((N, 100)).astype(np.float32)
     batches = zipf_batches(rng, N, 12, 200, 3000)
     _, tier = run_tiered_stream(B, torch_mod, feats, cap1, cap2, batches, True, threads, side=(threads != 2),
-                                early=("with_insert" if threads in (0, 3) else None))
+                                early=("with_insert" if threads in (0, 3) else None), copy_engine=(cap1 != 64))
     assert tier.stats()["threads"] == (threads or tier.stats()["threads"])
 
 
 @pytest.mark.parametrize("write_through,early", [(False, None), (True, None), (True, "own"), (True, "with_insert"),
                                                  (True, "alternate")])
 @pytest.mark.parametrize("side", [False, True])
-def test_staging_only_large_batches(B, torch_mod, write_through, side, early):
+@pytest.mark.parametrize("copy_engine", [False, True])
+def test_staging_only_large_batches(B, torch_mod, write_through, side, early, copy_engine):
     """Capacity 0 (every miss row passes through the ring) with batches of several chunks, hits
     that the same batch's insertions evict (small GPU cache), an empty batch, a repeat."""
     rng = np.random.default_rng(77)
@@ -163,7 +169,7 @@ def test_staging_only_large_batches(B, torch_mod, write_through, side, early):
     batches.insert(2, [])
     batches.insert(5, batches[4])     # immediate repeat: hits everywhere the cache kept them
     run_tiered_stream(B, torch_mod, feats, 50000, 0, batches, write_through, 0, side=side, cache_has_store=True,
-                      early=early)
+                      early=early, copy_engine=copy_engine)
 
 
 def test_tiered_uniform_ids_many_chunks(B, torch_mod):
@@ -173,6 +179,7 @@ def test_tiered_uniform_ids_many_chunks(B, torch_mod):
     feats = rng.integers(0, 2**32, (N, 25 * 4), dtype=np.uint32).view(np.float32)
     batches = [rng.permutation(N)[: int(rng.integers(60000, 90000))].tolist() for _ in range(5)]
     run_tiered_stream(B, torch_mod, feats, 40000, 120000, batches, True, threads=0)
+    run_tiered_stream(B, torch_mod, feats, 40000, 120000, batches, True, threads=0, early="with_insert", copy_engine=True)
 
 
 def test_tiered_argument_errors(B, torch_mod):
@@ -220,8 +227,8 @@ def test_tiered_argument_errors(B, torch_mod):
     assert (h1, h2) == (10, 0)
 
 
-@pytest.mark.parametrize("tier_fraction", [0.3, 0.0])
-def test_tiered_pipeline_as_benchmarked_matches_oracle(torch_mod, B, tier_fraction):
+@pytest.mark.parametrize("tier_fraction,copy_engine", [(0.3, True), (0.0, True), (0.0, False)])
+def test_tiered_pipeline_as_benchmarked_matches_oracle(torch_mod, B, tier_fraction, copy_engine):
     """The configurations `bench.py` times on the full-size mid workload (sampling ahead,
     tiered lookups on the chain stream, write-through GPU cache): a tier of 30 % of the nodes
     (`--two-level 0.3`) and the staging ring without a tier (the default miss path for
@@ -243,6 +250,7 @@ def test_tiered_pipeline_as_benchmarked_matches_oracle(torch_mod, B, tier_fracti
     tier_rows = int(tier_fraction * cfg.num_nodes)
     pipe = MinibatchPipeline(graph, cache, cfg.batch, cfg.fanouts, rb, write_through=True, tier=None)
     tier = B.HostTier(store, tier_rows, pipe.cap, 0)
+    tier.set_copy_engine(copy_engine)
     pipe.tier = tier
     seeds_dev = torch.from_numpy(w.seed_batches).cuda()
     got = {}
@@ -287,14 +295,15 @@ def test_tiered_random_cases_property(B, torch_mod):
     @settings(max_examples=25, deadline=None, derandomize=True, suppress_health_check=list(HealthCheck))
     @given(st.integers(50, 5000), st.integers(1, 65), st.integers(1, 3000), st.sampled_from([0, 0, 1, 17, 300, 4000]),
            st.lists(st.integers(0, 2500), min_size=1, max_size=8), st.booleans(), st.booleans(),
-           st.sampled_from([None, "own", "with_insert", "alternate"]), st.integers(1, 5), st.integers(0, 2**31))
-    def run(n_nodes, row_chunks, cap1, cap2, sizes, write_through, side, early, threads, seed):
+           st.sampled_from([None, "own", "with_insert", "alternate"]), st.integers(1, 5), st.integers(0, 2**31),
+           st.booleans())
+    def run(n_nodes, row_chunks, cap1, cap2, sizes, write_through, side, early, threads, seed, copy_engine):
         rng = np.random.default_rng(seed)
         feats = rng.integers(0, 2**32, (n_nodes, row_chunks * 4), dtype=np.uint32)
         batches = [rng.permutation(n_nodes)[: min(k, n_nodes)].tolist() for k in sizes]
         if early is not None and not write_through:
             early = None                      # the library refuses early lookups there (tested elsewhere)
         run_tiered_stream(B, torch_mod, feats, cap1, cap2, batches, write_through, threads, side=side,
-                          cache_has_store=(cap2 == 0), early=early)
+                          cache_has_store=(cap2 == 0), early=early, copy_engine=copy_engine)
 
     run()
