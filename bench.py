@@ -412,7 +412,10 @@ def main():
         tier = B.HostTier(store, tier_rows, pipe.cap, args.tier_threads)
         tier.set_copy_engine(args.miss_path != "staged_kernel")
         c2 = B.Cache(cfg.cache_rows, None, num_nodes=cfg.num_nodes, row_bytes=rb)
-        pipe2 = MinibatchPipeline(graph, c2, cfg.batch, cfg.fanouts, rb, write_through=True, tier=tier)
+        pipe2 = pipe                 # the same streams and workspaces (hardware queues are few)
+        pipe2.write_through = True
+        pipe2.tier = tier
+        pipe2.set_cache(c2)
         torch.cuda.synchronize()
         q0 = time.perf_counter()
         n2, h2 = pipe2.run(seeds_dev, w.rng_seeds, steps2)

@@ -70,7 +70,8 @@ struct bgl_cache {
     int64_t mpos_cap[2];
     uint64_t lookup_calls;
     uint64_t insert_calls;  // FIFO updates enqueued so far (selects the live copy of tail)
-    hipStream_t own_side;
+    hipStream_t own_side;   // the miss fetch's stream when the caller names none; created on first use
+                            // (a process has few hardware queues: a stream that is never used should not take one)
     // Ordering between streams.  ev_listed: lists and hit rows of the last lookup are complete
     // (recorded on that lookup's main stream); ev_miss: its miss rows are complete (recorded on
     // the stream the fetch ran on); ev_map: the last FIFO update is complete (recorded on the
@@ -719,8 +720,7 @@ extern "C" int bgl_cache_create(int64_t capacity_rows, int32_t row_bytes,
     TRY_ALLOC(c->slot_to_entry, (size_t)capacity_rows * sizeof(uint32_t));
     TRY_ALLOC(c->dev, sizeof(CacheDev));
 #undef TRY_ALLOC
-    if (hipStreamCreateWithFlags(&c->own_side, hipStreamNonBlocking) != hipSuccess ||
-        hipEventCreateWithFlags(&c->ev_listed, hipEventDisableTiming) != hipSuccess ||
+    if (hipEventCreateWithFlags(&c->ev_listed, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&c->ev_miss, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&c->ev_map, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&c->ev_ids, hipEventDisableTiming) != hipSuccess) {
@@ -876,6 +876,18 @@ int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, in
     return BGL_OK;
 }
 
+// The stream of the miss fetch: the caller's, or one of the cache's own.
+int side_stream_of(bgl_cache *c, void *side_stream, hipStream_t *out)
+{
+    if (side_stream) {
+        *out = static_cast<hipStream_t>(side_stream);
+        return BGL_OK;
+    }
+    if (!c->own_side) BGL_HIP(hipStreamCreateWithFlags(&c->own_side, hipStreamNonBlocking));
+    *out = c->own_side;
+    return BGL_OK;
+}
+
 int check_lookup_args(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, int32_t *out_slot,
                       int32_t *miss_pos)
 {
@@ -903,7 +915,9 @@ int lookup_gather_impl(bgl_cache_t *c, const int32_t *ids, int64_t n, void *out_
         BGL_FAIL(BGL_EINVAL, "an early lookup needs write-through mode");
     if (!c->features) BGL_FAIL(BGL_EINVAL, "the cache has no backing store: use bgl_cache_lookup_gather_tiered");
     hipStream_t ms = static_cast<hipStream_t>(main_stream);
-    hipStream_t ss = side_stream ? static_cast<hipStream_t>(side_stream) : c->own_side;
+    hipStream_t ss = nullptr;
+    rc = side_stream_of(c, side_stream, &ss);
+    if (rc != BGL_OK) return rc;
     // the hit count goes straight into the caller's page-locked word (no copy launch)
     int64_t *n_hit_dev = nullptr;
     if (n_hit_host) {
@@ -982,7 +996,9 @@ extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t
     if (n > bgl::tier_max_batch(t))
         BGL_FAIL(BGL_ECAPACITY, "n = %lld exceeds the tier's max_batch_rows", (long long)n);
     hipStream_t ms = static_cast<hipStream_t>(main_stream);
-    hipStream_t ss = side_stream ? static_cast<hipStream_t>(side_stream) : c->own_side;
+    hipStream_t ss = nullptr;
+    rc = side_stream_of(c, side_stream, &ss);
+    if (rc != BGL_OK) return rc;
     const int q = c->row_bytes / 16;
     // Early lookup: only in write-through mode (otherwise the previous call's row copy still reads
     // the caller's miss_pos).

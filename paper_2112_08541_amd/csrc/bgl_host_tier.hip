@@ -172,7 +172,7 @@ struct bgl_host_tier {
     char *pinned_dev = nullptr;
     // copy-engine transport: device memory the packed rows land in (one per call parity), its stream and event
     char *landing[2] = {nullptr, nullptr};
-    hipStream_t copy_stream = nullptr;
+    hipStream_t copy_stream = nullptr;  // shared by all tiers of the process (not owned)
     hipEvent_t copy_event = nullptr;
     // device: bookkeeping and per-batch lists
     int32_t *node_pos = nullptr, *slot_node = nullptr, *slot_pos = nullptr;
@@ -490,7 +490,13 @@ extern "C" int bgl_host_tier_set_copy_engine(bgl_host_tier_t *t, int enable)
         return BGL_OK;
     }
     if (t->landing[0]) return BGL_OK;
-    if (!t->copy_stream) BGL_HIP(hipStreamCreateWithFlags(&t->copy_stream, hipStreamNonBlocking));
+    if (!t->copy_stream) {
+        // One copy stream per process, shared by all tiers and never destroyed: a process has only a
+        // few hardware queues, and streams that map onto the same one run one after the other.
+        static hipStream_t shared_copy_stream = nullptr;
+        if (!shared_copy_stream) BGL_HIP(hipStreamCreateWithFlags(&shared_copy_stream, hipStreamNonBlocking));
+        t->copy_stream = shared_copy_stream;
+    }
     if (!t->copy_event) BGL_HIP(hipEventCreateWithFlags(&t->copy_event, hipEventDisableTiming));
     const size_t bytes = (size_t)t->max_batch * (size_t)t->row_bytes;
     for (int g = 0; g < 2; ++g) {
@@ -515,7 +521,6 @@ extern "C" int bgl_host_tier_destroy(bgl_host_tier_t *t)
     (void)hipFree(t->landing[0]);
     (void)hipFree(t->landing[1]);
     if (t->copy_event) (void)hipEventDestroy(t->copy_event);
-    if (t->copy_stream) (void)hipStreamDestroy(t->copy_stream);
     if (t->rows) (void)hipHostFree(t->rows);
     if (t->pinned) (void)hipHostFree(t->pinned);
     if (t->stage) (void)hipHostFree(t->stage);

@@ -55,7 +55,7 @@ class MinibatchPipeline:
         # own: the next batch's lookup then follows the map update at once instead of queueing behind
         # the sampling of the batch after it, and the host has the missed ids half a millisecond sooner
         # (all rows are then packed before the link is free, and one launch fetches them).
-        self.samp_stream = torch.cuda.Stream()
+        self.samp_stream = None                   # created when first needed (hardware queues are few)
         self.tier = tier                          # second cache level in host memory (Sec. 3.2.3), or None
         self.last_ids, self.last_n = None, 0      # input nodes of the most recent batch
         self.set_cache(cache)
@@ -77,7 +77,11 @@ class MinibatchPipeline:
         Returns (n_input per batch, n_hit per batch)."""
         nb = seeds_dev.shape[0]
         K, cache, chain, work = self.K, self.cache, self.chain, self.work
-        samp = self.samp_stream if (self.tier is not None and self.write_through and self.early_ok) else work
+        samp = work
+        if self.tier is not None and self.write_through and self.early_ok:
+            if self.samp_stream is None:
+                self.samp_stream = torch.cuda.Stream()
+            samp = self.samp_stream
         n_hits = torch.zeros(max(steps, 1), dtype=torch.int64).pin_memory()
         n_list = []
         self.tier_hits = []
