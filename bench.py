@@ -40,13 +40,14 @@ def parse_args():
                     help="leave the per-kernel HIP events out of the timed region")
     ap.add_argument("--all-stage-timers", action="store_true",
                     help="bracket every cache kernel with events (default: hit gather and miss fetch only)")
-    ap.add_argument("--miss-path", choices=("auto", "zero_copy", "staged", "staged_kernel"), default="auto",
+    ap.add_argument("--miss-path", choices=("auto", "trial", "zero_copy", "staged", "staged_kernel"), default="auto",
                     help="how miss rows cross the host link: kernels read the page-locked table in place "
                          "(zero_copy), or host threads pack the rows into a page-locked ring (no partial 128-byte "
                          "lines on the link) from where plain copies move them into device memory and kernels "
                          "scatter them (staged), or from where the kernels read them over the link themselves "
-                         "(staged_kernel); auto = the faster of zero_copy and staged in a warm-up trial when "
-                         "row_bytes is not a multiple of 128 and batches are large")
+                         "(staged_kernel); auto = staged when row_bytes is not a multiple of 128, batches are large "
+                         "and the box has 8 or more host threads for the packing, else zero_copy; trial = the "
+                         "faster of zero_copy and staged in the warm-up")
     ap.add_argument("--no-write-through", action="store_true",
                     help="FIFO update copies the rows after the fetch instead of the fetch filling the cache buffer")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -207,39 +208,41 @@ def main():
     pipe = MinibatchPipeline(graph, scratch, cfg.batch, cfg.fanouts, cfg.row_bytes,
                              write_through=not args.no_write_through)
     # Miss path.  Staging pays when rows are not multiples of 128 bytes and batches are large,
-    # provided the box has the host cores for the copy threads: "auto" tries both in the warm-up
-    # (each from an empty scratch cache, untimed for the benchmark) and keeps the faster one.
+    # provided the box has the host cores for the copy threads (with 3 of them zero-copy was the
+    # faster path): "auto" decides by that rule, "trial" times both in the warm-up (each from an
+    # empty scratch cache, untimed for the benchmark) and keeps the faster one.
     miss_path = args.miss_path
+    host_threads = args.tier_threads or max(1, min(os.cpu_count() or 2, 16) - 1)
     eligible = cfg.row_bytes % 128 != 0 and pipe.cap >= 65536 and feat_dev is None
+    if miss_path == "auto":
+        miss_path = "staged" if (eligible and host_threads >= 8) else "zero_copy"
     stage_ring = None
     trial = {}
-    if miss_path in ("staged", "staged_kernel") or (miss_path == "auto" and eligible):
+    if miss_path in ("staged", "staged_kernel") or (miss_path == "trial" and eligible):
         # capacity 0: nothing is kept in host memory, every miss row passes through the ring
         stage_ring = B.HostTier(w.features.view(np.uint8).reshape(cfg.num_nodes, cfg.row_bytes), 0, pipe.cap,
                                 args.tier_threads)
         stage_ring.set_copy_engine(miss_path != "staged_kernel")
-    if miss_path == "auto":
+    if miss_path == "trial":
         miss_path = "zero_copy"
-        if stage_ring is not None and args.warmup > 0:
+        if stage_ring is not None:
             for name, tier in (("zero_copy", None), ("staged", stage_ring)):
                 pipe.tier = tier
-                pipe.run(seeds_dev, w.rng_seeds, min(3, args.warmup))
+                pipe.run(seeds_dev, w.rng_seeds, 3)
                 scratch.close()
                 scratch = new_cache()
                 pipe.set_cache(scratch)
                 torch.cuda.synchronize()
                 q0 = time.perf_counter()
-                pipe.run(seeds_dev, w.rng_seeds, args.warmup)
-                trial[name] = 1e3 * (time.perf_counter() - q0) / args.warmup
+                pipe.run(seeds_dev, w.rng_seeds, max(args.warmup, 10))
+                trial[name] = 1e3 * (time.perf_counter() - q0) / max(args.warmup, 10)
                 scratch.close()
                 scratch = new_cache()
                 pipe.set_cache(scratch)
             miss_path = min(trial, key=trial.get)
-        elif stage_ring is not None:
-            miss_path = "staged"
     staged = miss_path in ("staged", "staged_kernel")
     pipe.tier = stage_ring if staged else None
-    if args.warmup > 0 and not trial:
+    if args.warmup > 0:
         pipe.run(seeds_dev, w.rng_seeds, args.warmup)
     scratch.close()
 

@@ -15,8 +15,11 @@ over the host link, so the loop is built to keep the link busy:
                  i+1's miss rows while fetch(i) is still on the link
   sampling stream  only with such a ring or tier: sample(i+2) runs there, so that
                  lookup(i+1) need not queue behind it and the host gets the missed ids
-                 at once; every row is then packed before the link is free, and one
-                 launch fetches the batch
+                 at once; every row is then packed before the link is free
+  (copy stream)  the tier's own, when its copy-engine transport is on: the packed rows of
+                 batch i+1 are copied into device memory right behind those of batch i,
+                 and the "miss fetch" on the chain stream is the short kernel that
+                 scatters the landed rows
 
 The cache is put in write-through mode (every lookup here is followed by the
 insert of all its misses), which makes the FIFO update a map update that needs no
