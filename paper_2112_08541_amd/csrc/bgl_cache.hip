@@ -269,8 +269,6 @@ constexpr int FETCH_BLOCKS = 64;
 // Tiered lookup: rows the host threads copy per chunk before that chunk's fetch is launched.
 constexpr int64_t TIER_CHUNK_ROWS = 49152;
 constexpr int64_t TIER_FIRST_CHUNK_ROWS = 3072;
-// The same with the copy-engine transport: rows per copy (a copy costs the link a few microseconds of gap).
-constexpr int64_t TIER_COPY_ROWS = 98304;
 
 // out[i] = buffer[out_slot[i]] for every hit i (taken from the hit list, so the
 // work is proportional to the hits).  Consecutive lanes take consecutive
@@ -1082,21 +1080,35 @@ extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t
             }
             return BGL_OK;
         };
-        int64_t chunk = ls != ms ? TIER_COPY_ROWS : TIER_FIRST_CHUNK_ROWS;
+        // A copy costs the link a few microseconds whatever its size, so while earlier copies (the
+        // previous call's, or this call's) still occupy the link the packed rows pile up for one larger
+        // copy; when the link is free a chunk goes at once.
+        int64_t chunk = ls != ms ? TIER_CHUNK_ROWS : TIER_FIRST_CHUNK_ROWS;
+        bool link_busy = bgl::tier_copy_event_recorded(t);
         for (int64_t launched = 0; launched < total;) {
             const int64_t ready = bgl::tier_copy_progress(t);
-            if (ready - launched >= chunk || (ready > launched && ready == total)) {
+            bool go = ready > launched && ready == total;
+            if (!go && ready - launched >= chunk) {
+                if (link_busy) {
+                    link_busy = hipEventQuery(bgl::tier_copy_event(t)) != hipSuccess;
+                    (void)hipGetLastError();  // "not ready" is no error
+                }
+                go = !link_busy;
+            }
+            if (go) {
                 rc = copy_rows(launched, ready);
                 if (rc != BGL_OK) return rc;
+                BGL_HIP(hipEventRecord(bgl::tier_copy_event(t), cs));
+                bgl::tier_set_copy_event_recorded(t);
+                link_busy = true;
                 launched = ready;
-                chunk = std::min<int64_t>(2 * chunk, TIER_COPY_ROWS);
+                chunk = std::min<int64_t>(2 * chunk, TIER_CHUNK_ROWS);
             } else {
                 __builtin_ia32_pause();
             }
         }
         bgl::tier_copy_wait(t);
-        BGL_HIP(hipEventRecord(bgl::tier_copy_event(t), cs));
-        BGL_HIP(hipStreamWaitEvent(ss, bgl::tier_copy_event(t), 0));
+        BGL_HIP(hipStreamWaitEvent(ss, bgl::tier_copy_event(t), 0));  // (recorded behind the last copy)
         auto scatter = [&](const char *src, const int32_t *rank, int64_t count) {
             if (count == 0) return;
             Prof p(c, BGL_STAGE_FETCH_MISS, ss);

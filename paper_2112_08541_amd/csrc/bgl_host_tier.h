@@ -60,6 +60,9 @@ void tier_copy_wait(bgl_host_tier *t);
 char *tier_landing(bgl_host_tier *t, int gen);
 hipStream_t tier_copy_stream(bgl_host_tier *t);
 hipEvent_t tier_copy_event(bgl_host_tier *t);
+// whether that event has ever been recorded (the caller records it behind every copy it enqueues)
+bool tier_copy_event_recorded(const bgl_host_tier *t);
+void tier_set_copy_event_recorded(bgl_host_tier *t);
 // Enqueue the first-in first-out update of the map on st and close the batch.
 int tier_enqueue_update(bgl_host_tier *t, const int32_t *ids, const int32_t *miss_pos, hipStream_t st);
 // Give up on the batch (after a failed tier_begin or launch).

@@ -174,6 +174,7 @@ struct bgl_host_tier {
     char *landing[2] = {nullptr, nullptr};
     hipStream_t copy_stream = nullptr;  // shared by all tiers of the process (not owned)
     hipEvent_t copy_event = nullptr;
+    bool copy_event_recorded = false;
     // device: bookkeeping and per-batch lists
     int32_t *node_pos = nullptr, *slot_node = nullptr, *slot_pos = nullptr;
     int32_t *rank_pos = nullptr, *tile_miss = nullptr;
@@ -214,6 +215,8 @@ int32_t tier_row_bytes(const bgl_host_tier *t) { return t->row_bytes; }
 char *tier_landing(bgl_host_tier *t, int gen) { return t->landing[gen & 1]; }
 hipStream_t tier_copy_stream(bgl_host_tier *t) { return t->copy_stream; }
 hipEvent_t tier_copy_event(bgl_host_tier *t) { return t->copy_event; }
+bool tier_copy_event_recorded(const bgl_host_tier *t) { return t->copy_event_recorded; }
+void tier_set_copy_event_recorded(bgl_host_tier *t) { t->copy_event_recorded = true; }
 int64_t tier_num_nodes(const bgl_host_tier *t) { return t->num_nodes; }
 
 int tier_enqueue_lookup(bgl_host_tier *t, const int32_t *ids, const int32_t *miss_pos,
