@@ -45,7 +45,7 @@ def parse_args():
                          "(zero_copy), or host threads pack the rows into a page-locked ring (no partial 128-byte "
                          "lines on the link) from where plain copies move them into device memory and kernels "
                          "scatter them (staged), or from where the kernels read them over the link themselves "
-                         "(staged_kernel); auto = staged when row_bytes is not a multiple of 128, batches are large "
+                         "(staged_kernel); auto = staged when batches are large (65,536 input nodes or more) "
                          "and the box has 8 or more host threads for the packing, else zero_copy; trial = the "
                          "faster of zero_copy and staged in the warm-up")
     ap.add_argument("--no-write-through", action="store_true",
@@ -207,13 +207,14 @@ def main():
     scratch = new_cache()
     pipe = MinibatchPipeline(graph, scratch, cfg.batch, cfg.fanouts, cfg.row_bytes,
                              write_through=not args.no_write_through)
-    # Miss path.  Staging pays when rows are not multiples of 128 bytes and batches are large,
-    # provided the box has the host cores for the copy threads (with 3 of them zero-copy was the
-    # faster path): "auto" decides by that rule, "trial" times both in the warm-up (each from an
-    # empty scratch cache, untimed for the benchmark) and keeps the faster one.
+    # Miss path.  Staging pays when batches are large (a quarter more for rows that are not multiples
+    # of 128 bytes, a few per cent otherwise: the link never waits for the hit gather), provided the
+    # box has the host cores for the copy threads (with 3 of them zero-copy was the faster path):
+    # "auto" decides by that rule, "trial" times both in the warm-up (each from an empty scratch
+    # cache, untimed for the benchmark) and keeps the faster one.
     miss_path = args.miss_path
     host_threads = args.tier_threads or max(1, min(os.cpu_count() or 2, 16) - 1)
-    eligible = cfg.row_bytes % 128 != 0 and pipe.cap >= 65536 and feat_dev is None
+    eligible = pipe.cap >= 65536 and feat_dev is None
     if miss_path == "auto":
         miss_path = "staged" if (eligible and host_threads >= 8) else "zero_copy"
     stage_ring = None
