@@ -431,15 +431,20 @@ def test_overlapped_pipeline_as_benchmarked_matches_oracle(torch_mod, B, write_t
     run_overlapped_against_oracle(torch_mod, B, w, 8, write_through)
 
 
-def run_overlapped_against_oracle(torch_mod, B, w, steps, write_through=True):
+def run_overlapped_against_oracle(torch_mod, B, w, steps, write_through=True, staged=False):
     """MinibatchPipeline as bench.py sets it up for the workload's configuration (graph placement
-    included); every batch's sampled blocks, lists and rows, and the final cache state."""
+    included; staged: miss rows packed by host threads into a page-locked ring and moved by the copy
+    engine, bench.py's default for large batches); every batch's sampled blocks, lists and rows, and
+    the final cache state."""
     from paper_2112_08541_amd.pipeline import MinibatchPipeline
     cfg = w.cfg
     placement = B.BGL_HOST_PINNED if cfg.graph_placement == "host_pinned" else B.BGL_DEVICE
     graph = B.Graph(w.row_ptr, w.col, placement)
     cache = B.Cache(cfg.cache_rows, w.features.ctypes.data, num_nodes=cfg.num_nodes, row_bytes=cfg.row_bytes)
     pipe = MinibatchPipeline(graph, cache, cfg.batch, cfg.fanouts, cfg.row_bytes, write_through=write_through)
+    if staged:
+        pipe.tier = B.HostTier(w.features.view(np.uint8).reshape(cfg.num_nodes, cfg.row_bytes), 0, pipe.cap, 0)
+        pipe.tier.set_copy_engine(True)
     seeds_dev = torch_mod.from_numpy(w.seed_batches).cuda()
     got = {}
 
@@ -541,7 +546,8 @@ def run_full(cfg, n_batches, check_every, overlapped_steps, torch_mod, B):
         run_config(cfg, n_batches, device_n_miss=True, check_every=check_every, w=w)
     except MemoryError as e:  # the box cannot page-lock this much host memory
         pytest.skip(f"not enough page-locked host memory for {cfg.name}: {e}")
-    run_overlapped_against_oracle(torch_mod, B, w, overlapped_steps)
+    run_overlapped_against_oracle(torch_mod, B, w, overlapped_steps, staged=True)    # bench.py's default for it
+    run_overlapped_against_oracle(torch_mod, B, w, max(2, overlapped_steps // 2))     # and with --miss-path zero_copy
 
 
 @pytest.mark.skipif(SKIP_FULL, reason="BGL_SKIP_FULL_SIZE is set")
