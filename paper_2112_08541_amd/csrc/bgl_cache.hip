@@ -981,6 +981,159 @@ extern "C" int bgl_cache_lookup_gather_early(bgl_cache_t *c, const int32_t *ids,
                               lookup_stream, static_cast<hipStream_t>(lookup_stream) != static_cast<hipStream_t>(main_stream));
 }
 
+namespace {
+
+// The packed rows of one tiered lookup on their way to out_rows (and, in write-through mode, to the
+// cache buffer).  Host threads pack them as one sequence: first the rows the tier holds (into its
+// staging rows, in list order), then the others (from the store into consecutive ring positions).
+struct TieredRows {
+    bgl_cache *c;
+    bgl_host_tier *t;
+    const bgl::TierPlan *plan;
+    hipStream_t ss;        // the stream of the kernels that write the rows to their places
+    const int32_t *mpos;   // this call's miss positions (the caller's list, or the library's copy)
+    void *out_rows;
+    int64_t n;
+    int par;               // which copy of the cache's tail the kernels read
+    bool early;            // the lookup ran early: the host is ahead of the link
+
+    // out[mpos[rank[l]]] = base[(first + l) mod ring] for l0 <= l < l0 + count
+    void launch_rows(const char *base, unsigned long long first, int64_t ring, const int32_t *rank, int64_t l0,
+                     int64_t count, int max_blocks) const
+    {
+        if (count == 0) return;
+        const int q = c->row_bytes / 16;
+        Prof p(c, BGL_STAGE_FETCH_MISS, ss);
+        const int blocks = (int)std::min<int64_t>(copy_blocks(count, q), max_blocks);
+        dispatch_q(q, [&](auto Q) {
+            auto k = c->write_through ? k_fetch_rows<decltype(Q)::value, true>
+                                      : k_fetch_rows<decltype(Q)::value, false>;
+            launch(c, ss, k, dim3(blocks), dim3(COPY_THREADS), rank, l0, count, first, ring, mpos, q,
+                   reinterpret_cast<const uint4 *>(base), reinterpret_cast<uint4 *>(out_rows), c->dev,
+                   reinterpret_cast<uint4 *>(c->buffer), c->capacity, par, n - plan->n_hit_gpu);
+        });
+    }
+};
+
+// Copy-engine transport: the packed rows go to device memory (`land`) with plain copies on the tier's
+// copy stream, as soon as they are packed and whatever the kernels of this cache are doing (the
+// previous call's rows may still be on their way); kernels then scatter them from there, after the
+// hit gather.  The link carries one batch after the other.
+int rows_by_copy_engine(const TieredRows &r, char *land)
+{
+    bgl_cache *c = r.c;
+    bgl_host_tier *t = r.t;
+    const bgl::TierPlan &plan = *r.plan;
+    const int64_t total = plan.n_hit + plan.n_miss;
+    const size_t rb = (size_t)c->row_bytes;
+    hipStream_t cs = bgl::tier_copy_stream(t);
+    const char *ring_rows = bgl::tier_rows_device(t);
+    auto copy = [&](char *dst, const char *src, int64_t count) -> int {
+        Prof p(c, BGL_STAGE_LINK_COPY, cs, false);
+        BGL_HIP(hipMemcpyAsync(dst, src, (size_t)count * rb, hipMemcpyDefault, cs));
+        return BGL_OK;
+    };
+    // rows x0 <= x < x1 of the packed sequence: the tier's hits (staging rows), then its misses (ring)
+    auto copy_rows = [&](int64_t x0, int64_t x1) -> int {
+        if (x0 < plan.n_hit) {
+            const int64_t e = std::min(x1, plan.n_hit);
+            const int r1 = copy(land + (size_t)x0 * rb, plan.stage + (size_t)x0 * rb, e - x0);
+            if (r1 != BGL_OK) return r1;
+        }
+        const int64_t a = std::max(x0, plan.n_hit) - plan.n_hit, b = x1 - plan.n_hit;
+        if (b > a) {
+            const int64_t pos = (int64_t)((plan.ptail + (uint64_t)a) % (uint64_t)plan.ring);
+            const int64_t len1 = std::min(b - a, plan.ring - pos);  // up to the end of the ring
+            const int r1 = copy(land + (size_t)(plan.n_hit + a) * rb, ring_rows + (size_t)pos * rb, len1);
+            if (r1 != BGL_OK) return r1;
+            if (len1 < b - a) {
+                const int r2 = copy(land + (size_t)(plan.n_hit + a + len1) * rb, ring_rows, b - a - len1);
+                if (r2 != BGL_OK) return r2;
+            }
+        }
+        return BGL_OK;
+    };
+    // A copy costs the link a few microseconds whatever its size, so while earlier copies (the
+    // previous call's, or this call's) still occupy the link the packed rows pile up for one larger
+    // copy; when the link is free a chunk goes at once.
+    int64_t chunk = r.early ? TIER_CHUNK_ROWS : TIER_FIRST_CHUNK_ROWS;
+    bool link_busy = bgl::tier_copy_event_recorded(t);
+    for (int64_t launched = 0; launched < total;) {
+        const int64_t ready = bgl::tier_copy_progress(t);
+        bool go = ready > launched && ready == total;
+        if (!go && ready - launched >= chunk) {
+            if (link_busy) {
+                link_busy = hipEventQuery(bgl::tier_copy_event(t)) != hipSuccess;
+                (void)hipGetLastError();  // "not ready" is no error
+            }
+            go = !link_busy;
+        }
+        if (go) {
+            const int rc = copy_rows(launched, ready);
+            if (rc != BGL_OK) return rc;
+            BGL_HIP(hipEventRecord(bgl::tier_copy_event(t), cs));
+            bgl::tier_set_copy_event_recorded(t);
+            link_busy = true;
+            launched = ready;
+            chunk = std::min<int64_t>(2 * chunk, TIER_CHUNK_ROWS);
+        } else {
+            __builtin_ia32_pause();
+        }
+    }
+    bgl::tier_copy_wait(t);
+    BGL_HIP(hipStreamWaitEvent(r.ss, bgl::tier_copy_event(t), 0));  // (recorded behind the last copy)
+    constexpr int whole_chip = 8192;  // the rows are in device memory now
+    r.launch_rows(land, 0ull, (int64_t)INT64_MAX, plan.hit_rank, 0, plan.n_hit, whole_chip);
+    r.launch_rows(land + (size_t)plan.n_hit * rb, 0ull, (int64_t)INT64_MAX, plan.miss_rank, 0, plan.n_miss, whole_chip);
+    return BGL_OK;
+}
+
+// Kernel transport: the kernels read the page-locked rows over the host link themselves, chunk by
+// chunk as the rows are packed.  Small chunks first, so that the link starts early; the copy threads
+// outrun the link only by a little, so the chunks grow until a launch is a few per cent of its kernel.
+int rows_by_kernels(const TieredRows &r)
+{
+    bgl_cache *c = r.c;
+    bgl_host_tier *t = r.t;
+    const bgl::TierPlan &plan = *r.plan;
+    const int64_t total = plan.n_hit + plan.n_miss;
+    const char *ring_rows = bgl::tier_rows_device(t);
+    // (an early lookup is ahead of the link anyway: full chunks from the start)
+    int64_t chunk = r.early ? TIER_CHUNK_ROWS : TIER_FIRST_CHUNK_ROWS;
+    bool gather_done = false;
+    for (int64_t launched = 0; launched < total;) {
+        const int64_t ready = bgl::tier_copy_progress(t);
+        // a chunk does not straddle the two kinds of rows
+        const int64_t limit = launched < plan.n_hit ? std::min(ready, plan.n_hit) : ready;
+        bool go = limit > launched && (limit == plan.n_hit || limit == total);
+        if (!go && limit - launched >= chunk) {
+            // An early lookup's fetch cannot start before its hit gather has run, which waits for
+            // the previous call's fetch: until then the packed rows pile up for one larger launch.
+            if (r.early && !gather_done) {
+                gather_done = hipEventQuery(c->ev_listed) == hipSuccess;
+                (void)hipGetLastError();  // "not ready" is no error
+            }
+            go = gather_done || !r.early;
+        }
+        if (go) {
+            if (launched < plan.n_hit)
+                r.launch_rows(plan.stage, 0ull, (int64_t)INT64_MAX, plan.hit_rank, launched, limit - launched,
+                              FETCH_BLOCKS);
+            else
+                r.launch_rows(ring_rows, (unsigned long long)plan.ptail, plan.ring, plan.miss_rank,
+                              launched - plan.n_hit, limit - launched, FETCH_BLOCKS);
+            launched = limit;
+            chunk = std::min<int64_t>(2 * chunk, TIER_CHUNK_ROWS);
+        } else {
+            __builtin_ia32_pause();
+        }
+    }
+    bgl::tier_copy_wait(t);
+    return BGL_OK;
+}
+
+}  // namespace
+
 extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t, const int32_t *ids,
                                               int64_t n, void *out_rows, int32_t *out_slot,
                                               int32_t *miss_pos, int64_t *n_hit, void *main_stream,
@@ -997,7 +1150,6 @@ extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t
     hipStream_t ss = nullptr;
     rc = side_stream_of(c, side_stream, &ss);
     if (rc != BGL_OK) return rc;
-    const int q = c->row_bytes / 16;
     // Early lookup: only in write-through mode (otherwise the previous call's row copy still reads
     // the caller's miss_pos).
     hipStream_t ls = ms;
@@ -1023,142 +1175,13 @@ extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t
     // (Waking the copy threads earlier, to have them spin until the ids arrive, was measured:
     // slower, the spinning threads get in the way of the wait for the lookup.)
     if (ss != ms) BGL_HIP(hipStreamWaitEvent(ss, c->ev_listed, 0));
-    const int par = (int)(c->insert_calls & 1);
-    const uint4 *rows = reinterpret_cast<const uint4 *>(bgl::tier_rows_device(t));
-    // out[miss_pos[rank[l]]] = base[(first + l) mod ring] for l0 <= l < l0 + count: packed rows
-    auto fetch = [&](const uint4 *base, unsigned long long first, int64_t ring, const int32_t *rank, int64_t l0,
-                     int64_t count) {
-        if (count == 0) return;
-        Prof p(c, BGL_STAGE_FETCH_MISS, ss);
-        const int blocks = (int)std::min<int64_t>(copy_blocks(count, q), FETCH_BLOCKS);
-        dispatch_q(q, [&](auto Q) {
-            auto k = c->write_through ? k_fetch_rows<decltype(Q)::value, true>
-                                      : k_fetch_rows<decltype(Q)::value, false>;
-            launch(c, ss, k, dim3(blocks), dim3(COPY_THREADS), rank, l0, count, first, ring, mpos, q, base,
-                   reinterpret_cast<uint4 *>(out_rows), c->dev, reinterpret_cast<uint4 *>(c->buffer), c->capacity,
-                   par, n - plan.n_hit_gpu);
-        });
-    };
-    // Host threads pack the rows: first those the tier holds (into staging rows), then the others
-    // (from the store into the ring).  Each chunk is fetched as soon as it is in place.  Small chunks
-    // first, so that the link starts early; the copy threads outrun the link only by a little, so the
-    // chunks grow until a launch is a few per cent of its kernel.
-    char *land = bgl::tier_landing(t, gen);
-    if (land && plan.n_hit + plan.n_miss > 0) {
-        // Copy-engine transport: the packed rows go to device memory with plain copies on the tier's
-        // copy stream, as soon as they are packed and whatever the kernels of this cache are doing
-        // (the previous call's rows may still be on their way); kernels on side_stream then scatter
-        // them from there, after the hit gather.  The link carries one batch after the other.
-        const int64_t total = plan.n_hit + plan.n_miss;
-        const size_t rb = (size_t)c->row_bytes;
-        hipStream_t cs = bgl::tier_copy_stream(t);
-        rc = bgl::tier_copy_start(t);
-        if (rc != BGL_OK) return rc;
-        const char *ring_rows = bgl::tier_rows_device(t);
-        auto copy = [&](char *dst, const char *src, int64_t count) -> int {
-            Prof p(c, BGL_STAGE_LINK_COPY, cs, false);
-            BGL_HIP(hipMemcpyAsync(dst, src, (size_t)count * rb, hipMemcpyDefault, cs));
-            return BGL_OK;
-        };
-        // rows x0 <= x < x1 of the packed sequence: the tier's hits (staging rows), then its misses (ring)
-        auto copy_rows = [&](int64_t x0, int64_t x1) -> int {
-            if (x0 < plan.n_hit) {
-                const int64_t e = std::min(x1, plan.n_hit);
-                const int r1 = copy(land + (size_t)x0 * rb, plan.stage + (size_t)x0 * rb, e - x0);
-                if (r1 != BGL_OK) return r1;
-            }
-            const int64_t a = std::max(x0, plan.n_hit) - plan.n_hit, b = x1 - plan.n_hit;
-            if (b > a) {
-                const int64_t pos = (int64_t)((plan.ptail + (uint64_t)a) % (uint64_t)plan.ring);
-                const int64_t len1 = std::min(b - a, plan.ring - pos);  // up to the end of the ring
-                const int r1 = copy(land + (size_t)(plan.n_hit + a) * rb, ring_rows + (size_t)pos * rb, len1);
-                if (r1 != BGL_OK) return r1;
-                if (len1 < b - a) {
-                    const int r2 = copy(land + (size_t)(plan.n_hit + a + len1) * rb, ring_rows, b - a - len1);
-                    if (r2 != BGL_OK) return r2;
-                }
-            }
-            return BGL_OK;
-        };
-        // A copy costs the link a few microseconds whatever its size, so while earlier copies (the
-        // previous call's, or this call's) still occupy the link the packed rows pile up for one larger
-        // copy; when the link is free a chunk goes at once.
-        int64_t chunk = ls != ms ? TIER_CHUNK_ROWS : TIER_FIRST_CHUNK_ROWS;
-        bool link_busy = bgl::tier_copy_event_recorded(t);
-        for (int64_t launched = 0; launched < total;) {
-            const int64_t ready = bgl::tier_copy_progress(t);
-            bool go = ready > launched && ready == total;
-            if (!go && ready - launched >= chunk) {
-                if (link_busy) {
-                    link_busy = hipEventQuery(bgl::tier_copy_event(t)) != hipSuccess;
-                    (void)hipGetLastError();  // "not ready" is no error
-                }
-                go = !link_busy;
-            }
-            if (go) {
-                rc = copy_rows(launched, ready);
-                if (rc != BGL_OK) return rc;
-                BGL_HIP(hipEventRecord(bgl::tier_copy_event(t), cs));
-                bgl::tier_set_copy_event_recorded(t);
-                link_busy = true;
-                launched = ready;
-                chunk = std::min<int64_t>(2 * chunk, TIER_CHUNK_ROWS);
-            } else {
-                __builtin_ia32_pause();
-            }
-        }
-        bgl::tier_copy_wait(t);
-        BGL_HIP(hipStreamWaitEvent(ss, bgl::tier_copy_event(t), 0));  // (recorded behind the last copy)
-        auto scatter = [&](const char *src, const int32_t *rank, int64_t count) {
-            if (count == 0) return;
-            Prof p(c, BGL_STAGE_FETCH_MISS, ss);
-            const int blocks = (int)std::min<int64_t>(copy_blocks(count, q), 8192);  // device memory: the whole chip
-            dispatch_q(q, [&](auto Q) {
-                auto k = c->write_through ? k_fetch_rows<decltype(Q)::value, true>
-                                          : k_fetch_rows<decltype(Q)::value, false>;
-                launch(c, ss, k, dim3(blocks), dim3(COPY_THREADS), rank, (int64_t)0, count, 0ull, (int64_t)INT64_MAX,
-                       mpos, q, reinterpret_cast<const uint4 *>(src), reinterpret_cast<uint4 *>(out_rows), c->dev,
-                       reinterpret_cast<uint4 *>(c->buffer), c->capacity, par, n - plan.n_hit_gpu);
-            });
-        };
-        scatter(land, plan.hit_rank, plan.n_hit);
-        scatter(land + (size_t)plan.n_hit * rb, plan.miss_rank, plan.n_miss);
-    } else
     if (plan.n_hit + plan.n_miss > 0) {
-        rc = bgl::tier_copy_start(t);
+        TieredRows rows{c, t, &plan, ss, mpos, out_rows, n, (int)(c->insert_calls & 1), ls != ms};
+        rc = bgl::tier_copy_start(t);  // host threads start packing
         if (rc != BGL_OK) return rc;
-        const uint4 *stage = reinterpret_cast<const uint4 *>(plan.stage);
-        // (an early lookup is ahead of the link anyway: full chunks from the start)
-        int64_t chunk = ls != ms ? TIER_CHUNK_ROWS : TIER_FIRST_CHUNK_ROWS;
-        const int64_t total = plan.n_hit + plan.n_miss;
-        bool gather_done = false;
-        for (int64_t launched = 0; launched < total;) {
-            const int64_t ready = bgl::tier_copy_progress(t);
-            // a chunk does not straddle the two kinds of rows
-            const int64_t limit = launched < plan.n_hit ? std::min(ready, plan.n_hit) : ready;
-            bool go = limit > launched && (limit == plan.n_hit || limit == total);
-            if (!go && limit - launched >= chunk) {
-                // An early lookup's fetch cannot start before its hit gather has run, which waits for
-                // the previous call's fetch: until then the packed rows pile up for one larger launch.
-                if (ls != ms && !gather_done) {
-                    gather_done = hipEventQuery(c->ev_listed) == hipSuccess;
-                    (void)hipGetLastError();  // "not ready" is no error
-                }
-                go = gather_done || ls == ms;
-            }
-            if (go) {
-                if (launched < plan.n_hit)
-                    fetch(stage, 0ull, (int64_t)INT64_MAX, plan.hit_rank, launched, limit - launched);
-                else
-                    fetch(rows, (unsigned long long)plan.ptail, plan.ring, plan.miss_rank, launched - plan.n_hit,
-                          limit - launched);
-                launched = limit;
-                chunk = std::min<int64_t>(2 * chunk, TIER_CHUNK_ROWS);
-            } else {
-                __builtin_ia32_pause();
-            }
-        }
-        bgl::tier_copy_wait(t);
+        char *land = bgl::tier_landing(t, gen);  // device memory the copy engine fills, if that transport is on
+        rc = land ? rows_by_copy_engine(rows, land) : rows_by_kernels(rows);
+        if (rc != BGL_OK) return rc;
     }
     BGL_HIP(hipEventRecord(c->ev_miss, ss));
     // the tier's map changes after this call's lists are final and before the next lookup,
