@@ -261,7 +261,7 @@ struct RowSplit {
 };
 
 constexpr int COPY_THREADS = 256;
-constexpr int COPY_UNROLL = 4;
+constexpr int COPY_UNROLL = 4;  // (the kernels name the four chunks of a lane by hand)
 // Workgroups of the miss fetch.  64 x 256 lanes x 4 chunks = 1 MiB of loads in
 // flight saturate the host link; much more than that queues host reads in front
 // of the concurrent hit gather's HBM reads and slows it by an order of magnitude.
@@ -280,26 +280,32 @@ __global__ __launch_bounds__(COPY_THREADS) void k_gather_hits(
     const int32_t *__restrict__ hit_pos, const int32_t *__restrict__ hit_slot, int q,
     const uint4 *__restrict__ buffer, uint4 *__restrict__ out, const CacheDev *dev)
 {
+    static_assert(COPY_UNROLL == 4, "the four chunks of a lane are written out by hand");
     const int qq = Q > 0 ? Q : q;
     const int64_t total = (int64_t)dev->n_hit_last * qq;
     const int64_t base = (int64_t)blockIdx.x * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
     if (base - threadIdx.x >= total) return;
-    uint4 v[COPY_UNROLL];
-    int64_t dst[COPY_UNROLL];
-#pragma unroll
-    for (int k = 0; k < COPY_UNROLL; ++k) {
+    // (Four named values, not an array: the compiler put a `uint4 v[4]` into LDS instead of registers.)
+    auto load = [&](int k, uint4 &v, int64_t &dst) {
         const int64_t idx = base + k * COPY_THREADS;
-        dst[k] = -1;
+        dst = -1;
         if (idx < total) {
             int64_t r; int c;
             RowSplit<Q>::split(idx, q, r, c);
-            v[k] = buffer[(int64_t)hit_slot[r] * qq + c];
-            dst[k] = (int64_t)hit_pos[r] * qq + c;
+            v = buffer[(int64_t)hit_slot[r] * qq + c];
+            dst = (int64_t)hit_pos[r] * qq + c;
         }
-    }
-#pragma unroll
-    for (int k = 0; k < COPY_UNROLL; ++k)
-        if (dst[k] >= 0) out[dst[k]] = v[k];
+    };
+    uint4 v0, v1, v2, v3;
+    int64_t d0, d1, d2, d3;
+    load(0, v0, d0);
+    load(1, v1, d1);
+    load(2, v2, d2);
+    load(3, v3, d3);
+    if (d0 >= 0) out[d0] = v0;
+    if (d1 >= 0) out[d1] = v1;
+    if (d2 >= 0) out[d2] = v2;
+    if (d3 >= 0) out[d3] = v3;
 }
 
 // out[miss_pos[r]] = features[ids[miss_pos[r]]] for every miss r; the loads cross
@@ -326,31 +332,38 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_miss(
     const int64_t step = (int64_t)gridDim.x * (COPY_THREADS * COPY_UNROLL);
     for (int64_t base = (int64_t)blockIdx.x * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
          base - threadIdx.x < total; base += step) {
-        uint4 v[COPY_UNROLL];
-        int64_t dst[COPY_UNROLL], dst2[COPY_UNROLL];
-#pragma unroll
-        for (int k = 0; k < COPY_UNROLL; ++k) {
+        // (named values, not arrays of COPY_UNROLL: the compiler puts such an array into LDS)
+        auto load = [&](int k, uint4 &v, int64_t &dst, int64_t &dst2) {
             const int64_t idx = base + k * COPY_THREADS;
-            dst[k] = -1;
-            dst2[k] = -1;
+            dst = -1;
+            dst2 = -1;
             if (idx < total) {
                 int64_t r; int c;
                 RowSplit<Q>::split(idx, q, r, c);
                 const int32_t row = miss_pos[r];
                 const int32_t id = ids[row];
                 if (id >= 0 && (int64_t)id < num_nodes) {
-                    v[k] = features[(int64_t)id * qq + c];
-                    dst[k] = (int64_t)row * qq + c;
+                    v = features[(int64_t)id * qq + c];
+                    dst = (int64_t)row * qq + c;
                     if (WT && r >= start)
-                        dst2[k] = (int64_t)((tail + (unsigned long long)r) % (unsigned long long)capacity) * qq + c;
+                        dst2 = (int64_t)((tail + (unsigned long long)r) % (unsigned long long)capacity) * qq + c;
                 }
             }
-        }
-#pragma unroll
-        for (int k = 0; k < COPY_UNROLL; ++k) {
-            if (dst[k] >= 0) out[dst[k]] = v[k];
-            if (WT && dst2[k] >= 0) buffer[dst2[k]] = v[k];
-        }
+        };
+        auto store = [&](const uint4 &v, int64_t dst, int64_t dst2) {
+            if (dst >= 0) out[dst] = v;
+            if (WT && dst2 >= 0) buffer[dst2] = v;
+        };
+        uint4 v0, v1, v2, v3;
+        int64_t d0, d1, d2, d3, e0, e1, e2, e3;
+        load(0, v0, d0, e0);
+        load(1, v1, d1, e1);
+        load(2, v2, d2, e2);
+        load(3, v3, d3, e3);
+        store(v0, d0, e0);
+        store(v1, d1, e1);
+        store(v2, d2, e2);
+        store(v3, d3, e3);
     }
 }
 
@@ -376,13 +389,11 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_rows(
     const int64_t step = (int64_t)gridDim.x * (COPY_THREADS * COPY_UNROLL);
     for (int64_t base = (int64_t)blockIdx.x * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
          base - threadIdx.x < total; base += step) {
-        uint4 v[COPY_UNROLL];
-        int64_t dst[COPY_UNROLL], dst2[COPY_UNROLL];
-#pragma unroll
-        for (int k = 0; k < COPY_UNROLL; ++k) {
+        // (named values, not arrays of COPY_UNROLL: the compiler puts such an array into LDS)
+        auto load = [&](int k, uint4 &v, int64_t &dst, int64_t &dst2) {
             const int64_t idx = base + k * COPY_THREADS;
-            dst[k] = -1;
-            dst2[k] = -1;
+            dst = -1;
+            dst2 = -1;
             if (idx < total) {
                 int64_t l; int c;
                 RowSplit<Q>::split(idx, q, l, c);
@@ -390,20 +401,29 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_rows(
                 const int64_t r = rank ? rank[l] : l;
                 int64_t p = first_pos + l;
                 if (p >= ring) p -= ring;
-                v[k] = rows[p * qq + c];
-                dst[k] = (int64_t)miss_pos[r] * qq + c;
+                v = rows[p * qq + c];
+                dst = (int64_t)miss_pos[r] * qq + c;
                 if (WT && r >= start) {
                     int64_t slot = tail_slot + r;
                     if (slot >= capacity) slot -= capacity;
-                    dst2[k] = slot * qq + c;
+                    dst2 = slot * qq + c;
                 }
             }
-        }
-#pragma unroll
-        for (int k = 0; k < COPY_UNROLL; ++k) {
-            if (dst[k] >= 0) out[dst[k]] = v[k];
-            if (WT && dst2[k] >= 0) buffer[dst2[k]] = v[k];
-        }
+        };
+        auto store = [&](const uint4 &v, int64_t dst, int64_t dst2) {
+            if (dst >= 0) out[dst] = v;
+            if (WT && dst2 >= 0) buffer[dst2] = v;
+        };
+        uint4 v0, v1, v2, v3;
+        int64_t d0, d1, d2, d3, e0, e1, e2, e3;
+        load(0, v0, d0, e0);
+        load(1, v1, d1, e1);
+        load(2, v2, d2, e2);
+        load(3, v3, d3, e3);
+        store(v0, d0, e0);
+        store(v1, d1, e1);
+        store(v2, d2, e2);
+        store(v3, d3, e3);
     }
 }
 
@@ -491,24 +511,29 @@ __device__ __forceinline__ void insert_rows_part(
     const int64_t total = (n_miss - start) * qq;
     const int64_t base = block * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
     if (base - threadIdx.x >= total) return;
-    uint4 v[COPY_UNROLL];
-    int64_t dst[COPY_UNROLL];
-#pragma unroll
-    for (int k = 0; k < COPY_UNROLL; ++k) {
+    // (named values, not arrays of COPY_UNROLL: the compiler puts such an array into LDS)
+    auto load = [&](int k, uint4 &v, int64_t &dst) {
         const int64_t idx = base + k * COPY_THREADS;
-        dst[k] = -1;
+        dst = -1;
         if (idx < total) {
             int64_t rr; int c;
             RowSplit<Q>::split(idx, q, rr, c);
             const int64_t r = start + rr;
             const int64_t slot = (int64_t)((tail + (unsigned long long)r) % (unsigned long long)capacity);
-            v[k] = out[(int64_t)miss_pos[r] * qq + c];
-            dst[k] = slot * qq + c;
+            v = out[(int64_t)miss_pos[r] * qq + c];
+            dst = slot * qq + c;
         }
-    }
-#pragma unroll
-    for (int k = 0; k < COPY_UNROLL; ++k)
-        if (dst[k] >= 0) buffer[dst[k]] = v[k];
+    };
+    uint4 v0, v1, v2, v3;
+    int64_t d0, d1, d2, d3;
+    load(0, v0, d0);
+    load(1, v1, d1);
+    load(2, v2, d2);
+    load(3, v3, d3);
+    if (d0 >= 0) buffer[d0] = v0;
+    if (d1 >= 0) buffer[d1] = v1;
+    if (d2 >= 0) buffer[d2] = v2;
+    if (d3 >= 0) buffer[d3] = v3;
 }
 
 // The FIFO update is two launches because only the row copy needs the fetched
