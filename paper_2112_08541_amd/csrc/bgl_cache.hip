@@ -1101,7 +1101,7 @@ int rows_by_copy_engine(const TieredRows &r, char *land)
             link_busy = true;
             launched = ready;
             chunk = std::min<int64_t>(2 * chunk, TIER_CHUNK_ROWS);
-        } else {
+        } else if (!bgl::tier_copy_help(t)) {  // nothing to send: pack a few rows too
             __builtin_ia32_pause();
         }
     }
@@ -1149,7 +1149,7 @@ int rows_by_kernels(const TieredRows &r)
                               launched - plan.n_hit, limit - launched, FETCH_BLOCKS);
             launched = limit;
             chunk = std::min<int64_t>(2 * chunk, TIER_CHUNK_ROWS);
-        } else {
+        } else if (!bgl::tier_copy_help(t)) {  // nothing to send: pack a few rows too
             __builtin_ia32_pause();
         }
     }

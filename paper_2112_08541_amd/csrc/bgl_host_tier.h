@@ -53,6 +53,8 @@ int tier_begin(bgl_host_tier *t, int64_t n, TierPlan *plan);
 // place (monotone, reaches n_hit + n_miss); tier_copy_wait ends the job.
 int tier_copy_start(bgl_host_tier *t);
 int64_t tier_copy_progress(bgl_host_tier *t);
+// The calling thread packs a few rows itself (one task of the copy job); false when none is left.
+bool tier_copy_help(bgl_host_tier *t);
 void tier_copy_wait(bgl_host_tier *t);
 // Copy-engine transport (bgl_host_tier_set_copy_engine): the packed rows of the batch whose lists
 // have parity gen are copied into tier_landing(t, gen) (device memory, max_batch rows) on

@@ -326,6 +326,8 @@ int64_t tier_copy_progress(bgl_host_tier *t)
     return ready;
 }
 
+bool tier_copy_help(bgl_host_tier *t) { return t->copying && t->pool->help_one(); }
+
 void tier_copy_wait(bgl_host_tier *t)
 {
     if (!t->copying) return;

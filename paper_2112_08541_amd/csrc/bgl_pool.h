@@ -16,8 +16,9 @@ namespace bgl {
 // A few host threads that run one job at a time: tasks 0..tasks-1, claimed in
 // increasing order.  run() also works on the calling thread and returns when
 // all tasks are done; start() returns at once, done_prefix() tells how many
-// leading tasks are complete (the caller launches work on them meanwhile) and
-// wait() ends the job.
+// leading tasks are complete (the caller launches work on them meanwhile),
+// help_one() lets the caller take a task itself when it has nothing else to do,
+// and wait() ends the job.
 class Pool {
 public:
     using Fn = std::function<void(int64_t)>;
@@ -57,6 +58,17 @@ public:
     {
         while (prefix_ < tasks_ && done_[(size_t)prefix_].load(std::memory_order_acquire)) ++prefix_;
         return prefix_;
+    }
+    // Between start() and wait(): the calling thread runs one task that nobody has claimed yet.
+    // False when none is left.
+    bool help_one()
+    {
+        if (next_.load(std::memory_order_relaxed) >= tasks_) return false;
+        const int64_t k = next_.fetch_add(1);
+        if (k >= tasks_) return false;
+        (*fn_)(k);
+        done_[(size_t)k].store(1, std::memory_order_release);
+        return true;
     }
     void wait()
     {

@@ -41,6 +41,7 @@ int main(int argc, char **argv)
                 if (out[(size_t)i] != (long)r * 1000003 + i) { printf("start: wrong value\n"); return 1; }
             checked += (done - seen) * per;
             seen = done;
+            if (r % 2 == 0) (void)pool.help_one();             // the caller takes a task between two looks
         }
         pool.wait();
         if (pool.done_prefix() != tasks) { printf("prefix after wait\n"); return 1; }
