@@ -285,27 +285,29 @@ __global__ __launch_bounds__(COPY_THREADS) void k_gather_hits(
     const int64_t total = (int64_t)dev->n_hit_last * qq;
     const int64_t base = (int64_t)blockIdx.x * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
     if (base - threadIdx.x >= total) return;
-    // (Four named values, not an array: the compiler put a `uint4 v[4]` into LDS instead of registers.)
-    auto load = [&](int k, uint4 &v, int64_t &dst) {
-        const int64_t idx = base + k * COPY_THREADS;
-        dst = -1;
-        if (idx < total) {
-            int64_t r; int c;
-            RowSplit<Q>::split(idx, q, r, c);
-            v = buffer[(int64_t)hit_slot[r] * qq + c];
-            dst = (int64_t)hit_pos[r] * qq + c;
-        }
-    };
-    uint4 v0, v1, v2, v3;
-    int64_t d0, d1, d2, d3;
-    load(0, v0, d0);
-    load(1, v1, d1);
-    load(2, v2, d2);
-    load(3, v3, d3);
-    if (d0 >= 0) out[d0] = v0;
-    if (d1 >= 0) out[d1] = v1;
-    if (d2 >= 0) out[d2] = v2;
-    if (d3 >= 0) out[d3] = v3;
+    // Three phases without a branch in between, so that the four list reads of a lane are in flight
+    // together, then its four row reads, then its stores: chunk numbers beyond the end are clamped
+    // to the last chunk, which those lanes then copy once more (same bytes to the same place).
+    // (Written chunk by chunk with a branch each, every read waited for the one before it; with only
+    // the stores under a branch the compiler moved reads back in there; and as an array `uint4 v[4]`
+    // the values were put into LDS instead of registers.)
+    const int64_t last = total - 1;
+    int64_t r0, r1, r2, r3;
+    int c0, c1, c2, c3;
+    RowSplit<Q>::split(min(base, last), q, r0, c0);
+    RowSplit<Q>::split(min(base + COPY_THREADS, last), q, r1, c1);
+    RowSplit<Q>::split(min(base + 2 * COPY_THREADS, last), q, r2, c2);
+    RowSplit<Q>::split(min(base + 3 * COPY_THREADS, last), q, r3, c3);
+    const int32_t s0 = hit_slot[r0], s1 = hit_slot[r1], s2 = hit_slot[r2], s3 = hit_slot[r3];
+    const int32_t p0 = hit_pos[r0], p1 = hit_pos[r1], p2 = hit_pos[r2], p3 = hit_pos[r3];
+    const uint4 v0 = buffer[(int64_t)s0 * qq + c0];
+    const uint4 v1 = buffer[(int64_t)s1 * qq + c1];
+    const uint4 v2 = buffer[(int64_t)s2 * qq + c2];
+    const uint4 v3 = buffer[(int64_t)s3 * qq + c3];
+    out[(int64_t)p0 * qq + c0] = v0;
+    out[(int64_t)p1 * qq + c1] = v1;
+    out[(int64_t)p2 * qq + c2] = v2;
+    out[(int64_t)p3 * qq + c3] = v3;
 }
 
 // out[miss_pos[r]] = features[ids[miss_pos[r]]] for every miss r; the loads cross
@@ -324,46 +326,50 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_miss(
     int64_t num_nodes, const uint4 *__restrict__ features, uint4 *__restrict__ out,
     const CacheDev *dev, uint4 *__restrict__ buffer, int64_t capacity, int par, int gen)
 {
+    static_assert(COPY_UNROLL == 4, "the four chunks of a lane are written out by hand");
     const int qq = Q > 0 ? Q : q;
     const int64_t n_miss = dev->n_miss_gen[gen];
     const int64_t total = n_miss * qq;
+    const int64_t last = total - 1;
     const int64_t start = n_miss > capacity ? n_miss - capacity : 0;
-    const unsigned long long tail = WT ? dev->tail[par] : 0ull;
+    // (start <= r < n_miss covers less than one turn of the buffer: the wrap-around is one subtraction)
+    const int64_t tail_slot = WT ? (int64_t)((dev->tail[par] + (unsigned long long)start) % (unsigned long long)capacity) - start : 0;
     const int64_t step = (int64_t)gridDim.x * (COPY_THREADS * COPY_UNROLL);
     for (int64_t base = (int64_t)blockIdx.x * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
          base - threadIdx.x < total; base += step) {
-        // (named values, not arrays of COPY_UNROLL: the compiler puts such an array into LDS)
-        auto load = [&](int k, uint4 &v, int64_t &dst, int64_t &dst2) {
-            const int64_t idx = base + k * COPY_THREADS;
-            dst = -1;
-            dst2 = -1;
-            if (idx < total) {
-                int64_t r; int c;
-                RowSplit<Q>::split(idx, q, r, c);
-                const int32_t row = miss_pos[r];
-                const int32_t id = ids[row];
-                if (id >= 0 && (int64_t)id < num_nodes) {
-                    v = features[(int64_t)id * qq + c];
-                    dst = (int64_t)row * qq + c;
-                    if (WT && r >= start)
-                        dst2 = (int64_t)((tail + (unsigned long long)r) % (unsigned long long)capacity) * qq + c;
-                }
+        // Phase by phase for the lane's four chunks, as in k_gather_hits: positions, ids, rows, stores;
+        // chunk numbers beyond the end are clamped to the last chunk, which is then copied again.
+        int64_t r0, r1, r2, r3;
+        int c0, c1, c2, c3;
+        RowSplit<Q>::split(min(base, last), q, r0, c0);
+        RowSplit<Q>::split(min(base + COPY_THREADS, last), q, r1, c1);
+        RowSplit<Q>::split(min(base + 2 * COPY_THREADS, last), q, r2, c2);
+        RowSplit<Q>::split(min(base + 3 * COPY_THREADS, last), q, r3, c3);
+        const int32_t m0 = miss_pos[r0], m1 = miss_pos[r1], m2 = miss_pos[r2], m3 = miss_pos[r3];
+        const int32_t i0 = ids[m0], i1 = ids[m1], i2 = ids[m2], i3 = ids[m3];
+        // an id outside the table (reported by the lookup) reads row 0 and stores nothing
+        const bool ok0 = i0 >= 0 && (int64_t)i0 < num_nodes, ok1 = i1 >= 0 && (int64_t)i1 < num_nodes;
+        const bool ok2 = i2 >= 0 && (int64_t)i2 < num_nodes, ok3 = i3 >= 0 && (int64_t)i3 < num_nodes;
+        uint4 v0 = features[(int64_t)(ok0 ? i0 : 0) * qq + c0];
+        uint4 v1 = features[(int64_t)(ok1 ? i1 : 0) * qq + c1];
+        uint4 v2 = features[(int64_t)(ok2 ? i2 : 0) * qq + c2];
+        uint4 v3 = features[(int64_t)(ok3 ? i3 : 0) * qq + c3];
+        // (the four reads stay above the branches that follow: the values are needed here)
+        asm volatile("" : "+v"(v0.x), "+v"(v0.y), "+v"(v0.z), "+v"(v0.w), "+v"(v1.x), "+v"(v1.y), "+v"(v1.z), "+v"(v1.w),
+                          "+v"(v2.x), "+v"(v2.y), "+v"(v2.z), "+v"(v2.w), "+v"(v3.x), "+v"(v3.y), "+v"(v3.z), "+v"(v3.w));
+        auto store = [&](bool ok, int64_t r, int32_t m, int c, const uint4 &v) {
+            if (!ok) return;
+            out[(int64_t)m * qq + c] = v;
+            if (WT && r >= start) {
+                int64_t slot = tail_slot + r;
+                if (slot >= capacity) slot -= capacity;
+                buffer[slot * qq + c] = v;
             }
         };
-        auto store = [&](const uint4 &v, int64_t dst, int64_t dst2) {
-            if (dst >= 0) out[dst] = v;
-            if (WT && dst2 >= 0) buffer[dst2] = v;
-        };
-        uint4 v0, v1, v2, v3;
-        int64_t d0, d1, d2, d3, e0, e1, e2, e3;
-        load(0, v0, d0, e0);
-        load(1, v1, d1, e1);
-        load(2, v2, d2, e2);
-        load(3, v3, d3, e3);
-        store(v0, d0, e0);
-        store(v1, d1, e1);
-        store(v2, d2, e2);
-        store(v3, d3, e3);
+        store(ok0, r0, m0, c0, v0);
+        store(ok1, r1, m1, c1, v1);
+        store(ok2, r2, m2, c2, v2);
+        store(ok3, r3, m3, c3, v3);
     }
 }
 
@@ -379,8 +385,10 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_rows(
     const int32_t *__restrict__ miss_pos, int q, const uint4 *__restrict__ rows, uint4 *__restrict__ out,
     const CacheDev *dev, uint4 *__restrict__ buffer, int64_t capacity, int par, int64_t n_miss)
 {
+    static_assert(COPY_UNROLL == 4, "the four chunks of a lane are written out by hand");
     const int qq = Q > 0 ? Q : q;
     const int64_t total = count * qq;
+    const int64_t last = total - 1;
     const int64_t start = n_miss > capacity ? n_miss - capacity : 0;
     // the two wrap-arounds without a division per chunk: the launch covers less than one turn of
     // the ring, and the ranks it stores (start <= r < n_miss) less than one turn of the buffer
@@ -389,41 +397,40 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_rows(
     const int64_t step = (int64_t)gridDim.x * (COPY_THREADS * COPY_UNROLL);
     for (int64_t base = (int64_t)blockIdx.x * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
          base - threadIdx.x < total; base += step) {
-        // (named values, not arrays of COPY_UNROLL: the compiler puts such an array into LDS)
-        auto load = [&](int k, uint4 &v, int64_t &dst, int64_t &dst2) {
-            const int64_t idx = base + k * COPY_THREADS;
-            dst = -1;
-            dst2 = -1;
-            if (idx < total) {
-                int64_t l; int c;
-                RowSplit<Q>::split(idx, q, l, c);
-                l += l0;
-                const int64_t r = rank ? rank[l] : l;
-                int64_t p = first_pos + l;
-                if (p >= ring) p -= ring;
-                v = rows[p * qq + c];
-                dst = (int64_t)miss_pos[r] * qq + c;
-                if (WT && r >= start) {
-                    int64_t slot = tail_slot + r;
-                    if (slot >= capacity) slot -= capacity;
-                    dst2 = slot * qq + c;
-                }
+        // Phase by phase for the lane's four chunks, as in k_gather_hits: ranks, positions, rows,
+        // stores; chunk numbers beyond the end are clamped to the last chunk, which is then copied again.
+        int64_t l_0, l_1, l_2, l_3;
+        int c0, c1, c2, c3;
+        RowSplit<Q>::split(min(base, last), q, l_0, c0);
+        RowSplit<Q>::split(min(base + COPY_THREADS, last), q, l_1, c1);
+        RowSplit<Q>::split(min(base + 2 * COPY_THREADS, last), q, l_2, c2);
+        RowSplit<Q>::split(min(base + 3 * COPY_THREADS, last), q, l_3, c3);
+        l_0 += l0; l_1 += l0; l_2 += l0; l_3 += l0;
+        int64_t r0 = l_0, r1 = l_1, r2 = l_2, r3 = l_3;
+        if (rank) { r0 = rank[l_0]; r1 = rank[l_1]; r2 = rank[l_2]; r3 = rank[l_3]; }
+        const int32_t m0 = miss_pos[r0], m1 = miss_pos[r1], m2 = miss_pos[r2], m3 = miss_pos[r3];
+        auto wrapped = [](int64_t x, int64_t turn) { return x >= turn ? x - turn : x; };
+        uint4 v0 = rows[wrapped(first_pos + l_0, ring) * qq + c0];
+        uint4 v1 = rows[wrapped(first_pos + l_1, ring) * qq + c1];
+        uint4 v2 = rows[wrapped(first_pos + l_2, ring) * qq + c2];
+        uint4 v3 = rows[wrapped(first_pos + l_3, ring) * qq + c3];
+        out[(int64_t)m0 * qq + c0] = v0;
+        out[(int64_t)m1 * qq + c1] = v1;
+        out[(int64_t)m2 * qq + c2] = v2;
+        out[(int64_t)m3 * qq + c3] = v3;
+        if (WT) {
+            if (start == 0) {  // every rank gets a slot (the usual case: fewer misses than slots)
+                buffer[wrapped(tail_slot + r0, capacity) * qq + c0] = v0;
+                buffer[wrapped(tail_slot + r1, capacity) * qq + c1] = v1;
+                buffer[wrapped(tail_slot + r2, capacity) * qq + c2] = v2;
+                buffer[wrapped(tail_slot + r3, capacity) * qq + c3] = v3;
+            } else {
+                if (r0 >= start) buffer[wrapped(tail_slot + r0, capacity) * qq + c0] = v0;
+                if (r1 >= start) buffer[wrapped(tail_slot + r1, capacity) * qq + c1] = v1;
+                if (r2 >= start) buffer[wrapped(tail_slot + r2, capacity) * qq + c2] = v2;
+                if (r3 >= start) buffer[wrapped(tail_slot + r3, capacity) * qq + c3] = v3;
             }
-        };
-        auto store = [&](const uint4 &v, int64_t dst, int64_t dst2) {
-            if (dst >= 0) out[dst] = v;
-            if (WT && dst2 >= 0) buffer[dst2] = v;
-        };
-        uint4 v0, v1, v2, v3;
-        int64_t d0, d1, d2, d3, e0, e1, e2, e3;
-        load(0, v0, d0, e0);
-        load(1, v1, d1, e1);
-        load(2, v2, d2, e2);
-        load(3, v3, d3, e3);
-        store(v0, d0, e0);
-        store(v1, d1, e1);
-        store(v2, d2, e2);
-        store(v3, d3, e3);
+        }
     }
 }
 
@@ -507,33 +514,33 @@ __device__ __forceinline__ void insert_rows_part(
     unsigned long long tail, int64_t capacity, int q, const uint4 *__restrict__ out,
     uint4 *__restrict__ buffer)
 {
+    static_assert(COPY_UNROLL == 4, "the four chunks of a lane are written out by hand");
     const int qq = Q > 0 ? Q : q;
     const int64_t total = (n_miss - start) * qq;
     const int64_t base = block * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
     if (base - threadIdx.x >= total) return;
-    // (named values, not arrays of COPY_UNROLL: the compiler puts such an array into LDS)
-    auto load = [&](int k, uint4 &v, int64_t &dst) {
-        const int64_t idx = base + k * COPY_THREADS;
-        dst = -1;
-        if (idx < total) {
-            int64_t rr; int c;
-            RowSplit<Q>::split(idx, q, rr, c);
-            const int64_t r = start + rr;
-            const int64_t slot = (int64_t)((tail + (unsigned long long)r) % (unsigned long long)capacity);
-            v = out[(int64_t)miss_pos[r] * qq + c];
-            dst = slot * qq + c;
-        }
-    };
-    uint4 v0, v1, v2, v3;
-    int64_t d0, d1, d2, d3;
-    load(0, v0, d0);
-    load(1, v1, d1);
-    load(2, v2, d2);
-    load(3, v3, d3);
-    if (d0 >= 0) buffer[d0] = v0;
-    if (d1 >= 0) buffer[d1] = v1;
-    if (d2 >= 0) buffer[d2] = v2;
-    if (d3 >= 0) buffer[d3] = v3;
+    // Phase by phase for the lane's four chunks, as in k_gather_hits: positions, rows, stores; chunk
+    // numbers beyond the end are clamped to the last chunk, which is then copied again.
+    const int64_t last = total - 1;
+    // (start <= r < n_miss covers at most one turn of the buffer: the wrap-around is one subtraction)
+    const int64_t tail_slot = (int64_t)((tail + (unsigned long long)start) % (unsigned long long)capacity);
+    int64_t r0, r1, r2, r3;
+    int c0, c1, c2, c3;
+    RowSplit<Q>::split(min(base, last), q, r0, c0);
+    RowSplit<Q>::split(min(base + COPY_THREADS, last), q, r1, c1);
+    RowSplit<Q>::split(min(base + 2 * COPY_THREADS, last), q, r2, c2);
+    RowSplit<Q>::split(min(base + 3 * COPY_THREADS, last), q, r3, c3);
+    const int32_t m0 = miss_pos[start + r0], m1 = miss_pos[start + r1], m2 = miss_pos[start + r2],
+                  m3 = miss_pos[start + r3];
+    const uint4 v0 = out[(int64_t)m0 * qq + c0];
+    const uint4 v1 = out[(int64_t)m1 * qq + c1];
+    const uint4 v2 = out[(int64_t)m2 * qq + c2];
+    const uint4 v3 = out[(int64_t)m3 * qq + c3];
+    auto wrapped = [capacity](int64_t slot) { return slot >= capacity ? slot - capacity : slot; };
+    buffer[wrapped(tail_slot + r0) * qq + c0] = v0;
+    buffer[wrapped(tail_slot + r1) * qq + c1] = v1;
+    buffer[wrapped(tail_slot + r2) * qq + c2] = v2;
+    buffer[wrapped(tail_slot + r3) * qq + c3] = v3;
 }
 
 // The FIFO update is two launches because only the row copy needs the fetched
