@@ -157,8 +157,11 @@ __global__ __launch_bounds__(TILE) void k_sample_insert(
     uint32_t v = 0;
     if (active) {
         v = (uint32_t)frontier[i];
-        lo = (int64_t)row_ptr[v];
-        d = (int64_t)row_ptr[v + 1] - lo;
+        // both ends of the row with one read (the pair is only 4 or 8 bytes aligned)
+        typedef RP Ends __attribute__((ext_vector_type(2), aligned(sizeof(RP))));
+        const Ends ends = *reinterpret_cast<const Ends *>(row_ptr + v);
+        lo = (int64_t)ends.x;
+        d = (int64_t)ends.y - lo;
     }
     const int c = (int)(d < (int64_t)fanout ? d : (int64_t)fanout);
     const bool need = active && d > (int64_t)fanout;  // Floyd's algorithm, else the whole row
