@@ -375,8 +375,9 @@ int bgl_host_tier_set_copy_engine(bgl_host_tier_t *t, int enable);
  * looked up against the tier's state at entry, then its own misses inserted in
  * that order (the rule of bgl_cache_insert_fifo, tail advancing by their
  * number).  The call blocks the host until the lists are known and the rows
- * are packed; the kernels that move them run on side_stream chunk by chunk
- * while the host threads are still copying.  On
+ * are packed; what moves them starts while the host threads are still copying
+ * (kernels on side_stream chunk by chunk, or with the copy-engine transport
+ * copies on the tier's own stream followed by kernels on side_stream).  On
  * return the fetch of all miss rows is enqueued on side_stream
  * (bgl_cache_wait_rows as usual) and the tier's update on main_stream (on
  * lookup_stream with early_lookup); the GPU
