@@ -361,6 +361,17 @@ def main():
         if miss_path == "staged":
             s_ms, s_n = prof["fetch_miss"]
             result["host_link"]["scatter_kernels_us_per_step"] = 1e3 * s_ms / max(len(sampled), 1)
+            # the kernel that scatters the landed rows: every miss row read once from HBM and written
+            # once to out_rows, and once more to the cache buffer in write-through mode
+            moved = (3.0 if pipe.write_through else 2.0) * rb * miss3
+            a3 = moved / (s_ms * 1e-3) / 1e9 if s_ms > 0 else 0.0
+            result["roofline_scatter"] = {
+                "kernel": "k_fetch_rows", "bound": "hbm", "achieved": a3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": a3 / HBM_PEAK_GBS, "bytes_per_step": moved / max(len(sampled), 1),
+                "avg_us_per_step": 1e3 * s_ms / max(len(sampled), 1), "launches": s_n,
+                "note": "landed miss rows to out_rows and the cache buffer, every %d-th batch; not the kernel "
+                        "the headline roofline is about" % every,
+            }
 
         # The same kernel on a launch that is mostly hits (outside the timed region, not
         # part of `value`): the epoch's last batch is looked up again right after its
