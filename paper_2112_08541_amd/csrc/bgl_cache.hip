@@ -262,10 +262,15 @@ struct RowSplit {
 
 constexpr int COPY_THREADS = 256;
 constexpr int COPY_UNROLL = 4;  // (the kernels name the four chunks of a lane by hand)
-// Workgroups of the miss fetch.  64 x 256 lanes x 4 chunks = 1 MiB of loads in
-// flight saturate the host link; much more than that queues host reads in front
-// of the concurrent hit gather's HBM reads and slows it by an order of magnitude.
+// Workgroups of a kernel that reads rows over the host link.  Each lane keeps
+// four 16-byte loads in flight, so 64 x 256 lanes hold 1 MiB: that saturates
+// the link for rows read in place (whole 128-byte lines, partly unused), and
+// much more queues host reads in front of the concurrent kernels' HBM reads and
+// slows those by an order of magnitude.  The packed ring is read densely and
+// needs half as much in flight; with 64 workgroups there the next batch's
+// lookup, and with it the packing of its rows, starts late.
 constexpr int FETCH_BLOCKS = 64;
+constexpr int RING_FETCH_BLOCKS = 32;
 // Tiered lookup: rows the host threads copy per chunk before that chunk's fetch is launched.
 constexpr int64_t TIER_CHUNK_ROWS = 49152;
 constexpr int64_t TIER_FIRST_CHUNK_ROWS = 3072;
@@ -1150,10 +1155,10 @@ int rows_by_kernels(const TieredRows &r)
         if (go) {
             if (launched < plan.n_hit)
                 r.launch_rows(plan.stage, 0ull, (int64_t)INT64_MAX, plan.hit_rank, launched, limit - launched,
-                              FETCH_BLOCKS);
+                              RING_FETCH_BLOCKS);
             else
                 r.launch_rows(ring_rows, (unsigned long long)plan.ptail, plan.ring, plan.miss_rank,
-                              launched - plan.n_hit, limit - launched, FETCH_BLOCKS);
+                              launched - plan.n_hit, limit - launched, RING_FETCH_BLOCKS);
             launched = limit;
             chunk = std::min<int64_t>(2 * chunk, TIER_CHUNK_ROWS);
         } else if (!bgl::tier_copy_help(t)) {  // nothing to send: pack a few rows too
