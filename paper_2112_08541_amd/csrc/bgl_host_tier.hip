@@ -2,16 +2,18 @@
 // the GPU cache uses the same policy as the GPU cache, i.e. FIFO; the misses of
 // both levels come from the feature store, the graph store servers' stand-in).
 //
-// Only the tier's ROWS live in host memory (page-locked).  Its bookkeeping lives in HBM, where random access is cheap: node ids
-// are dense, so the map is a plain array node -> row position (4 bytes per
-// node), looked up by a kernel for the GPU cache's misses right behind that
-// cache's own lookup; the same kernels list the rows the tier holds and the ids
+// Only the tier's ROWS live in host memory (page-locked).  Its bookkeeping lives
+// in HBM, where random access is cheap: node ids are dense, so the map is a
+// plain array node -> row position (4 bytes per node), looked up by a kernel
+// for the GPU cache's misses right behind that cache's own lookup; the same kernels list the rows the tier holds and the ids
 // it does not.  The host only feeds rows, always packed, because rows that are
 // not multiples of 128 bytes cross the link a quarter faster packed than read in
 // place: its threads copy the rows the tier holds into staging rows, in list
 // order, and the missing rows from the store into the positions first-in
-// first-out assigns (consecutive), and the calling thread launches a fetch
-// kernel on each chunk as soon as its rows are in place.
+// first-out assigns (consecutive), and the calling thread sends each chunk on
+// as soon as its rows are in place: a plain copy into device memory on the copy
+// stream (the copy-engine transport), or a fetch kernel that reads the chunk
+// over the link.
 //
 // Rows sit in a ring of capacity_rows + 2 * max_batch_rows positions, filled in
 // insertion order.  The newest capacity_rows insertions are the tier's content
