@@ -59,7 +59,7 @@ int device_view(const void *host, const void **dev)
 extern "C" int bgl_graph_load_csr(const void *row_ptr, int row_ptr_bits, const int32_t *col_idx,
                                   int64_t num_nodes, int64_t num_edges, int placement,
                                   bgl_graph_t **out)
-{
+try {
     if (!out) BGL_FAIL(BGL_EINVAL, "out is null");
     *out = nullptr;
     if (!row_ptr) BGL_FAIL(BGL_EINVAL, "row_ptr is null");
@@ -133,13 +133,13 @@ extern "C" int bgl_graph_load_csr(const void *row_ptr, int row_ptr_bits, const i
     }
     *out = g;
     return BGL_OK;
-}
+} BGL_NOTHROW_END
 
 extern "C" int bgl_graph_destroy(bgl_graph_t *g)
-{
+try {
     if (!g) return BGL_OK;
     (void)hipFree(g->owned_row_ptr);
     (void)hipFree(g->owned_col);
     delete g;
     return BGL_OK;
-}
+} BGL_NOTHROW_END

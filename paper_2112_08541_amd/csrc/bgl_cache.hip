@@ -703,7 +703,7 @@ int copy_blocks(int64_t rows, int q)
 // ------------------------------------------------------------------ C ABI
 extern "C" int bgl_cache_create(int64_t capacity_rows, int32_t row_bytes,
                                 const void *host_features, int64_t num_nodes, bgl_cache_t **out)
-{
+try {
     if (!out) BGL_FAIL(BGL_EINVAL, "out is null");
     *out = nullptr;
     if (capacity_rows < 1 || capacity_rows > INT32_MAX)
@@ -795,10 +795,10 @@ extern "C" int bgl_cache_create(int64_t capacity_rows, int32_t row_bytes,
     }
     *out = c;
     return BGL_OK;
-}
+} BGL_NOTHROW_END
 
 extern "C" int bgl_cache_destroy(bgl_cache_t *c)
-{
+try {
     if (!c) return BGL_OK;
     (void)hipDeviceSynchronize();
     for (auto ev : c->prof_ev) (void)hipEventDestroy(ev);
@@ -818,7 +818,7 @@ extern "C" int bgl_cache_destroy(bgl_cache_t *c)
     (void)hipFree(c->mpos_copy[1]);
     delete c;
     return BGL_OK;
-}
+} BGL_NOTHROW_END
 
 namespace {
 
@@ -1026,19 +1026,19 @@ int lookup_gather_impl(bgl_cache_t *c, const int32_t *ids, int64_t n, void *out_
 extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64_t n,
                                        void *out_rows, int32_t *out_slot, int32_t *miss_pos,
                                        int64_t *n_hit_host, void *main_stream, void *side_stream)
-{
+try {
     return lookup_gather_impl(c, ids, n, out_rows, out_slot, miss_pos, n_hit_host, main_stream, side_stream,
                               nullptr, false);
-}
+} BGL_NOTHROW_END
 
 extern "C" int bgl_cache_lookup_gather_early(bgl_cache_t *c, const int32_t *ids, int64_t n,
                                              void *out_rows, int32_t *out_slot, int32_t *miss_pos,
                                              int64_t *n_hit_host, void *main_stream, void *side_stream,
                                              void *lookup_stream)
-{
+try {
     return lookup_gather_impl(c, ids, n, out_rows, out_slot, miss_pos, n_hit_host, main_stream, side_stream,
                               lookup_stream, static_cast<hipStream_t>(lookup_stream) != static_cast<hipStream_t>(main_stream));
-}
+} BGL_NOTHROW_END
 
 namespace {
 
@@ -1200,7 +1200,7 @@ extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t
                                               int64_t n, void *out_rows, int32_t *out_slot,
                                               int32_t *miss_pos, int64_t *n_hit, void *main_stream,
                                               void *side_stream, void *lookup_stream, int early_lookup)
-{
+try {
     int rc = check_lookup_args(c, ids, n, out_rows, out_slot, miss_pos);
     if (rc != BGL_OK) return rc;
     if (!t) BGL_FAIL(BGL_EINVAL, "tier handle is null");
@@ -1265,11 +1265,11 @@ extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t
         c->wt_miss_pos = miss_pos;
     }
     return BGL_OK;
-}
+} BGL_NOTHROW_END
 
 extern "C" int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const int32_t *miss_pos,
                                      int64_t n_miss, const void *out_rows, void *stream)
-{
+try {
     if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
     if (n_miss < -1 || n_miss > INT32_MAX) BGL_FAIL(BGL_EINVAL, "n_miss out of range");
     const int64_t bound = n_miss >= 0 ? n_miss : c->last_n;  // launch size
@@ -1332,36 +1332,36 @@ extern "C" int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const i
     c->map_pending = true;
     c->map_stream = st;
     return BGL_OK;
-}
+} BGL_NOTHROW_END
 
 extern "C" int bgl_cache_set_write_through(bgl_cache_t *c, int enable)
-{
+try {
     if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
     if (c->awaiting_insert) BGL_FAIL(BGL_EINVAL, "a lookup's misses are still waiting for their insert_fifo");
     c->write_through = enable != 0;
     return BGL_OK;
-}
+} BGL_NOTHROW_END
 
 extern "C" int bgl_cache_wait_rows(bgl_cache_t *c, void *stream)
-{
+try {
     if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (c->fetch_pending && c->fetch_stream != st) BGL_HIP(hipStreamWaitEvent(st, c->ev_miss, 0));
     return BGL_OK;
-}
+} BGL_NOTHROW_END
 
 extern "C" int bgl_cache_wait_lists(bgl_cache_t *c, void *stream)
-{
+try {
     if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (c->ev_listed_valid && st != c->last_main)
         BGL_HIP(hipStreamWaitEvent(st, c->ev_listed, 0));
     return BGL_OK;
-}
+} BGL_NOTHROW_END
 
 extern "C" int bgl_cache_export_state(bgl_cache_t *c, int32_t *slot_to_node, uint64_t *tail,
                                       void *buffer)
-{
+try {
     if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
     BGL_HIP(hipDeviceSynchronize());
     if (slot_to_node)
@@ -1375,11 +1375,11 @@ extern "C" int bgl_cache_export_state(bgl_cache_t *c, int32_t *slot_to_node, uin
     if (buffer)
         BGL_HIP(hipMemcpy(buffer, c->buffer, (size_t)c->capacity * c->row_bytes, hipMemcpyDeviceToHost));
     return BGL_OK;
-}
+} BGL_NOTHROW_END
 
 extern "C" int bgl_cache_stats(bgl_cache_t *c, uint64_t *lookups, uint64_t *hits, uint64_t *inserts,
                                uint64_t *evictions, int32_t *status)
-{
+try {
     if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
     BGL_HIP(hipDeviceSynchronize());
     CacheDev h;
@@ -1392,10 +1392,10 @@ extern "C" int bgl_cache_stats(bgl_cache_t *c, uint64_t *lookups, uint64_t *hits
     if (evictions) *evictions = tail > (uint64_t)c->capacity ? tail - (uint64_t)c->capacity : 0;
     if (status) *status = h.status;
     return BGL_OK;
-}
+} BGL_NOTHROW_END
 
 extern "C" int bgl_cache_set_profiling(bgl_cache_t *c, int enable)
-{
+try {
     if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
     BGL_HIP(hipDeviceSynchronize());
     if (enable && c->prof_ev.empty()) {
@@ -1424,19 +1424,19 @@ extern "C" int bgl_cache_set_profiling(bgl_cache_t *c, int enable)
         c->prof_overhead_ms = sum / reps;
     }
     return BGL_OK;
-}
+} BGL_NOTHROW_END
 
 extern "C" int bgl_cache_set_profiling_every(bgl_cache_t *c, int stage, int every)
-{
+try {
     if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
     if (stage < 0 || stage >= BGL_NUM_STAGES) BGL_FAIL(BGL_EINVAL, "unknown stage %d", stage);
     if (every < 1) BGL_FAIL(BGL_EINVAL, "every must be >= 1 (got %d)", every);
     c->prof_every[stage] = every;
     return BGL_OK;
-}
+} BGL_NOTHROW_END
 
 extern "C" int bgl_cache_profile(bgl_cache_t *c, int stage, double *total_ms, int64_t *launches)
-{
+try {
     if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
     if (stage == BGL_STAGE_EVENT_OVERHEAD) {
         if (total_ms) *total_ms = c->prof_overhead_ms;
@@ -1452,4 +1452,4 @@ extern "C" int bgl_cache_profile(bgl_cache_t *c, int stage, double *total_ms, in
     if (total_ms) *total_ms = c->prof_ms[stage];
     if (launches) *launches = c->prof_n[stage];
     return BGL_OK;
-}
+} BGL_NOTHROW_END

@@ -26,6 +26,7 @@
 // rows pass through, packed, on their way over the link.
 #include <chrono>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <thread>
 #include <vector>
@@ -370,7 +371,7 @@ void tier_abort(bgl_host_tier *t)
 extern "C" int bgl_host_tier_create(const void *store, int64_t num_nodes, int32_t row_bytes,
                                     int64_t capacity_rows, int64_t max_batch_rows, int32_t num_threads,
                                     bgl_host_tier_t **out)
-{
+try {
     if (!out) BGL_FAIL(BGL_EINVAL, "out is null");
     *out = nullptr;
     if (!store) BGL_FAIL(BGL_EINVAL, "store is null");
@@ -482,10 +483,10 @@ extern "C" int bgl_host_tier_create(const void *store, int64_t num_nodes, int32_
     });
     *out = t;
     return BGL_OK;
-}
+} BGL_NOTHROW_END
 
 extern "C" int bgl_host_tier_set_copy_engine(bgl_host_tier_t *t, int enable)
-{
+try {
     if (!t) BGL_FAIL(BGL_EINVAL, "tier handle is null");
     if (t->serving) BGL_FAIL(BGL_EINVAL, "host tier: a batch is being served");
     BGL_HIP(hipDeviceSynchronize());  // earlier batches may still use what this call changes
@@ -500,7 +501,9 @@ extern "C" int bgl_host_tier_set_copy_engine(bgl_host_tier_t *t, int enable)
     if (!t->copy_stream) {
         // One copy stream per process, shared by all tiers and never destroyed: a process has only a
         // few hardware queues, and streams that map onto the same one run one after the other.
+        static std::mutex guard;  // (tiers of different callers may get here at the same time)
         static hipStream_t shared_copy_stream = nullptr;
+        std::lock_guard<std::mutex> lk(guard);
         if (!shared_copy_stream) BGL_HIP(hipStreamCreateWithFlags(&shared_copy_stream, hipStreamNonBlocking));
         t->copy_stream = shared_copy_stream;
     }
@@ -518,10 +521,10 @@ extern "C" int bgl_host_tier_set_copy_engine(bgl_host_tier_t *t, int enable)
         }
     }
     return BGL_OK;
-}
+} BGL_NOTHROW_END
 
 extern "C" int bgl_host_tier_destroy(bgl_host_tier_t *t)
-{
+try {
     if (!t) return BGL_OK;
     (void)hipDeviceSynchronize();  // kernels may still read the rows
     delete t->pool;
@@ -542,14 +545,20 @@ extern "C" int bgl_host_tier_destroy(bgl_host_tier_t *t)
     }
     delete t;
     return BGL_OK;
-}
+} BGL_NOTHROW_END
 
 extern "C" int bgl_host_tier_export_state(bgl_host_tier_t *t, int32_t *slot_to_node, uint64_t *tail,
                                           void *buffer_rows)
-{
+try {
     if (!t) BGL_FAIL(BGL_EINVAL, "tier handle is null");
     BGL_HIP(hipDeviceSynchronize());
-    std::vector<int32_t> node((size_t)t->capacity), pos((size_t)t->capacity);
+    std::vector<int32_t> node, pos;
+    try {
+        node.resize((size_t)t->capacity);
+        pos.resize((size_t)t->capacity);
+    } catch (const std::bad_alloc &) {
+        BGL_FAIL(BGL_ENOMEM, "out of host memory");
+    }
     if (t->capacity > 0) {
         BGL_HIP(hipMemcpy(node.data(), t->slot_node, sizeof(int32_t) * (size_t)t->capacity, hipMemcpyDeviceToHost));
         BGL_HIP(hipMemcpy(pos.data(), t->slot_pos, sizeof(int32_t) * (size_t)t->capacity, hipMemcpyDeviceToHost));
@@ -565,11 +574,11 @@ extern "C" int bgl_host_tier_export_state(bgl_host_tier_t *t, int32_t *slot_to_n
         }
     }
     return BGL_OK;
-}
+} BGL_NOTHROW_END
 
 extern "C" int bgl_host_tier_stats(bgl_host_tier_t *t, uint64_t *lookups, uint64_t *hits, double *copy_ms,
                                    uint64_t *batches, int32_t *threads)
-{
+try {
     if (!t) BGL_FAIL(BGL_EINVAL, "tier handle is null");
     if (lookups) *lookups = t->lookups;
     if (hits) *hits = t->hits;
@@ -577,4 +586,4 @@ extern "C" int bgl_host_tier_stats(bgl_host_tier_t *t, uint64_t *lookups, uint64
     if (batches) *batches = t->batches;
     if (threads) *threads = t->pool->threads();
     return BGL_OK;
-}
+} BGL_NOTHROW_END

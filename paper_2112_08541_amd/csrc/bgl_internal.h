@@ -8,6 +8,8 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <exception>
+#include <new>
 
 #include "bgl.h"
 
@@ -31,6 +33,25 @@ void set_error(const char *fmt, ...);
             return e__ == hipErrorOutOfMemory ? BGL_ENOMEM : BGL_EHIP;              \
         }                                                                           \
     } while (0)
+
+// The C ABI promises that nothing throws: every entry point is a function-try-block whose
+// handler returns this (called inside the handler: it looks at the exception in flight).
+inline int caught()
+{
+    try {
+        throw;
+    } catch (const std::bad_alloc &) {
+        set_error("out of host memory");
+        return BGL_ENOMEM;
+    } catch (const std::exception &e) {
+        set_error("unexpected exception: %s", e.what());
+        return BGL_EHIP;
+    } catch (...) {
+        set_error("unexpected exception");
+        return BGL_EHIP;
+    }
+}
+#define BGL_NOTHROW_END catch (...) { return ::bgl::caught(); }
 
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

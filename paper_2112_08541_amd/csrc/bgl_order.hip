@@ -357,7 +357,7 @@ int check_order_args(const bgl_graph_t *g, const int32_t *train_nodes, int64_t n
 
 extern "C" int bgl_order_bfs_sequence(const bgl_graph_t *g, const int32_t *train_nodes, int64_t num_train,
                                       int64_t root, int32_t *seq, void *stream)
-{
+try {
     int rc = check_order_args(g, train_nodes, num_train);
     if (rc != BGL_OK) return rc;
     if (root < 0 || root >= g->num_nodes) BGL_FAIL(BGL_EINVAL, "root is outside [0, num_nodes)");
@@ -370,7 +370,7 @@ extern "C" int bgl_order_bfs_sequence(const bgl_graph_t *g, const int32_t *train
     BGL_HIP(hipMemcpyAsync(seq, w.seq, num_train * 4, hipMemcpyDeviceToHost, st));
     BGL_HIP(hipStreamSynchronize(st));
     return BGL_OK;
-}
+} BGL_NOTHROW_END
 
 namespace {
 
@@ -428,7 +428,7 @@ void merge_sequences(const std::vector<std::vector<int32_t>> &seqs, int32_t num_
 extern "C" int bgl_order_proximity(const bgl_graph_t *g, const int32_t *train_nodes, int64_t num_train,
                                    int32_t num_sequences, const int64_t *roots, const int64_t *shifts,
                                    int64_t num_out, int32_t *order, void *stream)
-{
+try {
     int rc = check_proximity_args(g, train_nodes, num_train, num_sequences, roots, shifts);
     if (rc != BGL_OK) return rc;
     if (num_out < 0 || num_out > num_train) BGL_FAIL(BGL_EINVAL, "num_out must be in [0, num_train]");
@@ -438,14 +438,14 @@ extern "C" int bgl_order_proximity(const bgl_graph_t *g, const int32_t *train_no
     if (rc != BGL_OK) return rc;
     merge_sequences(seqs, num_sequences, shifts, num_train, g->num_nodes, num_out, order);
     return BGL_OK;
-}
+} BGL_NOTHROW_END
 
 extern "C" int bgl_order_choose_sequences(const bgl_graph_t *g, const int32_t *train_nodes, int64_t num_train,
                                           int32_t max_sequences, const int64_t *roots, const int64_t *shifts,
                                           int32_t batch, const int32_t *labels, int32_t num_classes,
                                           double threshold, int32_t *chosen, double *mean_tv_per_count,
                                           int32_t *order, void *stream)
-{
+try {
     int rc = check_proximity_args(g, train_nodes, num_train, max_sequences, roots, shifts);
     if (rc != BGL_OK) return rc;
     if (!labels || !chosen || !order) BGL_FAIL(BGL_EINVAL, "labels, chosen and order must not be null");
@@ -462,11 +462,11 @@ extern "C" int bgl_order_choose_sequences(const bgl_graph_t *g, const int32_t *t
         if (mean_tv <= threshold) break;   // `order` holds the order for this count
     }
     return BGL_OK;
-}
+} BGL_NOTHROW_END
 
 extern "C" int bgl_order_shuffling_error(const int32_t *order, int64_t n, int32_t batch, const int32_t *labels,
                                          int64_t num_nodes, int32_t num_classes, double *mean_tv, double *max_tv)
-{
+try {
     if (!order || !labels || !mean_tv || !max_tv) BGL_FAIL(BGL_EINVAL, "null argument");
     if (n < 1 || batch < 1 || num_classes < 1 || num_nodes < 1) BGL_FAIL(BGL_EINVAL, "sizes must be positive");
     std::vector<int64_t> global((size_t)num_classes, 0), local((size_t)num_classes);
@@ -493,4 +493,4 @@ extern "C" int bgl_order_shuffling_error(const int32_t *order, int64_t n, int32_
     *mean_tv = sum / (double)batches;
     *max_tv = mx;
     return BGL_OK;
-}
+} BGL_NOTHROW_END

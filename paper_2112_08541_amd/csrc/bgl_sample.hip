@@ -390,20 +390,20 @@ void launch_sample_g(int G, const bgl_graph *g, int blocks, hipStream_t st,
 
 extern "C" int bgl_sample_workspace_bytes(int32_t num_seeds, const int32_t *fanouts,
                                           int32_t num_hops, int64_t num_nodes, size_t *bytes)
-{
+try {
     if (!bytes) BGL_FAIL(BGL_EINVAL, "bytes is null");
     Layout L;
     int rc = make_layout(num_seeds, fanouts, num_hops, num_nodes, L);
     if (rc != BGL_OK) return rc;
     *bytes = L.bytes;
     return BGL_OK;
-}
+} BGL_NOTHROW_END
 
 extern "C" int bgl_sample_khop(const bgl_graph_t *g, const int32_t *seeds, int32_t num_seeds,
                                const int32_t *fanouts, int32_t num_hops, uint64_t rng_seed,
                                void *workspace, size_t workspace_bytes, bgl_subgraph_t *out,
                                int32_t *counts_host, void *stream)
-{
+try {
     if (!g) BGL_FAIL(BGL_EINVAL, "graph handle is null");
     if (!seeds) BGL_FAIL(BGL_EINVAL, "seeds is null");
     if (!out) BGL_FAIL(BGL_EINVAL, "out is null");
@@ -479,4 +479,4 @@ extern "C" int bgl_sample_khop(const bgl_graph_t *g, const int32_t *seeds, int32
         BGL_HIP(hipMemcpyAsync(counts_host, cnt, sizeof(int32_t) * BGL_COUNTS_LEN,
                                hipMemcpyDeviceToHost, st));
     return BGL_OK;
-}
+} BGL_NOTHROW_END
