@@ -49,54 +49,56 @@ struct CacheDev {          // device-resident scalars
 }  // namespace
 
 struct bgl_cache {
-    int64_t capacity;
-    int32_t row_bytes;
-    int64_t num_nodes;
-    const char *features;   // device-visible backing store
-    bool features_in_hbm;   // backing store is device memory (then the fetch is an HBM gather)
-    int device;
-    char *buffer;           // capacity * row_bytes
-    uint64_t *table;        // num_buckets * BUCKET words
-    uint32_t num_buckets;   // power of two
-    int32_t *slot_to_node;  // capacity
-    uint32_t *slot_to_entry;
-    CacheDev *dev;
-    int32_t *mbs;           // per-tile miss counts of the most recent lookup (mbs_cap of them), then mbs_cap prefixes
-    int64_t mbs_cap;
-    int32_t *hit_pos;       // hits of the most recent lookup: hit_cap positions, then hit_cap slots
-    int64_t hit_cap;
-    int64_t last_n;         // n of the most recent lookup
-    int32_t *mpos_copy[2];  // early lookups: the library's own copy of miss_pos, alternating between calls
-    int64_t mpos_cap[2];
-    uint64_t lookup_calls;
-    uint64_t insert_calls;  // FIFO updates enqueued so far (selects the live copy of tail)
-    hipStream_t own_side;   // the miss fetch's stream when the caller names none; created on first use
-                            // (a process has few hardware queues: a stream that is never used should not take one)
+    int64_t capacity = 0;
+    int32_t row_bytes = 0;
+    int64_t num_nodes = 0;
+    const char *features = nullptr;  // device-visible backing store
+    bool features_in_hbm = false;    // backing store is device memory (then the fetch is an HBM gather)
+    int device = 0;
+    char *buffer = nullptr;          // capacity * row_bytes
+    uint64_t *table = nullptr;       // num_buckets * BUCKET words
+    uint32_t num_buckets = 0;        // power of two
+    int32_t *slot_to_node = nullptr;  // capacity
+    uint32_t *slot_to_entry = nullptr;
+    CacheDev *dev = nullptr;
+    int32_t *mbs = nullptr;          // per-tile miss counts of the most recent lookup (mbs_cap of them), then mbs_cap prefixes
+    int64_t mbs_cap = 0;
+    int32_t *hit_pos = nullptr;      // hits of the most recent lookup: hit_cap positions, then hit_cap slots
+    int64_t hit_cap = 0;
+    int64_t last_n = 0;              // n of the most recent lookup
+    int32_t *mpos_copy[2] = {nullptr, nullptr};  // early lookups: the library's own copy of miss_pos, alternating between calls
+    int64_t mpos_cap[2] = {0, 0};
+    uint64_t lookup_calls = 0;
+    uint64_t insert_calls = 0;       // FIFO updates enqueued so far (selects the live copy of tail)
+    hipStream_t own_side = nullptr;  // the miss fetch's stream when the caller names none; created on first use
+                                     // (a process has few hardware queues: a stream that is never used should not take one)
     // Ordering between streams.  ev_listed: lists and hit rows of the last lookup are complete
     // (recorded on that lookup's main stream); ev_miss: its miss rows are complete (recorded on
     // the stream the fetch ran on); ev_map: the last FIFO update is complete (recorded on the
     // update's stream when that is not the lookup's main stream).
-    hipEvent_t ev_listed, ev_miss, ev_map;
-    hipEvent_t ev_ids;      // the lists of a lookup are complete (tiered: the missed ids have reached the host)
-    hipStream_t last_main, fetch_stream, map_stream;
-    bool fetch_pending;     // ev_miss marks a miss fetch that later work may have to wait for
-    bool fetch_reads_caller_lists;  // that fetch reads the caller's miss_pos (not the library's copy)
-    bool map_pending;       // ev_map marks a FIFO update the next lookup has to wait for
-    bool ev_listed_valid;   // a lookup has recorded ev_listed
-    bool write_through;     // the miss fetch also fills the cache buffer (see bgl_cache_set_write_through)
-    bool awaiting_insert;   // write-through: a lookup's misses are in the buffer but not in the map yet
-    const void *wt_ids, *wt_miss_pos;  // arguments of that lookup
+    hipEvent_t ev_listed = nullptr, ev_miss = nullptr, ev_map = nullptr;
+    hipEvent_t ev_ids = nullptr;     // the lists of a lookup are complete (tiered: the missed ids have reached the host)
+    hipStream_t last_main = nullptr, fetch_stream = nullptr, map_stream = nullptr;
+    bool fetch_pending = false;      // ev_miss marks a miss fetch that later work may have to wait for
+    bool fetch_reads_caller_lists = true;  // that fetch reads the caller's miss_pos (not the library's copy)
+    bool map_pending = false;        // ev_map marks a FIFO update the next lookup has to wait for
+    bool ev_listed_valid = false;    // a lookup has recorded ev_listed
+    bool write_through = false;      // the miss fetch also fills the cache buffer (see bgl_cache_set_write_through)
+    bool awaiting_insert = false;    // write-through: a lookup's misses are in the buffer but not in the map yet
+    const void *wt_ids = nullptr, *wt_miss_pos = nullptr;  // arguments of that lookup
     // profiling
-    unsigned profiling;     // bit s set: stage s is timed
-    hipEvent_t timed_start, timed_stop;  // events the next launch() hands to the kernel dispatch itself
+    unsigned profiling = 0;          // bit s set: stage s is timed
+    hipEvent_t timed_start = nullptr, timed_stop = nullptr;  // events the next launch() hands to the kernel dispatch itself
     std::vector<hipEvent_t> prof_ev;  // pairs
     struct Rec { int stage; int ev; };
     std::vector<Rec> prof_rec;
-    double prof_overhead_ms;  // event pair around an (almost) empty kernel
-    int64_t prof_dropped;     // timed launches that got no events (event creation failed)
+    double prof_overhead_ms = 0;     // event pair around an (almost) empty kernel
+    int64_t prof_dropped = 0;        // timed launches that got no events (event creation failed)
     int prof_every[BGL_NUM_STAGES];  // stage s is timed only in calls whose ordinal is a multiple of this
-    double prof_ms[BGL_NUM_STAGES];
-    int64_t prof_n[BGL_NUM_STAGES];
+    double prof_ms[BGL_NUM_STAGES] = {};
+    int64_t prof_n[BGL_NUM_STAGES] = {};
+
+    bgl_cache() { std::fill(prof_every, prof_every + BGL_NUM_STAGES, 1); }
 };
 
 namespace {
@@ -736,28 +738,6 @@ try {
     c->num_nodes = num_nodes;
     c->features = feat_dev;
     c->features_in_hbm = attr.type == hipMemoryTypeDevice;
-    c->profiling = 0;
-    c->prof_dropped = 0;
-    for (int st = 0; st < BGL_NUM_STAGES; ++st) c->prof_every[st] = 1;
-    c->timed_start = c->timed_stop = nullptr;
-    c->fetch_pending = false;
-    c->fetch_reads_caller_lists = true;
-    c->map_pending = false;
-    c->ev_listed_valid = false;
-    c->last_main = c->fetch_stream = c->map_stream = nullptr;
-    c->write_through = false;
-    c->awaiting_insert = false;
-    c->wt_ids = c->wt_miss_pos = nullptr;
-    for (int s = 0; s < BGL_NUM_STAGES; ++s) { c->prof_ms[s] = 0; c->prof_n[s] = 0; }
-    c->mbs = nullptr;
-    c->mbs_cap = 0;
-    c->hit_pos = nullptr;
-    c->hit_cap = 0;
-    c->last_n = 0;
-    c->mpos_copy[0] = c->mpos_copy[1] = nullptr;
-    c->mpos_cap[0] = c->mpos_cap[1] = 0;
-    c->lookup_calls = 0;
-    c->insert_calls = 0;
     // load <= 1/2 of the 15 usable words per bucket
     uint64_t nbk = 1;
     while (nbk * 15 < (uint64_t)capacity_rows * 2) nbk <<= 1;
