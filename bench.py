@@ -67,8 +67,9 @@ def parse_args():
                          "nodes) between the GPU cache and a feature store in ordinary host memory; "
                          "reported beside the headline, not part of it")
     ap.add_argument("--tier-threads", type=int, default=0, help="copy threads of that tier (0 = min(cores, 16) - 1)")
-    ap.add_argument("--cpu-batches", type=int, default=100,
-                    help="batches of the same workload the oracle is timed on")
+    ap.add_argument("--cpu-batches", type=int, default=200,
+                    help="batches of the same workload the oracle is timed on (10-30 s of CPU work on the "
+                         "configurations with 100-200 batches)")
     return ap.parse_args()
 
 
