@@ -14,7 +14,7 @@ import ctypes as C
 import dataclasses
 import os
 import subprocess
-from typing import List, Optional
+from typing import Optional
 
 import numpy as np
 

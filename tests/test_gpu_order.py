@@ -2,7 +2,6 @@
 the queue-order BFS sequence and the merged order are unique, so the comparison
 is exact; the shuffling error is compared to 1e-12 (a mean of a few
 hundred sums of ratios of integers, same operation order on both sides)."""
-import dataclasses
 import os
 import time
 
