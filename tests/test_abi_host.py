@@ -33,6 +33,23 @@ def test_library_exports_every_declared_symbol(L):
         assert hasattr(L, n), n
 
 
+def test_no_entry_point_lets_an_exception_out():
+    """The header promises that nothing throws: every int-returning entry point is a
+    function-try-block that ends in the library's catch-all."""
+    csrc = os.path.join(ROOT, "paper_2112_08541_amd", "csrc")
+    seen = 0
+    for name in sorted(os.listdir(csrc)):
+        if not name.endswith(".hip"):
+            continue
+        text = open(os.path.join(csrc, name)).read()
+        for m in re.finditer(r'^extern "C" int (bgl_[a-z_]+)\([^;{]*?\)\n(\S+)', text, re.M):
+            assert m.group(2) == "try", (name, m.group(1))
+            end = text.index("\n}", m.end())
+            assert text[end:end + 20].startswith("\n} BGL_NOTHROW_END"), (name, m.group(1))
+            seen += 1
+    assert seen == len(declared_symbols()) - 1      # all but bgl_last_error, which returns a pointer
+
+
 def test_the_five_entry_points_are_declared():
     names = declared_symbols()
     for n in ("bgl_graph_load_csr", "bgl_sample_khop", "bgl_cache_create",
