@@ -66,7 +66,7 @@ def parse_args():
                     help="also time the same batches with a FIFO tier in host memory (this fraction of the "
                          "nodes) between the GPU cache and a feature store in ordinary host memory; "
                          "reported beside the headline, not part of it")
-    ap.add_argument("--tier-threads", type=int, default=0, help="copy threads of that tier (0 = min(cores, 16) - 1)")
+    ap.add_argument("--tier-threads", type=int, default=0, help="copy threads of the staging ring and of that tier (0 = three quarters of min(cores, 16))")
     ap.add_argument("--cpu-batches", type=int, default=200,
                     help="batches of the same workload the oracle is timed on (10-30 s of CPU work on the "
                          "configurations with 100-200 batches)")
@@ -214,7 +214,7 @@ def main():
     # "auto" decides by that rule, "trial" times both in the warm-up (each from an empty scratch
     # cache, untimed for the benchmark) and keeps the faster one.
     miss_path = args.miss_path
-    host_threads = args.tier_threads or max(1, min(os.cpu_count() or 2, 16) - 1)
+    host_threads = args.tier_threads or max(1, min(os.cpu_count() or 2, 16) * 3 // 4)
     eligible = pipe.cap >= 65536 and feat_dev is None
     if miss_path == "auto":
         miss_path = "staged" if (eligible and host_threads >= 8) else "zero_copy"

@@ -339,7 +339,9 @@ int bgl_cache_set_profiling_every(bgl_cache_t *c, int stage, int every);
  *                   rows, the staging rows (capacity_rows > 0) another
  *                   2 * max_batch_rows
  *   num_threads     host threads that copy rows (the calling thread drives the
- *                   GPU meanwhile); 0 = min(cores, 16) - 1
+ *                   GPU meanwhile, and packs too when it has nothing to send);
+ *                   0 = three quarters of min(cores, 16): more threads than that
+ *                   take host memory bandwidth from the transfers they feed
  * Errors: BGL_EINVAL (null store, sizes out of range, row_bytes not a multiple
  * of 16), BGL_ENOMEM (page-locked, host or device allocation failed), BGL_EHIP.
  */
