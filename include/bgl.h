@@ -281,6 +281,25 @@ int bgl_cache_stats(bgl_cache_t *c, uint64_t *lookups, uint64_t *hits, uint64_t 
                     uint64_t *evictions, int32_t *status);
 
 /*
+ * Cost of the cache map's lookups (synchronises the device).  The paper's cache
+ * engine serves a whole training job (Sec. 3.2.1, Sec. 4: every insertion evicts
+ * the occupant of the next position from the map), so what a lookup costs must
+ * not depend on how many insertions and evictions the map has seen.  The map is
+ * a hash table of 128-byte buckets; a lookup reads its id's home bucket and goes
+ * on to the next one only while the bucket says that some live entry was pushed
+ * past it by an insertion that found it full.
+ *   ids_looked_up      ids of all lookups since creation
+ *   bucket_lines_read  bucket lines (128 bytes each) those lookups read; the
+ *                      ratio of the two is the mean length of a lookup
+ *   num_buckets        buckets of the map (15 entries each)
+ *   buckets_passed     buckets that some live entry is pushed past right now
+ *   passes             (live entry, bucket it is pushed past) pairs right now
+ * Any output pointer may be NULL.  Errors: BGL_EINVAL (null handle), BGL_EHIP.
+ */
+int bgl_cache_map_stats(bgl_cache_t *c, uint64_t *ids_looked_up, uint64_t *bucket_lines_read,
+                        uint64_t *num_buckets, uint64_t *buckets_passed, uint64_t *passes);
+
+/*
  * Per-kernel timing for measurements.  `stage_mask` has bit (1 << stage) set for
  * every stage the cache shall time (0 = off, BGL_ALL_STAGES = all).  A stage that
  * is one kernel per launch (all but BGL_STAGE_MISS_LIST and BGL_STAGE_LINK_COPY) is timed by the kernel

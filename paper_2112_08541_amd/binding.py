@@ -31,6 +31,7 @@ EXPORTS = [
     "bgl_sample_khop", "bgl_cache_create", "bgl_cache_destroy", "bgl_cache_lookup_gather",
     "bgl_cache_lookup_gather_early",
     "bgl_cache_insert_fifo", "bgl_cache_set_write_through", "bgl_cache_wait_rows", "bgl_cache_wait_lists", "bgl_cache_export_state", "bgl_cache_stats",
+    "bgl_cache_map_stats",
     "bgl_cache_set_profiling", "bgl_cache_profile", "bgl_cache_set_profiling_every",
     "bgl_host_tier_create", "bgl_host_tier_destroy", "bgl_host_tier_set_copy_engine", "bgl_cache_lookup_gather_tiered",
     "bgl_host_tier_export_state", "bgl_host_tier_stats",
@@ -86,6 +87,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     L.bgl_cache_export_state.argtypes = [vp, vp, C.POINTER(u64), vp]
     L.bgl_cache_stats.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(u64),
                                   C.POINTER(u64), C.POINTER(i32)]
+    L.bgl_cache_map_stats.argtypes = [vp] + [C.POINTER(u64)] * 5
     L.bgl_cache_set_profiling.argtypes = [vp, ci]
     L.bgl_cache_profile.argtypes = [vp, ci, C.POINTER(C.c_double), C.POINTER(i64)]
     L.bgl_cache_set_profiling_every.argtypes = [vp, ci, ci]
@@ -338,6 +340,15 @@ class Cache:
         _check(lib().bgl_cache_stats(self._h, *[C.byref(v) for v in vals], C.byref(status)))
         return dict(lookups=vals[0].value, hits=vals[1].value, inserts=vals[2].value,
                     evictions=vals[3].value, status=status.value)
+
+    def map_stats(self):
+        """bgl_cache_map_stats: what the map's lookups have cost so far and how many buckets
+        a lookup would walk past right now."""
+        vals = [C.c_uint64(0) for _ in range(5)]
+        _check(lib().bgl_cache_map_stats(self._h, *[C.byref(v) for v in vals]))
+        ids, lines, nb, passed, passes = (v.value for v in vals)
+        return dict(ids_looked_up=ids, bucket_lines_read=lines, num_buckets=nb, buckets_passed=passed,
+                    passes=passes, lines_per_id=(lines / ids if ids else 0.0))
 
     def set_profiling(self, stages=True) -> None:
         """stages: False/True (none/all) or an iterable of stage names to bracket with events."""

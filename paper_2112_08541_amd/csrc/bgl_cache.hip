@@ -6,17 +6,24 @@
 //
 // Cache map: open addressing over 128-byte buckets.  A bucket is 16 64-bit
 // words = exactly one cache line: words 0..14 hold (node id << 32 | slot) or
-// EMPTY, word 15 is a sticky overflow mark that is set when an insertion had to
-// walk past the full bucket.  A lookup reads its id's bucket (one line) and ends
-// at the first bucket without the overflow mark (one id per lane: a wavefront
-// keeps 64 independent line reads in flight; a 16-lanes-per-id lookup that found
-// the id with a ballot was measured at half the speed, the lookup being latency
-// bound).  An insertion is done by a group of 16 lanes that reads the bucket with
-// one coalesced request, picks a free word with a wavefront ballot and claims it
-// with a CAS.  Because the mark is only needed for full buckets (rare at load
-// <= 1/2), evictions simply blank their word: no tombstones, no rebuilds.
-// slot_to_entry[slot] remembers the word that maps a slot's occupant, so an
-// eviction needs no search.
+// EMPTY, word 15 counts the live entries that rest in a later bucket although
+// their id hashes to this one or to an earlier one, i.e. whose walk from their
+// home bucket to their resting bucket passed over this bucket.  A lookup reads
+// its id's bucket (one line) and goes on to the next bucket only while that
+// count is not zero (one id per lane: a wavefront keeps 64 independent line
+// reads in flight; a 16-lanes-per-id lookup that found the id with a ballot was
+// measured at half the speed, the lookup being latency bound).  An insertion is
+// done by a group of 16 lanes that reads the bucket with one coalesced request,
+// picks a free word with a wavefront ballot and claims it with a CAS; every full
+// bucket it walks past gets its count raised by one.  An eviction blanks its
+// word (slot_to_entry[slot] remembers the word that maps a slot's occupant, so
+// no search) and lowers the counts of the buckets between the evicted id's home
+// bucket (recomputed from the id) and that word's bucket: what one insertion
+// added, the eviction of the same entry takes away.  So the counts always say
+// exactly which buckets a live entry was pushed past, however long the cache
+// has been churning under the FIFO policy: no tombstones, no rebuilds, and the
+// length of a lookup depends on the load only (full buckets are rare at load
+// <= 1/2 of 15 words per bucket), not on the cache's age.
 #include <algorithm>
 #include <vector>
 
@@ -30,7 +37,7 @@ namespace {
 using namespace bgl;
 
 constexpr uint64_t EMPTY64 = ~0ull;
-constexpr int BUCKET = 16;       // 64-bit words per bucket (15 entries + overflow mark)
+constexpr int BUCKET = 16;       // 64-bit words per bucket (15 entries + the count of entries pushed past it)
 constexpr int KEYS_PER_TILE = 256;  // ids per workgroup in probe / miss-list kernels
 constexpr int PROF_RING = 4096;
 
@@ -44,6 +51,8 @@ struct CacheDev {          // device-resident scalars
     long long n_miss_gen[2];  // the same, kept per call parity for early lookups (the previous call's fetch still reads its own)
     long long n_hit_last;   // hit count of the most recent lookup
     int status;
+    unsigned long long probe_lines;  // bucket lines read by all map lookups so far
+    unsigned long long census[2];    // bgl_cache_map_stats: buckets with a count, sum of the counts
 };
 
 }  // namespace
@@ -61,7 +70,8 @@ struct bgl_cache {
     int32_t *slot_to_node = nullptr;  // capacity
     uint32_t *slot_to_entry = nullptr;
     CacheDev *dev = nullptr;
-    int32_t *mbs = nullptr;          // per-tile miss counts of the most recent lookup (mbs_cap of them), then mbs_cap prefixes
+    int32_t *mbs = nullptr;          // per-tile miss counts of the most recent lookup (mbs_cap of them), then mbs_cap prefixes,
+                                     // then mbs_cap counts of bucket lines read
     int64_t mbs_cap = 0;
     int32_t *hit_pos = nullptr;      // hits of the most recent lookup: hit_cap positions, then hit_cap slots
     int64_t hit_cap = 0;
@@ -106,7 +116,7 @@ namespace {
 // ------------------------------------------------------------------ kernels
 __global__ void k_fill_u64(uint64_t *p, int64_t n, uint64_t v, int mark_stride)
 {
-    // every mark_stride-th word (the overflow marks) starts at 0
+    // every mark_stride-th word (the buckets' pushed-past counts) starts at 0
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (; i < n; i += stride) p[i] = ((i % mark_stride) == mark_stride - 1) ? 0ull : v;
@@ -121,19 +131,22 @@ __global__ void k_fill_i32(int32_t *p, int64_t n, int32_t v)
 
 // Map lookup, one id per lane.  A lane reads its id's whole bucket (one 128-byte
 // line, eight 16-byte loads issued together) and compares the 15 entries in
-// registers; the chain continues only past a bucket that carries the overflow
-// mark.  A wavefront thus keeps 64 independent line reads in flight, which is
+// registers; the chain continues only past a bucket whose pushed-past count is
+// not zero.  A wavefront thus keeps 64 independent line reads in flight, which is
 // what a latency-bound random lookup needs.  The misses of a wavefront are
-// counted with one ballot.
+// counted with one ballot; the bucket lines read are summed per workgroup for
+// the map statistics (the list kernel adds the sums up).
 __global__ __launch_bounds__(KEYS_PER_TILE) void k_probe(const int32_t *__restrict__ ids, int64_t n,
                                                          int64_t num_nodes,
                                                          const uint64_t *__restrict__ table,
                                                          uint32_t bucket_mask, int32_t *out_slot,
-                                                         int32_t *mbs, CacheDev *dev)
+                                                         int32_t *mbs, int32_t *tile_lines, CacheDev *dev)
 {
     __shared__ int sh_miss[KEYS_PER_TILE / kWave];
+    __shared__ int sh_lines[KEYS_PER_TILE / kWave];
     const int64_t i = (int64_t)blockIdx.x * KEYS_PER_TILE + threadIdx.x;
     int slot = -1;
+    int lines = 0;
     if (i < n) {
         const int32_t id = ids[i];
         if (id < 0 || (int64_t)id >= num_nodes) {
@@ -155,20 +168,28 @@ __global__ __launch_bounds__(KEYS_PER_TILE) void k_probe(const int32_t *__restri
                         found = true;
                     }
                 }
-                if (found || w[BUCKET / 2 - 1].y == 0) break;  // mark clear: nothing was pushed past this bucket
+                ++lines;
+                if (found || w[BUCKET / 2 - 1].y == 0) break;  // count zero: no live entry was pushed past this bucket
                 b = (b + 1) & bucket_mask;
             }
         }
         out_slot[i] = slot;
     }
     const uint64_t missed = __ballot(i < n && slot < 0);
-    if ((threadIdx.x & (kWave - 1)) == 0) sh_miss[threadIdx.x / kWave] = __popcll(missed);
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) lines += __shfl_down(lines, d, kWave);
+    if ((threadIdx.x & (kWave - 1)) == 0) {
+        sh_miss[threadIdx.x / kWave] = __popcll(missed);
+        sh_lines[threadIdx.x / kWave] = lines;
+    }
     __syncthreads();
     if (threadIdx.x == 0) {
-        int t = 0;
+        int t = 0, ln = 0;
 #pragma unroll
-        for (int k = 0; k < KEYS_PER_TILE / kWave; ++k) t += sh_miss[k];
+        for (int k = 0; k < KEYS_PER_TILE / kWave; ++k) { t += sh_miss[k]; ln += sh_lines[k]; }
         mbs[blockIdx.x] = t;
+        tile_lines[blockIdx.x] = ln;  // (summed by the list kernel: one atomic per workgroup on one counter
+                                      // costs this kernel a third of its time)
     }
 }
 
@@ -199,6 +220,7 @@ __global__ __launch_bounds__(KEYS_PER_TILE) void k_split_list(const int32_t *__r
                                                               int64_t n,
                                                               const int32_t *__restrict__ mbs,
                                                               const int32_t *__restrict__ tile_prefix,
+                                                              const int32_t *__restrict__ tile_lines,
                                                               int32_t *miss_pos, int32_t *hit_pos,
                                                               int32_t *hit_slot, CacheDev *dev,
                                                               int64_t *n_hit_host,
@@ -234,8 +256,14 @@ __global__ __launch_bounds__(KEYS_PER_TILE) void k_split_list(const int32_t *__r
         hit_pos[i - mrank] = (int32_t)i;
         hit_slot[i - mrank] = slot;
     }
-    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+    if (blockIdx.x != gridDim.x - 1) return;
+    // the last workgroup publishes the call's counters
+    int lines = 0, all_lines;
+    for (int t = threadIdx.x; t < (int)gridDim.x; t += KEYS_PER_TILE) lines += tile_lines[t];
+    (void)block_excl_scan<KEYS_PER_TILE>(lines, sh_scan, all_lines);
+    if (threadIdx.x == 0) {
         const long long n_miss = sh_base + tot;
+        dev->probe_lines += (unsigned long long)all_lines;
         dev->n_miss_last = n_miss;
         dev->n_miss_gen[gen] = n_miss;
         dev->n_hit_last = n - n_miss;
@@ -464,11 +492,16 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_rows(
 }
 
 // Map update: 16 lanes per inserted row.  Evict the slot's occupant (blank its
-// word, found through slot_to_entry), then read the new id's bucket with one
-// coalesced request, pick a free word with a wavefront ballot and claim it with
-// a CAS.  Bucket words are read with device-scope atomic loads so that the retry
-// after a lost CAS sees the winner's word.  (One row per lane was measured too:
-// no faster, the update is bound by its random lines, not by lane count.)
+// word, found through slot_to_entry, and take one off the pushed-past count of
+// every bucket from the evicted id's home bucket up to the word's bucket), then
+// read the new id's bucket with one coalesced request, pick a free word with a
+// wavefront ballot and claim it with a CAS; a bucket without a free word gets
+// one added to its count before the group moves on.  Counts change by atomic
+// adds only and no lookup runs beside an update, so after the launch every
+// count is exact whatever the order of the groups.  Bucket words are read with
+// device-scope atomic loads so that the retry after a lost CAS sees the winner's
+// word.  (One row per lane was measured too: no faster, the update is bound by
+// its random lines, not by lane count.)
 __device__ __forceinline__ void insert_map_part(
     int64_t block, const int32_t *__restrict__ ids, const int32_t *__restrict__ miss_pos,
     int64_t n_miss, int64_t start, unsigned long long tail, int64_t capacity, int64_t num_nodes,
@@ -482,9 +515,14 @@ __device__ __forceinline__ void insert_map_part(
     const int64_t slot = (int64_t)((tail + (unsigned long long)r) % (unsigned long long)capacity);
     const int32_t key = ids[miss_pos[r]];
     const int32_t old = slot_to_node[slot];
-    if (old >= 0 && l == 0)
-        __hip_atomic_store(&table[slot_to_entry[slot]], EMPTY64, __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
+    if (old >= 0 && l == 0) {
+        const uint32_t word = slot_to_entry[slot];
+        __hip_atomic_store(&table[word], EMPTY64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // the buckets this entry had been pushed past (none for an entry in its home bucket)
+        const uint32_t rest = word / BUCKET;
+        for (uint32_t b = hash32((uint32_t)old) & bucket_mask; b != rest; b = (b + 1) & bucket_mask)
+            atomicAdd((unsigned long long *)&table[(size_t)b * BUCKET + (BUCKET - 1)], ~0ull);  // -1
+    }
     if (key < 0 || (int64_t)key >= num_nodes) {
         // reported by the lookup already: the slot's row will be overwritten, so
         // leave the slot unmapped rather than mapped to the wrong bytes
@@ -519,9 +557,8 @@ __device__ __forceinline__ void insert_map_part(
                 done = true;
             }
         } else {
-            if (l == BUCKET - 1 && e == 0)
-                __hip_atomic_store(&table[(size_t)b * BUCKET + l], 1ull, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
+            // full: this entry will rest beyond bucket b (its eviction takes the one off again)
+            if (l == BUCKET - 1) atomicAdd((unsigned long long *)&table[(size_t)b * BUCKET + l], 1ull);
             b = (b + 1) & bucket_mask;
         }
     }
@@ -612,6 +649,20 @@ __global__ void k_advance_tail(CacheDev *dev, int64_t n_miss_arg, int par)
 }
 
 __global__ void k_noop() {}
+
+// Census of the pushed-past counts for bgl_cache_map_stats: how many buckets a
+// lookup would walk past, and how many (entry, bucket) pairs that is.
+__global__ void k_map_census(const uint64_t *__restrict__ table, uint32_t num_buckets, CacheDev *dev)
+{
+    unsigned long long nz = 0, sum = 0;
+    for (uint32_t b = blockIdx.x * blockDim.x + threadIdx.x; b < num_buckets; b += gridDim.x * blockDim.x) {
+        const uint64_t cnt = table[(size_t)b * BUCKET + (BUCKET - 1)];
+        nz += cnt != 0;
+        sum += cnt;
+    }
+    if (nz) atomicAdd(&dev->census[0], nz);
+    if (sum) atomicAdd(&dev->census[1], sum);
+}
 
 // ------------------------------------------------------------------ host helpers
 // Stage timers.  A stage that is one kernel is timed by the dispatch itself: the
@@ -802,6 +853,16 @@ try {
 
 namespace {
 
+// The lists one lookup leaves for its own later kernels: per-tile miss counts (mbs_cap of them)
+// followed by mbs_cap prefixes and mbs_cap counts of bucket lines read, and the hits as hit_cap
+// positions followed by hit_cap slots.
+struct LookupLists {
+    int32_t *mbs;
+    int64_t mbs_cap;
+    int32_t *hit_pos;
+    int64_t hit_cap;
+};
+
 // First half of a lookup: map lookup and lists on stream ls, with a host tier its
 // lookup for the misses (followed by ev_ids), then the hit gather on stream ms,
 // ev_listed.  ls == ms unless the lookup runs early (see the tiered call): then
@@ -810,22 +871,23 @@ namespace {
 // fetch while this one's lists are written.
 int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, int32_t *out_slot,
                  int32_t *miss_pos, int64_t *n_hit_dev, hipStream_t ms, hipStream_t ls, bgl_host_tier *tier,
-                 const int32_t **mpos_used, int *gen_used)
+                 const int32_t **mpos_used, int *gen_used, const LookupLists *fixed = nullptr)
 {
     const bool early = ls != ms;
     const int gen = (int)(c->lookup_calls & 1);  // which copy of the per-call device state this call owns
     *gen_used = gen;
     const int64_t tiles = bgl::ceil_div(n, KEYS_PER_TILE);
-    if (tiles + 1 > c->mbs_cap) {
+    // the per-call lists: the cache's own, grown on demand, or the ones the caller of this function brings
+    if (!fixed && tiles + 1 > c->mbs_cap) {
         BGL_HIP(hipDeviceSynchronize());
         (void)hipFree(c->mbs);
         c->mbs = nullptr;
         c->mbs_cap = 0;
         const int64_t cap = std::max<int64_t>(2 * tiles + 1, 1024);
-        BGL_HIP(hipMalloc((void **)&c->mbs, 2 * sizeof(int32_t) * (size_t)cap));  // counts, then their prefixes
+        BGL_HIP(hipMalloc((void **)&c->mbs, 3 * sizeof(int32_t) * (size_t)cap));  // counts, their prefixes, lines read
         c->mbs_cap = cap;
     }
-    if (n > c->hit_cap) {
+    if (!fixed && n > c->hit_cap) {
         BGL_HIP(hipDeviceSynchronize());
         (void)hipFree(c->hit_pos);
         c->hit_pos = nullptr;
@@ -849,6 +911,10 @@ int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, in
         mpos_copy = c->mpos_copy[g];
     }
     *mpos_used = early ? mpos_copy : miss_pos;
+    int32_t *const mbs = fixed ? fixed->mbs : c->mbs;
+    const int64_t mbs_cap = fixed ? fixed->mbs_cap : c->mbs_cap;
+    int32_t *const hit_pos = fixed ? fixed->hit_pos : c->hit_pos;
+    const int64_t hit_cap = fixed ? fixed->hit_cap : c->hit_cap;
     c->lookup_calls += 1;
     c->last_n = n;
     const int q = c->row_bytes / 16;
@@ -866,17 +932,17 @@ int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, in
         {
             Prof p(c, BGL_STAGE_PROBE, ls);
             launch(c, ls, k_probe, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), ids, n, c->num_nodes, c->table,
-                   c->num_buckets - 1, out_slot, c->mbs, c->dev);
+                   c->num_buckets - 1, out_slot, mbs, mbs + 2 * mbs_cap, c->dev);
         }
         {
             Prof p(c, BGL_STAGE_MISS_LIST, ls, false);
             int32_t *tile_prefix = nullptr;
             if (tiles >= kSelfSumTiles) {
-                tile_prefix = c->mbs + c->mbs_cap;
-                hipLaunchKernelGGL(k_scan_tiles, dim3(1), dim3(kScanThreads), 0, ls, c->mbs, tiles, tile_prefix);
+                tile_prefix = mbs + mbs_cap;
+                hipLaunchKernelGGL(k_scan_tiles, dim3(1), dim3(kScanThreads), 0, ls, mbs, tiles, tile_prefix);
             }
             hipLaunchKernelGGL(k_split_list, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), 0, ls, out_slot,
-                               n, c->mbs, tile_prefix, miss_pos, c->hit_pos, c->hit_pos + c->hit_cap, c->dev,
+                               n, mbs, tile_prefix, mbs + 2 * mbs_cap, miss_pos, hit_pos, hit_pos + hit_cap, c->dev,
                                n_hit_dev, ids, c->num_nodes,
                                tier ? bgl::tier_ids_device_if_passthrough(tier) : nullptr, mpos_copy, gen);
         }
@@ -901,7 +967,7 @@ int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, in
         Prof p(c, BGL_STAGE_GATHER_HIT, ms);
         dispatch_q(q, [&](auto Q) {
             launch(c, ms, k_gather_hits<decltype(Q)::value>, dim3(copy_blocks(n, q)), dim3(COPY_THREADS),
-                   c->hit_pos, c->hit_pos + c->hit_cap, q, reinterpret_cast<const uint4 *>(c->buffer),
+                   hit_pos, hit_pos + hit_cap, q, reinterpret_cast<const uint4 *>(c->buffer),
                    reinterpret_cast<uint4 *>(out_rows), c->dev);
         });
     }
@@ -944,7 +1010,7 @@ namespace {
 
 int lookup_gather_impl(bgl_cache_t *c, const int32_t *ids, int64_t n, void *out_rows, int32_t *out_slot,
                        int32_t *miss_pos, int64_t *n_hit_host, void *main_stream, void *side_stream,
-                       void *lookup_stream, bool early)
+                       void *lookup_stream, bool early, const LookupLists *fixed = nullptr)
 {
     int rc = check_lookup_args(c, ids, n, out_rows, out_slot, miss_pos);
     if (rc != BGL_OK) return rc;
@@ -953,8 +1019,12 @@ int lookup_gather_impl(bgl_cache_t *c, const int32_t *ids, int64_t n, void *out_
     if (!c->features) BGL_FAIL(BGL_EINVAL, "the cache has no backing store: use bgl_cache_lookup_gather_tiered");
     hipStream_t ms = static_cast<hipStream_t>(main_stream);
     hipStream_t ss = nullptr;
-    rc = side_stream_of(c, side_stream, &ss);
-    if (rc != BGL_OK) return rc;
+    if (fixed) {
+        ss = side_stream ? static_cast<hipStream_t>(side_stream) : ms;  // (no stream is created here)
+    } else {
+        rc = side_stream_of(c, side_stream, &ss);
+        if (rc != BGL_OK) return rc;
+    }
     // the hit count goes straight into the caller's page-locked word (no copy launch)
     int64_t *n_hit_dev = nullptr;
     if (n_hit_host) {
@@ -970,7 +1040,7 @@ int lookup_gather_impl(bgl_cache_t *c, const int32_t *ids, int64_t n, void *out_
     hipStream_t ls = early ? static_cast<hipStream_t>(lookup_stream) : ms;
     const int32_t *mpos = nullptr;
     int gen = 0;
-    rc = lookup_phase(c, ids, n, out_rows, out_slot, miss_pos, n_hit_dev, ms, ls, nullptr, &mpos, &gen);
+    rc = lookup_phase(c, ids, n, out_rows, out_slot, miss_pos, n_hit_dev, ms, ls, nullptr, &mpos, &gen, fixed);
     if (rc != BGL_OK) return rc;
     if (n > 0) {
         if (ss != ms) BGL_HIP(hipStreamWaitEvent(ss, c->ev_listed, 0));
@@ -1371,6 +1441,27 @@ try {
     // every insertion beyond the first `capacity` ones overwrote an occupied slot
     if (evictions) *evictions = tail > (uint64_t)c->capacity ? tail - (uint64_t)c->capacity : 0;
     if (status) *status = h.status;
+    return BGL_OK;
+} BGL_NOTHROW_END
+
+extern "C" int bgl_cache_map_stats(bgl_cache_t *c, uint64_t *ids_looked_up, uint64_t *bucket_lines_read,
+                                   uint64_t *num_buckets, uint64_t *buckets_passed, uint64_t *passes)
+try {
+    if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
+    BGL_HIP(hipDeviceSynchronize());
+    CacheDev h;
+    if (buckets_passed || passes) {
+        BGL_HIP(hipMemset(&c->dev->census[0], 0, sizeof(h.census)));
+        hipLaunchKernelGGL(k_map_census, dim3(256), dim3(256), 0, 0, c->table, c->num_buckets, c->dev);
+        BGL_HIP(hipGetLastError());
+        BGL_HIP(hipDeviceSynchronize());
+    }
+    BGL_HIP(hipMemcpy(&h, c->dev, sizeof(h), hipMemcpyDeviceToHost));
+    if (ids_looked_up) *ids_looked_up = h.lookups;
+    if (bucket_lines_read) *bucket_lines_read = h.probe_lines;
+    if (num_buckets) *num_buckets = c->num_buckets;
+    if (buckets_passed) *buckets_passed = h.census[0];
+    if (passes) *passes = h.census[1];
     return BGL_OK;
 } BGL_NOTHROW_END
 

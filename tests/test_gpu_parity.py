@@ -373,6 +373,71 @@ def test_cache_long_churn_keeps_map_exact(B, torch_mod):
     assert np.array_equal(out.cpu().numpy(), feats.view(np.uint8).reshape(N, 16))
 
 
+@pytest.mark.parametrize("write_through", [False, True])
+def test_cache_map_lookups_stay_short_under_fifo_churn(B, torch_mod, write_through):
+    """More than 300 times the capacity flows through a cache whose map is at its highest load
+    (15,360 x 2 slots over 4,096 buckets of 15 words: load 1/2).  The cache engine of the paper
+    serves a whole training job, so the cost of a lookup must not grow with the number of
+    evictions: the bucket lines read per looked-up id stay near one, no higher at the end than
+    right after the cache has filled, while lookups and state stay equal to the oracle's."""
+    import oracle
+    torch = torch_mod
+    rng = np.random.default_rng(20211208)
+    cap, N, per_batch, turnovers = 30720, 200_000, 20_000, 310
+    feats = rng.integers(0, 2**31, (N, 4), dtype=np.int32).view(np.float32)      # 16-byte rows, compared as bytes
+    feat_t = torch.from_numpy(feats.view(np.uint8).reshape(N, 16)).pin_memory()
+    gc = B.Cache(cap, feat_t, num_nodes=N, row_bytes=16)
+    gc.set_write_through(write_through)
+    oc = oracle.Cache(cap, feats)
+    out = torch.empty((per_batch, 16), dtype=torch.uint8, device="cuda")
+    out_slot = torch.empty(per_batch, dtype=torch.int32, device="cuda")
+    miss_pos = torch.empty(per_batch, dtype=torch.int32, device="cuda")
+    assert gc.map_stats()["num_buckets"] * 15 == 2 * cap
+    marks, b = [], 0
+    while oc.tail < turnovers * cap:
+        ids = rng.choice(N, per_batch, replace=False).astype(np.int32)
+        ids_t = torch.from_numpy(ids).cuda()
+        gc.lookup_gather(ids_t, per_batch, out, out_slot, miss_pos)
+        gc.insert_fifo(ids_t, miss_pos, -1, out)
+        gc.wait_rows()
+        o_out, o_slot, o_miss, o_hit = oc.lookup_gather(ids)
+        oc.insert_fifo(ids, o_miss, o_out)
+        torch.cuda.synchronize()
+        assert int(gc.n_hit_host[0]) == o_hit, f"batch {b}"
+        assert np.array_equal(out_slot.cpu().numpy(), o_slot), f"batch {b}"
+        if b % 40 == 0:
+            assert np.array_equal(out.cpu().numpy(), o_out), f"batch {b}"
+            assert_state_equal(gc, oc, f"batch {b}")
+            ms = gc.map_stats()
+            marks.append((oc.tail / cap, ms["ids_looked_up"], ms["bucket_lines_read"], ms["buckets_passed"], ms["passes"]))
+        b += 1
+    assert_state_equal(gc, oc, "end")
+    ms = gc.map_stats()
+    marks.append((oc.tail / cap, ms["ids_looked_up"], ms["bucket_lines_read"], ms["buckets_passed"], ms["passes"]))
+    assert oc.tail >= 300 * cap
+    # lines per id over the whole run, and between consecutive marks
+    assert ms["lines_per_id"] <= 1.2, ms
+    per_span = [(t1, (l1 - l0) / (i1 - i0)) for (t0, i0, l0, _, _), (t1, i1, l1, _, _) in zip(marks, marks[1:])]
+    early_spans = [x for t, x in per_span if 2 <= t <= 40]
+    late_spans = [x for t, x in per_span if t >= 270]
+    assert early_spans and late_spans
+    assert max(late_spans) <= 1.2 and max(late_spans) <= 1.02 * max(early_spans), (early_spans, late_spans)
+    # buckets that some live entry is pushed past: a few per cent, not growing
+    assert marks[-1][3] <= 0.10 * ms["num_buckets"], marks[-1]
+    # the whole map against the oracle's: every node id looked up
+    ids = torch.arange(N, dtype=torch.int32, device="cuda")
+    big_out = torch.empty((N, 16), dtype=torch.uint8, device="cuda")
+    big_slot = torch.empty(N, dtype=torch.int32, device="cuda")
+    big_miss = torch.empty(N, dtype=torch.int32, device="cuda")
+    gc.set_write_through(False)
+    gc.lookup_gather(ids, N, big_out, big_slot, big_miss)
+    gc.wait_rows()
+    torch.cuda.synchronize()
+    assert np.array_equal(big_slot.cpu().numpy(), oc.node_to_slot)
+    assert np.array_equal(big_out.cpu().numpy(), feats.view(np.uint8).reshape(N, 16))
+    assert ms["passes"] >= ms["buckets_passed"]      # (every such bucket has at least one entry pushed past it)
+
+
 def test_cache_flags_out_of_range_id(B, torch_mod):
     feats = np.zeros((10, 4), dtype=np.float32)
     feat_t = torch_mod.from_numpy(feats.view(np.uint8).reshape(10, 16)).pin_memory()
