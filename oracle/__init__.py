@@ -38,6 +38,12 @@ def lib() -> C.CDLL:
         L.bglo_mix64.argtypes = [u64]
         L.bglo_draw.restype = u64
         L.bglo_draw.argtypes = [u64, i32, i32, i32]
+        L.bglo_hop_key.restype = u64
+        L.bglo_hop_key.argtypes = [u64, i32]
+        L.bglo_node_key.restype = u64
+        L.bglo_node_key.argtypes = [u64, i32]
+        L.bglo_slot_draw.restype = u64
+        L.bglo_slot_draw.argtypes = [u64, i32]
         L.bglo_mulhi64.restype = u64
         L.bglo_mulhi64.argtypes = [u64, u64]
         L.bglo_floyd_from_t.restype = None
@@ -82,6 +88,18 @@ def mix64(z: int) -> int:
 
 def draw(rng_seed: int, hop: int, node: int, slot: int) -> int:
     return int(lib().bglo_draw(rng_seed & (2**64 - 1), hop, node, slot))
+
+
+def hop_key(rng_seed: int, hop: int) -> int:
+    return int(lib().bglo_hop_key(rng_seed & (2**64 - 1), hop))
+
+
+def node_key(hop_key_: int, node: int) -> int:
+    return int(lib().bglo_node_key(hop_key_ & (2**64 - 1), node))
+
+
+def slot_draw(node_key_: int, slot: int) -> int:
+    return int(lib().bglo_slot_draw(node_key_ & (2**64 - 1), slot))
 
 
 def mulhi64(x: int, m: int) -> int:
@@ -187,6 +205,8 @@ class Cache:
         out_slot = np.empty(n, dtype=np.int32)
         miss_pos = np.empty(max(n, 1), dtype=np.int32)
         n_hit = lib().bglo_cache_lookup_gather(self._h, _ptr(ids), n, _ptr(out), _ptr(out_slot), _ptr(miss_pos))
+        if n_hit == -2:
+            raise ValueError("repeated id in one lookup: the ids of a call must be distinct")
         if n_hit < 0:
             raise ValueError("node id out of range")
         return out, out_slot, miss_pos[: n - n_hit].copy(), int(n_hit)
@@ -225,9 +245,40 @@ class Cache:
         return a.value, b.value
 
 
+class TwoLevel:
+    """The two cache levels of the paper's Sec. 3.2.3: a GPU cache, behind it a CPU cache with
+    the same (FIFO) policy, behind that the feature store.  Reading taken where the paper omits
+    the details: the second level sees the first level's misses of one call, in miss order, as
+    one FIFO batch of its own: they are looked up against the second level's state at entry,
+    then the ones it does not hold are inserted in that order (the rule of `Cache.insert_fifo`);
+    a hit in either level does not renew anything.  The first level is updated by the caller
+    afterwards, as in the one-level workflow.  capacity2 = 0: no second level."""
+
+    def __init__(self, capacity1: int, capacity2: int, features: np.ndarray):
+        self.level1 = Cache(capacity1, features)
+        self.level2 = Cache(capacity2, features) if capacity2 > 0 else None
+
+    def lookup_gather(self, ids):
+        """Returns (rows, out_slot, miss_pos, hits in level 1, hits in level 2 among level 1's
+        misses).  Level 2 is updated; level 1 is not (see insert_fifo)."""
+        ids = np.ascontiguousarray(ids, dtype=np.int32)
+        out, out_slot, miss_pos, n_hit1 = self.level1.lookup_gather(ids)
+        n_hit2 = 0
+        if self.level2 is not None:
+            missed = ids[miss_pos]
+            rows2, _, miss2, n_hit2 = self.level2.lookup_gather(missed)
+            self.level2.insert_fifo(missed, miss2, rows2)
+            out[miss_pos] = rows2          # what level 2 or the store returned for level 1's misses
+        return out, out_slot, miss_pos, n_hit1, n_hit2
+
+    def insert_fifo(self, ids, miss_pos, out_rows):
+        self.level1.insert_fifo(ids, miss_pos, out_rows)
+
+
 def bfs_sequence(row_ptr: np.ndarray, col: np.ndarray, train_nodes, root: int) -> np.ndarray:
-    """Training nodes in canonical BFS order from `root` (levels, ids inside a level,
-    restart at the smallest unvisited id)."""
+    """Training nodes in canonical BFS order from `root`: first-in first-out queue order, a
+    node's neighbors entering the queue in the order of its CSR row, restart at the smallest
+    unvisited id."""
     row_ptr = np.ascontiguousarray(row_ptr)
     bits = 64 if row_ptr.dtype == np.int64 else 32
     col = np.ascontiguousarray(col, dtype=np.int32)

@@ -41,12 +41,31 @@ uint64_t bglo_mix64(uint64_t z)
 }
 
 /* 64-bit word for (call seed, hop, node, slot): hop and node select a stream,
- * slot is the counter inside it. */
+ * slot is the counter inside it.  The three steps are functions of their own so
+ * that each can be checked against the published SplitMix64 outputs:
+ *   hop key   = output number hop+1 of the SplitMix64 generator seeded with the
+ *               call seed (the generator adds the golden-ratio constant to its
+ *               state before every output);
+ *   node key  = the hop key with the node id xor-ed in, mixed once;
+ *   draw      = output number slot+1 of the generator seeded with the node key. */
+uint64_t bglo_hop_key(uint64_t rng_seed, int32_t hop)
+{
+    return bglo_mix64(rng_seed + BGLO_GOLDEN * (uint64_t)(hop + 1));
+}
+
+uint64_t bglo_node_key(uint64_t hop_key, int32_t node)
+{
+    return bglo_mix64(hop_key ^ (uint64_t)(uint32_t)node);
+}
+
+uint64_t bglo_slot_draw(uint64_t node_key, int32_t slot)
+{
+    return bglo_mix64(node_key + BGLO_GOLDEN * (uint64_t)(slot + 1));
+}
+
 uint64_t bglo_draw(uint64_t rng_seed, int32_t hop, int32_t node, int32_t slot)
 {
-    uint64_t h0 = bglo_mix64(rng_seed + BGLO_GOLDEN * (uint64_t)(hop + 1));
-    uint64_t h1 = bglo_mix64(h0 ^ (uint64_t)(uint32_t)node);
-    return bglo_mix64(h1 + BGLO_GOLDEN * (uint64_t)(slot + 1));
+    return bglo_slot_draw(bglo_node_key(bglo_hop_key(rng_seed, hop), node), slot);
 }
 
 /* Map a 64-bit word to [0, m): floor(x * m / 2^64).  No rejection step, so
@@ -208,6 +227,8 @@ typedef struct {
     uint8_t *buffer;
     uint64_t tail;
     uint64_t lookups, hits;
+    uint32_t *seen_in_call; /* [N]: number of the last lookup call that contained the id */
+    uint32_t call;
 } bglo_cache;
 
 bglo_cache *bglo_cache_create(int64_t capacity_rows, int32_t row_bytes,
@@ -223,8 +244,9 @@ bglo_cache *bglo_cache_create(int64_t capacity_rows, int32_t row_bytes,
     c->slot_to_node = (int32_t *)malloc(sizeof(int32_t) * (size_t)capacity_rows);
     c->node_to_slot = (int32_t *)malloc(sizeof(int32_t) * (size_t)num_nodes);
     c->buffer = (uint8_t *)calloc((size_t)capacity_rows, (size_t)row_bytes);
-    if (!c->slot_to_node || !c->node_to_slot || !c->buffer) {
-        free(c->slot_to_node); free(c->node_to_slot); free(c->buffer); free(c);
+    c->seen_in_call = (uint32_t *)calloc((size_t)num_nodes, sizeof(uint32_t));
+    if (!c->slot_to_node || !c->node_to_slot || !c->buffer || !c->seen_in_call) {
+        free(c->slot_to_node); free(c->node_to_slot); free(c->buffer); free(c->seen_in_call); free(c);
         return NULL;
     }
     for (int64_t s = 0; s < capacity_rows; ++s) c->slot_to_node[s] = -1;
@@ -235,13 +257,16 @@ bglo_cache *bglo_cache_create(int64_t capacity_rows, int32_t row_bytes,
 void bglo_cache_destroy(bglo_cache *c)
 {
     if (!c) return;
-    free(c->slot_to_node); free(c->node_to_slot); free(c->buffer); free(c);
+    free(c->slot_to_node); free(c->node_to_slot); free(c->buffer); free(c->seen_in_call); free(c);
 }
 
 /* Lookup against the state at entry, then serve every row: hits from the cache
  * buffer, misses from the host table.  No state change (FIFO: a hit does not
  * refresh a row's position).  miss_pos receives the positions i of the misses
- * in ascending order.  Returns the number of hits, or -1 on a bad id. */
+ * in ascending order.  The ids of one call must be distinct (they are the
+ * deduplicated nodes of one sampled subgraph): a repeated id would be inserted
+ * twice by the update that follows.  Returns the number of hits, -1 on an id
+ * outside the table, -2 on a repeated id; nothing is counted in those cases. */
 int64_t bglo_cache_lookup_gather(bglo_cache *c, const int32_t *ids, int64_t n,
                                  void *out_rows, int32_t *out_slot,
                                  int32_t *miss_pos)
@@ -249,9 +274,19 @@ int64_t bglo_cache_lookup_gather(bglo_cache *c, const int32_t *ids, int64_t n,
     uint8_t *out = (uint8_t *)out_rows;
     size_t rb = (size_t)c->row_bytes;
     int64_t n_hit = 0, n_miss = 0;
+    c->call += 1;
+    if (c->call == 0) { /* the call number wrapped: forget the old marks */
+        memset(c->seen_in_call, 0, sizeof(uint32_t) * (size_t)c->num_nodes);
+        c->call = 1;
+    }
     for (int64_t i = 0; i < n; ++i) {
         int32_t v = ids[i];
         if (v < 0 || (int64_t)v >= c->num_nodes) return -1;
+        if (c->seen_in_call[v] == c->call) return -2;
+        c->seen_in_call[v] = c->call;
+    }
+    for (int64_t i = 0; i < n; ++i) {
+        int32_t v = ids[i];
         int32_t slot = c->node_to_slot[v];
         out_slot[i] = slot;
         if (slot >= 0) {

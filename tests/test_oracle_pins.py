@@ -420,3 +420,140 @@ def test_gather_bf16_sized_rows_and_bad_id():
     assert np.array_equal(out.view(np.uint16), feats[ids])
     with pytest.raises(ValueError):
         c.lookup_gather([30])
+
+
+# ---------------------------------------------------------------- key schedule
+def _published_splitmix64(golden_dir):
+    """(state seed, outputs) pairs of the published SplitMix64 check values."""
+    out = []
+    for line in open(os.path.join(golden_dir, "splitmix64_vectors.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        vals = [int(x) for x in line.split()]
+        out.append((vals[0], vals[1:]))
+    return out
+
+
+def test_key_schedule_steps_are_published_splitmix64_outputs(golden_dir):
+    """The hop key is output number hop+1 of SplitMix64 seeded with the call seed and a draw is
+    output number slot+1 of SplitMix64 seeded with the node key: with the published seed both
+    must reproduce the published outputs one by one (an off-by-one in either counter, or a
+    constant other than the generator's increment, gives other numbers)."""
+    G = 0x9E3779B97F4A7C15
+    for seed, outputs in _published_splitmix64(golden_dir):
+        for k, expect in enumerate(outputs):
+            assert oracle.hop_key(seed, k) == expect
+            assert oracle.slot_draw(seed, k) == expect
+    seed, outputs = _published_splitmix64(golden_dir)[0]
+    # the node key mixes (hop key XOR node) once: choose hop keys that land on the published states
+    for node in (0, 1, 0x7FFFFFFF, 123456789):
+        for k, expect in enumerate(outputs):
+            state = (seed + (k + 1) * G) & M64
+            assert oracle.node_key(state ^ node, node) == expect
+    # xor, not addition: a node id that overlaps set bits of the key
+    state = (seed + G) & M64
+    node = int(state & 0x7FFFFFFF) | 1
+    assert oracle.node_key(state ^ node, node) == outputs[0]
+    assert oracle.node_key((state - node) & M64, node) != outputs[0]
+    # and draw() is the three steps chained
+    for key in ((1234567, 0, 0, 0), (1234567, 2, 99, 14), (2**64 - 1, 7, 2**31 - 1, 63)):
+        s, h, v, sl = key
+        assert oracle.draw(*key) == oracle.slot_draw(oracle.node_key(oracle.hop_key(s, h), v), sl)
+    # seed 1234567, hop 0 and 1: the first two published outputs
+    assert oracle.hop_key(1234567, 0) == 6457827717110365317
+    assert oracle.hop_key(1234567, 1) == 3203168211198807973
+
+
+def test_draw_golden_values(golden_dir):
+    """Regression lock on the composed key schedule: values written by tests/golden/make_draw_golden.py
+    (which calls only the oracle), checked here with Python integers."""
+    G = 0x9E3779B97F4A7C15
+
+    def mix(z):
+        z ^= z >> 30
+        z = (z * 0xBF58476D1CE4E5B9) & M64
+        z ^= z >> 27
+        z = (z * 0x94D049BB133111EB) & M64
+        return z ^ (z >> 31)
+
+    n = 0
+    for line in open(os.path.join(golden_dir, "draw_values.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        seed, hop, node, slot, value = (int(x) for x in line.split())
+        assert oracle.draw(seed, hop, node, slot) == value
+        assert mix((mix(mix((seed + G * (hop + 1)) & M64) ^ node) + G * (slot + 1)) & M64) == value
+        n += 1
+    assert n >= 12
+
+
+# ------------------------------------------------------------------ two levels
+def test_lookup_rejects_a_repeated_id():
+    feats = _features(20, 4)
+    c = oracle.Cache(5, feats)
+    with pytest.raises(ValueError, match="repeated"):
+        c.lookup_gather([3, 4, 3])
+    assert c.stats() == (0, 0)
+    out, _, miss_pos, n_hit = c.lookup_gather([3, 4])       # the next call starts afresh
+    assert n_hit == 0 and miss_pos.tolist() == [0, 1]
+    c.insert_fifo([3, 4], miss_pos, out)
+    assert c.lookup_gather([4, 3])[3] == 2
+
+
+def test_two_level_hand_worked_example(golden_dir):
+    lines = [l.strip() for l in open(os.path.join(golden_dir, "two_level_worked_example.txt"))
+             if l.strip() and not l.startswith("#")]
+    c1, c2 = (int(x) for x in lines[0].split()[1:])
+    feats = _features(16, 4)
+    fbytes = feats.view(np.uint8).reshape(16, -1)
+    t = oracle.TwoLevel(c1, c2, feats)
+    for l in lines[1:]:
+        if not l.startswith("batch"):
+            continue
+        ids, slots, h2, s1, t1, s2, t2 = ([int(x) for x in p.split()] for p in l[len("batch"):].split("|"))
+        out, out_slot, miss_pos, n_hit1, n_hit2 = t.lookup_gather(ids)
+        assert out_slot.tolist() == slots
+        assert n_hit1 == sum(s >= 0 for s in slots) and n_hit2 == h2[0]
+        assert np.array_equal(out, fbytes[ids])
+        t.insert_fifo(ids, miss_pos, out)
+        assert t.level1.slot_to_node.tolist() == s1 and t.level1.tail == t1[0]
+        assert t.level2.slot_to_node.tolist() == s2 and t.level2.tail == t2[0]
+    tot = [int(x) for x in lines[-1].replace("hits", "").replace("lookups", "").split()]
+    assert t.level1.stats() == (tot[2], tot[0]) and t.level2.stats() == (tot[3], tot[1])
+
+
+@pytest.mark.parametrize("c1,c2,N,batch", [(4, 9, 40, 12), (30, 80, 400, 60), (50, 20, 300, 70), (1, 1, 10, 6)])
+def test_two_level_matches_chained_deque_models(c1, c2, N, batch):
+    """Two independent queue models chained the way Sec. 3.2.3 describes: the second one sees what
+    the first one missed, in that order."""
+    rng = np.random.default_rng(c1 * 1000 + c2)
+    feats = _features(N, 8, seed=c2)
+    fbytes = feats.view(np.uint8).reshape(N, -1)
+    t = oracle.TwoLevel(c1, c2, feats)
+    m1, m2 = DequeFifo(c1), DequeFifo(c2)
+    for b in range(30):
+        ids = list(dict.fromkeys((rng.zipf(1.3, batch) % N).tolist()))
+        out, out_slot, miss_pos, n_hit1, n_hit2 = t.lookup_gather(ids)
+        hit1 = m1.batch(ids)
+        missed = [i for i, h in zip(ids, hit1) if not h]
+        hit2 = m2.batch(missed)
+        assert (out_slot >= 0).tolist() == hit1
+        assert (n_hit1, n_hit2) == (sum(hit1), sum(hit2))
+        assert np.array_equal(out, fbytes[ids])
+        t.insert_fifo(ids, miss_pos, out)
+        assert sorted(m1.members) == sorted(t.level1.slot_to_node[t.level1.slot_to_node >= 0].tolist())
+        assert sorted(m2.members) == sorted(t.level2.slot_to_node[t.level2.slot_to_node >= 0].tolist())
+
+
+def test_two_level_without_second_level_is_the_one_level_cache():
+    feats = _features(60, 4)
+    t, c = oracle.TwoLevel(7, 0, feats), oracle.Cache(7, feats)
+    rng = np.random.default_rng(4)
+    for b in range(10):
+        ids = rng.permutation(60)[:15].tolist()
+        out, out_slot, miss_pos, h1, h2 = t.lookup_gather(ids)
+        o2, s2, m2, hh = c.lookup_gather(ids)
+        assert h2 == 0 and h1 == hh and np.array_equal(out, o2) and np.array_equal(out_slot, s2)
+        t.insert_fifo(ids, miss_pos, out)
+        c.insert_fifo(ids, m2, o2)
+    assert np.array_equal(t.level1.slot_to_node, c.slot_to_node)
