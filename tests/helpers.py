@@ -69,19 +69,22 @@ class GpuPipeline:
 
 
 class OraclePipeline:
-    def __init__(self, workload, cache_rows=None):
+    """tier_rows > 0: a second cache level behind the first (oracle.TwoLevel)."""
+
+    def __init__(self, workload, cache_rows=None, tier_rows=0):
         import oracle
         self.oracle = oracle
         self.w = workload
-        self.cache = oracle.Cache(cache_rows or workload.cfg.cache_rows, workload.features)
+        self.two = oracle.TwoLevel(cache_rows or workload.cfg.cache_rows, tier_rows, workload.features)
+        self.cache, self.tier = self.two.level1, self.two.level2
 
     def run_batch(self, seeds_np, rng_seed):
         cfg = self.w.cfg
         sg = self.oracle.sample_khop(self.w.row_ptr, self.w.col, seeds_np, cfg.fanouts, int(rng_seed))
-        out, out_slot, miss_pos, n_hit = self.cache.lookup_gather(sg.input_nodes)
-        self.cache.insert_fifo(sg.input_nodes, miss_pos, out)
+        out, out_slot, miss_pos, n_hit, n_hit_tier = self.two.lookup_gather(sg.input_nodes)
+        self.two.insert_fifo(sg.input_nodes, miss_pos, out)
         return dict(n_frontier=sg.n_frontier.astype(np.int64), nnz=np.array(sg.nnz, dtype=np.int64),
-                    n=len(sg.input_nodes), n_hit=n_hit, input_nodes=sg.input_nodes,
+                    n=len(sg.input_nodes), n_hit=n_hit, n_hit_tier=n_hit_tier, input_nodes=sg.input_nodes,
                     row_ptr=sg.row_ptr, col_local=sg.col_local, out_slot=out_slot,
                     miss_pos=miss_pos, out_rows=out)
 

@@ -1,7 +1,7 @@
 """GPU parity for the two-level cache (GPU cache, then the FIFO tier in host
-memory, then the feature store; Sec. 3.2.3) against two oracle caches chained
-the same way: the second one sees the first one's misses, in order, as its
-batch.  Bytes, slots, lists and both levels' states must be equal."""
+memory, then the feature store; Sec. 3.2.3) against the oracle's two-level
+cache (oracle.TwoLevel: the second level sees the first one's misses, in order,
+as its batch).  Bytes, slots, lists and both levels' states must be equal."""
 import numpy as np
 import pytest
 
@@ -46,7 +46,8 @@ def run_tiered_stream(B, torch, feats, cap1, cap2, batches, write_through, threa
     if copy_engine:     # the packed rows cross the link as plain copies into device memory
         tier.set_copy_engine(True)
     # capacity 0: the tier keeps nothing (every miss row just passes through its ring)
-    oc1, oc2 = oracle.Cache(cap1, feats), (oracle.Cache(cap2, feats) if cap2 > 0 else None)
+    two = oracle.TwoLevel(cap1, cap2, feats)
+    oc1, oc2 = two.level1, two.level2
     if write_through:
         gc.set_write_through(True)
     side_stream = torch.cuda.Stream() if side else None
@@ -76,20 +77,14 @@ def run_tiered_stream(B, torch, feats, cap1, cap2, batches, write_through, threa
         gc.wait_rows()
         torch.cuda.synchronize()
         # oracle: level 1, then level 2 on level 1's misses, both updated first-in first-out
-        o_out, o_slot, o_miss, o_hit = oc1.lookup_gather(ids)
-        mids = np.asarray(ids, dtype=np.int32)[o_miss] if n else np.empty(0, np.int32)
-        if oc2 is not None:
-            o2_out, o2_slot, o2_miss, o2_hit = oc2.lookup_gather(mids)
-            oc2.insert_fifo(mids, o2_miss, o2_out)
-        else:
-            o2_out, o2_hit = o_out[o_miss], 0
-        oc1.insert_fifo(ids, o_miss, o_out)
+        o_out, o_slot, o_miss, o_hit, o2_hit = two.lookup_gather(ids)
+        two.insert_fifo(ids, o_miss, o_out)
         what = f"batch {bi}"
         assert (h1, h2) == (o_hit, o2_hit), what
         assert np.array_equal(out_slot[:n].cpu().numpy(), o_slot), what
         assert np.array_equal(miss_pos[: n - h1].cpu().numpy(), o_miss), what
         assert np.array_equal(out[:n].cpu().numpy(), o_out), what
-        assert np.array_equal(o2_out, o_out[o_miss]), what     # the tier level returns the store's bytes
+        assert np.array_equal(o_out, store[np.asarray(ids, dtype=np.int64)] if n else o_out), what  # the store's bytes
         assert_state_equal(gc, oc1, what)
         if oc2 is not None:
             assert_tier_state_equal(tier, oc2, what)
@@ -270,20 +265,14 @@ def test_tiered_pipeline_as_benchmarked_matches_oracle(torch_mod, B, tier_fracti
 
     steps = 6
     n_list, hit_list = pipe.run(seeds_dev, w.rng_seeds, steps, on_batch=grab)
-    op = OraclePipeline(w)
-    oc2 = oracle.Cache(tier_rows, w.features) if tier_rows > 0 else None
+    op = OraclePipeline(w, tier_rows=tier_rows)
     for b in range(steps):
         o = op.run_batch(w.seed_batches[b], w.rng_seeds[b])
         assert_batch_equal(got[b], o, f"tiered batch {b}")
-        o2_hit = 0
-        if oc2 is not None:
-            mids = o["input_nodes"][o["miss_pos"]]
-            o2_out, _, o2_miss, o2_hit = oc2.lookup_gather(mids)
-            oc2.insert_fifo(mids, o2_miss, o2_out)
-        assert (n_list[b], hit_list[b], pipe.tier_hits[b]) == (o["n"], o["n_hit"], o2_hit)
+        assert (n_list[b], hit_list[b], pipe.tier_hits[b]) == (o["n"], o["n_hit"], o["n_hit_tier"])
     assert_state_equal(cache, op.cache, "tiered pipeline")
-    if oc2 is not None:
-        assert_tier_state_equal(tier, oc2, "tiered pipeline")
+    if op.tier is not None:
+        assert_tier_state_equal(tier, op.tier, "tiered pipeline")
 
 
 def test_tiered_random_cases_property(B, torch_mod):
