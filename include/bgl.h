@@ -190,6 +190,31 @@ int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64_t n, void 
                             void *main_stream, void *side_stream);
 
 /*
+ * bgl_cache_lookup_gather for callers that cannot allocate: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same results,
+ * same arguments and stream contract, except:
+ *  - the call's own lists (per-tile miss counts, the hit list) do not live in
+ *    memory the cache allocates and grows on demand but in a fixed array of
+ *    device memory inside the library, about 10.5 MB per GPU, held by every GPU
+ *    the library runs on until the process ends; hence n <= BGL_NOALLOC_MAX_IDS;
+ *  - side_stream NULL means main_stream (no stream is created);
+ *  - its kernels are never timed (bgl_cache_set_profiling does not apply to it);
+ *  - the current device must be the one the cache was created on.
+ * The call makes no hipMalloc / hipFree, creates no stream and no event.  All
+ * such calls on one GPU share the one array, whatever cache they are for: the
+ * array keeps the last call's contents (every part of it that a call reads is
+ * written by that call first, nothing needs clearing), and two such calls whose
+ * work overlaps on one GPU (different streams, different caches) race.  A call's
+ * lists are read until its hit gather has finished on main_stream.
+ * Errors: as bgl_cache_lookup_gather, plus BGL_ECAPACITY (n > BGL_NOALLOC_MAX_IDS),
+ * BGL_EINVAL (wrong current device), BGL_EUNSUPPORTED (device ordinal >= 64).
+ */
+#define BGL_NOALLOC_MAX_IDS 1310720 /* 1.25 x 2^20: above the largest batch bound of the paper's settings */
+int bgl_cache_lookup_gather_noalloc(bgl_cache_t *c, const int32_t *ids, int64_t n, void *out_rows,
+                                    int32_t *out_slot, int32_t *miss_pos, int64_t *n_hit_host,
+                                    void *main_stream, void *side_stream);
+
+/*
  * bgl_cache_lookup_gather with the map lookup and the lists on lookup_stream
  * instead of main_stream (write-through mode only).  When main_stream is the
  * stream that also carries the miss fetches, a plain lookup starts only when the

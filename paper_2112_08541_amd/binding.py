@@ -21,6 +21,7 @@ BGL_OK, BGL_EINVAL, BGL_ENOMEM, BGL_EHIP, BGL_ECAPACITY, BGL_EUNSUPPORTED = 0, -
 BGL_MAX_HOPS = 8
 BGL_MAX_FANOUT = 64
 BGL_COUNTS_LEN = 2 * BGL_MAX_HOPS + 2
+BGL_NOALLOC_MAX_IDS = 1310720
 BGL_DEVICE, BGL_HOST_PINNED, BGL_HOST_PINNED_COL = 0, 1, 2
 (STAGE_PROBE, STAGE_MISS_LIST, STAGE_GATHER_HIT, STAGE_FETCH_MISS,
  STAGE_INSERT_MAP, STAGE_INSERT_ROWS, STAGE_LINK_COPY) = range(7)
@@ -29,7 +30,7 @@ STAGE_NAMES = ["probe", "miss_list", "gather_hit", "fetch_miss", "insert_map", "
 EXPORTS = [
     "bgl_last_error", "bgl_graph_load_csr", "bgl_graph_destroy", "bgl_sample_workspace_bytes",
     "bgl_sample_khop", "bgl_cache_create", "bgl_cache_destroy", "bgl_cache_lookup_gather",
-    "bgl_cache_lookup_gather_early",
+    "bgl_cache_lookup_gather_early", "bgl_cache_lookup_gather_noalloc",
     "bgl_cache_insert_fifo", "bgl_cache_set_write_through", "bgl_cache_wait_rows", "bgl_cache_wait_lists", "bgl_cache_export_state", "bgl_cache_stats",
     "bgl_cache_map_stats",
     "bgl_cache_set_profiling", "bgl_cache_profile", "bgl_cache_set_profiling_every",
@@ -73,6 +74,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     L.bgl_cache_create.argtypes = [i64, i32, vp, i64, C.POINTER(vp)]
     L.bgl_cache_destroy.argtypes = [vp]
     L.bgl_cache_lookup_gather.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, vp]
+    L.bgl_cache_lookup_gather_noalloc.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, vp]
     L.bgl_cache_lookup_gather_early.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
     L.bgl_cache_insert_fifo.argtypes = [vp, vp, vp, i64, vp, vp]
     L.bgl_cache_set_write_through.argtypes = [vp, ci]
@@ -280,9 +282,10 @@ class Cache:
 
     def lookup_gather(self, ids: torch.Tensor, n: int, out_rows: torch.Tensor, out_slot: torch.Tensor,
                       miss_pos: torch.Tensor, main_stream=None, side_stream=None,
-                      n_hit_ptr: Optional[int] = None, lookup_stream=None) -> None:
+                      n_hit_ptr: Optional[int] = None, lookup_stream=None, noalloc: bool = False) -> None:
         """n_hit_ptr: address of a page-locked int64 for the hit count (default: self.n_hit_host).
-        lookup_stream: run the map lookup and the lists there (bgl_cache_lookup_gather_early)."""
+        lookup_stream: run the map lookup and the lists there (bgl_cache_lookup_gather_early).
+        noalloc: bgl_cache_lookup_gather_noalloc (the call that allocates nothing)."""
         if n > 0 and (ids.numel() < n or out_slot.numel() < n or miss_pos.numel() < n or
                       out_rows.numel() * out_rows.element_size() < n * self.row_bytes):
             raise ValueError("an argument is smaller than n")
@@ -290,7 +293,11 @@ class Cache:
                 _dev_ptr(miss_pos, torch.int32),
                 self.n_hit_host.data_ptr() if n_hit_ptr is None else n_hit_ptr, _stream_handle(main_stream),
                 None if side_stream is None else int(side_stream.cuda_stream))
-        if lookup_stream is None:
+        if noalloc:
+            if lookup_stream is not None:
+                raise ValueError("the call that allocates nothing has no early form")
+            _check(lib().bgl_cache_lookup_gather_noalloc(*args))
+        elif lookup_stream is None:
             _check(lib().bgl_cache_lookup_gather(*args))
         else:
             _check(lib().bgl_cache_lookup_gather_early(*args, _stream_handle(lookup_stream)))

@@ -25,6 +25,7 @@
 // length of a lookup depends on the load only (full buckets are rare at load
 // <= 1/2 of 15 words per bucket), not on the cache's age.
 #include <algorithm>
+#include <mutex>
 #include <vector>
 
 #include <hip/hip_ext.h>
@@ -1079,6 +1080,66 @@ extern "C" int bgl_cache_lookup_gather(bgl_cache_t *c, const int32_t *ids, int64
 try {
     return lookup_gather_impl(c, ids, n, out_rows, out_slot, miss_pos, n_hit_host, main_stream, side_stream,
                               nullptr, false);
+} BGL_NOTHROW_END
+
+// ---- the lookup that allocates nothing
+// Its lists live in a fixed array in device memory that is part of the library's code object
+// (every GPU the library runs on holds its own copy until the process ends).  The array's name
+// is only a host-side stand-in: the address the kernels get is asked for once per device.
+namespace {
+
+constexpr int64_t NOALLOC_MAX_IDS = BGL_NOALLOC_MAX_IDS;
+constexpr int64_t NOALLOC_TILES = (NOALLOC_MAX_IDS + KEYS_PER_TILE - 1) / KEYS_PER_TILE + 1;
+constexpr size_t NOALLOC_MBS_BYTES = (3 * sizeof(int32_t) * (size_t)NOALLOC_TILES + 255) / 256 * 256;
+constexpr size_t NOALLOC_BYTES = NOALLOC_MBS_BYTES + 2 * sizeof(int32_t) * (size_t)NOALLOC_MAX_IDS;
+constexpr int NOALLOC_MAX_DEVICES = 64;
+
+static __device__ __align__(256) unsigned char scratch[NOALLOC_BYTES];
+
+void *g_scratch_ptr[NOALLOC_MAX_DEVICES];  // device address of `scratch` on each device, once asked for
+std::mutex g_scratch_mutex;
+
+int scratch_of_current_device(int device, void **out)
+{
+    if (device < 0 || device >= NOALLOC_MAX_DEVICES) BGL_FAIL(BGL_EUNSUPPORTED, "device ordinal %d is out of range", device);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void *ptr = nullptr;
+        BGL_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) BGL_FAIL(BGL_EHIP, "hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[device] = ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return BGL_OK;
+}
+
+}  // namespace
+
+extern "C" int bgl_cache_lookup_gather_noalloc(bgl_cache_t *c, const int32_t *ids, int64_t n,
+                                               void *out_rows, int32_t *out_slot, int32_t *miss_pos,
+                                               int64_t *n_hit_host, void *main_stream, void *side_stream)
+try {
+    if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
+    if (n > NOALLOC_MAX_IDS)
+        BGL_FAIL(BGL_ECAPACITY, "n = %lld exceeds BGL_NOALLOC_MAX_IDS = %lld: use bgl_cache_lookup_gather",
+                 (long long)n, (long long)NOALLOC_MAX_IDS);
+    int device = -1;
+    BGL_HIP(hipGetDevice(&device));
+    if (device != c->device)
+        BGL_FAIL(BGL_EINVAL, "the cache lives on device %d, the current device is %d", c->device, device);
+    void *ptr = nullptr;
+    int rc = scratch_of_current_device(device, &ptr);
+    if (rc != BGL_OK) return rc;
+    unsigned char *base = static_cast<unsigned char *>(ptr);
+    const LookupLists lists{reinterpret_cast<int32_t *>(base), NOALLOC_TILES,
+                            reinterpret_cast<int32_t *>(base + NOALLOC_MBS_BYTES), NOALLOC_MAX_IDS};
+    // (a timed launch may have to create events: this call's kernels are not timed)
+    const unsigned profiling = c->profiling;
+    c->profiling = 0;
+    rc = lookup_gather_impl(c, ids, n, out_rows, out_slot, miss_pos, n_hit_host, main_stream, side_stream,
+                            nullptr, false, &lists);
+    c->profiling = profiling;
+    return rc;
 } BGL_NOTHROW_END
 
 extern "C" int bgl_cache_lookup_gather_early(bgl_cache_t *c, const int32_t *ids, int64_t n,

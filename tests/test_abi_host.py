@@ -89,6 +89,7 @@ def test_null_handles_are_rejected_without_touching_the_gpu(L):
     assert L.bgl_cache_lookup_gather(None, None, 0, None, None, None, None, None, None) == B.BGL_EINVAL
     assert L.bgl_cache_insert_fifo(None, None, None, 0, None, None) == B.BGL_EINVAL
     assert L.bgl_cache_lookup_gather_early(None, None, 0, None, None, None, None, None, None, None) == B.BGL_EINVAL
+    assert L.bgl_cache_lookup_gather_noalloc(None, None, 0, None, None, None, None, None, None) == B.BGL_EINVAL
     assert L.bgl_cache_export_state(None, None, None, None) == B.BGL_EINVAL
     assert L.bgl_cache_stats(None, None, None, None, None, None) == B.BGL_EINVAL
     assert L.bgl_cache_map_stats(None, None, None, None, None, None) == B.BGL_EINVAL
