@@ -83,8 +83,8 @@ def sample_streams(graph, cfg, seed_batches, rng_seeds):
     return out
 
 
-def gpu_fifo_hit_ratio(streams, num_nodes, capacity):
-    """The library's FIFO cache (16-byte dummy rows: only hits are counted)."""
+def gpu_fifo_hits(streams, num_nodes, capacity):
+    """Hits of the library's FIFO cache over the batches (16-byte dummy rows: only hits are counted)."""
     import torch
     from . import binding as B
     feats = torch.zeros((num_nodes, 16), dtype=torch.uint8, device="cuda")
@@ -99,7 +99,50 @@ def gpu_fifo_hit_ratio(streams, num_nodes, capacity):
         cache.insert_fifo(ids, miss_pos, -1, out_rows)
     st = cache.stats()
     cache.close()
-    return st["hits"] / max(st["lookups"], 1)
+    assert st["lookups"] == sum(len(s) for s in streams)
+    return int(st["hits"])
+
+
+COLUMNS = ("static", "lru", "lfu", "fifo_random", "fifo_po", "lru_po")
+
+
+def run_study(cfg, row_ptr, col, num_batches, fractions):
+    """The study on one graph: seed orders (random, and proximity-aware from the library's
+    bgl_order_proximity), the input nodes of every batch from the library's sampler, and per cache
+    size the hits of every policy.  Returns a dictionary with the inputs it drew (train, roots,
+    shifts, rng_seeds, both seed orders), the streams, the capacities and `hits[capacity][column]`."""
+    from . import binding as B
+    N = cfg.num_nodes
+    graph = B.Graph(row_ptr, col)
+    nb = num_batches
+    rng = np.random.default_rng(cfg.seed + 7)
+    train = rng.choice(N, max(cfg.train_size, nb * cfg.batch), replace=False).astype(np.int32)
+    rng_seeds = rng.integers(0, 2**64, size=nb, dtype=np.uint64)
+    roots = rng.integers(0, N, cfg.po_sequences)
+    shifts = rng.integers(0, len(train), cfg.po_sequences)
+    po = B.order_proximity(graph, train, roots, shifts, nb * cfg.batch).reshape(nb, cfg.batch)
+    rnd = rng.permutation(train)[: nb * cfg.batch].reshape(nb, cfg.batch).astype(np.int32)
+    streams = {"random": sample_streams(graph, cfg, rnd, rng_seeds),
+               "po": sample_streams(graph, cfg, po, rng_seeds)}
+    # static cache: the nodes that appear most often as a neighbor, ties by id
+    hottest = np.argsort(-np.bincount(col, minlength=N), kind="stable").astype(np.int32)
+    hits, caps = {}, []
+    for frac in fractions:
+        cap = max(1, int(round(frac * N)))
+        caps.append(cap)
+        row = {}
+        for kind in ("static", "lru", "lfu"):
+            sim = PolicySim(kind, N, cap, hottest)
+            row[kind] = sum(sim.batch(s) for s in streams["random"])
+        row["fifo_random"] = gpu_fifo_hits(streams["random"], N, cap)
+        row["fifo_po"] = gpu_fifo_hits(streams["po"], N, cap)
+        sim = PolicySim("lru", N, cap)
+        row["lru_po"] = sum(sim.batch(s) for s in streams["po"])
+        hits[cap] = row
+    graph.close()
+    return dict(train=train, roots=roots, shifts=shifts, rng_seeds=rng_seeds, order_random=rnd, order_po=po,
+                streams=streams, hottest=hottest, capacities=caps, hits=hits,
+                lookups={k: sum(len(s) for s in v) for k, v in streams.items()})
 
 
 def main():
@@ -113,7 +156,6 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="override the number of seeds per batch")
     args = ap.parse_args()
     import torch
-    from . import binding as B
     from . import inputs
     cfg = inputs.CONFIGS[args.config]
     if args.nodes:
@@ -126,35 +168,19 @@ def main():
     t0 = time.time()
     row_ptr, col, _keep = inputs.make_graph(cfg)          # no feature table: only ids matter here
     N = cfg.num_nodes
-    graph = B.Graph(row_ptr, col)
     nb = min(args.batches, cfg.num_batches)
-    rng = np.random.default_rng(cfg.seed + 7)
-    train = rng.choice(N, max(cfg.train_size, nb * cfg.batch), replace=False).astype(np.int32)
-    rng_seeds = rng.integers(0, 2**64, size=nb, dtype=np.uint64)
-    roots = rng.integers(0, N, cfg.po_sequences)
-    shifts = rng.integers(0, len(train), cfg.po_sequences)
-    po = B.order_proximity(graph, train, roots, shifts, nb * cfg.batch).reshape(nb, cfg.batch)
-    rnd = rng.permutation(train)[: nb * cfg.batch].reshape(nb, cfg.batch).astype(np.int32)
-    streams = {"random": sample_streams(graph, cfg, rnd, rng_seeds),
-               "po": sample_streams(graph, cfg, po, rng_seeds)}
-    hottest = np.argsort(-np.bincount(col, minlength=N), kind="stable").astype(np.int32)
-    total = {k: sum(len(s) for s in v) for k, v in streams.items()}
+    fractions = [float(x) for x in args.fractions.split(",")]
+    r = run_study(cfg, row_ptr, col, nb, fractions)
+    total = r["lookups"]
     print(f"# Cache policy study on the `{cfg.name}` workload ({nb} batches, "
-          f"{total['random'] / nb:.0f} input nodes per batch; generated in {time.time() - t0:.0f} s)\n")
+          f"{total['random'] / nb:.0f} input nodes per batch; generated and run in {time.time() - t0:.0f} s)\n")
     print("| cache size (fraction of nodes) | static (in-degree) | LRU | LFU | FIFO, random order | "
           "FIFO, proximity-aware order | LRU, proximity-aware order |")
     print("|---|---|---|---|---|---|---|")
-    for frac in [float(x) for x in args.fractions.split(",")]:
-        cap = max(1, int(round(frac * N)))
-        row = []
-        for kind in ("static", "lru", "lfu"):
-            sim = PolicySim(kind, N, cap, hottest)
-            row.append(sum(sim.batch(s) for s in streams["random"]) / total["random"])
-        row.append(gpu_fifo_hit_ratio(streams["random"], N, cap))
-        row.append(gpu_fifo_hit_ratio(streams["po"], N, cap))
-        sim = PolicySim("lru", N, cap)
-        row.append(sum(sim.batch(s) for s in streams["po"]) / total["po"])
-        print(f"| {frac:.3f} ({cap} rows) | " + " | ".join(f"{x:.3f}" for x in row) + " |")
+    for frac, cap in zip(fractions, r["capacities"]):
+        row = r["hits"][cap]
+        ratios = [row[c] / total["po" if c.endswith("_po") else "random"] for c in COLUMNS]
+        print(f"| {frac:.3f} ({cap} rows) | " + " | ".join(f"{x:.3f}" for x in ratios) + " |")
     torch.cuda.synchronize()
 
 
