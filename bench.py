@@ -3,14 +3,17 @@
 
 One "step" = one minibatch through the whole path: k-hop neighbor sampling,
 cache lookup, gather of the hits from HBM, fetch of the misses from page-locked
-host memory, FIFO insertion.  Workload: the "mid" configuration (2.45 M nodes,
-~122 M edges, fp32 x 100 features, 1,024 seeds, fanout 15/10/5, cache of 20 % of
-the nodes, one epoch of 200 random-order batches starting from an empty cache),
-a synthetic stand-in with the shape of Ogbn-products.
+host memory, FIFO insertion.  By default all five configurations run, one after
+the other, each from an empty cache; the headline is the largest one that fits
+one GPU, "large" (111 M nodes, ~1.6 B edges with 64-bit offsets and the CSR in
+page-locked host memory, fp32 x 128 features, 1,024 seeds, fanout 15/10/5, cache
+of 25 M rows; 200 random-order batches), a synthetic stand-in with the shape of
+Ogbn-papers; the others ("wide", "mid" = the shape of Ogbn-products, "bfs",
+"tiny") are reported beside it in `configs`.  `--config NAME` runs one of them.
 
-Prints ONE JSON line: the headline value, the roofline of the hit gather (kernel time
-recorded by the kernel's own dispatch), the host-link rate of the miss fetch, and the CPU
-oracle timed on the same box.
+Prints ONE JSON line: the headline value, the roofline of the dominant HBM-bound
+kernel (kernel time recorded by the kernel's own dispatch), the host-link rate of
+the miss fetch, and the CPU oracle timed on the same box on the same batches.
 """
 from __future__ import annotations
 
@@ -34,13 +37,15 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="mid", help="workload preset (default: mid)")
+    ap.add_argument("--config", default="all",
+                    help="workload preset: tiny, mid, bfs, large, wide, or all (default): all five, one after the "
+                         "other, the headline on `large`, the others beside it in `configs`")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stage-timers", action="store_true",
                     help="leave the per-kernel HIP events out of the timed region")
     ap.add_argument("--all-stage-timers", action="store_true",
                     help="bracket every cache kernel with events (default: hit gather and miss fetch only)")
-    ap.add_argument("--miss-path", choices=("auto", "trial", "zero_copy", "staged", "staged_kernel"), default="auto",
+    ap.add_argument("--miss-path", choices=("auto", "trial", "zero_copy", "staged", "staged_scatter", "staged_kernel"), default="auto",
                     help="how miss rows cross the host link: kernels read the page-locked table in place "
                          "(zero_copy), or host threads pack the rows into a page-locked ring (no partial 128-byte "
                          "lines on the link) from where plain copies move them into device memory and kernels "
@@ -68,8 +73,9 @@ def parse_args():
                          "reported beside the headline, not part of it")
     ap.add_argument("--tier-threads", type=int, default=0, help="copy threads of the staging ring and of that tier (0 = three quarters of min(cores, 16))")
     ap.add_argument("--cpu-batches", type=int, default=200,
-                    help="batches of the same workload the oracle is timed on (10-30 s of CPU work on the "
-                         "configurations with 100-200 batches)")
+                    help="upper limit of the batches the oracle is timed on (it runs the first of the batches the "
+                         "GPU leg timed; with --config all at most 100 for the headline configuration and 20 for "
+                         "each of the others)")
     return ap.parse_args()
 
 
@@ -156,35 +162,26 @@ def hit_gather_sweep(torch, np, B):
             "timing": "begin/end of each kernel recorded on the device by its own dispatch"}
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
-              f"--gpus {args.gpus} is not supported", file=sys.stderr)
-        return 2
-    import numpy as np
-    import torch
-    if not torch.cuda.is_available():
-        print("bench.py needs a GPU", file=sys.stderr)
-        return 2
-    if args.calibrate_copy:
-        a = torch.full((1 << 30,), 7, dtype=torch.uint8, device="cuda")
-        b = torch.empty_like(a)
-        for _ in range(3):
-            b.copy_(a)
-        torch.cuda.synchronize()
-        print(json.dumps({"calibrate_copy_bytes": 1 << 30, "copies": 3}))
-        return 0
-    from paper_2112_08541_amd import binding as B
-    if args.hit_gather_sweep:
-        torch.cuda.set_device(0)
-        print(json.dumps(hit_gather_sweep(torch, np, B)))
-        return 0
-    from paper_2112_08541_amd import inputs
-    from paper_2112_08541_amd.pipeline import MinibatchPipeline
+def frac_in_lines(rb, hits, misses, assembled, write_through):
+    """Bytes the dominant kernel moves when every access is counted in whole 128-byte lines (what the
+    memory system moves): a row read at a random slot of the cache buffer touches every line it overlaps,
+    streams (the landed rows, the assembled output, the run of slots the misses go to) touch exactly
+    their bytes."""
+    def lines(off_step):
+        # mean 128-byte lines touched by a row of rb bytes that starts at a multiple of off_step
+        import math
+        g = math.gcd(off_step, 128)
+        offs = range(0, 128, g)
+        return sum(((o % 128) + rb + 127) // 128 for o in offs) / len(offs) * 128
+    row_lines = lines(rb)
+    if assembled:
+        return hits * (row_lines + rb) + misses * (3.0 if write_through else 2.0) * rb
+    return hits * 2.0 * row_lines            # hit rows land between miss rows that another kernel writes later
 
-    cfg = inputs.CONFIGS[args.config]
-    torch.cuda.set_device(0)
+
+def run_config(cfg, args, torch, np, B, inputs, MinibatchPipeline, want_cpu):
+    """One configuration: generate its inputs, warm up on a scratch cache, time `steps` minibatches of the
+    whole path from an empty cache, then the side measurements.  Returns the result dictionary."""
     w = inputs.make_workload(cfg, pinned=True)
     feat_t = w.features.ctypes.data      # address of the page-locked feature table
     feat_dev = None
@@ -200,6 +197,7 @@ def main():
     graph = B.Graph(w.row_ptr, w.col, placement)
     seeds_dev = torch.from_numpy(w.seed_batches).cuda()      # inputs resident in HBM
     nb = cfg.num_batches
+    steps = min(args.steps, nb) if args.steps_capped else args.steps
 
     def new_cache():
         return B.Cache(cfg.cache_rows, feat_t, num_nodes=cfg.num_nodes, row_bytes=cfg.row_bytes)
@@ -220,11 +218,13 @@ def main():
         miss_path = "staged" if (eligible and host_threads >= 8) else "zero_copy"
     stage_ring = None
     trial = {}
-    if miss_path in ("staged", "staged_kernel") or (miss_path == "trial" and eligible):
+    if miss_path in ("staged", "staged_scatter", "staged_kernel") or (miss_path == "trial" and eligible):
         # capacity 0: nothing is kept in host memory, every miss row passes through the ring
         stage_ring = B.HostTier(w.features.view(np.uint8).reshape(cfg.num_nodes, cfg.row_bytes), 0, pipe.cap,
                                 args.tier_threads)
-        stage_ring.set_copy_engine(miss_path != "staged_kernel")
+        # staged: one pass writes the whole output once the rows have landed; staged_scatter: hit gather at
+        # lookup time, landed rows scattered later; staged_kernel: kernels read the packed rows over the link
+        stage_ring.set_copy_engine({"staged_kernel": 0, "staged_scatter": 1}.get(miss_path, 2))
     if miss_path == "trial":
         miss_path = "zero_copy"
         if stage_ring is not None:
@@ -242,7 +242,8 @@ def main():
                 scratch = new_cache()
                 pipe.set_cache(scratch)
             miss_path = min(trial, key=trial.get)
-    staged = miss_path in ("staged", "staged_kernel")
+    staged = miss_path in ("staged", "staged_scatter", "staged_kernel")
+    copies_over_link = miss_path in ("staged", "staged_scatter")
     pipe.tier = stage_ring if staged else None
     if args.warmup > 0:
         pipe.run(seeds_dev, w.rng_seeds, args.warmup)
@@ -251,42 +252,44 @@ def main():
     cache = new_cache()
     pipe.set_cache(cache)
     # (a run of a few batches times every one of them)
-    g_every = 1 if (args.all_stage_timers or args.steps < 2 * GATHER_SAMPLE_EVERY) else GATHER_SAMPLE_EVERY
-    l_every = 1 if (args.all_stage_timers or args.steps < 2 * LINK_SAMPLE_EVERY) else LINK_SAMPLE_EVERY
+    g_every = 1 if (args.all_stage_timers or steps < 2 * GATHER_SAMPLE_EVERY) else GATHER_SAMPLE_EVERY
+    l_every = 1 if (args.all_stage_timers or steps < 2 * LINK_SAMPLE_EVERY) else LINK_SAMPLE_EVERY
     if not args.no_stage_timers:
-        # A timed launch holds its stream up for ~10 us, so the hit gather is timed in every 4th
-        # batch only and the miss fetch (several launches per batch) in every 10th.
-        cache.set_profiling(True if args.all_stage_timers else ("gather_hit", "fetch_miss", "link_copy"))
+        # A timed launch holds its stream up for ~10 us, so the kernels that move the rows in HBM are timed
+        # in every 4th batch only and what crosses the link (several launches per batch) in every 10th.
+        cache.set_profiling(True if args.all_stage_timers else ("gather_hit", "fetch_miss", "link_copy",
+                                                                 "assemble_pre", "assemble"))
         if not args.all_stage_timers:
-            cache.set_profiling_every("gather_hit", g_every)
+            for stage in ("gather_hit", "assemble_pre", "assemble"):
+                cache.set_profiling_every(stage, g_every)
             cache.set_profiling_every("fetch_miss", l_every)
             cache.set_profiling_every("link_copy", l_every)
     ring_before = stage_ring.stats() if staged else None
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    n_list, hit_list = pipe.run(seeds_dev, w.rng_seeds, args.steps)   # ends with a device synchronise
+    n_list, hit_list = pipe.run(seeds_dev, w.rng_seeds, steps)   # ends with a device synchronise
     t1 = time.perf_counter()
     elapsed = t1 - t0
 
     n_arr, h_arr = np.array(n_list, dtype=np.int64), np.array(hit_list, dtype=np.int64)
     tot_n, tot_hit = int(n_arr.sum()), int(h_arr.sum())
-    tot_miss = tot_n - tot_hit
     st = cache.stats()
     assert st["status"] == 0 and st["lookups"] == tot_n and st["hits"] == tot_hit
     # steady state: batches issued after the cache has filled once
     filled = np.cumsum(n_arr - h_arr) >= cfg.cache_rows
     steady = slice(int(np.argmax(filled)) + 1, None) if filled.any() else slice(0, 0)
     steady_ratio = (float(h_arr[steady].sum()) / float(n_arr[steady].sum())) if n_arr[steady].sum() else None
+    ms_map = cache.map_stats()
 
     rb = cfg.row_bytes
     result = {
         "metric": "minibatches/sec + gathered feature GB/s (% HBM peak) + cache hit ratio",
-        "value": args.steps / elapsed,
+        "value": steps / elapsed,
         "unit": "minibatches/s",
         "n_gpus": 1,
-        "steps": args.steps,
+        "steps": steps,
         "warmup": args.warmup,
-        "ms_per_step": 1e3 * elapsed / args.steps,
+        "ms_per_step": 1e3 * elapsed / steps,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -299,67 +302,104 @@ def main():
                         f"{cfg.order} seed order, epoch from an empty cache, miss path {miss_path}"
                         + ("" if args.graph_placement == "config" else f", CSR placement {where}")
                         + ("" if feat_dev is None else ", feature table in HBM"),
+            "name": cfg.name,
             "row_bytes": rb,
-            "mean_input_nodes": tot_n / args.steps,
+            "mean_input_nodes": tot_n / steps,
             "hit_ratio_cumulative": tot_hit / max(tot_n, 1),
             "hit_ratio_steady_state": steady_ratio,
             "miss_path": miss_path,
             "miss_path_trial_ms_per_batch": trial or None,
             "host_copy_threads": (stage_ring.stats()["threads"] if staged else 0),
-            "host_copy_ms_per_batch": ((stage_ring.stats()["copy_ms"] - ring_before["copy_ms"]) / args.steps
+            "host_copy_ms_per_batch": ((stage_ring.stats()["copy_ms"] - ring_before["copy_ms"]) / steps
                                        if staged else None),
             "gathered_feature_GBps": rb * tot_n / elapsed / 1e9,
+            "map_bucket_lines_per_lookup": ms_map["lines_per_id"],
         },
     }
     if not args.no_stage_timers:
         prof = cache.profile()
-        g_ms, g_n = prof["gather_hit"]
-        # The library has the kernel dispatch itself record the kernel's begin and end on the
-        # device, so g_ms is the sum of the kernel's own durations (what a kernel trace shows).
-        g_kernel_ms = max(g_ms, 1e-9)
-        g_sampled = [i for i in range(args.steps) if (i + 1) % g_every == 0]  # the cache counts its lookups from 1
+        g_sampled = [i for i in range(steps) if (i + 1) % g_every == 0]  # the cache counts its lookups from 1
         g_hit = int(sum(h_arr[i] for i in g_sampled))
-        achieved = 2.0 * rb * g_hit / (g_kernel_ms * 1e-3) / 1e9 if g_n > 0 else 0.0
-        # HBM bytes per launch from the committed rocprofv3 --pmc summary of this same workload
-        traffic = None
+        g_miss = int(sum(n_arr[i] - h_arr[i] for i in g_sampled))
+        # HBM bytes per batch of the dominant kernel from the committed rocprofv3 --pmc summary of this same
+        # workload (a builder-run profile, not measured in this run: counters need the profiler)
+        traffic, tsrc = None, None
         tpath = os.path.join(ROOT, "profiles", f"pmc_hbm_traffic_{cfg.name}.md")
+        assembled = prof["assemble"][1] > 0
         if os.path.exists(tpath):
             import re
-            m = re.search(r"^k_gather_hits hbm_bytes_per_launch = (\d+)", open(tpath).read(), re.M)
-            traffic = float(m.group(1)) if m else None
-        result["roofline"] = {
-            "kernel": "k_gather_hits", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-            "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-            "bytes_per_launch": 2.0 * rb * g_hit / max(g_n, 1),
-            "avg_launch_us": 1e3 * g_kernel_ms / max(g_n, 1), "launches": g_n,
-            "timing": "begin/end of each kernel recorded on the device by its own dispatch (hipExtLaunchKernelGGL "
-                      "events), every %d-th batch of the timed epoch" % g_every,
-        }
-        result["stage_ms_per_step"] = {k: (v[0] / (len(g_sampled) if k == "gather_hit" else args.steps)
-                                           if k != "event_overhead" else v[0])
-                                       for k, v in prof.items() if v[1] > 0 and k not in ("fetch_miss", "link_copy")}
-        # Host link: the miss fetch kernels of the sampled batches of the timed epoch
+            key = "k_assemble_rows" if assembled else "k_gather_hits"
+            m = re.search(r"^%s hbm_bytes_per_launch = (\d+)" % key, open(tpath).read(), re.M)
+            if m:
+                traffic = float(m.group(1))
+                tsrc = f"profiles/pmc_hbm_traffic_{cfg.name}.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, committed; not measured in this run)"
+        # The library has the kernel dispatch itself record the kernel's begin and end on the
+        # device, so the stage times are sums of the kernels' own durations (what a kernel trace shows).
+        timing = ("begin/end of each kernel recorded on the device by its own dispatch (hipExtLaunchKernelGGL "
+                  "events), every %d-th batch of the timed epoch" % g_every)
+        if assembled:
+            # One pass writes the whole output: per hit a row read from the cache buffer and written to out_rows,
+            # per miss a landed row read, written to out_rows and (write-through) to the cache buffer.  The short
+            # pass before it (hits whose slots this batch's misses take) is counted with it, bytes and time.
+            a_ms, a_n = prof["assemble"]
+            p_ms, p_n = prof["assemble_pre"]
+            per_miss = 3.0 if pipe.write_through else 2.0
+            moved = 2.0 * rb * g_hit + per_miss * rb * g_miss
+            k_ms = max(a_ms + p_ms, 1e-9)
+            achieved = moved / (k_ms * 1e-3) / 1e9
+            result["roofline"] = {
+                "kernel": "k_assemble_rows (with k_assemble_pre)", "bound": "hbm", "achieved": achieved,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                "traffic_source": tsrc,
+                "frac_lines": frac_in_lines(rb, g_hit, g_miss, True, pipe.write_through) / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "bytes_per_launch": moved / max(a_n, 1), "avg_launch_us": 1e3 * k_ms / max(a_n, 1), "launches": a_n,
+                "avg_us": {"k_assemble_rows": 1e3 * a_ms / max(a_n, 1), "k_assemble_pre": 1e3 * p_ms / max(p_n, 1)},
+                "bytes": "per batch: 2 x row_bytes x hits + %d x row_bytes x misses; a launch = the two passes of one batch" % per_miss,
+                "timing": timing,
+            }
+        else:
+            g_ms, g_n = prof["gather_hit"]
+            g_kernel_ms = max(g_ms, 1e-9)
+            achieved = 2.0 * rb * g_hit / (g_kernel_ms * 1e-3) / 1e9 if g_n > 0 else 0.0
+            result["roofline"] = {
+                "kernel": "k_gather_hits", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": tsrc,
+                "frac_lines": frac_in_lines(rb, g_hit, g_miss, False, pipe.write_through) / (g_kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "bytes_per_launch": 2.0 * rb * g_hit / max(g_n, 1),
+                "avg_launch_us": 1e3 * g_kernel_ms / max(g_n, 1), "launches": g_n,
+                "bytes": "per launch: 2 x row_bytes x hits",
+                "timing": timing,
+            }
+        skip = ("fetch_miss", "link_copy", "gather_hit", "assemble", "assemble_pre")
+        result["stage_ms_per_step"] = {k: (v[0] / steps if k != "event_overhead" else v[0])
+                                       for k, v in prof.items() if v[1] > 0 and k not in skip}
+        for k in ("gather_hit", "assemble", "assemble_pre"):
+            if prof[k][1] > 0:
+                result["stage_ms_per_step"][k] = prof[k][0] / max(len(g_sampled), 1)
+        # Host link: what carries the miss rows of the sampled batches of the timed epoch
         every = l_every
-        sampled = [i for i in range(args.steps) if (i + 1) % every == 0]      # the cache counts its lookups from 1
+        sampled = [i for i in range(steps) if (i + 1) % every == 0]      # the cache counts its lookups from 1
         # staged: the link is the copies' (timed by event records on the copy stream), the fetch stage is
         # the kernels that scatter the landed rows in device memory
-        over_link = "link_copy" if miss_path == "staged" else "fetch_miss"
+        over_link = "link_copy" if copies_over_link else "fetch_miss"
         f_ms, f_n = prof[over_link]
         miss3 = int(sum(n_arr[i] - h_arr[i] for i in sampled))
         link = miss3 * rb / (f_ms * 1e-3) / 1e9 if f_ms > 0 else 0.0
         h2d = measure_h2d_peak(torch)
         result["host_link"] = {
-            "kernel": {"staged": "hipMemcpyAsync of the packed rows", "staged_kernel": "k_fetch_rows"}.get(miss_path, "k_fetch_miss"),
+            "kernel": {"staged": "hipMemcpyAsync of the packed rows", "staged_scatter": "hipMemcpyAsync of the packed rows",
+                       "staged_kernel": "k_fetch_rows"}.get(miss_path, "k_fetch_miss"),
             "achieved": link, "unit": "GB/s",
             "nominal_peak": HOST_LINK_NOMINAL_GBS, "measured_h2d_copy_peak": h2d,
             "frac_of_nominal": link / HOST_LINK_NOMINAL_GBS, "frac_of_measured": link / h2d,
             "avg_launch_us": 1e3 * f_ms / max(f_n, 1), "launches_per_step": f_n / max(len(sampled), 1),
             "link_ms_per_step": f_ms / max(len(sampled), 1),
+            "link_bound_ms_per_step": 1e3 * (tot_n - tot_hit) / steps * rb / (h2d * 1e9),
             "note": "%s of every %d-th batch of the timed epoch (%d batches), timed by %s"
-                    % ("copies" if miss_path == "staged" else "fetch kernels", every, len(sampled),
-                       "event records around each copy" if miss_path == "staged" else "their dispatches"),
+                    % ("copies" if copies_over_link else "fetch kernels", every, len(sampled),
+                       "event records around each copy" if copies_over_link else "their dispatches"),
         }
-        if miss_path == "staged":
+        if miss_path == "staged_scatter":
             s_ms, s_n = prof["fetch_miss"]
             result["host_link"]["scatter_kernels_us_per_step"] = 1e3 * s_ms / max(len(sampled), 1)
             # the kernel that scatters the landed rows: every miss row read once from HBM and written
@@ -370,13 +410,12 @@ def main():
                 "kernel": "k_fetch_rows", "bound": "hbm", "achieved": a3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": a3 / HBM_PEAK_GBS, "bytes_per_step": moved / max(len(sampled), 1),
                 "avg_us_per_step": 1e3 * s_ms / max(len(sampled), 1), "launches": s_n,
-                "note": "landed miss rows to out_rows and the cache buffer, every %d-th batch; not the kernel "
-                        "the headline roofline is about" % every,
+                "note": "landed miss rows to out_rows and the cache buffer, every %d-th batch" % every,
             }
 
-        # The same kernel on a launch that is mostly hits (outside the timed region, not
-        # part of `value`): the epoch's last batch is looked up again right after its
-        # insertion; only the rows its own insertions evicted miss.
+        # The stand-alone hit gather (k_gather_hits, the kernel of bgl_cache_lookup_gather) on a launch that
+        # is mostly hits (outside the timed region, not part of `value`): the epoch's last batch is looked up
+        # again right after its insertion; only the rows its own insertions evicted miss.
         if pipe.last_n:
             cache.set_write_through(False)       # lookups without inserts follow
             cache.set_profiling(("gather_hit",))
@@ -424,7 +463,7 @@ def main():
         # tier serves the GPU cache's misses.
         store = np.array(w.features.view(np.uint8).reshape(cfg.num_nodes, rb), copy=True)
         tier_rows = int(args.two_level * cfg.num_nodes)
-        steps2 = min(args.steps, 100)
+        steps2 = min(steps, 100)
         tier = B.HostTier(store, tier_rows, pipe.cap, args.tier_threads)
         tier.set_copy_engine(args.miss_path != "staged_kernel")
         c2 = B.Cache(cfg.cache_rows, None, num_nodes=cfg.num_nodes, row_bytes=rb)
@@ -473,30 +512,115 @@ def main():
             "seconds": o1 - o0,
             "edges_traversed_per_s": cfg.po_sequences * w.num_edges / (o1 - o0),
         }
-        if not args.no_cpu_baseline:
+        if want_cpu:
             import oracle
             c0 = time.perf_counter()
             want = oracle.proximity_order(w.row_ptr, w.col, train, roots, shifts, len(train))
             result["ordering"]["oracle_seconds"] = time.perf_counter() - c0
             assert np.array_equal(order, want)
 
-    if not args.no_cpu_baseline:
+    if want_cpu:
+        # The CPU oracle on the batches the GPU leg has just run (a bounded sample: the first ones of them),
+        # one core; its input counts and hit counts must be the GPU's.
         import oracle
         oc = oracle.Cache(cfg.cache_rows, w.features)
-        nbat = min(args.cpu_batches, nb)
+        nbat = min(steps, nb, args.cpu_batches)
+        if args.steps_capped:                    # five configurations in one run: bound each one's share
+            nbat = min(nbat, 100 if cfg.name == HEADLINE else 20)
         c0 = time.perf_counter()
+        o_n, o_h = [], []
         for b in range(nbat):
             sg = oracle.sample_khop(w.row_ptr, w.col, w.seed_batches[b], cfg.fanouts, int(w.rng_seeds[b]))
             out, o_slot, o_miss, o_hit = oc.lookup_gather(sg.input_nodes)
             oc.insert_fifo(sg.input_nodes, o_miss, out)
+            o_n.append(len(sg.input_nodes))
+            o_h.append(o_hit)
         c1 = time.perf_counter()
+        assert o_n == n_list[:nbat] and o_h == hit_list[:nbat], "the oracle's batches differ from the GPU's"
         result["cpu_baseline"] = {
             "value": nbat / (c1 - c0), "unit": "minibatches/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {nbat} of the {nb} batches of the same workload, same inputs, "
-                      "from an empty cache (includes the Python/numpy marshalling around the C oracle)",
+            "sample": f"the first {nbat} of the {steps} timed batches of this workload, same inputs, from an empty "
+                      "cache (includes the Python/numpy marshalling around the C oracle); input and hit counts "
+                      "per batch checked against the GPU run",
             "host_cores_available": os.cpu_count(),
         }
-    print(json.dumps(result))
+    if stage_ring is not None:
+        stage_ring.close()
+    cache.close()
+    return result
+
+
+ALL_CONFIGS = ("large", "wide", "mid", "bfs", "tiny")
+HEADLINE = "large"       # the largest configuration that fits one GPU (Ogbn-papers shape)
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        return 2
+    import gc
+    import numpy as np
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    if args.calibrate_copy:
+        a = torch.full((1 << 30,), 7, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": 1 << 30, "copies": 3}))
+        return 0
+    from paper_2112_08541_amd import binding as B
+    torch.cuda.set_device(0)
+    if args.hit_gather_sweep:
+        print(json.dumps(hit_gather_sweep(torch, np, B)))
+        return 0
+    from paper_2112_08541_amd import inputs
+    from paper_2112_08541_amd.pipeline import MinibatchPipeline
+
+    names = ALL_CONFIGS if args.config == "all" else (args.config,)
+    args.steps_capped = args.config == "all"     # one line for five epochs of different lengths
+    results = {}
+    for name in names:
+        t0 = time.perf_counter()
+        results[name] = run_config(inputs.CONFIGS[name], args, torch, np, B, inputs, MinibatchPipeline,
+                                   want_cpu=not args.no_cpu_baseline)
+        results[name]["config"]["wall_seconds_incl_input_generation"] = time.perf_counter() - t0
+        gc.collect()
+        torch.cuda.empty_cache()
+    head = dict(results[HEADLINE if args.config == "all" else names[0]])
+    if args.config == "all":
+        # every configuration's figures beside the headline's (each one epoch, or `steps` batches of it,
+        # from an empty cache, with its own oracle sample)
+        def brief(r):
+            out = {"name": r["config"]["name"], "workload": r["config"]["workload"],
+                   "minibatches_per_s": r["value"], "ms_per_step": r["ms_per_step"], "steps": r["steps"],
+                   "mean_input_nodes": r["config"]["mean_input_nodes"],
+                   "hit_ratio_cumulative": r["config"]["hit_ratio_cumulative"],
+                   "hit_ratio_steady_state": r["config"]["hit_ratio_steady_state"],
+                   "gathered_feature_GBps": r["config"]["gathered_feature_GBps"],
+                   "miss_path": r["config"]["miss_path"],
+                   "map_bucket_lines_per_lookup": r["config"]["map_bucket_lines_per_lookup"]}
+            if "roofline" in r:
+                rf = r["roofline"]
+                out["roofline"] = {k: rf[k] for k in ("kernel", "achieved", "frac", "frac_lines", "bytes_per_launch",
+                                                      "avg_launch_us", "launches")}
+                out["roofline_repeat_lookup_frac"] = r.get("roofline_repeat_lookup", {}).get("frac")
+                hl = r["host_link"]
+                out["host_link"] = {k: hl[k] for k in ("kernel", "achieved", "frac_of_nominal", "frac_of_measured",
+                                                       "link_ms_per_step", "link_bound_ms_per_step")}
+            out["sampling_only_ms_per_batch"] = r["sampling_only"]["ms_per_batch"]
+            if "cpu_baseline" in r:
+                out["cpu_baseline"] = {k: r["cpu_baseline"][k] for k in ("value", "cores", "sample")}
+            if "ordering" in r:
+                out["ordering"] = r["ordering"]
+            return out
+        head["configs"] = [brief(results[n]) for n in names]
+    print(json.dumps(head))
     return 0
 
 

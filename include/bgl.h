@@ -343,7 +343,9 @@ int bgl_cache_map_stats(bgl_cache_t *c, uint64_t *ids_looked_up, uint64_t *bucke
 #define BGL_STAGE_INSERT_ROWS 5 /* out_rows -> cache buffer */
 #define BGL_STAGE_LINK_COPY 6   /* tiered lookup with the copy-engine transport: the copies over the host
                                    link, each bracketed by two event records on the copy stream */
-#define BGL_NUM_STAGES 7
+#define BGL_STAGE_ASSEMBLE_PRE 7 /* assembled output: the hits whose slots the call's own misses take */
+#define BGL_STAGE_ASSEMBLE 8    /* assembled output: every other row -> out_rows, miss rows -> cache buffer */
+#define BGL_NUM_STAGES 9
 /* pseudo stage: what two event records read around a kernel that does nothing
  * (measured when profiling is enabled; the share of BGL_STAGE_MISS_LIST that is
  * not kernel time); total_ms is that single figure */
@@ -396,19 +398,30 @@ int bgl_host_tier_create(const void *store, int64_t num_nodes, int32_t row_bytes
 int bgl_host_tier_destroy(bgl_host_tier_t *t);
 
 /*
- * Transport of the packed rows (off by default).  Off: kernels on side_stream
+ * Transport of the packed rows (0, off, by default).  0: kernels on side_stream
  * read the page-locked rows over the host link and write them to their places,
  * so the link is idle while those kernels wait for the lookup's hit gather.
- * On: plain copies on a stream of the tier's own move the packed rows into
+ * 1: plain copies on a stream of the tier's own move the packed rows into
  * device memory (2 * max_batch_rows rows of it, allocated by this call) as soon
  * as they are packed, independent of the cache's kernels; kernels on
  * side_stream then scatter them from there.  With early lookups the link then
- * carries one batch after the other without a pause.  Results are identical.
- * Waits for the device to go idle.  BGL_STAGE_FETCH_MISS then times the scatter
- * kernels, BGL_STAGE_LINK_COPY the copies.
- * Errors: BGL_EINVAL, BGL_ENOMEM, BGL_EHIP.
+ * carries one batch after the other without a pause.
+ * 2: as 1, and where the tier keeps nothing (capacity_rows = 0) and the cache is
+ * in write-through mode, the lookup has no hit gather of its own: once the rows
+ * have landed one pass writes the whole of out_rows in its own order (a hit's
+ * row from the cache buffer, a miss's row from the landed rows, which also go
+ * into the cache buffer), after a short pass that saves the hits whose slots
+ * this call's misses take.  Every output line is then written whole and the
+ * launch is large enough to fill the memory system.  The rows of the hits are
+ * then complete when the rows of the misses are (bgl_cache_wait_rows), not
+ * earlier.  Elsewhere mode 2 behaves as mode 1.
+ * Results are identical in all modes.  Waits for the device to go idle.
+ * BGL_STAGE_FETCH_MISS then times the scatter kernels, BGL_STAGE_LINK_COPY the
+ * copies, BGL_STAGE_ASSEMBLE_PRE and BGL_STAGE_ASSEMBLE the two passes of mode 2.
+ * Errors: BGL_EINVAL (null handle, a batch is being served, mode not 0..2),
+ * BGL_ENOMEM, BGL_EHIP.
  */
-int bgl_host_tier_set_copy_engine(bgl_host_tier_t *t, int enable);
+int bgl_host_tier_set_copy_engine(bgl_host_tier_t *t, int mode);
 
 /*
  * bgl_cache_lookup_gather with the host tier behind the GPU cache (workflow of

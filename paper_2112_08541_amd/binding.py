@@ -24,8 +24,9 @@ BGL_COUNTS_LEN = 2 * BGL_MAX_HOPS + 2
 BGL_NOALLOC_MAX_IDS = 1310720
 BGL_DEVICE, BGL_HOST_PINNED, BGL_HOST_PINNED_COL = 0, 1, 2
 (STAGE_PROBE, STAGE_MISS_LIST, STAGE_GATHER_HIT, STAGE_FETCH_MISS,
- STAGE_INSERT_MAP, STAGE_INSERT_ROWS, STAGE_LINK_COPY) = range(7)
-STAGE_NAMES = ["probe", "miss_list", "gather_hit", "fetch_miss", "insert_map", "insert_rows", "link_copy"]
+ STAGE_INSERT_MAP, STAGE_INSERT_ROWS, STAGE_LINK_COPY, STAGE_ASSEMBLE_PRE, STAGE_ASSEMBLE) = range(9)
+STAGE_NAMES = ["probe", "miss_list", "gather_hit", "fetch_miss", "insert_map", "insert_rows", "link_copy",
+               "assemble_pre", "assemble"]
 
 EXPORTS = [
     "bgl_last_error", "bgl_graph_load_csr", "bgl_graph_destroy", "bgl_sample_workspace_bytes",
@@ -407,10 +408,11 @@ class HostTier:
 
     __del__ = close
 
-    def set_copy_engine(self, enable: bool) -> None:
+    def set_copy_engine(self, mode) -> None:
         """Packed rows cross the link as plain copies into device memory (then scattered by kernels)
-        instead of being read over the link by the kernels themselves."""
-        _check(lib().bgl_host_tier_set_copy_engine(self._h, 1 if enable else 0))
+        instead of being read over the link by the kernels themselves.  mode: False/0, True/1, or
+        2 = as 1, with the cache writing its whole output in one pass where it can."""
+        _check(lib().bgl_host_tier_set_copy_engine(self._h, int(mode)))
 
     def export_state(self, with_buffer: bool = True):
         s2n = np.empty(self.capacity, dtype=np.int32)

@@ -79,6 +79,8 @@ struct bgl_cache {
     int64_t last_n = 0;              // n of the most recent lookup
     int32_t *mpos_copy[2] = {nullptr, nullptr};  // early lookups: the library's own copy of miss_pos, alternating between calls
     int64_t mpos_cap[2] = {0, 0};
+    int32_t *src_of[2] = {nullptr, nullptr};  // assembled output: where each position's row comes from, alternating between calls
+    int64_t src_cap[2] = {0, 0};
     uint64_t lookup_calls = 0;
     uint64_t insert_calls = 0;       // FIFO updates enqueued so far (selects the live copy of tail)
     hipStream_t own_side = nullptr;  // the miss fetch's stream when the caller names none; created on first use
@@ -227,7 +229,7 @@ __global__ __launch_bounds__(KEYS_PER_TILE) void k_split_list(const int32_t *__r
                                                               int64_t *n_hit_host,
                                                               const int32_t *__restrict__ ids,
                                                               int64_t num_nodes, int32_t *miss_ids_host,
-                                                              int32_t *miss_pos_copy, int gen)
+                                                              int32_t *miss_pos_copy, int gen, int32_t *src_of)
 {
     __shared__ int sh_scan[KEYS_PER_TILE / kWave];
     __shared__ int sh_base;
@@ -253,10 +255,13 @@ __global__ __launch_bounds__(KEYS_PER_TILE) void k_split_list(const int32_t *__r
             miss_ids_host[mrank] = id;
             if (id < 0 || (int64_t)id >= num_nodes) n_hit_host[3] = 1;  // the host refuses the batch
         }
-    } else if (i < n) {
+    } else if (i < n && !src_of) {
         hit_pos[i - mrank] = (int32_t)i;
         hit_slot[i - mrank] = slot;
     }
+    // assembled output (k_assemble_rows): the source of every position's row, a slot of the cache
+    // buffer (>= 0) or, as -(r + 1), miss number r, whose row comes in with the packed miss rows
+    if (src_of && i < n) src_of[i] = flag ? -(mrank + 1) : slot;
     if (blockIdx.x != gridDim.x - 1) return;
     // the last workgroup publishes the call's counters
     int lines = 0, all_lines;
@@ -489,6 +494,154 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_rows(
                 if (r3 >= start) st16<NT>(&buffer[wrapped(tail_slot + r3, capacity) * qq + c3], v3);
             }
         }
+    }
+}
+
+// ---- assembled output
+// With the packed miss rows of a call already in device memory (the copy engine
+// has landed them, in miss order), one pass over the output in its own order can
+// write every row: a hit's row comes from the cache buffer, a miss's row from the
+// landed rows, and the miss rows also go to the buffer slots the FIFO rule gives
+// them (write-through).  Every output line is then written whole by one stream of
+// stores, and the hit gather and the scatter of the landed rows are one launch
+// large enough to fill the memory system.  One hazard: a hit whose slot lies in
+// the window of slots that this call's own misses are written to must be read
+// before it is overwritten.  Those rows (few when a batch's misses are few
+// against the capacity, all of the hits when they outnumber it) are copied by
+// k_assemble_pre, which runs first; k_assemble_rows leaves them alone.
+//
+// The window: ranks start <= r < n_miss go to slots (tail + r) mod capacity, less
+// than one turn of the buffer.
+struct FifoWindow {
+    int64_t first;     // slot of rank `start`
+    int64_t count;     // n_miss - start
+    int64_t start;
+    int64_t capacity;
+    __device__ __forceinline__ FifoWindow(unsigned long long tail, int64_t n_miss, int64_t cap) : capacity(cap)
+    {
+        start = n_miss > cap ? n_miss - cap : 0;
+        count = n_miss - start;
+        first = (int64_t)((tail + (unsigned long long)start) % (unsigned long long)cap);
+    }
+    __device__ __forceinline__ bool holds(int32_t slot) const
+    {
+        int64_t d = (int64_t)slot - first;
+        if (d < 0) d += capacity;
+        return d < count;
+    }
+    __device__ __forceinline__ int64_t slot_of_rank(int64_t r) const  // start <= r < n_miss
+    {
+        const int64_t s = first + (r - start);
+        return s >= capacity ? s - capacity : s;
+    }
+};
+
+// The hits inside the window, copied before the window is written.  Each wavefront scans 64
+// positions (one per lane), packs the ones concerned into LDS with a ballot and copies their rows
+// with all its lanes, four 16-byte chunks in flight per lane.
+template <int Q>
+__global__ __launch_bounds__(COPY_THREADS) void k_assemble_pre(
+    const int32_t *__restrict__ src_of, int64_t n, int q, const uint4 *__restrict__ buffer,
+    uint4 *__restrict__ out, const CacheDev *dev, int64_t capacity, int par, int64_t n_miss)
+{
+    constexpr int WAVES = COPY_THREADS / kWave;
+    __shared__ int32_t sh_pos[WAVES][kWave];
+    __shared__ int32_t sh_slot[WAVES][kWave];
+    const int qq = Q > 0 ? Q : q;
+    const FifoWindow win(dev->tail[par], n_miss, capacity);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int64_t step = (int64_t)gridDim.x * COPY_THREADS;
+    for (int64_t base = (int64_t)blockIdx.x * COPY_THREADS + wave * kWave; base < n; base += step) {
+        const int64_t i = base + lane;
+        const int32_t s = i < n ? src_of[i] : -1;
+        const bool mine = s >= 0 && win.holds(s);
+        const uint64_t mask = __ballot(mine);
+        if (mask == 0) continue;  // (uniform in the wavefront)
+        const int m = __popcll(mask);
+        if (mine) {
+            const int at = __popcll(mask & ((1ull << lane) - 1ull));
+            sh_pos[wave][at] = (int32_t)i;
+            sh_slot[wave][at] = s;
+        }
+        // (the lists are written and read by this wavefront only)
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const int total = m * qq;
+        for (int k0 = 0; k0 < total; k0 += 4 * kWave) {
+            const int last = total - 1;
+            const int k[4] = {min(k0 + lane, last), min(k0 + kWave + lane, last), min(k0 + 2 * kWave + lane, last),
+                              min(k0 + 3 * kWave + lane, last)};
+            int j[4], cc[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if constexpr (Q > 0) { j[u] = k[u] / Q; cc[u] = k[u] - j[u] * Q; }
+                else { j[u] = k[u] / q; cc[u] = k[u] - j[u] * q; }
+            }
+            const uint4 v0 = buffer[(int64_t)sh_slot[wave][j[0]] * qq + cc[0]];
+            const uint4 v1 = buffer[(int64_t)sh_slot[wave][j[1]] * qq + cc[1]];
+            const uint4 v2 = buffer[(int64_t)sh_slot[wave][j[2]] * qq + cc[2]];
+            const uint4 v3 = buffer[(int64_t)sh_slot[wave][j[3]] * qq + cc[3]];
+            out[(int64_t)sh_pos[wave][j[0]] * qq + cc[0]] = v0;
+            out[(int64_t)sh_pos[wave][j[1]] * qq + cc[1]] = v1;
+            out[(int64_t)sh_pos[wave][j[2]] * qq + cc[2]] = v2;
+            out[(int64_t)sh_pos[wave][j[3]] * qq + cc[3]] = v3;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// Every other row, in output order: chunk number -> (position, chunk in row); the position's
+// source decides where the chunk is read.  Phases as in k_gather_hits: the four sources of a lane,
+// then its four chunks, then the stores; chunk numbers beyond the end are clamped to the last
+// chunk, which is then copied again.  A chunk of a hit inside the window is read (from a slot that
+// may be changing: the value is not used) and not stored.
+template <int Q>
+__global__ __launch_bounds__(COPY_THREADS) void k_assemble_rows(
+    const int32_t *__restrict__ src_of, int64_t n, int q, const uint4 *__restrict__ landed,
+    uint4 *buffer, uint4 *__restrict__ out, const CacheDev *dev, int64_t capacity, int par, int64_t n_miss)
+{
+    static_assert(COPY_UNROLL == 4, "the four chunks of a lane are written out by hand");
+    const int qq = Q > 0 ? Q : q;
+    const int64_t total = n * qq;
+    const int64_t last = total - 1;
+    const FifoWindow win(dev->tail[par], n_miss, capacity);
+    const int64_t step = (int64_t)gridDim.x * (COPY_THREADS * COPY_UNROLL);
+    for (int64_t base = (int64_t)blockIdx.x * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
+         base - threadIdx.x < total; base += step) {
+        const int64_t x0 = min(base, last), x1 = min(base + COPY_THREADS, last),
+                      x2 = min(base + 2 * COPY_THREADS, last), x3 = min(base + 3 * COPY_THREADS, last);
+        int64_t i0, i1, i2, i3;
+        int c0, c1, c2, c3;
+        RowSplit<Q>::split(x0, q, i0, c0);
+        RowSplit<Q>::split(x1, q, i1, c1);
+        RowSplit<Q>::split(x2, q, i2, c2);
+        RowSplit<Q>::split(x3, q, i3, c3);
+        const int32_t s0 = src_of[i0], s1 = src_of[i1], s2 = src_of[i2], s3 = src_of[i3];
+        auto source = [&](int32_t s, int c) -> const uint4 * {
+            return s >= 0 ? buffer + (int64_t)s * qq + c : landed + (int64_t)(-s - 1) * qq + c;
+        };
+        uint4 v0 = *source(s0, c0);
+        uint4 v1 = *source(s1, c1);
+        uint4 v2 = *source(s2, c2);
+        uint4 v3 = *source(s3, c3);
+        // (the four reads stay above the branches that follow: the values are needed here)
+        asm volatile("" : "+v"(v0.x), "+v"(v0.y), "+v"(v0.z), "+v"(v0.w), "+v"(v1.x), "+v"(v1.y), "+v"(v1.z), "+v"(v1.w),
+                          "+v"(v2.x), "+v"(v2.y), "+v"(v2.z), "+v"(v2.w), "+v"(v3.x), "+v"(v3.y), "+v"(v3.z), "+v"(v3.w));
+        auto store = [&](int32_t s, int c, int64_t x, const uint4 &v) {
+            if (s >= 0) {
+                if (!win.holds(s)) st16<true>(&out[x], v);
+            } else {
+                st16<true>(&out[x], v);
+                const int64_t r = -(int64_t)s - 1;
+                if (r >= win.start) st16<true>(&buffer[win.slot_of_rank(r) * qq + c], v);
+            }
+        };
+        store(s0, c0, x0, v0);
+        store(s1, c1, x1, v1);
+        store(s2, c2, x2, v2);
+        store(s3, c3, x3, v3);
     }
 }
 
@@ -848,6 +1001,8 @@ try {
     (void)hipFree(c->hit_pos);
     (void)hipFree(c->mpos_copy[0]);
     (void)hipFree(c->mpos_copy[1]);
+    (void)hipFree(c->src_of[0]);
+    (void)hipFree(c->src_of[1]);
     delete c;
     return BGL_OK;
 } BGL_NOTHROW_END
@@ -872,7 +1027,8 @@ struct LookupLists {
 // fetch while this one's lists are written.
 int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, int32_t *out_slot,
                  int32_t *miss_pos, int64_t *n_hit_dev, hipStream_t ms, hipStream_t ls, bgl_host_tier *tier,
-                 const int32_t **mpos_used, int *gen_used, const LookupLists *fixed = nullptr)
+                 const int32_t **mpos_used, int *gen_used, const LookupLists *fixed = nullptr,
+                 const int32_t **src_of_used = nullptr)
 {
     const bool early = ls != ms;
     const int gen = (int)(c->lookup_calls & 1);  // which copy of the per-call device state this call owns
@@ -912,6 +1068,23 @@ int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, in
         mpos_copy = c->mpos_copy[g];
     }
     *mpos_used = early ? mpos_copy : miss_pos;
+    // Assembled output (the caller launches k_assemble_pre / k_assemble_rows once the miss rows have
+    // landed): the list kernel records every position's source, and there is no hit gather here.
+    int32_t *src_of = nullptr;
+    if (src_of_used) {
+        const int g = gen;
+        if (n > c->src_cap[g]) {
+            BGL_HIP(hipDeviceSynchronize());
+            (void)hipFree(c->src_of[g]);
+            c->src_of[g] = nullptr;
+            c->src_cap[g] = 0;
+            const int64_t cap = std::max<int64_t>(n + n / 2, 4096);
+            BGL_HIP(hipMalloc((void **)&c->src_of[g], sizeof(int32_t) * (size_t)cap));
+            c->src_cap[g] = cap;
+        }
+        src_of = c->src_of[g];
+        *src_of_used = src_of;
+    }
     int32_t *const mbs = fixed ? fixed->mbs : c->mbs;
     const int64_t mbs_cap = fixed ? fixed->mbs_cap : c->mbs_cap;
     int32_t *const hit_pos = fixed ? fixed->hit_pos : c->hit_pos;
@@ -945,7 +1118,7 @@ int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, in
             hipLaunchKernelGGL(k_split_list, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), 0, ls, out_slot,
                                n, mbs, tile_prefix, mbs + 2 * mbs_cap, miss_pos, hit_pos, hit_pos + hit_cap, c->dev,
                                n_hit_dev, ids, c->num_nodes,
-                               tier ? bgl::tier_ids_device_if_passthrough(tier) : nullptr, mpos_copy, gen);
+                               tier ? bgl::tier_ids_device_if_passthrough(tier) : nullptr, mpos_copy, gen, src_of);
         }
     } else {
         hipLaunchKernelGGL(k_empty_lookup, dim3(1), dim3(64), 0, ls, c->dev, n_hit_dev, gen);
@@ -964,7 +1137,7 @@ int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, in
     c->map_pending = false;
     c->last_main = ms;
     c->ev_listed_valid = true;
-    if (n > 0) {
+    if (n > 0 && !src_of) {
         Prof p(c, BGL_STAGE_GATHER_HIT, ms);
         dispatch_q(q, [&](auto Q) {
             launch(c, ms, k_gather_hits<decltype(Q)::value>, dim3(copy_blocks(n, q)), dim3(COPY_THREADS),
@@ -1166,6 +1339,7 @@ struct TieredRows {
     int64_t n;
     int par;               // which copy of the cache's tail the kernels read
     bool early;            // the lookup ran early: the host is ahead of the link
+    const int32_t *src_of; // assembled output: the source of every position's row (else null)
 
     // out[mpos[rank[l]]] = base[(first + l) mod ring] for l0 <= l < l0 + count.  landed: the rows are in
     // device memory (whole chip; rows read once, and written for a later kernel: non-temporal accesses, so
@@ -1185,6 +1359,31 @@ struct TieredRows {
             launch(c, ss, k, dim3(blocks), dim3(COPY_THREADS), rank, l0, count, first, ring, mpos, q,
                    reinterpret_cast<const uint4 *>(base), reinterpret_cast<uint4 *>(out_rows), c->dev,
                    reinterpret_cast<uint4 *>(c->buffer), c->capacity, par, n - plan->n_hit_gpu);
+        });
+    }
+    // Assembled output, first launch: the hits whose slots this call's misses are about to take.
+    void launch_assemble_pre() const
+    {
+        const int q = c->row_bytes / 16;
+        Prof p(c, BGL_STAGE_ASSEMBLE_PRE, ss);
+        const int blocks = (int)std::min<int64_t>(bgl::ceil_div(n, COPY_THREADS), 2048);
+        dispatch_q(q, [&](auto Q) {
+            launch(c, ss, k_assemble_pre<decltype(Q)::value>, dim3(blocks), dim3(COPY_THREADS), src_of, n, q,
+                   reinterpret_cast<const uint4 *>(c->buffer), reinterpret_cast<uint4 *>(out_rows), c->dev,
+                   c->capacity, par, n - plan->n_hit_gpu);
+        });
+    }
+    // Second launch, once the packed miss rows are in `land`: every other row of the output, and
+    // the miss rows into the cache buffer.
+    void launch_assemble_rows(const char *land) const
+    {
+        const int q = c->row_bytes / 16;
+        Prof p(c, BGL_STAGE_ASSEMBLE, ss);
+        const int blocks = (int)std::min<int64_t>(copy_blocks(n, q), 8192);
+        dispatch_q(q, [&](auto Q) {
+            launch(c, ss, k_assemble_rows<decltype(Q)::value>, dim3(blocks), dim3(COPY_THREADS), src_of, n, q,
+                   reinterpret_cast<const uint4 *>(land), reinterpret_cast<uint4 *>(c->buffer),
+                   reinterpret_cast<uint4 *>(out_rows), c->dev, c->capacity, par, n - plan->n_hit_gpu);
         });
     }
 };
@@ -1255,6 +1454,12 @@ int rows_by_copy_engine(const TieredRows &r, char *land)
         }
     }
     bgl::tier_copy_wait(t);
+    if (r.src_of) {  // (the tier keeps nothing: plan.n_hit == 0, the landed rows are in miss order)
+        r.launch_assemble_pre();  // needs no landed row: it runs while the copies are still on their way
+        BGL_HIP(hipStreamWaitEvent(r.ss, bgl::tier_copy_event(t), 0));
+        r.launch_assemble_rows(land);
+        return BGL_OK;
+    }
     BGL_HIP(hipStreamWaitEvent(r.ss, bgl::tier_copy_event(t), 0));  // (recorded behind the last copy)
     r.launch_rows(land, 0ull, (int64_t)INT64_MAX, plan.hit_rank, 0, plan.n_hit, true);
     r.launch_rows(land + (size_t)plan.n_hit * rb, 0ull, (int64_t)INT64_MAX, plan.miss_rank, 0, plan.n_miss, true);
@@ -1332,7 +1537,14 @@ try {
     }
     const int32_t *mpos = nullptr;
     int gen = 0;
-    rc = lookup_phase(c, ids, n, out_rows, out_slot, miss_pos, bgl::tier_count_device(t), ms, ls, t, &mpos, &gen);
+    // One pass that writes the whole output (k_assemble_rows) instead of a hit gather now and a scatter of
+    // the landed miss rows later: when the tier was asked for it, keeps nothing (its packed rows are then
+    // in miss order), lands them in device memory, and the cache is in write-through mode.
+    const bool assemble = bgl::tier_assemble(t) && bgl::tier_capacity(t) == 0 && c->write_through &&
+                          bgl::tier_landing(t, (int)(c->lookup_calls & 1)) != nullptr;
+    const int32_t *src_of = nullptr;
+    rc = lookup_phase(c, ids, n, out_rows, out_slot, miss_pos, bgl::tier_count_device(t), ms, ls, t, &mpos, &gen,
+                      nullptr, assemble ? &src_of : nullptr);
     if (rc != BGL_OK) return rc;
     BGL_HIP(hipGetLastError());
     struct Guard {  // whatever goes wrong below, the copy threads are released and the batch is dropped
@@ -1348,13 +1560,15 @@ try {
     // (Waking the copy threads earlier, to have them spin until the ids arrive, was measured:
     // slower, the spinning threads get in the way of the wait for the lookup.)
     if (ss != ms) BGL_HIP(hipStreamWaitEvent(ss, c->ev_listed, 0));
+    const TieredRows rows{c, t, &plan, ss, mpos, out_rows, n, (int)(c->insert_calls & 1), ls != ms, src_of};
     if (plan.n_hit + plan.n_miss > 0) {
-        TieredRows rows{c, t, &plan, ss, mpos, out_rows, n, (int)(c->insert_calls & 1), ls != ms};
         rc = bgl::tier_copy_start(t);  // host threads start packing
         if (rc != BGL_OK) return rc;
         char *land = bgl::tier_landing(t, gen);  // device memory the copy engine fills, if that transport is on
         rc = land ? rows_by_copy_engine(rows, land) : rows_by_kernels(rows);
         if (rc != BGL_OK) return rc;
+    } else if (src_of && n > 0) {
+        rows.launch_assemble_rows(nullptr);  // every id hit: the pass only gathers (no landed row is read)
     }
     BGL_HIP(hipEventRecord(c->ev_miss, ss));
     // the tier's map changes after this call's lists are final and before the next lookup,

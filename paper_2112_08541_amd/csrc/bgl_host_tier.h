@@ -60,6 +60,8 @@ void tier_copy_wait(bgl_host_tier *t);
 // have parity gen are copied into tier_landing(t, gen) (device memory, max_batch rows) on
 // tier_copy_stream(t) before kernels scatter them; null when the transport is off.
 char *tier_landing(bgl_host_tier *t, int gen);
+// Mode 2 of the transport: the cache may write its whole output in one pass once the rows have landed.
+bool tier_assemble(const bgl_host_tier *t);
 hipStream_t tier_copy_stream(bgl_host_tier *t);
 hipEvent_t tier_copy_event(bgl_host_tier *t);
 // whether that event has ever been recorded (the caller records it behind every copy it enqueues)

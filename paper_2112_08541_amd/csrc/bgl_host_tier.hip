@@ -175,6 +175,7 @@ struct bgl_host_tier {
     char *pinned_dev = nullptr;
     // copy-engine transport: device memory the packed rows land in (one per call parity), its stream and event
     char *landing[2] = {nullptr, nullptr};
+    bool assemble = false;     // copy-engine transport, mode 2: the cache writes its whole output in one pass
     hipStream_t copy_stream = nullptr;  // shared by all tiers of the process (not owned)
     hipEvent_t copy_event = nullptr;
     bool copy_event_recorded = false;
@@ -216,6 +217,7 @@ int32_t *tier_ids_device_if_passthrough(bgl_host_tier *t)
 }
 int32_t tier_row_bytes(const bgl_host_tier *t) { return t->row_bytes; }
 char *tier_landing(bgl_host_tier *t, int gen) { return t->landing[gen & 1]; }
+bool tier_assemble(const bgl_host_tier *t) { return t->assemble; }
 hipStream_t tier_copy_stream(bgl_host_tier *t) { return t->copy_stream; }
 hipEvent_t tier_copy_event(bgl_host_tier *t) { return t->copy_event; }
 bool tier_copy_event_recorded(const bgl_host_tier *t) { return t->copy_event_recorded; }
@@ -491,7 +493,9 @@ extern "C" int bgl_host_tier_set_copy_engine(bgl_host_tier_t *t, int enable)
 try {
     if (!t) BGL_FAIL(BGL_EINVAL, "tier handle is null");
     if (t->serving) BGL_FAIL(BGL_EINVAL, "host tier: a batch is being served");
+    if (enable < 0 || enable > 2) BGL_FAIL(BGL_EINVAL, "the transport is 0, 1 or 2 (got %d)", enable);
     BGL_HIP(hipDeviceSynchronize());  // earlier batches may still use what this call changes
+    t->assemble = enable == 2;
     if (!enable) {
         for (int g = 0; g < 2; ++g) {
             (void)hipFree(t->landing[g]);

@@ -2,9 +2,10 @@
 (1,024-byte rows x 4.5 M slots: the `wide` shape; 512-byte rows x 9.5 M slots: the row width of
 `large`), filled, wrapped around several times and evicted from by million-id batches, compared
 with the CPU oracle after every call and byte by byte at the end, on both sides of the 4 GiB
-offset.  The batches take turns through the four ways a miss row gets into the buffer: the FIFO
-update's row copy, the write-through fetch from the page-locked table, and the write-through
-scatter of packed rows (landed by the copy engine, or read over the link)."""
+offset.  The batches take turns through the five ways a miss row gets into the buffer: the FIFO
+update's row copy, the write-through fetch from the page-locked table, the write-through
+scatter of packed rows (landed by the copy engine, or read over the link), and the one pass that
+writes the whole output and the landed miss rows' slots."""
 import os
 
 import numpy as np
@@ -15,7 +16,9 @@ from helpers import assert_state_equal
 pytestmark = pytest.mark.gpu
 
 SKIP_FULL = os.environ.get("BGL_SKIP_FULL_SIZE", "") not in ("", "0")
-MODES = ("row_copy", "write_through", "write_through_landed", "write_through_packed_over_link")
+MODES = ("row_copy", "write_through", "write_through_landed", "write_through_packed_over_link",
+         "write_through_assembled")
+TRANSPORT = {"write_through_landed": 1, "write_through_packed_over_link": 0, "write_through_assembled": 2}
 
 
 @pytest.mark.skipif(SKIP_FULL, reason="BGL_SKIP_FULL_SIZE is set")
@@ -46,7 +49,7 @@ def test_cache_buffer_beyond_4gib_wraps_and_evicts(row_bytes, cap, num_nodes, fr
     miss_pos = torch.empty(n_max, dtype=torch.int32, device="cuda")
     sweep = rng.permutation(num_nodes).astype(np.int32)              # ids not in the cache when their turn comes
     wrote_past_4gib = {m: False for m in MODES}
-    b = 0
+    b = past = 0
     while oc.tail < turns * cap:
         take = (np.arange(fresh, dtype=np.int64) + b * fresh) % num_nodes
         ids = sweep[take]
@@ -57,7 +60,14 @@ def test_cache_buffer_beyond_4gib_wraps_and_evicts(row_bytes, cap, num_nodes, fr
         ids = np.ascontiguousarray(ids, dtype=np.int32)
         n = len(ids)
         ids_t = torch.from_numpy(ids).cuda()
-        mode = MODES[b % len(MODES)]
+        # the modes take turns, separately over the batches whose insertions reach beyond 4 GiB (the swept ids
+        # all miss, the held ones all hit, so where a batch's insertions go is known beforehand) and the others
+        e0, e1 = oc.tail % cap, (oc.tail + fresh - 1) % cap
+        if e1 < e0 or e1 >= first_slot_past_4gib:
+            mode = MODES[past % len(MODES)]
+            past += 1
+        else:
+            mode = MODES[b % len(MODES)]
         gc.set_write_through(mode != "row_copy")
         if mode in ("row_copy", "write_through"):
             gc.lookup_gather(ids_t, n, out, out_slot, miss_pos)
@@ -66,7 +76,7 @@ def test_cache_buffer_beyond_4gib_wraps_and_evicts(row_bytes, cap, num_nodes, fr
             torch.cuda.synchronize()
             n_hit = int(gc.n_hit_host[0])
         else:
-            tier.set_copy_engine(mode == "write_through_landed")
+            tier.set_copy_engine(TRANSPORT[mode])
             n_hit, _ = gc.lookup_gather_tiered(tier, ids_t, n, out, out_slot, miss_pos)
             gc.insert_fifo(ids_t, miss_pos, -1, out)
             gc.wait_rows()

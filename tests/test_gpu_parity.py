@@ -509,7 +509,7 @@ def run_overlapped_against_oracle(torch_mod, B, w, steps, write_through=True, st
     pipe = MinibatchPipeline(graph, cache, cfg.batch, cfg.fanouts, cfg.row_bytes, write_through=write_through)
     if staged:
         pipe.tier = B.HostTier(w.features.view(np.uint8).reshape(cfg.num_nodes, cfg.row_bytes), 0, pipe.cap, 0)
-        pipe.tier.set_copy_engine(True)
+        pipe.tier.set_copy_engine(int(staged))        # True: landed rows scattered; 2: the whole output in one pass
     seeds_dev = torch_mod.from_numpy(w.seed_batches).cuda()
     got = {}
 
@@ -535,7 +535,7 @@ def run_overlapped_against_oracle(torch_mod, B, w, steps, write_through=True, st
     assert_state_equal(cache, op.cache, "overlapped")
 
 
-@pytest.mark.parametrize("miss_path", ["zero_copy", "staged", "staged_kernel"])
+@pytest.mark.parametrize("miss_path", ["zero_copy", "staged", "staged_kernel", "staged_assembled"])
 def test_overlapped_pipeline_full_epoch_counts_and_final_state(torch_mod, B, miss_path):
     """The whole benchmarked epoch (mid, 200 batches, overlapped, write-through) on both miss
     paths (staged = the ring of a host tier that keeps nothing, with the early lookup, as
@@ -550,7 +550,7 @@ def test_overlapped_pipeline_full_epoch_counts_and_final_state(torch_mod, B, mis
     pipe = MinibatchPipeline(graph, cache, cfg.batch, cfg.fanouts, cfg.row_bytes)
     if miss_path != "zero_copy":
         pipe.tier = B.HostTier(w.features.view(np.uint8).reshape(cfg.num_nodes, cfg.row_bytes), 0, pipe.cap, 0)
-        pipe.tier.set_copy_engine(miss_path == "staged")
+        pipe.tier.set_copy_engine({"staged": 1, "staged_kernel": 0, "staged_assembled": 2}[miss_path])
     seeds_dev = torch_mod.from_numpy(w.seed_batches).cuda()
     steps = cfg.num_batches
 
@@ -603,23 +603,27 @@ def test_pipeline_wide_shape_scaled():
 SKIP_FULL = os.environ.get("BGL_SKIP_FULL_SIZE", "") not in ("", "0")
 
 
-def run_full(cfg, n_batches, check_every, overlapped_steps, torch_mod, B):
+def run_full(cfg, n_batches, check_every, overlapped_steps, torch_mod, B, other_steps=None):
     """One batch after the other with a check of every output, then the overlapped pipeline
     as bench.py runs this configuration, on the same full-size workload."""
+    other_steps = other_steps or max(2, overlapped_steps // 2)
     try:
         w = _inputs().make_workload(cfg, pinned=True)
         run_config(cfg, n_batches, device_n_miss=True, check_every=check_every, w=w)
     except MemoryError as e:  # the box cannot page-lock this much host memory
         pytest.skip(f"not enough page-locked host memory for {cfg.name}: {e}")
-    run_overlapped_against_oracle(torch_mod, B, w, overlapped_steps, staged=True)    # bench.py's default for it
-    run_overlapped_against_oracle(torch_mod, B, w, max(2, overlapped_steps // 2))     # and with --miss-path zero_copy
+    run_overlapped_against_oracle(torch_mod, B, w, overlapped_steps, staged=2)       # bench.py's default for it
+    run_overlapped_against_oracle(torch_mod, B, w, other_steps, staged=True)          # --miss-path staged
+    run_overlapped_against_oracle(torch_mod, B, w, other_steps)                       # and with --miss-path zero_copy
 
 
 @pytest.mark.skipif(SKIP_FULL, reason="BGL_SKIP_FULL_SIZE is set")
 def test_pipeline_wide_config_full_size(torch_mod, B):
     """30 M nodes, ~600 M edges, bf16 x 512 rows, 4,096 seeds, fanout 25/10, 4.5 M-row cache
-    (~33 GB of page-locked host memory, ~20 s)."""
-    run_full(_inputs().CONFIGS["wide"], 4, 2, 5, torch_mod, B)
+    (~33 GB of page-locked host memory).  The overlapped run is long enough (30 batches of about
+    180 K misses) for the cache to fill and wrap around: every batch's outputs and the final state
+    are compared, so evictions and slots on both sides of the buffer's 4 GiB offset are."""
+    run_full(_inputs().CONFIGS["wide"], 4, 2, 30, torch_mod, B, other_steps=3)
 
 
 @pytest.mark.skipif(SKIP_FULL, reason="BGL_SKIP_FULL_SIZE is set")

@@ -43,8 +43,8 @@ def run_tiered_stream(B, torch, feats, cap1, cap2, batches, write_through, threa
     pinned = torch.from_numpy(store).pin_memory() if cache_has_store else None
     gc = B.Cache(cap1, pinned, num_nodes=N, row_bytes=rb)
     tier = B.HostTier(store, cap2, max_n, threads)
-    if copy_engine:     # the packed rows cross the link as plain copies into device memory
-        tier.set_copy_engine(True)
+    if copy_engine:     # the packed rows cross the link as plain copies into device memory (2: assembled output)
+        tier.set_copy_engine(copy_engine)
     # capacity 0: the tier keeps nothing (every miss row just passes through its ring)
     two = oracle.TwoLevel(cap1, cap2, feats)
     oc1, oc2 = two.level1, two.level2
@@ -111,7 +111,7 @@ def zipf_batches(rng, N, count, lo, hi, big=None):
 @pytest.mark.parametrize("dim,dtype", [(4, np.float32), (100, np.float32), (128, np.float32), (264, np.uint16)])
 @pytest.mark.parametrize("write_through,early", [(False, None), (True, None), (True, "own"), (True, "with_insert"),
                                                  (True, "alternate")])
-@pytest.mark.parametrize("copy_engine", [False, True])
+@pytest.mark.parametrize("copy_engine", [False, True, 2])
 def test_tiered_random_streams(B, torch_mod, dim, dtype, write_through, early, copy_engine):
     rng = np.random.default_rng(100 + dim)
     N = 20000
@@ -132,7 +132,7 @@ def test_tiered_lookups_of_many_tiles(B, torch_mod, cap2):
     perm = rng.permutation(N).astype(np.int32)
     batches = [perm[:1_300_000], perm[600_000:2_000_001], perm[:1_200_000]]
     run_tiered_stream(B, torch_mod, feats, 200_000, cap2, batches, True, threads=0, early="with_insert",
-                      copy_engine=(cap2 == 0))
+                      copy_engine=(2 if cap2 == 0 else False))
 
 
 @pytest.mark.parametrize("cap1,cap2,threads", [(64, 300, 1), (1, 1, 3), (500, 100, 2), (3000, 18000, 0),
@@ -146,14 +146,15 @@ def test_tiered_capacity_corners(B, torch_mod, cap1, cap2, threads):
     feats = rng.standard_normal((N, 100)).astype(np.float32)
     batches = zipf_batches(rng, N, 12, 200, 3000)
     _, tier = run_tiered_stream(B, torch_mod, feats, cap1, cap2, batches, True, threads, side=(threads != 2),
-                                early=("with_insert" if threads in (0, 3) else None), copy_engine=(cap1 != 64))
+                                early=("with_insert" if threads in (0, 3) else None),
+                                copy_engine=(False if cap1 == 64 else 2 if cap2 == 0 else True))
     assert tier.stats()["threads"] == (threads or tier.stats()["threads"])
 
 
 @pytest.mark.parametrize("write_through,early", [(False, None), (True, None), (True, "own"), (True, "with_insert"),
                                                  (True, "alternate")])
 @pytest.mark.parametrize("side", [False, True])
-@pytest.mark.parametrize("copy_engine", [False, True])
+@pytest.mark.parametrize("copy_engine", [False, True, 2])
 def test_staging_only_large_batches(B, torch_mod, write_through, side, early, copy_engine):
     """Capacity 0 (every miss row passes through the ring) with batches of several chunks, hits
     that the same batch's insertions evict (small GPU cache), an empty batch, a repeat."""
@@ -165,6 +166,26 @@ def test_staging_only_large_batches(B, torch_mod, write_through, side, early, co
     batches.insert(5, batches[4])     # immediate repeat: hits everywhere the cache kept them
     run_tiered_stream(B, torch_mod, feats, 50000, 0, batches, write_through, 0, side=side, cache_has_store=True,
                       early=early, copy_engine=copy_engine)
+
+
+@pytest.mark.parametrize("dim,cap1", [(100, 6000), (128, 900), (256, 2500), (4, 1), (36, 40000)])
+@pytest.mark.parametrize("early", [None, "with_insert"])
+def test_assembled_output_corner_cases(B, torch_mod, dim, cap1, early):
+    """The one-pass output (copy-engine transport, mode 2) where its two launches split the work
+    differently: no miss at all (nothing lands, the pass only gathers), only misses, hits that
+    all sit in the slots the batch's own misses take (more misses than slots; a repeat of the
+    previous batch in a cache that wraps), none of them there (few misses in a large cache),
+    an empty batch, one id."""
+    rng = np.random.default_rng(dim * 31 + cap1)
+    N = 50000
+    feats = rng.integers(0, 2**32, (N, dim), dtype=np.uint32).view(np.float32)
+    a = rng.permutation(N)[:2000].tolist()
+    b = rng.permutation(N)[:7000].tolist()
+    few_new = a[:1900] + [x for x in rng.permutation(N)[:200].tolist() if x not in set(a)][:50]
+    mixed = list(dict.fromkeys(b[:3000] + a[:500]))
+    batches = [a, a, [], a[:1], few_new, b, b, a, mixed, rng.permutation(N)[:45000].tolist(), a]
+    run_tiered_stream(B, torch_mod, feats, cap1, 0, batches, True, threads=3, cache_has_store=True,
+                      early=early, copy_engine=2)
 
 
 def test_tiered_uniform_ids_many_chunks(B, torch_mod):
@@ -222,7 +243,7 @@ def test_tiered_argument_errors(B, torch_mod):
     assert (h1, h2) == (10, 0)
 
 
-@pytest.mark.parametrize("tier_fraction,copy_engine", [(0.3, True), (0.0, True), (0.0, False)])
+@pytest.mark.parametrize("tier_fraction,copy_engine", [(0.3, True), (0.0, True), (0.0, False), (0.0, 2)])
 def test_tiered_pipeline_as_benchmarked_matches_oracle(torch_mod, B, tier_fraction, copy_engine):
     """The configurations `bench.py` times on the full-size mid workload (sampling ahead,
     tiered lookups on the chain stream, write-through GPU cache): a tier of 30 % of the nodes
@@ -285,7 +306,7 @@ def test_tiered_random_cases_property(B, torch_mod):
     @given(st.integers(50, 5000), st.integers(1, 65), st.integers(1, 3000), st.sampled_from([0, 0, 1, 17, 300, 4000]),
            st.lists(st.integers(0, 2500), min_size=1, max_size=8), st.booleans(), st.booleans(),
            st.sampled_from([None, "own", "with_insert", "alternate"]), st.integers(1, 5), st.integers(0, 2**31),
-           st.booleans())
+           st.sampled_from([0, 1, 2]))
     def run(n_nodes, row_chunks, cap1, cap2, sizes, write_through, side, early, threads, seed, copy_engine):
         rng = np.random.default_rng(seed)
         feats = rng.integers(0, 2**32, (n_nodes, row_chunks * 4), dtype=np.uint32)
