@@ -182,7 +182,14 @@ def frac_in_lines(rb, hits, misses, assembled, write_through):
 def run_config(cfg, args, torch, np, B, inputs, MinibatchPipeline, want_cpu):
     """One configuration: generate its inputs, warm up on a scratch cache, time `steps` minibatches of the
     whole path from an empty cache, then the side measurements.  Returns the result dictionary."""
-    w = inputs.make_workload(cfg, pinned=True)
+    def library_order(row_ptr, col, train, roots, shifts, num_out):
+        # the proximity-aware seed order (Sec. 3.2.2) of such a configuration comes from the library itself
+        g = B.Graph(row_ptr, col)
+        order = B.order_proximity(g, train, roots, shifts, num_out)
+        g.close()
+        return order
+
+    w = inputs.make_workload(cfg, pinned=True, order_fn=library_order if cfg.order == "po" else None)
     feat_t = w.features.ctypes.data      # address of the page-locked feature table
     feat_dev = None
     if args.feature_placement == "device":
@@ -339,8 +346,9 @@ def run_config(cfg, args, torch, np, B, inputs, MinibatchPipeline, want_cpu):
                   "events), every %d-th batch of the timed epoch" % g_every)
         if assembled:
             # One pass writes the whole output: per hit a row read from the cache buffer and written to out_rows,
-            # per miss a landed row read, written to out_rows and (write-through) to the cache buffer.  The short
-            # pass before it (hits whose slots this batch's misses take) is counted with it, bytes and time.
+            # per miss a landed row read, written to out_rows and (write-through) to the cache buffer.  Where the
+            # buffer has no spare row positions a short pass runs before it (hits whose rows this batch's misses
+            # overwrite); it is then counted with it, bytes and time.
             a_ms, a_n = prof["assemble"]
             p_ms, p_n = prof["assemble_pre"]
             per_miss = 3.0 if pipe.write_through else 2.0
@@ -348,13 +356,14 @@ def run_config(cfg, args, torch, np, B, inputs, MinibatchPipeline, want_cpu):
             k_ms = max(a_ms + p_ms, 1e-9)
             achieved = moved / (k_ms * 1e-3) / 1e9
             result["roofline"] = {
-                "kernel": "k_assemble_rows (with k_assemble_pre)", "bound": "hbm", "achieved": achieved,
+                "kernel": "k_assemble_rows" + (" (with k_assemble_pre)" if p_n else ""), "bound": "hbm", "achieved": achieved,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                 "traffic_source": tsrc,
                 "frac_lines": frac_in_lines(rb, g_hit, g_miss, True, pipe.write_through) / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                 "bytes_per_launch": moved / max(a_n, 1), "avg_launch_us": 1e3 * k_ms / max(a_n, 1), "launches": a_n,
                 "avg_us": {"k_assemble_rows": 1e3 * a_ms / max(a_n, 1), "k_assemble_pre": 1e3 * p_ms / max(p_n, 1)},
-                "bytes": "per batch: 2 x row_bytes x hits + %d x row_bytes x misses; a launch = the two passes of one batch" % per_miss,
+                "bytes": "per launch (= per batch): 2 x row_bytes x hits + %d x row_bytes x misses" % per_miss
+                         + ("; the first pass of a batch is counted with its launch" if p_n else ""),
                 "timing": timing,
             }
         else:
@@ -499,10 +508,8 @@ def run_config(cfg, args, torch, np, B, inputs, MinibatchPipeline, want_cpu):
     if cfg.order == "po":
         # Proximity-aware ordering as the library computes it (once per epoch, outside the
         # timed region): 5 BFS sequences over the training set on the GPU, merged on the host.
-        rng = np.random.default_rng(cfg.seed + 6)
-        train = np.unique(w.seed_batches.reshape(-1)).astype(np.int32)
-        roots = rng.integers(0, cfg.num_nodes, cfg.po_sequences)
-        shifts = rng.integers(0, len(train), cfg.po_sequences)
+        # (the epoch's seed batches above are the first batch x num_batches nodes of this order)
+        train, roots, shifts = (w.order_draws[k] for k in ("train", "roots", "shifts"))
         B.order_proximity(graph, train, roots, shifts, len(train))          # warm-up
         o0 = time.perf_counter()
         order = B.order_proximity(graph, train, roots, shifts, len(train))
@@ -518,6 +525,7 @@ def run_config(cfg, args, torch, np, B, inputs, MinibatchPipeline, want_cpu):
             want = oracle.proximity_order(w.row_ptr, w.col, train, roots, shifts, len(train))
             result["ordering"]["oracle_seconds"] = time.perf_counter() - c0
             assert np.array_equal(order, want)
+            assert np.array_equal(order[: w.seed_batches.size], w.seed_batches.reshape(-1))
 
     if want_cpu:
         # The CPU oracle on the batches the GPU leg has just run (a bounded sample: the first ones of them),

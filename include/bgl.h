@@ -257,6 +257,25 @@ int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const int32_t *mis
                           int64_t n_miss, const void *out_rows, void *stream);
 
 /*
+ * Spare row positions in the cache buffer (0 by default).  The FIFO rule of
+ * Sec. 4 overwrites the row of the evicted node with the new one, so a row that
+ * a lookup has found and that the same call's insertions evict must be read
+ * before it is overwritten.  With spare_rows extra positions in the buffer the
+ * new rows of a call go to positions that hold no live row as long as the call
+ * has at most spare_rows misses (insertion number k sits at position
+ * k mod (capacity_rows + spare_rows); its slot stays k mod capacity_rows, and
+ * out_slot, bgl_cache_export_state and the eviction order are unchanged).  The
+ * one-pass output of bgl_host_tier_set_copy_engine mode 2 then needs no first
+ * pass.  Give it the largest number of ids a lookup will be called with.  Costs
+ * spare_rows * row_bytes of device memory.
+ * Only before the first insertion into the cache (the buffer is allocated
+ * anew); synchronises the device.
+ * Errors: BGL_EINVAL (null handle, spare_rows < 0 or capacity_rows + spare_rows
+ * >= 2^31, insertions have happened), BGL_ENOMEM, BGL_EHIP.
+ */
+int bgl_cache_set_spare_rows(bgl_cache_t *c, int64_t spare_rows);
+
+/*
  * Write-through mode (off by default).  When on, the caller promises that every
  * bgl_cache_lookup_gather is followed, before any other call on the cache, by
  * bgl_cache_insert_fifo with the same ids and miss_pos and n_miss = -1 (the

@@ -33,7 +33,7 @@ EXPORTS = [
     "bgl_sample_khop", "bgl_cache_create", "bgl_cache_destroy", "bgl_cache_lookup_gather",
     "bgl_cache_lookup_gather_early", "bgl_cache_lookup_gather_noalloc",
     "bgl_cache_insert_fifo", "bgl_cache_set_write_through", "bgl_cache_wait_rows", "bgl_cache_wait_lists", "bgl_cache_export_state", "bgl_cache_stats",
-    "bgl_cache_map_stats",
+    "bgl_cache_map_stats", "bgl_cache_set_spare_rows",
     "bgl_cache_set_profiling", "bgl_cache_profile", "bgl_cache_set_profiling_every",
     "bgl_host_tier_create", "bgl_host_tier_destroy", "bgl_host_tier_set_copy_engine", "bgl_cache_lookup_gather_tiered",
     "bgl_host_tier_export_state", "bgl_host_tier_stats",
@@ -79,6 +79,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     L.bgl_cache_lookup_gather_early.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
     L.bgl_cache_insert_fifo.argtypes = [vp, vp, vp, i64, vp, vp]
     L.bgl_cache_set_write_through.argtypes = [vp, ci]
+    L.bgl_cache_set_spare_rows.argtypes = [vp, i64]
     L.bgl_cache_wait_rows.argtypes = [vp, vp]
     L.bgl_cache_wait_lists.argtypes = [vp, vp]
     L.bgl_host_tier_create.argtypes = [vp, i64, i32, i64, i64, i32, C.POINTER(vp)]
@@ -324,6 +325,10 @@ class Cache:
         _check(lib().bgl_cache_insert_fifo(self._h, _dev_ptr(ids, torch.int32),
                                            _dev_ptr(miss_pos, torch.int32), n_miss, _dev_ptr(out_rows),
                                            _stream_handle(stream)))
+
+    def set_spare_rows(self, spare_rows: int) -> None:
+        """bgl_cache_set_spare_rows: extra row positions in the buffer (before the first insertion)."""
+        _check(lib().bgl_cache_set_spare_rows(self._h, int(spare_rows)))
 
     def set_write_through(self, enable: bool) -> None:
         _check(lib().bgl_cache_set_write_through(self._h, 1 if enable else 0))

@@ -25,6 +25,7 @@
 // length of a lookup depends on the load only (full buckets are rare at load
 // <= 1/2 of 15 words per bucket), not on the cache's age.
 #include <algorithm>
+#include <cstring>
 #include <mutex>
 #include <vector>
 
@@ -65,7 +66,8 @@ struct bgl_cache {
     const char *features = nullptr;  // device-visible backing store
     bool features_in_hbm = false;    // backing store is device memory (then the fetch is an HBM gather)
     int device = 0;
-    char *buffer = nullptr;          // capacity * row_bytes
+    int64_t rows = 0;                // row positions of the buffer: capacity + spare positions (see RowRing)
+    char *buffer = nullptr;          // rows * row_bytes
     uint64_t *table = nullptr;       // num_buckets * BUCKET words
     uint32_t num_buckets = 0;        // power of two
     int32_t *slot_to_node = nullptr;  // capacity
@@ -213,6 +215,50 @@ __global__ void k_empty_lookup(CacheDev *dev, int64_t *n_hit_host, int gen)
     }
 }
 
+// Where the rows live.  The cache buffer has `rows` >= capacity row positions.  Insertion
+// number k (counted from the cache's creation, k = tail at the time) is written to position
+// k mod rows, while its slot, which is what the map, out_slot and slot_to_node speak of, is
+// k mod capacity.  With rows == capacity the two are the same number.  With spare positions
+// (bgl_cache_set_spare_rows) a batch's new rows go to positions that hold no live row as long
+// as the batch has no more misses than there are spare positions: the rows its own
+// insertions evict stay readable until the next batch, so nothing has to be read "before it
+// is overwritten".  The live rows are the last min(tail, capacity) insertions; slot and
+// position of a live row follow from each other and tail by additions alone.
+struct RowRing {
+    int64_t capacity, rows;
+    int64_t newest_slot, newest_pos;  // of insertion tail - 1 (tail > 0)
+    // this call's insertions: ranks start <= r < start + count stay, rank r goes to position first_pos + (r - start)
+    int64_t start, count, first_pos;
+    __device__ __forceinline__ RowRing(unsigned long long tail, int64_t capacity_, int64_t rows_, int64_t n_miss = 0)
+        : capacity(capacity_), rows(rows_)
+    {
+        const unsigned long long newest = tail > 0 ? tail - 1 : 0;
+        newest_slot = (int64_t)(newest % (unsigned long long)capacity);
+        newest_pos = (int64_t)(newest % (unsigned long long)rows);
+        start = n_miss > capacity ? n_miss - capacity : 0;
+        count = n_miss - start;
+        first_pos = (int64_t)((tail + (unsigned long long)start) % (unsigned long long)rows);
+    }
+    __device__ __forceinline__ int64_t pos_of_slot(int64_t slot) const  // an occupied slot
+    {
+        int64_t age = newest_slot - slot;  // insertions since
+        if (age < 0) age += capacity;
+        const int64_t pos = newest_pos - age;
+        return pos < 0 ? pos + rows : pos;
+    }
+    __device__ __forceinline__ int64_t pos_of_rank(int64_t r) const  // start <= r < start + count
+    {
+        const int64_t pos = first_pos + (r - start);
+        return pos >= rows ? pos - rows : pos;
+    }
+    __device__ __forceinline__ bool overwritten(int64_t pos) const  // by this call's insertions
+    {
+        int64_t d = pos - first_pos;
+        if (d < 0) d += rows;
+        return d < count;
+    }
+};
+
 // Ordered lists of the miss positions and of the hits (position and slot side by
 // side, so the gather needs no dependent lookup).  A hit's rank is its position
 // minus the number of misses before it.  Every workgroup sums the miss counts of
@@ -229,7 +275,8 @@ __global__ __launch_bounds__(KEYS_PER_TILE) void k_split_list(const int32_t *__r
                                                               int64_t *n_hit_host,
                                                               const int32_t *__restrict__ ids,
                                                               int64_t num_nodes, int32_t *miss_ids_host,
-                                                              int32_t *miss_pos_copy, int gen, int32_t *src_of)
+                                                              int32_t *miss_pos_copy, int gen, int32_t *src_of,
+                                                              int64_t capacity, int64_t rows, int par)
 {
     __shared__ int sh_scan[KEYS_PER_TILE / kWave];
     __shared__ int sh_base;
@@ -255,13 +302,19 @@ __global__ __launch_bounds__(KEYS_PER_TILE) void k_split_list(const int32_t *__r
             miss_ids_host[mrank] = id;
             if (id < 0 || (int64_t)id >= num_nodes) n_hit_host[3] = 1;  // the host refuses the batch
         }
-    } else if (i < n && !src_of) {
-        hit_pos[i - mrank] = (int32_t)i;
-        hit_slot[i - mrank] = slot;
+    } else if (i < n) {
+        // the kernels that read the row get its position in the cache buffer (see RowRing)
+        const int32_t pos = (int32_t)RowRing(dev->tail[par], capacity, rows).pos_of_slot(slot);
+        if (!src_of) {
+            hit_pos[i - mrank] = (int32_t)i;
+            hit_slot[i - mrank] = pos;
+        } else {
+            src_of[i] = pos;
+        }
     }
-    // assembled output (k_assemble_rows): the source of every position's row, a slot of the cache
-    // buffer (>= 0) or, as -(r + 1), miss number r, whose row comes in with the packed miss rows
-    if (src_of && i < n) src_of[i] = flag ? -(mrank + 1) : slot;
+    // assembled output (k_assemble_rows): the source of every position's row, a row position of the
+    // cache buffer (>= 0) or, as -(r + 1), miss number r, whose row comes in with the packed miss rows
+    if (src_of && flag) src_of[i] = -(mrank + 1);
     if (blockIdx.x != gridDim.x - 1) return;
     // the last workgroup publishes the call's counters
     int lines = 0, all_lines;
@@ -311,8 +364,8 @@ constexpr int RING_FETCH_BLOCKS = 32;
 constexpr int64_t TIER_CHUNK_ROWS = 49152;
 constexpr int64_t TIER_FIRST_CHUNK_ROWS = 3072;
 
-// out[i] = buffer[out_slot[i]] for every hit i (taken from the hit list, so the
-// work is proportional to the hits).  Consecutive lanes take consecutive
+// out[i] = the cached row of ids[i] for every hit i (taken from the hit list, which holds the
+// rows' positions in the cache buffer, so the work is proportional to the hits).  Consecutive lanes take consecutive
 // 16-byte chunks of a row, so the loads and stores of one row are contiguous;
 // four independent chunks per lane keep loads in flight.  The grid is sized for
 // n rows; workgroups beyond the hit count leave at once.
@@ -365,16 +418,16 @@ template <int Q, bool WT>
 __global__ __launch_bounds__(COPY_THREADS) void k_fetch_miss(
     const int32_t *__restrict__ miss_pos, const int32_t *__restrict__ ids, int q,
     int64_t num_nodes, const uint4 *__restrict__ features, uint4 *__restrict__ out,
-    const CacheDev *dev, uint4 *__restrict__ buffer, int64_t capacity, int par, int gen)
+    const CacheDev *dev, uint4 *__restrict__ buffer, int64_t capacity, int64_t rows, int par, int gen)
 {
     static_assert(COPY_UNROLL == 4, "the four chunks of a lane are written out by hand");
     const int qq = Q > 0 ? Q : q;
     const int64_t n_miss = dev->n_miss_gen[gen];
     const int64_t total = n_miss * qq;
     const int64_t last = total - 1;
-    const int64_t start = n_miss > capacity ? n_miss - capacity : 0;
-    // (start <= r < n_miss covers less than one turn of the buffer: the wrap-around is one subtraction)
-    const int64_t tail_slot = WT ? (int64_t)((dev->tail[par] + (unsigned long long)start) % (unsigned long long)capacity) - start : 0;
+    // (the ranks that stay cover less than one turn of the buffer: the wrap-around is one subtraction)
+    const RowRing ring(WT ? dev->tail[par] : 0ull, capacity, rows, n_miss);
+    const int64_t start = ring.start;
     const int64_t step = (int64_t)gridDim.x * (COPY_THREADS * COPY_UNROLL);
     for (int64_t base = (int64_t)blockIdx.x * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
          base - threadIdx.x < total; base += step) {
@@ -401,11 +454,7 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_miss(
         auto store = [&](bool ok, int64_t r, int32_t m, int c, const uint4 &v) {
             if (!ok) return;
             out[(int64_t)m * qq + c] = v;
-            if (WT && r >= start) {
-                int64_t slot = tail_slot + r;
-                if (slot >= capacity) slot -= capacity;
-                buffer[slot * qq + c] = v;
-            }
+            if (WT && r >= start) buffer[ring.pos_of_rank(r) * qq + c] = v;
         };
         store(ok0, r0, m0, c0, v0);
         store(ok1, r1, m1, c1, v1);
@@ -446,17 +495,17 @@ template <int Q, bool WT, bool NT>
 __global__ __launch_bounds__(COPY_THREADS) void k_fetch_rows(
     const int32_t *__restrict__ rank, int64_t l0, int64_t count, unsigned long long first, int64_t ring,
     const int32_t *__restrict__ miss_pos, int q, const uint4 *__restrict__ rows, uint4 *__restrict__ out,
-    const CacheDev *dev, uint4 *__restrict__ buffer, int64_t capacity, int par, int64_t n_miss)
+    const CacheDev *dev, uint4 *__restrict__ buffer, int64_t capacity, int64_t buffer_rows, int par, int64_t n_miss)
 {
     static_assert(COPY_UNROLL == 4, "the four chunks of a lane are written out by hand");
     const int qq = Q > 0 ? Q : q;
     const int64_t total = count * qq;
     const int64_t last = total - 1;
-    const int64_t start = n_miss > capacity ? n_miss - capacity : 0;
     // the two wrap-arounds without a division per chunk: the launch covers less than one turn of
     // the ring, and the ranks it stores (start <= r < n_miss) less than one turn of the buffer
     const int64_t first_pos = (int64_t)((first + (unsigned long long)l0) % (unsigned long long)ring) - l0;
-    const int64_t tail_slot = WT ? (int64_t)((dev->tail[par] + (unsigned long long)start) % (unsigned long long)capacity) - start : 0;
+    const RowRing dst(WT ? dev->tail[par] : 0ull, capacity, buffer_rows, n_miss);
+    const int64_t start = dst.start;
     const int64_t step = (int64_t)gridDim.x * (COPY_THREADS * COPY_UNROLL);
     for (int64_t base = (int64_t)blockIdx.x * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
          base - threadIdx.x < total; base += step) {
@@ -483,15 +532,15 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_rows(
         st16<NT>(&out[(int64_t)m3 * qq + c3], v3);
         if (WT) {
             if (start == 0) {  // every rank gets a slot (the usual case: fewer misses than slots)
-                st16<NT>(&buffer[wrapped(tail_slot + r0, capacity) * qq + c0], v0);
-                st16<NT>(&buffer[wrapped(tail_slot + r1, capacity) * qq + c1], v1);
-                st16<NT>(&buffer[wrapped(tail_slot + r2, capacity) * qq + c2], v2);
-                st16<NT>(&buffer[wrapped(tail_slot + r3, capacity) * qq + c3], v3);
+                st16<NT>(&buffer[dst.pos_of_rank(r0) * qq + c0], v0);
+                st16<NT>(&buffer[dst.pos_of_rank(r1) * qq + c1], v1);
+                st16<NT>(&buffer[dst.pos_of_rank(r2) * qq + c2], v2);
+                st16<NT>(&buffer[dst.pos_of_rank(r3) * qq + c3], v3);
             } else {
-                if (r0 >= start) st16<NT>(&buffer[wrapped(tail_slot + r0, capacity) * qq + c0], v0);
-                if (r1 >= start) st16<NT>(&buffer[wrapped(tail_slot + r1, capacity) * qq + c1], v1);
-                if (r2 >= start) st16<NT>(&buffer[wrapped(tail_slot + r2, capacity) * qq + c2], v2);
-                if (r3 >= start) st16<NT>(&buffer[wrapped(tail_slot + r3, capacity) * qq + c3], v3);
+                if (r0 >= start) st16<NT>(&buffer[dst.pos_of_rank(r0) * qq + c0], v0);
+                if (r1 >= start) st16<NT>(&buffer[dst.pos_of_rank(r1) * qq + c1], v1);
+                if (r2 >= start) st16<NT>(&buffer[dst.pos_of_rank(r2) * qq + c2], v2);
+                if (r3 >= start) st16<NT>(&buffer[dst.pos_of_rank(r3) * qq + c3], v3);
             }
         }
     }
@@ -504,58 +553,33 @@ __global__ __launch_bounds__(COPY_THREADS) void k_fetch_rows(
 // landed rows, and the miss rows also go to the buffer slots the FIFO rule gives
 // them (write-through).  Every output line is then written whole by one stream of
 // stores, and the hit gather and the scatter of the landed rows are one launch
-// large enough to fill the memory system.  One hazard: a hit whose slot lies in
-// the window of slots that this call's own misses are written to must be read
-// before it is overwritten.  Those rows (few when a batch's misses are few
-// against the capacity, all of the hits when they outnumber it) are copied by
+// large enough to fill the memory system.  One hazard: a hit whose row lies
+// where this call's own misses are written must be read before it is
+// overwritten.  Those rows (few when a batch's misses are few against the
+// capacity, all of the hits when they outnumber it) are copied by
 // k_assemble_pre, which runs first; k_assemble_rows leaves them alone.
-//
-// The window: ranks start <= r < n_miss go to slots (tail + r) mod capacity, less
-// than one turn of the buffer.
-struct FifoWindow {
-    int64_t first;     // slot of rank `start`
-    int64_t count;     // n_miss - start
-    int64_t start;
-    int64_t capacity;
-    __device__ __forceinline__ FifoWindow(unsigned long long tail, int64_t n_miss, int64_t cap) : capacity(cap)
-    {
-        start = n_miss > cap ? n_miss - cap : 0;
-        count = n_miss - start;
-        first = (int64_t)((tail + (unsigned long long)start) % (unsigned long long)cap);
-    }
-    __device__ __forceinline__ bool holds(int32_t slot) const
-    {
-        int64_t d = (int64_t)slot - first;
-        if (d < 0) d += capacity;
-        return d < count;
-    }
-    __device__ __forceinline__ int64_t slot_of_rank(int64_t r) const  // start <= r < n_miss
-    {
-        const int64_t s = first + (r - start);
-        return s >= capacity ? s - capacity : s;
-    }
-};
-
+// With enough spare row positions in the buffer (RowRing) no live row lies where this call
+// writes, and the first pass is not launched at all.
 // The hits inside the window, copied before the window is written.  Each wavefront scans 64
 // positions (one per lane), packs the ones concerned into LDS with a ballot and copies their rows
 // with all its lanes, four 16-byte chunks in flight per lane.
 template <int Q>
 __global__ __launch_bounds__(COPY_THREADS) void k_assemble_pre(
     const int32_t *__restrict__ src_of, int64_t n, int q, const uint4 *__restrict__ buffer,
-    uint4 *__restrict__ out, const CacheDev *dev, int64_t capacity, int par, int64_t n_miss)
+    uint4 *__restrict__ out, const CacheDev *dev, int64_t capacity, int64_t rows, int par, int64_t n_miss)
 {
     constexpr int WAVES = COPY_THREADS / kWave;
     __shared__ int32_t sh_pos[WAVES][kWave];
     __shared__ int32_t sh_slot[WAVES][kWave];
     const int qq = Q > 0 ? Q : q;
-    const FifoWindow win(dev->tail[par], n_miss, capacity);
+    const RowRing ring(dev->tail[par], capacity, rows, n_miss);
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int64_t step = (int64_t)gridDim.x * COPY_THREADS;
     for (int64_t base = (int64_t)blockIdx.x * COPY_THREADS + wave * kWave; base < n; base += step) {
         const int64_t i = base + lane;
         const int32_t s = i < n ? src_of[i] : -1;
-        const bool mine = s >= 0 && win.holds(s);
+        const bool mine = s >= 0 && ring.overwritten(s);
         const uint64_t mask = __ballot(mine);
         if (mask == 0) continue;  // (uniform in the wavefront)
         const int m = __popcll(mask);
@@ -600,13 +624,14 @@ __global__ __launch_bounds__(COPY_THREADS) void k_assemble_pre(
 template <int Q>
 __global__ __launch_bounds__(COPY_THREADS) void k_assemble_rows(
     const int32_t *__restrict__ src_of, int64_t n, int q, const uint4 *__restrict__ landed,
-    uint4 *buffer, uint4 *__restrict__ out, const CacheDev *dev, int64_t capacity, int par, int64_t n_miss)
+    uint4 *buffer, uint4 *__restrict__ out, const CacheDev *dev, int64_t capacity, int64_t rows, int par,
+    int64_t n_miss)
 {
     static_assert(COPY_UNROLL == 4, "the four chunks of a lane are written out by hand");
     const int qq = Q > 0 ? Q : q;
     const int64_t total = n * qq;
     const int64_t last = total - 1;
-    const FifoWindow win(dev->tail[par], n_miss, capacity);
+    const RowRing ring(dev->tail[par], capacity, rows, n_miss);
     const int64_t step = (int64_t)gridDim.x * (COPY_THREADS * COPY_UNROLL);
     for (int64_t base = (int64_t)blockIdx.x * (COPY_THREADS * COPY_UNROLL) + threadIdx.x;
          base - threadIdx.x < total; base += step) {
@@ -631,11 +656,11 @@ __global__ __launch_bounds__(COPY_THREADS) void k_assemble_rows(
                           "+v"(v2.x), "+v"(v2.y), "+v"(v2.z), "+v"(v2.w), "+v"(v3.x), "+v"(v3.y), "+v"(v3.z), "+v"(v3.w));
         auto store = [&](int32_t s, int c, int64_t x, const uint4 &v) {
             if (s >= 0) {
-                if (!win.holds(s)) st16<true>(&out[x], v);
+                if (!ring.overwritten(s)) st16<true>(&out[x], v);
             } else {
                 st16<true>(&out[x], v);
                 const int64_t r = -(int64_t)s - 1;
-                if (r >= win.start) st16<true>(&buffer[win.slot_of_rank(r) * qq + c], v);
+                if (r >= ring.start) st16<true>(&buffer[ring.pos_of_rank(r) * qq + c], v);
             }
         };
         store(s0, c0, x0, v0);
@@ -731,7 +756,7 @@ __device__ __forceinline__ void insert_map_part(
 template <int Q>
 __device__ __forceinline__ void insert_rows_part(
     int64_t block, const int32_t *__restrict__ miss_pos, int64_t n_miss, int64_t start,
-    unsigned long long tail, int64_t capacity, int q, const uint4 *__restrict__ out,
+    unsigned long long tail, int64_t capacity, int64_t rows, int q, const uint4 *__restrict__ out,
     uint4 *__restrict__ buffer)
 {
     static_assert(COPY_UNROLL == 4, "the four chunks of a lane are written out by hand");
@@ -743,7 +768,7 @@ __device__ __forceinline__ void insert_rows_part(
     // numbers beyond the end are clamped to the last chunk, which is then copied again.
     const int64_t last = total - 1;
     // (start <= r < n_miss covers at most one turn of the buffer: the wrap-around is one subtraction)
-    const int64_t tail_slot = (int64_t)((tail + (unsigned long long)start) % (unsigned long long)capacity);
+    const RowRing ring(tail, capacity, rows, n_miss);
     int64_t r0, r1, r2, r3;
     int c0, c1, c2, c3;
     RowSplit<Q>::split(min(base, last), q, r0, c0);
@@ -756,11 +781,10 @@ __device__ __forceinline__ void insert_rows_part(
     const uint4 v1 = out[(int64_t)m1 * qq + c1];
     const uint4 v2 = out[(int64_t)m2 * qq + c2];
     const uint4 v3 = out[(int64_t)m3 * qq + c3];
-    auto wrapped = [capacity](int64_t slot) { return slot >= capacity ? slot - capacity : slot; };
-    buffer[wrapped(tail_slot + r0) * qq + c0] = v0;
-    buffer[wrapped(tail_slot + r1) * qq + c1] = v1;
-    buffer[wrapped(tail_slot + r2) * qq + c2] = v2;
-    buffer[wrapped(tail_slot + r3) * qq + c3] = v3;
+    buffer[ring.pos_of_rank(start + r0) * qq + c0] = v0;
+    buffer[ring.pos_of_rank(start + r1) * qq + c1] = v1;
+    buffer[ring.pos_of_rank(start + r2) * qq + c2] = v2;
+    buffer[ring.pos_of_rank(start + r3) * qq + c3] = v3;
 }
 
 // The FIFO update is two launches because only the row copy needs the fetched
@@ -783,14 +807,14 @@ __global__ __launch_bounds__(COPY_THREADS) void k_insert_map(
 
 template <int Q>
 __global__ __launch_bounds__(COPY_THREADS) void k_insert_rows(
-    const int32_t *__restrict__ miss_pos, int64_t n_miss_arg, int64_t capacity, int q,
+    const int32_t *__restrict__ miss_pos, int64_t n_miss_arg, int64_t capacity, int64_t rows, int q,
     const uint4 *__restrict__ out, uint4 *__restrict__ buffer, CacheDev *dev, int par)
 {
     const int64_t n_miss = n_miss_arg >= 0 ? n_miss_arg : dev->n_miss_last;
     const int64_t start = n_miss > capacity ? n_miss - capacity : 0;
     const unsigned long long tail = dev->tail[par];
     if (blockIdx.x == 0 && threadIdx.x == 0) dev->tail[par ^ 1] = tail + (unsigned long long)n_miss;
-    insert_rows_part<Q>(blockIdx.x, miss_pos, n_miss, start, tail, capacity, q, out, buffer);
+    insert_rows_part<Q>(blockIdx.x, miss_pos, n_miss, start, tail, capacity, rows, q, out, buffer);
 }
 
 // FIFO update when the launches above are skipped (nothing can be inserted).
@@ -939,6 +963,7 @@ try {
     bgl_cache *c = new (std::nothrow) bgl_cache();
     if (!c) BGL_FAIL(BGL_ENOMEM, "out of host memory");
     c->capacity = capacity_rows;
+    c->rows = capacity_rows;
     c->row_bytes = row_bytes;
     c->num_nodes = num_nodes;
     c->features = feat_dev;
@@ -956,7 +981,7 @@ try {
         bgl::set_error("hipMalloc of %zu bytes failed: %s", (size_t)(bytes), hipGetErrorString(e)); \
         return fail(e == hipErrorOutOfMemory ? BGL_ENOMEM : BGL_EHIP);                     \
     }
-    TRY_ALLOC(c->buffer, (size_t)capacity_rows * row_bytes);
+    TRY_ALLOC(c->buffer, (size_t)c->rows * row_bytes);
     TRY_ALLOC(c->table, (size_t)nbk * BUCKET * sizeof(uint64_t));
     TRY_ALLOC(c->slot_to_node, (size_t)capacity_rows * sizeof(int32_t));
     TRY_ALLOC(c->slot_to_entry, (size_t)capacity_rows * sizeof(uint32_t));
@@ -973,7 +998,7 @@ try {
                        EMPTY64, BUCKET);
     hipLaunchKernelGGL(k_fill_i32, dim3(1024), dim3(256), 0, 0, c->slot_to_node, capacity_rows, -1);
     if (hipMemset(c->dev, 0, sizeof(CacheDev)) != hipSuccess ||
-        hipMemset(c->buffer, 0, (size_t)capacity_rows * row_bytes) != hipSuccess ||
+        hipMemset(c->buffer, 0, (size_t)c->rows * row_bytes) != hipSuccess ||
         hipDeviceSynchronize() != hipSuccess) {
         bgl::set_error("cache initialisation failed: %s", hipGetErrorString(hipGetLastError()));
         return fail(BGL_EHIP);
@@ -1118,7 +1143,8 @@ int lookup_phase(bgl_cache *c, const int32_t *ids, int64_t n, void *out_rows, in
             hipLaunchKernelGGL(k_split_list, dim3((unsigned)tiles), dim3(KEYS_PER_TILE), 0, ls, out_slot,
                                n, mbs, tile_prefix, mbs + 2 * mbs_cap, miss_pos, hit_pos, hit_pos + hit_cap, c->dev,
                                n_hit_dev, ids, c->num_nodes,
-                               tier ? bgl::tier_ids_device_if_passthrough(tier) : nullptr, mpos_copy, gen, src_of);
+                               tier ? bgl::tier_ids_device_if_passthrough(tier) : nullptr, mpos_copy, gen, src_of,
+                               c->capacity, c->rows, (int)(c->insert_calls & 1));
         }
     } else {
         hipLaunchKernelGGL(k_empty_lookup, dim3(1), dim3(64), 0, ls, c->dev, n_hit_dev, gen);
@@ -1228,7 +1254,7 @@ int lookup_gather_impl(bgl_cache_t *c, const int32_t *ids, int64_t n, void *out_
                                           : k_fetch_miss<decltype(Q)::value, false>;
                 launch(c, ss, k, dim3(blocks), dim3(COPY_THREADS), mpos, ids, q, c->num_nodes,
                        reinterpret_cast<const uint4 *>(c->features), reinterpret_cast<uint4 *>(out_rows), c->dev,
-                       reinterpret_cast<uint4 *>(c->buffer), c->capacity, par, gen);
+                       reinterpret_cast<uint4 *>(c->buffer), c->capacity, c->rows, par, gen);
             });
         }
         BGL_HIP(hipEventRecord(c->ev_miss, ss));
@@ -1358,7 +1384,7 @@ struct TieredRows {
                             : (c->write_through ? k_fetch_rows<QQ, true, false> : k_fetch_rows<QQ, false, false>);
             launch(c, ss, k, dim3(blocks), dim3(COPY_THREADS), rank, l0, count, first, ring, mpos, q,
                    reinterpret_cast<const uint4 *>(base), reinterpret_cast<uint4 *>(out_rows), c->dev,
-                   reinterpret_cast<uint4 *>(c->buffer), c->capacity, par, n - plan->n_hit_gpu);
+                   reinterpret_cast<uint4 *>(c->buffer), c->capacity, c->rows, par, n - plan->n_hit_gpu);
         });
     }
     // Assembled output, first launch: the hits whose slots this call's misses are about to take.
@@ -1370,7 +1396,7 @@ struct TieredRows {
         dispatch_q(q, [&](auto Q) {
             launch(c, ss, k_assemble_pre<decltype(Q)::value>, dim3(blocks), dim3(COPY_THREADS), src_of, n, q,
                    reinterpret_cast<const uint4 *>(c->buffer), reinterpret_cast<uint4 *>(out_rows), c->dev,
-                   c->capacity, par, n - plan->n_hit_gpu);
+                   c->capacity, c->rows, par, n - plan->n_hit_gpu);
         });
     }
     // Second launch, once the packed miss rows are in `land`: every other row of the output, and
@@ -1383,7 +1409,7 @@ struct TieredRows {
         dispatch_q(q, [&](auto Q) {
             launch(c, ss, k_assemble_rows<decltype(Q)::value>, dim3(blocks), dim3(COPY_THREADS), src_of, n, q,
                    reinterpret_cast<const uint4 *>(land), reinterpret_cast<uint4 *>(c->buffer),
-                   reinterpret_cast<uint4 *>(out_rows), c->dev, c->capacity, par, n - plan->n_hit_gpu);
+                   reinterpret_cast<uint4 *>(out_rows), c->dev, c->capacity, c->rows, par, n - plan->n_hit_gpu);
         });
     }
 };
@@ -1455,7 +1481,10 @@ int rows_by_copy_engine(const TieredRows &r, char *land)
     }
     bgl::tier_copy_wait(t);
     if (r.src_of) {  // (the tier keeps nothing: plan.n_hit == 0, the landed rows are in miss order)
-        r.launch_assemble_pre();  // needs no landed row: it runs while the copies are still on their way
+        // The first pass is needed only if this call's rows may land on live ones: not when the buffer
+        // has a spare position for every miss of the call (the misses that do not stay advance the
+        // position too).  (It needs no landed row: it runs while the copies are still on their way.)
+        if (r.n - plan.n_hit_gpu > c->rows - c->capacity) r.launch_assemble_pre();
         BGL_HIP(hipStreamWaitEvent(r.ss, bgl::tier_copy_event(t), 0));
         r.launch_assemble_rows(land);
         return BGL_OK;
@@ -1643,7 +1672,7 @@ try {
             Prof p(c, BGL_STAGE_INSERT_ROWS, st);
             dispatch_q(q, [&](auto Q) {
                 launch(c, st, k_insert_rows<decltype(Q)::value>, dim3(copy_blocks(eff, q)), dim3(COPY_THREADS),
-                       miss_pos, n_miss, c->capacity, q, reinterpret_cast<const uint4 *>(out_rows),
+                       miss_pos, n_miss, c->capacity, c->rows, q, reinterpret_cast<const uint4 *>(out_rows),
                        reinterpret_cast<uint4 *>(c->buffer), c->dev, par);
             });
         }
@@ -1656,6 +1685,33 @@ try {
     BGL_HIP(hipEventRecord(c->ev_map, st));
     c->map_pending = true;
     c->map_stream = st;
+    return BGL_OK;
+} BGL_NOTHROW_END
+
+extern "C" int bgl_cache_set_spare_rows(bgl_cache_t *c, int64_t spare_rows)
+try {
+    if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
+    if (spare_rows < 0 || c->capacity + spare_rows > INT32_MAX)
+        BGL_FAIL(BGL_EINVAL, "spare_rows must be >= 0 and capacity + spare_rows < 2^31 (got %lld)", (long long)spare_rows);
+    if (c->insert_calls != 0 || c->awaiting_insert)
+        BGL_FAIL(BGL_EINVAL, "the spare rows can only be set before the first insertion");
+    BGL_HIP(hipDeviceSynchronize());
+    const int64_t rows = c->capacity + spare_rows;
+    if (rows == c->rows) return BGL_OK;
+    char *buf = nullptr;
+    const hipError_t e = hipMalloc((void **)&buf, (size_t)rows * c->row_bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        bgl::set_error("hipMalloc of %zu bytes failed: %s", (size_t)rows * c->row_bytes, hipGetErrorString(e));
+        return e == hipErrorOutOfMemory ? BGL_ENOMEM : BGL_EHIP;
+    }
+    if (hipMemset(buf, 0, (size_t)rows * c->row_bytes) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+        (void)hipFree(buf);
+        BGL_FAIL(BGL_EHIP, "clearing the cache buffer failed: %s", hipGetErrorString(hipGetLastError()));
+    }
+    (void)hipFree(c->buffer);
+    c->buffer = buf;
+    c->rows = rows;
     return BGL_OK;
 } BGL_NOTHROW_END
 
@@ -1697,8 +1753,24 @@ try {
         BGL_HIP(hipMemcpy(&h, c->dev, sizeof(h), hipMemcpyDeviceToHost));
         *tail = h.tail[c->insert_calls & 1];
     }
-    if (buffer)
-        BGL_HIP(hipMemcpy(buffer, c->buffer, (size_t)c->capacity * c->row_bytes, hipMemcpyDeviceToHost));
+    if (buffer) {
+        // rows by slot: the live rows are the last min(tail, capacity) insertions, insertion k sits at
+        // position k mod rows and belongs to slot k mod capacity; runs of consecutive insertions are
+        // copied whole (they break where either number wraps), empty slots read as zeros
+        CacheDev h;
+        BGL_HIP(hipMemcpy(&h, c->dev, sizeof(h), hipMemcpyDeviceToHost));
+        const uint64_t t = h.tail[c->insert_calls & 1];
+        const uint64_t cap = (uint64_t)c->capacity, rows = (uint64_t)c->rows, rb = (uint64_t)c->row_bytes;
+        const uint64_t live = std::min<uint64_t>(t, cap);
+        char *dst = static_cast<char *>(buffer);
+        if (live < cap) std::memset(dst + live * rb, 0, (size_t)((cap - live) * rb));  // (then t < capacity: slots 0 .. t-1 are live)
+        for (uint64_t k = t - live; k < t;) {
+            const uint64_t slot = k % cap, pos = k % rows;
+            const uint64_t run = std::min<uint64_t>(std::min<uint64_t>(cap - slot, rows - pos), t - k);
+            BGL_HIP(hipMemcpy(dst + slot * rb, c->buffer + pos * rb, (size_t)(run * rb), hipMemcpyDeviceToHost));
+            k += run;
+        }
+    }
     return BGL_OK;
 } BGL_NOTHROW_END
 

@@ -1,6 +1,6 @@
 /*
  * Seeded synthetic inputs for the minibatch-preparation path: power-law CSR
- * graphs, feature tables and breadth-first visit orders.  These are inputs
+ * graphs and feature tables.  These are inputs
  * only: nothing here belongs to the sampling or caching method, and this file
  * has its own random-number generator (a counter hash built on the MurmurHash3
  * 64-bit finaliser) so that it shares no arithmetic with either the HIP library
@@ -122,30 +122,59 @@ static inline int64_t zipf_rank(double u, int64_t n, double beta)
     return k;
 }
 
-/* Edge destinations.  Nodes live, in a hidden "generation order", in contiguous
- * communities of comm_size; with probability p_local an edge goes to a
- * Zipf-ranked member of the source's community, otherwise to a Zipf-ranked node
- * of the whole graph (power-law in-degree, hubs, and neighborhood locality).
- * perm maps generation order -> node id, inv is its inverse, so that node ids
- * carry no locality.  Rows are not sorted; repeated edges and self loops stay. */
+/* Edge destinations.  Nodes live, in a hidden "generation order", on a ring of
+ * num_nodes positions.  With probability p_local an edge is a short-range one: it
+ * goes to the position at a signed distance from the source drawn from an
+ * exponential law of mean `reach` (of two such draws the one that lands on the
+ * more "popular" position is kept, popularity being a fixed hash of the
+ * position: a mild local skew of the in-degree).  Otherwise it goes to one of
+ * num_hubs hub positions scattered over the ring, chosen by a Zipf law over
+ * their ranks (heavy-tailed in-degree).  The
+ * short-range edges give the graph a geometry: a breadth-first traversal grows
+ * region by region over many levels instead of reaching everything in two or
+ * three, so that nodes that follow each other in a breadth-first order have
+ * neighborhoods that overlap, which is the property of real graphs that
+ * proximity-aware ordering (Sec. 3.2.2 of the paper) relies on; a graph whose
+ * edges all go to ranks of a large block, or a pure configuration model, is an
+ * expander and shows none of it.  perm maps generation order -> node id, inv is
+ * its inverse, so that node ids carry no locality.  Rows are not sorted;
+ * repeated edges and self loops stay. */
 int bglgen_edges(int64_t num_nodes, const void *row_ptr, int bits, int32_t *col,
-                 uint64_t seed, int64_t comm_size, double p_local, double beta,
+                 uint64_t seed, int64_t reach, double p_local, double beta, int64_t num_hubs,
                  const int32_t *perm, const int32_t *inv)
 {
-    if (num_nodes <= 0 || comm_size <= 0) return -1;
+    if (num_nodes <= 0 || reach <= 0 || num_hubs <= 0) return -1;
+    if (num_hubs > num_nodes) num_hubs = num_nodes;
 #pragma omp parallel for schedule(dynamic, 4096)
     for (int64_t v = 0; v < num_nodes; ++v) {
         int64_t lo = bits == 64 ? ((const int64_t *)row_ptr)[v] : ((const int32_t *)row_ptr)[v];
         int64_t hi = bits == 64 ? ((const int64_t *)row_ptr)[v + 1] : ((const int32_t *)row_ptr)[v + 1];
         int64_t g = inv[v];
-        int64_t base = (g / comm_size) * comm_size;
-        int64_t csize = num_nodes - base < comm_size ? num_nodes - base : comm_size;
         for (int64_t e = lo; e < hi; ++e) {
             uint64_t c = (uint64_t)(e - lo);
-            double u0 = gen_unit(gen_word(seed, (uint64_t)v, 2 * c + 1));
-            double u1 = gen_unit(gen_word(seed, (uint64_t)v, 2 * c + 2));
-            int64_t dst_g = u0 < p_local ? base + zipf_rank(u1, csize, beta)
-                                         : zipf_rank(u1, num_nodes, beta);
+            uint64_t w0 = gen_word(seed, (uint64_t)v, 3 * c + 1);
+            double u1 = gen_unit(gen_word(seed, (uint64_t)v, 3 * c + 2));
+            int64_t dst_g;
+            if (gen_unit(w0) < p_local) {
+                double u2 = gen_unit(gen_word(seed, (uint64_t)v, 3 * c + 3));
+                int64_t best = g;
+                uint64_t best_pop = 0;
+                for (int k = 0; k < 2; ++k) {
+                    double u = k == 0 ? u1 : u2;
+                    int64_t d = 1 + (int64_t)(-(double)reach * log(u));
+                    if (d >= num_nodes) d = num_nodes - 1;
+                    int64_t cand = ((w0 >> k) & 1) ? g + d : g - d;
+                    cand %= num_nodes;
+                    if (cand < 0) cand += num_nodes;
+                    uint64_t pop = fmix64((uint64_t)cand * 0x9FB21C651E98DF25ULL + seed);
+                    if (k == 0 || pop > best_pop) { best = cand; best_pop = pop; }
+                }
+                dst_g = best;
+            } else {
+                /* one of num_hubs hub positions, Zipf-ranked; the hubs are scattered over the ring */
+                dst_g = (int64_t)(fmix64((uint64_t)zipf_rank(u1, num_hubs, beta) + 0x632BE59BD9B4E019ULL * (seed | 1)) %
+                                  (uint64_t)num_nodes);
+            }
             col[e] = perm[dst_g];
         }
     }
@@ -178,40 +207,4 @@ int bglgen_features(int64_t num_rows, int32_t dim, int32_t elem_bytes, uint64_t 
         }
     }
     return 0;
-}
-
-/* Breadth-first visit order over the CSR starting at `root`; when a component
- * is exhausted the traversal restarts at the next unvisited node id (cyclically
- * after root).  Only nodes with is_train[v] != 0 are recorded, in visit order.
- * Returns the number recorded (= number of training nodes), or -1 on failure. */
-int64_t bglgen_bfs_order(int64_t num_nodes, const void *row_ptr, int bits, const int32_t *col,
-                         const uint8_t *is_train, int64_t root, int32_t *out_seq)
-{
-    if (num_nodes <= 0 || root < 0 || root >= num_nodes) return -1;
-    uint8_t *seen = (uint8_t *)calloc((size_t)num_nodes, 1);
-    int32_t *queue = (int32_t *)malloc(sizeof(int32_t) * (size_t)num_nodes);
-    if (!seen || !queue) { free(seen); free(queue); return -1; }
-    int64_t head = 0, tailq = 0, n_out = 0, scan = 0;
-    int64_t start = root;
-    for (;;) {
-        seen[start] = 1;
-        queue[tailq++] = (int32_t)start;
-        while (head < tailq) {
-            int32_t v = queue[head++];
-            if (is_train[v]) out_seq[n_out++] = v;
-            int64_t lo = bits == 64 ? ((const int64_t *)row_ptr)[v] : ((const int32_t *)row_ptr)[v];
-            int64_t hi = bits == 64 ? ((const int64_t *)row_ptr)[v + 1] : ((const int32_t *)row_ptr)[v + 1];
-            for (int64_t e = lo; e < hi; ++e) {
-                int32_t u = col[e];
-                if (!seen[u]) { seen[u] = 1; queue[tailq++] = u; }
-            }
-        }
-        if (tailq == num_nodes) break;
-        while (scan < num_nodes && seen[(root + scan) % num_nodes]) ++scan;
-        if (scan >= num_nodes) break;
-        start = (root + scan) % num_nodes;
-    }
-    free(seen);
-    free(queue);
-    return n_out;
 }

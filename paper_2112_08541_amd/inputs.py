@@ -14,7 +14,7 @@ import ctypes as C
 import dataclasses
 import os
 import subprocess
-from typing import Optional
+from typing import Callable, Optional
 
 import numpy as np
 
@@ -47,11 +47,9 @@ def _gen() -> C.CDLL:
         L.bglgen_permutation.restype = None
         L.bglgen_permutation.argtypes = [i64, u64, vp, vp]
         L.bglgen_edges.restype = C.c_int
-        L.bglgen_edges.argtypes = [i64, vp, C.c_int, vp, u64, i64, dbl, dbl, vp, vp]
+        L.bglgen_edges.argtypes = [i64, vp, C.c_int, vp, u64, i64, dbl, dbl, i64, vp, vp]
         L.bglgen_features.restype = C.c_int
         L.bglgen_features.argtypes = [i64, i32, i32, u64, vp]
-        L.bglgen_bfs_order.restype = i64
-        L.bglgen_bfs_order.argtypes = [i64, vp, C.c_int, vp, vp, i64, vp]
         _lib = L
     return _lib
 
@@ -74,9 +72,10 @@ class Config:
     row_ptr_bits: int = 32
     graph_placement: str = "device"   # "device" | "host_pinned"
     seed: int = 20211208
-    comm_size: int = 4096
-    p_local: float = 0.75
-    beta: float = 0.75
+    reach: int = 2000          # mean distance of a short-range edge on the generator's hidden ring
+    p_local: float = 0.97      # share of short-range edges; the others go to hubs
+    beta: float = 0.75         # Zipf exponent over the hub ranks
+    num_hubs: int = 0          # 0: one hub per 16,384 nodes, at least 16
     po_sequences: int = 5
     dmin: int = 1
 
@@ -93,9 +92,9 @@ CONFIGS = {
     "tiny": Config("tiny", 10_000, 10.0, 1_000, 100, "f32", 512, (10, 5), 2_000, 20,
                    "random_all", 0, seed=20211208, dmin=2),
     "mid": Config("mid", 2_450_000, 50.2, 20_000, 100, "f32", 1024, (15, 10, 5), 490_000, 200,
-                  "random_train", 204_800, seed=20211209, dmin=8),
+                  "random_train", 204_800, seed=20211209, dmin=5),
     "bfs": Config("bfs", 2_450_000, 50.2, 20_000, 100, "f32", 1024, (15, 10, 5), 245_000, 200,
-                  "po", 204_800, seed=20211209, dmin=8),
+                  "po", 204_800, seed=20211209, dmin=5),
     "large": Config("large", 111_000_000, 14.4, 50_000, 128, "f32", 1024, (15, 10, 5), 25_000_000, 200,
                     "random_train", 1_200_000, row_ptr_bits=64, graph_placement="host_pinned",
                     seed=20211211, dmin=3),
@@ -170,6 +169,7 @@ class Workload:
     seed_batches: np.ndarray     # int32 [num_batches, batch]
     rng_seeds: np.ndarray        # uint64 [num_batches], one per sampling call
     keepalive: list = dataclasses.field(default_factory=list)
+    order_draws: Optional[dict] = None   # proximity-aware order: training set, roots, shifts it was computed from
 
     @property
     def num_edges(self) -> int:
@@ -199,7 +199,8 @@ def make_graph(cfg: Config, pinned: bool = False):
     inv = np.empty(N, dtype=np.int32)
     g.bglgen_permutation(N, cfg.seed + 1, perm.ctypes.data, inv.ctypes.data)
     rc = g.bglgen_edges(N, rp.ctypes.data, cfg.row_ptr_bits, col.ctypes.data, cfg.seed + 2,
-                        cfg.comm_size, cfg.p_local, cfg.beta, perm.ctypes.data, inv.ctypes.data)
+                        cfg.reach, cfg.p_local, cfg.beta, cfg.num_hubs or max(16, N // 16384),
+                        perm.ctypes.data, inv.ctypes.data)
     if rc != 0:
         raise ValueError("edge generation failed")
     return rp, col[:E], keep
@@ -214,72 +215,41 @@ def make_features(cfg: Config, pinned: bool = False):
     return feats, [t]
 
 
-def bfs_order(row_ptr: np.ndarray, col: np.ndarray, is_train: np.ndarray, root: int) -> np.ndarray:
-    N = len(row_ptr) - 1
-    bits = 64 if row_ptr.dtype == np.int64 else 32
-    is_train = np.ascontiguousarray(is_train, dtype=np.uint8)
-    out = np.empty(int(is_train.sum()), dtype=np.int32)
-    n = _gen().bglgen_bfs_order(N, row_ptr.ctypes.data, bits, col.ctypes.data,
-                                is_train.ctypes.data, int(root), out.ctypes.data)
-    if n != len(out):
-        raise RuntimeError("BFS order did not visit every training node")
-    return out
-
-
-def proximity_order(row_ptr, col, train_nodes: np.ndarray, n_sequences: int,
-                    batch: int, num_batches: int, rng: np.random.Generator) -> np.ndarray:
-    """Seed order of the paper's Sec. 3.2.2: several breadth-first sequences over
-    the training nodes from random roots, each rotated by a random offset; batches
-    take nodes from the sequences in turn, skipping nodes already used."""
-    N = len(row_ptr) - 1
-    is_train = np.zeros(N, dtype=np.uint8)
-    is_train[train_nodes] = 1
-    seqs = []
-    for _ in range(n_sequences):
-        root = int(rng.integers(0, N))
-        s = bfs_order(row_ptr, col, is_train, root)
-        seqs.append(np.roll(s, int(rng.integers(0, len(s)))))
-    used = np.zeros(N, dtype=bool)
-    cursors = [0] * n_sequences
-    order = np.empty(batch * num_batches, dtype=np.int32)
-    k, turn = 0, 0
-    total = len(train_nodes)
-    while k < len(order):
-        if k >= total:
-            raise ValueError("not enough training nodes for the requested batches")
-        s = seqs[turn % n_sequences]
-        c = cursors[turn % n_sequences]
-        while used[s[c]]:
-            c += 1
-        order[k] = s[c]
-        used[s[c]] = True
-        cursors[turn % n_sequences] = c + 1
-        k += 1
-        turn += 1
-    return order.reshape(num_batches, batch)
-
-
-def make_seed_batches(cfg: Config, row_ptr=None, col=None) -> np.ndarray:
+def make_seed_batches(cfg: Config, order_fn: Optional[Callable] = None):
+    """Seed batches [num_batches, batch] and, for the proximity-aware order, the random draws that
+    order was given.  The proximity-aware order of the paper's Sec. 3.2.2 is part of the method, not
+    of the inputs: this module only draws the training set, the BFS roots and the shifts, and
+    `order_fn(train_nodes, roots, shifts, num_out) -> order` (the library's bgl_order_proximity, or
+    the oracle's) turns them into the order."""
     rng = np.random.default_rng(cfg.seed + 4)
     N, B, nb = cfg.num_nodes, cfg.batch, cfg.num_batches
     if cfg.order == "random_all":
-        return np.stack([rng.choice(N, size=B, replace=False) for _ in range(nb)]).astype(np.int32)
+        return np.stack([rng.choice(N, size=B, replace=False) for _ in range(nb)]).astype(np.int32), None
     train = rng.choice(N, size=cfg.train_size, replace=False).astype(np.int32)
+    if B * nb > len(train):
+        raise ValueError("training set smaller than one epoch of batches")
     if cfg.order == "random_train":
-        if B * nb > len(train):
-            raise ValueError("training set smaller than one epoch of batches")
-        return rng.permutation(train)[: B * nb].reshape(nb, B).astype(np.int32)
+        return rng.permutation(train)[: B * nb].reshape(nb, B).astype(np.int32), None
     if cfg.order == "po":
-        return proximity_order(row_ptr, col, train, cfg.po_sequences, B, nb, rng)
+        draws = dict(train=train, roots=rng.integers(0, N, cfg.po_sequences).astype(np.int64),
+                     shifts=rng.integers(0, len(train), cfg.po_sequences).astype(np.int64), num_out=B * nb)
+        if order_fn is None:
+            raise ValueError("the proximity-aware order needs order_fn (the library's or the oracle's ordering call)")
+        order = np.asarray(order_fn(draws["train"], draws["roots"], draws["shifts"], draws["num_out"]), dtype=np.int32)
+        return order.reshape(nb, B), draws
     raise ValueError(cfg.order)
 
 
-def make_workload(cfg: Config, pinned: bool = False) -> Workload:
+def make_workload(cfg: Config, pinned: bool = False, order_fn: Optional[Callable] = None) -> Workload:
     """Generate everything one configuration needs.  `pinned` places the feature
-    table (and, for host-resident graphs, the CSR) in page-locked memory."""
+    table (and, for host-resident graphs, the CSR) in page-locked memory.
+    order_fn(row_ptr, col, train_nodes, roots, shifts, num_out) -> order: needed for a configuration
+    with proximity-aware seed order (see make_seed_batches); the draws it got are kept in
+    `Workload.order_draws`."""
     rp, col, keep = make_graph(cfg, pinned and cfg.graph_placement == "host_pinned")
     feats, keep2 = make_features(cfg, pinned)
-    seeds = make_seed_batches(cfg, rp, col)
+    fn = (lambda train, roots, shifts, num_out: order_fn(rp, col, train, roots, shifts, num_out)) if order_fn else None
+    seeds, draws = make_seed_batches(cfg, fn)
     rng = np.random.default_rng(cfg.seed + 5)
     rng_seeds = rng.integers(0, 2**64, size=cfg.num_batches, dtype=np.uint64)
-    return Workload(cfg, rp, col, feats, seeds, rng_seeds, keep + keep2)
+    return Workload(cfg, rp, col, feats, seeds, rng_seeds, keep + keep2, draws)

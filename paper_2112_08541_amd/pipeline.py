@@ -40,7 +40,7 @@ from . import binding as B
 
 class MinibatchPipeline:
     def __init__(self, graph: B.Graph, cache: B.Cache, batch: int, fanouts, row_bytes: int,
-                 write_through: bool = True, tier: Optional[B.HostTier] = None):
+                 write_through: bool = True, tier: Optional[B.HostTier] = None, spare_rows: bool = True):
         self.graph = graph
         self.fanouts = tuple(int(f) for f in fanouts)
         self.K = len(self.fanouts)
@@ -52,6 +52,10 @@ class MinibatchPipeline:
         self.chain = torch.cuda.Stream()          # lookups, hit gathers, miss fetches
         self.work = torch.cuda.current_stream()   # map updates, early lookups, (sampling)
         self.write_through = write_through
+        # One spare row position in the cache buffer per id of the largest batch: a batch's new rows then
+        # never land on a row the same batch still has to read, and the one-pass output of the staged miss
+        # path (copy-engine transport, mode 2) is one launch.  Costs cap * row_bytes of device memory.
+        self.spare_rows = spare_rows
         # an early lookup adds two hand-overs between streams: it pays for batches of many thousand ids
         self.early_ok = self.cap >= 65536
         # With early lookups and host threads that pack the miss rows, sampling gets a stream of its
@@ -64,7 +68,10 @@ class MinibatchPipeline:
         self.set_cache(cache)
 
     def set_cache(self, cache: B.Cache) -> None:
+        """`cache` must be new (no insertion yet) when the pipeline gives it spare row positions."""
         self.cache = cache
+        if self.spare_rows:
+            cache.set_spare_rows(self.cap)
         cache.set_write_through(self.write_through)
 
     def run(self, seeds_dev: torch.Tensor, rng_seeds, steps: int,

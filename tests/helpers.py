@@ -4,6 +4,26 @@ oracle, and compare everything bit for bit."""
 import numpy as np
 
 
+def proximity_order_checked(row_ptr, col, train_nodes, roots, shifts, num_out):
+    """order_fn for inputs.make_workload: the proximity-aware seed order from the library's
+    bgl_order_proximity (GPU), accepted only if it equals the oracle's."""
+    import oracle
+    from paper_2112_08541_amd import binding as B
+    graph = B.Graph(row_ptr, col)
+    got = B.order_proximity(graph, train_nodes, roots, shifts, num_out)
+    graph.close()
+    want = oracle.proximity_order(row_ptr, col, train_nodes, roots, shifts, num_out)
+    assert np.array_equal(got, want), "bgl_order_proximity differs from the oracle's order"
+    return got
+
+
+def make_workload(cfg, pinned=True):
+    """inputs.make_workload with the seed order of a proximity-ordered configuration computed by
+    the library and checked against the oracle."""
+    from paper_2112_08541_amd import inputs
+    return inputs.make_workload(cfg, pinned=pinned, order_fn=proximity_order_checked if cfg.order == "po" else None)
+
+
 class GpuPipeline:
     """sample_khop -> lookup_gather -> insert_fifo on the GPU for one workload."""
 

@@ -161,11 +161,36 @@ def test_proximity_order_uses_each_training_node_once():
     from paper_2112_08541_amd import inputs
     import dataclasses
     cfg = dataclasses.replace(inputs.scaled(inputs.CONFIGS["bfs"], 50_000, num_batches=10), batch=64)
+    import oracle
     rp, col, _ = inputs.make_graph(cfg)
-    seeds = inputs.make_seed_batches(cfg, rp, col)
+    with pytest.raises(ValueError):
+        inputs.make_seed_batches(cfg)                       # the order is the method's, not the generator's
+    seeds, draws = inputs.make_seed_batches(
+        cfg, lambda train, roots, shifts, num_out: oracle.proximity_order(rp, col, train, roots, shifts, num_out))
     assert seeds.shape == (10, 64)
     flat = seeds.reshape(-1)
     assert len(np.unique(flat)) == len(flat)
+    assert set(flat.tolist()) <= set(draws["train"].tolist()) and len(draws["roots"]) == cfg.po_sequences
+
+
+def test_generated_graph_has_the_locality_breadth_first_orders_need():
+    """Short-range edges on the generator's hidden ring: a breadth-first traversal from one node needs
+    many levels to reach the graph (an expander would need three or four), and ids carry no locality."""
+    import dataclasses
+    import scipy.sparse as sp
+    import scipy.sparse.csgraph as csg
+    from paper_2112_08541_amd import inputs
+    cfg = dataclasses.replace(inputs.scaled(inputs.CONFIGS["mid"], 400_000, num_batches=4), num_hubs=2)
+    rp, col, _ = inputs.make_graph(cfg)
+    N = cfg.num_nodes
+    g = sp.csr_matrix((np.ones(len(col), dtype=np.int8), col, rp), shape=(N, N))
+    dist = csg.shortest_path(g, method="D", unweighted=True, indices=[12345])[0]
+    reached = np.isfinite(dist)
+    assert reached.mean() > 0.95
+    assert np.percentile(dist[reached], 50) >= 6
+    # neighbors are not close in id: the ring positions are hidden behind a permutation
+    v = np.repeat(np.arange(N), np.diff(rp))[:200000]
+    assert np.median(np.abs(col[:200000].astype(np.int64) - v)) > N / 20
 
 
 def test_bench_refuses_more_than_one_gpu():

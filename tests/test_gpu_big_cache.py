@@ -22,11 +22,11 @@ TRANSPORT = {"write_through_landed": 1, "write_through_packed_over_link": 0, "wr
 
 
 @pytest.mark.skipif(SKIP_FULL, reason="BGL_SKIP_FULL_SIZE is set")
-@pytest.mark.parametrize("row_bytes,cap,num_nodes,fresh,hits,turns", [
-    (1024, 4_500_000, 6_000_000, 800_000, 200_000, 4.2),
-    (512, 9_500_000, 12_000_000, 1_000_000, 250_000, 3.2),
+@pytest.mark.parametrize("row_bytes,cap,num_nodes,fresh,hits,turns,spare", [
+    (1024, 4_500_000, 6_000_000, 800_000, 200_000, 4.2, 0),
+    (512, 9_500_000, 12_000_000, 1_000_000, 250_000, 3.2, 1_250_000),   # spare row positions: slot != position
 ])
-def test_cache_buffer_beyond_4gib_wraps_and_evicts(row_bytes, cap, num_nodes, fresh, hits, turns):
+def test_cache_buffer_beyond_4gib_wraps_and_evicts(row_bytes, cap, num_nodes, fresh, hits, turns, spare):
     import torch
     import oracle
     from paper_2112_08541_amd import binding as B, inputs
@@ -41,6 +41,7 @@ def test_cache_buffer_beyond_4gib_wraps_and_evicts(row_bytes, cap, num_nodes, fr
     fb = feats.view(np.uint8).reshape(num_nodes, row_bytes)
     rng = np.random.default_rng(cap)
     gc = B.Cache(cap, feats.ctypes.data, num_nodes=num_nodes, row_bytes=row_bytes)
+    gc.set_spare_rows(spare)
     oc = oracle.Cache(cap, feats)
     n_max = fresh + hits
     tier = B.HostTier(fb, 0, n_max, 0)                               # keeps nothing: the staging ring

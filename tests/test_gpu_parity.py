@@ -7,7 +7,7 @@ import os
 import numpy as np
 import pytest
 
-from helpers import GpuPipeline, OraclePipeline, assert_batch_equal, assert_state_equal
+from helpers import GpuPipeline, OraclePipeline, assert_batch_equal, assert_state_equal, make_workload
 
 pytestmark = pytest.mark.gpu
 
@@ -170,7 +170,7 @@ def test_sample_reports_out_of_range_seed(B, torch_mod):
 
 # --------------------------------------------------------------------- cache
 def run_cache_stream(B, torch, feats, cap, batches, device_n_miss=False, side=True, write_through=False,
-                     early=None):
+                     early=None, spare=0):
     """Feed id batches through GPU cache and oracle cache; compare after every call.
     early: "own" / "with_insert" / "alternate" = map lookup and lists on a stream of their own,
     on the one that also carries the FIFO updates, or only in every other call."""
@@ -178,6 +178,8 @@ def run_cache_stream(B, torch, feats, cap, batches, device_n_miss=False, side=Tr
     N, rb = feats.shape[0], feats.shape[1] * feats.itemsize
     feat_t = torch.from_numpy(feats.view(np.uint8).reshape(N, rb)).pin_memory()
     gc = B.Cache(cap, feat_t, num_nodes=N, row_bytes=rb)
+    if spare:      # extra row positions in the buffer: slots, lookups and exported state must not change
+        gc.set_spare_rows(spare)
     oc = oracle.Cache(cap, feats)
     if write_through:
         gc.set_write_through(True)
@@ -237,8 +239,8 @@ def test_cache_hand_worked_example(B, torch_mod, golden_dir):
 
 @pytest.mark.parametrize("dim,dtype", [(4, np.float32), (100, np.float32), (128, np.float32),
                                        (512, np.uint16), (12, np.float32), (264, np.uint16)])
-@pytest.mark.parametrize("device_n_miss", [False, True])
-def test_cache_random_streams(B, torch_mod, dim, dtype, device_n_miss):
+@pytest.mark.parametrize("device_n_miss,spare", [(False, 0), (True, 0), (True, 777), (False, 6000)])
+def test_cache_random_streams(B, torch_mod, dim, dtype, device_n_miss, spare):
     rng = np.random.default_rng(dim)
     N, cap = 20000, 3000
     if dtype == np.float32:
@@ -252,12 +254,12 @@ def test_cache_random_streams(B, torch_mod, dim, dtype, device_n_miss):
         batches.append(list(dict.fromkeys(hot.tolist())))
     batches.insert(3, [])          # empty lookup
     batches.insert(8, batches[7])  # immediate repeat: all hits unless evicted
-    run_cache_stream(B, torch_mod, feats, cap, batches, device_n_miss=device_n_miss)
+    run_cache_stream(B, torch_mod, feats, cap, batches, device_n_miss=device_n_miss, spare=spare)
 
 
 @pytest.mark.parametrize("dim,dtype", [(4, np.float32), (100, np.float32), (512, np.uint16), (264, np.uint16)])
-@pytest.mark.parametrize("side", [True, False])
-def test_cache_write_through_mode(B, torch_mod, dim, dtype, side):
+@pytest.mark.parametrize("side,spare", [(True, 0), (False, 0), (True, 1), (False, 2900), (True, 10000)])
+def test_cache_write_through_mode(B, torch_mod, dim, dtype, side, spare):
     """The miss fetch fills the cache buffer itself; same results as the default mode,
     including a batch with more misses than slots, an empty batch and tiny capacities."""
     rng = np.random.default_rng(dim + 1)
@@ -270,8 +272,8 @@ def test_cache_write_through_mode(B, torch_mod, dim, dtype, side):
         batches.append(list(dict.fromkeys((rng.zipf(1.2, size) % N).tolist())))
     batches.insert(3, [])
     batches.insert(8, batches[7])
-    run_cache_stream(B, torch_mod, feats, 3000, batches, side=side, write_through=True)
-    run_cache_stream(B, torch_mod, feats, 1, batches[:6], side=side, write_through=True)
+    run_cache_stream(B, torch_mod, feats, 3000, batches, side=side, write_through=True, spare=spare)
+    run_cache_stream(B, torch_mod, feats, 1, batches[:6], side=side, write_through=True, spare=spare)
 
 
 @pytest.mark.parametrize("early", ["own", "with_insert", "alternate"])
@@ -375,6 +377,7 @@ def test_cache_long_churn_keeps_map_exact(B, torch_mod):
 
 @pytest.mark.parametrize("write_through", [False, True])
 def test_cache_map_lookups_stay_short_under_fifo_churn(B, torch_mod, write_through):
+    spare = 12345 if write_through else 0        # (with spare row positions in the buffer as well)
     """More than 300 times the capacity flows through a cache whose map is at its highest load
     (15,360 x 2 slots over 4,096 buckets of 15 words: load 1/2).  The cache engine of the paper
     serves a whole training job, so the cost of a lookup must not grow with the number of
@@ -387,6 +390,7 @@ def test_cache_map_lookups_stay_short_under_fifo_churn(B, torch_mod, write_throu
     feats = rng.integers(0, 2**31, (N, 4), dtype=np.int32).view(np.float32)      # 16-byte rows, compared as bytes
     feat_t = torch.from_numpy(feats.view(np.uint8).reshape(N, 16)).pin_memory()
     gc = B.Cache(cap, feat_t, num_nodes=N, row_bytes=16)
+    gc.set_spare_rows(spare)
     gc.set_write_through(write_through)
     oc = oracle.Cache(cap, feats)
     out = torch.empty((per_batch, 16), dtype=torch.uint8, device="cuda")
@@ -454,9 +458,8 @@ def test_cache_flags_out_of_range_id(B, torch_mod):
 
 # ------------------------------------------------------------ whole pipeline
 def run_config(cfg, n_batches, device_n_miss=False, check_every=1, write_through=False, w=None):
-    inputs = _inputs()
     if w is None:
-        w = inputs.make_workload(cfg, pinned=True)
+        w = make_workload(cfg)
     gp = GpuPipeline(w, device_n_miss=device_n_miss, write_through=write_through)
     op = OraclePipeline(w)
     hits = total = 0
@@ -576,12 +579,16 @@ def test_overlapped_pipeline_full_epoch_counts_and_final_state(torch_mod, B, mis
 
 
 def test_pipeline_bfs_order_config_full_size_and_locality():
+    """The `bfs` configuration at full size: its seed order comes from the library's
+    bgl_order_proximity (checked against the oracle's order when the workload is made), every
+    compared batch equals the oracle's, and with the cache at 10 % of the nodes the proximity-aware
+    order beats random order over the same training set by a clear margin (paper Sec. 3.2.2: the
+    order is there to raise the FIFO hit ratio).  Cumulative hit ratios from an empty cache."""
     inputs = _inputs()
-    po = run_config(inputs.CONFIGS["bfs"], 10, check_every=5)
+    po = run_config(inputs.CONFIGS["bfs"], 12, check_every=4)
     rnd = run_config(dataclasses.replace(inputs.CONFIGS["bfs"], order="random_train", name="bfs-random"),
-                     10, check_every=5)
-    # proximity-aware order must beat random order at equal cache size (paper Sec. 3.2.2)
-    assert po > rnd
+                     12, check_every=4)
+    assert po > 2.0 * rnd and po > rnd + 0.2, (po, rnd)
 
 
 def test_pipeline_large_shape_scaled():

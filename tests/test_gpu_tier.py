@@ -34,7 +34,7 @@ def assert_tier_state_equal(tier, oc2, what):
 
 
 def run_tiered_stream(B, torch, feats, cap1, cap2, batches, write_through, threads, side=True,
-                      cache_has_store=False, early=None, copy_engine=False):
+                      cache_has_store=False, early=None, copy_engine=False, spare=0):
     import oracle
     N, rb = feats.shape[0], feats.shape[1] * feats.itemsize
     store = np.ascontiguousarray(feats.view(np.uint8).reshape(N, rb))      # ordinary host memory
@@ -42,6 +42,8 @@ def run_tiered_stream(B, torch, feats, cap1, cap2, batches, write_through, threa
     # as in bench.py's staged miss path: the cache keeps its own page-locked table
     pinned = torch.from_numpy(store).pin_memory() if cache_has_store else None
     gc = B.Cache(cap1, pinned, num_nodes=N, row_bytes=rb)
+    if spare:           # extra row positions in the cache buffer (with enough of them the one-pass output has no first pass)
+        gc.set_spare_rows(spare)
     tier = B.HostTier(store, cap2, max_n, threads)
     if copy_engine:     # the packed rows cross the link as plain copies into device memory (2: assembled output)
         tier.set_copy_engine(copy_engine)
@@ -165,12 +167,12 @@ def test_staging_only_large_batches(B, torch_mod, write_through, side, early, co
     batches.insert(2, [])
     batches.insert(5, batches[4])     # immediate repeat: hits everywhere the cache kept them
     run_tiered_stream(B, torch_mod, feats, 50000, 0, batches, write_through, 0, side=side, cache_has_store=True,
-                      early=early, copy_engine=copy_engine)
+                      early=early, copy_engine=copy_engine, spare=(90000 if side else 0))
 
 
 @pytest.mark.parametrize("dim,cap1", [(100, 6000), (128, 900), (256, 2500), (4, 1), (36, 40000)])
-@pytest.mark.parametrize("early", [None, "with_insert"])
-def test_assembled_output_corner_cases(B, torch_mod, dim, cap1, early):
+@pytest.mark.parametrize("early,spare", [(None, 0), ("with_insert", 0), (None, 45000), ("with_insert", 2500), ("own", 1)])
+def test_assembled_output_corner_cases(B, torch_mod, dim, cap1, early, spare):
     """The one-pass output (copy-engine transport, mode 2) where its two launches split the work
     differently: no miss at all (nothing lands, the pass only gathers), only misses, hits that
     all sit in the slots the batch's own misses take (more misses than slots; a repeat of the
@@ -185,7 +187,7 @@ def test_assembled_output_corner_cases(B, torch_mod, dim, cap1, early):
     mixed = list(dict.fromkeys(b[:3000] + a[:500]))
     batches = [a, a, [], a[:1], few_new, b, b, a, mixed, rng.permutation(N)[:45000].tolist(), a]
     run_tiered_stream(B, torch_mod, feats, cap1, 0, batches, True, threads=3, cache_has_store=True,
-                      early=early, copy_engine=2)
+                      early=early, copy_engine=2, spare=spare)
 
 
 def test_tiered_uniform_ids_many_chunks(B, torch_mod):
@@ -256,7 +258,7 @@ def test_tiered_pipeline_as_benchmarked_matches_oracle(torch_mod, B, tier_fracti
     torch = torch_mod
     cfg = inputs.CONFIGS["mid"]
     staging_only = tier_fraction == 0.0
-    w = inputs.make_workload(cfg, pinned=staging_only)
+    w = inputs.make_workload(cfg, pinned=staging_only)      # (mid: random seed order)
     rb = cfg.row_bytes
     store = np.ascontiguousarray(w.features.view(np.uint8).reshape(cfg.num_nodes, rb))
     graph = B.Graph(w.row_ptr, w.col)
@@ -306,14 +308,14 @@ def test_tiered_random_cases_property(B, torch_mod):
     @given(st.integers(50, 5000), st.integers(1, 65), st.integers(1, 3000), st.sampled_from([0, 0, 1, 17, 300, 4000]),
            st.lists(st.integers(0, 2500), min_size=1, max_size=8), st.booleans(), st.booleans(),
            st.sampled_from([None, "own", "with_insert", "alternate"]), st.integers(1, 5), st.integers(0, 2**31),
-           st.sampled_from([0, 1, 2]))
-    def run(n_nodes, row_chunks, cap1, cap2, sizes, write_through, side, early, threads, seed, copy_engine):
+           st.sampled_from([0, 1, 2]), st.sampled_from([0, 0, 3, 700, 2600]))
+    def run(n_nodes, row_chunks, cap1, cap2, sizes, write_through, side, early, threads, seed, copy_engine, spare):
         rng = np.random.default_rng(seed)
         feats = rng.integers(0, 2**32, (n_nodes, row_chunks * 4), dtype=np.uint32)
         batches = [rng.permutation(n_nodes)[: min(k, n_nodes)].tolist() for k in sizes]
         if early is not None and not write_through:
             early = None                      # the library refuses early lookups there (tested elsewhere)
         run_tiered_stream(B, torch_mod, feats, cap1, cap2, batches, write_through, threads, side=side,
-                          cache_has_store=(cap2 == 0), early=early, copy_engine=copy_engine)
+                          cache_has_store=(cap2 == 0), early=early, copy_engine=copy_engine, spare=spare)
 
     run()
