@@ -226,12 +226,10 @@ struct OrderWork {
     size_t sort_tmp_bytes = 0;
     OrderDev *dev = nullptr;
     OrderDev *host = nullptr;  // page-locked mirror
+    char *block = nullptr;     // the one device allocation all of the above are carved from
     ~OrderWork()
     {
-        (void)hipFree(visited); (void)hipFree(next); (void)hipFree(train); (void)hipFree(frontier);
-        (void)hipFree(cand); (void)hipFree(seq); (void)hipFree(train_ids); (void)hipFree(bs);
-        (void)hipFree(seq_base); (void)hipFree(key); (void)hipFree(keys_in); (void)hipFree(keys_out);
-        (void)hipFree(sort_tmp); (void)hipFree(dev);
+        (void)hipFree(block);
         if (host) (void)hipHostFree(host);
     }
 };
@@ -247,23 +245,33 @@ int prepare(const bgl_graph *g, const int32_t *train_nodes, int64_t num_train, O
 {
     const int64_t N = g->num_nodes, words = ceil_div(N, 32);
     const int64_t nb = std::max(ceil_div(words, BT), ceil_div(N, BT));
-    BGL_HIP(hipMalloc((void **)&w.visited, words * 4));
-    BGL_HIP(hipMalloc((void **)&w.next, words * 4));
-    BGL_HIP(hipMalloc((void **)&w.train, words * 4));
-    BGL_HIP(hipMalloc((void **)&w.frontier, N * 4));
-    BGL_HIP(hipMalloc((void **)&w.cand, N * 4));
-    BGL_HIP(hipMalloc((void **)&w.key, N * 8));
-    BGL_HIP(hipMalloc((void **)&w.keys_in, N * 8));
-    BGL_HIP(hipMalloc((void **)&w.keys_out, N * 8));
-    BGL_HIP(hipMalloc((void **)&w.seq, std::max<int64_t>(num_train, 1) * 4));
-    BGL_HIP(hipMalloc((void **)&w.train_ids, std::max<int64_t>(num_train, 1) * 4));
-    BGL_HIP(hipMalloc((void **)&w.bs, (nb + 1) * 4));
-    BGL_HIP(hipMalloc((void **)&w.seq_base, 4));
-    BGL_HIP(hipMalloc((void **)&w.dev, sizeof(OrderDev)));
-    BGL_HIP(hipHostMalloc((void **)&w.host, sizeof(OrderDev), hipHostMallocDefault));
+    // one device allocation for the whole call, sized up front and carved into 256-byte aligned parts
     BGL_HIP(rocprim::radix_sort_pairs(nullptr, w.sort_tmp_bytes, w.keys_in, w.keys_out, w.cand, w.frontier,
                                       (size_t)N, 0, 64, st));
-    BGL_HIP(hipMalloc(&w.sort_tmp, std::max<size_t>(w.sort_tmp_bytes, 16)));
+    const size_t nt = (size_t)std::max<int64_t>(num_train, 1);
+    const size_t sizes[] = {(size_t)words * 4, (size_t)words * 4, (size_t)words * 4, (size_t)N * 4, (size_t)N * 4,
+                            (size_t)N * 8, (size_t)N * 8, (size_t)N * 8, nt * 4, nt * 4, (size_t)(nb + 1) * 4, 4,
+                            sizeof(OrderDev), std::max<size_t>(w.sort_tmp_bytes, 16)};
+    size_t total = 0;
+    for (size_t sz : sizes) total += round_up(sz, 256);
+    BGL_HIP(hipMalloc((void **)&w.block, total));
+    char *at = w.block;
+    auto take = [&](size_t k) { char *p = at; at += round_up(sizes[k], 256); return p; };
+    w.visited = reinterpret_cast<uint32_t *>(take(0));
+    w.next = reinterpret_cast<uint32_t *>(take(1));
+    w.train = reinterpret_cast<uint32_t *>(take(2));
+    w.frontier = reinterpret_cast<int32_t *>(take(3));
+    w.cand = reinterpret_cast<int32_t *>(take(4));
+    w.key = reinterpret_cast<uint64_t *>(take(5));
+    w.keys_in = reinterpret_cast<uint64_t *>(take(6));
+    w.keys_out = reinterpret_cast<uint64_t *>(take(7));
+    w.seq = reinterpret_cast<int32_t *>(take(8));
+    w.train_ids = reinterpret_cast<int32_t *>(take(9));
+    w.bs = reinterpret_cast<int32_t *>(take(10));
+    w.seq_base = reinterpret_cast<int32_t *>(take(11));
+    w.dev = reinterpret_cast<OrderDev *>(take(12));
+    w.sort_tmp = take(13);
+    BGL_HIP(hipHostMalloc((void **)&w.host, sizeof(OrderDev), hipHostMallocDefault));
     BGL_HIP(hipMemsetAsync(w.dev, 0, sizeof(OrderDev), st));
     BGL_HIP(hipMemcpyAsync(w.train_ids, train_nodes, num_train * 4, hipMemcpyHostToDevice, st));
     hipLaunchKernelGGL(k_fill_u32, dim3(std::min<int64_t>(ceil_div(words, BT), 4096)), dim3(BT), 0, st, w.train, words, 0u);
