@@ -44,16 +44,13 @@ __host__ __device__ __forceinline__ uint64_t mix64(uint64_t z)
     return z;
 }
 
-__global__ void k_fill_u64(uint64_t *p, int64_t n, uint64_t v)
+// Start of a call: empty table, counts at zero.
+__global__ void k_prepare(uint64_t *p, int64_t n, uint64_t v, int32_t *cnt)
 {
+    if (blockIdx.x == 0 && threadIdx.x < BGL_COUNTS_LEN) cnt[threadIdx.x] = 0;
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (; i < n; i += stride) p[i] = v;
-}
-
-__global__ void k_zero_counts(int32_t *cnt)
-{
-    if (threadIdx.x < BGL_COUNTS_LEN) cnt[threadIdx.x] = 0;
 }
 
 // Enter (key, val) in the global table, keeping the smallest val per key.
@@ -439,10 +436,9 @@ try {
         out->cap_edges[h] = h < num_hops ? L.ube[h] : 0;
     }
 
-    hipLaunchKernelGGL(k_zero_counts, dim3(1), dim3(64), 0, st, cnt);
     {
         int blocks = (int)std::min<int64_t>(bgl::ceil_div(L.table_entries, 1024), 4096);
-        hipLaunchKernelGGL(k_fill_u64, dim3(blocks), dim3(256), 0, st, tab, L.table_entries, EMPTY64);
+        hipLaunchKernelGGL(k_prepare, dim3(blocks), dim3(256), 0, st, tab, L.table_entries, EMPTY64, cnt);
     }
     // stage 0: unique seeds
     {
