@@ -300,7 +300,9 @@ int bgl_cache_wait_rows(bgl_cache_t *c, void *stream);
 /*
  * Make `stream` wait (on the device) until the lists (out_slot, miss_pos, hit
  * count) and the hit rows of the most recent bgl_cache_lookup_gather are
- * complete.  A no-op for that call's main_stream.  bgl_cache_insert_fifo does
+ * complete (the lists only after a tiered lookup whose output is written in one
+ * pass, bgl_host_tier_set_copy_engine mode 2: its hit rows come with its miss
+ * rows, bgl_cache_wait_rows).  A no-op for that call's main_stream.  bgl_cache_insert_fifo does
  * this itself when it is given another stream than the lookup's main_stream, and
  * the next lookup then waits for that update; so the lookups of one cache may run
  * on one stream (with side_stream = main_stream the whole chain lookup, lists,

@@ -56,7 +56,7 @@ def _gen() -> C.CDLL:
 
 @dataclasses.dataclass(frozen=True)
 class Config:
-    """One benchmark/parity configuration (the five of the project's baseline file)."""
+    """One benchmark/parity configuration (tiny, mid, bfs, large, wide)."""
     name: str
     num_nodes: int
     mean_degree: float
