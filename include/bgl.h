@@ -486,6 +486,31 @@ int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t, const int
                                    void *lookup_stream, int early_lookup);
 
 /*
+ * bgl_cache_lookup_gather_tiered in two halves, for a caller that has other work
+ * to enqueue while the host threads pack the batch's rows (Sec. 3.3: the stages
+ * of minibatch preparation overlap; here the calling thread's own launches, e.g.
+ * the sampling of a later batch, overlap the packing).
+ *   bgl_cache_lookup_tiered_begin: same arguments and errors as
+ *     bgl_cache_lookup_gather_tiered.  Enqueues the lookups, blocks until their
+ *     lists have reached the host, starts the host threads and returns; n_hit
+ *     (host, two words, may be null) holds the two hit counts on return.
+ *   bgl_cache_lookup_tiered_finish: sends the packed rows on their way as they
+ *     get ready and enqueues the kernels that take them to their places; blocks
+ *     until the last row is packed.  BGL_EINVAL without a begun call.
+ * Between the two the caller may enqueue this batch's bgl_cache_insert_fifo (in
+ * write-through mode only: the update then touches the map alone) and work that
+ * does not involve this cache or tier; any other lookup, and a change of the
+ * cache's modes, fails with BGL_EINVAL.  The arrays handed to begin stay the
+ * caller's to keep alive and unchanged until the work finish enqueues is done.
+ * begin followed at once by finish is bgl_cache_lookup_gather_tiered.
+ */
+int bgl_cache_lookup_tiered_begin(bgl_cache_t *c, bgl_host_tier_t *t, const int32_t *ids, int64_t n,
+                                  void *out_rows, int32_t *out_slot, int32_t *miss_pos,
+                                  int64_t *n_hit, void *main_stream, void *side_stream,
+                                  void *lookup_stream, int early_lookup);
+int bgl_cache_lookup_tiered_finish(bgl_cache_t *c);
+
+/*
  * Tier state for tests: slot_to_node (capacity_rows ints, -1 = empty), the
  * running tail, the tier's rows by slot (capacity_rows * row_bytes bytes, zeros
  * for empty slots).  Any pointer may be null.  Host memory; waits for the device.

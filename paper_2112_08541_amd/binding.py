@@ -36,6 +36,7 @@ EXPORTS = [
     "bgl_cache_map_stats", "bgl_cache_set_spare_rows",
     "bgl_cache_set_profiling", "bgl_cache_profile", "bgl_cache_set_profiling_every",
     "bgl_host_tier_create", "bgl_host_tier_destroy", "bgl_host_tier_set_copy_engine", "bgl_cache_lookup_gather_tiered",
+    "bgl_cache_lookup_tiered_begin", "bgl_cache_lookup_tiered_finish",
     "bgl_host_tier_export_state", "bgl_host_tier_stats",
     "bgl_order_bfs_sequence", "bgl_order_proximity", "bgl_order_choose_sequences",
     "bgl_order_shuffling_error",
@@ -86,6 +87,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     L.bgl_host_tier_destroy.argtypes = [vp]
     L.bgl_host_tier_set_copy_engine.argtypes = [vp, ci]
     L.bgl_cache_lookup_gather_tiered.argtypes = [vp, vp, vp, i64, vp, vp, vp, C.POINTER(i64), vp, vp, vp, ci]
+    L.bgl_cache_lookup_tiered_begin.argtypes = L.bgl_cache_lookup_gather_tiered.argtypes
+    L.bgl_cache_lookup_tiered_finish.argtypes = [vp]
     L.bgl_host_tier_export_state.argtypes = [vp, vp, C.POINTER(C.c_uint64), vp]
     L.bgl_host_tier_stats.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), C.POINTER(C.c_double), C.POINTER(u64), C.POINTER(i32)]
     L.bgl_cache_export_state.argtypes = [vp, vp, C.POINTER(u64), vp]
@@ -306,19 +309,24 @@ class Cache:
 
     def lookup_gather_tiered(self, tier: "HostTier", ids: torch.Tensor, n: int, out_rows: torch.Tensor,
                              out_slot: torch.Tensor, miss_pos: torch.Tensor, main_stream=None,
-                             side_stream=None, lookup_stream=None):
+                             side_stream=None, lookup_stream=None, begin_only: bool = False):
         """Returns (hits in this cache, hits in the tier).  lookup_stream: run the map lookup and
-        the lists there (early lookup; tier of capacity 0 and write-through mode only)."""
+        the lists there (early lookup; write-through mode only).  begin_only: the first half alone
+        (bgl_cache_lookup_tiered_begin); lookup_tiered_finish() is the second."""
         if n > 0 and (ids.numel() < n or out_slot.numel() < n or miss_pos.numel() < n or
                       out_rows.numel() * out_rows.element_size() < n * self.row_bytes):
             raise ValueError("an argument is smaller than n")
         n_hit = (C.c_int64 * 2)(0, 0)
-        _check(lib().bgl_cache_lookup_gather_tiered(
+        call = lib().bgl_cache_lookup_tiered_begin if begin_only else lib().bgl_cache_lookup_gather_tiered
+        _check(call(
             self._h, tier._h, _dev_ptr(ids, torch.int32), n, _dev_ptr(out_rows),
             _dev_ptr(out_slot, torch.int32), _dev_ptr(miss_pos, torch.int32), n_hit,
             _stream_handle(main_stream), None if side_stream is None else int(side_stream.cuda_stream),
             None if lookup_stream is None else _stream_handle(lookup_stream), 0 if lookup_stream is None else 1))
         return int(n_hit[0]), int(n_hit[1])
+
+    def lookup_tiered_finish(self) -> None:
+        _check(lib().bgl_cache_lookup_tiered_finish(self._h))
 
     def insert_fifo(self, ids: torch.Tensor, miss_pos: torch.Tensor, n_miss: int,
                     out_rows: torch.Tensor, stream=None) -> None:

@@ -101,6 +101,19 @@ struct bgl_cache {
     bool write_through = false;      // the miss fetch also fills the cache buffer (see bgl_cache_set_write_through)
     bool awaiting_insert = false;    // write-through: a lookup's misses are in the buffer but not in the map yet
     const void *wt_ids = nullptr, *wt_miss_pos = nullptr;  // arguments of that lookup
+    // A tiered lookup between its two halves (bgl_cache_lookup_tiered_begin / _finish): the host threads
+    // are packing its rows, the kernels that take them to their places have not been enqueued yet.
+    struct TieredCall {
+        bool active = false;
+        bgl_host_tier *t = nullptr;
+        bgl::TierPlan plan;
+        hipStream_t ms = nullptr, ss = nullptr, ls = nullptr;
+        const int32_t *ids = nullptr, *mpos = nullptr, *src_of = nullptr;
+        int32_t *miss_pos = nullptr;
+        void *out_rows = nullptr;
+        int64_t n = 0;
+        int par = 0, gen = 0;
+    } tiered;
     // profiling
     unsigned profiling = 0;          // bit s set: stage s is timed
     hipEvent_t timed_start = nullptr, timed_stop = nullptr;  // events the next launch() hands to the kernel dispatch itself
@@ -1201,6 +1214,8 @@ int check_lookup_args(bgl_cache *c, const int32_t *ids, int64_t n, void *out_row
     if (n > 0 && (!ids || !out_rows || !out_slot || !miss_pos))
         BGL_FAIL(BGL_EINVAL, "ids, out_rows, out_slot and miss_pos must not be null");
     if (!bgl::aligned(out_rows, 16)) BGL_FAIL(BGL_EINVAL, "out_rows is not 16-byte aligned");
+    if (c->tiered.active)
+        BGL_FAIL(BGL_EINVAL, "a tiered lookup has been begun: bgl_cache_lookup_tiered_finish comes first");
     if (c->write_through && c->awaiting_insert)
         BGL_FAIL(BGL_EINVAL, "write-through mode: the previous lookup's misses have not been inserted yet");
     return BGL_OK;
@@ -1335,12 +1350,14 @@ try {
     const LookupLists lists{reinterpret_cast<int32_t *>(base), NOALLOC_TILES,
                             reinterpret_cast<int32_t *>(base + NOALLOC_MBS_BYTES), NOALLOC_MAX_IDS};
     // (a timed launch may have to create events: this call's kernels are not timed)
-    const unsigned profiling = c->profiling;
-    c->profiling = 0;
-    rc = lookup_gather_impl(c, ids, n, out_rows, out_slot, miss_pos, n_hit_host, main_stream, side_stream,
-                            nullptr, false, &lists);
-    c->profiling = profiling;
-    return rc;
+    struct Untimed {
+        bgl_cache *c;
+        unsigned saved;
+        explicit Untimed(bgl_cache *c_) : c(c_), saved(c_->profiling) { c->profiling = 0; }
+        ~Untimed() { c->profiling = saved; }
+    } untimed(c);
+    return lookup_gather_impl(c, ids, n, out_rows, out_slot, miss_pos, n_hit_host, main_stream, side_stream,
+                              nullptr, false, &lists);
 } BGL_NOTHROW_END
 
 extern "C" int bgl_cache_lookup_gather_early(bgl_cache_t *c, const int32_t *ids, int64_t n,
@@ -1467,6 +1484,9 @@ int rows_by_copy_engine(const TieredRows &r, char *land)
     // A copy costs the link a few microseconds whatever its size, so while earlier copies (the
     // previous call's, or this call's) still occupy the link the packed rows pile up for one larger
     // copy; when the link is free a chunk goes at once.
+    // (`land` was last read by the kernels of the call before the previous one.  They are over: this call's
+    // lists, which the host has just waited for, follow the previous call's map update, which follows that
+    // call's lists, which were recorded behind the wait for those kernels.)
     int64_t chunk = r.early ? TIER_CHUNK_ROWS : TIER_FIRST_CHUNK_ROWS;
     bool link_busy = bgl::tier_copy_event_recorded(t);
     for (int64_t launched = 0; launched < total;) {
@@ -1553,11 +1573,14 @@ int rows_by_kernels(const TieredRows &r)
 
 }  // namespace
 
-extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t, const int32_t *ids,
-                                              int64_t n, void *out_rows, int32_t *out_slot,
-                                              int32_t *miss_pos, int64_t *n_hit, void *main_stream,
-                                              void *side_stream, void *lookup_stream, int early_lookup)
-try {
+namespace {
+
+// First half of a tiered lookup: the map lookup and the lists (and, unless one pass will write the whole
+// output, the hit gather) are enqueued, the host waits for the lists and its threads start packing rows.
+int tiered_begin(bgl_cache_t *c, bgl_host_tier_t *t, const int32_t *ids, int64_t n, void *out_rows,
+                 int32_t *out_slot, int32_t *miss_pos, void *main_stream, void *side_stream, void *lookup_stream,
+                 int early_lookup)
+{
     int rc = check_lookup_args(c, ids, n, out_rows, out_slot, miss_pos);
     if (rc != BGL_OK) return rc;
     if (!t) BGL_FAIL(BGL_EINVAL, "tier handle is null");
@@ -1595,42 +1618,110 @@ try {
     } guard{t};
     // the host continues as soon as the lists are there; the hit gather runs meanwhile
     BGL_HIP(hipEventSynchronize(c->ev_ids));
-    bgl::TierPlan plan;
-    rc = bgl::tier_begin(t, n, &plan);
+    bgl_cache::TieredCall &tc = c->tiered;
+    rc = bgl::tier_begin(t, n, &tc.plan);
     if (rc != BGL_OK) return rc;
     // (Waking the copy threads earlier, to have them spin until the ids arrive, was measured:
     // slower, the spinning threads get in the way of the wait for the lookup.)
     if (ss != ms) BGL_HIP(hipStreamWaitEvent(ss, c->ev_listed, 0));
-    const TieredRows rows{c, t, &plan, ss, mpos, out_rows, n, (int)(c->insert_calls & 1), ls != ms, src_of};
-    if (plan.n_hit + plan.n_miss > 0) {
+    if (tc.plan.n_hit + tc.plan.n_miss > 0) {
         rc = bgl::tier_copy_start(t);  // host threads start packing
         if (rc != BGL_OK) return rc;
-        char *land = bgl::tier_landing(t, gen);  // device memory the copy engine fills, if that transport is on
-        rc = land ? rows_by_copy_engine(rows, land) : rows_by_kernels(rows);
-        if (rc != BGL_OK) return rc;
-    } else if (src_of && n > 0) {
-        rows.launch_assemble_rows(nullptr);  // every id hit: the pass only gathers (no landed row is read)
     }
-    BGL_HIP(hipEventRecord(c->ev_miss, ss));
-    // the tier's map changes after this call's lists are final and before the next lookup,
-    // which runs on the lookup stream
-    rc = bgl::tier_enqueue_update(t, ids, miss_pos, ls);
-    if (rc != BGL_OK) return rc;
     guard.armed = false;
-    BGL_HIP(hipGetLastError());
-    c->fetch_pending = true;
-    c->fetch_stream = ss;
-    c->fetch_reads_caller_lists = mpos == miss_pos;
-    if (n_hit) {
-        n_hit[0] = plan.n_hit_gpu;
-        n_hit[1] = plan.n_hit;
-    }
+    tc.active = true;
+    tc.t = t;
+    tc.ms = ms;
+    tc.ss = ss;
+    tc.ls = ls;
+    tc.ids = ids;
+    tc.mpos = mpos;
+    tc.src_of = src_of;
+    tc.miss_pos = miss_pos;
+    tc.out_rows = out_rows;
+    tc.n = n;
+    tc.par = (int)(c->insert_calls & 1);  // (the map update of this batch may be enqueued before the second half)
+    tc.gen = gen;
     if (c->write_through) {
         c->awaiting_insert = true;
         c->wt_ids = ids;
         c->wt_miss_pos = miss_pos;
     }
     return BGL_OK;
+}
+
+// Second half: the packed rows go on their way as the host threads finish them, and the kernels that take
+// them to their places are enqueued.  Returns when the last row is packed and everything is enqueued.
+int tiered_finish(bgl_cache_t *c, int64_t *n_hit)
+{
+    bgl_cache::TieredCall &tc = c->tiered;
+    bgl_host_tier *t = tc.t;
+    tc.active = false;
+    struct Guard {
+        bgl_host_tier *t;
+        bool armed = true;
+        ~Guard() { if (armed) bgl::tier_abort(t); }
+    } guard{t};
+    const bgl::TierPlan &plan = tc.plan;
+    const TieredRows rows{c, t, &plan, tc.ss, tc.mpos, tc.out_rows, tc.n, tc.par, tc.ls != tc.ms, tc.src_of};
+    int rc;
+    if (plan.n_hit + plan.n_miss > 0) {
+        char *land = bgl::tier_landing(t, tc.gen);  // device memory the copy engine fills, if that transport is on
+        rc = land ? rows_by_copy_engine(rows, land) : rows_by_kernels(rows);
+        if (rc != BGL_OK) return rc;
+    } else if (tc.src_of && tc.n > 0) {
+        rows.launch_assemble_rows(nullptr);  // every id hit: the pass only gathers (no landed row is read)
+    }
+    BGL_HIP(hipEventRecord(c->ev_miss, tc.ss));
+    // the tier's map changes after this call's lists are final and before the next lookup,
+    // which runs on the lookup stream
+    rc = bgl::tier_enqueue_update(t, tc.ids, tc.miss_pos, tc.ls);
+    if (rc != BGL_OK) return rc;
+    guard.armed = false;
+    BGL_HIP(hipGetLastError());
+    c->fetch_pending = true;
+    c->fetch_stream = tc.ss;
+    c->fetch_reads_caller_lists = tc.mpos == tc.miss_pos;
+    if (n_hit) {
+        n_hit[0] = plan.n_hit_gpu;
+        n_hit[1] = plan.n_hit;
+    }
+    return BGL_OK;
+}
+
+}  // namespace
+
+extern "C" int bgl_cache_lookup_gather_tiered(bgl_cache_t *c, bgl_host_tier_t *t, const int32_t *ids,
+                                              int64_t n, void *out_rows, int32_t *out_slot,
+                                              int32_t *miss_pos, int64_t *n_hit, void *main_stream,
+                                              void *side_stream, void *lookup_stream, int early_lookup)
+try {
+    const int rc = tiered_begin(c, t, ids, n, out_rows, out_slot, miss_pos, main_stream, side_stream, lookup_stream,
+                                early_lookup);
+    if (rc != BGL_OK) return rc;
+    return tiered_finish(c, n_hit);
+} BGL_NOTHROW_END
+
+extern "C" int bgl_cache_lookup_tiered_begin(bgl_cache_t *c, bgl_host_tier_t *t, const int32_t *ids, int64_t n,
+                                             void *out_rows, int32_t *out_slot, int32_t *miss_pos,
+                                             int64_t *n_hit, void *main_stream, void *side_stream,
+                                             void *lookup_stream, int early_lookup)
+try {
+    const int rc = tiered_begin(c, t, ids, n, out_rows, out_slot, miss_pos, main_stream, side_stream, lookup_stream,
+                                early_lookup);
+    if (rc != BGL_OK) return rc;
+    if (n_hit) {  // known already: the lists are on the host
+        n_hit[0] = c->tiered.plan.n_hit_gpu;
+        n_hit[1] = c->tiered.plan.n_hit;
+    }
+    return BGL_OK;
+} BGL_NOTHROW_END
+
+extern "C" int bgl_cache_lookup_tiered_finish(bgl_cache_t *c)
+try {
+    if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
+    if (!c->tiered.active) BGL_FAIL(BGL_EINVAL, "no tiered lookup has been begun");
+    return tiered_finish(c, nullptr);
 } BGL_NOTHROW_END
 
 extern "C" int bgl_cache_insert_fifo(bgl_cache_t *c, const int32_t *ids, const int32_t *miss_pos,
@@ -1642,6 +1733,9 @@ try {
     if (bound > 0 && (!ids || !miss_pos || !out_rows))
         BGL_FAIL(BGL_EINVAL, "ids, miss_pos and out_rows must not be null");
     if (!bgl::aligned(out_rows, 16)) BGL_FAIL(BGL_EINVAL, "out_rows is not 16-byte aligned");
+    if (c->tiered.active && !c->write_through)
+        BGL_FAIL(BGL_EINVAL, "a tiered lookup has been begun: without write-through mode the FIFO update copies "
+                             "rows that bgl_cache_lookup_tiered_finish has yet to bring in");
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int q = c->row_bytes / 16;
     const int64_t eff = std::min<int64_t>(bound, c->capacity);
@@ -1705,7 +1799,7 @@ try {
     if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
     if (spare_rows < 0 || c->capacity + spare_rows > INT32_MAX)
         BGL_FAIL(BGL_EINVAL, "spare_rows must be >= 0 and capacity + spare_rows < 2^31 (got %lld)", (long long)spare_rows);
-    if (c->insert_calls != 0 || c->awaiting_insert)
+    if (c->insert_calls != 0 || c->awaiting_insert || c->tiered.active)
         BGL_FAIL(BGL_EINVAL, "the spare rows can only be set before the first insertion");
     BGL_HIP(hipDeviceSynchronize());
     const int64_t rows = c->capacity + spare_rows;
@@ -1731,6 +1825,7 @@ extern "C" int bgl_cache_set_write_through(bgl_cache_t *c, int enable)
 try {
     if (!c) BGL_FAIL(BGL_EINVAL, "cache handle is null");
     if (c->awaiting_insert) BGL_FAIL(BGL_EINVAL, "a lookup's misses are still waiting for their insert_fifo");
+    if (c->tiered.active) BGL_FAIL(BGL_EINVAL, "a tiered lookup has been begun: bgl_cache_lookup_tiered_finish comes first");
     c->write_through = enable != 0;
     return BGL_OK;
 } BGL_NOTHROW_END

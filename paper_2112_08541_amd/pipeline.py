@@ -135,17 +135,23 @@ class MinibatchPipeline:
                 # early, on the work stream (behind the previous batch's map update), so the host brings
                 # this batch's rows in while the previous fetch is on the link.
                 early = self.write_through and self.early_ok
+                # In write-through mode the call comes in two halves: once the host has the lists its threads
+                # pack the rows, and this thread enqueues the map update and the sampling of batch i+2
+                # meanwhile (a short batch would otherwise wait for those launches).
                 n_hits[i], h2 = cache.lookup_gather_tiered(self.tier, ids, n, self.out_rows, self.out_slot,
                                                            self.miss_pos, main_stream=chain, side_stream=chain,
-                                                           lookup_stream=work if early else None)
+                                                           lookup_stream=work if early else None,
+                                                           begin_only=self.write_through)
                 self.tier_hits.append(h2)
             if self.tier is not None:
-                # the host was held back by the call: the map update first, the next lookup is waiting for it
+                # the map update first: the next lookup is waiting for it
                 cache.insert_fifo(ids, self.miss_pos, -1, self.out_rows, stream=work)
             if i + 2 < steps:
                 # workspace (i+2) % 3 was batch i-1's; its fetch ended before hit gather(i)
                 cache.wait_lists(samp)
                 sbs[i + 2] = sample(i + 2)
+            if self.tier is not None and self.write_through:
+                cache.lookup_tiered_finish()
             if self.tier is None:
                 cache.insert_fifo(ids, self.miss_pos, -1, self.out_rows, stream=work)
             n_list.append(n)

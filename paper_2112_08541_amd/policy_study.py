@@ -83,8 +83,10 @@ def sample_streams(graph, cfg, seed_batches, rng_seeds):
     return out
 
 
-def gpu_fifo_hits(streams, num_nodes, capacity):
-    """Hits of the library's FIFO cache over the batches (16-byte dummy rows: only hits are counted)."""
+def gpu_fifo_hits(streams, num_nodes, capacity, timing=None):
+    """Hits of the library's FIFO cache over the batches (16-byte dummy rows: only hits are counted).
+    `timing`, a list, receives the mean milliseconds per batch of the calls (lookup + FIFO update with
+    rows of 16 bytes: the policy's bookkeeping, Sec. 3.2.1's "overhead", next to no row traffic)."""
     import torch
     from . import binding as B
     feats = torch.zeros((num_nodes, 16), dtype=torch.uint8, device="cuda")
@@ -93,10 +95,18 @@ def gpu_fifo_hits(streams, num_nodes, capacity):
     out_rows = torch.empty((cap, 16), dtype=torch.uint8, device="cuda")
     out_slot = torch.empty(cap, dtype=torch.int32, device="cuda")
     miss_pos = torch.empty(cap, dtype=torch.int32, device="cuda")
-    for s in streams:
-        ids = torch.from_numpy(s).cuda()
-        cache.lookup_gather(ids, len(s), out_rows, out_slot, miss_pos)
+    on_dev = [torch.from_numpy(s).cuda() for s in streams]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for ids in on_dev:
+        cache.lookup_gather(ids, len(ids), out_rows, out_slot, miss_pos)
         cache.insert_fifo(ids, miss_pos, -1, out_rows)
+    cache.wait_rows()
+    e1.record()
+    torch.cuda.synchronize()
+    if timing is not None:
+        timing.append(e0.elapsed_time(e1) / max(len(streams), 1))
     st = cache.stats()
     cache.close()
     assert st["lookups"] == sum(len(s) for s in streams)
@@ -126,22 +136,29 @@ def run_study(cfg, row_ptr, col, num_batches, fractions):
                "po": sample_streams(graph, cfg, po, rng_seeds)}
     # static cache: the nodes that appear most often as a neighbor, ties by id
     hottest = np.argsort(-np.bincount(col, minlength=N), kind="stable").astype(np.int32)
-    hits, caps = {}, []
+    hits, overhead_ms, caps = {}, {}, []
+
+    def simulate(kind, cap, which, ms):
+        sim = PolicySim(kind, N, cap, hottest)
+        t0 = time.perf_counter()
+        h = sum(sim.batch(s) for s in streams[which])
+        ms.append(1e3 * (time.perf_counter() - t0) / nb)
+        return h
+
     for frac in fractions:
         cap = max(1, int(round(frac * N)))
         caps.append(cap)
-        row = {}
+        row, ms = {}, {c: [] for c in COLUMNS}
         for kind in ("static", "lru", "lfu"):
-            sim = PolicySim(kind, N, cap, hottest)
-            row[kind] = sum(sim.batch(s) for s in streams["random"])
-        row["fifo_random"] = gpu_fifo_hits(streams["random"], N, cap)
-        row["fifo_po"] = gpu_fifo_hits(streams["po"], N, cap)
-        sim = PolicySim("lru", N, cap)
-        row["lru_po"] = sum(sim.batch(s) for s in streams["po"])
+            row[kind] = simulate(kind, cap, "random", ms[kind])
+        row["fifo_random"] = gpu_fifo_hits(streams["random"], N, cap, ms["fifo_random"])
+        row["fifo_po"] = gpu_fifo_hits(streams["po"], N, cap, ms["fifo_po"])
+        row["lru_po"] = simulate("lru", cap, "po", ms["lru_po"])
         hits[cap] = row
+        overhead_ms[cap] = {c: v[0] for c, v in ms.items()}
     graph.close()
     return dict(train=train, roots=roots, shifts=shifts, rng_seeds=rng_seeds, order_random=rnd, order_po=po,
-                streams=streams, hottest=hottest, capacities=caps, hits=hits,
+                streams=streams, hottest=hottest, capacities=caps, hits=hits, overhead_ms=overhead_ms,
                 lookups={k: sum(len(s) for s in v) for k, v in streams.items()})
 
 
@@ -181,6 +198,13 @@ def main():
         row = r["hits"][cap]
         ratios = [row[c] / total["po" if c.endswith("_po") else "random"] for c in COLUMNS]
         print(f"| {frac:.3f} ({cap} rows) | " + " | ".join(f"{x:.3f}" for x in ratios) + " |")
+    print("\nBookkeeping per batch in milliseconds (lookup + policy update, Sec. 3.2.1's overhead; FIFO columns: the library's "
+          "calls on the GPU with 16-byte rows, one after the other on one stream; the others: the host simulators on one core, "
+          "O(1) list updates per id):\n")
+    print("| cache size | static | LRU | LFU | FIFO, random order | FIFO, proximity-aware order | LRU, proximity-aware order |")
+    print("|---|---|---|---|---|---|---|")
+    for frac, cap in zip(fractions, r["capacities"]):
+        print(f"| {frac:.3f} | " + " | ".join(f"{r['overhead_ms'][cap][c]:.2f}" for c in COLUMNS) + " |")
     torch.cuda.synchronize()
 
 

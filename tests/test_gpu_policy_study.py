@@ -55,3 +55,4 @@ def test_policy_study_every_column_matches_the_oracle():
     small, large = r["hits"][r["capacities"][0]], r["hits"][r["capacities"][-1]]
     for c in policy_study.COLUMNS:
         assert 0 < large[c] and small[c] <= large[c], c
+        assert all(r["overhead_ms"][cap][c] > 0 for cap in r["capacities"]), c

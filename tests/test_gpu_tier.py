@@ -34,7 +34,7 @@ def assert_tier_state_equal(tier, oc2, what):
 
 
 def run_tiered_stream(B, torch, feats, cap1, cap2, batches, write_through, threads, side=True,
-                      cache_has_store=False, early=None, copy_engine=False, spare=0):
+                      cache_has_store=False, early=None, copy_engine=False, spare=0, halves=False):
     import oracle
     N, rb = feats.shape[0], feats.shape[1] * feats.itemsize
     store = np.ascontiguousarray(feats.view(np.uint8).reshape(N, rb))      # ordinary host memory
@@ -74,8 +74,13 @@ def run_tiered_stream(B, torch, feats, cap1, cap2, batches, write_through, threa
                 torch.cuda._sleep(2_000_000)
         use_ls = lookup_stream if (early != "alternate" or bi % 2 == 1) else None
         h1, h2 = gc.lookup_gather_tiered(tier, ids_t, n, out, out_slot, miss_pos, side_stream=side_stream,
-                                         lookup_stream=use_ls)
+                                         lookup_stream=use_ls, begin_only=halves)
         gc.insert_fifo(ids_t, miss_pos, -1, out, stream=lookup_stream if early == "with_insert" else None)
+        if halves:      # the call in two halves: the map update is enqueued between them, as the pipeline does
+            if bi % 3 == 1:
+                with torch.cuda.stream(streams[(bi + 1) % len(streams)]):
+                    torch.cuda._sleep(1_000_000)
+            gc.lookup_tiered_finish()
         gc.wait_rows()
         torch.cuda.synchronize()
         # oracle: level 1, then level 2 on level 1's misses, both updated first-in first-out
@@ -123,6 +128,56 @@ def test_tiered_random_streams(B, torch_mod, dim, dtype, write_through, early, c
     batches = zipf_batches(rng, N, 14, 1, 2500, big=9000)
     run_tiered_stream(B, torch_mod, feats, 1500, 4000, batches, write_through, threads=4, early=early,
                       copy_engine=copy_engine)
+
+
+@pytest.mark.parametrize("cap2", [0, 4000])
+@pytest.mark.parametrize("early", [None, "own", "with_insert"])
+@pytest.mark.parametrize("copy_engine,spare", [(False, 0), (True, 0), (2, 0), (2, 9000)])
+def test_tiered_lookup_in_two_halves(B, torch_mod, cap2, early, copy_engine, spare):
+    """bgl_cache_lookup_tiered_begin / _finish with the batch's map update enqueued between them."""
+    rng = np.random.default_rng(77 + cap2)
+    N = 20000
+    feats = rng.standard_normal((N, 100)).astype(np.float32)
+    batches = zipf_batches(rng, N, 14, 1, 2500, big=9000)
+    run_tiered_stream(B, torch_mod, feats, 1500, cap2, batches, True, threads=4, early=early,
+                      copy_engine=copy_engine, spare=spare, halves=True)
+
+
+def test_tiered_halves_refuse_what_does_not_fit_between_them(B, torch_mod):
+    torch = torch_mod
+    rng = np.random.default_rng(5)
+    N = 4000
+    feats = rng.standard_normal((N, 8)).astype(np.float32)
+    store = np.ascontiguousarray(feats.view(np.uint8).reshape(N, 32))
+    gc = B.Cache(500, None, num_nodes=N, row_bytes=32)
+    tier = B.HostTier(store, 0, 1000, 2)
+    ids = torch.arange(0, 300, dtype=torch.int32, device="cuda")
+    out = torch.zeros((1000, 32), dtype=torch.uint8, device="cuda")
+    slot = torch.zeros(1000, dtype=torch.int32, device="cuda")
+    mp = torch.zeros(1000, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.BglError, match="no tiered lookup has been begun"):
+        gc.lookup_tiered_finish()
+    # without write-through mode the FIFO update needs the rows the second half brings in
+    gc.lookup_gather_tiered(tier, ids, 300, out, slot, mp, begin_only=True)
+    with pytest.raises(B.BglError, match="has been begun"):
+        gc.insert_fifo(ids, mp, -1, out)
+    with pytest.raises(B.BglError, match="has been begun"):
+        gc.lookup_gather_tiered(tier, ids, 300, out, slot, mp)
+    with pytest.raises(B.BglError, match="has been begun"):
+        gc.set_write_through(True)
+    gc.lookup_tiered_finish()
+    gc.insert_fifo(ids, mp, -1, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out[:300].cpu().numpy(), store[:300])
+    # and the pair still works after the refusals: everything hits now
+    h1, h2 = gc.lookup_gather_tiered(tier, ids, 300, out, slot, mp, begin_only=True)
+    gc.lookup_tiered_finish()
+    gc.insert_fifo(ids, mp, -1, out)
+    torch.cuda.synchronize()
+    assert (h1, h2) == (300, 0)
+    assert np.array_equal(out[:300].cpu().numpy(), store[:300])
+    tier.close()
+    gc.close()
 
 
 @pytest.mark.parametrize("cap2", [0, 900_000])
