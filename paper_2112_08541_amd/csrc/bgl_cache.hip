@@ -1487,7 +1487,10 @@ int rows_by_copy_engine(const TieredRows &r, char *land)
     // (`land` was last read by the kernels of the call before the previous one.  They are over: this call's
     // lists, which the host has just waited for, follow the previous call's map update, which follows that
     // call's lists, which were recorded behind the wait for those kernels.)
-    int64_t chunk = r.early ? TIER_CHUNK_ROWS : TIER_FIRST_CHUNK_ROWS;
+    // (an early lookup is ahead of the link as a rule: large chunks from the start, but a short batch is
+    // not held back for one)
+    int64_t chunk = r.early ? std::min(TIER_CHUNK_ROWS, std::max<int64_t>(total / 4, 4 * TIER_FIRST_CHUNK_ROWS))
+                            : TIER_FIRST_CHUNK_ROWS;
     bool link_busy = bgl::tier_copy_event_recorded(t);
     for (int64_t launched = 0; launched < total;) {
         const int64_t ready = bgl::tier_copy_progress(t);
