@@ -189,19 +189,27 @@ __global__ __launch_bounds__(BT) void k_list_write(const int32_t *__restrict__ l
     if (flag) seq[*seq_base + pre[blockIdx.x] + ex] = list[i];
 }
 
-// Smallest unvisited node with an unvisited out-neighbor other than itself.
+// Smallest unvisited node with an unvisited out-neighbor other than itself.  The search runs at every
+// restart of the traversal, and the visited set only grows: an edge that once led to a visited node
+// (or back to its own node) always will, so every node keeps the number of leading edges of its row
+// that are known to (`cursor`) and the next search goes on from there.  Over a whole traversal a row
+// is walked once, however many restarts there are.
 template <typename RP>
 __global__ __launch_bounds__(BT) void k_open_min(const RP *__restrict__ row_ptr, const int32_t *__restrict__ col,
-                                                 const uint32_t *__restrict__ visited, int64_t num_nodes, OrderDev *dev)
+                                                 const uint32_t *__restrict__ visited, int64_t num_nodes,
+                                                 int32_t *cursor, OrderDev *dev)
 {
     const int64_t v = (int64_t)blockIdx.x * BT + threadIdx.x;
     if (v >= num_nodes || test_bit(visited, (uint32_t)v)) return;
     if (v >= dev->open_min) return;  // cannot improve the minimum
     const int64_t lo = (int64_t)row_ptr[v], hi = (int64_t)row_ptr[v + 1];
-    for (int64_t e = lo; e < hi; ++e) {
+    int64_t e = lo + cursor[v];
+    for (; e < hi; ++e) {
         const uint32_t u = (uint32_t)col[e];
-        if ((int64_t)u != v && !test_bit(visited, u)) { atomicMin(&dev->open_min, (int)v); return; }
+        if ((int64_t)u != v && !test_bit(visited, u)) break;
     }
+    cursor[v] = (int32_t)(e - lo);
+    if (e < hi) atomicMin(&dev->open_min, (int)v);
 }
 
 // Every unvisited node below dev->open_min is closed: mark them all for the next compaction.
@@ -221,6 +229,7 @@ __global__ __launch_bounds__(BT) void k_take_closed(const uint32_t *__restrict__
 struct OrderWork {
     uint32_t *visited = nullptr, *next = nullptr, *train = nullptr;
     int32_t *frontier = nullptr, *cand = nullptr, *seq = nullptr, *train_ids = nullptr, *bs = nullptr, *seq_base = nullptr;
+    int32_t *cursor = nullptr;  // per node: leading edges of its row known to end at visited nodes (k_open_min)
     uint64_t *key = nullptr, *keys_in = nullptr, *keys_out = nullptr;
     void *sort_tmp = nullptr;
     size_t sort_tmp_bytes = 0;
@@ -251,7 +260,7 @@ int prepare(const bgl_graph *g, const int32_t *train_nodes, int64_t num_train, O
     const size_t nt = (size_t)std::max<int64_t>(num_train, 1);
     const size_t sizes[] = {(size_t)words * 4, (size_t)words * 4, (size_t)words * 4, (size_t)N * 4, (size_t)N * 4,
                             (size_t)N * 8, (size_t)N * 8, (size_t)N * 8, nt * 4, nt * 4, (size_t)(nb + 1) * 4, 4,
-                            sizeof(OrderDev), std::max<size_t>(w.sort_tmp_bytes, 16)};
+                            sizeof(OrderDev), std::max<size_t>(w.sort_tmp_bytes, 16), (size_t)N * 4};
     size_t total = 0;
     for (size_t sz : sizes) total += round_up(sz, 256);
     BGL_HIP(hipMalloc((void **)&w.block, total));
@@ -271,6 +280,7 @@ int prepare(const bgl_graph *g, const int32_t *train_nodes, int64_t num_train, O
     w.seq_base = reinterpret_cast<int32_t *>(take(11));
     w.dev = reinterpret_cast<OrderDev *>(take(12));
     w.sort_tmp = take(13);
+    w.cursor = reinterpret_cast<int32_t *>(take(14));
     BGL_HIP(hipHostMalloc((void **)&w.host, sizeof(OrderDev), hipHostMallocDefault));
     BGL_HIP(hipMemsetAsync(w.dev, 0, sizeof(OrderDev), st));
     BGL_HIP(hipMemcpyAsync(w.train_ids, train_nodes, num_train * 4, hipMemcpyHostToDevice, st));
@@ -293,6 +303,8 @@ int bfs_sequence(const bgl_graph *g, int64_t root, int64_t num_train, OrderWork 
     const RP *rp = static_cast<const RP *>(g->row_ptr);
     hipLaunchKernelGGL(k_reset, dim3(nbw), dim3(BT), 0, st, w.visited, w.next, words, N, w.dev);
     hipLaunchKernelGGL(k_fill_key, dim3((unsigned)std::min<int64_t>(ceil_div(N, BT), 8192)), dim3(BT), 0, st, w.key, N);
+    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)std::min<int64_t>(ceil_div(N, BT), 8192)), dim3(BT), 0, st,
+                       reinterpret_cast<uint32_t *>(w.cursor), N, 0u);
     hipLaunchKernelGGL(k_start_at, dim3(1), dim3(64), 0, st, (int32_t)root, w.visited, w.train, w.frontier, w.seq, w.dev);
     int64_t visited_count = 1;
     int fsize = 1;
@@ -332,7 +344,8 @@ int bfs_sequence(const bgl_graph *g, int64_t root, int64_t num_train, OrderWork 
             append_training(w.frontier, fsize);
         }
         if (visited_count >= N) break;
-        hipLaunchKernelGGL((k_open_min<RP>), dim3((unsigned)ceil_div(N, BT)), dim3(BT), 0, st, rp, g->col, w.visited, N, w.dev);
+        hipLaunchKernelGGL((k_open_min<RP>), dim3((unsigned)ceil_div(N, BT)), dim3(BT), 0, st, rp, g->col, w.visited, N, w.cursor,
+                           w.dev);
         hipLaunchKernelGGL(k_take_closed, dim3(nbw), dim3(BT), 0, st, w.visited, w.next, words, w.dev);
         int closed = 0;
         int rc = compact(closed);       // one-node traversals, in id order
