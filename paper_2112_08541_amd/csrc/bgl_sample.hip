@@ -18,6 +18,9 @@
 //                  publishes the stage's sizes
 //   finalize       gives every new id its local id (old frontier size + rank),
 //                  appends it to the frontier, and writes the hop's CSR block
+// A stage of at most TILE tiles (262,144 padded positions) has no scan launch:
+// every workgroup of finalize turns the tile totals into prefixes itself, in LDS
+// (one block scan), and the first one publishes the sizes.
 // Launches are sized by upper bounds; the real sizes stay on the device.
 #include "bgl_internal.h"
 
@@ -249,16 +252,40 @@ __global__ __launch_bounds__(1024) void k_scan_sums(int32_t *cnt, int stage, int
     }
 }
 
-// Local ids, frontier append, CSR block.
-__global__ __launch_bounds__(TILE) void k_finalize(const int32_t *cnt, int stage, int logG,
+// Local ids, frontier append, CSR block.  SELF_SCAN: the stage has at most TILE tiles and no scan
+// launch; fpre / cpre then hold the tile TOTALS (what k_flag and k_sample_insert wrote), every
+// workgroup scans them in LDS, and workgroup 0 publishes the stage's sizes.
+template <bool SELF_SCAN>
+__global__ __launch_bounds__(TILE) void k_finalize(int32_t *cnt, int stage, int logG,
                                                    int32_t num_seeds, uint64_t *tab,
                                                    const int32_t *slotidx, const int32_t *lrank,
                                                    const int32_t *fpre, const int32_t *cpre,
                                                    const int32_t *lrow, int32_t *frontier,
                                                    int32_t *row_ptr_h, int32_t *col_local)
 {
+    __shared__ int sh_scan[TILE / kWave];
+    __shared__ int32_t sh_f[SELF_SCAN ? TILE : 1], sh_c[SELF_SCAN ? TILE : 1];
     const int n_dst = stage == 0 ? 0 : cnt[stage - 1];
     const int64_t P = stage == 0 ? (int64_t)num_seeds : ((int64_t)n_dst << logG);
+    // (whole workgroups; the one that publishes the sizes stays, also for an empty stage)
+    if ((int64_t)blockIdx.x * TILE >= P && !(SELF_SCAN && blockIdx.x == 0)) return;
+    if constexpr (SELF_SCAN) {
+        const int nb = (int)((P + TILE - 1) / TILE);  // <= TILE
+        const int t = threadIdx.x;
+        int tf, tc;
+        sh_f[t] = block_excl_scan<TILE>(t < nb ? fpre[t] : 0, sh_scan, tf);
+        sh_c[t] = block_excl_scan<TILE>((stage > 0 && t < nb) ? cpre[t] : 0, sh_scan, tc);
+        __syncthreads();
+        if (blockIdx.x == 0 && t == 0) {
+            cnt[stage] = n_dst + tf;
+            if (stage > 0) {
+                cnt[NNZ0 + stage - 1] = tc;
+                row_ptr_h[n_dst] = tc;
+            }
+        }
+        fpre = sh_f;
+        cpre = sh_c;
+    }
     const uint32_t p = blockIdx.x * TILE + threadIdx.x;
     if ((int64_t)p >= P) return;
     const int gs = slotidx[p];
@@ -447,11 +474,16 @@ try {
                            g->num_nodes, tab, mask, slotidx, cnt);
         hipLaunchKernelGGL(k_flag, dim3(blocks), dim3(TILE), 0, st, cnt, 0, 1, num_seeds, tab,
                            slotidx, lrank, fbs);
-        hipLaunchKernelGGL(k_scan_sums, dim3(1), dim3(1024), 0, st, cnt, 0, 1, num_seeds, fbs,
-                           (const int32_t *)nullptr, fpre, cpre, (int32_t *)nullptr);
-        hipLaunchKernelGGL(k_finalize, dim3(blocks), dim3(TILE), 0, st, cnt, 0, 0, num_seeds, tab,
-                           slotidx, lrank, fpre, cpre, lrow, frontier, (int32_t *)nullptr,
-                           (int32_t *)nullptr);
+        if (blocks <= TILE) {
+            hipLaunchKernelGGL(k_finalize<true>, dim3(blocks), dim3(TILE), 0, st, cnt, 0, 0, num_seeds, tab,
+                               slotidx, lrank, fbs, cbs, lrow, frontier, (int32_t *)nullptr, (int32_t *)nullptr);
+        } else {
+            hipLaunchKernelGGL(k_scan_sums, dim3(1), dim3(1024), 0, st, cnt, 0, 1, num_seeds, fbs,
+                               (const int32_t *)nullptr, fpre, cpre, (int32_t *)nullptr);
+            hipLaunchKernelGGL(k_finalize<false>, dim3(blocks), dim3(TILE), 0, st, cnt, 0, 0, num_seeds, tab,
+                               slotidx, lrank, fpre, cpre, lrow, frontier, (int32_t *)nullptr,
+                               (int32_t *)nullptr);
+        }
     }
     for (int h = 0; h < num_hops; ++h) {
         const int blocks = (int)bgl::ceil_div(L.P[h + 1], TILE);
@@ -464,11 +496,17 @@ try {
                                      mask, slotidx, lrow, cbs);
         hipLaunchKernelGGL(k_flag, dim3(blocks), dim3(TILE), 0, st, cnt, h + 1, L.G[h], num_seeds,
                            tab, slotidx, lrank, fbs);
-        hipLaunchKernelGGL(k_scan_sums, dim3(1), dim3(1024), 0, st, cnt, h + 1, L.G[h], num_seeds,
-                           fbs, cbs, fpre, cpre, out->row_ptr[h]);
-        hipLaunchKernelGGL(k_finalize, dim3(blocks), dim3(TILE), 0, st, cnt, h + 1, L.logG[h],
-                           num_seeds, tab, slotidx, lrank, fpre, cpre, lrow, frontier,
-                           out->row_ptr[h], out->col_local[h]);
+        if (blocks <= TILE) {
+            hipLaunchKernelGGL(k_finalize<true>, dim3(blocks), dim3(TILE), 0, st, cnt, h + 1, L.logG[h],
+                               num_seeds, tab, slotidx, lrank, fbs, cbs, lrow, frontier,
+                               out->row_ptr[h], out->col_local[h]);
+        } else {
+            hipLaunchKernelGGL(k_scan_sums, dim3(1), dim3(1024), 0, st, cnt, h + 1, L.G[h], num_seeds,
+                               fbs, cbs, fpre, cpre, out->row_ptr[h]);
+            hipLaunchKernelGGL(k_finalize<false>, dim3(blocks), dim3(TILE), 0, st, cnt, h + 1, L.logG[h],
+                               num_seeds, tab, slotidx, lrank, fpre, cpre, lrow, frontier,
+                               out->row_ptr[h], out->col_local[h]);
+        }
     }
     BGL_HIP(hipGetLastError());
     if (counts_host)
