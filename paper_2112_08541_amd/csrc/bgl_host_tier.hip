@@ -303,7 +303,8 @@ int tier_copy_start(bgl_host_tier *t)
         const int64_t n_hit = t->cur_hit;
         const int64_t hi = std::min<int64_t>(n_hit + t->cur_miss, (k + 1) * COPY_TASK);
         // (asking for the scattered source rows a few rows ahead was measured: no faster, a dozen threads
-        // already keep enough reads in flight)
+        // already keep enough reads in flight; writing the packed rows with 16-byte streaming stores was
+        // measured too: 20-80 % slower than the library's memcpy)
         for (int64_t x = k * COPY_TASK; x < hi; ++x) {
             if (x < n_hit) {
                 std::memcpy(stage + (size_t)x * rb, t->rows + (size_t)hp[x] * rb, rb);
