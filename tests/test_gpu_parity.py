@@ -128,6 +128,23 @@ def test_sample_random_cases_property(B, torch_mod):
     run()
 
 
+@pytest.mark.parametrize("num_seeds", [16384, 16385, 511 * 32, 1])
+def test_sample_stage_sizes_around_the_scan_threshold(B, torch_mod, num_seeds):
+    """A stage of at most 512 tiles of 512 padded positions has its tile totals scanned inside the
+    finalize kernel, a larger one by a launch of its own: 16,384 seeds x 16 lanes (fanout 10) are
+    exactly 512 tiles, one seed more is 513; the second hop (fanout 3) is far beyond either way."""
+    import oracle
+    rng = np.random.default_rng(num_seeds)
+    N = 40000
+    deg = rng.integers(0, 25, N)
+    rp = np.zeros(N + 1, dtype=np.int32)
+    rp[1:] = np.cumsum(deg)
+    col = rng.integers(0, N, rp[-1]).astype(np.int32)
+    seeds = rng.permutation(N)[:num_seeds].astype(np.int32)
+    res = gpu_sample(B, torch_mod, rp, col, seeds.tolist(), [10, 3], 4242)
+    assert_sample_equal(res, oracle.sample_khop(rp, col, seeds, [10, 3], 4242))
+
+
 def test_sample_high_degree_hub_and_host_pinned_graph(B, torch_mod):
     import oracle
     rng = np.random.default_rng(11)
