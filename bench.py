@@ -67,6 +67,9 @@ def parse_args():
     ap.add_argument("--feature-placement", choices=("host_pinned", "device"), default="host_pinned",
                     help="where the feature table lives: page-locked host memory (the path this benchmark is "
                          "about, default) or a copy in HBM (then a miss is an HBM gather; context only)")
+    ap.add_argument("--pipeline", choices=("native", "python"), default="native",
+                    help="the overlapped batch loop: one call into the library (bgl_pipeline_run), or the same loop "
+                         "written in Python over the binding (pipeline.py)")
     ap.add_argument("--two-level", type=float, default=-1.0, metavar="FRACTION",
                     help="also time the same batches with a FIFO tier in host memory (this fraction of the "
                          "nodes) between the GPU cache and a feature store in ordinary host memory; "
@@ -211,8 +214,13 @@ def run_config(cfg, args, torch, np, B, inputs, MinibatchPipeline, want_cpu):
 
     # warm-up on a scratch cache of the same size, so the timed epoch starts from an empty cache
     scratch = new_cache()
-    pipe = MinibatchPipeline(graph, scratch, cfg.batch, cfg.fanouts, cfg.row_bytes,
-                             write_through=not args.no_write_through)
+    if args.pipeline == "native" and not args.no_write_through:
+        # the overlapped loop as one call into the library (bgl_pipeline_run); same calls, same streams
+        from paper_2112_08541_amd.pipeline import NativePipeline
+        pipe = NativePipeline(graph, scratch, cfg.batch, cfg.fanouts, cfg.row_bytes)
+    else:
+        pipe = MinibatchPipeline(graph, scratch, cfg.batch, cfg.fanouts, cfg.row_bytes,
+                                 write_through=not args.no_write_through)
     # Miss path.  Staging pays when batches are large (a quarter more for rows that are not multiples
     # of 128 bytes, a few per cent otherwise: the link never waits for the hit gather), provided the
     # box has the host cores for the copy threads (with 3 of them zero-copy was the faster path):
@@ -314,7 +322,7 @@ def run_config(cfg, args, torch, np, B, inputs, MinibatchPipeline, want_cpu):
             "mean_input_nodes": tot_n / steps,
             "hit_ratio_cumulative": tot_hit / max(tot_n, 1),
             "hit_ratio_steady_state": steady_ratio,
-            "miss_path": miss_path,
+            "miss_path": miss_path, "pipeline": type(pipe).__name__,
             "miss_path_trial_ms_per_batch": trial or None,
             "host_copy_threads": (stage_ring.stats()["threads"] if staged else 0),
             "host_copy_ms_per_batch": ((stage_ring.stats()["copy_ms"] - ring_before["copy_ms"]) / steps

@@ -593,6 +593,98 @@ int bgl_order_choose_sequences(const bgl_graph_t *g, const int32_t *train_nodes,
 int bgl_order_shuffling_error(const int32_t *order, int64_t n, int32_t batch, const int32_t *labels,
                               int64_t num_nodes, int32_t num_classes, double *mean_tv, double *max_tv);
 
+/* ------------------------------------------------------ the overlapped loop */
+
+/*
+ * Minibatch preparation as one loop over the calls above (Sec. 3.3: the stages
+ * of minibatch preparation run as an asynchronous pipeline; on one GPU: batch
+ * i+2 is sampled and batch i+1 looked up while batch i's miss rows cross the
+ * host link).  Per batch: bgl_sample_khop two batches ahead, the host reads the
+ * number of input nodes, bgl_cache_lookup_gather (early form for batches of
+ * 65,536 input nodes or more; with a host tier the two halves of
+ * bgl_cache_lookup_gather_tiered) and bgl_cache_insert_fifo of all misses.  The
+ * loop enqueues what a caller of those functions would, on a stream of its own
+ * for lookups, gathers and miss rows, on work_stream for the map updates and
+ * early lookups, and (with a host tier and early lookups) on a third for the
+ * sampling; results equal those of the calls made one after the other.
+ *
+ * The buffers stay the caller's (device memory unless stated), alive until
+ * bgl_pipeline_destroy:
+ *   workspace[3]     sampling workspaces, 256-byte aligned, workspace_bytes >=
+ *                    bgl_sample_workspace_bytes(batch, fanouts, ...) each
+ *   counts_host[3]   page-locked host memory, BGL_COUNTS_LEN ints each
+ *   out_rows         cap_rows * row_bytes bytes, 16-byte aligned: the feature
+ *                    rows of the current batch's input nodes
+ *   out_slot, miss_pos  cap_rows ints each (as in bgl_cache_lookup_gather)
+ *   cap_rows         >= min(num_nodes, batch * prod(1 + fanouts[h])), the bound
+ *                    on a batch's input nodes
+ */
+typedef struct bgl_pipeline bgl_pipeline_t;
+typedef struct {
+    void *workspace[3];
+    size_t workspace_bytes;
+    int32_t *counts_host[3];
+    void *out_rows;
+    int32_t *out_slot;
+    int32_t *miss_pos;
+    int64_t cap_rows;
+} bgl_pipeline_buffers_t;
+
+/*
+ * Called on the calling thread once batch `step`'s lookup and FIFO update have
+ * been enqueued: sg is the batch's sampled subgraph (in workspace[sampler]),
+ * n_input its number of input nodes.  Work the callback enqueues on the chain
+ * stream (bgl_pipeline_streams) behind bgl_cache_wait_rows sees the batch's
+ * complete out_rows; out_slot and miss_pos are rewritten by the next batch's
+ * lookup, which may run on work_stream, so their readers enqueue there.
+ */
+typedef void (*bgl_batch_fn)(void *user, int64_t step, int32_t sampler, const bgl_subgraph_t *sg,
+                             int64_t n_input);
+
+/*
+ * The cache is put in write-through mode; spare_rows != 0 also gives it one
+ * spare row position per id of the largest batch (bgl_cache_set_spare_rows:
+ * the cache must be new).  tier may be null (misses are read from the cache's
+ * backing store in place).  work_stream: see above (NULL = the default stream).
+ * Errors: BGL_EINVAL, BGL_ECAPACITY (a buffer is too small), BGL_ENOMEM,
+ * BGL_EHIP, and those of the calls named.
+ */
+int bgl_pipeline_create(const bgl_graph_t *g, bgl_cache_t *c, bgl_host_tier_t *tier, int32_t batch,
+                        const int32_t *fanouts, int32_t num_hops,
+                        const bgl_pipeline_buffers_t *buffers, int spare_rows, void *work_stream,
+                        bgl_pipeline_t **out);
+int bgl_pipeline_destroy(bgl_pipeline_t *p);
+/* Another cache from the next run on: put in write-through mode and (spare_rows != 0; the cache must
+ * be new) given its spare row positions, as by bgl_pipeline_create. */
+int bgl_pipeline_set_cache(bgl_pipeline_t *p, bgl_cache_t *c, int spare_rows);
+/* Another host tier (or none) from the next run on. */
+int bgl_pipeline_set_tier(bgl_pipeline_t *p, bgl_host_tier_t *tier);
+/* The loop's streams (hipStream_t as void*); either pointer may be null. */
+int bgl_pipeline_streams(bgl_pipeline_t *p, void **chain_stream, void **work_stream);
+/* The most recent batch: its input nodes (device, inside one of the workspaces; null before the
+ * first batch) and their number; out_rows holds their rows.  Either pointer may be null. */
+int bgl_pipeline_last_batch(bgl_pipeline_t *p, const int32_t **input_nodes, int64_t *n_input);
+/*
+ * Prepare `steps` minibatches.  Batch i uses the seeds of seed batch
+ * b = (first_step + i) mod seed_batches and the call seed
+ * rng_seeds[b] xor ((first_step + i) / seed_batches), so that a later pass over
+ * the same seeds samples differently.
+ *   seeds        device, seed_batches * batch ids, ready in work_stream order
+ *   rng_seeds    host, seed_batches values
+ *   n_input      host, steps values: input nodes per batch
+ *   n_hit        host, steps values: cache hits per batch; page-locked memory
+ *                when the pipeline has no host tier (the device writes them)
+ *   n_hit_tier   host, steps values or null: hits in the host tier
+ *   on_batch     may be null
+ * Returns after a device synchronisation: every batch is complete, the last
+ * batch's rows are in out_rows.
+ * Errors: those of the calls named above; after an error the cache and the tier
+ * may be between two batches (destroy them).
+ */
+int bgl_pipeline_run(bgl_pipeline_t *p, const int32_t *seeds, int64_t seed_batches,
+                     const uint64_t *rng_seeds, int64_t steps, int64_t first_step, int64_t *n_input,
+                     int64_t *n_hit, int64_t *n_hit_tier, bgl_batch_fn on_batch, void *user);
+
 #ifdef __cplusplus
 }
 #endif

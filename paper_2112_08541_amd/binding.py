@@ -40,6 +40,7 @@ EXPORTS = [
     "bgl_host_tier_export_state", "bgl_host_tier_stats",
     "bgl_order_bfs_sequence", "bgl_order_proximity", "bgl_order_choose_sequences",
     "bgl_order_shuffling_error",
+    "bgl_pipeline_create", "bgl_pipeline_destroy", "bgl_pipeline_set_cache", "bgl_pipeline_set_tier", "bgl_pipeline_streams", "bgl_pipeline_last_batch", "bgl_pipeline_run",
 ]
 
 
@@ -59,6 +60,21 @@ class SubgraphStruct(C.Structure):
         ("cap_edges", C.c_int64 * BGL_MAX_HOPS),
         ("counts", C.c_void_p),
     ]
+
+
+class PipelineBuffers(C.Structure):
+    _fields_ = [
+        ("workspace", C.c_void_p * 3),
+        ("workspace_bytes", C.c_size_t),
+        ("counts_host", C.c_void_p * 3),
+        ("out_rows", C.c_void_p),
+        ("out_slot", C.c_void_p),
+        ("miss_pos", C.c_void_p),
+        ("cap_rows", C.c_int64),
+    ]
+
+
+BATCH_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_int64, C.c_int32, C.POINTER(SubgraphStruct), C.c_int64)
 
 
 def load_library(path: str = LIB_PATH) -> C.CDLL:
@@ -104,6 +120,13 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
                                              C.POINTER(i32), vp, vp, vp]
     L.bgl_order_shuffling_error.argtypes = [vp, i64, i32, vp, i64, i32, C.POINTER(C.c_double),
                                             C.POINTER(C.c_double)]
+    L.bgl_pipeline_create.argtypes = [vp, vp, vp, i32, vp, i32, C.POINTER(PipelineBuffers), ci, vp, C.POINTER(vp)]
+    L.bgl_pipeline_destroy.argtypes = [vp]
+    L.bgl_pipeline_set_cache.argtypes = [vp, vp, ci]
+    L.bgl_pipeline_set_tier.argtypes = [vp, vp]
+    L.bgl_pipeline_streams.argtypes = [vp, C.POINTER(vp), C.POINTER(vp)]
+    L.bgl_pipeline_last_batch.argtypes = [vp, C.POINTER(vp), C.POINTER(i64)]
+    L.bgl_pipeline_run.argtypes = [vp, vp, i64, vp, i64, i64, vp, vp, vp, BATCH_FN, vp]
     for name in EXPORTS:
         if name != "bgl_last_error":
             getattr(L, name).restype = ci

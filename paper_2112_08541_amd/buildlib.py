@@ -10,7 +10,7 @@ _ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 INCLUDE = os.path.join(_ROOT, "include")
 LIB = os.path.join(_HERE, "libbgl.so")
-HIP_SOURCES = ["bgl_api.hip", "bgl_sample.hip", "bgl_cache.hip", "bgl_host_tier.hip", "bgl_order.hip"]
+HIP_SOURCES = ["bgl_api.hip", "bgl_sample.hip", "bgl_cache.hip", "bgl_host_tier.hip", "bgl_order.hip", "bgl_pipeline.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

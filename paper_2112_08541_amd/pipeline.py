@@ -160,3 +160,108 @@ class MinibatchPipeline:
                 on_batch(i, sb, n, self)
         torch.cuda.synchronize()
         return n_list, [int(x) for x in n_hits[:steps]]
+
+
+class NativePipeline:
+    """The same loop as one call into the library (bgl_pipeline_run): write-through mode only.  Same
+    attributes and run() as MinibatchPipeline; the buffers are torch tensors handed to the library."""
+
+    def __init__(self, graph: B.Graph, cache: B.Cache, batch: int, fanouts, row_bytes: int,
+                 tier: Optional[B.HostTier] = None, spare_rows: bool = True):
+        import ctypes as C
+        self.graph, self.cache = graph, cache
+        self.batch = int(batch)
+        self.fanouts = np.ascontiguousarray([int(f) for f in fanouts], dtype=np.int32)
+        self.K = len(self.fanouts)
+        self.samplers = [B.Sampler(graph, batch, self.fanouts) for _ in range(3)]   # workspaces and counts blocks
+        self.cap = int(min(graph.num_nodes, batch * np.prod([1 + int(f) for f in self.fanouts])))
+        self.out_rows = torch.empty((self.cap, row_bytes), dtype=torch.uint8, device="cuda")
+        self.out_slot = torch.empty(self.cap, dtype=torch.int32, device="cuda")
+        self.miss_pos = torch.empty(self.cap, dtype=torch.int32, device="cuda")
+        self.write_through = True
+        self.spare_rows = spare_rows
+        self.early_ok = self.cap >= 65536
+        self.work = torch.cuda.current_stream()
+        buf = B.PipelineBuffers()
+        for k, smp in enumerate(self.samplers):
+            buf.workspace[k] = smp.workspace.data_ptr()
+            buf.counts_host[k] = smp.counts_host.data_ptr()
+        buf.workspace_bytes = self.samplers[0].workspace_bytes
+        buf.out_rows, buf.out_slot, buf.miss_pos = (self.out_rows.data_ptr(), self.out_slot.data_ptr(),
+                                                    self.miss_pos.data_ptr())
+        buf.cap_rows = self.cap
+        h = C.c_void_p()
+        B._check(B.lib().bgl_pipeline_create(graph._h, cache._h, None if tier is None else tier._h, self.batch,
+                                             self.fanouts.ctypes.data, self.K, C.byref(buf), 1 if spare_rows else 0,
+                                             B._stream_handle(self.work), C.byref(h)))
+        self._h = h
+        self._tier = tier
+        chain = C.c_void_p()
+        B._check(B.lib().bgl_pipeline_streams(self._h, C.byref(chain), None))
+        self.chain = torch.cuda.ExternalStream(chain.value or 0)
+        self.tier_hits = []
+        self.last_ids, self.last_n = None, 0
+
+    def set_cache(self, cache: B.Cache) -> None:
+        """`cache` must be new (no insertion yet) when the pipeline gives it spare row positions."""
+        B._check(B.lib().bgl_pipeline_set_cache(self._h, cache._h, 1 if self.spare_rows else 0))
+        self.cache = cache
+
+    @property
+    def tier(self):
+        return self._tier
+
+    @tier.setter
+    def tier(self, tier):
+        B._check(B.lib().bgl_pipeline_set_tier(self._h, None if tier is None else tier._h))
+        self._tier = tier
+
+    def run(self, seeds_dev: torch.Tensor, rng_seeds, steps: int,
+            on_batch: Optional[Callable] = None, first_step: int = 0):
+        import ctypes as C
+        nb = seeds_dev.shape[0]
+        seeds_dev = seeds_dev.contiguous()
+        rng = np.ascontiguousarray(rng_seeds, dtype=np.uint64)
+        n_input = np.zeros(max(steps, 1), dtype=np.int64)
+        n_hit = torch.zeros(max(steps, 1), dtype=torch.int64).pin_memory()
+        n_tier = np.zeros(max(steps, 1), dtype=np.int64)
+        raised = []
+
+        def hook(_user, i, k, sg, n):
+            if raised:
+                return
+            try:
+                st = B.SubgraphStruct()
+                C.memmove(C.byref(st), sg, C.sizeof(st))
+                sb = B.SampledBatch(self.samplers[k], st)
+                self.last_ids, self.last_n = sb.input_nodes(self.cap), int(n)
+                on_batch(int(i), sb, int(n), self)
+            except BaseException as e:       # (an exception cannot cross the C frames: it is raised afterwards)
+                raised.append(e)
+
+        cb = B.BATCH_FN(hook) if on_batch is not None else C.cast(None, B.BATCH_FN)
+        B._check(B.lib().bgl_pipeline_run(self._h, B._dev_ptr(seeds_dev, torch.int32), nb, rng.ctypes.data, steps,
+                                          first_step, n_input.ctypes.data, n_hit.data_ptr(), n_tier.ctypes.data, cb, None))
+        if raised:
+            raise raised[0]
+        self.tier_hits = [int(x) for x in n_tier[:steps]] if self._tier is not None else []
+        ids, n = C.c_void_p(), C.c_int64()
+        B._check(B.lib().bgl_pipeline_last_batch(self._h, C.byref(ids), C.byref(n)))
+        if ids.value:
+            for smp in self.samplers:       # the ids are a view into the workspace that holds them
+                off = ids.value - smp.workspace.data_ptr()
+                if 0 <= off < smp.workspace_bytes:
+                    self.last_ids = smp.workspace[off: off + 4 * self.cap].view(torch.int32)
+            self.last_n = int(n.value)
+        return [int(x) for x in n_input[:steps]], [int(x) for x in n_hit[:steps]]
+
+    def close(self):
+        if getattr(self, "_h", None):
+            B._check(B.lib().bgl_pipeline_destroy(self._h))
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

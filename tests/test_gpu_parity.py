@@ -516,7 +516,16 @@ def test_overlapped_pipeline_as_benchmarked_matches_oracle(torch_mod, B, write_t
     run_overlapped_against_oracle(torch_mod, B, w, 8, write_through)
 
 
-def run_overlapped_against_oracle(torch_mod, B, w, steps, write_through=True, staged=False):
+@pytest.mark.parametrize("config,staged", [("tiny", False), ("mid", False), ("mid", True), ("mid", 2), ("bfs", 2)])
+def test_native_pipeline_matches_oracle(torch_mod, B, config, staged):
+    """bgl_pipeline_run, the overlapped loop as one call into the library: every batch's sampled
+    blocks, lists and rows (read in the per-batch callback) and the final cache state."""
+    from helpers import make_workload
+    w = make_workload(_inputs().CONFIGS[config], pinned=True)
+    run_overlapped_against_oracle(torch_mod, B, w, 10, staged=staged, native=True)
+
+
+def run_overlapped_against_oracle(torch_mod, B, w, steps, write_through=True, staged=False, native=False):
     """MinibatchPipeline as bench.py sets it up for the workload's configuration (graph placement
     included; staged: miss rows packed by host threads into a page-locked ring and moved by the copy
     engine, bench.py's default for large batches); every batch's sampled blocks, lists and rows, and
@@ -526,7 +535,11 @@ def run_overlapped_against_oracle(torch_mod, B, w, steps, write_through=True, st
     placement = B.BGL_HOST_PINNED if cfg.graph_placement == "host_pinned" else B.BGL_DEVICE
     graph = B.Graph(w.row_ptr, w.col, placement)
     cache = B.Cache(cfg.cache_rows, w.features.ctypes.data, num_nodes=cfg.num_nodes, row_bytes=cfg.row_bytes)
-    pipe = MinibatchPipeline(graph, cache, cfg.batch, cfg.fanouts, cfg.row_bytes, write_through=write_through)
+    if native:      # the same loop as one call into the library (bgl_pipeline_run)
+        from paper_2112_08541_amd.pipeline import NativePipeline
+        pipe = NativePipeline(graph, cache, cfg.batch, cfg.fanouts, cfg.row_bytes)
+    else:
+        pipe = MinibatchPipeline(graph, cache, cfg.batch, cfg.fanouts, cfg.row_bytes, write_through=write_through)
     if staged:
         pipe.tier = B.HostTier(w.features.view(np.uint8).reshape(cfg.num_nodes, cfg.row_bytes), 0, pipe.cap, 0)
         pipe.tier.set_copy_engine(int(staged))        # True: landed rows scattered; 2: the whole output in one pass
@@ -555,7 +568,8 @@ def run_overlapped_against_oracle(torch_mod, B, w, steps, write_through=True, st
     assert_state_equal(cache, op.cache, "overlapped")
 
 
-@pytest.mark.parametrize("miss_path", ["zero_copy", "staged", "staged_kernel", "staged_assembled"])
+@pytest.mark.parametrize("miss_path", ["zero_copy", "staged", "staged_kernel", "staged_assembled",
+                                       "native_zero_copy", "native_staged_assembled"])
 def test_overlapped_pipeline_full_epoch_counts_and_final_state(torch_mod, B, miss_path):
     """The whole benchmarked epoch (mid, 200 batches, overlapped, write-through) on both miss
     paths (staged = the ring of a host tier that keeps nothing, with the early lookup, as
@@ -567,10 +581,16 @@ def test_overlapped_pipeline_full_epoch_counts_and_final_state(torch_mod, B, mis
     w = inputs.make_workload(cfg, pinned=True)
     graph = B.Graph(w.row_ptr, w.col)
     cache = B.Cache(cfg.cache_rows, w.features.ctypes.data, num_nodes=cfg.num_nodes, row_bytes=cfg.row_bytes)
-    pipe = MinibatchPipeline(graph, cache, cfg.batch, cfg.fanouts, cfg.row_bytes)
+    if miss_path.startswith("native_"):     # the loop as one call into the library (bgl_pipeline_run)
+        from paper_2112_08541_amd.pipeline import NativePipeline
+        pipe = NativePipeline(graph, cache, cfg.batch, cfg.fanouts, cfg.row_bytes)
+        miss_path = miss_path[len("native_"):]
+    else:
+        pipe = MinibatchPipeline(graph, cache, cfg.batch, cfg.fanouts, cfg.row_bytes)
     if miss_path != "zero_copy":
-        pipe.tier = B.HostTier(w.features.view(np.uint8).reshape(cfg.num_nodes, cfg.row_bytes), 0, pipe.cap, 0)
-        pipe.tier.set_copy_engine({"staged": 1, "staged_kernel": 0, "staged_assembled": 2}[miss_path])
+        tier = B.HostTier(w.features.view(np.uint8).reshape(cfg.num_nodes, cfg.row_bytes), 0, pipe.cap, 0)
+        tier.set_copy_engine({"staged": 1, "staged_kernel": 0, "staged_assembled": 2}[miss_path])
+        pipe.tier = tier
     seeds_dev = torch_mod.from_numpy(w.seed_batches).cuda()
     steps = cfg.num_batches
 
