@@ -126,6 +126,20 @@ def test_null_handles_are_rejected_without_touching_the_gpu(L):
     assert L.bgl_host_tier_set_copy_engine(None, 1) == B.BGL_EINVAL
     assert L.bgl_cache_lookup_gather_tiered(None, None, None, 0, None, None, None, None, None, None, None, 0) == B.BGL_EINVAL
     assert L.bgl_cache_create(4, 16, feats.ctypes.data, 0, C.byref(h)) == B.BGL_EINVAL
+    assert L.bgl_cache_lookup_tiered_begin(None, None, None, 0, None, None, None, None, None, None, None, 0) == B.BGL_EINVAL
+    assert L.bgl_cache_lookup_tiered_finish(None) == B.BGL_EINVAL
+    # the overlapped loop
+    fan = np.array([2], dtype=np.int32)
+    buf = B.PipelineBuffers()
+    assert L.bgl_pipeline_create(None, None, None, 4, fan.ctypes.data, 1, C.byref(buf), 0, None, C.byref(h)) == B.BGL_EINVAL
+    assert b"handle is null" in L.bgl_last_error()
+    assert L.bgl_pipeline_create(None, None, None, 4, fan.ctypes.data, 1, C.byref(buf), 0, None, None) == B.BGL_EINVAL
+    assert L.bgl_pipeline_destroy(None) == B.BGL_OK
+    assert L.bgl_pipeline_set_cache(None, None, 0) == B.BGL_EINVAL
+    assert L.bgl_pipeline_set_tier(None, None) == B.BGL_EINVAL
+    assert L.bgl_pipeline_streams(None, None, None) == B.BGL_EINVAL
+    assert L.bgl_pipeline_last_batch(None, None, None) == B.BGL_EINVAL
+    assert L.bgl_pipeline_run(None, None, 0, None, 0, 0, None, None, None, C.cast(None, B.BATCH_FN), None) == B.BGL_EINVAL
 
 
 def test_binding_refuses_to_run_without_a_gpu():
