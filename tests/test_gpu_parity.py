@@ -568,6 +568,51 @@ def run_overlapped_against_oracle(torch_mod, B, w, steps, write_through=True, st
     assert_state_equal(cache, op.cache, "overlapped")
 
 
+def test_native_pipeline_argument_errors_and_second_pass(torch_mod, B):
+    """bgl_pipeline_create refuses buffers that are too small; a second run over the same seeds (first_step
+    past the seed batches) samples differently, as the Python loop does, and both loops agree on it."""
+    import ctypes as C
+    from paper_2112_08541_amd.pipeline import MinibatchPipeline, NativePipeline
+    inputs = _inputs()
+    cfg = inputs.CONFIGS["tiny"]
+    w = inputs.make_workload(cfg, pinned=True)
+    graph = B.Graph(w.row_ptr, w.col)
+    seeds_dev = torch_mod.from_numpy(w.seed_batches).cuda()
+    runs = []
+    for cls in (NativePipeline, MinibatchPipeline):
+        cache = B.Cache(cfg.cache_rows, w.features.ctypes.data, num_nodes=cfg.num_nodes, row_bytes=cfg.row_bytes)
+        pipe = cls(graph, cache, cfg.batch, cfg.fanouts, cfg.row_bytes)
+        first = pipe.run(seeds_dev, w.rng_seeds, cfg.num_batches)
+        second = pipe.run(seeds_dev, w.rng_seeds, 7, first_step=cfg.num_batches)
+        rows = pipe.out_rows[: second[0][-1]].cpu().numpy()
+        ids = pipe.last_ids[: second[0][-1]].cpu().numpy()
+        assert np.array_equal(rows, w.features.view(np.uint8).reshape(cfg.num_nodes, cfg.row_bytes)[ids])
+        runs.append((first, second, ids.tolist(), cache.export_state(True)))
+        if cls is NativePipeline:
+            # too few output rows, and a sampling workspace that is too small
+            buf = B.PipelineBuffers()
+            for k, smp in enumerate(pipe.samplers):
+                buf.workspace[k] = smp.workspace.data_ptr()
+                buf.counts_host[k] = smp.counts_host.data_ptr()
+            buf.workspace_bytes = pipe.samplers[0].workspace_bytes
+            buf.out_rows, buf.out_slot, buf.miss_pos = (pipe.out_rows.data_ptr(), pipe.out_slot.data_ptr(),
+                                                        pipe.miss_pos.data_ptr())
+            buf.cap_rows = pipe.cap - 1
+            h = C.c_void_p()
+            fan = np.ascontiguousarray(cfg.fanouts, dtype=np.int32)
+            args = (graph._h, cache._h, None, cfg.batch, fan.ctypes.data, len(fan))
+            assert B.lib().bgl_pipeline_create(*args, C.byref(buf), 0, None, C.byref(h)) == B.BGL_ECAPACITY
+            buf.cap_rows = pipe.cap
+            buf.workspace_bytes = 1024
+            assert B.lib().bgl_pipeline_create(*args, C.byref(buf), 0, None, C.byref(h)) == B.BGL_ECAPACITY
+            assert not h.value
+    (f0, s0, ids0, st0), (f1, s1, ids1, st1) = runs
+    assert f0 == f1 and s0 == s1 and ids0 == ids1
+    assert s0[0] != f0[0][:7]                       # the second pass sampled other neighbors
+    for a, b in zip(st0, st1):
+        assert np.array_equal(a, b)
+
+
 @pytest.mark.parametrize("miss_path", ["zero_copy", "staged", "staged_kernel", "staged_assembled",
                                        "native_zero_copy", "native_staged_assembled"])
 def test_overlapped_pipeline_full_epoch_counts_and_final_state(torch_mod, B, miss_path):
